@@ -1,0 +1,113 @@
+"""Seeded synthetic TTC-shaped LQR batches.
+
+One LQR problem per (batch, head, token); the recipe stands in for the per-token parameters
+a trained TTC-Net would synthesise (no weights or datasets are available).  This module only
+draws inputs: it contains none of the solver's arithmetic and is the one piece of code that
+both the HIP path's tests/benchmark and the CPU oracle's tests may import.
+
+Per problem, independent draws in the order A, B, L, M, x0 (d = state size, m = control size):
+    A  = I + 0.1 * N(0,1)^{d x d} / sqrt(d)         (optionally rescaled to spectral radius rho)
+    B  = N(0,1)^{d x m} / sqrt(d)
+    Q  = L L^T / d + 1e-2 I,  L ~ N(0,1)^{d x d}    (symmetrised)
+    R  = I + M M^T / m,       M ~ N(0,1)^{m x m}    (symmetrised)
+    QT = Q (aliased, returned as None),  x0 ~ N(0,1)^d
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+#: The five workload configurations (problems = batch * heads * tokens).
+CONFIGS = {
+    "tiny": dict(batch=1, heads=1, tokens=256, d=16, m=16, T=8, dtype="f32", rho=None),
+    "small_head": dict(batch=4, heads=16, tokens=1024, d=64, m=64, T=8, dtype="f32", rho=None),
+    "llm_adapter": dict(batch=2, heads=32, tokens=8192, d=128, m=128, T=16, dtype="f32", rho=None),
+    "long_horizon": dict(batch=1, heads=16, tokens=4096, d=64, m=64, T=64, dtype="f32", rho=0.98),
+    "mixed_precision": dict(batch=4, heads=32, tokens=8192, d=128, m=128, T=32, dtype="bf16", rho=None),
+}
+
+
+def config_problems(name: str) -> int:
+    c = CONFIGS[name]
+    return c["batch"] * c["heads"] * c["tokens"]
+
+
+@dataclass
+class LqrBatch:
+    """n problems, row-major, problem-major: A (n,d,d), B (n,d,m), Q (n,d,d), R (n,m,m), x0 (n,d)."""
+    A: torch.Tensor
+    B: torch.Tensor
+    Q: torch.Tensor
+    R: torch.Tensor
+    x0: torch.Tensor
+    T: int
+
+    @property
+    def n(self):
+        return self.A.shape[0]
+
+    @property
+    def d(self):
+        return self.A.shape[1]
+
+    @property
+    def m(self):
+        return self.B.shape[2]
+
+    def take(self, index) -> "LqrBatch":
+        """Sub-batch (index: slice or LongTensor) on the same device."""
+        return LqrBatch(self.A[index], self.B[index], self.Q[index], self.R[index], self.x0[index], self.T)
+
+    def numpy64(self):
+        """Stored values widened to float64 numpy arrays on the host: (A, B, Q, R, x0)."""
+        return tuple(t.detach().to("cpu", torch.float64).numpy() for t in (self.A, self.B, self.Q, self.R, self.x0))
+
+
+def _scale_spectral_radius(A: torch.Tensor, rho: float) -> torch.Tensor:
+    ev = torch.linalg.eigvals(A.to("cpu", torch.float64))
+    r = ev.abs().amax(dim=-1)
+    return A * (rho / r).to(A.device, A.dtype)[:, None, None]
+
+
+def make_batch(n: int, d: int, m: int, T: int, seed: int = 0, device="cpu", dtype: str = "f32",
+               rho: float | None = None, chunk: int = 4096) -> LqrBatch:
+    """Draw n problems.  Values are generated in float32 (in chunks, to bound temporaries) and,
+    for dtype == "bf16", rounded to bfloat16 storage at the end."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    store = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    A = torch.empty((n, d, d), dtype=store, device=dev)
+    B = torch.empty((n, d, m), dtype=store, device=dev)
+    Q = torch.empty((n, d, d), dtype=store, device=dev)
+    R = torch.empty((n, m, m), dtype=store, device=dev)
+    x0 = torch.empty((n, d), dtype=store, device=dev)
+    eye_d = torch.eye(d, device=dev)
+    eye_m = torch.eye(m, device=dev)
+    for lo in range(0, n, chunk):
+        c = min(chunk, n - lo)
+        rn = lambda *s: torch.randn(*s, generator=gen, device=dev, dtype=torch.float32)
+        a = eye_d + 0.1 * rn(c, d, d) / d ** 0.5
+        b = rn(c, d, m) / d ** 0.5
+        L = rn(c, d, d)
+        M = rn(c, m, m)
+        x = rn(c, d)
+        if rho is not None:
+            a = _scale_spectral_radius(a, rho)
+        q = L @ L.transpose(1, 2) / d + 1e-2 * eye_d
+        r = eye_m + M @ M.transpose(1, 2) / m
+        A[lo:lo + c] = a
+        B[lo:lo + c] = b
+        Q[lo:lo + c] = 0.5 * (q + q.transpose(1, 2))
+        R[lo:lo + c] = 0.5 * (r + r.transpose(1, 2))
+        x0[lo:lo + c] = x
+    return LqrBatch(A, B, Q, R, x0, T)
+
+
+def make_config(name: str, n: int | None = None, seed: int = 0, device="cpu") -> LqrBatch:
+    """The named configuration (optionally only its first n problems' worth of draws)."""
+    c = CONFIGS[name]
+    total = config_problems(name)
+    return make_batch(total if n is None else n, c["d"], c["m"], c["T"], seed=seed, device=device,
+                      dtype=c["dtype"], rho=c["rho"])
