@@ -1,0 +1,119 @@
+/*
+ * ttc_lqr.h -- C ABI of the batched finite-horizon LQR solver behind a Test-Time Control (TTC) layer.
+ *
+ * One independent LQR problem per (batch, head, token), n problems per call.  Each problem is the
+ * paper's Eq. "ttc" (Sec. 3.1; formal statement: Def. A.1) with time-invariant parameters (the
+ * paper's "Homo." setting): dynamics x_{t+1} = A x_t + B u_t, stage costs x_t^T Q x_t (1 <= t <= T-1)
+ * and u_t^T R u_t (0 <= t <= T-1), terminal cost x_T^T Q_T x_T, no cost on the initial state
+ * (the paper's Q_0 = 0).  Textbook indexing is used here: x0 = h_0, u0 = u_1^*, K0 = K_1^*.
+ *
+ * The solve runs the backward Riccati recursion (Prop. 3.1) through the reverse symplectic
+ * iteration of Thm 3.3: the pair [Y1 Y2] is multiplied by the factored symplectic matrices
+ * Sigma_t (App. C "Kernel Fusion") and P = Y1^{-1} Y2 is recovered by a pivoted dense solve.
+ * Because cond(Y1) grows geometrically with the number of accumulated factors, the pair is
+ * re-based to [I P] every `rebase_every` steps (the paper's algorithm is rebase_every >= T-1).
+ *
+ * Conventions
+ *   - All matrix arguments are DEVICE pointers to row-major, problem-major arrays: problem p of A
+ *     starts at A + p*sA elements.  A stride of 0 shares one matrix between all problems.
+ *   - Inputs are borrowed and read-only; outputs and the workspace are caller-owned.  The library
+ *     never allocates device memory, never synchronises the stream, and launches asynchronously on
+ *     the HIP stream passed as `hip_stream` (a hipStream_t cast to void*; NULL = default stream).
+ *   - Q, R and Q_T are read as their symmetric parts (M + M^T)/2.  R must be positive definite and
+ *     A invertible (the paper's parameterisation A = I + ... guarantees it, Sec. 4).
+ *   - Inputs may be float32 or bfloat16 (in_dtype); every on-chip quantity and every output is
+ *     float32 (App. C "Mixed Precision").
+ *   - Supported shapes: d = m in {16, 32, 64, 128}, T >= 1.  Anything else returns
+ *     TTC_ERR_UNSUPPORTED and launches nothing.  Pointers of float32 inputs/outputs must be 16-byte
+ *     aligned (8-byte for bfloat16 inputs) and strides multiples of 4 elements, else
+ *     TTC_ERR_INVALID_ARG.
+ *   - Argument errors are reported by the return code and nothing is launched.  Numerical breakdown
+ *     (a zero or non-finite pivot: R not positive definite, singular A, singular Y1) is reported
+ *     per problem in info[] and that problem's outputs are NaN; the call still returns TTC_OK.
+ */
+#ifndef TTC_LQR_H
+#define TTC_LQR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TTC_OK = 0,
+  TTC_ERR_INVALID_ARG = 1, /* NULL/misaligned pointer, n < 0, T < 1, bad stride or enum value   */
+  TTC_ERR_UNSUPPORTED = 2, /* shape outside the supported set                                    */
+  TTC_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than ttc_lqr_workspace_bytes()           */
+  TTC_ERR_DEVICE = 4       /* the HIP runtime refused the launch (no device, bad stream, ...)    */
+} ttc_status_t;
+
+typedef enum { TTC_F32 = 0, TTC_BF16 = 1 } ttc_dtype_t;
+
+enum {
+  /* P0 += Q: charge the stage cost on x0 as textbooks do.  Default 0 is the paper's Q_0 = 0
+   * (Sec. 3.1, Thm A.3).  K0 and u0 do not depend on it. */
+  TTC_FLAG_STAGE_COST_AT_X0 = 1,
+  /* Never re-base inside the horizon: accumulate all T-1 factors Sigma_T..Sigma_2 with row
+   * normalisation after every step (App. C "Numerical Stability") and do the dense solve once,
+   * as Alg. 4 does.  For study: accuracy degrades quickly with T on dense problems. */
+  TTC_FLAG_PURE_SYMPLECTIC = 2
+};
+
+/* Problem statement: the (A, B, Q, R, Q_T, x0, T) of Eq. "ttc" for n problems. */
+typedef struct {
+  int64_t n;            /* number of problems (batch*heads*tokens), n >= 0                        */
+  int32_t d, m, T;      /* state size, control size, horizon                                       */
+  int32_t in_dtype;     /* ttc_dtype_t of A, B, Q, R, QT, x0                                       */
+  int32_t flags;        /* TTC_FLAG_*                                                              */
+  int32_t rebase_every; /* re-base [Y1 Y2] -> [I P] every this many steps; 0 = library default     */
+  const void *A;        /* (n, d, d)                                                               */
+  const void *B;        /* (n, d, m)                                                               */
+  const void *Q;        /* (n, d, d)                                                               */
+  const void *R;        /* (n, m, m)                                                               */
+  const void *QT;       /* (n, d, d) or NULL meaning Q_T = Q                                       */
+  const void *x0;       /* (n, d)                                                                  */
+  int64_t sA, sB, sQ, sR, sQT, sx0; /* elements between consecutive problems; 0 = shared           */
+} ttc_lqr_problem_t;
+
+/* Outputs of ttc_lqr_solve, float32, DEVICE pointers; P0, K0, value and info may be NULL. */
+typedef struct {
+  float *P0;     /* (n, d, d) value matrix at x0: lambda_0 = P0 x0 (Alg. 4: P = Y1^{-1} Y2)         */
+  float *K0;     /* (n, m, d) first gain, Eq. "decode" at t = 1                                     */
+  float *u0;     /* (n, m)    first optimal control u0 = K0 x0 (the layer's output o)               */
+  float *value;  /* (n)       x0^T P0 x0 = 2x the optimal objective of Eq. "ttc"                    */
+  int32_t *info; /* (n)       0 = ok; s > 0 = the s-th dense solve of that problem broke down
+                               (1: R^{-1}B^T, 2: A^{-1}, 3..: re-bases in order, last: final solve) */
+} ttc_lqr_solution_t;
+
+/* Bytes of device workspace ttc_lqr_solve (for_rollout = 0) or ttc_lqr_rollout (for_rollout = 1)
+ * needs for this problem on the current device.  Returns 0 for an unsupported/invalid problem.
+ * Depends only on d, m, T and the device's compute-unit count, never on n. */
+size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t *problem, int for_rollout);
+
+/* Solve n problems: P0, K0, u0, value (Prop. 3.1 via Thm 3.3 / Alg. 4, see the file header).
+ * `workspace` is a DEVICE buffer of at least ttc_lqr_workspace_bytes(problem, 0) bytes, 16-byte
+ * aligned, used as scratch for the duration of the launch.  Asynchronous on `hip_stream`. */
+ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t *problem, const ttc_lqr_solution_t *solution,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Full optimal trajectory (Alg. 1, forward loop, r = 0): U (n, T, m) controls u_0..u_{T-1},
+ * X (n, T+1, d) states x_0..x_T, cost (n) = sum_t u_t^T R u_t + sum_{t=1}^{T-1} x_t^T Q x_t +
+ * x_T^T Q_T x_T (+ x_0^T Q x_0 with TTC_FLAG_STAGE_COST_AT_X0), which equals `value` of
+ * ttc_lqr_solve.  The gains K_t are produced by a re-based backward sweep and kept in the
+ * workspace.  X, cost and info may be NULL.  Same conventions and error behaviour as above. */
+ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t *problem, float *U, float *X, float *cost,
+                             int32_t *info, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *ttc_status_string(ttc_status_t status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int ttc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TTC_LQR_H */

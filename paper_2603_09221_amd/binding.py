@@ -1,0 +1,170 @@
+"""ctypes binding of the C-ABI library (include/ttc_lqr.h): argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the path runs in the HIP library.
+The library must have been built (``python -c "import __graft_entry__ as g; g.build()"``); there is
+no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_int, c_int32, c_int64, c_size_t, c_void_p
+
+import torch
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libttc_lqr.so")
+
+TTC_OK, TTC_ERR_INVALID_ARG, TTC_ERR_UNSUPPORTED, TTC_ERR_WORKSPACE, TTC_ERR_DEVICE = range(5)
+TTC_F32, TTC_BF16 = 0, 1
+TTC_FLAG_STAGE_COST_AT_X0 = 1
+TTC_FLAG_PURE_SYMPLECTIC = 2
+
+EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_status_string", "ttc_version")
+
+
+class Problem(ctypes.Structure):
+    _fields_ = [("n", c_int64), ("d", c_int32), ("m", c_int32), ("T", c_int32), ("in_dtype", c_int32),
+                ("flags", c_int32), ("rebase_every", c_int32),
+                ("A", c_void_p), ("B", c_void_p), ("Q", c_void_p), ("R", c_void_p), ("QT", c_void_p),
+                ("x0", c_void_p),
+                ("sA", c_int64), ("sB", c_int64), ("sQ", c_int64), ("sR", c_int64), ("sQT", c_int64),
+                ("sx0", c_int64)]
+
+
+class Solution(ctypes.Structure):
+    _fields_ = [("P0", c_void_p), ("K0", c_void_p), ("u0", c_void_p), ("value", c_void_p), ("info", c_void_p)]
+
+
+class TtcError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"ttc_lqr: {text} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Load the shared library (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: build it with __graft_entry__.build()")
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.ttc_lqr_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_workspace_bytes.argtypes = [ctypes.POINTER(Problem), c_int]
+    lib.ttc_lqr_solve.restype = c_int
+    lib.ttc_lqr_solve.argtypes = [ctypes.POINTER(Problem), ctypes.POINTER(Solution), c_void_p, c_size_t, c_void_p]
+    lib.ttc_lqr_rollout.restype = c_int
+    lib.ttc_lqr_rollout.argtypes = [ctypes.POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                    c_size_t, c_void_p]
+    lib.ttc_status_string.restype = c_char_p
+    lib.ttc_status_string.argtypes = [c_int]
+    lib.ttc_version.restype = c_int
+    lib.ttc_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def ttc_version() -> int:
+    return load().ttc_version()
+
+
+def ttc_status_string(status: int) -> str:
+    return load().ttc_status_string(status).decode()
+
+
+def _check(status):
+    if status != TTC_OK:
+        raise TtcError(status, ttc_status_string(status))
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stride(t):
+    """Elements between consecutive problems of a (n, ...) tensor whose trailing dims are contiguous."""
+    if t is None:
+        return 0
+    inner = 1
+    for k in range(t.dim() - 1, 0, -1):
+        if t.shape[k] != 1 and t.stride(k) != inner:
+            raise ValueError("per-problem matrices must be contiguous row-major")
+        inner *= t.shape[k]
+    return t.stride(0)
+
+
+def make_problem(A, B, Q, R, QT, x0, T, flags=0, rebase_every=0, n=None) -> Problem:
+    """Fill the problem descriptor from tensors A (n,d,d), B (n,d,m), Q (n,d,d), R (n,m,m), QT or None,
+    x0 (n,d).  A leading dimension expanded with stride 0 is passed through as a shared matrix."""
+    dt = A.dtype
+    for t in (B, Q, R, x0) + (() if QT is None else (QT,)):
+        if t.dtype != dt:
+            raise ValueError("all inputs must share one dtype")
+    in_dtype = {torch.float32: TTC_F32, torch.bfloat16: TTC_BF16}.get(dt)
+    if in_dtype is None:
+        raise ValueError("inputs must be float32 or bfloat16")
+    p = Problem()
+    p.n = A.shape[0] if n is None else n
+    p.d, p.m, p.T = A.shape[1], B.shape[2], T
+    p.in_dtype, p.flags, p.rebase_every = in_dtype, flags, rebase_every
+    p.A, p.B, p.Q, p.R, p.QT, p.x0 = _ptr(A), _ptr(B), _ptr(Q), _ptr(R), _ptr(QT), _ptr(x0)
+    p.sA, p.sB, p.sQ, p.sR, p.sQT, p.sx0 = (_stride(t) for t in (A, B, Q, R, QT, x0))
+    return p
+
+
+def ttc_lqr_workspace_bytes(problem: Problem, for_rollout: bool = False) -> int:
+    return load().ttc_lqr_workspace_bytes(ctypes.byref(problem), 1 if for_rollout else 0)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def ttc_lqr_solve(A, B, Q, R, QT, x0, T, *, flags=0, rebase_every=0, want_P0=True, want_K0=True,
+                  out=None, workspace=None, stream=None):
+    """P0 (n,d,d), K0 (n,m,d), u0 (n,m), value (n), info (n) of n LQR problems; all float32 device tensors.
+
+    `out` may carry preallocated tensors under the same names; `workspace` a uint8 device tensor."""
+    lib = load()
+    prob = make_problem(A, B, Q, R, QT, x0, T, flags, rebase_every)
+    n, d, m, dev = prob.n, prob.d, prob.m, A.device
+    out = dict(out or {})
+    f32 = dict(dtype=torch.float32, device=dev)
+    if want_P0 and "P0" not in out:
+        out["P0"] = torch.empty((n, d, d), **f32)
+    if want_K0 and "K0" not in out:
+        out["K0"] = torch.empty((n, m, d), **f32)
+    out.setdefault("u0", torch.empty((n, m), **f32))
+    out.setdefault("value", torch.empty((n,), **f32))
+    out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
+    sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
+    need = lib.ttc_lqr_workspace_bytes(ctypes.byref(prob), 0)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    _check(lib.ttc_lqr_solve(ctypes.byref(prob), ctypes.byref(sol), c_void_p(workspace.data_ptr()),
+                             workspace.numel(), _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_rollout(A, B, Q, R, QT, x0, T, *, flags=0, rebase_every=0, workspace=None, stream=None):
+    """U (n,T,m), X (n,T+1,d), cost (n), info (n) of n LQR problems; float32 device tensors."""
+    lib = load()
+    prob = make_problem(A, B, Q, R, QT, x0, T, flags, rebase_every)
+    n, d, m, dev = prob.n, prob.d, prob.m, A.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    U = torch.empty((n, T, m), **f32)
+    X = torch.empty((n, T + 1, d), **f32)
+    cost = torch.empty((n,), **f32)
+    info = torch.empty((n,), dtype=torch.int32, device=dev)
+    need = lib.ttc_lqr_workspace_bytes(ctypes.byref(prob), 1)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    _check(lib.ttc_lqr_rollout(ctypes.byref(prob), c_void_p(U.data_ptr()), c_void_p(X.data_ptr()),
+                               c_void_p(cost.data_ptr()), c_void_p(info.data_ptr()),
+                               c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
+    return {"U": U, "X": X, "cost": cost, "info": info}

@@ -1,0 +1,326 @@
+// Device-side building blocks of the batched LQR solver (gfx950 / CDNA4, wave64).
+//
+// One workgroup solves one problem at a time.  A workgroup has D/16 wavefronts; wavefront w owns
+// rows [16w, 16w+16) of every d x d product it forms.  The d x 2d pair [Y1 Y2] of the reverse
+// symplectic iteration (Thm 3.3) lives in LDS in transposed form Z = [Y1 Y2]^T ("Z-land": left
+// half Z1 = Y1^T, right half Z2 = Y2^T), so that one factored step (App. C "Kernel Fusion")
+//     Y1 <- (Y1 + Y2 G) A^{-T},   Y2 <- Y2 A + Y1 Q
+// becomes left-multiplications by constant matrices,
+//     Z1 <- A^{-1} (Z1 + G Z2),   Z2 <- A^T Z2 + Q Z1,
+// whose row blocks stay in the owning wavefront's registers for the whole horizon (MFMA A operand)
+// while the state is the shared MFMA B operand read from LDS.  Nothing is re-read from HBM inside
+// the horizon loop.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ttc {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+template <int D>
+struct Cfg {
+  static constexpr int NTHR = 4 * D;            // threads per workgroup
+  static constexpr int NW = D / 16;             // wavefronts per workgroup
+  static constexpr int KS = D / 4;              // k-steps of v_mfma_f32_16x16x4_f32 per product
+  static constexpr int NT = D / 16;             // 16-column tiles per row block
+  static constexpr int VEC = NT >= 4 ? 4 : NT;  // consecutive floats per B-operand LDS read
+  static constexpr int NH = NT / VEC;           // B-operand reads per k-step
+  static constexpr int PITCH = 2 * D + 4;       // floats per LDS row of the d x 2d pair (+4: bank skew)
+};
+
+// ----------------------------------------------------------------------------------------------
+// input element access: float32 or bfloat16 (stored as uint16_t), widened to float32
+template <typename TIn>
+__device__ __forceinline__ float ld1(const TIn* p, long i);
+template <>
+__device__ __forceinline__ float ld1<float>(const float* p, long i) { return p[i]; }
+template <>
+__device__ __forceinline__ float ld1<uint16_t>(const uint16_t* p, long i) {
+  return __uint_as_float(((uint32_t)p[i]) << 16);
+}
+template <typename TIn>
+__device__ __forceinline__ floatx4 ld4(const TIn* p, long i);  // i % 4 == 0, p + i vector-aligned
+template <>
+__device__ __forceinline__ floatx4 ld4<float>(const float* p, long i) {
+  return *reinterpret_cast<const floatx4*>(p + i);
+}
+template <>
+__device__ __forceinline__ floatx4 ld4<uint16_t>(const uint16_t* p, long i) {
+  uint2 u = *reinterpret_cast<const uint2*>(p + i);
+  floatx4 r;
+  r[0] = __uint_as_float(u.x << 16);
+  r[1] = __uint_as_float(u.x & 0xffff0000u);
+  r[2] = __uint_as_float(u.y << 16);
+  r[3] = __uint_as_float(u.y & 0xffff0000u);
+  return r;
+}
+
+// ----------------------------------------------------------------------------------------------
+// LDS access of VEC consecutive floats
+template <int VEC>
+__device__ __forceinline__ void lds_ldv(const float* p, float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    floatx4 t = *reinterpret_cast<const floatx4*>(p);
+    v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+  } else if constexpr (VEC == 2) {
+    floatx2 t = *reinterpret_cast<const floatx2*>(p);
+    v[0] = t[0]; v[1] = t[1];
+  } else {
+    v[0] = p[0];
+  }
+}
+template <int VEC>
+__device__ __forceinline__ void lds_stv(float* p, const float (&v)[VEC]) {
+  if constexpr (VEC == 4) {
+    floatx4 t; t[0] = v[0]; t[1] = v[1]; t[2] = v[2]; t[3] = v[3];
+    *reinterpret_cast<floatx4*>(p) = t;
+  } else if constexpr (VEC == 2) {
+    floatx2 t; t[0] = v[0]; t[1] = v[1];
+    *reinterpret_cast<floatx2*>(p) = t;
+  } else {
+    p[0] = v[0];
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// wavefront reductions
+// max over the 64 lanes of an unsigned key, returned in every lane (DPP inside rows of 16 lanes,
+// then the four row results are combined through scalar registers)
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
+  x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false));  // row_mirror
+  uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0);
+  uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+  uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32);
+  uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+  return mx(mx(a, b), mx(c, d));
+}
+// sum over the 16 lanes that share lane/16 (xor butterflies 1,2,4,8)
+__device__ __forceinline__ float sum16(float x) {
+  x += __shfl_xor(x, 1, 64);
+  x += __shfl_xor(x, 2, 64);
+  x += __shfl_xor(x, 4, 64);
+  x += __shfl_xor(x, 8, 64);
+  return x;
+}
+__device__ __forceinline__ float sum64(float x) {
+  x = sum16(x);
+  x += __shfl_xor(x, 16, 64);
+  x += __shfl_xor(x, 32, 64);
+  return x;
+}
+
+// ----------------------------------------------------------------------------------------------
+// Row-block product on the matrix cores: acc(16 x D) += C[16w:16w+16, :] * Z(D x D).
+//
+// v_mfma_f32_16x16x4_f32 operand layout (lane = 16 g + i): A operand = A[i][g], B operand =
+// B[g][i], accumulator register v = D[4 g + v][i].
+//   * a[4q+t] holds C[16w+i][16q+4g+t]: the contraction index is visited in the permuted order
+//     k(q,t,g) = 16q + 4g + t so that a lane's four values for fixed q are contiguous in memory.
+//   * the matching B operand is row k(q,t,g) of Z; one LDS read of VEC consecutive floats at
+//     column 16*VEC*h + VEC*i feeds VEC tiles, i.e. tile c = h*VEC + tp covers the strided column
+//     set { 16*VEC*h + VEC*i + tp : i = 0..15 }.
+//   * acc[c][v] is therefore element (row 16w+4g+v, column 16*VEC*h + VEC*i + tp) of the product.
+template <int D>
+__device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::NT], const float (&a)[Cfg<D>::KS],
+                                         const float* __restrict__ Zb, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int q = 0; q < D / 16; ++q) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float* row = Zb + (16 * q + 4 * g + t) * C::PITCH + C::VEC * i;
+#pragma unroll
+      for (int h = 0; h < C::NH; ++h) {
+        float b[C::VEC];
+        lds_ldv<C::VEC>(row + 16 * C::VEC * h, b);
+#pragma unroll
+        for (int tp = 0; tp < C::VEC; ++tp)
+          acc[h * C::VEC + tp] =
+              __builtin_amdgcn_mfma_f32_16x16x4f32(a[4 * q + t], b[tp], acc[h * C::VEC + tp], 0, 0, 0);
+      }
+    }
+  }
+}
+
+template <int D>
+__device__ __forceinline__ int tile_col(int c, int i) {  // column of tile c, lane-in-row i
+  using C = Cfg<D>;
+  return 16 * C::VEC * (c / C::VEC) + C::VEC * i + (c % C::VEC);
+}
+
+template <int D>
+__device__ __forceinline__ void zero_acc(floatx4 (&acc)[Cfg<D>::NT]) {
+#pragma unroll
+  for (int c = 0; c < Cfg<D>::NT; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+}
+// rows [16w,16w+16) of the identity in accumulator layout
+template <int D>
+__device__ __forceinline__ void eye_acc(floatx4 (&acc)[Cfg<D>::NT], int w, int i, int g) {
+#pragma unroll
+  for (int c = 0; c < Cfg<D>::NT; ++c)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[c][v] = (16 * w + 4 * g + v == tile_col<D>(c, i)) ? 1.f : 0.f;
+}
+// accumulator rows <-> LDS, untransposed: element (r, col) at Zb[r*PITCH + col]
+template <int D>
+__device__ __forceinline__ void store_rows(float* Zb, const floatx4 (&acc)[Cfg<D>::NT], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int h = 0; h < C::NH; ++h) {
+      float t[C::VEC];
+#pragma unroll
+      for (int tp = 0; tp < C::VEC; ++tp) t[tp] = acc[h * C::VEC + tp][v];
+      lds_stv<C::VEC>(Zb + (16 * w + 4 * g + v) * C::PITCH + 16 * C::VEC * h + C::VEC * i, t);
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_rows(const float* Zb, floatx4 (&acc)[Cfg<D>::NT], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int h = 0; h < C::NH; ++h) {
+      float t[C::VEC];
+      lds_ldv<C::VEC>(Zb + (16 * w + 4 * g + v) * C::PITCH + 16 * C::VEC * h + C::VEC * i, t);
+#pragma unroll
+      for (int tp = 0; tp < C::VEC; ++tp) acc[h * C::VEC + tp][v] = t[tp];
+    }
+}
+// accumulator rows -> LDS transposed: element (r, col) at Yb[col*PITCH + r]; a lane's four rows
+// 16w+4g..+3 are contiguous there
+template <int D>
+__device__ __forceinline__ void store_rows_T(float* Yb, const floatx4 (&acc)[Cfg<D>::NT], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int c = 0; c < C::NT; ++c)
+    *reinterpret_cast<floatx4*>(Yb + tile_col<D>(c, i) * C::PITCH + 16 * w + 4 * g) = acc[c];
+}
+// A-operand registers of rows [16w,16w+16) of a matrix held in LDS: a[4q+t] = M[16w+i][16q+4g+t]
+template <int D>
+__device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>::KS], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int q = 0; q < D / 16; ++q) {
+    floatx4 t = *reinterpret_cast<const floatx4*>(Mb + (16 * w + i) * C::PITCH + 16 * q + 4 * g);
+    a[4 * q + 0] = t[0]; a[4 * q + 1] = t[1]; a[4 * q + 2] = t[2]; a[4 * q + 3] = t[3];
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Dense solve M X = RHS inside LDS: Gauss-Jordan elimination with partial (row) pivoting on the
+// augmented d x 2d array W = [M | RHS] (row r at W + r*PITCH; M = columns [0,d), RHS = [d,2d)).
+// Rows are never moved: the pivot row of column c is remembered in s_piv[c] (implicit pivoting) and
+// the solution is gathered at the end, X[c][:] = RHS[s_piv[c]][:] / pivot_c, into columns [d,2d).
+// Returns nonzero (uniformly over the workgroup) if a pivot was zero or not finite.  All threads of
+// the workgroup must call it; it starts by assuming W is visible (caller synchronised) and ends
+// with the result visible to every thread.
+template <int D>
+__device__ int lds_solve(float* W, int* s_piv, float* s_inv, int tid) {
+  using C = Cfg<D>;
+  constexpr int NG = D / 2;   // float4 column groups across the 2d columns
+  constexpr int RPS = D / 8;  // rows per thread: NTHR / NG = 8 row slices
+  constexpr int NRL = (D + 63) / 64;
+  const int lane = tid & 63;
+  const int cg = tid % NG, rs = tid / NG;
+  bool done[NRL];
+#pragma unroll
+  for (int rr = 0; rr < NRL; ++rr) done[rr] = false;
+  int bad = 0;
+  for (int c = 0; c < D; ++c) {
+    // pivot search, done redundantly (and identically) by every wavefront: key = |value| with the
+    // low 7 mantissa bits replaced by (127 - row), so that a single unsigned max gives the argmax
+    uint32_t key = 0;
+#pragma unroll
+    for (int rr = 0; rr < NRL; ++rr) {
+      const int r = lane + 64 * rr;
+      if (r < D && !done[rr]) {
+        const uint32_t k = (__float_as_uint(fabsf(W[r * C::PITCH + c])) & 0xFFFFFF80u) | (uint32_t)(127 - r);
+        key = k > key ? k : key;
+      }
+    }
+    key = wave_max_u32(key);
+    int pr = 127 - (int)(key & 0x7Fu);
+    pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
+    const float pv = W[pr * C::PITCH + c];
+    const float apv = fabsf(pv);
+    if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
+    const float inv = 1.0f / pv;
+#pragma unroll
+    for (int rr = 0; rr < NRL; ++rr)
+      if (lane + 64 * rr == pr) done[rr] = true;
+    if (tid == 0) { s_piv[c] = pr; s_inv[c] = inv; }
+    // eliminate column c from every other row, columns > c only (column c itself is left as is:
+    // it holds the multipliers every thread reads during this phase)
+    const int cg0 = (c + 1) >> 2;
+    if (cg >= cg0) {
+      const int cb = 4 * cg;
+      const floatx4 prow = *reinterpret_cast<const floatx4*>(W + pr * C::PITCH + cb);
+#pragma unroll 4
+      for (int rr = 0; rr < RPS; ++rr) {
+        const int r = rs * RPS + rr;
+        if (r != pr) {
+          const float mlt = W[r * C::PITCH + c] * inv;
+          floatx4* px = reinterpret_cast<floatx4*>(W + r * C::PITCH + cb);
+          const floatx4 x = *px;
+          floatx4 y = x - mlt * prow;
+          if (cb + 0 <= c) y[0] = x[0];
+          if (cb + 1 <= c) y[1] = x[1];
+          if (cb + 2 <= c) y[2] = x[2];
+          if (cb + 3 <= c) y[3] = x[3];
+          *px = y;
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // gather + scale into the (now dead) left half, then copy back to the right half
+  for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
+    const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
+    const floatx4 x = *reinterpret_cast<const floatx4*>(W + s_piv[c] * C::PITCH + D + j4);
+    *reinterpret_cast<floatx4*>(W + c * C::PITCH + j4) = x * s_inv[c];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
+    const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
+    *reinterpret_cast<floatx4*>(W + c * C::PITCH + D + j4) = *reinterpret_cast<const floatx4*>(W + c * C::PITCH + j4);
+  }
+  __syncthreads();
+  return bad;
+}
+
+// Row normalisation of [Y1 Y2] (App. C "Numerical Stability") in Z-land: column c of Z is row c of
+// the pair.  The scale is the power of two just below max(||Y1_c||_1, ||Y2_c||_1), so the scaling
+// is exact and Y1^{-1} Y2 is unchanged bit for bit (barring under/overflow).  Four threads per column.
+template <int D>
+__device__ void normalise_rows_zland(float* W, int tid) {
+  using C = Cfg<D>;
+  const int c = tid >> 2, part = tid & 3;  // NTHR = 4 D threads -> D columns x 4 row quarters
+  float s1 = 0.f, s2 = 0.f;
+  for (int r = part; r < D; r += 4) {
+    s1 += fabsf(W[r * C::PITCH + c]);
+    s2 += fabsf(W[r * C::PITCH + D + c]);
+  }
+  s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
+  s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
+  const float mx = fmaxf(s1, s2);
+  float scale = 1.0f;
+  if (mx > 0.f && mx < __builtin_inff()) {
+    int e;
+    frexpf(mx, &e);              // mx = f * 2^e, f in [0.5, 1)
+    scale = ldexpf(1.0f, -e);    // exact power of two
+  }
+  for (int r = part; r < D; r += 4) {
+    W[r * C::PITCH + c] *= scale;
+    W[r * C::PITCH + D + c] *= scale;
+  }
+}
+
+}  // namespace ttc

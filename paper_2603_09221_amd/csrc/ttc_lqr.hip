@@ -1,0 +1,381 @@
+// C-ABI entry points and kernels of the batched finite-horizon LQR solver (see include/ttc_lqr.h).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ttc_lqr.h"
+#include "ttc_device.hpp"
+
+namespace ttc {
+
+struct SolveArgs {
+  long long n;
+  int T, flags, rebase_every;
+  const void *A, *B, *Q, *R, *QT, *x0;
+  long long sA, sB, sQ, sR, sQT, sx0;
+  float *P0, *K0, *u0, *value;
+  int* info;
+  float* ws;  // gridDim.x slots of d*m floats: R^{-1} B^T of the problem in flight
+};
+
+// A-operand registers of rows [16w,16w+16) of a row-major global matrix: a[4q+t] = M[16w+i][16q+4g+t]
+template <int D, typename TIn>
+__device__ __forceinline__ void load_aop_global(const TIn* M, float (&a)[Cfg<D>::KS], int w, int i, int g) {
+#pragma unroll
+  for (int q = 0; q < D / 16; ++q) {
+    floatx4 t = ld4<TIn>(M, (long)(16 * w + i) * D + 16 * q + 4 * g);
+    a[4 * q + 0] = t[0]; a[4 * q + 1] = t[1]; a[4 * q + 2] = t[2]; a[4 * q + 3] = t[3];
+  }
+}
+
+// copy a row-major global d x d matrix into one half of the LDS pair (optionally transposed)
+template <int D, typename TIn, bool TRANS>
+__device__ __forceinline__ void load_half(float* Wh, const TIn* M, int tid) {
+  using C = Cfg<D>;
+  for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
+    const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
+    const floatx4 v = ld4<TIn>(M, (long)r * D + c4);
+    if constexpr (TRANS) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) Wh[(c4 + j) * C::PITCH + r] = v[j];
+    } else {
+      *reinterpret_cast<floatx4*>(Wh + r * C::PITCH + c4) = v;
+    }
+  }
+}
+// replace one half by its symmetric part (caller synchronises before and after)
+template <int D>
+__device__ __forceinline__ void symmetrise_half(float* Wh, int tid) {
+  using C = Cfg<D>;
+  for (int idx = tid; idx < D * D; idx += C::NTHR) {
+    const int r = idx / D, c = idx % D;
+    if (r < c) {
+      const float s = 0.5f * (Wh[r * C::PITCH + c] + Wh[c * C::PITCH + r]);
+      Wh[r * C::PITCH + c] = s;
+      Wh[c * C::PITCH + r] = s;
+    }
+  }
+}
+template <int D>
+__device__ __forceinline__ void set_half_identity(float* Wh, int tid) {
+  using C = Cfg<D>;
+  for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
+    const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
+    floatx4 v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = (c4 + j == r) ? 1.f : 0.f;
+    *reinterpret_cast<floatx4*>(Wh + r * C::PITCH + c4) = v;
+  }
+}
+
+// Solve kernel.  Persistent workgroups: workgroup b handles problems b, b + gridDim.x, ...
+//
+// Per problem:
+//   setup   X = R^{-1} B^T (dense solve), G = B X (Thm 3.3), A^{-1} (dense solve); the row blocks of
+//           G, A^{-1}, A^T and Q go to registers; Z2 = Q_T, Z1 = I.
+//   T-1 reverse symplectic steps with Q_{t-1} = Q (Thm 3.3 / Alg. 4 body); every `rebase_every`
+//           steps and after the last one the pair is re-based, [Y1 Y2] <- [I, Y1^{-1} Y2].
+//   final   the last factor Sigma_1 (Q_0 = 0) is applied in solved form: with P_1 explicit,
+//           M = (I + P_1 G)^{-1} P_1 A (dense solve), P_0 = A^T M (+ Q), K_0 = -(R^{-1} B^T) M, which is
+//           Y1^{-1} Y2 of Alg. 4 and Eq. "decode" at t = 1 without multiplying by A^{-T} and back.
+template <int D, typename TIn>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) {
+  using C = Cfg<D>;
+  __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
+  __shared__ int s_piv[D];
+  __shared__ float s_inv[D];
+  __shared__ float s_red[C::NW];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  float* const WL = W;      // left half  (Z1 / Y1 / M of a dense solve)
+  float* const WR = W + D;  // right half (Z2 / Y2 / RHS)
+  float* const wsX = p.ws + (long)blockIdx.x * D * D;
+  const bool pure = (p.flags & TTC_FLAG_PURE_SYMPLECTIC) != 0;
+  const int kreb = pure ? 0x7fffffff : p.rebase_every;
+
+  for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
+    const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
+    const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
+    const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
+    const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
+    const TIn* QTp = p.QT ? reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT : Qp;
+    const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
+    int info = 0, nsolve = 0;
+    float cG[C::KS], cAi[C::KS], cAT[C::KS], cQ[C::KS];
+    floatx4 acc1[C::NT], acc2[C::NT], acc3[C::NT];
+
+    // ---- setup 1: X = R^{-1} B^T, G = B X
+    load_half<D, TIn, false>(WL, Rp, tid);
+    load_half<D, TIn, true>(WR, Bp, tid);
+    __syncthreads();
+    symmetrise_half<D>(WL, tid);
+    __syncthreads();
+    ++nsolve;
+    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+    for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {  // keep X for the final gain
+      const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
+      *reinterpret_cast<floatx4*>(wsX + r * D + c4) = *reinterpret_cast<const floatx4*>(WR + r * C::PITCH + c4);
+    }
+    load_aop_global<D, TIn>(Bp, cG, w, i, g);  // rows of B, temporarily in G's registers
+    zero_acc<D>(acc1);
+    gemm_acc<D>(acc1, cG, WR, i, g);           // rows of G = B X
+    store_rows<D>(WL, acc1, w, i, g);
+    __syncthreads();
+    symmetrise_half<D>(WL, tid);               // G is symmetric up to rounding; make it exactly so
+    __syncthreads();
+    load_aop_lds<D>(WL, cG, w, i, g);
+    __syncthreads();
+
+    // ---- setup 2: A^{-1}
+    load_half<D, TIn, false>(WL, Ap, tid);
+    set_half_identity<D>(WR, tid);
+    __syncthreads();
+    ++nsolve;
+    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+    load_aop_lds<D>(WR, cAi, w, i, g);
+    // rows of A^T (columns of A) and of the symmetric part of Q straight from global memory
+#pragma unroll
+    for (int q = 0; q < D / 16; ++q) {
+      const floatx4 qr = ld4<TIn>(Qp, (long)(16 * w + i) * D + 16 * q + 4 * g);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const long k = 16 * q + 4 * g + t;
+        cAT[4 * q + t] = ld1<TIn>(Ap, k * D + 16 * w + i);
+        cQ[4 * q + t] = 0.5f * (qr[t] + ld1<TIn>(Qp, k * D + 16 * w + i));
+      }
+    }
+    __syncthreads();
+
+    // ---- initial pair [Y1 Y2] = [I Q_T]
+    load_half<D, TIn, false>(WR, QTp, tid);
+    __syncthreads();
+    symmetrise_half<D>(WR, tid);
+    __syncthreads();
+    bool fresh = true;  // Z1 = I, not materialised
+    int since = 0;
+
+    // ---- T-1 reverse symplectic steps with Q_{t-1} = Q
+    for (int s = 1; s < p.T; ++s) {
+      if (fresh) eye_acc<D>(acc1, w, i, g); else load_rows<D>(WL, acc1, w, i, g);
+      gemm_acc<D>(acc1, cG, WR, i, g);   // Z1 + G Z2        (Y1 + Y2 G)
+      store_rows<D>(WL, acc1, w, i, g);
+      __syncthreads();
+      zero_acc<D>(acc2);
+      gemm_acc<D>(acc2, cAi, WL, i, g);  // A^{-1} (.)       (... A^{-T})  = new Z1
+      zero_acc<D>(acc3);
+      gemm_acc<D>(acc3, cAT, WR, i, g);  // A^T Z2           (Y2 A)
+      __syncthreads();
+      store_rows<D>(WL, acc2, w, i, g);
+      __syncthreads();
+      gemm_acc<D>(acc3, cQ, WL, i, g);   // + Q Z1           (+ Y1 Q)      = new Z2
+      __syncthreads();
+      ++since;
+      const bool rebase = (since >= kreb) || (s == p.T - 1);
+      if (!rebase) {
+        store_rows<D>(WR, acc3, w, i, g);
+        __syncthreads();
+        fresh = false;
+        if (pure) {
+          normalise_rows_zland<D>(W, tid);
+          __syncthreads();
+        }
+      } else {
+        // leave Z-land: write the pair untransposed, [Y1 | Y2], and solve Y1 P = Y2
+        store_rows_T<D>(WL, acc2, w, i, g);
+        store_rows_T<D>(WR, acc3, w, i, g);
+        __syncthreads();
+        ++nsolve;
+        if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+        symmetrise_half<D>(WR, tid);     // P is symmetric; also makes it its own Z-land image
+        __syncthreads();
+        fresh = true;
+        since = 0;
+      }
+    }
+
+    // ---- final factor in solved form: M = (I + P_1 G)^{-1} P_1 A
+    eye_acc<D>(acc1, w, i, g);
+    gemm_acc<D>(acc1, cG, WR, i, g);     // rows of I + G P_1 = (I + P_1 G)^T
+    zero_acc<D>(acc3);
+    gemm_acc<D>(acc3, cAT, WR, i, g);    // rows of A^T P_1   = (P_1 A)^T
+    __syncthreads();
+    store_rows_T<D>(WL, acc1, w, i, g);
+    store_rows_T<D>(WR, acc3, w, i, g);
+    __syncthreads();
+    ++nsolve;
+    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+
+    // ---- outputs
+    zero_acc<D>(acc1);
+    gemm_acc<D>(acc1, cAT, WR, i, g);    // P_0 = A^T M
+    load_aop_global<D, float>(wsX, cG, w, i, g);
+    zero_acc<D>(acc2);
+    gemm_acc<D>(acc2, cG, WR, i, g);     // -K_0 = (R^{-1} B^T) M
+    const float nanv = __builtin_nanf("");
+    float x0c[C::NT], x0r[4];
+#pragma unroll
+    for (int c = 0; c < C::NT; ++c) x0c[c] = ld1<TIn>(x0p, tile_col<D>(c, i));
+#pragma unroll
+    for (int v = 0; v < 4; ++v) x0r[v] = ld1<TIn>(x0p, 16 * w + 4 * g + v);
+    float vpart = 0.f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const long row = 16 * w + 4 * g + v;
+      float pu = 0.f, pw = 0.f;
+#pragma unroll
+      for (int c = 0; c < C::NT; ++c) {
+        float pe = acc1[c][v], ke = -acc2[c][v];
+        if (p.flags & TTC_FLAG_STAGE_COST_AT_X0) {
+          const long col = tile_col<D>(c, i);
+          pe += 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
+        }
+        if (info) { pe = nanv; ke = nanv; }
+        acc1[c][v] = pe;
+        acc2[c][v] = ke;
+        pu += ke * x0c[c];
+        pw += pe * x0c[c];
+      }
+      pu = sum16(pu);
+      pw = sum16(pw);
+      if (i == 0) p.u0[prob * D + row] = pu;
+      vpart += x0r[v] * pw;
+    }
+    vpart *= (i == 0) ? 1.f : 0.f;
+    vpart = sum64(vpart);
+    if (lane == 0) s_red[w] = vpart;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int h = 0; h < C::NH; ++h) {
+        const long off = prob * (long)D * D + (long)(16 * w + 4 * g + v) * D + 16 * C::VEC * h + C::VEC * i;
+#pragma unroll
+        for (int tp = 0; tp < C::VEC; ++tp) {
+          if (p.P0) p.P0[off + tp] = acc1[h * C::VEC + tp][v];
+          if (p.K0) p.K0[off + tp] = acc2[h * C::VEC + tp][v];
+        }
+      }
+    __syncthreads();
+    if (tid == 0) {
+      float val = 0.f;
+      for (int ww = 0; ww < C::NW; ++ww) val += s_red[ww];
+      if (p.value) p.value[prob] = val;
+      if (p.info) p.info[prob] = info;
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+static int cu_count() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+    cached = n;
+    return n;
+  }
+  (void)hipGetLastError();
+  return 256;  // MI355X
+}
+// resident workgroups per compute unit the grid is sized for
+static int blocks_per_cu(int d) { return d >= 128 ? 1 : d >= 64 ? 2 : 8; }
+static long long grid_blocks(int d) { return (long long)cu_count() * blocks_per_cu(d); }
+
+static bool shape_supported(const ttc_lqr_problem_t* q) {
+  return q->d == q->m && (q->d == 16 || q->d == 32 || q->d == 64 || q->d == 128);
+}
+static bool aligned_ptr(const void* ptr, size_t a) { return (reinterpret_cast<uintptr_t>(ptr) % a) == 0; }
+
+static ttc_status_t validate(const ttc_lqr_problem_t* q) {
+  if (!q) return TTC_ERR_INVALID_ARG;
+  if (q->n < 0 || q->T < 1 || q->d < 1 || q->m < 1 || q->rebase_every < 0) return TTC_ERR_INVALID_ARG;
+  if (q->in_dtype != TTC_F32 && q->in_dtype != TTC_BF16) return TTC_ERR_INVALID_ARG;
+  if (q->flags & ~(TTC_FLAG_STAGE_COST_AT_X0 | TTC_FLAG_PURE_SYMPLECTIC)) return TTC_ERR_INVALID_ARG;
+  if (!shape_supported(q)) return TTC_ERR_UNSUPPORTED;
+  if (q->n == 0) return TTC_OK;
+  if (!q->A || !q->B || !q->Q || !q->R || !q->x0) return TTC_ERR_INVALID_ARG;
+  const size_t al = q->in_dtype == TTC_F32 ? 16 : 8;
+  const void* ptrs[] = {q->A, q->B, q->Q, q->R, q->QT};
+  const int64_t strides[] = {q->sA, q->sB, q->sQ, q->sR, q->sQT};
+  for (int k = 0; k < 5; ++k) {
+    if (ptrs[k] && !aligned_ptr(ptrs[k], al)) return TTC_ERR_INVALID_ARG;
+    if (strides[k] < 0 || strides[k] % 4) return TTC_ERR_INVALID_ARG;
+  }
+  if (q->sx0 < 0) return TTC_ERR_INVALID_ARG;
+  return TTC_OK;
+}
+
+template <typename TIn>
+static hipError_t launch_solve(const SolveArgs& a, int d, dim3 grid, hipStream_t st) {
+  switch (d) {
+    case 16: hipLaunchKernelGGL((solve_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((solve_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((solve_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((solve_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace ttc
+
+extern "C" {
+
+size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t* problem, int for_rollout) {
+  if (!problem || problem->T < 1 || !ttc::shape_supported(problem)) return 0;
+  const size_t slots = (size_t)ttc::grid_blocks(problem->d);
+  const size_t per = (size_t)problem->d * problem->m * sizeof(float);
+  return slots * per * (for_rollout ? (size_t)problem->T + 1 : 1);
+}
+
+ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solution_t* solution,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t st = ttc::validate(problem);
+  if (st != TTC_OK) return st;
+  if (!solution || !solution->u0) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
+  if (problem->n == 0) return TTC_OK;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) ||
+      workspace_bytes < ttc_lqr_workspace_bytes(problem, 0))
+    return TTC_ERR_WORKSPACE;
+  ttc::SolveArgs a;
+  a.n = problem->n;
+  a.T = problem->T;
+  a.flags = problem->flags;
+  a.rebase_every = problem->rebase_every > 0 ? problem->rebase_every : 2;
+  a.A = problem->A; a.B = problem->B; a.Q = problem->Q; a.R = problem->R; a.QT = problem->QT; a.x0 = problem->x0;
+  a.sA = problem->sA; a.sB = problem->sB; a.sQ = problem->sQ; a.sR = problem->sR; a.sQT = problem->sQT;
+  a.sx0 = problem->sx0;
+  a.P0 = solution->P0; a.K0 = solution->K0; a.u0 = solution->u0; a.value = solution->value;
+  a.info = solution->info;
+  a.ws = static_cast<float*>(workspace);
+  const long long gb = ttc::grid_blocks(problem->d);
+  const dim3 grid((unsigned)(problem->n < gb ? problem->n : gb));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = problem->in_dtype == TTC_F32 ? ttc::launch_solve<float>(a, problem->d, grid, s)
+                                                     : ttc::launch_solve<uint16_t>(a, problem->d, grid, s);
+  return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+}
+
+ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t* problem, float* U, float* X, float* cost,
+                             int32_t* info, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)U; (void)X; (void)cost; (void)info; (void)workspace; (void)workspace_bytes; (void)hip_stream;
+  const ttc_status_t st = ttc::validate(problem);
+  if (st != TTC_OK) return st;
+  return TTC_ERR_UNSUPPORTED;
+}
+
+const char* ttc_status_string(ttc_status_t status) {
+  switch (status) {
+    case TTC_OK: return "ok";
+    case TTC_ERR_INVALID_ARG: return "invalid argument";
+    case TTC_ERR_UNSUPPORTED: return "unsupported shape or option";
+    case TTC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case TTC_ERR_DEVICE: return "HIP runtime error at launch";
+  }
+  return "unknown status";
+}
+
+int ttc_version(void) { return 100; }
+
+}  // extern "C"

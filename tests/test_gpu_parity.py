@@ -1,0 +1,119 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU float64 oracle, element by
+element on the same seeded inputs.  Tolerances: relative error <= 1e-4 (float32 inputs) and <= 2e-2
+(bfloat16 inputs, float32 accumulation) on P0, K0, u0 and the value, per problem (Frobenius / 2-norm)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_09221_amd import binding, synth
+from tests.parity import oracle_solve, rel_err, solve_errors
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL_F32, TOL_BF16 = 1e-4, 2e-2
+
+
+def run(batch, **kw):
+    out = binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, kw.pop("QT", None), batch.x0, batch.T, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def check(batch, tol, QT=None, flag=False, **kw):
+    flags = binding.TTC_FLAG_STAGE_COST_AT_X0 if flag else 0
+    out = run(batch, QT=QT, flags=flags | kw.pop("flags", 0), **kw)
+    assert int(out["info"].abs().max()) == 0
+    errs = solve_errors(out, oracle_solve(batch, QT=QT, flag=flag))
+    print({k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= tol, (k, v)
+    return errs
+
+
+def test_config0_tiny_all_problems():
+    check(synth.make_config("tiny", device=DEV), TOL_F32)
+
+
+@pytest.mark.parametrize("d,T,n", [(16, 8, 1), (16, 1, 5), (16, 2, 70), (32, 8, 37), (64, 8, 600), (128, 4, 9),
+                                    (128, 16, 300)])
+def test_shapes_and_ragged_batches(d, T, n):
+    """n spans less than one grid, a ragged tail, and several passes of the persistent workgroups."""
+    check(synth.make_batch(n, d, d, T, seed=d + T, device=DEV), TOL_F32)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_rebase_period(k):
+    check(synth.make_batch(64, 64, 64, 8, seed=3, device=DEV), TOL_F32, rebase_every=k)
+    check(synth.make_batch(20, 128, 128, 16, seed=4, device=DEV), TOL_F32, rebase_every=k)
+
+
+def test_pure_symplectic_short_horizon():
+    """Alg. 4 as printed (one dense solve for the whole product): accurate only for short horizons."""
+    b = synth.make_batch(32, 16, 16, 4, seed=5, device=DEV)
+    check(b, 2e-3, flags=binding.TTC_FLAG_PURE_SYMPLECTIC)
+
+
+def test_terminal_cost_and_stage_flag():
+    b = synth.make_batch(40, 64, 64, 6, seed=6, device=DEV)
+    QT = (2.0 * b.Q + 0.1 * torch.eye(64, device=DEV)).contiguous()
+    check(b, TOL_F32, QT=QT)
+    check(b, TOL_F32, QT=QT, flag=True)
+
+
+def test_shared_matrices_stride_zero():
+    b = synth.make_batch(50, 32, 32, 5, seed=7, device=DEV)
+    A0, R0 = b.A[:1].contiguous(), b.R[:1].contiguous()
+    shared = synth.LqrBatch(A0.expand(50, -1, -1), b.B, b.Q, R0.expand(50, -1, -1), b.x0, b.T)
+    out = run(shared)
+    ref = oracle_solve(synth.LqrBatch(A0.repeat(50, 1, 1), b.B, b.Q, R0.repeat(50, 1, 1), b.x0, b.T))
+    for k, v in solve_errors(out, ref).items():
+        assert v <= TOL_F32, (k, v)
+
+
+def test_bf16_inputs():
+    for d, T, n in [(16, 8, 64), (64, 8, 64), (128, 32, 24)]:
+        b = synth.make_batch(n, d, d, T, seed=8, device=DEV, dtype="bf16")
+        check(b, TOL_BF16)      # the oracle consumes the same bf16-rounded values
+
+
+def test_long_horizon_config3_sample():
+    c = synth.CONFIGS["long_horizon"]
+    b = synth.make_batch(96, c["d"], c["m"], c["T"], seed=0, device=DEV, rho=c["rho"])
+    check(b, TOL_F32)
+
+
+def test_needs_pivoting():
+    """A close to a cyclic shift: its LU has zero leading pivots, so the dense solves must pivot."""
+    d, n = 32, 12
+    b = synth.make_batch(n, d, d, 5, seed=9, device=DEV)
+    shift = torch.roll(torch.eye(d, device=DEV), 1, dims=1)
+    A = (0.9 * shift + 0.05 * (b.A - torch.eye(d, device=DEV))).contiguous()
+    check(synth.LqrBatch(A, b.B, b.Q, b.R, b.x0, b.T), TOL_F32)
+
+
+def test_info_reports_breakdown():
+    b = synth.make_batch(6, 16, 16, 4, seed=10, device=DEV)
+    A = b.A.clone()
+    A[2] = 0.0                                  # singular A: the A^{-1} solve must fail
+    out = run(synth.LqrBatch(A, b.B, b.Q, b.R, b.x0, b.T))
+    info = out["info"].cpu().numpy()
+    assert info[2] == 2 and (np.delete(info, 2) == 0).all()
+    assert torch.isnan(out["u0"][2]).all() and torch.isnan(out["P0"][2]).all()
+    good = [0, 1, 3, 4, 5]
+    ref = oracle_solve(b.take(torch.tensor(good, device=DEV)))
+    assert rel_err(out["u0"][good].cpu().numpy(), ref["u0"]).max() <= TOL_F32
+
+
+def test_optional_outputs_and_determinism():
+    b = synth.make_batch(33, 64, 64, 8, seed=11, device=DEV)
+    full = run(b)
+    slim = run(b, want_P0=False, want_K0=False)
+    assert "P0" not in slim and torch.equal(slim["u0"], full["u0"]) and torch.equal(slim["value"], full["value"])
+    again = run(b)
+    assert torch.equal(again["P0"], full["P0"]) and torch.equal(again["K0"], full["K0"])
+
+
+def test_empty_batch():
+    b = synth.make_batch(1, 16, 16, 4, seed=0, device=DEV)
+    out = binding.ttc_lqr_solve(b.A[:0], b.B[:0], b.Q[:0], b.R[:0], None, b.x0[:0], 4)
+    assert out["u0"].shape == (0, 16)
