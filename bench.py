@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched LQR hot path on one MI355X.
+
+A "step" is one pass of the whole hot path (ttc_lqr_solve: load, setup, reverse symplectic steps,
+re-bases, final solve, outputs) over every problem of the workload, inputs resident in HBM.
+Prints ONE JSON line: problems/s plus a roofline object for the solve kernel (fp32 MFMA) and the CPU
+oracle timed on the host cores on a bounded sample of the same inputs.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llm_adapter] [--n N] [--rebase-every k]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
+DEFAULT_REBASE = 3              # keep in step with the library default
+
+
+def alg_flops(d, T, k):
+    """Algorithmic flops of one problem (2*M*N*K per product): what the re-based symplectic method
+    has to compute, not what the kernel happens to execute.
+      setup   R^{-1}B^T factor d^3/3, G = B R^{-1} B^T 3 d^3, A^{-1} 2 d^3
+      steps   (T-1) reverse symplectic steps of 4 products: 8 d^3 each
+      re-base ceil((T-1)/k) pivoted solves Y1^{-1} Y2: 8/3 d^3 each
+      final   I + G P_1 and A^T P_1 (4 d^3), the solve (8/3 d^3), P_0 and K_0 (4 d^3)
+    """
+    nreb = math.ceil((T - 1) / k) if T > 1 else 0
+    return (1.0 / 3 + 3 + 2 + 8 * (T - 1) + (8.0 / 3) * (nreb + 1) + 8) * d ** 3
+
+
+def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):
+    """The oracle, as it stands, on the host cores: one problem chunk per thread, BLAS single-threaded."""
+    import numpy as np
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import lqr_oracle
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:  # pragma: no cover
+        threadpool_limits = None
+    cores = min(16, os.cpu_count() or 1)
+    sub = batch.take(slice(0, sample))
+    A, B, Q, R, x0 = sub.numpy64()
+    chunks = np.array_split(np.arange(sample), cores * 4)
+
+    def work(ix):
+        if len(ix) == 0:
+            return None
+        r = lqr_oracle.riccati_solve(A[ix], B[ix], Q[ix], R[ix], None, x0[ix], sub.T)
+        return ix, {k: r[k] for k in ("P0", "K0", "u0", "value")}
+
+    import contextlib
+    limit = threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()
+    with limit:
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=cores) as ex:
+            parts = [p for p in ex.map(work, chunks) if p is not None]
+        dt = time.perf_counter() - t0
+    ref = {k: np.concatenate([p[1][k] for p in parts]) for k in ("P0", "K0", "u0", "value")}
+    return ref, dt, cores
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="llm_adapter")
+    ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
+    ap.add_argument("--rebase-every", type=int, default=DEFAULT_REBASE)
+    ap.add_argument("--cpu-sample", type=int, default=None)
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (problems are independent; see DESIGN.md for the "
+              "sharding note). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_09221_amd import binding, synth
+    from tests.parity import rel_err
+
+    cfg = synth.CONFIGS[args.config]
+    n = args.n or synth.config_problems(args.config)
+    d, m, T, k = cfg["d"], cfg["m"], cfg["T"], args.rebase_every
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    binding.load()
+
+    batch = synth.make_batch(n, d, m, T, seed=0, device=dev, dtype=cfg["dtype"], rho=cfg["rho"])
+    out = {
+        "P0": torch.empty((n, d, d), dtype=torch.float32, device=dev),
+        "K0": torch.empty((n, m, d), dtype=torch.float32, device=dev),
+        "u0": torch.empty((n, m), dtype=torch.float32, device=dev),
+        "value": torch.empty((n,), dtype=torch.float32, device=dev),
+        "info": torch.empty((n,), dtype=torch.int32, device=dev),
+    }
+    prob = binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, 0, k)
+    ws = torch.empty((max(binding.ttc_lqr_workspace_bytes(prob), 16),), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, rebase_every=k,
+                              out=out, workspace=ws, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record(stream)      # HIP events on the stream the kernel is launched on
+        step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]   # one solve_kernel launch per step
+    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+    ms_per_step = wall / args.steps * 1e3
+    value = n / (wall / args.steps)
+    assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
+
+    flops = alg_flops(d, T, k) * n
+    achieved = flops / avg_kernel_s / 1e12
+    in_bytes = n * (2 * d * d + d * m + m * m + d) * batch.A.element_size()
+    out_bytes = n * (d * d + m * d + m + 2) * 4
+    res = {
+        "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d" % (d, T),
+        "value": value, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.config, "problems": n, "d": d, "m": m, "T": T, "input_dtype": cfg["dtype"],
+                   "rebase_every": k, "outputs": "P0,K0,u0,value"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "kernel": "solve_kernel<%d>" % d, "kernel_ms": avg_kernel_s * 1e3,
+                     "alg_flops_per_problem": alg_flops(d, T, k),
+                     "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / avg_kernel_s / 1e12,
+                     "alg_bytes_per_launch": in_bytes + out_bytes,
+                     "alg_GBps": (in_bytes + out_bytes) / avg_kernel_s / 1e9},
+    }
+    if not args.no_cpu:
+        cores_guess = min(16, os.cpu_count() or 1)
+        pilot = min(n, cores_guess * 8)
+        _, pilot_dt, _ = cpu_baseline(batch, pilot)             # calibrate: aim at ~15 s of wall-clock
+        sample = args.cpu_sample or int(min(n, max(pilot, pilot * 15.0 / max(pilot_dt, 1e-3))))
+        ref, dt, cores = cpu_baseline(batch, sample)
+        errs = {kk: float(rel_err(out[kk][:sample].cpu().numpy(), ref[kk]).max()) for kk in ("P0", "K0", "u0", "value")}
+        res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": cores, "kind": "oracle",
+                               "sample": "first %d problems of the same workload, float64 numpy Riccati, "
+                                         "%.1f s wall" % (sample, dt)}
+        res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": 1e-4 if cfg["dtype"] == "f32" else 2e-2}
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -332,9 +332,10 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
   const ttc_status_t st = ttc::validate(problem);
   if (st != TTC_OK) return st;
-  if (!solution || !solution->u0) return TTC_ERR_INVALID_ARG;
-  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
+  if (!solution) return TTC_ERR_INVALID_ARG;
   if (problem->n == 0) return TTC_OK;
+  if (!solution->u0) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
   if (!workspace || !ttc::aligned_ptr(workspace, 16) ||
       workspace_bytes < ttc_lqr_workspace_bytes(problem, 0))
     return TTC_ERR_WORKSPACE;
@@ -342,7 +343,7 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   a.n = problem->n;
   a.T = problem->T;
   a.flags = problem->flags;
-  a.rebase_every = problem->rebase_every > 0 ? problem->rebase_every : 2;
+  a.rebase_every = problem->rebase_every > 0 ? problem->rebase_every : 3;
   a.A = problem->A; a.B = problem->B; a.Q = problem->Q; a.R = problem->R; a.QT = problem->QT; a.x0 = problem->x0;
   a.sA = problem->sA; a.sB = problem->sB; a.sQ = problem->sQ; a.sR = problem->sR; a.sQT = problem->sQT;
   a.sx0 = problem->sx0;
