@@ -265,6 +265,175 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
 }
 
 // ------------------------------------------------------------------------------------------------
+struct RolloutArgs {
+  long long n;
+  int T, flags;
+  const void *A, *B, *Q, *R, *QT, *x0;
+  long long sA, sB, sQ, sR, sQT, sx0;
+  float *U, *X, *cost;
+  int* info;
+  float* ws;  // gridDim.x slots of (T+1) d*d floats: R^{-1} B^T, then K_0 .. K_{T-1}
+};
+
+// y[r] = sum_c M[r][c] x[c] for the row r = tid/4 of a row-major global d x d matrix; the four
+// threads of a row each take a quarter of the columns.  Every thread of the quad gets the sum.
+template <int D, typename TM>
+__device__ __forceinline__ float matvec_row(const TM* M, const float* xs, int tid) {
+  const int r = tid >> 2, part = tid & 3;
+  float s = 0.f;
+#pragma unroll
+  for (int c4 = part * (D / 4); c4 < (part + 1) * (D / 4); c4 += 4) {
+    const floatx4 mv = ld4<TM>(M, (long)r * D + c4);
+    s += mv[0] * xs[c4] + mv[1] * xs[c4 + 1] + mv[2] * xs[c4 + 2] + mv[3] * xs[c4 + 3];
+  }
+  s += __shfl_xor(s, 1, 64);
+  s += __shfl_xor(s, 2, 64);
+  return s;
+}
+
+// Roll-out kernel (Alg. 1 with r = 0).  Backward sweep: the value matrices P_T .. P_1 are produced
+// one step at a time in the re-based form of the reverse symplectic factor (re-base every step):
+//     M_t = (I + P_{t+1} G)^{-1} P_{t+1} A,   K_t = -(R^{-1} B^T) M_t,   P_t = Q + A^T M_t,
+// the gains go to the workspace; forward sweep: u_t = K_t x_t, x_{t+1} = A x_t + B u_t and the cost.
+template <int D, typename TIn>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs p) {
+  using C = Cfg<D>;
+  __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
+  __shared__ int s_piv[D];
+  __shared__ float s_inv[D];
+  __shared__ float s_red[C::NW];
+  __shared__ float s_x[D], s_u[D], s_xn[D];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  float* const WL = W;
+  float* const WR = W + D;
+  float* const wsX = p.ws + (long)blockIdx.x * (p.T + 1) * D * D;
+  float* const wsK = wsX + D * D;
+
+  for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
+    const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
+    const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
+    const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
+    const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
+    const TIn* QTp = p.QT ? reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT : Qp;
+    const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
+    int info = 0, nsolve = 0;
+    float cG[C::KS], cX[C::KS], cAT[C::KS];
+    floatx4 qd[C::NT], acc1[C::NT], acc2[C::NT], acc3[C::NT];
+
+    // ---- setup: X = R^{-1} B^T, G = B X
+    load_half<D, TIn, false>(WL, Rp, tid);
+    load_half<D, TIn, true>(WR, Bp, tid);
+    __syncthreads();
+    symmetrise_half<D>(WL, tid);
+    __syncthreads();
+    ++nsolve;
+    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+    load_aop_lds<D>(WR, cX, w, i, g);
+    load_aop_global<D, TIn>(Bp, cG, w, i, g);
+    zero_acc<D>(acc1);
+    gemm_acc<D>(acc1, cG, WR, i, g);
+    store_rows<D>(WL, acc1, w, i, g);
+    __syncthreads();
+    symmetrise_half<D>(WL, tid);
+    __syncthreads();
+    load_aop_lds<D>(WL, cG, w, i, g);
+#pragma unroll
+    for (int q = 0; q < D / 16; ++q)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) cAT[4 * q + t] = ld1<TIn>(Ap, (long)(16 * q + 4 * g + t) * D + 16 * w + i);
+#pragma unroll
+    for (int c = 0; c < C::NT; ++c)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const long row = 16 * w + 4 * g + v, col = tile_col<D>(c, i);
+        qd[c][v] = 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
+      }
+    __syncthreads();
+    load_half<D, TIn, false>(WR, QTp, tid);
+    __syncthreads();
+    symmetrise_half<D>(WR, tid);
+    __syncthreads();
+
+    // ---- backward sweep
+    for (int t = p.T - 1; t >= 0; --t) {
+      eye_acc<D>(acc1, w, i, g);
+      gemm_acc<D>(acc1, cG, WR, i, g);   // (I + P G)^T
+      zero_acc<D>(acc3);
+      gemm_acc<D>(acc3, cAT, WR, i, g);  // (P A)^T
+      __syncthreads();
+      store_rows_T<D>(WL, acc1, w, i, g);
+      store_rows_T<D>(WR, acc3, w, i, g);
+      __syncthreads();
+      ++nsolve;
+      if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+      zero_acc<D>(acc2);
+      gemm_acc<D>(acc2, cX, WR, i, g);   // -K_t
+      float* Kt = wsK + (long)t * D * D;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int h = 0; h < C::NH; ++h)
+#pragma unroll
+          for (int tp = 0; tp < C::VEC; ++tp)
+            Kt[(16 * w + 4 * g + v) * D + 16 * C::VEC * h + C::VEC * i + tp] = -acc2[h * C::VEC + tp][v];
+      if (t >= 1) {
+#pragma unroll
+        for (int c = 0; c < C::NT; ++c) acc1[c] = qd[c];
+        gemm_acc<D>(acc1, cAT, WR, i, g);  // P_t = Q + A^T M_t
+        __syncthreads();
+        store_rows<D>(WR, acc1, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WR, tid);
+        __syncthreads();
+      }
+    }
+    __syncthreads();  // gains visible to the whole workgroup
+
+    // ---- forward sweep
+    const int r = tid >> 2, part = tid & 3;
+    if (tid < D) s_x[tid] = ld1<TIn>(x0p, tid);
+    __syncthreads();
+    float cpart = 0.f;
+    if (p.flags & TTC_FLAG_STAGE_COST_AT_X0) {
+      const float qx = matvec_row<D, TIn>(Qp, s_x, tid);
+      if (part == 0) cpart += s_x[r] * qx;
+    }
+    if (p.X && tid < D) p.X[prob * (long)(p.T + 1) * D + tid] = s_x[tid];
+    for (int t = 0; t < p.T; ++t) {
+      const float u = matvec_row<D, float>(wsK + (long)t * D * D, s_x, tid);
+      if (part == 0) s_u[r] = u;
+      __syncthreads();
+      const float ru = matvec_row<D, TIn>(Rp, s_u, tid);
+      const float xn = matvec_row<D, TIn>(Ap, s_x, tid) + matvec_row<D, TIn>(Bp, s_u, tid);
+      if (part == 0) {
+        cpart += s_u[r] * ru;
+        s_xn[r] = xn;
+        p.U[(prob * p.T + t) * (long)D + r] = info ? __builtin_nanf("") : u;
+      }
+      __syncthreads();
+      const float qx = matvec_row<D, TIn>(t == p.T - 1 ? QTp : Qp, s_xn, tid);
+      if (part == 0) {
+        cpart += s_xn[r] * qx;
+        s_x[r] = xn;
+        if (p.X) p.X[(prob * (p.T + 1) + t + 1) * (long)D + r] = info ? __builtin_nanf("") : xn;
+      }
+      __syncthreads();
+    }
+    cpart = sum64(cpart);
+    if (lane == 0) s_red[w] = cpart;
+    __syncthreads();
+    if (tid == 0) {
+      float cst = 0.f;
+      for (int ww = 0; ww < C::NW; ++ww) cst += s_red[ww];
+      if (p.cost) p.cost[prob] = info ? __builtin_nanf("") : cst;
+      if (p.info) p.info[prob] = info;
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 static int cu_count() {
   static int cached = 0;
   if (cached > 0) return cached;
@@ -317,6 +486,18 @@ static hipError_t launch_solve(const SolveArgs& a, int d, dim3 grid, hipStream_t
   return hipGetLastError();
 }
 
+template <typename TIn>
+static hipError_t launch_rollout(const RolloutArgs& a, int d, dim3 grid, hipStream_t st) {
+  switch (d) {
+    case 16: hipLaunchKernelGGL((rollout_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((rollout_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((rollout_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((rollout_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 }  // namespace ttc
 
 extern "C" {
@@ -360,10 +541,28 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
 
 ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t* problem, float* U, float* X, float* cost,
                              int32_t* info, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)U; (void)X; (void)cost; (void)info; (void)workspace; (void)workspace_bytes; (void)hip_stream;
   const ttc_status_t st = ttc::validate(problem);
   if (st != TTC_OK) return st;
-  return TTC_ERR_UNSUPPORTED;
+  if (problem->n == 0) return TTC_OK;
+  if (!U) return TTC_ERR_INVALID_ARG;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) ||
+      workspace_bytes < ttc_lqr_workspace_bytes(problem, 1))
+    return TTC_ERR_WORKSPACE;
+  ttc::RolloutArgs a;
+  a.n = problem->n;
+  a.T = problem->T;
+  a.flags = problem->flags;
+  a.A = problem->A; a.B = problem->B; a.Q = problem->Q; a.R = problem->R; a.QT = problem->QT; a.x0 = problem->x0;
+  a.sA = problem->sA; a.sB = problem->sB; a.sQ = problem->sQ; a.sR = problem->sR; a.sQT = problem->sQT;
+  a.sx0 = problem->sx0;
+  a.U = U; a.X = X; a.cost = cost; a.info = info;
+  a.ws = static_cast<float*>(workspace);
+  const long long gb = ttc::grid_blocks(problem->d);
+  const dim3 grid((unsigned)(problem->n < gb ? problem->n : gb));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = problem->in_dtype == TTC_F32 ? ttc::launch_rollout<float>(a, problem->d, grid, s)
+                                                     : ttc::launch_rollout<uint16_t>(a, problem->d, grid, s);
+  return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 
 const char* ttc_status_string(ttc_status_t status) {
