@@ -19,6 +19,18 @@ namespace ttc {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
+// compile-time loop: f(std::integral_constant<int, I>) for I = B..E-1.  Used where register arrays
+// must only ever be indexed by constants (a plain "#pragma unroll" is a request, not a guarantee).
+template <int I>
+struct IntC { static constexpr int value = I; };
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(IntC<B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 template <int D>
 struct Cfg {
   static constexpr int NTHR = 4 * D;            // threads per workgroup
@@ -215,85 +227,183 @@ __device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>:
 }
 
 // ----------------------------------------------------------------------------------------------
-// Dense solve M X = RHS inside LDS: Gauss-Jordan elimination with partial (row) pivoting on the
-// augmented d x 2d array W = [M | RHS] (row r at W + r*PITCH; M = columns [0,d), RHS = [d,2d)).
-// Rows are never moved: the pivot row of column c is remembered in s_piv[c] (implicit pivoting) and
-// the solution is gathered at the end, X[c][:] = RHS[s_piv[c]][:] / pivot_c, into columns [d,2d).
-// Returns nonzero (uniformly over the workgroup) if a pivot was zero or not finite.  All threads of
-// the workgroup must call it; it starts by assuming W is visible (caller synchronised) and ends
-// with the result visible to every thread.
+// Dense solve M X = RHS inside LDS: blocked Gauss-Jordan elimination with partial (row) pivoting on
+// the augmented d x 2d array W = [M | RHS] (row r at W + r*PITCH; M = columns [0,d), RHS = [d,2d)),
+// 16 columns per panel.  Rows are never moved: the pivot row of column c is remembered in s_piv[c]
+// (implicit pivoting) and the solution is gathered at the end, X[c][:] = RHS[s_piv[c]][:] / pivot_c.
+//
+// Per panel P = [16p, 16p+16):
+//   (a) wavefront 0 holds the d x 16 panel in registers (a lane owns rows lane, lane+64) and runs
+//       unblocked Gauss-Jordan on it: pivot = max |.| over rows never used as a pivot (one DPP max
+//       of a packed key), pivot row broadcast with v_readlane, every other row -- pivoted earlier or
+//       not -- gets its multiplier and is updated.  It leaves in W[:, P] the multiplier matrix Lm
+//       (for the j-th pivot row of the panel: zero up to column j, the later "Jordan" multipliers
+//       after it) and in s_L11 the unit-lower multipliers among the 16 pivot rows.
+//   (b) one thread per remaining column: gather the 16 pivot-row entries, forward-substitute with
+//       L11 -> U12; U12 goes back into the pivot rows and, negated, into the 16 x 2d buffer Ub.
+//   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows: wavefront w owns rows [16w,16w+16);
+//       the product is formed transposed (MFMA M index = column, N index = row) so that a lane's
+//       four accumulator values are contiguous in LDS.
+// Returns nonzero (uniformly) if a pivot was zero or not finite.  All threads must call it; W must be
+// visible on entry (caller synchronised); the result is visible to every thread on return.
 template <int D>
-__device__ int lds_solve(float* W, int* s_piv, float* s_inv, int tid) {
+struct SolveScratch {
+  float Ub[16 * Cfg<D>::PITCH];
+  float L11[16 * 16];
+  float inv[D];
+  int piv[D];
+  int flag;
+};
+
+template <int D>
+__device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) {
   using C = Cfg<D>;
-  constexpr int NG = D / 2;   // float4 column groups across the 2d columns
-  constexpr int RPS = D / 8;  // rows per thread: NTHR / NG = 8 row slices
+  constexpr int NP = D / 16;
   constexpr int NRL = (D + 63) / 64;
-  const int lane = tid & 63;
-  const int cg = tid % NG, rs = tid / NG;
-  bool done[NRL];
+  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  bool active[NRL];
 #pragma unroll
-  for (int rr = 0; rr < NRL; ++rr) done[rr] = false;
+  for (int rr = 0; rr < NRL; ++rr) active[rr] = (lane + 64 * rr) < D;
   int bad = 0;
-  for (int c = 0; c < D; ++c) {
-    // pivot search, done redundantly (and identically) by every wavefront: key = |value| with the
-    // low 7 mantissa bits replaced by (127 - row), so that a single unsigned max gives the argmax
-    uint32_t key = 0;
+
+  for (int p = 0; p < NP; ++p) {
+    const int cb = 16 * p;
+    // ---------------------------------------------------------------- (a) panel, wavefront 0
+    if (w == 0) {
+      float a[NRL][16];
+      int myj[NRL];
 #pragma unroll
-    for (int rr = 0; rr < NRL; ++rr) {
-      const int r = lane + 64 * rr;
-      if (r < D && !done[rr]) {
-        const uint32_t k = (__float_as_uint(fabsf(W[r * C::PITCH + c])) & 0xFFFFFF80u) | (uint32_t)(127 - r);
-        key = k > key ? k : key;
+      for (int rr = 0; rr < NRL; ++rr) {
+        const int r = lane + 64 * rr;
+        myj[rr] = -1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          floatx4 t = floatx4{0.f, 0.f, 0.f, 0.f};
+          if (r < D) t = *reinterpret_cast<const floatx4*>(W + r * C::PITCH + cb + 4 * q);
+          a[rr][4 * q + 0] = t[0]; a[rr][4 * q + 1] = t[1]; a[rr][4 * q + 2] = t[2]; a[rr][4 * q + 3] = t[3];
+        }
       }
-    }
-    key = wave_max_u32(key);
-    int pr = 127 - (int)(key & 0x7Fu);
-    pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
-    const float pv = W[pr * C::PITCH + c];
-    const float apv = fabsf(pv);
-    if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
-    const float inv = 1.0f / pv;
+      static_for<0, 16>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        uint32_t key = 0;
 #pragma unroll
-    for (int rr = 0; rr < NRL; ++rr)
-      if (lane + 64 * rr == pr) done[rr] = true;
-    if (tid == 0) { s_piv[c] = pr; s_inv[c] = inv; }
-    // eliminate column c from every other row, columns > c only (column c itself is left as is:
-    // it holds the multipliers every thread reads during this phase)
-    const int cg0 = (c + 1) >> 2;
-    if (cg >= cg0) {
-      const int cb = 4 * cg;
-      const floatx4 prow = *reinterpret_cast<const floatx4*>(W + pr * C::PITCH + cb);
-#pragma unroll 4
-      for (int rr = 0; rr < RPS; ++rr) {
-        const int r = rs * RPS + rr;
-        if (r != pr) {
-          const float mlt = W[r * C::PITCH + c] * inv;
-          floatx4* px = reinterpret_cast<floatx4*>(W + r * C::PITCH + cb);
-          const floatx4 x = *px;
-          floatx4 y = x - mlt * prow;
-          if (cb + 0 <= c) y[0] = x[0];
-          if (cb + 1 <= c) y[1] = x[1];
-          if (cb + 2 <= c) y[2] = x[2];
-          if (cb + 3 <= c) y[3] = x[3];
-          *px = y;
+        for (int rr = 0; rr < NRL; ++rr) {
+          const uint32_t k = (__float_as_uint(fabsf(a[rr][j])) & 0xFFFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
+          key = (active[rr] && k > key) ? k : key;
+        }
+        key = wave_max_u32(key);
+        int pr = 127 - (int)(key & 0x7Fu);
+        pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
+        const int pl = pr & 63;
+        const bool ps = (NRL > 1) && (pr >= 64);
+        float prow[16];
+        static_for<j, 16>([&](auto JJ) {
+          constexpr int jj = decltype(JJ)::value;
+          const float src = ps ? a[NRL - 1][jj] : a[0][jj];
+          prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, src), pl));
+        });
+        const float apv = fabsf(prow[j]);
+        if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
+        const float inv = 1.0f / prow[j];
+#pragma unroll
+        for (int rr = 0; rr < NRL; ++rr) {
+          const bool mine = (lane == pl) && ((rr == NRL - 1 && NRL > 1) == ps);
+          const float l = mine ? 0.f : a[rr][j] * inv;
+          active[rr] = active[rr] && !mine;
+          myj[rr] = mine ? j : myj[rr];
+          a[rr][j] = mine ? a[rr][j] : l;
+          static_for<j + 1, 16>([&](auto JJ) {
+            constexpr int jj = decltype(JJ)::value;
+            a[rr][jj] -= l * prow[jj];      // l = 0 for the pivot row itself
+          });
+        }
+        if (lane == 0) { S.piv[cb + j] = pr; S.inv[cb + j] = inv; }
+      });
+#pragma unroll
+      for (int rr = 0; rr < NRL; ++rr) {
+        const int r = lane + 64 * rr;
+        if (r < D) {
+          const int j0 = myj[rr];
+          if (j0 >= 0) {
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+              if (jj < j0) S.L11[j0 * 16 + jj] = a[rr][jj];
+              if (jj <= j0) a[rr][jj] = 0.f;
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            floatx4 t;
+            t[0] = a[rr][4 * q + 0]; t[1] = a[rr][4 * q + 1]; t[2] = a[rr][4 * q + 2]; t[3] = a[rr][4 * q + 3];
+            *reinterpret_cast<floatx4*>(W + r * C::PITCH + cb + 4 * q) = t;
+          }
         }
       }
     }
     __syncthreads();
+    // ---------------------------------------------------------------- (b) U12, one thread per column
+    const int nrest = 2 * D - cb - 16;
+    if (tid < nrest) {
+      const int c = cb + 16 + tid;
+      float u[16];
+      int pv[16];
+      static_for<0, 16>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        pv[j] = S.piv[cb + j];
+        u[j] = W[pv[j] * C::PITCH + c];
+      });
+      static_for<1, 16>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        static_for<0, (j + 3) / 4>([&](auto Q) {
+          constexpr int q = decltype(Q)::value;
+          const floatx4 l = *reinterpret_cast<const floatx4*>(S.L11 + j * 16 + 4 * q);
+          static_for<0, 4>([&](auto E) {
+            constexpr int e = decltype(E)::value;
+            if constexpr (4 * q + e < j) u[j] -= l[e] * u[4 * q + e];
+          });
+        });
+      });
+      static_for<0, 16>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        S.Ub[j * C::PITCH + c] = -u[j];
+        W[pv[j] * C::PITCH + c] = u[j];
+      });
+    }
+    __syncthreads();
+    // ---------------------------------------------------------------- (c) trailing update on MFMA
+    {
+      float bl[4];
+      const float* lrow = W + (16 * w + i) * C::PITCH + cb + g;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) bl[kk] = lrow[4 * kk];
+      const int nct = nrest / 16;
+      float* crow = W + (16 * w + i) * C::PITCH + cb + 16 + 4 * g;
+      const float* urow = S.Ub + g * C::PITCH + cb + 16 + i;
+      for (int ct = 0; ct < nct; ++ct) {
+        floatx4 acc = *reinterpret_cast<const floatx4*>(crow + 16 * ct);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          acc = __builtin_amdgcn_mfma_f32_16x16x4f32(urow[4 * kk * C::PITCH + 16 * ct], bl[kk], acc, 0, 0, 0);
+        *reinterpret_cast<floatx4*>(crow + 16 * ct) = acc;
+      }
+    }
+    __syncthreads();
   }
+  if (tid == 0) S.flag = bad;
   // gather + scale into the (now dead) left half, then copy back to the right half
   for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
     const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
-    const floatx4 x = *reinterpret_cast<const floatx4*>(W + s_piv[c] * C::PITCH + D + j4);
-    *reinterpret_cast<floatx4*>(W + c * C::PITCH + j4) = x * s_inv[c];
+    const floatx4 x = *reinterpret_cast<const floatx4*>(W + S.piv[c] * C::PITCH + D + j4);
+    *reinterpret_cast<floatx4*>(W + c * C::PITCH + j4) = x * S.inv[c];
   }
   __syncthreads();
   for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
     const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
     *reinterpret_cast<floatx4*>(W + c * C::PITCH + D + j4) = *reinterpret_cast<const floatx4*>(W + c * C::PITCH + j4);
   }
+  const int flag = S.flag;
   __syncthreads();
-  return bad;
+  return flag;
 }
 
 // Row normalisation of [Y1 Y2] (App. C "Numerical Stability") in Z-land: column c of Z is row c of

@@ -81,8 +81,7 @@ template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
-  __shared__ int s_piv[D];
-  __shared__ float s_inv[D];
+  __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
   __shared__ float s_red[C::NW];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
@@ -110,7 +109,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     symmetrise_half<D>(WL, tid);
     __syncthreads();
     ++nsolve;
-    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
     for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {  // keep X for the final gain
       const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
       *reinterpret_cast<floatx4*>(wsX + r * D + c4) = *reinterpret_cast<const floatx4*>(WR + r * C::PITCH + c4);
@@ -130,7 +129,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     set_half_identity<D>(WR, tid);
     __syncthreads();
     ++nsolve;
-    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
     load_aop_lds<D>(WR, cAi, w, i, g);
     // rows of A^T (columns of A) and of the symmetric part of Q straight from global memory
 #pragma unroll
@@ -184,7 +183,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
         store_rows_T<D>(WR, acc3, w, i, g);
         __syncthreads();
         ++nsolve;
-        if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+        if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
         symmetrise_half<D>(WR, tid);     // P is symmetric; also makes it its own Z-land image
         __syncthreads();
         fresh = true;
@@ -202,7 +201,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     store_rows_T<D>(WR, acc3, w, i, g);
     __syncthreads();
     ++nsolve;
-    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
 
     // ---- outputs
     zero_acc<D>(acc1);
@@ -299,8 +298,7 @@ template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs p) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
-  __shared__ int s_piv[D];
-  __shared__ float s_inv[D];
+  __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
   __shared__ float s_red[C::NW];
   __shared__ float s_x[D], s_u[D], s_xn[D];
 
@@ -328,7 +326,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
     symmetrise_half<D>(WL, tid);
     __syncthreads();
     ++nsolve;
-    if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
     load_aop_lds<D>(WR, cX, w, i, g);
     load_aop_global<D, TIn>(Bp, cG, w, i, g);
     zero_acc<D>(acc1);
@@ -366,7 +364,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
       store_rows_T<D>(WR, acc3, w, i, g);
       __syncthreads();
       ++nsolve;
-      if (lds_solve<D>(W, s_piv, s_inv, tid) && !info) info = nsolve;
+      if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
       zero_acc<D>(acc2);
       gemm_acc<D>(acc2, cX, WR, i, g);   // -K_t
       float* Kt = wsK + (long)t * D * D;
