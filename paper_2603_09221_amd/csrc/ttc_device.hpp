@@ -1,7 +1,8 @@
 // Device-side building blocks of the batched LQR solver (gfx950 / CDNA4, wave64).
 //
-// One workgroup solves one problem at a time.  A workgroup has D/16 wavefronts; wavefront w owns
-// rows [16w, 16w+16) of every d x d product it forms.  The d x 2d pair [Y1 Y2] of the reverse
+// One workgroup solves one problem at a time.  Every d x d product is formed in 16-row blocks; a
+// wavefront owns RB of them (two at d >= 32: 256 threads at d = 128, one wavefront per SIMD, so that
+// each wavefront may use the whole 512-entry register file).  The d x 2d pair [Y1 Y2] of the reverse
 // symplectic iteration (Thm 3.3) lives in LDS in transposed form Z = [Y1 Y2]^T ("Z-land": left
 // half Z1 = Y1^T, right half Z2 = Y2^T), so that one factored step (App. C "Kernel Fusion")
 //     Y1 <- (Y1 + Y2 G) A^{-T},   Y2 <- Y2 A + Y1 Q
@@ -33,8 +34,10 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 template <int D>
 struct Cfg {
-  static constexpr int NTHR = 4 * D;            // threads per workgroup
-  static constexpr int NW = D / 16;             // wavefronts per workgroup
+  static constexpr int RB = D >= 32 ? 2 : 1;    // 16-row blocks owned by one wavefront
+  static constexpr int NRT = D / 16;            // 16-row blocks (= 16-column tiles) of a d x d matrix
+  static constexpr int NW = NRT / RB;           // wavefronts per workgroup
+  static constexpr int NTHR = 64 * NW;          // threads per workgroup (256 at d = 128: one wave per SIMD)
   static constexpr int KS = D / 4;              // k-steps of v_mfma_f32_16x16x4_f32 per product
   static constexpr int NT = D / 16;             // 16-column tiles per row block
   static constexpr int VEC = NT >= 4 ? 4 : NT;  // consecutive floats per B-operand LDS read
@@ -128,7 +131,7 @@ __device__ __forceinline__ float sum64(float x) {
 }
 
 // ----------------------------------------------------------------------------------------------
-// Row-block product on the matrix cores: acc(16 x D) += C[16w:16w+16, :] * Z(D x D).
+// Row-block product on the matrix cores: acc(16 x D) += C[16w:16w+16, :] * Z(D x D) for each row block w of the wavefront.
 //
 // v_mfma_f32_16x16x4_f32 operand layout (lane = 16 g + i): A operand = A[i][g], B operand =
 // B[g][i], accumulator register v = D[4 g + v][i].
@@ -139,25 +142,35 @@ __device__ __forceinline__ float sum64(float x) {
 //     set { 16*VEC*h + VEC*i + tp : i = 0..15 }.
 //   * acc[c][v] is therefore element (row 16w+4g+v, column 16*VEC*h + VEC*i + tp) of the product.
 template <int D>
-__device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::NT], const float (&a)[Cfg<D>::KS],
+__device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
+                                         const float (&a)[Cfg<D>::RB][Cfg<D>::KS],
                                          const float* __restrict__ Zb, int i, int g) {
   using C = Cfg<D>;
+  // software pipeline of depth one: the B operand of k-step ks+1 is read from LDS while the RB*NT
+  // matrix-core instructions of k-step ks run (every B value feeds all RB row blocks); scheduling
+  // barriers keep the compiler from hoisting more reads than that.
+  const float* base = Zb + 4 * g * C::PITCH + C::VEC * i;
+  float b[2][C::NH][C::VEC];
 #pragma unroll
-  for (int q = 0; q < D / 16; ++q) {
+  for (int h = 0; h < C::NH; ++h) lds_ldv<C::VEC>(base + 16 * C::VEC * h, b[0][h]);
+  static_for<0, C::KS>([&](auto KS_) {
+    constexpr int ks = decltype(KS_)::value;  // = 4q + t, contraction rows 16q + 4g + t
+    constexpr int cur = ks & 1, nxt = cur ^ 1;
+    if constexpr (ks + 1 < C::KS) {
+      constexpr int q1 = (ks + 1) / 4, t1 = (ks + 1) % 4;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const float* row = Zb + (16 * q + 4 * g + t) * C::PITCH + C::VEC * i;
-#pragma unroll
-      for (int h = 0; h < C::NH; ++h) {
-        float b[C::VEC];
-        lds_ldv<C::VEC>(row + 16 * C::VEC * h, b);
-#pragma unroll
-        for (int tp = 0; tp < C::VEC; ++tp)
-          acc[h * C::VEC + tp] =
-              __builtin_amdgcn_mfma_f32_16x16x4f32(a[4 * q + t], b[tp], acc[h * C::VEC + tp], 0, 0, 0);
-      }
+      for (int h = 0; h < C::NH; ++h) lds_ldv<C::VEC>(base + (16 * q1 + t1) * C::PITCH + 16 * C::VEC * h, b[nxt][h]);
     }
-  }
+#pragma unroll
+    for (int h = 0; h < C::NH; ++h)
+#pragma unroll
+      for (int tp = 0; tp < C::VEC; ++tp)
+#pragma unroll
+        for (int rb = 0; rb < C::RB; ++rb)
+          acc[rb][h * C::VEC + tp] =
+              __builtin_amdgcn_mfma_f32_16x16x4f32(a[rb][ks], b[cur][h][tp], acc[rb][h * C::VEC + tp], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  });
 }
 
 template <int D>
@@ -226,11 +239,44 @@ __device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>:
   }
 }
 
+// The same helpers for all RB row blocks of wavefront w (row block index RB*w + rb)
+#define TTC_FOR_RB for (int rb = 0; rb < Cfg<D>::RB; ++rb)
+template <int D>
+__device__ __forceinline__ void zero_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT]) {
+#pragma unroll
+  TTC_FOR_RB zero_acc<D>(acc[rb]);
+}
+template <int D>
+__device__ __forceinline__ void eye_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT], int w, int i, int g) {
+#pragma unroll
+  TTC_FOR_RB eye_acc<D>(acc[rb], Cfg<D>::RB * w + rb, i, g);
+}
+template <int D>
+__device__ __forceinline__ void store_rows(float* Zb, const floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT], int w, int i, int g) {
+#pragma unroll
+  TTC_FOR_RB store_rows<D>(Zb, acc[rb], Cfg<D>::RB * w + rb, i, g);
+}
+template <int D>
+__device__ __forceinline__ void load_rows(const float* Zb, floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT], int w, int i, int g) {
+#pragma unroll
+  TTC_FOR_RB load_rows<D>(Zb, acc[rb], Cfg<D>::RB * w + rb, i, g);
+}
+template <int D>
+__device__ __forceinline__ void store_rows_T(float* Yb, const floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT], int w, int i, int g) {
+#pragma unroll
+  TTC_FOR_RB store_rows_T<D>(Yb, acc[rb], Cfg<D>::RB * w + rb, i, g);
+}
+template <int D>
+__device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>::RB][Cfg<D>::KS], int w, int i, int g) {
+#pragma unroll
+  TTC_FOR_RB load_aop_lds<D>(Mb, a[rb], Cfg<D>::RB * w + rb, i, g);
+}
+
 // ----------------------------------------------------------------------------------------------
 // Dense solve M X = RHS inside LDS: blocked Gauss-Jordan elimination with partial (row) pivoting on
 // the augmented d x 2d array W = [M | RHS] (row r at W + r*PITCH; M = columns [0,d), RHS = [d,2d)),
-// 16 columns per panel.  Rows are never moved: the pivot row of column c is remembered in s_piv[c]
-// (implicit pivoting) and the solution is gathered at the end, X[c][:] = RHS[s_piv[c]][:] / pivot_c.
+// 16 columns per panel.  Rows are never moved: the pivot row of column c is remembered in S.piv[c]
+// (implicit pivoting) and the solution is gathered at the end, X[c][:] = RHS[S.piv[c]][:] / pivot_c.
 //
 // Per panel P = [16p, 16p+16):
 //   (a) wavefront 0 holds the d x 16 panel in registers (a lane owns rows lane, lane+64) and runs
@@ -238,12 +284,14 @@ __device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>:
 //       of a packed key), pivot row broadcast with v_readlane, every other row -- pivoted earlier or
 //       not -- gets its multiplier and is updated.  It leaves in W[:, P] the multiplier matrix Lm
 //       (for the j-th pivot row of the panel: zero up to column j, the later "Jordan" multipliers
-//       after it) and in s_L11 the unit-lower multipliers among the 16 pivot rows.
+//       after it) and in S.L11 the unit-lower multipliers among the 16 pivot rows.
 //   (b) one thread per remaining column: gather the 16 pivot-row entries, forward-substitute with
-//       L11 -> U12; U12 goes back into the pivot rows and, negated, into the 16 x 2d buffer Ub.
-//   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows: wavefront w owns rows [16w,16w+16);
-//       the product is formed transposed (MFMA M index = column, N index = row) so that a lane's
-//       four accumulator values are contiguous in LDS.
+//       L11 -> U12; U12 goes back into the pivot rows and, negated, into the 16 x 2d buffer S.Ub.
+//   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows, in 16 x 16 tiles; the product is
+//       formed transposed (MFMA M index = column, N index = row) so that a lane's four accumulator
+//       values are contiguous in LDS.
+// Look-ahead: the first column tile of (c) is the next panel, so it is updated first (c0); then
+// wavefront 0 factors panel p+1 while the other wavefronts finish (c) of panel p.
 // Returns nonzero (uniformly) if a pivot was zero or not finite.  All threads must call it; W must be
 // visible on entry (caller synchronised); the result is visible to every thread on return.
 template <int D>
@@ -255,95 +303,136 @@ struct SolveScratch {
   int flag;
 };
 
+// (a): Gauss-Jordan on the d x 16 panel starting at column cb, by one wavefront
 template <int D>
+__device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb, int lane,
+                                            bool (&active)[(D + 63) / 64], int& bad) {
+  using C = Cfg<D>;
+  constexpr int NRL = (D + 63) / 64;
+  float a[NRL][16];
+  int myj[NRL];
+#pragma unroll
+  for (int rr = 0; rr < NRL; ++rr) {
+    const int r = lane + 64 * rr;
+    myj[rr] = -1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      floatx4 t = floatx4{0.f, 0.f, 0.f, 0.f};
+      if (r < D) t = *reinterpret_cast<const floatx4*>(W + r * C::PITCH + cb + 4 * q);
+      a[rr][4 * q + 0] = t[0]; a[rr][4 * q + 1] = t[1]; a[rr][4 * q + 2] = t[2]; a[rr][4 * q + 3] = t[3];
+    }
+  }
+  static_for<0, 16>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    // key = |value| with the low 7 mantissa bits replaced by (127 - row): one unsigned max = argmax
+    uint32_t key = 0;
+#pragma unroll
+    for (int rr = 0; rr < NRL; ++rr) {
+      const uint32_t k = (__float_as_uint(fabsf(a[rr][j])) & 0xFFFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
+      key = (active[rr] && k > key) ? k : key;
+    }
+    key = wave_max_u32(key);
+    int pr = 127 - (int)(key & 0x7Fu);
+    pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
+    const int pl = pr & 63;
+    const bool ps = (NRL > 1) && (pr >= 64);
+    float prow[16];
+    static_for<j, 16>([&](auto JJ) {
+      constexpr int jj = decltype(JJ)::value;
+      const float src = ps ? a[NRL - 1][jj] : a[0][jj];
+      prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, src), pl));
+    });
+    const float apv = fabsf(prow[j]);
+    if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
+    const float inv = __builtin_amdgcn_rcpf(prow[j]);
+#pragma unroll
+    for (int rr = 0; rr < NRL; ++rr) {
+      const bool mine = (lane == pl) && ((rr == NRL - 1 && NRL > 1) == ps);
+      const float l = mine ? 0.f : a[rr][j] * inv;
+      active[rr] = active[rr] && !mine;
+      myj[rr] = mine ? j : myj[rr];
+      a[rr][j] = mine ? a[rr][j] : l;
+      static_for<j + 1, 16>([&](auto JJ) {
+        constexpr int jj = decltype(JJ)::value;
+        a[rr][jj] -= l * prow[jj];  // l = 0 for the pivot row itself
+      });
+    }
+    if (lane == 0) { S.piv[cb + j] = pr; S.inv[cb + j] = inv; }
+  });
+#pragma unroll
+  for (int rr = 0; rr < NRL; ++rr) {
+    const int r = lane + 64 * rr;
+    if (r < D) {
+      const int j0 = myj[rr];
+      if (j0 >= 0) {
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+          if (jj < j0) S.L11[j0 * 16 + jj] = a[rr][jj];
+          if (jj <= j0) a[rr][jj] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        floatx4 t;
+        t[0] = a[rr][4 * q + 0]; t[1] = a[rr][4 * q + 1]; t[2] = a[rr][4 * q + 2]; t[3] = a[rr][4 * q + 3];
+        *reinterpret_cast<floatx4*>(W + r * C::PITCH + cb + 4 * q) = t;
+      }
+    }
+  }
+}
+
+// (c) for up to NG tiles at once: tile (rt, ct) = rows [16 rt, +16) x columns [cb+16+16 ct, +16)
+template <int D, int NG>
+__device__ __forceinline__ void solve_update_tiles(float* W, const SolveScratch<D>& S, int cb, int i, int g,
+                                                   const int (&rt)[NG], const int (&ct)[NG], int ntile) {
+  using C = Cfg<D>;
+  float bl[NG][4], av[NG][4];
+  floatx4 acc[NG];
+  float* cp[NG];
+#pragma unroll
+  for (int u = 0; u < NG; ++u) {
+    if (u < ntile) {
+      const float* lrow = W + (16 * rt[u] + i) * C::PITCH + cb + g;
+      const float* urow = S.Ub + g * C::PITCH + cb + 16 + 16 * ct[u] + i;
+      cp[u] = W + (16 * rt[u] + i) * C::PITCH + cb + 16 + 16 * ct[u] + 4 * g;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bl[u][kk] = lrow[4 * kk];
+        av[u][kk] = urow[4 * kk * C::PITCH];
+      }
+      acc[u] = *reinterpret_cast<const floatx4*>(cp[u]);
+    }
+  }
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int u = 0; u < NG; ++u)
+      if (u < ntile) acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][kk], bl[u][kk], acc[u], 0, 0, 0);
+#pragma unroll
+  for (int u = 0; u < NG; ++u)
+    if (u < ntile) *reinterpret_cast<floatx4*>(cp[u]) = acc[u];
+}
+
+// PARTS is a development switch (bit 0: panels, bit 1: U12, bit 2: trailing updates); 7 = everything.
+template <int D, int PARTS = 7>
 __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) {
   using C = Cfg<D>;
   constexpr int NP = D / 16;
   constexpr int NRL = (D + 63) / 64;
+  constexpr int NG = 4;
   const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   bool active[NRL];
 #pragma unroll
   for (int rr = 0; rr < NRL; ++rr) active[rr] = (lane + 64 * rr) < D;
   int bad = 0;
 
+  if ((PARTS & 1) && w == 0) solve_panel<D>(W, S, 0, lane, active, bad);
+  __syncthreads();
   for (int p = 0; p < NP; ++p) {
     const int cb = 16 * p;
-    // ---------------------------------------------------------------- (a) panel, wavefront 0
-    if (w == 0) {
-      float a[NRL][16];
-      int myj[NRL];
-#pragma unroll
-      for (int rr = 0; rr < NRL; ++rr) {
-        const int r = lane + 64 * rr;
-        myj[rr] = -1;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          floatx4 t = floatx4{0.f, 0.f, 0.f, 0.f};
-          if (r < D) t = *reinterpret_cast<const floatx4*>(W + r * C::PITCH + cb + 4 * q);
-          a[rr][4 * q + 0] = t[0]; a[rr][4 * q + 1] = t[1]; a[rr][4 * q + 2] = t[2]; a[rr][4 * q + 3] = t[3];
-        }
-      }
-      static_for<0, 16>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        uint32_t key = 0;
-#pragma unroll
-        for (int rr = 0; rr < NRL; ++rr) {
-          const uint32_t k = (__float_as_uint(fabsf(a[rr][j])) & 0xFFFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
-          key = (active[rr] && k > key) ? k : key;
-        }
-        key = wave_max_u32(key);
-        int pr = 127 - (int)(key & 0x7Fu);
-        pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
-        const int pl = pr & 63;
-        const bool ps = (NRL > 1) && (pr >= 64);
-        float prow[16];
-        static_for<j, 16>([&](auto JJ) {
-          constexpr int jj = decltype(JJ)::value;
-          const float src = ps ? a[NRL - 1][jj] : a[0][jj];
-          prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, src), pl));
-        });
-        const float apv = fabsf(prow[j]);
-        if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
-        const float inv = 1.0f / prow[j];
-#pragma unroll
-        for (int rr = 0; rr < NRL; ++rr) {
-          const bool mine = (lane == pl) && ((rr == NRL - 1 && NRL > 1) == ps);
-          const float l = mine ? 0.f : a[rr][j] * inv;
-          active[rr] = active[rr] && !mine;
-          myj[rr] = mine ? j : myj[rr];
-          a[rr][j] = mine ? a[rr][j] : l;
-          static_for<j + 1, 16>([&](auto JJ) {
-            constexpr int jj = decltype(JJ)::value;
-            a[rr][jj] -= l * prow[jj];      // l = 0 for the pivot row itself
-          });
-        }
-        if (lane == 0) { S.piv[cb + j] = pr; S.inv[cb + j] = inv; }
-      });
-#pragma unroll
-      for (int rr = 0; rr < NRL; ++rr) {
-        const int r = lane + 64 * rr;
-        if (r < D) {
-          const int j0 = myj[rr];
-          if (j0 >= 0) {
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-              if (jj < j0) S.L11[j0 * 16 + jj] = a[rr][jj];
-              if (jj <= j0) a[rr][jj] = 0.f;
-            }
-          }
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            floatx4 t;
-            t[0] = a[rr][4 * q + 0]; t[1] = a[rr][4 * q + 1]; t[2] = a[rr][4 * q + 2]; t[3] = a[rr][4 * q + 3];
-            *reinterpret_cast<floatx4*>(W + r * C::PITCH + cb + 4 * q) = t;
-          }
-        }
-      }
-    }
-    __syncthreads();
     // ---------------------------------------------------------------- (b) U12, one thread per column
     const int nrest = 2 * D - cb - 16;
-    if (tid < nrest) {
+    if ((PARTS & 2) && tid < nrest) {
       const int c = cb + 16 + tid;
       float u[16];
       int pv[16];
@@ -362,6 +451,7 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
             if constexpr (4 * q + e < j) u[j] -= l[e] * u[4 * q + e];
           });
         });
+        __builtin_amdgcn_sched_barrier(0);  // keep the L11 reads from all being hoisted (register pressure)
       });
       static_for<0, 16>([&](auto J) {
         constexpr int j = decltype(J)::value;
@@ -370,23 +460,38 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
       });
     }
     __syncthreads();
-    // ---------------------------------------------------------------- (c) trailing update on MFMA
+    // ---------------------------------------------------------------- (c0) the next panel's columns
     {
-      float bl[4];
-      const float* lrow = W + (16 * w + i) * C::PITCH + cb + g;
+      int rt1[C::RB], ct1[C::RB];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) bl[kk] = lrow[4 * kk];
+      for (int rb = 0; rb < C::RB; ++rb) { rt1[rb] = C::RB * w + rb; ct1[rb] = 0; }
+      if (PARTS & 4) solve_update_tiles<D, C::RB>(W, S, cb, i, g, rt1, ct1, C::RB);
+    }
+    __syncthreads();
+    // ---------------------------------------------------------------- (a) of p+1  ||  rest of (c)
+    const bool more = (p + 1 < NP);
+    const bool panel_here = more && w == 0;
+    if ((PARTS & 4) && (!panel_here || C::NW == 1)) {
+      const bool spare0 = more && C::NW > 1;           // wavefront 0 is busy with the next panel
       const int nct = nrest / 16;
-      float* crow = W + (16 * w + i) * C::PITCH + cb + 16 + 4 * g;
-      const float* urow = S.Ub + g * C::PITCH + cb + 16 + i;
-      for (int ct = 0; ct < nct; ++ct) {
-        floatx4 acc = *reinterpret_cast<const floatx4*>(crow + 16 * ct);
+      const int ntiles = (nct - 1) * C::NRT;           // column tiles 1..nct-1, all row tiles
+      const int nworkers = spare0 ? C::NW - 1 : C::NW;
+      const int wi = spare0 ? w - 1 : w;
+      for (int t0 = wi; t0 < ntiles; t0 += NG * nworkers) {
+        int rt[NG], ct[NG];
+        int cnt = 0;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-          acc = __builtin_amdgcn_mfma_f32_16x16x4f32(urow[4 * kk * C::PITCH + 16 * ct], bl[kk], acc, 0, 0, 0);
-        *reinterpret_cast<floatx4*>(crow + 16 * ct) = acc;
+        for (int u = 0; u < NG; ++u) {
+          const int t = t0 + u * nworkers;
+          rt[u] = t % C::NRT;
+          ct[u] = 1 + t / C::NRT;
+          cnt += (t < ntiles) ? 1 : 0;
+        }
+        if (cnt == NG) solve_update_tiles<D, NG>(W, S, cb, i, g, rt, ct, NG);
+        else solve_update_tiles<D, NG>(W, S, cb, i, g, rt, ct, cnt);
       }
     }
+    if ((PARTS & 1) && panel_here) solve_panel<D>(W, S, cb + 16, lane, active, bad);
     __syncthreads();
   }
   if (tid == 0) S.flag = bad;
@@ -408,18 +513,22 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
 
 // Row normalisation of [Y1 Y2] (App. C "Numerical Stability") in Z-land: column c of Z is row c of
 // the pair.  The scale is the power of two just below max(||Y1_c||_1, ||Y2_c||_1), so the scaling
-// is exact and Y1^{-1} Y2 is unchanged bit for bit (barring under/overflow).  Four threads per column.
+// is exact and Y1^{-1} Y2 is unchanged bit for bit (barring under/overflow).
 template <int D>
 __device__ void normalise_rows_zland(float* W, int tid) {
   using C = Cfg<D>;
-  const int c = tid >> 2, part = tid & 3;  // NTHR = 4 D threads -> D columns x 4 row quarters
+  constexpr int TPC = C::NTHR / D;           // threads per column (a power of two, 2 or 4)
+  const int c = tid / TPC, part = tid % TPC;
   float s1 = 0.f, s2 = 0.f;
-  for (int r = part; r < D; r += 4) {
+  for (int r = part; r < D; r += TPC) {
     s1 += fabsf(W[r * C::PITCH + c]);
     s2 += fabsf(W[r * C::PITCH + D + c]);
   }
-  s1 += __shfl_xor(s1, 1, 64); s1 += __shfl_xor(s1, 2, 64);
-  s2 += __shfl_xor(s2, 1, 64); s2 += __shfl_xor(s2, 2, 64);
+#pragma unroll
+  for (int m = 1; m < TPC; m <<= 1) {
+    s1 += __shfl_xor(s1, m, 64);
+    s2 += __shfl_xor(s2, m, 64);
+  }
   const float mx = fmaxf(s1, s2);
   float scale = 1.0f;
   if (mx > 0.f && mx < __builtin_inff()) {
@@ -427,7 +536,7 @@ __device__ void normalise_rows_zland(float* W, int tid) {
     frexpf(mx, &e);              // mx = f * 2^e, f in [0.5, 1)
     scale = ldexpf(1.0f, -e);    // exact power of two
   }
-  for (int r = part; r < D; r += 4) {
+  for (int r = part; r < D; r += TPC) {
     W[r * C::PITCH + c] *= scale;
     W[r * C::PITCH + D + c] *= scale;
   }

@@ -14,7 +14,7 @@ struct SolveArgs {
   long long sA, sB, sQ, sR, sQT, sx0;
   float *P0, *K0, *u0, *value;
   int* info;
-  float* ws;  // gridDim.x slots of d*m floats: R^{-1} B^T of the problem in flight
+  float* ws;  // gridDim.x slots of 5 d*d floats: constants of the problem in flight, register layout
 };
 
 // A-operand registers of rows [16w,16w+16) of a row-major global matrix: a[4q+t] = M[16w+i][16q+4g+t]
@@ -25,6 +25,44 @@ __device__ __forceinline__ void load_aop_global(const TIn* M, float (&a)[Cfg<D>:
     floatx4 t = ld4<TIn>(M, (long)(16 * w + i) * D + 16 * q + 4 * g);
     a[4 * q + 0] = t[0]; a[4 * q + 1] = t[1]; a[4 * q + 2] = t[2]; a[4 * q + 3] = t[3];
   }
+}
+
+template <int D, typename TIn>
+__device__ __forceinline__ void load_aop_global(const TIn* M, float (&a)[Cfg<D>::RB][Cfg<D>::KS], int w, int i, int g) {
+#pragma unroll
+  TTC_FOR_RB load_aop_global<D, TIn>(M, a[rb], Cfg<D>::RB * w + rb, i, g);
+}
+
+// A-operand registers <-> workspace, in lane order (thread t's k-th float4 at [k][t]): fully coalesced.
+// The constants are parked there while a dense solve runs, so that the solve has the register file
+// to itself; `off` is an opaque zero that keeps the compiler from hoisting the reloads out of loops.
+template <int D>
+__device__ __forceinline__ void store_aop_ws(float* wsc, const float (&a)[Cfg<D>::RB][Cfg<D>::KS], int tid) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int q = 0; q < C::KS / 4; ++q) {
+      floatx4 v;
+      v[0] = a[rb][4 * q + 0]; v[1] = a[rb][4 * q + 1]; v[2] = a[rb][4 * q + 2]; v[3] = a[rb][4 * q + 3];
+      *reinterpret_cast<floatx4*>(wsc + ((long)(rb * (C::KS / 4) + q) * C::NTHR + tid) * 4) = v;
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_aop_ws(const float* wsc, float (&a)[Cfg<D>::RB][Cfg<D>::KS], int tid, int off) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int q = 0; q < C::KS / 4; ++q) {
+      const floatx4 v = *reinterpret_cast<const floatx4*>(wsc + off + ((long)(rb * (C::KS / 4) + q) * C::NTHR + tid) * 4);
+      a[rb][4 * q + 0] = v[0]; a[rb][4 * q + 1] = v[1]; a[rb][4 * q + 2] = v[2]; a[rb][4 * q + 3] = v[3];
+    }
+}
+__device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return z;
 }
 
 // copy a row-major global d x d matrix into one half of the LDS pair (optionally transposed)
@@ -67,16 +105,33 @@ __device__ __forceinline__ void set_half_identity(float* Wh, int tid) {
   }
 }
 
+// store `info`-aware outputs of one accumulator (rows of P0 or K0) and return this lane's share of
+// (M x0)[row] for its four rows: out[v] = sum over the lane's columns of acc[c][v] * x0[col]
+template <int D>
+__device__ __forceinline__ void write_rows_global(float* dst, const floatx4 (&acc)[Cfg<D>::NT], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+#pragma unroll
+    for (int h = 0; h < C::NH; ++h) {
+      float* q = dst + (long)(16 * w + 4 * g + v) * D + 16 * C::VEC * h + C::VEC * i;
+#pragma unroll
+      for (int tp = 0; tp < C::VEC; ++tp) q[tp] = acc[h * C::VEC + tp][v];
+    }
+}
+
 // Solve kernel.  Persistent workgroups: workgroup b handles problems b, b + gridDim.x, ...
 //
-// Per problem:
-//   setup   X = R^{-1} B^T (dense solve), G = B X (Thm 3.3), A^{-1} (dense solve); the row blocks of
-//           G, A^{-1}, A^T and Q go to registers; Z2 = Q_T, Z1 = I.
-//   T-1 reverse symplectic steps with Q_{t-1} = Q (Thm 3.3 / Alg. 4 body); every `rebase_every`
-//           steps and after the last one the pair is re-based, [Y1 Y2] <- [I, Y1^{-1} Y2].
-//   final   the last factor Sigma_1 (Q_0 = 0) is applied in solved form: with P_1 explicit,
-//           M = (I + P_1 G)^{-1} P_1 A (dense solve), P_0 = A^T M (+ Q), K_0 = -(R^{-1} B^T) M, which is
-//           Y1^{-1} Y2 of Alg. 4 and Eq. "decode" at t = 1 without multiplying by A^{-T} and back.
+// Per problem the work is a sequence of phases, each "build [M | RHS] in LDS, dense solve, consume":
+//   phase R  X = R^{-1} B^T, then G = B X (Thm 3.3's G); rows of G go to registers.
+//   phase A  A^{-1}; rows of A^{-1}, A^T and Q go to registers; Z2 = Q_T, Z1 = I.
+//   phase S  up to `rebase_every` reverse symplectic steps with Q_{t-1} = Q (Alg. 4 body), the last
+//            one leaving the pair untransposed; the solve re-bases it, [Y1 Y2] <- [I, Y1^{-1} Y2].
+//            Repeated until T-1 steps are done (always re-based after the last one: P_1 explicit).
+//   phase F  the last factor Sigma_1 (Q_0 = 0) in solved form: M = (I + P_1 G)^{-1} P_1 A,
+//            P_0 = A^T M (+ Q), K_0 = -(R^{-1} B^T) M, which is Y1^{-1} Y2 of Alg. 4 and Eq. "decode"
+//            at t = 1 without multiplying by A^{-T} and back.
+// Phases S and F share one instance of the dense solve (the final phase is the loop's last pass).
 template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) {
   using C = Cfg<D>;
@@ -87,7 +142,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   float* const WL = W;      // left half  (Z1 / Y1 / M of a dense solve)
   float* const WR = W + D;  // right half (Z2 / Y2 / RHS)
-  float* const wsX = p.ws + (long)blockIdx.x * D * D;
+  // per-workgroup workspace: the row blocks of G, A^{-1}, A^T, Q and X = R^{-1} B^T in register layout
+  float* const wsC = p.ws + (long)blockIdx.x * 5 * D * D;
   const bool pure = (p.flags & TTC_FLAG_PURE_SYMPLECTIC) != 0;
   const int kreb = pure ? 0x7fffffff : p.rebase_every;
 
@@ -99,10 +155,11 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     const TIn* QTp = p.QT ? reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT : Qp;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
     int info = 0, nsolve = 0;
-    float cG[C::KS], cAi[C::KS], cAT[C::KS], cQ[C::KS];
-    floatx4 acc1[C::NT], acc2[C::NT], acc3[C::NT];
+    floatx4 acc[C::RB][C::NT];
+    int s = 1;          // next reverse step (1 .. T-1)
+    bool fresh = true;  // Z1 = I, not materialised
 
-    // ---- setup 1: X = R^{-1} B^T, G = B X
+    // ---------------------------------------------------------------- phase R: X = R^{-1} B^T, G = B X
     load_half<D, TIn, false>(WL, Rp, tid);
     load_half<D, TIn, true>(WR, Bp, tid);
     __syncthreads();
@@ -110,148 +167,185 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     __syncthreads();
     ++nsolve;
     if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-    for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {  // keep X for the final gain
-      const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
-      *reinterpret_cast<floatx4*>(wsX + r * D + c4) = *reinterpret_cast<const floatx4*>(WR + r * C::PITCH + c4);
+    {
+      float c[C::RB][C::KS];
+      load_aop_lds<D>(WR, c, w, i, g);             // rows of X, kept for the final gain
+      store_aop_ws<D>(wsC + 4 * D * D, c, tid);
+      load_aop_global<D, TIn>(Bp, c, w, i, g);     // rows of B
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, c, WR, i, g);               // rows of G = B X
+      store_rows<D>(WL, acc, w, i, g);
+      __syncthreads();
+      symmetrise_half<D>(WL, tid);                 // G is symmetric up to rounding; make it exactly so
+      __syncthreads();
+      load_aop_lds<D>(WL, c, w, i, g);
+      store_aop_ws<D>(wsC + 0 * D * D, c, tid);
+      __syncthreads();
     }
-    load_aop_global<D, TIn>(Bp, cG, w, i, g);  // rows of B, temporarily in G's registers
-    zero_acc<D>(acc1);
-    gemm_acc<D>(acc1, cG, WR, i, g);           // rows of G = B X
-    store_rows<D>(WL, acc1, w, i, g);
-    __syncthreads();
-    symmetrise_half<D>(WL, tid);               // G is symmetric up to rounding; make it exactly so
-    __syncthreads();
-    load_aop_lds<D>(WL, cG, w, i, g);
-    __syncthreads();
 
-    // ---- setup 2: A^{-1}
+    // ---------------------------------------------------------------- phase A: A^{-1}, A^T, Q, Z2 = Q_T
     load_half<D, TIn, false>(WL, Ap, tid);
     set_half_identity<D>(WR, tid);
     __syncthreads();
     ++nsolve;
     if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-    load_aop_lds<D>(WR, cAi, w, i, g);
-    // rows of A^T (columns of A) and of the symmetric part of Q straight from global memory
+    {
+      float c[C::RB][C::KS];
+      load_aop_lds<D>(WR, c, w, i, g);
+      store_aop_ws<D>(wsC + 1 * D * D, c, tid);
+      // rows of A^T (columns of A), then rows of the symmetric part of Q, straight from global memory
 #pragma unroll
-    for (int q = 0; q < D / 16; ++q) {
-      const floatx4 qr = ld4<TIn>(Qp, (long)(16 * w + i) * D + 16 * q + 4 * g);
+      for (int rb = 0; rb < C::RB; ++rb)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const long k = 16 * q + 4 * g + t;
-        cAT[4 * q + t] = ld1<TIn>(Ap, k * D + 16 * w + i);
-        cQ[4 * q + t] = 0.5f * (qr[t] + ld1<TIn>(Qp, k * D + 16 * w + i));
+        for (int k = 0; k < C::KS; ++k)
+          c[rb][k] = ld1<TIn>(Ap, (long)(16 * (k / 4) + 4 * g + (k % 4)) * D + 16 * (C::RB * w + rb) + i);
+      store_aop_ws<D>(wsC + 2 * D * D, c, tid);
+#pragma unroll
+      for (int rb = 0; rb < C::RB; ++rb) {
+        const int row = 16 * (C::RB * w + rb) + i;
+#pragma unroll
+        for (int q = 0; q < D / 16; ++q) {
+          const floatx4 qr = ld4<TIn>(Qp, (long)row * D + 16 * q + 4 * g);
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt)
+            c[rb][4 * q + tt] = 0.5f * (qr[tt] + ld1<TIn>(Qp, (long)(16 * q + 4 * g + tt) * D + row));
+        }
       }
+      store_aop_ws<D>(wsC + 3 * D * D, c, tid);
     }
     __syncthreads();
-
-    // ---- initial pair [Y1 Y2] = [I Q_T]
-    load_half<D, TIn, false>(WR, QTp, tid);
+    load_half<D, TIn, false>(WR, QTp, tid);    // initial pair [Y1 Y2] = [I Q_T]
     __syncthreads();
     symmetrise_half<D>(WR, tid);
     __syncthreads();
-    bool fresh = true;  // Z1 = I, not materialised
-    int since = 0;
 
-    // ---- T-1 reverse symplectic steps with Q_{t-1} = Q
-    for (int s = 1; s < p.T; ++s) {
-      if (fresh) eye_acc<D>(acc1, w, i, g); else load_rows<D>(WL, acc1, w, i, g);
-      gemm_acc<D>(acc1, cG, WR, i, g);   // Z1 + G Z2        (Y1 + Y2 G)
-      store_rows<D>(WL, acc1, w, i, g);
-      __syncthreads();
-      zero_acc<D>(acc2);
-      gemm_acc<D>(acc2, cAi, WL, i, g);  // A^{-1} (.)       (... A^{-T})  = new Z1
-      zero_acc<D>(acc3);
-      gemm_acc<D>(acc3, cAT, WR, i, g);  // A^T Z2           (Y2 A)
-      __syncthreads();
-      store_rows<D>(WL, acc2, w, i, g);
-      __syncthreads();
-      gemm_acc<D>(acc3, cQ, WL, i, g);   // + Q Z1           (+ Y1 Q)      = new Z2
-      __syncthreads();
-      ++since;
-      const bool rebase = (since >= kreb) || (s == p.T - 1);
-      if (!rebase) {
-        store_rows<D>(WR, acc3, w, i, g);
-        __syncthreads();
-        fresh = false;
-        if (pure) {
-          normalise_rows_zland<D>(W, tid);
+    // ---------------------------------------------------------------- phases S ... S, F
+    for (bool fin = (p.T == 1);;) {
+      {
+        // the constant row blocks live in registers only between two dense solves
+        float cG[C::RB][C::KS], cAT[C::RB][C::KS];
+        const int off = opaque_zero();
+        load_aop_ws<D>(wsC + 0 * D * D, cG, tid, off);
+        load_aop_ws<D>(wsC + 2 * D * D, cAT, tid, off);
+        if (!fin) {
+          float cAi[C::RB][C::KS], cQ[C::RB][C::KS];
+          load_aop_ws<D>(wsC + 1 * D * D, cAi, tid, off);
+          load_aop_ws<D>(wsC + 3 * D * D, cQ, tid, off);
+          for (int since = 1;; ++since, ++s) {
+            const bool last = (since >= kreb) || (s == p.T - 1);
+            if (fresh) eye_acc<D>(acc, w, i, g); else load_rows<D>(WL, acc, w, i, g);
+            gemm_acc<D>(acc, cG, WR, i, g);    // Z1 + G Z2       (Y1 + Y2 G)
+            store_rows<D>(WL, acc, w, i, g);
+            __syncthreads();
+            zero_acc<D>(acc);
+            gemm_acc<D>(acc, cAi, WL, i, g);   // A^{-1} (.)      (... A^{-T})  = new Z1
+            __syncthreads();
+            store_rows<D>(WL, acc, w, i, g);
+            __syncthreads();
+            zero_acc<D>(acc);
+            gemm_acc<D>(acc, cAT, WR, i, g);   // A^T Z2          (Y2 A)
+            gemm_acc<D>(acc, cQ, WL, i, g);    // + Q Z1          (+ Y1 Q)      = new Z2
+            __syncthreads();
+            fresh = false;
+            if (!last) {
+              store_rows<D>(WR, acc, w, i, g);
+              __syncthreads();
+              if (pure) {
+                normalise_rows_zland<D>(W, tid);
+                __syncthreads();
+              }
+            } else {
+              // leave Z-land: [Y1 | Y2] untransposed for the solve Y1 P = Y2
+              store_rows_T<D>(WR, acc, w, i, g);
+              load_rows<D>(WL, acc, w, i, g);
+              __syncthreads();
+              store_rows_T<D>(WL, acc, w, i, g);
+              __syncthreads();
+              ++s;
+              break;
+            }
+          }
+        } else {
+          eye_acc<D>(acc, w, i, g);
+          gemm_acc<D>(acc, cG, WR, i, g);      // rows of I + G P_1 = (I + P_1 G)^T
+          store_rows_T<D>(WL, acc, w, i, g);
+          zero_acc<D>(acc);
+          gemm_acc<D>(acc, cAT, WR, i, g);     // rows of A^T P_1   = (P_1 A)^T
+          __syncthreads();
+          store_rows_T<D>(WR, acc, w, i, g);
           __syncthreads();
         }
-      } else {
-        // leave Z-land: write the pair untransposed, [Y1 | Y2], and solve Y1 P = Y2
-        store_rows_T<D>(WL, acc2, w, i, g);
-        store_rows_T<D>(WR, acc3, w, i, g);
-        __syncthreads();
-        ++nsolve;
-        if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-        symmetrise_half<D>(WR, tid);     // P is symmetric; also makes it its own Z-land image
-        __syncthreads();
-        fresh = true;
-        since = 0;
       }
+      ++nsolve;
+      if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+      if (fin) break;
+      symmetrise_half<D>(WR, tid);           // P is symmetric; also makes it its own Z-land image
+      __syncthreads();
+      fresh = true;
+      fin = (s >= p.T);
     }
 
-    // ---- final factor in solved form: M = (I + P_1 G)^{-1} P_1 A
-    eye_acc<D>(acc1, w, i, g);
-    gemm_acc<D>(acc1, cG, WR, i, g);     // rows of I + G P_1 = (I + P_1 G)^T
-    zero_acc<D>(acc3);
-    gemm_acc<D>(acc3, cAT, WR, i, g);    // rows of A^T P_1   = (P_1 A)^T
-    __syncthreads();
-    store_rows_T<D>(WL, acc1, w, i, g);
-    store_rows_T<D>(WR, acc3, w, i, g);
-    __syncthreads();
-    ++nsolve;
-    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-
-    // ---- outputs
-    zero_acc<D>(acc1);
-    gemm_acc<D>(acc1, cAT, WR, i, g);    // P_0 = A^T M
-    load_aop_global<D, float>(wsX, cG, w, i, g);
-    zero_acc<D>(acc2);
-    gemm_acc<D>(acc2, cG, WR, i, g);     // -K_0 = (R^{-1} B^T) M
+    // ---- outputs: WR holds M = (I + P_1 G)^{-1} P_1 A
     const float nanv = __builtin_nanf("");
-    float x0c[C::NT], x0r[4];
+    float x0c[C::NT];
 #pragma unroll
     for (int c = 0; c < C::NT; ++c) x0c[c] = ld1<TIn>(x0p, tile_col<D>(c, i));
-#pragma unroll
-    for (int v = 0; v < 4; ++v) x0r[v] = ld1<TIn>(x0p, 16 * w + 4 * g + v);
     float vpart = 0.f;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const long row = 16 * w + 4 * g + v;
-      float pu = 0.f, pw = 0.f;
-#pragma unroll
-      for (int c = 0; c < C::NT; ++c) {
-        float pe = acc1[c][v], ke = -acc2[c][v];
-        if (p.flags & TTC_FLAG_STAGE_COST_AT_X0) {
-          const long col = tile_col<D>(c, i);
-          pe += 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
-        }
-        if (info) { pe = nanv; ke = nanv; }
-        acc1[c][v] = pe;
-        acc2[c][v] = ke;
-        pu += ke * x0c[c];
-        pw += pe * x0c[c];
-      }
-      pu = sum16(pu);
-      pw = sum16(pw);
-      if (i == 0) p.u0[prob * D + row] = pu;
-      vpart += x0r[v] * pw;
+    {
+      float c[C::RB][C::KS];
+      load_aop_ws<D>(wsC + 2 * D * D, c, tid, opaque_zero());
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, c, WR, i, g);               // P_0 = A^T M
     }
-    vpart *= (i == 0) ? 1.f : 0.f;
+#pragma unroll
+    for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const long row = 16 * (C::RB * w + rb) + 4 * g + v;
+        float pw = 0.f;
+#pragma unroll
+        for (int c = 0; c < C::NT; ++c) {
+          float pe = acc[rb][c][v];
+          if (p.flags & TTC_FLAG_STAGE_COST_AT_X0) {
+            const long col = tile_col<D>(c, i);
+            pe += 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
+          }
+          if (info) pe = nanv;
+          acc[rb][c][v] = pe;
+          pw += pe * x0c[c];
+        }
+        vpart += ld1<TIn>(x0p, row) * pw;
+      }
     vpart = sum64(vpart);
     if (lane == 0) s_red[w] = vpart;
+    if (p.P0) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
+      for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.P0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
+    }
+    {
+      float c[C::RB][C::KS];
+      load_aop_ws<D>(wsC + 4 * D * D, c, tid, opaque_zero());
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, c, WR, i, g);               // -K_0 = (R^{-1} B^T) M
+    }
 #pragma unroll
-      for (int h = 0; h < C::NH; ++h) {
-        const long off = prob * (long)D * D + (long)(16 * w + 4 * g + v) * D + 16 * C::VEC * h + C::VEC * i;
+    for (int rb = 0; rb < C::RB; ++rb)
 #pragma unroll
-        for (int tp = 0; tp < C::VEC; ++tp) {
-          if (p.P0) p.P0[off + tp] = acc1[h * C::VEC + tp][v];
-          if (p.K0) p.K0[off + tp] = acc2[h * C::VEC + tp][v];
+      for (int v = 0; v < 4; ++v) {
+        float pu = 0.f;
+#pragma unroll
+        for (int c = 0; c < C::NT; ++c) {
+          const float ke = info ? nanv : -acc[rb][c][v];
+          acc[rb][c][v] = ke;
+          pu += ke * x0c[c];
         }
+        pu = sum16(pu);
+        if (i == 0) p.u0[prob * D + 16 * (C::RB * w + rb) + 4 * g + v] = pu;
       }
+    if (p.K0) {
+#pragma unroll
+      for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.K0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
+    }
     __syncthreads();
     if (tid == 0) {
       float val = 0.f;
@@ -271,22 +365,23 @@ struct RolloutArgs {
   long long sA, sB, sQ, sR, sQT, sx0;
   float *U, *X, *cost;
   int* info;
-  float* ws;  // gridDim.x slots of (T+1) d*d floats: R^{-1} B^T, then K_0 .. K_{T-1}
+  float* ws;  // gridDim.x slots of (T+3) d*d floats: G, R^{-1} B^T, A^T (register layout), K_0 .. K_{T-1}
 };
 
-// y[r] = sum_c M[r][c] x[c] for the row r = tid/4 of a row-major global d x d matrix; the four
-// threads of a row each take a quarter of the columns.  Every thread of the quad gets the sum.
+// y[r] = sum_c M[r][c] x[c] for the row r = tid / TPR of a row-major global d x d matrix; the TPR
+// threads of a row (adjacent lanes) each take a share of the columns; all of them get the sum.
 template <int D, typename TM>
 __device__ __forceinline__ float matvec_row(const TM* M, const float* xs, int tid) {
-  const int r = tid >> 2, part = tid & 3;
+  constexpr int TPR = Cfg<D>::NTHR / D;  // 2 or 4
+  const int r = tid / TPR, part = tid % TPR;
   float s = 0.f;
 #pragma unroll
-  for (int c4 = part * (D / 4); c4 < (part + 1) * (D / 4); c4 += 4) {
+  for (int c4 = part * (D / TPR); c4 < (part + 1) * (D / TPR); c4 += 4) {
     const floatx4 mv = ld4<TM>(M, (long)r * D + c4);
     s += mv[0] * xs[c4] + mv[1] * xs[c4 + 1] + mv[2] * xs[c4 + 2] + mv[3] * xs[c4 + 3];
   }
-  s += __shfl_xor(s, 1, 64);
-  s += __shfl_xor(s, 2, 64);
+#pragma unroll
+  for (int m = 1; m < TPR; m <<= 1) s += __shfl_xor(s, m, 64);
   return s;
 }
 
@@ -305,8 +400,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   float* const WL = W;
   float* const WR = W + D;
-  float* const wsX = p.ws + (long)blockIdx.x * (p.T + 1) * D * D;
-  float* const wsK = wsX + D * D;
+  float* const wsC = p.ws + (long)blockIdx.x * (p.T + 3) * D * D;  // G, X, A^T in register layout
+  float* const wsK = wsC + 3 * D * D;                              // K_0 .. K_{T-1}, row-major
 
   for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
     const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
@@ -316,10 +411,9 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
     const TIn* QTp = p.QT ? reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT : Qp;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
     int info = 0, nsolve = 0;
-    float cG[C::KS], cX[C::KS], cAT[C::KS];
-    floatx4 qd[C::NT], acc1[C::NT], acc2[C::NT], acc3[C::NT];
+    floatx4 acc[C::RB][C::NT];
 
-    // ---- setup: X = R^{-1} B^T, G = B X
+    // ---- setup: X = R^{-1} B^T, G = B X; row blocks of G, X, A^T parked in the workspace
     load_half<D, TIn, false>(WL, Rp, tid);
     load_half<D, TIn, true>(WR, Bp, tid);
     __syncthreads();
@@ -327,26 +421,26 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
     __syncthreads();
     ++nsolve;
     if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-    load_aop_lds<D>(WR, cX, w, i, g);
-    load_aop_global<D, TIn>(Bp, cG, w, i, g);
-    zero_acc<D>(acc1);
-    gemm_acc<D>(acc1, cG, WR, i, g);
-    store_rows<D>(WL, acc1, w, i, g);
-    __syncthreads();
-    symmetrise_half<D>(WL, tid);
-    __syncthreads();
-    load_aop_lds<D>(WL, cG, w, i, g);
+    {
+      float c[C::RB][C::KS];
+      load_aop_lds<D>(WR, c, w, i, g);
+      store_aop_ws<D>(wsC + 1 * D * D, c, tid);
+      load_aop_global<D, TIn>(Bp, c, w, i, g);
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, c, WR, i, g);
+      store_rows<D>(WL, acc, w, i, g);
+      __syncthreads();
+      symmetrise_half<D>(WL, tid);
+      __syncthreads();
+      load_aop_lds<D>(WL, c, w, i, g);
+      store_aop_ws<D>(wsC + 0 * D * D, c, tid);
 #pragma unroll
-    for (int q = 0; q < D / 16; ++q)
+      for (int rb = 0; rb < C::RB; ++rb)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) cAT[4 * q + t] = ld1<TIn>(Ap, (long)(16 * q + 4 * g + t) * D + 16 * w + i);
-#pragma unroll
-    for (int c = 0; c < C::NT; ++c)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const long row = 16 * w + 4 * g + v, col = tile_col<D>(c, i);
-        qd[c][v] = 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
-      }
+        for (int k = 0; k < C::KS; ++k)
+          c[rb][k] = ld1<TIn>(Ap, (long)(16 * (k / 4) + 4 * g + (k % 4)) * D + 16 * (C::RB * w + rb) + i);
+      store_aop_ws<D>(wsC + 2 * D * D, c, tid);
+    }
     __syncthreads();
     load_half<D, TIn, false>(WR, QTp, tid);
     __syncthreads();
@@ -355,41 +449,57 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
 
     // ---- backward sweep
     for (int t = p.T - 1; t >= 0; --t) {
-      eye_acc<D>(acc1, w, i, g);
-      gemm_acc<D>(acc1, cG, WR, i, g);   // (I + P G)^T
-      zero_acc<D>(acc3);
-      gemm_acc<D>(acc3, cAT, WR, i, g);  // (P A)^T
-      __syncthreads();
-      store_rows_T<D>(WL, acc1, w, i, g);
-      store_rows_T<D>(WR, acc3, w, i, g);
-      __syncthreads();
+      const int off = opaque_zero();
+      {
+        float cG[C::RB][C::KS], cAT[C::RB][C::KS];
+        load_aop_ws<D>(wsC + 0 * D * D, cG, tid, off);
+        load_aop_ws<D>(wsC + 2 * D * D, cAT, tid, off);
+        eye_acc<D>(acc, w, i, g);
+        gemm_acc<D>(acc, cG, WR, i, g);   // (I + P G)^T
+        store_rows_T<D>(WL, acc, w, i, g);
+        zero_acc<D>(acc);
+        gemm_acc<D>(acc, cAT, WR, i, g);  // (P A)^T
+        __syncthreads();
+        store_rows_T<D>(WR, acc, w, i, g);
+        __syncthreads();
+      }
       ++nsolve;
       if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-      zero_acc<D>(acc2);
-      gemm_acc<D>(acc2, cX, WR, i, g);   // -K_t
-      float* Kt = wsK + (long)t * D * D;
+      {
+        float c[C::RB][C::KS];
+        load_aop_ws<D>(wsC + 1 * D * D, c, tid, off);
+        zero_acc<D>(acc);
+        gemm_acc<D>(acc, c, WR, i, g);    // -K_t
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
+        for (int rb = 0; rb < C::RB; ++rb) {
 #pragma unroll
-        for (int h = 0; h < C::NH; ++h)
+          for (int cc = 0; cc < C::NT; ++cc) acc[rb][cc] = -acc[rb][cc];
+          write_rows_global<D>(wsK + (long)t * D * D, acc[rb], C::RB * w + rb, i, g);
+        }
+        if (t >= 1) {
+          load_aop_ws<D>(wsC + 2 * D * D, c, tid, off);
 #pragma unroll
-          for (int tp = 0; tp < C::VEC; ++tp)
-            Kt[(16 * w + 4 * g + v) * D + 16 * C::VEC * h + C::VEC * i + tp] = -acc2[h * C::VEC + tp][v];
-      if (t >= 1) {
+          for (int rb = 0; rb < C::RB; ++rb)
 #pragma unroll
-        for (int c = 0; c < C::NT; ++c) acc1[c] = qd[c];
-        gemm_acc<D>(acc1, cAT, WR, i, g);  // P_t = Q + A^T M_t
-        __syncthreads();
-        store_rows<D>(WR, acc1, w, i, g);
-        __syncthreads();
-        symmetrise_half<D>(WR, tid);
-        __syncthreads();
+            for (int cc = 0; cc < C::NT; ++cc)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                const long row = 16 * (C::RB * w + rb) + 4 * g + v, col = tile_col<D>(cc, i);
+                acc[rb][cc][v] = 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
+              }
+          gemm_acc<D>(acc, c, WR, i, g);  // P_t = Q + A^T M_t
+          __syncthreads();
+          store_rows<D>(WR, acc, w, i, g);
+          __syncthreads();
+          symmetrise_half<D>(WR, tid);
+          __syncthreads();
+        }
       }
     }
     __syncthreads();  // gains visible to the whole workgroup
 
     // ---- forward sweep
-    const int r = tid >> 2, part = tid & 3;
+    const int r = tid / (C::NTHR / D), part = tid % (C::NTHR / D);
     if (tid < D) s_x[tid] = ld1<TIn>(x0p, tid);
     __syncthreads();
     float cpart = 0.f;
@@ -504,7 +614,7 @@ size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t* problem, int for_rollout
   if (!problem || problem->T < 1 || !ttc::shape_supported(problem)) return 0;
   const size_t slots = (size_t)ttc::grid_blocks(problem->d);
   const size_t per = (size_t)problem->d * problem->m * sizeof(float);
-  return slots * per * (for_rollout ? (size_t)problem->T + 1 : 1);
+  return slots * per * (for_rollout ? (size_t)problem->T + 3 : 5);
 }
 
 ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solution_t* solution,

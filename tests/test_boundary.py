@@ -76,8 +76,8 @@ def test_argument_validation_without_device(lib):
 def test_workspace_bytes(lib):
     p = _problem(d=128, m=128, T=16)
     w = binding.ttc_lqr_workspace_bytes(p)
-    assert w > 0 and w % (128 * 128 * 4) == 0
-    assert binding.ttc_lqr_workspace_bytes(p, for_rollout=True) == w * 17
+    assert w > 0 and w % (5 * 128 * 128 * 4) == 0
+    assert binding.ttc_lqr_workspace_bytes(p, for_rollout=True) * 5 == w * 19
     assert binding.ttc_lqr_workspace_bytes(_problem(d=48, m=48)) == 0
     p.n = 10 ** 9
     assert binding.ttc_lqr_workspace_bytes(p) == w                               # independent of n
