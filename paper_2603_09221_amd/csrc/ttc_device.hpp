@@ -285,19 +285,22 @@ __device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>:
 //       not -- gets its multiplier and is updated.  It leaves in W[:, P] the multiplier matrix Lm
 //       (for the j-th pivot row of the panel: zero up to column j, the later "Jordan" multipliers
 //       after it) and in S.L11 the unit-lower multipliers among the 16 pivot rows.
-//   (b) one thread per remaining column: gather the 16 pivot-row entries, forward-substitute with
-//       L11 -> U12; U12 goes back into the pivot rows and, negated, into the 16 x 2d buffer S.Ub.
+//   (b) one lane per remaining column: gather the 16 pivot-row entries, forward-substitute with
+//       L11 -> U12; U12 goes back into the pivot rows and, negated and transposed, into S.UbT.
 //   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows, in 16 x 16 tiles; the product is
 //       formed transposed (MFMA M index = column, N index = row) so that a lane's four accumulator
-//       values are contiguous in LDS.
-// Look-ahead: the first column tile of (c) is the next panel, so it is updated first (c0); then
-// wavefront 0 factors panel p+1 while the other wavefronts finish (c) of panel p.
+//       values, and its four operand values of either side, are 16 contiguous bytes of LDS.
+// Schedule: (b) and (c) are done column tile by column tile, so a wavefront needs no one else's
+// results.  Wavefront 0 takes the first column tile of the rest (= the next panel) and then factors
+// panel p+1, while the other wavefronts share the remaining column tiles of panel p: one workgroup
+// barrier per panel.
 // Returns nonzero (uniformly) if a pivot was zero or not finite.  All threads must call it; W must be
 // visible on entry (caller synchronised); the result is visible to every thread on return.
 template <int D>
 struct SolveScratch {
-  float Ub[16 * Cfg<D>::PITCH];
-  float L11[16 * 16];
+  static constexpr int UP = 20;     // floats per column of UbT (16 + 4: bank skew, keeps 16-byte alignment)
+  float UbT[2 * D * UP];            // -U12 transposed: column c of the pair at UbT + c*UP
+  float L11[2][16 * 16];            // double-buffered: panel p+1 is factored while p's is still read
   float inv[D];
   int piv[D];
   int flag;
@@ -322,13 +325,15 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
       a[rr][4 * q + 0] = t[0]; a[rr][4 * q + 1] = t[1]; a[rr][4 * q + 2] = t[2]; a[rr][4 * q + 3] = t[3];
     }
   }
+  int lane_piv = 0;     // lane j: pivot row of column cb + j
+  float lane_pv = 1.f;  // lane j: its pivot value
   static_for<0, 16>([&](auto J) {
     constexpr int j = decltype(J)::value;
     // key = |value| with the low 7 mantissa bits replaced by (127 - row): one unsigned max = argmax
     uint32_t key = 0;
 #pragma unroll
     for (int rr = 0; rr < NRL; ++rr) {
-      const uint32_t k = (__float_as_uint(fabsf(a[rr][j])) & 0xFFFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
+      const uint32_t k = (__float_as_uint(a[rr][j]) & 0x7FFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
       key = (active[rr] && k > key) ? k : key;
     }
     key = wave_max_u32(key);
@@ -337,13 +342,19 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
     const int pl = pr & 63;
     const bool ps = (NRL > 1) && (pr >= 64);
     float prow[16];
-    static_for<j, 16>([&](auto JJ) {
-      constexpr int jj = decltype(JJ)::value;
-      const float src = ps ? a[NRL - 1][jj] : a[0][jj];
-      prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, src), pl));
-    });
-    const float apv = fabsf(prow[j]);
-    if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
+    if (ps) {  // uniform branch: which of the lane's rows holds the pivot row
+      static_for<j, 16>([&](auto JJ) {
+        constexpr int jj = decltype(JJ)::value;
+        prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[NRL - 1][jj]), pl));
+      });
+    } else {
+      static_for<j, 16>([&](auto JJ) {
+        constexpr int jj = decltype(JJ)::value;
+        prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[0][jj]), pl));
+      });
+    }
+    lane_piv = (lane == j) ? pr : lane_piv;
+    lane_pv = (lane == j) ? prow[j] : lane_pv;
     const float inv = __builtin_amdgcn_rcpf(prow[j]);
 #pragma unroll
     for (int rr = 0; rr < NRL; ++rr) {
@@ -357,8 +368,15 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
         a[rr][jj] -= l * prow[jj];  // l = 0 for the pivot row itself
       });
     }
-    if (lane == 0) { S.piv[cb + j] = pr; S.inv[cb + j] = inv; }
   });
+  if (lane < 16) {
+    const float apv = fabsf(lane_pv);
+    S.piv[cb + lane] = lane_piv;
+    S.inv[cb + lane] = __builtin_amdgcn_rcpf(lane_pv);
+    if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
+  }
+  bad = __any(bad) ? 1 : 0;
+  float* L11 = S.L11[(cb >> 4) & 1];
 #pragma unroll
   for (int rr = 0; rr < NRL; ++rr) {
     const int r = lane + 64 * rr;
@@ -367,7 +385,7 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
       if (j0 >= 0) {
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
-          if (jj < j0) S.L11[j0 * 16 + jj] = a[rr][jj];
+          if (jj < j0) L11[j0 * 16 + jj] = a[rr][jj];
           if (jj <= j0) a[rr][jj] = 0.f;
         }
       }
@@ -381,36 +399,97 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   }
 }
 
-// (c) for up to NG tiles at once: tile (rt, ct) = rows [16 rt, +16) x columns [cb+16+16 ct, +16)
-template <int D, int NG>
-__device__ __forceinline__ void solve_update_tiles(float* W, const SolveScratch<D>& S, int cb, int i, int g,
-                                                   const int (&rt)[NG], const int (&ct)[NG], int ntile) {
+// (b) + (c) for up to four column tiles ct[0..nt) of the rest of panel cb (column tile t covers
+// columns [cb+16+16t, +16)), by one wavefront: lane 16u + i first forms column i of tile ct[u] of
+// U12, then the wavefront updates those tiles for every row tile.
+template <int D, int PARTS = 7>
+__device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb, int lane,
+                                            const int (&ct)[4], int nt) {
   using C = Cfg<D>;
-  float bl[NG][4], av[NG][4];
-  floatx4 acc[NG];
-  float* cp[NG];
+  using SS = SolveScratch<D>;
+  const int i = lane & 15, g = lane >> 4;
+  const float* L11 = S.L11[(cb >> 4) & 1];
+  // ---- (b)
+  if ((PARTS & 2) && g < nt) {
+    int mct = ct[0];
 #pragma unroll
-  for (int u = 0; u < NG; ++u) {
-    if (u < ntile) {
-      const float* lrow = W + (16 * rt[u] + i) * C::PITCH + cb + g;
-      const float* urow = S.Ub + g * C::PITCH + cb + 16 + 16 * ct[u] + i;
-      cp[u] = W + (16 * rt[u] + i) * C::PITCH + cb + 16 + 16 * ct[u] + 4 * g;
+    for (int u = 1; u < 4; ++u) mct = (g == u) ? ct[u] : mct;
+    const int c = cb + 16 + 16 * mct + i;
+    float u_[16];
+    int pv[16];
+    static_for<0, 16>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      pv[j] = S.piv[cb + j];
+      u_[j] = W[pv[j] * C::PITCH + c];
+    });
+    static_for<1, 16>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      static_for<0, (j + 3) / 4>([&](auto Q) {
+        constexpr int q = decltype(Q)::value;
+        const floatx4 l = *reinterpret_cast<const floatx4*>(L11 + j * 16 + 4 * q);
+        static_for<0, 4>([&](auto E) {
+          constexpr int e = decltype(E)::value;
+          if constexpr (4 * q + e < j) u_[j] -= l[e] * u_[4 * q + e];
+        });
+      });
+    });
+    static_for<0, 4>([&](auto Q) {
+      constexpr int q = decltype(Q)::value;
+      floatx4 t;
+      t[0] = -u_[4 * q + 0]; t[1] = -u_[4 * q + 1]; t[2] = -u_[4 * q + 2]; t[3] = -u_[4 * q + 3];
+      *reinterpret_cast<floatx4*>(S.UbT + c * SS::UP + 4 * q) = t;
+    });
+    static_for<0, 16>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      W[pv[j] * C::PITCH + c] = u_[j];
+    });
+  }
+  // ---- (c): MFMA k-step kk contracts the panel columns { 4g + kk }: lane (i, g) supplies, as A
+  // operand, -U12[4g+kk][column i of the tile] and, as B operand, Lm[row i of the row tile][4g+kk]
+  if (!(PARTS & 4)) return;
+  floatx4 av[4];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bl[u][kk] = lrow[4 * kk];
-        av[u][kk] = urow[4 * kk * C::PITCH];
-      }
-      acc[u] = *reinterpret_cast<const floatx4*>(cp[u]);
-    }
+  for (int u = 0; u < 4; ++u)
+    if (u < nt) av[u] = *reinterpret_cast<const floatx4*>(S.UbT + (cb + 16 + 16 * ct[u] + i) * SS::UP + 4 * g);
+  // all reads, then all matrix-core work, then all writes: the compiler cannot tell that the writes
+  // of one row tile do not feed the reads of the next, so a fused loop would serialise on LDS latency
+  float* const rowp = W + i * C::PITCH + cb;
+  floatx4 bl[C::NRT], acc[C::NRT][4];
+#pragma unroll
+  for (int rt = 0; rt < C::NRT; ++rt) {
+    bl[rt] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 4 * g);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (u < nt) acc[rt][u] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct[u] + 4 * g);
   }
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
+  for (int rt = 0; rt < C::NRT; ++rt)
 #pragma unroll
-    for (int u = 0; u < NG; ++u)
-      if (u < ntile) acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][kk], bl[u][kk], acc[u], 0, 0, 0);
+    for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-  for (int u = 0; u < NG; ++u)
-    if (u < ntile) *reinterpret_cast<floatx4*>(cp[u]) = acc[u];
+      for (int u = 0; u < 4; ++u)
+        if (u < nt) acc[rt][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][kk], bl[rt][kk], acc[rt][u], 0, 0, 0);
+#pragma unroll
+  for (int rt = 0; rt < C::NRT; ++rt)
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (u < nt) *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct[u] + 4 * g) = acc[rt][u];
+}
+
+// column tiles first, first+stride, ... < nct of the rest of panel cb, four at a time
+template <int D, int PARTS = 7>
+__device__ __forceinline__ void solve_tile_range(float* W, SolveScratch<D>& S, int cb, int lane, int first,
+                                                 int stride, int nct) {
+  for (int t0 = first; t0 < nct; t0 += 4 * stride) {
+    int ct[4];
+    int nt = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      ct[u] = t0 + u * stride;
+      nt += (ct[u] < nct) ? 1 : 0;
+    }
+    solve_tiles<D, PARTS>(W, S, cb, lane, ct, nt);
+  }
 }
 
 // PARTS is a development switch (bit 0: panels, bit 1: U12, bit 2: trailing updates); 7 = everything.
@@ -419,82 +498,33 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
   using C = Cfg<D>;
   constexpr int NP = D / 16;
   constexpr int NRL = (D + 63) / 64;
-  constexpr int NG = 4;
-  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  const int lane = tid & 63, w = tid >> 6;
   bool active[NRL];
 #pragma unroll
   for (int rr = 0; rr < NRL; ++rr) active[rr] = (lane + 64 * rr) < D;
   int bad = 0;
 
   if ((PARTS & 1) && w == 0) solve_panel<D>(W, S, 0, lane, active, bad);
-  __syncthreads();
   for (int p = 0; p < NP; ++p) {
+    __syncthreads();  // panel p is in place; every update of panel p-1 is done
     const int cb = 16 * p;
-    // ---------------------------------------------------------------- (b) U12, one thread per column
-    const int nrest = 2 * D - cb - 16;
-    if ((PARTS & 2) && tid < nrest) {
-      const int c = cb + 16 + tid;
-      float u[16];
-      int pv[16];
-      static_for<0, 16>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        pv[j] = S.piv[cb + j];
-        u[j] = W[pv[j] * C::PITCH + c];
-      });
-      static_for<1, 16>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        static_for<0, (j + 3) / 4>([&](auto Q) {
-          constexpr int q = decltype(Q)::value;
-          const floatx4 l = *reinterpret_cast<const floatx4*>(S.L11 + j * 16 + 4 * q);
-          static_for<0, 4>([&](auto E) {
-            constexpr int e = decltype(E)::value;
-            if constexpr (4 * q + e < j) u[j] -= l[e] * u[4 * q + e];
-          });
-        });
-        __builtin_amdgcn_sched_barrier(0);  // keep the L11 reads from all being hoisted (register pressure)
-      });
-      static_for<0, 16>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        S.Ub[j * C::PITCH + c] = -u[j];
-        W[pv[j] * C::PITCH + c] = u[j];
-      });
-    }
-    __syncthreads();
-    // ---------------------------------------------------------------- (c0) the next panel's columns
-    {
-      int rt1[C::RB], ct1[C::RB];
-#pragma unroll
-      for (int rb = 0; rb < C::RB; ++rb) { rt1[rb] = C::RB * w + rb; ct1[rb] = 0; }
-      if (PARTS & 4) solve_update_tiles<D, C::RB>(W, S, cb, i, g, rt1, ct1, C::RB);
-    }
-    __syncthreads();
-    // ---------------------------------------------------------------- (a) of p+1  ||  rest of (c)
+    const int nct = (2 * D - cb - 16) / 16;  // column tiles to the right of the panel
     const bool more = (p + 1 < NP);
-    const bool panel_here = more && w == 0;
-    if ((PARTS & 4) && (!panel_here || C::NW == 1)) {
-      const bool spare0 = more && C::NW > 1;           // wavefront 0 is busy with the next panel
-      const int nct = nrest / 16;
-      const int ntiles = (nct - 1) * C::NRT;           // column tiles 1..nct-1, all row tiles
-      const int nworkers = spare0 ? C::NW - 1 : C::NW;
-      const int wi = spare0 ? w - 1 : w;
-      for (int t0 = wi; t0 < ntiles; t0 += NG * nworkers) {
-        int rt[NG], ct[NG];
-        int cnt = 0;
-#pragma unroll
-        for (int u = 0; u < NG; ++u) {
-          const int t = t0 + u * nworkers;
-          rt[u] = t % C::NRT;
-          ct[u] = 1 + t / C::NRT;
-          cnt += (t < ntiles) ? 1 : 0;
-        }
-        if (cnt == NG) solve_update_tiles<D, NG>(W, S, cb, i, g, rt, ct, NG);
-        else solve_update_tiles<D, NG>(W, S, cb, i, g, rt, ct, cnt);
+    if (more && w == 0) {
+      if (PARTS & 6) {
+        solve_tile_range<D, PARTS>(W, S, cb, lane, 0, 1, 1);                    // the next panel's columns
+        if (C::NW == 1) solve_tile_range<D, PARTS>(W, S, cb, lane, 1, 1, nct);  // nobody else to do the rest
       }
+      if (PARTS & 1) solve_panel<D>(W, S, cb + 16, lane, active, bad);
+    } else if (PARTS & 6) {
+      const int workers = more ? C::NW - 1 : C::NW;
+      const int wi = more ? w - 1 : w;
+      const int first = more ? 1 : 0;
+      solve_tile_range<D, PARTS>(W, S, cb, lane, first + wi, workers, nct);
     }
-    if ((PARTS & 1) && panel_here) solve_panel<D>(W, S, cb + 16, lane, active, bad);
-    __syncthreads();
   }
   if (tid == 0) S.flag = bad;
+  __syncthreads();
   // gather + scale into the (now dead) left half, then copy back to the right half
   for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
     const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
