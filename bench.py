@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--rebase-every", type=int, default=DEFAULT_REBASE)
     ap.add_argument("--cpu-sample", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one device-to-device copy of this many MiB (a kernel of known traffic, "
+                         "to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (problems are independent; see DESIGN.md for the "
@@ -111,6 +114,12 @@ def main():
         binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, rebase_every=k,
                               out=out, workspace=ws, stream=stream)
 
+    if args.calib_copy_mib:
+        src = torch.ones((args.calib_copy_mib << 18,), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

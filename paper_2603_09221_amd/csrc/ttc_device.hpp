@@ -160,6 +160,7 @@ __device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
       constexpr int q1 = (ks + 1) / 4, t1 = (ks + 1) % 4;
 #pragma unroll
       for (int h = 0; h < C::NH; ++h) lds_ldv<C::VEC>(base + (16 * q1 + t1) * C::PITCH + 16 * C::VEC * h, b[nxt][h]);
+      __builtin_amdgcn_sched_barrier(0);  // reads first: a full k-step of matrix-core work hides their latency
     }
 #pragma unroll
     for (int h = 0; h < C::NH; ++h)

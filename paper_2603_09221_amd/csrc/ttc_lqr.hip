@@ -7,6 +7,18 @@
 
 namespace ttc {
 
+// Development aid: with -DTTC_PHASE_TIMERS, workgroup 0 accumulates s_memtime ticks per phase and
+// writes them to the end of its workspace slot (read back by a profiling script); otherwise no code.
+#ifdef TTC_PHASE_TIMERS
+#define TTC_TIMER_DECL long long tt_[8] = {0, 0, 0, 0, 0, 0, 0, 0}; long long tt0_ = __builtin_amdgcn_s_memtime();
+#define TTC_TOC(k) { const long long now_ = __builtin_amdgcn_s_memtime(); tt_[k] += now_ - tt0_; tt0_ = now_; }
+#define TTC_TIMER_DUMP(ptr) if (threadIdx.x == 0 && blockIdx.x == 0) { for (int k_ = 0; k_ < 8; ++k_) (ptr)[k_] += tt_[k_]; }
+#else
+#define TTC_TIMER_DECL
+#define TTC_TOC(k)
+#define TTC_TIMER_DUMP(ptr)
+#endif
+
 struct SolveArgs {
   long long n;
   int T, flags, rebase_every;
@@ -65,33 +77,73 @@ __device__ __forceinline__ int opaque_zero() {
   return z;
 }
 
-// copy a row-major global d x d matrix into one half of the LDS pair (optionally transposed)
+// copy a row-major global d x d matrix into one half of the LDS pair (optionally transposed).
+// All of a thread's global reads are issued before the first LDS write, so the memory latency is
+// paid once per matrix and not once per 16 bytes.
 template <int D, typename TIn, bool TRANS>
 __device__ __forceinline__ void load_half(float* Wh, const TIn* M, int tid) {
   using C = Cfg<D>;
-  for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
-    const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
-    const floatx4 v = ld4<TIn>(M, (long)r * D + c4);
-    if constexpr (TRANS) {
+  constexpr int NV = (D * D / 4 + C::NTHR - 1) / C::NTHR;  // float4 pieces per thread
+  floatx4 v[NV];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) Wh[(c4 + j) * C::PITCH + r] = v[j];
-    } else {
-      *reinterpret_cast<floatx4*>(Wh + r * C::PITCH + c4) = v;
+  for (int k = 0; k < NV; ++k) {
+    const int idx = tid + k * C::NTHR;
+    if (idx < D * D / 4) v[k] = ld4<TIn>(M, (long)(idx / (D / 4)) * D + (idx % (D / 4)) * 4);
+  }
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int idx = tid + k * C::NTHR;
+    if (idx < D * D / 4) {
+      const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
+      if constexpr (TRANS) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) Wh[(c4 + j) * C::PITCH + r] = v[k][j];
+      } else {
+        *reinterpret_cast<floatx4*>(Wh + r * C::PITCH + c4) = v[k];
+      }
     }
   }
 }
-// replace one half by its symmetric part (caller synchronises before and after)
+// replace one half by its symmetric part (caller synchronises before and after).  The matrix is cut
+// into 4 x 4 blocks; a thread takes the block pair (bi, bj), bi <= bj, reads both blocks with 16-byte
+// LDS reads, averages each with the other's transpose in registers and writes them back.
 template <int D>
 __device__ __forceinline__ void symmetrise_half(float* Wh, int tid) {
   using C = Cfg<D>;
-  for (int idx = tid; idx < D * D; idx += C::NTHR) {
-    const int r = idx / D, c = idx % D;
-    if (r < c) {
-      const float s = 0.5f * (Wh[r * C::PITCH + c] + Wh[c * C::PITCH + r]);
-      Wh[r * C::PITCH + c] = s;
-      Wh[c * C::PITCH + r] = s;
+  constexpr int NB = D / 4;
+  for (int idx = tid; idx < NB * NB; idx += C::NTHR) {
+    const int bi = idx / NB, bj = idx % NB;
+    if (bi > bj) continue;
+    floatx4 u[4], l[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      u[r] = *reinterpret_cast<const floatx4*>(Wh + (4 * bi + r) * C::PITCH + 4 * bj);
+      l[r] = *reinterpret_cast<const floatx4*>(Wh + (4 * bj + r) * C::PITCH + 4 * bi);
+    }
+    floatx4 un[4], ln[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float s = 0.5f * (u[r][c] + l[c][r]);
+        un[r][c] = s;
+        ln[c][r] = s;
+      }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      *reinterpret_cast<floatx4*>(Wh + (4 * bi + r) * C::PITCH + 4 * bj) = un[r];
+      *reinterpret_cast<floatx4*>(Wh + (4 * bj + r) * C::PITCH + 4 * bi) = ln[r];
     }
   }
+}
+// transpose one half in place through the accumulator layout (all threads; contains the barriers)
+template <int D>
+__device__ __forceinline__ void transpose_half(float* Wh, int w, int i, int g) {
+  floatx4 t[Cfg<D>::RB][Cfg<D>::NT];
+  load_rows<D>(Wh, t, w, i, g);
+  __syncthreads();
+  store_rows_T<D>(Wh, t, w, i, g);
+  __syncthreads();
 }
 template <int D>
 __device__ __forceinline__ void set_half_identity(float* Wh, int tid) {
@@ -154,6 +206,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
     const TIn* QTp = p.QT ? reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT : Qp;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
+    TTC_TIMER_DECL
     int info = 0, nsolve = 0;
     floatx4 acc[C::RB][C::NT];
     int s = 1;          // next reverse step (1 .. T-1)
@@ -161,12 +214,14 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
 
     // ---------------------------------------------------------------- phase R: X = R^{-1} B^T, G = B X
     load_half<D, TIn, false>(WL, Rp, tid);
-    load_half<D, TIn, true>(WR, Bp, tid);
+    load_half<D, TIn, false>(WR, Bp, tid);
     __syncthreads();
     symmetrise_half<D>(WL, tid);
-    __syncthreads();
+    transpose_half<D>(WR, w, i, g);              // RHS = B^T
+    TTC_TOC(0)
     ++nsolve;
     if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+    TTC_TOC(1)
     {
       float c[C::RB][C::KS];
       load_aop_lds<D>(WR, c, w, i, g);             // rows of X, kept for the final gain
@@ -185,33 +240,33 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
 
     // ---------------------------------------------------------------- phase A: A^{-1}, A^T, Q, Z2 = Q_T
     load_half<D, TIn, false>(WL, Ap, tid);
-    set_half_identity<D>(WR, tid);
+    load_half<D, TIn, false>(WR, Qp, tid);
     __syncthreads();
-    ++nsolve;
-    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+    symmetrise_half<D>(WR, tid);
     {
       float c[C::RB][C::KS];
-      load_aop_lds<D>(WR, c, w, i, g);
-      store_aop_ws<D>(wsC + 1 * D * D, c, tid);
-      // rows of A^T (columns of A), then rows of the symmetric part of Q, straight from global memory
+      // rows of A^T = columns of A, read from the LDS copy of A: c[4q+t] = A[16q+4g+t][row]
 #pragma unroll
       for (int rb = 0; rb < C::RB; ++rb)
 #pragma unroll
         for (int k = 0; k < C::KS; ++k)
-          c[rb][k] = ld1<TIn>(Ap, (long)(16 * (k / 4) + 4 * g + (k % 4)) * D + 16 * (C::RB * w + rb) + i);
+          c[rb][k] = WL[(16 * (k / 4) + 4 * g + (k % 4)) * C::PITCH + 16 * (C::RB * w + rb) + i];
       store_aop_ws<D>(wsC + 2 * D * D, c, tid);
-#pragma unroll
-      for (int rb = 0; rb < C::RB; ++rb) {
-        const int row = 16 * (C::RB * w + rb) + i;
-#pragma unroll
-        for (int q = 0; q < D / 16; ++q) {
-          const floatx4 qr = ld4<TIn>(Qp, (long)row * D + 16 * q + 4 * g);
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt)
-            c[rb][4 * q + tt] = 0.5f * (qr[tt] + ld1<TIn>(Qp, (long)(16 * q + 4 * g + tt) * D + row));
-        }
-      }
+      __syncthreads();
+      load_aop_lds<D>(WR, c, w, i, g);          // rows of the symmetric part of Q
       store_aop_ws<D>(wsC + 3 * D * D, c, tid);
+    }
+    __syncthreads();
+    set_half_identity<D>(WR, tid);
+    __syncthreads();
+    TTC_TOC(0)
+    ++nsolve;
+    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+    TTC_TOC(1)
+    {
+      float c[C::RB][C::KS];
+      load_aop_lds<D>(WR, c, w, i, g);
+      store_aop_ws<D>(wsC + 1 * D * D, c, tid);
     }
     __syncthreads();
     load_half<D, TIn, false>(WR, QTp, tid);    // initial pair [Y1 Y2] = [I Q_T]
@@ -220,6 +275,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     __syncthreads();
 
     // ---------------------------------------------------------------- phases S ... S, F
+    TTC_TOC(0)
     for (bool fin = (p.T == 1);;) {
       {
         // the constant row blocks live in registers only between two dense solves
@@ -231,6 +287,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
           float cAi[C::RB][C::KS], cQ[C::RB][C::KS];
           load_aop_ws<D>(wsC + 1 * D * D, cAi, tid, off);
           load_aop_ws<D>(wsC + 3 * D * D, cQ, tid, off);
+          TTC_TOC(2)
           for (int since = 1;; ++since, ++s) {
             const bool last = (since >= kreb) || (s == p.T - 1);
             if (fresh) eye_acc<D>(acc, w, i, g); else load_rows<D>(WL, acc, w, i, g);
@@ -276,8 +333,10 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
           __syncthreads();
         }
       }
+      TTC_TOC(3)
       ++nsolve;
       if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+      TTC_TOC(4)
       if (fin) break;
       symmetrise_half<D>(WR, tid);           // P is symmetric; also makes it its own Z-land image
       __syncthreads();
@@ -347,6 +406,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
       for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.K0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
     }
     __syncthreads();
+    TTC_TOC(5)
+    TTC_TIMER_DUMP(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * 5 * D * D / 2)
     if (tid == 0) {
       float val = 0.f;
       for (int ww = 0; ww < C::NW; ++ww) val += s_red[ww];
@@ -415,10 +476,10 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
 
     // ---- setup: X = R^{-1} B^T, G = B X; row blocks of G, X, A^T parked in the workspace
     load_half<D, TIn, false>(WL, Rp, tid);
-    load_half<D, TIn, true>(WR, Bp, tid);
+    load_half<D, TIn, false>(WR, Bp, tid);
     __syncthreads();
     symmetrise_half<D>(WL, tid);
-    __syncthreads();
+    transpose_half<D>(WR, w, i, g);              // RHS = B^T
     ++nsolve;
     if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
     {
