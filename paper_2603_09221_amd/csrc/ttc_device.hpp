@@ -101,19 +101,18 @@ __device__ __forceinline__ void lds_stv(float* p, const float (&v)[VEC]) {
 
 // ----------------------------------------------------------------------------------------------
 // wavefront reductions
-// max over the 64 lanes of an unsigned key, returned in every lane (DPP inside rows of 16 lanes,
-// then the four row results are combined through scalar registers)
+// max over the 64 lanes of an unsigned key, returned as a wave-uniform value (DPP only)
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
   auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
   x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
   x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
   x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, false));  // row_half_mirror
   x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, false));  // row_mirror
-  uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0);
-  uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
-  uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32);
-  uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
-  return mx(mx(a, b), mx(c, d));
+  // every lane of a row now holds its row's max; fold the four rows: row_bcast15 into rows 1 and 3,
+  // row_bcast31 into rows 2 and 3, so that lane 63 ends up with the max of all 64 lanes
+  x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xA, 0xF, false));
+  x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false));
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
 }
 // sum over the 16 lanes that share lane/16 (xor butterflies 1,2,4,8)
 __device__ __forceinline__ float sum16(float x) {
@@ -337,18 +336,25 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
       const uint32_t k = (__float_as_uint(a[rr][j]) & 0x7FFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
       key = (active[rr] && k > key) ? k : key;
     }
+    // every row's reciprocal is formed while the max is being reduced; the pivot row's one is used
+    float rinv[NRL];
+#pragma unroll
+    for (int rr = 0; rr < NRL; ++rr) rinv[rr] = __builtin_amdgcn_rcpf(a[rr][j]);
     key = wave_max_u32(key);
     int pr = 127 - (int)(key & 0x7Fu);
     pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
     const int pl = pr & 63;
     const bool ps = (NRL > 1) && (pr >= 64);
     float prow[16];
-    if (ps) {  // uniform branch: which of the lane's rows holds the pivot row
+    float inv;
+    if (ps) {
+      inv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rinv[NRL - 1]), pl));  // uniform branch: which of the lane's rows holds the pivot row
       static_for<j, 16>([&](auto JJ) {
         constexpr int jj = decltype(JJ)::value;
         prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[NRL - 1][jj]), pl));
       });
     } else {
+      inv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rinv[0]), pl));
       static_for<j, 16>([&](auto JJ) {
         constexpr int jj = decltype(JJ)::value;
         prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[0][jj]), pl));
@@ -356,7 +362,6 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
     }
     lane_piv = (lane == j) ? pr : lane_piv;
     lane_pv = (lane == j) ? prow[j] : lane_pv;
-    const float inv = __builtin_amdgcn_rcpf(prow[j]);
 #pragma unroll
     for (int rr = 0; rr < NRL; ++rr) {
       const bool mine = (lane == pl) && ((rr == NRL - 1 && NRL > 1) == ps);
