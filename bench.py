@@ -20,7 +20,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
-DEFAULT_REBASE = 3              # keep in step with the library default
+def default_rebase(d):
+    """The library default (re-base period by state size)."""
+    return 4 if d >= 128 else 3
 
 
 def alg_flops(d, T, k):
@@ -74,7 +76,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="llm_adapter")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
-    ap.add_argument("--rebase-every", type=int, default=DEFAULT_REBASE)
+    ap.add_argument("--rebase-every", type=int, default=0, help="0 = library default")
     ap.add_argument("--cpu-sample", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -93,7 +95,8 @@ def main():
 
     cfg = synth.CONFIGS[args.config]
     n = args.n or synth.config_problems(args.config)
-    d, m, T, k = cfg["d"], cfg["m"], cfg["T"], args.rebase_every
+    d, m, T = cfg["d"], cfg["m"], cfg["T"]
+    k = args.rebase_every or default_rebase(d)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     binding.load()

@@ -15,6 +15,14 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// 16-row blocks per wavefront as a function of d (workgroup = d/16/RB wavefronts)
+#ifndef TTC_ROW_BLOCKS
+#define TTC_ROW_BLOCKS(D) ((D) >= 32 ? 2 : 1)
+#endif
+#ifndef TTC_SCHED_BARRIER
+#define TTC_SCHED_BARRIER() __builtin_amdgcn_sched_barrier(0)
+#endif
+
 namespace ttc {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -34,7 +42,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 template <int D>
 struct Cfg {
-  static constexpr int RB = D >= 32 ? 2 : 1;    // 16-row blocks owned by one wavefront
+  static constexpr int RB = TTC_ROW_BLOCKS(D);  // 16-row blocks owned by one wavefront
   static constexpr int NRT = D / 16;            // 16-row blocks (= 16-column tiles) of a d x d matrix
   static constexpr int NW = NRT / RB;           // wavefronts per workgroup
   static constexpr int NTHR = 64 * NW;          // threads per workgroup (256 at d = 128: one wave per SIMD)
@@ -159,7 +167,7 @@ __device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
       constexpr int q1 = (ks + 1) / 4, t1 = (ks + 1) % 4;
 #pragma unroll
       for (int h = 0; h < C::NH; ++h) lds_ldv<C::VEC>(base + (16 * q1 + t1) * C::PITCH + 16 * C::VEC * h, b[nxt][h]);
-      __builtin_amdgcn_sched_barrier(0);  // reads first: a full k-step of matrix-core work hides their latency
+      TTC_SCHED_BARRIER();  // reads first: a full k-step of matrix-core work hides their latency
     }
 #pragma unroll
     for (int h = 0; h < C::NH; ++h)
@@ -169,7 +177,7 @@ __device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
         for (int rb = 0; rb < C::RB; ++rb)
           acc[rb][h * C::VEC + tp] =
               __builtin_amdgcn_mfma_f32_16x16x4f32(a[rb][ks], b[cur][h][tp], acc[rb][h * C::VEC + tp], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    TTC_SCHED_BARRIER();
   });
 }
 
