@@ -20,21 +20,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
-def default_rebase(d):
-    """The library default (re-base period by state size)."""
-    return 4 if d >= 128 else 3
+def default_groups(T, dtype):
+    """The library default: number of groups the T factors are split into (one dense solve each)."""
+    return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
 
 
-def alg_flops(d, T, k):
+def alg_flops(d, T, groups):
     """Algorithmic flops of one problem (2*M*N*K per product): what the re-based symplectic method
     has to compute, not what the kernel happens to execute.
-      setup   R^{-1}B^T factor d^3/3, G = B R^{-1} B^T 3 d^3, A^{-1} 2 d^3
-      steps   (T-1) reverse symplectic steps of 4 products: 8 d^3 each
-      re-base ceil((T-1)/k) pivoted solves Y1^{-1} Y2: 8/3 d^3 each
-      final   I + G P_1 and A^T P_1 (4 d^3), the solve (8/3 d^3), P_0 and K_0 (4 d^3)
+      setup   R^{-1}B^T factor d^3/3, G = B R^{-1} B^T 3 d^3, A^{-1} 2 d^3, C_K = R^{-1}B^T A^{-T} 2 d^3
+      steps   T-1 reverse symplectic steps of 4 products (8 d^3 each), the last factor (Q_0 = 0) 3 products
+      re-base one pivoted solve Y1^{-1} Y2 per group (the last one yields P_0): 8/3 d^3 each
+      output  K_0 = -C_K P_0: 2 d^3
     """
-    nreb = math.ceil((T - 1) / k) if T > 1 else 0
-    return (1.0 / 3 + 3 + 2 + 8 * (T - 1) + (8.0 / 3) * (nreb + 1) + 8) * d ** 3
+    return (1.0 / 3 + 3 + 2 + 2 + 8 * (T - 1) + 6 + (8.0 / 3) * groups + 2) * d ** 3
 
 
 def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):
@@ -96,7 +95,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     n = args.n or synth.config_problems(args.config)
     d, m, T = cfg["d"], cfg["m"], cfg["T"]
-    k = args.rebase_every or default_rebase(d)
+    k = args.rebase_every
+    groups = math.ceil(T / k) if k else default_groups(T, cfg["dtype"])
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     binding.load()
@@ -140,7 +140,7 @@ def main():
     value = n / (wall / args.steps)
     assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
 
-    flops = alg_flops(d, T, k) * n
+    flops = alg_flops(d, T, groups) * n
     achieved = flops / avg_kernel_s / 1e12
     in_bytes = n * (2 * d * d + d * m + m * m + d) * batch.A.element_size()
     out_bytes = n * (d * d + m * d + m + 2) * 4
@@ -150,11 +150,11 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.config, "problems": n, "d": d, "m": m, "T": T, "input_dtype": cfg["dtype"],
-                   "rebase_every": k, "outputs": "P0,K0,u0,value"},
+                   "rebase_every": k or "default", "groups": groups, "outputs": "P0,K0,u0,value"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
                      "kernel": "solve_kernel<%d>" % d, "kernel_ms": avg_kernel_s * 1e3,
-                     "alg_flops_per_problem": alg_flops(d, T, k),
+                     "alg_flops_per_problem": alg_flops(d, T, groups),
                      "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / avg_kernel_s / 1e12,
                      "alg_bytes_per_launch": in_bytes + out_bytes,
                      "alg_GBps": (in_bytes + out_bytes) / avg_kernel_s / 1e9},

@@ -10,8 +10,9 @@
  * The solve runs the backward Riccati recursion (Prop. 3.1) through the reverse symplectic
  * iteration of Thm 3.3: the pair [Y1 Y2] is multiplied by the factored symplectic matrices
  * Sigma_t (App. C "Kernel Fusion") and P = Y1^{-1} Y2 is recovered by a pivoted dense solve.
- * Because cond(Y1) grows geometrically with the number of accumulated factors, the pair is
- * re-based to [I P] every `rebase_every` steps (the paper's algorithm is rebase_every >= T-1).
+ * Because cond(Y1) grows geometrically with the number of accumulated factors, the T factors are
+ * applied in groups and the pair is re-based to [I P] after each group: rebase_every = k asks for
+ * ceil(T/k) groups of nearly equal length (the paper's algorithm is one group, rebase_every >= T).
  *
  * Conventions
  *   - All matrix arguments are DEVICE pointers to row-major, problem-major arrays: problem p of A
@@ -55,7 +56,7 @@ enum {
   /* P0 += Q: charge the stage cost on x0 as textbooks do.  Default 0 is the paper's Q_0 = 0
    * (Sec. 3.1, Thm A.3).  K0 and u0 do not depend on it. */
   TTC_FLAG_STAGE_COST_AT_X0 = 1,
-  /* Never re-base inside the horizon: accumulate all T-1 factors Sigma_T..Sigma_2 with row
+  /* Never re-base inside the horizon: accumulate all T factors Sigma_T..Sigma_1 with row
    * normalisation after every step (App. C "Numerical Stability") and do the dense solve once,
    * as Alg. 4 does.  For study: accuracy degrades quickly with T on dense problems. */
   TTC_FLAG_PURE_SYMPLECTIC = 2
@@ -67,7 +68,7 @@ typedef struct {
   int32_t d, m, T;      /* state size, control size, horizon                                       */
   int32_t in_dtype;     /* ttc_dtype_t of A, B, Q, R, QT, x0                                       */
   int32_t flags;        /* TTC_FLAG_*                                                              */
-  int32_t rebase_every; /* re-base [Y1 Y2] -> [I P] every this many steps; 0 = library default     */
+  int32_t rebase_every; /* at most this many factors between re-bases; 0 = library default         */
   const void *A;        /* (n, d, d)                                                               */
   const void *B;        /* (n, d, m)                                                               */
   const void *Q;        /* (n, d, d)                                                               */
@@ -84,7 +85,7 @@ typedef struct {
   float *u0;     /* (n, m)    first optimal control u0 = K0 x0 (the layer's output o)               */
   float *value;  /* (n)       x0^T P0 x0 = 2x the optimal objective of Eq. "ttc"                    */
   int32_t *info; /* (n)       0 = ok; s > 0 = the s-th dense solve of that problem broke down
-                               (1: R^{-1}B^T, 2: A^{-1}, 3..: re-bases in order, last: final solve) */
+                               (1: R^{-1}B^T, 2: A^{-1}, 3..: re-bases in order; the last yields P0)  */
 } ttc_lqr_solution_t;
 
 /* Bytes of device workspace ttc_lqr_solve (for_rollout = 0) or ttc_lqr_rollout (for_rollout = 1)
