@@ -20,6 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
+# HBM-side bytes per problem of solve_kernel<128, float> at the llm_adapter workload with the default
+# grouping, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy kernel
+# (profiles/solve_kernel_d128_T16_llm_adapter_n65536.md): (153.63e6 + 34.43e6) KiB / 65536 problems.
+MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (153.63e6 + 34.43e6) * 1024 / 65536}
 def default_groups(T, dtype):
     """The library default: number of groups the T factors are split into (one dense solve each)."""
     return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
@@ -152,7 +156,9 @@ def main():
         "config": {"workload": args.config, "problems": n, "d": d, "m": m, "T": T, "input_dtype": cfg["dtype"],
                    "rebase_every": k or "default", "groups": groups, "outputs": "P0,K0,u0,value"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[(args.config, groups)] * n
+                                 if (args.config, groups) in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
                      "kernel": "solve_kernel<%d>" % d, "kernel_ms": avg_kernel_s * 1e3,
                      "alg_flops_per_problem": alg_flops(d, T, groups),
                      "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / avg_kernel_s / 1e12,
