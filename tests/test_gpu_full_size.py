@@ -1,0 +1,61 @@
+"""GPU parity at the workloads' full sizes, in the launch configuration bench.py times (one launch over
+the whole batch, library defaults).  The oracle checks a random sample of problems one by one; properties
+that hold at any size (symmetry of P0, value >= 0, u0 = K0 x0, info == 0) are checked on every problem."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_09221_amd import binding, synth
+from tests.parity import oracle_solve, solve_errors
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def full_size_check(name, n, tol, sample=192, chunk=1 << 15):
+    cfg = synth.CONFIGS[name]
+    batch = synth.make_batch(n, cfg["d"], cfg["m"], cfg["T"], seed=0, device=DEV, dtype=cfg["dtype"], rho=cfg["rho"])
+    out = binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, batch.T)
+    torch.cuda.synchronize()
+    assert int(out["info"].abs().max()) == 0
+    # properties on every problem, evaluated on the device in chunks
+    for lo in range(0, n, chunk):
+        sl = slice(lo, min(n, lo + chunk))
+        P0, K0, u0, val, x0 = out["P0"][sl], out["K0"][sl], out["u0"][sl], out["value"][sl], batch.x0[sl].float()
+        assert torch.isfinite(val).all() and (val >= 0).all()
+        asym = (P0 - P0.transpose(1, 2)).flatten(1).norm(dim=1) / P0.flatten(1).norm(dim=1)
+        assert float(asym.max()) < 1e-5
+        ku = torch.einsum("nij,nj->ni", K0, x0)
+        assert float(((ku - u0).norm(dim=1) / u0.norm(dim=1)).max()) < 1e-4
+        quad = torch.einsum("ni,nij,nj->n", x0, P0, x0)
+        assert float(((quad - val).abs() / val.abs()).max()) < 1e-4
+    # oracle on a random sample
+    g = torch.Generator().manual_seed(123)
+    idx = torch.randperm(n, generator=g)[:sample].sort().values.to(DEV)
+    sub = batch.take(idx)
+    errs = solve_errors({k: out[k][idx] for k in ("P0", "K0", "u0", "value")}, oracle_solve(sub))
+    print(name, n, {k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= tol, (k, v)
+
+
+def test_config1_small_head_full():
+    full_size_check("small_head", synth.config_problems("small_head"), 1e-4)
+
+
+def test_config3_long_horizon_slice():
+    # the host-side spectral-radius scaling makes generation slow; an eighth of the workload, several grid passes
+    full_size_check("long_horizon", 8192, 1e-4, sample=128)
+
+
+def test_config4_mixed_precision_slice():
+    # the full workload does not fit next to its outputs (172 GB in, 138 GB out): one (batch, head) slice
+    full_size_check("mixed_precision", 8192 * 4, 2e-2, sample=96)
+
+
+def test_config2_llm_adapter_full():
+    n = synth.config_problems("llm_adapter")
+    free, _ = torch.cuda.mem_get_info()
+    if free < 230e9:
+        pytest.skip("needs 206 GB of free device memory")
+    full_size_check("llm_adapter", n, 1e-4, sample=256)
