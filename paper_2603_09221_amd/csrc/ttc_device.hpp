@@ -19,6 +19,10 @@
 #ifndef TTC_ROW_BLOCKS
 #define TTC_ROW_BLOCKS(D) ((D) >= 32 ? 2 : 1)
 #endif
+// column tiles a wavefront updates in one batch of the dense solve (registers: 4*NRT*NTC accumulators)
+#ifndef TTC_SOLVE_NTC
+#define TTC_SOLVE_NTC 4
+#endif
 #ifndef TTC_SCHED_BARRIER
 #define TTC_SCHED_BARRIER() __builtin_amdgcn_sched_barrier(0)
 #endif
@@ -413,96 +417,94 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   }
 }
 
-// (b) + (c) for up to four column tiles ct[0..nt) of the rest of panel cb (column tile t covers
-// columns [cb+16+16t, +16)), by one wavefront: lane 16u + i first forms column i of tile ct[u] of
-// U12, then the wavefront updates those tiles for every row tile.
-template <int D, int PARTS = 7>
-__device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb, int lane,
-                                            const int (&ct)[4], int nt) {
+// (b) + (c) for the nt <= NTC consecutive column tiles ct0 .. ct0+nt-1 of the rest of panel cb (column
+// tile t covers columns [cb+16+16t, +16)), by one wavefront: lane 16u + i first forms column i of a
+// tile of U12 (four tiles per pass), then the wavefront updates its tiles for every row tile.
+template <int D, int NTC, int PARTS = 7>
+__device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb, int lane, int ct0, int nt) {
   using C = Cfg<D>;
   using SS = SolveScratch<D>;
   const int i = lane & 15, g = lane >> 4;
   const float* L11 = S.L11[(cb >> 4) & 1];
   // ---- (b)
-  if ((PARTS & 2) && g < nt) {
-    int mct = ct[0];
+  if (PARTS & 2) {
 #pragma unroll
-    for (int u = 1; u < 4; ++u) mct = (g == u) ? ct[u] : mct;
-    const int c = cb + 16 + 16 * mct + i;
-    float u_[16];
-    int pv[16];
-    static_for<0, 16>([&](auto J) {
-      constexpr int j = decltype(J)::value;
-      pv[j] = S.piv[cb + j];
-      u_[j] = W[pv[j] * C::PITCH + c];
-    });
-    static_for<1, 16>([&](auto J) {
-      constexpr int j = decltype(J)::value;
-      static_for<0, (j + 3) / 4>([&](auto Q) {
-        constexpr int q = decltype(Q)::value;
-        const floatx4 l = *reinterpret_cast<const floatx4*>(L11 + j * 16 + 4 * q);
-        static_for<0, 4>([&](auto E) {
-          constexpr int e = decltype(E)::value;
-          if constexpr (4 * q + e < j) u_[j] -= l[e] * u_[4 * q + e];
+    for (int pass = 0; pass < (NTC + 3) / 4; ++pass) {
+      if (4 * pass + g < nt) {
+        const int c = cb + 16 + 16 * (ct0 + 4 * pass + g) + i;
+        float u_[16];
+        int pv[16];
+        static_for<0, 16>([&](auto J) {
+          constexpr int j = decltype(J)::value;
+          pv[j] = S.piv[cb + j];
+          u_[j] = W[pv[j] * C::PITCH + c];
         });
-      });
-    });
-    static_for<0, 4>([&](auto Q) {
-      constexpr int q = decltype(Q)::value;
-      floatx4 t;
-      t[0] = -u_[4 * q + 0]; t[1] = -u_[4 * q + 1]; t[2] = -u_[4 * q + 2]; t[3] = -u_[4 * q + 3];
-      *reinterpret_cast<floatx4*>(S.UbT + c * SS::UP + 4 * q) = t;
-    });
-    static_for<0, 16>([&](auto J) {
-      constexpr int j = decltype(J)::value;
-      W[pv[j] * C::PITCH + c] = u_[j];
-    });
+        static_for<1, 16>([&](auto J) {
+          constexpr int j = decltype(J)::value;
+          static_for<0, (j + 3) / 4>([&](auto Q) {
+            constexpr int q = decltype(Q)::value;
+            const floatx4 l = *reinterpret_cast<const floatx4*>(L11 + j * 16 + 4 * q);
+            static_for<0, 4>([&](auto E) {
+              constexpr int e = decltype(E)::value;
+              if constexpr (4 * q + e < j) u_[j] -= l[e] * u_[4 * q + e];
+            });
+          });
+        });
+        static_for<0, 4>([&](auto Q) {
+          constexpr int q = decltype(Q)::value;
+          floatx4 t;
+          t[0] = -u_[4 * q + 0]; t[1] = -u_[4 * q + 1]; t[2] = -u_[4 * q + 2]; t[3] = -u_[4 * q + 3];
+          *reinterpret_cast<floatx4*>(S.UbT + c * SS::UP + 4 * q) = t;
+        });
+        static_for<0, 16>([&](auto J) {
+          constexpr int j = decltype(J)::value;
+          W[pv[j] * C::PITCH + c] = u_[j];
+        });
+      }
+    }
   }
-  // ---- (c): MFMA k-step kk contracts the panel columns { 4g + kk }: lane (i, g) supplies, as A
-  // operand, -U12[4g+kk][column i of the tile] and, as B operand, Lm[row i of the row tile][4g+kk]
   if (!(PARTS & 4)) return;
-  floatx4 av[4];
-#pragma unroll
-  for (int u = 0; u < 4; ++u)
-    if (u < nt) av[u] = *reinterpret_cast<const floatx4*>(S.UbT + (cb + 16 + 16 * ct[u] + i) * SS::UP + 4 * g);
-  // all reads, then all matrix-core work, then all writes: the compiler cannot tell that the writes
-  // of one row tile do not feed the reads of the next, so a fused loop would serialise on LDS latency
+  // ---- (c): MFMA k-step kk contracts the panel columns { 4g + kk }: lane (i, g) supplies, as A
+  // operand, -U12[4g+kk][column i of the tile] and, as B operand, Lm[row i of the row tile][4g+kk].
+  // All reads, then all matrix-core work, then all writes: the compiler cannot tell that the writes
+  // of one row tile do not feed the reads of the next, so a fused loop would serialise on LDS latency.
   float* const rowp = W + i * C::PITCH + cb;
-  floatx4 bl[C::NRT], acc[C::NRT][4];
+  const int c0 = 16 + 16 * ct0 + 4 * g;
+  floatx4 av[NTC], bl[C::NRT], acc[C::NRT][NTC];
+#pragma unroll
+  for (int u = 0; u < NTC; ++u)
+    if (u < nt) av[u] = *reinterpret_cast<const floatx4*>(S.UbT + (cb + 16 + 16 * (ct0 + u) + i) * SS::UP + 4 * g);
 #pragma unroll
   for (int rt = 0; rt < C::NRT; ++rt) {
     bl[rt] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 4 * g);
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (u < nt) acc[rt][u] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct[u] + 4 * g);
+    for (int u = 0; u < NTC; ++u)
+      if (u < nt) acc[rt][u] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + c0 + 16 * u);
   }
 #pragma unroll
   for (int rt = 0; rt < C::NRT; ++rt)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < NTC; ++u)
         if (u < nt) acc[rt][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][kk], bl[rt][kk], acc[rt][u], 0, 0, 0);
 #pragma unroll
   for (int rt = 0; rt < C::NRT; ++rt)
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (u < nt) *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct[u] + 4 * g) = acc[rt][u];
+    for (int u = 0; u < NTC; ++u)
+      if (u < nt) *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + c0 + 16 * u) = acc[rt][u];
 }
 
-// column tiles first, first+stride, ... < nct of the rest of panel cb, four at a time
+// the consecutive column tiles lo .. hi-1 of the rest of panel cb, at most NTC per call
 template <int D, int PARTS = 7>
-__device__ __forceinline__ void solve_tile_range(float* W, SolveScratch<D>& S, int cb, int lane, int first,
-                                                 int stride, int nct) {
-  for (int t0 = first; t0 < nct; t0 += 4 * stride) {
-    int ct[4];
-    int nt = 0;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      ct[u] = t0 + u * stride;
-      nt += (ct[u] < nct) ? 1 : 0;
-    }
-    solve_tiles<D, PARTS>(W, S, cb, lane, ct, nt);
+__device__ __forceinline__ void solve_tile_range(float* W, SolveScratch<D>& S, int cb, int lane, int lo, int hi) {
+  constexpr int NTC = TTC_SOLVE_NTC;
+  for (int t0 = lo; t0 < hi; t0 += NTC) {
+    const int nt = hi - t0 < NTC ? hi - t0 : NTC;
+    if (nt == 1) solve_tiles<D, 1, PARTS>(W, S, cb, lane, t0, 1);
+    else if (nt <= 2) solve_tiles<D, 2, PARTS>(W, S, cb, lane, t0, nt);
+    else if (nt <= 4 || NTC <= 4) solve_tiles<D, (NTC < 4 ? NTC : 4), PARTS>(W, S, cb, lane, t0, nt);
+    else solve_tiles<D, NTC, PARTS>(W, S, cb, lane, t0, nt);
   }
 }
 
@@ -526,15 +528,15 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
     const bool more = (p + 1 < NP);
     if (more && w == 0) {
       if (PARTS & 6) {
-        solve_tile_range<D, PARTS>(W, S, cb, lane, 0, 1, 1);                    // the next panel's columns
-        if (C::NW == 1) solve_tile_range<D, PARTS>(W, S, cb, lane, 1, 1, nct);  // nobody else to do the rest
+        solve_tile_range<D, PARTS>(W, S, cb, lane, 0, 1);                     // the next panel's columns
+        if (C::NW == 1) solve_tile_range<D, PARTS>(W, S, cb, lane, 1, nct);   // nobody else to do the rest
       }
       if (PARTS & 1) solve_panel<D>(W, S, cb + 16, lane, active, bad);
     } else if (PARTS & 6) {
       const int workers = more ? C::NW - 1 : C::NW;
       const int wi = more ? w - 1 : w;
-      const int first = more ? 1 : 0;
-      solve_tile_range<D, PARTS>(W, S, cb, lane, first + wi, workers, nct);
+      const int first = more ? 1 : 0, ntile = nct - first;   // a contiguous share of the column tiles each
+      solve_tile_range<D, PARTS>(W, S, cb, lane, first + (wi * ntile) / workers, first + ((wi + 1) * ntile) / workers);
     }
   }
   if (tid == 0) S.flag = bad;

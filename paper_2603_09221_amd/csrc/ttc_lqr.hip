@@ -186,7 +186,7 @@ __device__ __forceinline__ void write_rows_global(float* dst, const floatx4 (&ac
 //            T factors Sigma_T .. Sigma_1 are applied; the last factor has Q_0 = 0, i.e. no "+ Y1 Q".
 //   output   after the last solve the right half is P_0 = Y1^{-1} Y2 itself (Alg. 4), lambda_0 = P_0 x0,
 //            and K_0 = -R^{-1} B^T A^{-T} P_0 = -C_K P_0 (Thm A.4: u_1 = -R^{-1} B^T A^{-T} lambda_0).
-// The constant row blocks live in registers only between two dense solves (parked in the workspace).
+// The constant row blocks stay in registers from the end of the set-up to the end of the problem.
 template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) {
   using C = Cfg<D>;
@@ -287,14 +287,15 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     __syncthreads();
 
     // ---------------------------------------------------------------- groups of steps, each ended by a re-base
+    // the constant row blocks, in registers for the rest of the problem (they took a detour through the
+    // workspace because they were produced while the dense solves of the set-up needed the registers)
+    float cG[C::RB][C::KS], cAi[C::RB][C::KS], cAT[C::RB][C::KS], cQ[C::RB][C::KS];
+    load_aop_ws<D>(wsC + 0 * D * D, cG, tid, 0);
+    load_aop_ws<D>(wsC + 1 * D * D, cAi, tid, 0);
+    load_aop_ws<D>(wsC + 2 * D * D, cAT, tid, 0);
+    load_aop_ws<D>(wsC + 3 * D * D, cQ, tid, 0);
     for (;;) {
       {
-        float cG[C::RB][C::KS], cAi[C::RB][C::KS], cAT[C::RB][C::KS], cQ[C::RB][C::KS];
-        const int off = opaque_zero();
-        load_aop_ws<D>(wsC + 0 * D * D, cG, tid, off);
-        load_aop_ws<D>(wsC + 1 * D * D, cAi, tid, off);
-        load_aop_ws<D>(wsC + 2 * D * D, cAT, tid, off);
-        load_aop_ws<D>(wsC + 3 * D * D, cQ, tid, off);
         TTC_TOC(2)
         const int gend = p.gend[grp];  // last step of this group
         for (;; ++s) {
@@ -502,53 +503,46 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
     symmetrise_half<D>(WR, tid);
     __syncthreads();
 
-    // ---- backward sweep
+    // ---- backward sweep (the constant row blocks stay in registers)
+    float cG[C::RB][C::KS], cX[C::RB][C::KS], cAT[C::RB][C::KS];
+    load_aop_ws<D>(wsC + 0 * D * D, cG, tid, 0);
+    load_aop_ws<D>(wsC + 1 * D * D, cX, tid, 0);
+    load_aop_ws<D>(wsC + 2 * D * D, cAT, tid, 0);
     for (int t = p.T - 1; t >= 0; --t) {
-      const int off = opaque_zero();
-      {
-        float cG[C::RB][C::KS], cAT[C::RB][C::KS];
-        load_aop_ws<D>(wsC + 0 * D * D, cG, tid, off);
-        load_aop_ws<D>(wsC + 2 * D * D, cAT, tid, off);
-        eye_acc<D>(acc, w, i, g);
-        gemm_acc<D>(acc, cG, WR, i, g);   // (I + P G)^T
-        store_rows_T<D>(WL, acc, w, i, g);
-        zero_acc<D>(acc);
-        gemm_acc<D>(acc, cAT, WR, i, g);  // (P A)^T
-        __syncthreads();
-        store_rows_T<D>(WR, acc, w, i, g);
-        __syncthreads();
-      }
+      eye_acc<D>(acc, w, i, g);
+      gemm_acc<D>(acc, cG, WR, i, g);   // (I + P G)^T
+      store_rows_T<D>(WL, acc, w, i, g);
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, cAT, WR, i, g);  // (P A)^T
+      __syncthreads();
+      store_rows_T<D>(WR, acc, w, i, g);
+      __syncthreads();
       ++nsolve;
       if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-      {
-        float c[C::RB][C::KS];
-        load_aop_ws<D>(wsC + 1 * D * D, c, tid, off);
-        zero_acc<D>(acc);
-        gemm_acc<D>(acc, c, WR, i, g);    // -K_t
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, cX, WR, i, g);    // -K_t
 #pragma unroll
-        for (int rb = 0; rb < C::RB; ++rb) {
+      for (int rb = 0; rb < C::RB; ++rb) {
 #pragma unroll
-          for (int cc = 0; cc < C::NT; ++cc) acc[rb][cc] = -acc[rb][cc];
-          write_rows_global<D>(wsK + (long)t * D * D, acc[rb], C::RB * w + rb, i, g);
-        }
-        if (t >= 1) {
-          load_aop_ws<D>(wsC + 2 * D * D, c, tid, off);
+        for (int cc = 0; cc < C::NT; ++cc) acc[rb][cc] = -acc[rb][cc];
+        write_rows_global<D>(wsK + (long)t * D * D, acc[rb], C::RB * w + rb, i, g);
+      }
+      if (t >= 1) {
 #pragma unroll
-          for (int rb = 0; rb < C::RB; ++rb)
+        for (int rb = 0; rb < C::RB; ++rb)
 #pragma unroll
-            for (int cc = 0; cc < C::NT; ++cc)
+          for (int cc = 0; cc < C::NT; ++cc)
 #pragma unroll
-              for (int v = 0; v < 4; ++v) {
-                const long row = 16 * (C::RB * w + rb) + 4 * g + v, col = tile_col<D>(cc, i);
-                acc[rb][cc][v] = 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
-              }
-          gemm_acc<D>(acc, c, WR, i, g);  // P_t = Q + A^T M_t
-          __syncthreads();
-          store_rows<D>(WR, acc, w, i, g);
-          __syncthreads();
-          symmetrise_half<D>(WR, tid);
-          __syncthreads();
-        }
+            for (int v = 0; v < 4; ++v) {
+              const long row = 16 * (C::RB * w + rb) + 4 * g + v, col = tile_col<D>(cc, i);
+              acc[rb][cc][v] = 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
+            }
+        gemm_acc<D>(acc, cAT, WR, i, g);  // P_t = Q + A^T M_t
+        __syncthreads();
+        store_rows<D>(WR, acc, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WR, tid);
+        __syncthreads();
       }
     }
     __syncthreads();  // gains visible to the whole workgroup
