@@ -50,8 +50,9 @@ __device__ __forceinline__ void load_aop_global(const TIn* M, float (&a)[Cfg<D>:
 }
 
 // A-operand registers <-> workspace, in lane order (thread t's k-th float4 at [k][t]): fully coalesced.
-// The constants are parked there while a dense solve runs, so that the solve has the register file
-// to itself; `off` is an opaque zero that keeps the compiler from hoisting the reloads out of loops.
+// The constant row blocks are produced while the dense solves of the set-up own the register file,
+// so they pass through the workspace once; `off` is an opaque zero that keeps the compiler from
+// moving the reloads across the code in between.
 template <int D>
 __device__ __forceinline__ void store_aop_ws(float* wsc, const float (&a)[Cfg<D>::RB][Cfg<D>::KS], int tid) {
   using C = Cfg<D>;
@@ -469,7 +470,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
     int info = 0, nsolve = 0;
     floatx4 acc[C::RB][C::NT];
 
-    // ---- setup: X = R^{-1} B^T, G = B X; row blocks of G, X, A^T parked in the workspace
+    // ---- setup: X = R^{-1} B^T, G = B X; row blocks of G, X, A^T to the workspace
     load_half<D, TIn, false>(WL, Rp, tid);
     load_half<D, TIn, false>(WR, Bp, tid);
     __syncthreads();
