@@ -59,7 +59,15 @@ enum {
   /* Never re-base inside the horizon: accumulate all T factors Sigma_T..Sigma_1 with row
    * normalisation after every step (App. C "Numerical Stability") and do the dense solve once,
    * as Alg. 4 does.  For study: accuracy degrades quickly with T on dense problems. */
-  TTC_FLAG_PURE_SYMPLECTIC = 2
+  TTC_FLAG_PURE_SYMPLECTIC = 2,
+  /* Long-horizon path (ttc_lqr_solve only): the parameters are time-invariant (the paper's "Homo."
+   * setting), so the T factors of Thm 3.3 are T copies of one matrix and their product (Sec. 3.3)
+   * is formed by repeated squaring, about log2(T) dense solves instead of one per group of factors.
+   * Each factor is held as the triple (A_e, G_e, H_e) of the map P -> H_e + A_e^T P (I + G_e P)^{-1} A_e
+   * (Prop. 3.1 in that form), which composes without A^{-1} and needs no re-basing.  Same outputs and
+   * tolerances; rebase_every is ignored; cannot be combined with TTC_FLAG_PURE_SYMPLECTIC.
+   * info: 1 = R^{-1}B^T, then every dense solve in program order, the last one being the final step. */
+  TTC_FLAG_DOUBLING = 4
 };
 
 /* Problem statement: the (A, B, Q, R, Q_T, x0, T) of Eq. "ttc" for n problems. */
@@ -90,7 +98,7 @@ typedef struct {
 
 /* Bytes of device workspace ttc_lqr_solve (for_rollout = 0) or ttc_lqr_rollout (for_rollout = 1)
  * needs for this problem on the current device.  Returns 0 for an unsupported/invalid problem.
- * Depends only on d, m, T and the device's compute-unit count, never on n. */
+ * Depends only on d, m, T, flags and the device's compute-unit count, never on n. */
 size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t *problem, int for_rollout);
 
 /* Solve n problems: P0, K0, u0, value (Prop. 3.1 via Thm 3.3 / Alg. 4, see the file header).

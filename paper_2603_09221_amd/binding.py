@@ -18,6 +18,7 @@ TTC_OK, TTC_ERR_INVALID_ARG, TTC_ERR_UNSUPPORTED, TTC_ERR_WORKSPACE, TTC_ERR_DEV
 TTC_F32, TTC_BF16 = 0, 1
 TTC_FLAG_STAGE_COST_AT_X0 = 1
 TTC_FLAG_PURE_SYMPLECTIC = 2
+TTC_FLAG_DOUBLING = 4
 
 EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_status_string", "ttc_version")
 

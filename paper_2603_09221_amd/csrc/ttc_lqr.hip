@@ -177,6 +177,75 @@ __device__ __forceinline__ void write_rows_global(float* dst, const floatx4 (&ac
     }
 }
 
+// Outputs of one problem.  On entry acc holds this wavefront's rows of -K_0 and the LDS half WP holds
+// P_0 in the paper's convention (Q_0 = 0).  Writes u_0 = K_0 x0, K_0, P_0 (+ Q with
+// TTC_FLAG_STAGE_COST_AT_X0), value = x0^T P_0 x0 and info; a problem whose info is non-zero gets NaN.
+// Ends with a barrier, so the caller may reuse LDS right away.
+template <int D, typename TIn>
+__device__ __forceinline__ void emit_outputs(const SolveArgs& p, long long prob, floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
+                                             const float* WP, const TIn* Qp, const TIn* x0p, int info, float* s_red,
+                                             int tid) {
+  using C = Cfg<D>;
+  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  const float nanv = __builtin_nanf("");
+  float x0c[C::NT];
+#pragma unroll
+  for (int c = 0; c < C::NT; ++c) x0c[c] = ld1<TIn>(x0p, tile_col<D>(c, i));
+  float vpart = 0.f;
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float pu = 0.f;
+#pragma unroll
+      for (int c = 0; c < C::NT; ++c) {
+        const float ke = info ? nanv : -acc[rb][c][v];
+        acc[rb][c][v] = ke;
+        pu += ke * x0c[c];
+      }
+      pu = sum16(pu);
+      if (i == 0) p.u0[prob * D + 16 * (C::RB * w + rb) + 4 * g + v] = pu;
+    }
+  if (p.K0) {
+#pragma unroll
+    for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.K0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
+  }
+  load_rows<D>(WP, acc, w, i, g);                // rows of P_0
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const long row = 16 * (C::RB * w + rb) + 4 * g + v;
+      float pw = 0.f;
+#pragma unroll
+      for (int c = 0; c < C::NT; ++c) {
+        float pe = acc[rb][c][v];
+        if (p.flags & TTC_FLAG_STAGE_COST_AT_X0) {
+          const long col = tile_col<D>(c, i);
+          pe += 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
+        }
+        if (info) pe = nanv;
+        acc[rb][c][v] = pe;
+        pw += pe * x0c[c];
+      }
+      vpart += ld1<TIn>(x0p, row) * pw;
+    }
+  vpart = sum64(vpart);
+  if (lane == 0) s_red[w] = vpart;
+  if (p.P0) {
+#pragma unroll
+    for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.P0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float val = 0.f;
+    for (int ww = 0; ww < C::NW; ++ww) val += s_red[ww];
+    if (p.value) p.value[prob] = val;
+    if (p.info) p.info[prob] = info;
+  }
+  __syncthreads();
+}
+
 // Solve kernel.  Persistent workgroups: workgroup b handles problems b, b + gridDim.x, ...
 //
 // Per problem the work is a sequence of phases, each "build [M | RHS] in LDS, dense solve, consume":
@@ -346,73 +415,21 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     }
 
     // ---- outputs: WR holds P_0 (paper convention, Q_0 = 0)
-    const float nanv = __builtin_nanf("");
-    float x0c[C::NT];
-#pragma unroll
-    for (int c = 0; c < C::NT; ++c) x0c[c] = ld1<TIn>(x0p, tile_col<D>(c, i));
-    float vpart = 0.f;
     {
       float c[C::RB][C::KS];
       load_aop_ws<D>(wsC + 4 * D * D, c, tid, opaque_zero());
       zero_acc<D>(acc);
       gemm_acc<D>(acc, c, WR, i, g);               // -K_0 = C_K P_0
     }
-#pragma unroll
-    for (int rb = 0; rb < C::RB; ++rb)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        float pu = 0.f;
-#pragma unroll
-        for (int c = 0; c < C::NT; ++c) {
-          const float ke = info ? nanv : -acc[rb][c][v];
-          acc[rb][c][v] = ke;
-          pu += ke * x0c[c];
-        }
-        pu = sum16(pu);
-        if (i == 0) p.u0[prob * D + 16 * (C::RB * w + rb) + 4 * g + v] = pu;
-      }
-    if (p.K0) {
-#pragma unroll
-      for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.K0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
-    }
-    load_rows<D>(WR, acc, w, i, g);                // rows of P_0
-#pragma unroll
-    for (int rb = 0; rb < C::RB; ++rb)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const long row = 16 * (C::RB * w + rb) + 4 * g + v;
-        float pw = 0.f;
-#pragma unroll
-        for (int c = 0; c < C::NT; ++c) {
-          float pe = acc[rb][c][v];
-          if (p.flags & TTC_FLAG_STAGE_COST_AT_X0) {
-            const long col = tile_col<D>(c, i);
-            pe += 0.5f * (ld1<TIn>(Qp, row * D + col) + ld1<TIn>(Qp, col * D + row));
-          }
-          if (info) pe = nanv;
-          acc[rb][c][v] = pe;
-          pw += pe * x0c[c];
-        }
-        vpart += ld1<TIn>(x0p, row) * pw;
-      }
-    vpart = sum64(vpart);
-    if (lane == 0) s_red[w] = vpart;
-    if (p.P0) {
-#pragma unroll
-      for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.P0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
-    }
-    __syncthreads();
+    emit_outputs<D, TIn>(p, prob, acc, WR, Qp, x0p, info, s_red, tid);
     TTC_TOC(5)
     TTC_TIMER_DUMP(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * 5 * D * D / 2)
-    if (tid == 0) {
-      float val = 0.f;
-      for (int ww = 0; ww < C::NW; ++ww) val += s_red[ww];
-      if (p.value) p.value[prob] = val;
-      if (p.info) p.info[prob] = info;
-    }
-    __syncthreads();
   }
 }
+
+}  // namespace ttc
+#include "ttc_doubling.hpp"
+namespace ttc {
 
 // ------------------------------------------------------------------------------------------------
 struct RolloutArgs {
@@ -617,7 +634,8 @@ static ttc_status_t validate(const ttc_lqr_problem_t* q) {
   if (!q) return TTC_ERR_INVALID_ARG;
   if (q->n < 0 || q->T < 1 || q->d < 1 || q->m < 1 || q->rebase_every < 0) return TTC_ERR_INVALID_ARG;
   if (q->in_dtype != TTC_F32 && q->in_dtype != TTC_BF16) return TTC_ERR_INVALID_ARG;
-  if (q->flags & ~(TTC_FLAG_STAGE_COST_AT_X0 | TTC_FLAG_PURE_SYMPLECTIC)) return TTC_ERR_INVALID_ARG;
+  if (q->flags & ~(TTC_FLAG_STAGE_COST_AT_X0 | TTC_FLAG_PURE_SYMPLECTIC | TTC_FLAG_DOUBLING)) return TTC_ERR_INVALID_ARG;
+  if ((q->flags & TTC_FLAG_PURE_SYMPLECTIC) && (q->flags & TTC_FLAG_DOUBLING)) return TTC_ERR_INVALID_ARG;
   if (!shape_supported(q)) return TTC_ERR_UNSUPPORTED;
   if (q->n == 0) return TTC_OK;
   if (!q->A || !q->B || !q->Q || !q->R || !q->x0) return TTC_ERR_INVALID_ARG;
@@ -645,6 +663,18 @@ static hipError_t launch_solve(const SolveArgs& a, int d, dim3 grid, hipStream_t
 }
 
 template <typename TIn>
+static hipError_t launch_doubling(const DoublingArgs& a, int d, dim3 grid, hipStream_t st) {
+  switch (d) {
+    case 16: hipLaunchKernelGGL((doubling_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((doubling_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((doubling_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((doubling_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <typename TIn>
 static hipError_t launch_rollout(const RolloutArgs& a, int d, dim3 grid, hipStream_t st) {
   switch (d) {
     case 16: hipLaunchKernelGGL((rollout_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
@@ -664,7 +694,8 @@ size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t* problem, int for_rollout
   if (!problem || problem->T < 1 || !ttc::shape_supported(problem)) return 0;
   const size_t slots = (size_t)ttc::grid_blocks(problem->d);
   const size_t per = (size_t)problem->d * problem->m * sizeof(float);
-  return slots * per * (for_rollout ? (size_t)problem->T + 3 : 5);
+  const size_t solve_slots = (problem->flags & TTC_FLAG_DOUBLING) ? (size_t)ttc::DBL_SLOTS : 5;
+  return slots * per * (for_rollout ? (size_t)problem->T + 3 : solve_slots);
 }
 
 ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solution_t* solution,
@@ -721,8 +752,20 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   const long long gb = ttc::grid_blocks(problem->d);
   const dim3 grid((unsigned)(problem->n < gb ? problem->n : gb));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const hipError_t e = problem->in_dtype == TTC_F32 ? ttc::launch_solve<float>(a, problem->d, grid, s)
-                                                     : ttc::launch_solve<uint16_t>(a, problem->d, grid, s);
+  hipError_t e;
+  if (problem->flags & TTC_FLAG_DOUBLING) {
+    // Q_T "is Q" when it is absent or the very same array: then P_T = Q = f(0) and the recursion starts at 0
+    ttc::DoublingArgs da;
+    const bool qt_is_q = !problem->QT || (problem->QT == problem->Q && problem->sQT == problem->sQ);
+    da.s = a;
+    da.m = qt_is_q ? problem->T : problem->T - 1;
+    da.p_from_qt = qt_is_q ? 0 : 1;
+    e = problem->in_dtype == TTC_F32 ? ttc::launch_doubling<float>(da, problem->d, grid, s)
+                                     : ttc::launch_doubling<uint16_t>(da, problem->d, grid, s);
+  } else {
+    e = problem->in_dtype == TTC_F32 ? ttc::launch_solve<float>(a, problem->d, grid, s)
+                                     : ttc::launch_solve<uint16_t>(a, problem->d, grid, s);
+  }
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 

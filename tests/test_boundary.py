@@ -61,6 +61,8 @@ def test_argument_validation_without_device(lib):
     assert _solve(lib, _problem(n=-1)) == binding.TTC_ERR_INVALID_ARG
     assert _solve(lib, _problem(in_dtype=7)) == binding.TTC_ERR_INVALID_ARG
     assert _solve(lib, _problem(flags=64)) == binding.TTC_ERR_INVALID_ARG
+    assert _solve(lib, _problem(flags=binding.TTC_FLAG_DOUBLING | binding.TTC_FLAG_PURE_SYMPLECTIC)) \
+        == binding.TTC_ERR_INVALID_ARG
     assert _solve(lib, _problem(A=None)) == binding.TTC_ERR_INVALID_ARG
     assert _solve(lib, _problem(A=0x1004)) == binding.TTC_ERR_INVALID_ARG      # misaligned
     assert _solve(lib, _problem(sQ=255)) == binding.TTC_ERR_INVALID_ARG        # stride not a multiple of 4
@@ -81,6 +83,8 @@ def test_workspace_bytes(lib):
     assert binding.ttc_lqr_workspace_bytes(_problem(d=48, m=48)) == 0
     p.n = 10 ** 9
     assert binding.ttc_lqr_workspace_bytes(p) == w                               # independent of n
+    p.flags = binding.TTC_FLAG_DOUBLING                                          # six matrices per workgroup
+    assert binding.ttc_lqr_workspace_bytes(p) * 5 == w * 6
 
 
 def test_binding_rejects_mixed_dtypes():
