@@ -68,18 +68,24 @@ __device__ __forceinline__ void load_aopT_lds(const float* Mb, float (&a)[Cfg<D>
 }
 
 // e <- e o e in the workspace (gA, gG, gH).  Returns the solve's breakdown flag.
+// Global reads are started one product ahead of their use (issue_half / load_*_global into registers
+// that are only consumed after the next product), so that their latency is covered by matrix work.
 template <int D>
-__device__ __forceinline__ int square_element(float* W, SolveScratch<D>& S, float* gA, float* gG, float* gH, int tid) {
+__device__ __forceinline__ int square_element(float* W, SolveScratch<D>& S, float* gA, float* gG, float* gH, int tid,
+                                              PhaseTimers& tm) {
   using C = Cfg<D>;
+  tid += opaque_zero();  // address arithmetic starts afresh here instead of living in registers from kernel entry
   const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   float* const WL = W;
   float* const WR = W + D;
   floatx4 acc[C::RB][C::NT];
+  HalfRegs<D> hA;
   {
     float rG[C::RB][C::KS];
     load_half<D, float, false>(WR, gH, tid);
     load_aop_global<D, float>(gG, rG, w, i, g);
     __syncthreads();
+    issue_half<D, float>(hA, gA, tid);  // wanted right after the solve
     eye_acc<D>(acc, w, i, g);
     gemm_acc<D>(acc, rG, WR, i, g);  // I + G H
     store_rows<D>(WL, acc, w, i, g);
@@ -87,26 +93,32 @@ __device__ __forceinline__ int square_element(float* W, SolveScratch<D>& S, floa
   }
   set_half_identity<D>(WR, tid);
   __syncthreads();
+  tm.toc(2);
   const int flag = lds_solve<D>(W, S, tid);  // right half: M = (I + G H)^{-1}
+  tm.toc(1);
 
   float rM[C::RB][C::KS], rA[C::RB][C::KS], rAT[C::RB][C::KS];
+  floatx4 init[C::RB][C::NT];
   load_aop_lds<D>(WR, rM, w, i, g);
-  load_half<D, float, false>(WL, gA, tid);
+  commit_half<D, false>(WL, hA, tid);
   __syncthreads();
-  load_half<D, float, false>(WR, gG, tid);  // M is in registers now; G is the right operand of A G below
-  zero_acc<D>(acc);
-  gemm_acc<D>(acc, rM, WL, i, g);  // X1 = M A
-  load_aop_lds<D>(WL, rA, w, i, g);
-  load_aopT_lds<D>(WL, rAT, w, i, g);
-  __syncthreads();
-  store_rows<D>(WL, acc, w, i, g);
-  __syncthreads();
-  zero_acc<D>(acc);
-  gemm_acc<D>(acc, rA, WL, i, g);  // A' = A X1
-  write_rows_global<D>(gA, acc, w, i, g);
   {
+    HalfRegs<D> hG;
     float rH[C::RB][C::KS];
+    issue_half<D, float>(hG, gG, tid);  // G is the right operand of A G below; M is in registers now
     load_aop_global<D, float>(gH, rH, w, i, g);
+    zero_acc<D>(acc);
+    gemm_acc<D>(acc, rM, WL, i, g);  // X1 = M A
+    commit_half<D, false>(WR, hG, tid);
+    load_aop_lds<D>(WL, rA, w, i, g);
+    load_aopT_lds<D>(WL, rAT, w, i, g);
+    __syncthreads();
+    store_rows<D>(WL, acc, w, i, g);
+    __syncthreads();
+    load_rows_global<D>(gH, init, w, i, g);  // for H' two products later
+    zero_acc<D>(acc);
+    gemm_acc<D>(acc, rA, WL, i, g);  // A' = A X1
+    write_rows_global<D>(gA, acc, w, i, g);
     zero_acc<D>(acc);
     gemm_acc<D>(acc, rH, WL, i, g);  // V = H X1
   }
@@ -116,26 +128,27 @@ __device__ __forceinline__ int square_element(float* W, SolveScratch<D>& S, floa
   gemm_acc<D>(acc, rA, WR, i, g);  // A G
   __syncthreads();
   store_rows_T<D>(WR, acc, w, i, g);  // right half: G A^T
-  load_rows_global<D>(gH, acc, w, i, g);
-  gemm_acc<D>(acc, rAT, WL, i, g);  // H' = H + A^T V
-  write_rows_global<D>(gH, acc, w, i, g);
+  gemm_acc<D>(init, rAT, WL, i, g);  // H' = H + A^T V
+  write_rows_global<D>(gH, init, w, i, g);
+  load_rows_global<D>(gG, init, w, i, g);  // for G' one product later
   __syncthreads();
   zero_acc<D>(acc);
   gemm_acc<D>(acc, rM, WR, i, g);  // X2 = M G A^T
   store_rows<D>(WL, acc, w, i, g);  // (every wavefront is past its reads of V)
   __syncthreads();
-  load_rows_global<D>(gG, acc, w, i, g);
-  gemm_acc<D>(acc, rA, WL, i, g);  // G' = G + A X2
-  write_rows_global<D>(gG, acc, w, i, g);
+  gemm_acc<D>(init, rA, WL, i, g);  // G' = G + A X2
+  write_rows_global<D>(gG, init, w, i, g);
   __syncthreads();
+  tm.toc(2);
   return flag;
 }
 
 // gH <- H of e o e only (A and G of the square are not needed after the last squaring when P is still 0)
 template <int D>
 __device__ __forceinline__ int square_element_H(float* W, SolveScratch<D>& S, const float* gA, const float* gG, float* gH,
-                                                int tid) {
+                                                int tid, PhaseTimers& tm) {
   using C = Cfg<D>;
+  tid += opaque_zero();  // address arithmetic starts afresh here instead of living in registers from kernel entry
   const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   float* const WL = W;
   float* const WR = W + D;
@@ -154,7 +167,9 @@ __device__ __forceinline__ int square_element_H(float* W, SolveScratch<D>& S, co
   load_half<D, float, false>(WR, gA, tid);
   __syncthreads();
   load_aopT_lds<D>(WR, rAT, w, i, g);
+  tm.toc(2);
   const int flag = lds_solve<D>(W, S, tid);  // right half: X1 = (I + G H)^{-1} A
+  tm.toc(1);
   {
     float rH[C::RB][C::KS];
     load_aop_global<D, float>(gH, rH, w, i, g);
@@ -167,6 +182,7 @@ __device__ __forceinline__ int square_element_H(float* W, SolveScratch<D>& S, co
   gemm_acc<D>(acc, rAT, WL, i, g);  // H' = H + A^T V
   write_rows_global<D>(gH, acc, w, i, g);
   __syncthreads();
+  tm.toc(2);
   return flag;
 }
 
@@ -174,8 +190,10 @@ __device__ __forceinline__ int square_element_H(float* W, SolveScratch<D>& S, co
 // the wavefront's rows of A^T.
 template <int D, typename TA>
 __device__ __forceinline__ int mobius_solve(float* W, SolveScratch<D>& S, const TA* Asrc, const float* Gsrc,
-                                            const float* Psrc, float (&rAT)[Cfg<D>::RB][Cfg<D>::KS], int tid) {
+                                            const float* Psrc, float (&rAT)[Cfg<D>::RB][Cfg<D>::KS], int tid,
+                                            PhaseTimers& tm) {
   using C = Cfg<D>;
+  tid += opaque_zero();  // address arithmetic starts afresh here instead of living in registers from kernel entry
   const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   float* const WL = W;
   float* const WR = W + D;
@@ -196,7 +214,10 @@ __device__ __forceinline__ int mobius_solve(float* W, SolveScratch<D>& S, const 
     store_rows<D>(WR, accR, w, i, g);
     __syncthreads();
   }
-  return lds_solve<D>(W, S, tid);
+  tm.toc(3);
+  const int flag = lds_solve<D>(W, S, tid);
+  tm.toc(1);
+  return flag;
 }
 
 struct DoublingArgs {
@@ -216,7 +237,6 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
   __shared__ float s_red[C::NW];
   const SolveArgs& p = da.s;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   float* const WL = W;
   float* const WR = W + D;
   float* const ws = p.ws + (long)blockIdx.x * DBL_SLOTS * D * D;
@@ -228,6 +248,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
   float* const gX = ws + DBL_X * D * D;  // rows of R^{-1} B^T in register layout
 
   for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
+    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
     const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
     const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
     const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
@@ -235,6 +256,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
     int info = 0, nsolve = 0;
     floatx4 acc[C::RB][C::NT];
+    PhaseTimers tm;  // phases: 0 set-up, 1 dense solves, 2 squarings, 3 applications and last step, 4 outputs
 
     // ---- set-up: X = R^{-1} B^T, G = B X; the element e = (A, G, Q) goes to the workspace
     load_half<D, TIn, false>(WL, Rp, tid);
@@ -243,7 +265,9 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
     symmetrise_half<D>(WL, tid);
     transpose_half<D>(WR, w, i, g);
     ++nsolve;
+    tm.toc(0);
     if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+    tm.toc(1);
     {
       float c[C::RB][C::KS];
       load_aop_lds<D>(WR, c, w, i, g);
@@ -274,6 +298,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
       __syncthreads();
     }
 
+    tm.toc(0);
     // ---- P_1 by binary powering of the one-step map
     const float* Pcur = gP;
     bool have_p = da.p_from_qt != 0;
@@ -292,18 +317,19 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
         } else {
           float rAT[C::RB][C::KS];
           ++nsolve;
-          if (mobius_solve<D, float>(W, S, gA, gG, gP, rAT, tid) && !info) info = nsolve;
+          if (mobius_solve<D, float>(W, S, gA, gG, gP, rAT, tid, tm) && !info) info = nsolve;
           load_rows_global<D>(gH, acc, w, i, g);
           gemm_acc<D>(acc, rAT, WR, i, g);  // P <- H_e + A_e^T (I + P G_e)^{-1} P A_e
           write_rows_global<D>(gP, acc, w, i, g);
           __syncthreads();
+          tm.toc(3);
         }
       }
       m >>= 1;
       if (m) {
         ++nsolve;
-        const int flag = (m == 1 && !have_p) ? square_element_H<D>(W, S, gA, gG, gH, tid)
-                                             : square_element<D>(W, S, gA, gG, gH, tid);
+        const int flag = (m == 1 && !have_p) ? square_element_H<D>(W, S, gA, gG, gH, tid, tm)
+                                             : square_element<D>(W, S, gA, gG, gH, tid, tm);
         if (flag && !info) info = nsolve;
       }
     }
@@ -312,7 +338,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
     {
       float rAT[C::RB][C::KS];
       ++nsolve;
-      if (mobius_solve<D, TIn>(W, S, Ap, gG0, Pcur, rAT, tid) && !info) info = nsolve;
+      if (mobius_solve<D, TIn>(W, S, Ap, gG0, Pcur, rAT, tid, tm) && !info) info = nsolve;
       zero_acc<D>(acc);
       gemm_acc<D>(acc, rAT, WR, i, g);
       store_rows<D>(WL, acc, w, i, g);
@@ -326,7 +352,10 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
       zero_acc<D>(acc);
       gemm_acc<D>(acc, c, WR, i, g);
     }
+    tm.toc(3);
     emit_outputs<D, TIn>(p, prob, acc, WL, Qp, x0p, info, s_red, tid);
+    tm.toc(4);
+    tm.dump(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * DBL_SLOTS * D * D / 2);
   }
 }
 

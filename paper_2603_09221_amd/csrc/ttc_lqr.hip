@@ -20,6 +20,26 @@ namespace ttc {
 #define TTC_TIMER_DUMP(ptr)
 #endif
 
+// The same aid as an object, for code split over several functions.
+struct PhaseTimers {
+#ifdef TTC_PHASE_TIMERS
+  long long t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  long long t0 = __builtin_amdgcn_s_memtime();
+  __device__ __forceinline__ void toc(int k) {
+    const long long now = __builtin_amdgcn_s_memtime();
+    t[k] += now - t0;
+    t0 = now;
+  }
+  __device__ __forceinline__ void dump(long long* dst) const {
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+      for (int k = 0; k < 8; ++k) dst[k] += t[k];
+  }
+#else
+  __device__ __forceinline__ void toc(int) {}
+  __device__ __forceinline__ void dump(long long*) const {}
+#endif
+};
+
 #define TTC_MAX_GROUPS 64
 
 struct SolveArgs {
@@ -82,32 +102,45 @@ __device__ __forceinline__ int opaque_zero() {
   return z;
 }
 
-// copy a row-major global d x d matrix into one half of the LDS pair (optionally transposed).
-// All of a thread's global reads are issued before the first LDS write, so the memory latency is
-// paid once per matrix and not once per 16 bytes.
-template <int D, typename TIn, bool TRANS>
-__device__ __forceinline__ void load_half(float* Wh, const TIn* M, int tid) {
-  using C = Cfg<D>;
-  constexpr int NV = (D * D / 4 + C::NTHR - 1) / C::NTHR;  // float4 pieces per thread
+// copy a row-major global d x d matrix into one half of the LDS pair (optionally transposed), in two
+// steps so that other work can be placed between them: issue_half starts all of a thread's global
+// reads (the memory latency is paid once per matrix, not once per 16 bytes), commit_half writes LDS.
+template <int D>
+struct HalfRegs {
+  static constexpr int NV = (D * D / 4 + Cfg<D>::NTHR - 1) / Cfg<D>::NTHR;  // float4 pieces per thread
   floatx4 v[NV];
+};
+template <int D, typename TIn>
+__device__ __forceinline__ void issue_half(HalfRegs<D>& h, const TIn* M, int tid) {
+  using C = Cfg<D>;
 #pragma unroll
-  for (int k = 0; k < NV; ++k) {
+  for (int k = 0; k < HalfRegs<D>::NV; ++k) {
     const int idx = tid + k * C::NTHR;
-    if (idx < D * D / 4) v[k] = ld4<TIn>(M, (long)(idx / (D / 4)) * D + (idx % (D / 4)) * 4);
+    if (idx < D * D / 4) h.v[k] = ld4<TIn>(M, (long)(idx / (D / 4)) * D + (idx % (D / 4)) * 4);
   }
+}
+template <int D, bool TRANS>
+__device__ __forceinline__ void commit_half(float* Wh, const HalfRegs<D>& h, int tid) {
+  using C = Cfg<D>;
 #pragma unroll
-  for (int k = 0; k < NV; ++k) {
+  for (int k = 0; k < HalfRegs<D>::NV; ++k) {
     const int idx = tid + k * C::NTHR;
     if (idx < D * D / 4) {
       const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
       if constexpr (TRANS) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) Wh[(c4 + j) * C::PITCH + r] = v[k][j];
+        for (int j = 0; j < 4; ++j) Wh[(c4 + j) * C::PITCH + r] = h.v[k][j];
       } else {
-        *reinterpret_cast<floatx4*>(Wh + r * C::PITCH + c4) = v[k];
+        *reinterpret_cast<floatx4*>(Wh + r * C::PITCH + c4) = h.v[k];
       }
     }
   }
+}
+template <int D, typename TIn, bool TRANS>
+__device__ __forceinline__ void load_half(float* Wh, const TIn* M, int tid) {
+  HalfRegs<D> h;
+  issue_half<D, TIn>(h, M, tid);
+  commit_half<D, TRANS>(Wh, h, tid);
 }
 // replace one half by its symmetric part (caller synchronises before and after).  The matrix is cut
 // into 4 x 4 blocks; a thread takes the block pair (bi, bj), bi <= bj, reads both blocks with 16-byte
