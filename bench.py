@@ -40,6 +40,27 @@ def alg_flops(d, T, groups):
     return (1.0 / 3 + 3 + 2 + 2 + 8 * (T - 1) + 6 + (8.0 / 3) * groups + 2) * d ** 3
 
 
+def alg_flops_doubling(d, T):
+    """Algorithmic flops of one problem on the long-horizon (squaring) path with Q_T = Q: the schedule
+    of ttc_lqr_solve under TTC_FLAG_DOUBLING, counted product by product.
+      setup    R^{-1}B^T factor d^3/3, G = B R^{-1} B^T 3 d^3
+      squaring 8 products + one solve with d right-hand sides (8/3 d^3); the last one, of which only H
+               is needed, 3 products + solve
+      apply    P <- H + A^T (I + P G)^{-1} P A: 3 products + solve (free while P = 0)
+      last     the same with the gain: 4 products + solve
+    """
+    f, m, have_p = 1.0 / 3 + 3, T, False
+    while m:
+        if m & 1:
+            if have_p:
+                f += 6 + 8.0 / 3
+            have_p = True
+        m >>= 1
+        if m:
+            f += (6 if (m == 1 and not have_p) else 16) + 8.0 / 3
+    return (f + 8 + 8.0 / 3) * d ** 3
+
+
 def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):
     """The oracle, as it stands, on the host cores: one problem chunk per thread, BLAS single-threaded."""
     import numpy as np
@@ -78,6 +99,10 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="llm_adapter")
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling"),
+                    help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
+                         "doubling: the long-horizon path, the same product formed by squaring")
+    ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
     ap.add_argument("--rebase-every", type=int, default=0, help="0 = library default")
     ap.add_argument("--cpu-sample", type=int, default=None)
@@ -113,13 +138,32 @@ def main():
         "value": torch.empty((n,), dtype=torch.float32, device=dev),
         "info": torch.empty((n,), dtype=torch.int32, device=dev),
     }
-    prob = binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, 0, k)
-    ws = torch.empty((max(binding.ttc_lqr_workspace_bytes(prob), 16),), dtype=torch.uint8, device=dev)
+    dbl = binding.TTC_FLAG_DOUBLING
+    main_flags = dbl if args.path == "doubling" else 0
+    ws_bytes = max(binding.ttc_lqr_workspace_bytes(
+        binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, f, k)) for f in (0, dbl))
+    ws = torch.empty((max(ws_bytes, 16),), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
-    def step():
-        binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, rebase_every=k,
-                              out=out, workspace=ws, stream=stream)
+    def timed(flags, steps, warmup):
+        """warmup untimed + steps timed launches of the whole workload; (wall s per step, kernel s per launch)"""
+        def step():
+            binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, flags=flags, rebase_every=k,
+                                  out=out, workspace=ws, stream=stream)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for e0, e1 in evs:
+            e0.record(stream)      # HIP events on the stream the kernel is launched on
+            step()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]   # one kernel launch per step
+        assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
+        return wall / steps, sum(kernel_ms) / len(kernel_ms) / 1e3
 
     if args.calib_copy_mib:
         src = torch.ones((args.calib_copy_mib << 18,), dtype=torch.float32, device=dev)
@@ -127,44 +171,36 @@ def main():
         dst.copy_(src)          # reads and writes calib_copy_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for e0, e1 in evs:
-        e0.record(stream)      # HIP events on the stream the kernel is launched on
-        step()
-        e1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]   # one solve_kernel launch per step
-    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
-    ms_per_step = wall / args.steps * 1e3
-    value = n / (wall / args.steps)
-    assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
+    wall_per_step, avg_kernel_s = timed(main_flags, args.steps, args.warmup)
+    ms_per_step = wall_per_step * 1e3
+    value = n / wall_per_step
 
-    flops = alg_flops(d, T, groups) * n
-    achieved = flops / avg_kernel_s / 1e12
+    flops_pp = alg_flops_doubling(d, T) if args.path == "doubling" else alg_flops(d, T, groups)
+    achieved = flops_pp * n / avg_kernel_s / 1e12
     in_bytes = n * (2 * d * d + d * m + m * m + d) * batch.A.element_size()
     out_bytes = n * (d * d + m * d + m + 2) * 4
+    traffic_key = (args.config, groups if args.path == "symplectic" else "doubling")
     res = {
         "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d" % (d, T),
         "value": value, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.config, "problems": n, "d": d, "m": m, "T": T, "input_dtype": cfg["dtype"],
-                   "rebase_every": k or "default", "groups": groups, "outputs": "P0,K0,u0,value"},
+                   "path": args.path, "rebase_every": k or "default", "groups": groups,
+                   "outputs": "P0,K0,u0,value"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[(args.config, groups)] * n
-                                 if (args.config, groups) in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
-                     "kernel": "solve_kernel<%d>" % d, "kernel_ms": avg_kernel_s * 1e3,
-                     "alg_flops_per_problem": alg_flops(d, T, groups),
+                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[traffic_key] * n
+                                 if traffic_key in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
+                     "kernel": ("doubling_kernel<%d>" if args.path == "doubling" else "solve_kernel<%d>") % d,
+                     "kernel_ms": avg_kernel_s * 1e3,
+                     "alg_flops_per_problem": flops_pp,
                      "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / avg_kernel_s / 1e12,
                      "alg_bytes_per_launch": in_bytes + out_bytes,
                      "alg_GBps": (in_bytes + out_bytes) / avg_kernel_s / 1e9},
     }
+    tol = 1e-4 if cfg["dtype"] == "f32" else 2e-2
+    sample, ref = 0, None
     if not args.no_cpu:
         cores_guess = min(16, os.cpu_count() or 1)
         pilot = min(n, cores_guess * 8)
@@ -175,7 +211,19 @@ def main():
         res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": cores, "kind": "oracle",
                                "sample": "first %d problems of the same workload, float64 numpy Riccati, "
                                          "%.1f s wall" % (sample, dt)}
-        res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": 1e-4 if cfg["dtype"] == "f32" else 2e-2}
+        res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": tol}
+    if not args.no_extra:
+        # the other path on the same inputs, for comparison (never the headline value)
+        other = "doubling" if args.path == "symplectic" else "symplectic"
+        o_wall, o_kernel = timed(dbl if other == "doubling" else 0, max(1, min(args.steps, 2)), 1)
+        o_flops = alg_flops_doubling(d, T) if other == "doubling" else alg_flops(d, T, groups)
+        extra = {"path": other, "value": n / o_wall, "unit": "problems/s", "kernel_ms": o_kernel * 1e3,
+                 "alg_flops_per_problem": o_flops, "achieved_TFLOPs": o_flops * n / o_kernel / 1e12,
+                 "frac_of_peak": o_flops * n / o_kernel / 1e12 / PEAK_FP32_MFMA_TFLOPS}
+        if ref is not None:
+            extra["max_rel_err"] = {kk: float(rel_err(out[kk][:sample].cpu().numpy(), ref[kk]).max())
+                                    for kk in ("P0", "K0", "u0", "value")}
+        res["other_path"] = extra
     print(json.dumps(res))
 
 

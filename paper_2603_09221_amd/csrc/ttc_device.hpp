@@ -44,6 +44,15 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// A zero the compiler cannot see through.  Added to a thread index, it makes the address arithmetic
+// derived from it start at that point of the program: otherwise the compiler computes every LDS and
+// global address of the whole kernel once, ahead of the loop over problems, and spills most of them.
+__device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return z;
+}
+
 template <int D>
 struct Cfg {
   static constexpr int RB = TTC_ROW_BLOCKS(D);  // 16-row blocks owned by one wavefront
@@ -514,6 +523,7 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
   using C = Cfg<D>;
   constexpr int NP = D / 16;
   constexpr int NRL = (D + 63) / 64;
+  tid += opaque_zero();
   const int lane = tid & 63, w = tid >> 6;
   bool active[NRL];
 #pragma unroll

@@ -96,11 +96,6 @@ __device__ __forceinline__ void load_aop_ws(const float* wsc, float (&a)[Cfg<D>:
       a[rb][4 * q + 0] = v[0]; a[rb][4 * q + 1] = v[1]; a[rb][4 * q + 2] = v[2]; a[rb][4 * q + 3] = v[3];
     }
 }
-__device__ __forceinline__ int opaque_zero() {
-  int z = 0;
-  asm volatile("" : "+v"(z));
-  return z;
-}
 
 // copy a row-major global d x d matrix into one half of the LDS pair (optionally transposed), in two
 // steps so that other work can be placed between them: issue_half starts all of a thread's global
@@ -297,7 +292,6 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
   __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
   __shared__ float s_red[C::NW];
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   float* const WL = W;      // left half  (Z1 / Y1 / M of a dense solve)
   float* const WR = W + D;  // right half (Z2 / Y2 / RHS)
   // per-workgroup workspace: the row blocks of G, A^{-1}, A^T, Q and X = R^{-1} B^T in register layout
@@ -305,6 +299,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
   const bool pure = (p.flags & TTC_FLAG_PURE_SYMPLECTIC) != 0;
 
   for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
+    // (the opaque zero keeps the address arithmetic of a problem from being hoisted out of this loop and spilled)
+    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
     const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
     const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
     const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
@@ -400,6 +396,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     for (;;) {
       {
         TTC_TOC(2)
+        const int tg = tid + opaque_zero(), lane = tg & 63, w = tg >> 6, i = lane & 15, g = lane >> 4;
         const int gend = p.gend[grp];  // last step of this group
         for (;; ++s) {
           const bool last = (s >= gend);
