@@ -53,6 +53,11 @@ __device__ __forceinline__ int opaque_zero() {
   return z;
 }
 
+__device__ __forceinline__ int opaque_int(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 template <int D>
 struct Cfg {
   static constexpr int RB = TTC_ROW_BLOCKS(D);  // 16-row blocks owned by one wavefront
@@ -169,7 +174,16 @@ __device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
   // software pipeline of depth one: the B operand of k-step ks+1 is read from LDS while the RB*NT
   // matrix-core instructions of k-step ks run (every B value feeds all RB row blocks); scheduling
   // barriers keep the compiler from hoisting more reads than that.
+  // An LDS instruction carries a 16-bit byte offset.  Rows further than that from the lane's base get
+  // a second base register (an opaque offset, so that the compiler does not fold it back into one
+  // base plus 32-bit constants, which costs an address register per read).
+  constexpr int SEG = 65000 / (C::PITCH * 4) - 1;      // rows reachable from one base
+  constexpr int NSEG = (16 * (D / 16 - 1) + 3) / SEG + 1;
   const float* base = Zb + 4 * g * C::PITCH + C::VEC * i;
+  const float* segbase[NSEG];
+  segbase[0] = base;
+#pragma unroll
+  for (int sg = 1; sg < NSEG; ++sg) segbase[sg] = base + opaque_int(sg * SEG * C::PITCH);
   float b[2][C::NH][C::VEC];
 #pragma unroll
   for (int h = 0; h < C::NH; ++h) lds_ldv<C::VEC>(base + 16 * C::VEC * h, b[0][h]);
@@ -177,9 +191,10 @@ __device__ __forceinline__ void gemm_acc(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
     constexpr int ks = decltype(KS_)::value;  // = 4q + t, contraction rows 16q + 4g + t
     constexpr int cur = ks & 1, nxt = cur ^ 1;
     if constexpr (ks + 1 < C::KS) {
-      constexpr int q1 = (ks + 1) / 4, t1 = (ks + 1) % 4;
+      constexpr int r1 = 16 * ((ks + 1) / 4) + (ks + 1) % 4;
 #pragma unroll
-      for (int h = 0; h < C::NH; ++h) lds_ldv<C::VEC>(base + (16 * q1 + t1) * C::PITCH + 16 * C::VEC * h, b[nxt][h]);
+      for (int h = 0; h < C::NH; ++h)
+        lds_ldv<C::VEC>(segbase[r1 / SEG] + (r1 % SEG) * C::PITCH + 16 * C::VEC * h, b[nxt][h]);
       TTC_SCHED_BARRIER();  // reads first: a full k-step of matrix-core work hides their latency
     }
 #pragma unroll
@@ -293,6 +308,31 @@ __device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>:
   TTC_FOR_RB load_aop_lds<D>(Mb, a[rb], Cfg<D>::RB * w + rb, i, g);
 }
 
+// A-operand registers of the wavefront's rows of M^T, M held in LDS: a[4q+t] = M[16q+4g+t][row]
+template <int D>
+__device__ __forceinline__ void load_aopT_lds(const float* Mb, float (&a)[Cfg<D>::RB][Cfg<D>::KS], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int k = 0; k < C::KS; ++k)
+      a[rb][k] = Mb[(16 * (k / 4) + 4 * g + (k % 4)) * C::PITCH + 16 * (C::RB * w + rb) + i];
+}
+
+// the inverse of load_aop_lds: A-operand registers of the wavefront's rows -> row-major matrix in LDS
+template <int D>
+__device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>::RB][Cfg<D>::KS], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int q = 0; q < D / 16; ++q) {
+      floatx4 t;
+      t[0] = a[rb][4 * q + 0]; t[1] = a[rb][4 * q + 1]; t[2] = a[rb][4 * q + 2]; t[3] = a[rb][4 * q + 3];
+      *reinterpret_cast<floatx4*>(Mb + (16 * (C::RB * w + rb) + i) * C::PITCH + 16 * q + 4 * g) = t;
+    }
+}
+
 // ----------------------------------------------------------------------------------------------
 // Dense solve M X = RHS inside LDS: blocked Gauss-Jordan elimination with partial (row) pivoting on
 // the augmented d x 2d array W = [M | RHS] (row r at W + r*PITCH; M = columns [0,d), RHS = [d,2d)),
@@ -327,8 +367,10 @@ struct SolveScratch {
   int flag;
 };
 
-// (a): Gauss-Jordan on the d x 16 panel starting at column cb, by one wavefront
-template <int D>
+// (a): Gauss-Jordan on the d x 16 panel starting at column cb, by one wavefront.  PIVOT = false takes
+// the diagonal element as the pivot of every column (for symmetric positive definite M, whose Schur
+// complements stay positive definite: no search, and a pivot that is not positive is a breakdown).
+template <int D, bool PIVOT = true>
 __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb, int lane,
                                             bool (&active)[(D + 63) / 64], int& bad) {
   using C = Cfg<D>;
@@ -350,20 +392,25 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   float lane_pv = 1.f;  // lane j: its pivot value
   static_for<0, 16>([&](auto J) {
     constexpr int j = decltype(J)::value;
-    // key = |value| with the low 7 mantissa bits replaced by (127 - row): one unsigned max = argmax
-    uint32_t key = 0;
-#pragma unroll
-    for (int rr = 0; rr < NRL; ++rr) {
-      const uint32_t k = (__float_as_uint(a[rr][j]) & 0x7FFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
-      key = (active[rr] && k > key) ? k : key;
-    }
     // every row's reciprocal is formed while the max is being reduced; the pivot row's one is used
     float rinv[NRL];
 #pragma unroll
     for (int rr = 0; rr < NRL; ++rr) rinv[rr] = __builtin_amdgcn_rcpf(a[rr][j]);
-    key = wave_max_u32(key);
-    int pr = 127 - (int)(key & 0x7Fu);
-    pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
+    int pr;
+    if constexpr (PIVOT) {
+      // key = |value| with the low 7 mantissa bits replaced by (127 - row): one unsigned max = argmax
+      uint32_t key = 0;
+#pragma unroll
+      for (int rr = 0; rr < NRL; ++rr) {
+        const uint32_t k = (__float_as_uint(a[rr][j]) & 0x7FFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
+        key = (active[rr] && k > key) ? k : key;
+      }
+      key = wave_max_u32(key);
+      pr = 127 - (int)(key & 0x7Fu);
+      pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
+    } else {
+      pr = cb + j;
+    }
     const int pl = pr & 63;
     const bool ps = (NRL > 1) && (pr >= 64);
     float prow[16];
@@ -397,7 +444,7 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
     }
   });
   if (lane < 16) {
-    const float apv = fabsf(lane_pv);
+    const float apv = PIVOT ? fabsf(lane_pv) : lane_pv;
     S.piv[cb + lane] = lane_piv;
     S.inv[cb + lane] = __builtin_amdgcn_rcpf(lane_pv);
     if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
@@ -518,7 +565,7 @@ __device__ __forceinline__ void solve_tile_range(float* W, SolveScratch<D>& S, i
 }
 
 // PARTS is a development switch (bit 0: panels, bit 1: U12, bit 2: trailing updates); 7 = everything.
-template <int D, int PARTS = 7>
+template <int D, int PARTS = 7, bool PIVOT = true>
 __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) {
   using C = Cfg<D>;
   constexpr int NP = D / 16;
@@ -530,7 +577,7 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
   for (int rr = 0; rr < NRL; ++rr) active[rr] = (lane + 64 * rr) < D;
   int bad = 0;
 
-  if ((PARTS & 1) && w == 0) solve_panel<D>(W, S, 0, lane, active, bad);
+  if ((PARTS & 1) && w == 0) solve_panel<D, PIVOT>(W, S, 0, lane, active, bad);
   for (int p = 0; p < NP; ++p) {
     __syncthreads();  // panel p is in place; every update of panel p-1 is done
     const int cb = 16 * p;
@@ -541,7 +588,7 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
         solve_tile_range<D, PARTS>(W, S, cb, lane, 0, 1);                     // the next panel's columns
         if (C::NW == 1) solve_tile_range<D, PARTS>(W, S, cb, lane, 1, nct);   // nobody else to do the rest
       }
-      if (PARTS & 1) solve_panel<D>(W, S, cb + 16, lane, active, bad);
+      if (PARTS & 1) solve_panel<D, PIVOT>(W, S, cb + 16, lane, active, bad);
     } else if (PARTS & 6) {
       const int workers = more ? C::NW - 1 : C::NW;
       const int wi = more ? w - 1 : w;

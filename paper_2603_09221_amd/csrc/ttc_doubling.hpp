@@ -56,17 +56,6 @@ __device__ __forceinline__ void write_rows_global(float* dst, const floatx4 (&ac
 #pragma unroll
   for (int rb = 0; rb < Cfg<D>::RB; ++rb) write_rows_global<D>(dst, acc[rb], Cfg<D>::RB * w + rb, i, g);
 }
-// A-operand registers of the wavefront's rows of M^T, M held in LDS: a[4q+t] = M[16q+4g+t][row]
-template <int D>
-__device__ __forceinline__ void load_aopT_lds(const float* Mb, float (&a)[Cfg<D>::RB][Cfg<D>::KS], int w, int i, int g) {
-  using C = Cfg<D>;
-#pragma unroll
-  for (int rb = 0; rb < C::RB; ++rb)
-#pragma unroll
-    for (int k = 0; k < C::KS; ++k)
-      a[rb][k] = Mb[(16 * (k / 4) + 4 * g + (k % 4)) * C::PITCH + 16 * (C::RB * w + rb) + i];
-}
-
 // e <- e o e in the workspace (gA, gG, gH).  Returns the solve's breakdown flag.
 // Global reads are started one product ahead of their use (issue_half / load_*_global into registers
 // that are only consumed after the next product), so that their latency is covered by matrix work.
@@ -266,7 +255,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
     transpose_half<D>(WR, w, i, g);
     ++nsolve;
     tm.toc(0);
-    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+    if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;  // R is positive definite: no pivot search
     tm.toc(1);
     {
       float c[C::RB][C::KS];
@@ -353,7 +342,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
       gemm_acc<D>(acc, c, WR, i, g);
     }
     tm.toc(3);
-    emit_outputs<D, TIn>(p, prob, acc, WL, Qp, x0p, info, s_red, tid);
+    emit_gain<D, TIn>(p, prob, acc, x0p, info, tid);
+    emit_value<D, TIn>(p, prob, WL, Qp, x0p, info, s_red, tid);
     tm.toc(4);
     tm.dump(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * DBL_SLOTS * D * D / 2);
   }

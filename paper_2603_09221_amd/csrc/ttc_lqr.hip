@@ -50,7 +50,7 @@ struct SolveArgs {
   long long sA, sB, sQ, sR, sQT, sx0;
   float *P0, *K0, *u0, *value;
   int* info;
-  float* ws;  // gridDim.x slots of 5 d*d floats: constants of the problem in flight, register layout
+  float* ws;  // gridDim.x slots of d*d floats (C_K of the problem in flight, register layout); more for doubling
 };
 
 // A-operand registers of rows [16w,16w+16) of a row-major global matrix: a[4q+t] = M[16w+i][16q+4g+t]
@@ -205,21 +205,17 @@ __device__ __forceinline__ void write_rows_global(float* dst, const floatx4 (&ac
     }
 }
 
-// Outputs of one problem.  On entry acc holds this wavefront's rows of -K_0 and the LDS half WP holds
-// P_0 in the paper's convention (Q_0 = 0).  Writes u_0 = K_0 x0, K_0, P_0 (+ Q with
-// TTC_FLAG_STAGE_COST_AT_X0), value = x0^T P_0 x0 and info; a problem whose info is non-zero gets NaN.
-// Ends with a barrier, so the caller may reuse LDS right away.
+// Outputs of one problem, in two parts.  A problem whose info is non-zero gets NaN.
+// emit_gain: on entry acc holds this wavefront's rows of -K_0; writes u_0 = K_0 x0 and K_0.
 template <int D, typename TIn>
-__device__ __forceinline__ void emit_outputs(const SolveArgs& p, long long prob, floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
-                                             const float* WP, const TIn* Qp, const TIn* x0p, int info, float* s_red,
-                                             int tid) {
+__device__ __forceinline__ void emit_gain(const SolveArgs& p, long long prob, floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT],
+                                          const TIn* x0p, int info, int tid) {
   using C = Cfg<D>;
   const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
   const float nanv = __builtin_nanf("");
   float x0c[C::NT];
 #pragma unroll
   for (int c = 0; c < C::NT; ++c) x0c[c] = ld1<TIn>(x0p, tile_col<D>(c, i));
-  float vpart = 0.f;
 #pragma unroll
   for (int rb = 0; rb < C::RB; ++rb)
 #pragma unroll
@@ -238,6 +234,20 @@ __device__ __forceinline__ void emit_outputs(const SolveArgs& p, long long prob,
 #pragma unroll
     for (int rb = 0; rb < C::RB; ++rb) write_rows_global<D>(p.K0 + prob * (long)D * D, acc[rb], C::RB * w + rb, i, g);
   }
+}
+// emit_value: the LDS half WP holds P_0 in the paper's convention (Q_0 = 0); writes P_0 (+ Q with
+// TTC_FLAG_STAGE_COST_AT_X0), value = x0^T P_0 x0 and info.  Contains two barriers, the second at its end.
+template <int D, typename TIn>
+__device__ __forceinline__ void emit_value(const SolveArgs& p, long long prob, const float* WP, const TIn* Qp,
+                                           const TIn* x0p, int info, float* s_red, int tid) {
+  using C = Cfg<D>;
+  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  const float nanv = __builtin_nanf("");
+  floatx4 acc[C::RB][C::NT];
+  float x0c[C::NT];
+#pragma unroll
+  for (int c = 0; c < C::NT; ++c) x0c[c] = ld1<TIn>(x0p, tile_col<D>(c, i));
+  float vpart = 0.f;
   load_rows<D>(WP, acc, w, i, g);                // rows of P_0
 #pragma unroll
   for (int rb = 0; rb < C::RB; ++rb)
@@ -277,14 +287,16 @@ __device__ __forceinline__ void emit_outputs(const SolveArgs& p, long long prob,
 // Solve kernel.  Persistent workgroups: workgroup b handles problems b, b + gridDim.x, ...
 //
 // Per problem the work is a sequence of phases, each "build [M | RHS] in LDS, dense solve, consume":
-//   phase R  X = R^{-1} B^T, then G = B X (Thm 3.3's G); rows of G go to registers.
-//   phase A  A^{-1}; rows of A^{-1}, A^T, Q and of C_K = X A^{-T}; Z2 = Q_T, Z1 = I.
+//   phase R  X = R^{-1} B^T, then G = B X (Thm 3.3's G).
+//   phase A  A^{-1}; C_K = X A^{-T}; Z2 = Q_T, Z1 = I.
 //   phase S  one group of reverse symplectic steps (Alg. 4 body), the last one leaving the
 //            pair untransposed; the solve re-bases it, [Y1 Y2] <- [I, Y1^{-1} Y2].  Repeated until all
 //            T factors Sigma_T .. Sigma_1 are applied; the last factor has Q_0 = 0, i.e. no "+ Y1 Q".
 //   output   after the last solve the right half is P_0 = Y1^{-1} Y2 itself (Alg. 4), lambda_0 = P_0 x0,
 //            and K_0 = -R^{-1} B^T A^{-T} P_0 = -C_K P_0 (Thm A.4: u_1 = -R^{-1} B^T A^{-T} lambda_0).
-// The constant row blocks stay in registers from the end of the set-up to the end of the problem.
+// The row blocks of G, A^T, Q and A^{-1} go from LDS straight into registers as they are produced and
+// stay there to the end of the problem; only C_K, needed once at the very end, waits in the workspace.
+// Global reads are started a phase ahead of their use where registers allow.
 template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) {
   using C = Cfg<D>;
@@ -294,18 +306,15 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
 
   float* const WL = W;      // left half  (Z1 / Y1 / M of a dense solve)
   float* const WR = W + D;  // right half (Z2 / Y2 / RHS)
-  // per-workgroup workspace: the row blocks of G, A^{-1}, A^T, Q and X = R^{-1} B^T in register layout
-  float* const wsC = p.ws + (long)blockIdx.x * 5 * D * D;
+  // per-workgroup workspace: the row blocks of C_K in register layout
+  float* const wsC = p.ws + (long)blockIdx.x * D * D;
   const bool pure = (p.flags & TTC_FLAG_PURE_SYMPLECTIC) != 0;
 
   for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
     // (the opaque zero keeps the address arithmetic of a problem from being hoisted out of this loop and spilled)
     const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
     const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
-    const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
     const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
-    const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
-    const TIn* QTp = p.QT ? reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT : Qp;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
     TTC_TIMER_DECL
     int info = 0, nsolve = 0;
@@ -313,86 +322,77 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     int s = 1;          // next reverse step (1 .. T; step s applies Sigma_{T-s+1})
     int grp = 0;        // current group of steps
     bool fresh = true;  // Z1 = I, not materialised
+    // the constant row blocks, in registers from here to the end of the problem
+    float cG[C::RB][C::KS], cAi[C::RB][C::KS], cAT[C::RB][C::KS], cQ[C::RB][C::KS];
 
     // ---------------------------------------------------------------- phase R: X = R^{-1} B^T, G = B X
-    load_half<D, TIn, false>(WL, Rp, tid);
-    load_half<D, TIn, false>(WR, Bp, tid);
+    load_half<D, TIn, false>(WL, reinterpret_cast<const TIn*>(p.R) + prob * p.sR, tid);
+    load_half<D, TIn, false>(WR, reinterpret_cast<const TIn*>(p.B) + prob * p.sB, tid);
     __syncthreads();
     symmetrise_half<D>(WL, tid);
     transpose_half<D>(WR, w, i, g);              // RHS = B^T
-    TTC_TOC(0)
-    ++nsolve;
-    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-    TTC_TOC(1)
     {
-      float c[C::RB][C::KS];
-      load_aop_lds<D>(WR, c, w, i, g);             // rows of X, kept for the final gain
-      store_aop_ws<D>(wsC + 4 * D * D, c, tid);
-      load_aop_global<D, TIn>(Bp, c, w, i, g);     // rows of B
+      float cX[C::RB][C::KS];
+      {
+        float cB[C::RB][C::KS];
+        load_aopT_lds<D>(WR, cB, w, i, g);       // rows of B = columns of B^T
+        TTC_TOC(6)
+        ++nsolve;
+        if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;  // R is positive definite: no pivot search
+        TTC_TOC(1)
+        HalfRegs<D> hA, hQ;
+        issue_half<D, TIn>(hA, Ap, tid);         // wanted after the product below
+        issue_half<D, TIn>(hQ, Qp, tid);
+        zero_acc<D>(acc);
+        gemm_acc<D>(acc, cB, WR, i, g);          // rows of G = B X
+        load_aop_lds<D>(WR, cX, w, i, g);        // rows of X, for C_K
+        store_rows<D>(WL, acc, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);             // G is symmetric up to rounding; make it exactly so
+        __syncthreads();
+        load_aop_lds<D>(WL, cG, w, i, g);
+        __syncthreads();
+        TTC_TOC(7)
+        // ------------------------------------------------------------ phase A: A^{-1}, A^T, Q, C_K
+        commit_half<D, false>(WL, hA, tid);
+        commit_half<D, false>(WR, hQ, tid);
+      }
+      __syncthreads();
+      symmetrise_half<D>(WR, tid);
+      load_aopT_lds<D>(WL, cAT, w, i, g);        // rows of A^T = columns of A
+      __syncthreads();
+      load_aop_lds<D>(WR, cQ, w, i, g);          // rows of the symmetric part of Q
+      __syncthreads();
+      set_half_identity<D>(WR, tid);
+      __syncthreads();
+      TTC_TOC(0)
+      ++nsolve;
+      if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+      TTC_TOC(1)
+      load_aop_lds<D>(WR, cAi, w, i, g);
+      __syncthreads();
+      transpose_half<D>(WR, w, i, g);            // A^{-T}
       zero_acc<D>(acc);
-      gemm_acc<D>(acc, c, WR, i, g);               // rows of G = B X
-      store_rows<D>(WL, acc, w, i, g);
-      __syncthreads();
-      symmetrise_half<D>(WL, tid);                 // G is symmetric up to rounding; make it exactly so
-      __syncthreads();
-      load_aop_lds<D>(WL, c, w, i, g);
-      store_aop_ws<D>(wsC + 0 * D * D, c, tid);
-      __syncthreads();
+      gemm_acc<D>(acc, cX, WR, i, g);            // rows of C_K = X A^{-T}
     }
-
-    // ---------------------------------------------------------------- phase A: A^{-1}, A^T, Q, Z2 = Q_T
-    load_half<D, TIn, false>(WL, Ap, tid);
-    load_half<D, TIn, false>(WR, Qp, tid);
+    store_rows<D>(WL, acc, w, i, g);
     __syncthreads();
-    symmetrise_half<D>(WR, tid);
     {
       float c[C::RB][C::KS];
-      // rows of A^T = columns of A, read from the LDS copy of A: c[4q+t] = A[16q+4g+t][row]
-#pragma unroll
-      for (int rb = 0; rb < C::RB; ++rb)
-#pragma unroll
-        for (int k = 0; k < C::KS; ++k)
-          c[rb][k] = WL[(16 * (k / 4) + 4 * g + (k % 4)) * C::PITCH + 16 * (C::RB * w + rb) + i];
-      store_aop_ws<D>(wsC + 2 * D * D, c, tid);
-      __syncthreads();
-      load_aop_lds<D>(WR, c, w, i, g);          // rows of the symmetric part of Q
-      store_aop_ws<D>(wsC + 3 * D * D, c, tid);
-    }
-    __syncthreads();
-    set_half_identity<D>(WR, tid);
-    __syncthreads();
-    TTC_TOC(0)
-    ++nsolve;
-    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
-    TTC_TOC(1)
-    {
-      float c[C::RB][C::KS];
-      load_aop_lds<D>(WR, c, w, i, g);
-      store_aop_ws<D>(wsC + 1 * D * D, c, tid);
-      __syncthreads();
-      transpose_half<D>(WR, w, i, g);              // A^{-T}
-      load_aop_ws<D>(wsC + 4 * D * D, c, tid, opaque_zero());   // rows of X
-      zero_acc<D>(acc);
-      gemm_acc<D>(acc, c, WR, i, g);               // rows of C_K = X A^{-T}
-      store_rows<D>(WL, acc, w, i, g);
-      __syncthreads();
       load_aop_lds<D>(WL, c, w, i, g);
-      store_aop_ws<D>(wsC + 4 * D * D, c, tid);    // X is not needed any more
+      store_aop_ws<D>(wsC, c, tid);
     }
-    __syncthreads();
-    load_half<D, TIn, false>(WR, QTp, tid);    // initial pair [Y1 Y2] = [I Q_T]
-    __syncthreads();
-    symmetrise_half<D>(WR, tid);
+    // initial pair [Y1 Y2] = [I Q_T]
+    if (p.QT) {
+      load_half<D, TIn, false>(WR, reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT, tid);
+      __syncthreads();
+      symmetrise_half<D>(WR, tid);
+    } else {
+      store_aop_lds<D>(WR, cQ, w, i, g);         // Q_T = Q, already symmetric
+    }
     __syncthreads();
 
     // ---------------------------------------------------------------- groups of steps, each ended by a re-base
-    // the constant row blocks, in registers for the rest of the problem (they took a detour through the
-    // workspace because they were produced while the dense solves of the set-up needed the registers)
-    float cG[C::RB][C::KS], cAi[C::RB][C::KS], cAT[C::RB][C::KS], cQ[C::RB][C::KS];
-    load_aop_ws<D>(wsC + 0 * D * D, cG, tid, 0);
-    load_aop_ws<D>(wsC + 1 * D * D, cAi, tid, 0);
-    load_aop_ws<D>(wsC + 2 * D * D, cAT, tid, 0);
-    load_aop_ws<D>(wsC + 3 * D * D, cQ, tid, 0);
     for (;;) {
       {
         TTC_TOC(2)
@@ -447,13 +447,15 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     // ---- outputs: WR holds P_0 (paper convention, Q_0 = 0)
     {
       float c[C::RB][C::KS];
-      load_aop_ws<D>(wsC + 4 * D * D, c, tid, opaque_zero());
+      load_aop_ws<D>(wsC, c, tid, opaque_zero());  // C_K; in flight while P_0 is written out
+      emit_value<D, TIn>(p, prob, WR, Qp, x0p, info, s_red, tid);
       zero_acc<D>(acc);
       gemm_acc<D>(acc, c, WR, i, g);               // -K_0 = C_K P_0
     }
-    emit_outputs<D, TIn>(p, prob, acc, WR, Qp, x0p, info, s_red, tid);
+    emit_gain<D, TIn>(p, prob, acc, x0p, info, tid);
+    __syncthreads();                               // every wavefront is done with the pair
     TTC_TOC(5)
-    TTC_TIMER_DUMP(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * 5 * D * D / 2)
+    TTC_TIMER_DUMP(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * D * D / 2)
   }
 }
 
@@ -524,7 +526,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
     symmetrise_half<D>(WL, tid);
     transpose_half<D>(WR, w, i, g);              // RHS = B^T
     ++nsolve;
-    if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
+    if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;  // R is positive definite: no pivot search
     {
       float c[C::RB][C::KS];
       load_aop_lds<D>(WR, c, w, i, g);
@@ -652,8 +654,52 @@ static int cu_count() {
   return 256;  // MI355X
 }
 // resident workgroups per compute unit the grid is sized for
-static int blocks_per_cu(int d) { return d >= 128 ? 1 : d >= 64 ? 2 : 8; }
-static long long grid_blocks(int d) { return (long long)cu_count() * blocks_per_cu(d); }
+// Persistent grids: as many workgroups as are resident at once, CUs x (workgroups per CU), so that no
+// workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
+// (registers and LDS decide it); the table is the fallback when no device can be asked.
+enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2 };
+static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
+template <int D>
+static int occupancy_of(Kind kind, bool bf16) {
+  int nb = 0;
+  hipError_t e;
+  const int nthr = Cfg<D>::NTHR;
+  if (kind == KIND_SOLVE)
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_kernel<D, uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_kernel<D, float>, nthr, 0);
+  else if (kind == KIND_DOUBLING)
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, doubling_kernel<D, uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, doubling_kernel<D, float>, nthr, 0);
+  else
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_kernel<D, uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_kernel<D, float>, nthr, 0);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  return nb;
+}
+static int blocks_per_cu(Kind kind, int d, bool bf16) {
+  static int cached[3][4][2];  // 0 = not asked yet
+  int& c = cached[kind][dindex(d)][bf16 ? 1 : 0];
+  if (c > 0) return c;
+  int nb = 0;
+  switch (d) {
+    case 16: nb = occupancy_of<16>(kind, bf16); break;
+    case 32: nb = occupancy_of<32>(kind, bf16); break;
+    case 64: nb = occupancy_of<64>(kind, bf16); break;
+    case 128: nb = occupancy_of<128>(kind, bf16); break;
+  }
+  if (nb > 0) {
+    c = nb > 32 ? 32 : nb;
+    return c;
+  }
+  static const int table[3][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}};
+  return table[kind][dindex(d)];
+}
+static long long grid_blocks(Kind kind, int d, bool bf16) {
+  return (long long)cu_count() * blocks_per_cu(kind, d, bf16);
+}
 
 static bool shape_supported(const ttc_lqr_problem_t* q) {
   return q->d == q->m && (q->d == 16 || q->d == 32 || q->d == 64 || q->d == 128);
@@ -722,9 +768,11 @@ extern "C" {
 
 size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t* problem, int for_rollout) {
   if (!problem || problem->T < 1 || !ttc::shape_supported(problem)) return 0;
-  const size_t slots = (size_t)ttc::grid_blocks(problem->d);
+  const ttc::Kind kind = for_rollout ? ttc::KIND_ROLLOUT
+                         : (problem->flags & TTC_FLAG_DOUBLING) ? ttc::KIND_DOUBLING : ttc::KIND_SOLVE;
+  const size_t slots = (size_t)ttc::grid_blocks(kind, problem->d, problem->in_dtype == TTC_BF16);
   const size_t per = (size_t)problem->d * problem->m * sizeof(float);
-  const size_t solve_slots = (problem->flags & TTC_FLAG_DOUBLING) ? (size_t)ttc::DBL_SLOTS : 5;
+  const size_t solve_slots = (problem->flags & TTC_FLAG_DOUBLING) ? (size_t)ttc::DBL_SLOTS : 1;
   return slots * per * (for_rollout ? (size_t)problem->T + 3 : solve_slots);
 }
 
@@ -779,7 +827,8 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   a.P0 = solution->P0; a.K0 = solution->K0; a.u0 = solution->u0; a.value = solution->value;
   a.info = solution->info;
   a.ws = static_cast<float*>(workspace);
-  const long long gb = ttc::grid_blocks(problem->d);
+  const long long gb = ttc::grid_blocks((problem->flags & TTC_FLAG_DOUBLING) ? ttc::KIND_DOUBLING : ttc::KIND_SOLVE,
+                                        problem->d, problem->in_dtype == TTC_BF16);
   const dim3 grid((unsigned)(problem->n < gb ? problem->n : gb));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
@@ -817,7 +866,7 @@ ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t* problem, float* U, float* 
   a.sx0 = problem->sx0;
   a.U = U; a.X = X; a.cost = cost; a.info = info;
   a.ws = static_cast<float*>(workspace);
-  const long long gb = ttc::grid_blocks(problem->d);
+  const long long gb = ttc::grid_blocks(ttc::KIND_ROLLOUT, problem->d, problem->in_dtype == TTC_BF16);
   const dim3 grid((unsigned)(problem->n < gb ? problem->n : gb));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const hipError_t e = problem->in_dtype == TTC_F32 ? ttc::launch_rollout<float>(a, problem->d, grid, s)
