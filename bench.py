@@ -206,7 +206,7 @@ def main():
         cores_guess = min(16, os.cpu_count() or 1)
         pilot = min(n, cores_guess * 8)
         _, pilot_dt, _ = cpu_baseline(batch, pilot)             # calibrate: aim at ~15 s of wall-clock
-        sample = args.cpu_sample or int(min(n, max(pilot, pilot * 15.0 / max(pilot_dt, 1e-3))))
+        sample = min(n, args.cpu_sample or int(max(pilot, pilot * 15.0 / max(pilot_dt, 1e-3))))
         ref, dt, cores = cpu_baseline(batch, sample)
         errs = {kk: float(rel_err(out[kk][:sample].cpu().numpy(), ref[kk]).max()) for kk in ("P0", "K0", "u0", "value")}
         res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": cores, "kind": "oracle",

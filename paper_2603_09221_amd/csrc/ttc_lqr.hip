@@ -40,11 +40,12 @@ struct PhaseTimers {
 #endif
 };
 
-#define TTC_MAX_GROUPS 64
+#define TTC_MAX_GROUPS 64  // explicit group lengths (development override) only; the default schedule has no limit
 
 struct SolveArgs {
   long long n;
   int T, flags, ngroups;  // the T factors are applied in ngroups groups, one dense solve each
+  int explicit_groups;       // 0: group g ends at step T - floor((ngroups-1-g) T / ngroups); 1: at gend[g]
   int gend[TTC_MAX_GROUPS];  // gend[g] = last step (1-based) of group g; gend[ngroups-1] = T
   const void *A, *B, *Q, *R, *QT, *x0;
   long long sA, sB, sQ, sR, sQT, sx0;
@@ -397,7 +398,9 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
       {
         TTC_TOC(2)
         const int tg = tid + opaque_zero(), lane = tg & 63, w = tg >> 6, i = lane & 15, g = lane >> 4;
-        const int gend = p.gend[grp];  // last step of this group
+        // last step of this group: lengths differ by at most one, the longer groups first
+        const int gend = p.explicit_groups ? p.gend[grp]
+                                           : p.T - (int)(((long long)(p.ngroups - 1 - grp) * p.T) / p.ngroups);
         for (;; ++s) {
           const bool last = (s >= gend);
           if (fresh) eye_acc<D>(acc, w, i, g); else load_rows<D>(WL, acc, w, i, g);
@@ -805,9 +808,8 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
     else g = ((long)problem->T * 10 + 33) / 34;
     if (g < 1) g = 1;
     if (g > problem->T) g = problem->T;
-    if (g > TTC_MAX_GROUPS) g = TTC_MAX_GROUPS;   // very long horizons: longer groups, fewer solves
     a.ngroups = (int)g;
-    for (long k = 0; k < g; ++k) a.gend[k] = problem->T - (int)(((g - 1 - k) * problem->T) / g);
+    a.explicit_groups = 0;
 #ifdef TTC_PHASE_TIMERS
     if (const char* e = getenv("TTC_GROUP_LENGTHS")) {   // development: explicit lengths "5,4,4,3"
       int cnt = 0, end = 0;
@@ -817,7 +819,10 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
         while (*c && *c != ',') ++c;
         if (*c == ',') ++c;
       }
-      if (end == problem->T) a.ngroups = cnt;
+      if (end == problem->T) {
+        a.ngroups = cnt;
+        a.explicit_groups = 1;
+      }
     }
 #endif
   }

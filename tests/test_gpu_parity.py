@@ -82,6 +82,13 @@ def test_long_horizon_config3_sample():
     check(b, TOL_F32)
 
 
+def test_very_long_horizon_keeps_short_groups():
+    """Hundreds of factors: the number of groups grows with T (no cap), so every group stays short."""
+    check(synth.make_batch(40, 16, 16, 300, seed=12, device=DEV), TOL_F32)
+    c = synth.CONFIGS["long_horizon"]
+    check(synth.make_batch(12, c["d"], c["m"], 250, seed=13, device=DEV, rho=c["rho"]), TOL_F32)
+
+
 def test_needs_pivoting():
     """A close to a cyclic shift: its LU has zero leading pivots, so the dense solves must pivot."""
     d, n = 32, 12
