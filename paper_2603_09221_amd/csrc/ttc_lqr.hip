@@ -464,6 +464,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
 
 }  // namespace ttc
 #include "ttc_doubling.hpp"
+#include "ttc_small.hpp"
 namespace ttc {
 
 // ------------------------------------------------------------------------------------------------
@@ -667,7 +668,10 @@ static int occupancy_of(Kind kind, bool bf16) {
   int nb = 0;
   hipError_t e;
   const int nthr = Cfg<D>::NTHR;
-  if (kind == KIND_SOLVE)
+  if (kind == KIND_SOLVE && D == 16)  // the four-problems-per-wavefront kernel
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
+  else if (kind == KIND_SOLVE)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_kernel<D, uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_kernel<D, float>, nthr, 0);
   else if (kind == KIND_DOUBLING)
@@ -732,7 +736,7 @@ static ttc_status_t validate(const ttc_lqr_problem_t* q) {
 template <typename TIn>
 static hipError_t launch_solve(const SolveArgs& a, int d, dim3 grid, hipStream_t st) {
   switch (d) {
-    case 16: hipLaunchKernelGGL((solve_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 16: hipLaunchKernelGGL((solve_small_kernel<TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
     case 32: hipLaunchKernelGGL((solve_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
     case 64: hipLaunchKernelGGL((solve_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
     case 128: hipLaunchKernelGGL((solve_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
@@ -832,9 +836,12 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   a.P0 = solution->P0; a.K0 = solution->K0; a.u0 = solution->u0; a.value = solution->value;
   a.info = solution->info;
   a.ws = static_cast<float*>(workspace);
-  const long long gb = ttc::grid_blocks((problem->flags & TTC_FLAG_DOUBLING) ? ttc::KIND_DOUBLING : ttc::KIND_SOLVE,
-                                        problem->d, problem->in_dtype == TTC_BF16);
-  const dim3 grid((unsigned)(problem->n < gb ? problem->n : gb));
+  const bool doubling = (problem->flags & TTC_FLAG_DOUBLING) != 0;
+  const long long gb = ttc::grid_blocks(doubling ? ttc::KIND_DOUBLING : ttc::KIND_SOLVE, problem->d,
+                                        problem->in_dtype == TTC_BF16);
+  // work items of the persistent grid: problems, or quads of problems in the d = 16 kernel
+  const long long items = (problem->d == 16 && !doubling) ? (problem->n + 3) / 4 : problem->n;
+  const dim3 grid((unsigned)(items < gb ? items : gb));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
   if (problem->flags & TTC_FLAG_DOUBLING) {
