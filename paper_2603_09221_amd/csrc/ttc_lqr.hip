@@ -661,14 +661,14 @@ static int cu_count() {
 // Persistent grids: as many workgroups as are resident at once, CUs x (workgroups per CU), so that no
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
 // (registers and LDS decide it); the table is the fallback when no device can be asked.
-enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2 };
+enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3 };
 static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
 template <int D>
 static int occupancy_of(Kind kind, bool bf16) {
   int nb = 0;
   hipError_t e;
   const int nthr = Cfg<D>::NTHR;
-  if (kind == KIND_SOLVE && D == 16)  // the four-problems-per-wavefront kernel
+  if (kind == KIND_SOLVE_QUAD)  // the four-problems-per-wavefront kernel (d = 16 only)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
   else if (kind == KIND_SOLVE)
@@ -687,7 +687,7 @@ static int occupancy_of(Kind kind, bool bf16) {
   return nb;
 }
 static int blocks_per_cu(Kind kind, int d, bool bf16) {
-  static int cached[3][4][2];  // 0 = not asked yet
+  static int cached[4][4][2];  // 0 = not asked yet
   int& c = cached[kind][dindex(d)][bf16 ? 1 : 0];
   if (c > 0) return c;
   int nb = 0;
@@ -701,11 +701,16 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
     c = nb > 32 ? 32 : nb;
     return c;
   }
-  static const int table[3][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}};
+  static const int table[4][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}};
   return table[kind][dindex(d)];
 }
 static long long grid_blocks(Kind kind, int d, bool bf16) {
   return (long long)cu_count() * blocks_per_cu(kind, d, bf16);
+}
+// d = 16, default path: batches that fill the chip go four problems to a wavefront (more throughput);
+// small batches keep one problem per wavefront (more wavefronts in flight, lower latency).
+static bool use_quad_kernel(const ttc_lqr_problem_t* q) {
+  return q->d == 16 && !(q->flags & TTC_FLAG_DOUBLING) && q->n >= 8LL * cu_count();
 }
 
 static bool shape_supported(const ttc_lqr_problem_t* q) {
@@ -736,7 +741,7 @@ static ttc_status_t validate(const ttc_lqr_problem_t* q) {
 template <typename TIn>
 static hipError_t launch_solve(const SolveArgs& a, int d, dim3 grid, hipStream_t st) {
   switch (d) {
-    case 16: hipLaunchKernelGGL((solve_small_kernel<TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 16: hipLaunchKernelGGL((solve_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
     case 32: hipLaunchKernelGGL((solve_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
     case 64: hipLaunchKernelGGL((solve_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
     case 128: hipLaunchKernelGGL((solve_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
@@ -777,6 +782,7 @@ size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t* problem, int for_rollout
   if (!problem || problem->T < 1 || !ttc::shape_supported(problem)) return 0;
   const ttc::Kind kind = for_rollout ? ttc::KIND_ROLLOUT
                          : (problem->flags & TTC_FLAG_DOUBLING) ? ttc::KIND_DOUBLING : ttc::KIND_SOLVE;
+  // (the four-problems-per-wavefront kernel of d = 16 runs fewer workgroups and needs no workspace)
   const size_t slots = (size_t)ttc::grid_blocks(kind, problem->d, problem->in_dtype == TTC_BF16);
   const size_t per = (size_t)problem->d * problem->m * sizeof(float);
   const size_t solve_slots = (problem->flags & TTC_FLAG_DOUBLING) ? (size_t)ttc::DBL_SLOTS : 1;
@@ -837,10 +843,11 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   a.info = solution->info;
   a.ws = static_cast<float*>(workspace);
   const bool doubling = (problem->flags & TTC_FLAG_DOUBLING) != 0;
-  const long long gb = ttc::grid_blocks(doubling ? ttc::KIND_DOUBLING : ttc::KIND_SOLVE, problem->d,
-                                        problem->in_dtype == TTC_BF16);
-  // work items of the persistent grid: problems, or quads of problems in the d = 16 kernel
-  const long long items = (problem->d == 16 && !doubling) ? (problem->n + 3) / 4 : problem->n;
+  const bool quad = ttc::use_quad_kernel(problem);
+  const long long gb = ttc::grid_blocks(doubling ? ttc::KIND_DOUBLING : quad ? ttc::KIND_SOLVE_QUAD : ttc::KIND_SOLVE,
+                                        problem->d, problem->in_dtype == TTC_BF16);
+  // work items of the persistent grid: problems, or quads of problems
+  const long long items = quad ? (problem->n + 3) / 4 : problem->n;
   const dim3 grid((unsigned)(items < gb ? items : gb));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
@@ -853,6 +860,10 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
     da.p_from_qt = qt_is_q ? 0 : 1;
     e = problem->in_dtype == TTC_F32 ? ttc::launch_doubling<float>(da, problem->d, grid, s)
                                      : ttc::launch_doubling<uint16_t>(da, problem->d, grid, s);
+  } else if (quad) {
+    if (problem->in_dtype == TTC_F32) hipLaunchKernelGGL((ttc::solve_small_kernel<float>), grid, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL((ttc::solve_small_kernel<uint16_t>), grid, dim3(64), 0, s, a);
+    e = hipGetLastError();
   } else {
     e = problem->in_dtype == TTC_F32 ? ttc::launch_solve<float>(a, problem->d, grid, s)
                                      : ttc::launch_solve<uint16_t>(a, problem->d, grid, s);

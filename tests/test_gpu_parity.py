@@ -82,6 +82,28 @@ def test_long_horizon_config3_sample():
     check(b, TOL_F32)
 
 
+def test_d16_large_batches_four_problems_per_wavefront():
+    """From 8 x CUs problems on, d = 16 runs four problems per wavefront: ragged last quad, a given Q_T, the
+    stage-cost flag, bfloat16 inputs, a horizon of one, and a breakdown that must stay with its own problem."""
+    n = 2048 + 37
+    b = synth.make_batch(n, 16, 16, 8, seed=21, device=DEV)
+    check(b, TOL_F32)
+    QT = (1.5 * b.Q + 0.2 * torch.eye(16, device=DEV)).contiguous()
+    check(b, TOL_F32, QT=QT, flag=True)
+    check(b, TOL_F32, rebase_every=2)
+    check(synth.make_batch(n, 16, 16, 1, seed=22, device=DEV), TOL_F32)
+    check(synth.make_batch(n + 1, 16, 16, 12, seed=23, device=DEV, dtype="bf16"), TOL_BF16)
+    A = b.A.clone()
+    A[1001] = 0.0
+    out = run(synth.LqrBatch(A, b.B, b.Q, b.R, b.x0, b.T))
+    info = out["info"].cpu().numpy()
+    assert info[1001] == 2 and (np.delete(info, 1001) == 0).all()
+    assert torch.isnan(out["u0"][1001]).all()
+    keep = torch.tensor([1000, 1002, 1003, 2084], device=DEV)      # its quad neighbours and the ragged tail
+    ref = oracle_solve(b.take(keep))
+    assert rel_err(out["u0"][keep].cpu().numpy(), ref["u0"]).max() <= TOL_F32
+
+
 def test_very_long_horizon_keeps_short_groups():
     """Hundreds of factors: the number of groups grows with T (no cap), so every group stays short."""
     check(synth.make_batch(40, 16, 16, 300, seed=12, device=DEV), TOL_F32)
