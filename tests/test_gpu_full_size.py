@@ -12,10 +12,10 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def full_size_check(name, n, tol, sample=192, chunk=1 << 15):
+def full_size_check(name, n, tol, sample=192, chunk=1 << 15, flags=0):
     cfg = synth.CONFIGS[name]
     batch = synth.make_batch(n, cfg["d"], cfg["m"], cfg["T"], seed=0, device=DEV, dtype=cfg["dtype"], rho=cfg["rho"])
-    out = binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, batch.T)
+    out = binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, batch.T, flags=flags)
     torch.cuda.synchronize()
     assert int(out["info"].abs().max()) == 0
     # properties on every problem, evaluated on the device in chunks
@@ -51,6 +51,23 @@ def test_config3_long_horizon_slice():
 def test_config4_mixed_precision_slice():
     # the full workload does not fit next to its outputs (172 GB in, 138 GB out): one (batch, head) slice
     full_size_check("mixed_precision", 8192 * 4, 2e-2, sample=96)
+
+
+def test_config0_shape_at_a_batch_that_fills_the_chip():
+    # config 0 itself (256 problems) is covered element by element in test_gpu_parity; this is its shape at the
+    # size where d = 16 switches to four problems per wavefront
+    full_size_check("tiny", 1 << 17, 1e-4, sample=2048)
+
+
+def test_long_horizon_path_configs_1_3_4():
+    dbl = binding.TTC_FLAG_DOUBLING
+    full_size_check("small_head", synth.config_problems("small_head"), 1e-4, flags=dbl)
+    full_size_check("long_horizon", 8192, 1e-4, sample=128, flags=dbl)
+    full_size_check("mixed_precision", 8192 * 2, 2e-2, sample=64, flags=dbl)
+
+
+def test_long_horizon_path_config2_slice():
+    full_size_check("llm_adapter", 8192 * 4, 1e-4, sample=128, flags=binding.TTC_FLAG_DOUBLING)
 
 
 def test_config2_llm_adapter_full():
