@@ -346,8 +346,10 @@ __device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>
 //       not -- gets its multiplier and is updated.  It leaves in W[:, P] the multiplier matrix Lm
 //       (for the j-th pivot row of the panel: zero up to column j, the later "Jordan" multipliers
 //       after it) and in S.L11 the unit-lower multipliers among the 16 pivot rows.
-//   (b) one lane per remaining column: gather the 16 pivot-row entries, forward-substitute with
-//       L11 -> U12; U12 goes back into the pivot rows and, negated and transposed, into S.UbT.
+//   (b) U12 = Lf^{-1} P for the 16 pivot rows P of the remaining columns, Lf the unit-lower factor among
+//       the pivot rows (S.L11): every wavefront inverts Lf once per panel (one lane per column, a
+//       forward substitution on the identity) and then forms U12 tile by tile on the matrix cores;
+//       U12 goes back into the pivot rows and, negated, stays in registers as an operand of (c).
 //   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows, in 16 x 16 tiles; the product is
 //       formed transposed (MFMA M index = column, N index = row) so that a lane's four accumulator
 //       values, and its four operand values of either side, are 16 contiguous bytes of LDS.
@@ -359,8 +361,7 @@ __device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>
 // visible on entry (caller synchronised); the result is visible to every thread on return.
 template <int D>
 struct SolveScratch {
-  static constexpr int UP = 20;     // floats per column of UbT (16 + 4: bank skew, keeps 16-byte alignment)
-  float UbT[2 * D * UP];            // -U12 transposed: column c of the pair at UbT + c*UP
+  float LinvT[Cfg<D>::NW][16 * 16];  // per wavefront: its copy of the inverse of the panel's unit-lower factor, by columns
   float L11[2][16 * 16];            // double-buffered: panel p+1 is factored while p's is still read
   float inv[D];
   int piv[D];
@@ -476,48 +477,76 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
 // (b) + (c) for the nt <= NTC consecutive column tiles ct0 .. ct0+nt-1 of the rest of panel cb (column
 // tile t covers columns [cb+16+16t, +16)), by one wavefront: lane 16u + i first forms column i of a
 // tile of U12 (four tiles per pass), then the wavefront updates its tiles for every row tile.
-template <int D, int NTC, int PARTS = 7>
-__device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb, int lane, int ct0, int nt) {
-  using C = Cfg<D>;
-  using SS = SolveScratch<D>;
-  const int i = lane & 15, g = lane >> 4;
+// Inverse of the panel's unit-lower factor Lf (rows of multipliers in S.L11), as the matrix-core A
+// operand of U12 = Lf^{-1} P: the lane (i, g) gets Linv[i][4g .. 4g+3].  Lane c computes column c
+// (forward substitution on e_c); the columns pass through this wavefront's own LDS buffer to be read
+// back by rows.  Every wavefront does this for itself, once per panel.
+template <int D>
+__device__ __forceinline__ floatx4 panel_linv(SolveScratch<D>& S, int cb, int lane, int w) {
   const float* L11 = S.L11[(cb >> 4) & 1];
-  // ---- (b)
-  if (PARTS & 2) {
+  float* buf = S.LinvT[w];
+  const int c = lane & 15, g = lane >> 4;
+  float x[16];
+  static_for<0, 16>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    float sacc = (j == c) ? 1.f : 0.f;
+    static_for<0, (j + 3) / 4>([&](auto Q) {
+      constexpr int q = decltype(Q)::value;
+      const floatx4 l = *reinterpret_cast<const floatx4*>(L11 + j * 16 + 4 * q);
+      static_for<0, 4>([&](auto E) {
+        constexpr int e = decltype(E)::value;
+        if constexpr (4 * q + e < j) sacc -= l[e] * x[4 * q + e];
+      });
+    });
+    x[j] = sacc;
+  });
+  if (g == 0) {
 #pragma unroll
-    for (int pass = 0; pass < (NTC + 3) / 4; ++pass) {
-      if (4 * pass + g < nt) {
-        const int c = cb + 16 + 16 * (ct0 + 4 * pass + g) + i;
-        float u_[16];
-        int pv[16];
-        static_for<0, 16>([&](auto J) {
-          constexpr int j = decltype(J)::value;
-          pv[j] = S.piv[cb + j];
-          u_[j] = W[pv[j] * C::PITCH + c];
-        });
-        static_for<1, 16>([&](auto J) {
-          constexpr int j = decltype(J)::value;
-          static_for<0, (j + 3) / 4>([&](auto Q) {
-            constexpr int q = decltype(Q)::value;
-            const floatx4 l = *reinterpret_cast<const floatx4*>(L11 + j * 16 + 4 * q);
-            static_for<0, 4>([&](auto E) {
-              constexpr int e = decltype(E)::value;
-              if constexpr (4 * q + e < j) u_[j] -= l[e] * u_[4 * q + e];
-            });
-          });
-        });
-        static_for<0, 4>([&](auto Q) {
-          constexpr int q = decltype(Q)::value;
-          floatx4 t;
-          t[0] = -u_[4 * q + 0]; t[1] = -u_[4 * q + 1]; t[2] = -u_[4 * q + 2]; t[3] = -u_[4 * q + 3];
-          *reinterpret_cast<floatx4*>(S.UbT + c * SS::UP + 4 * q) = t;
-        });
-        static_for<0, 16>([&](auto J) {
-          constexpr int j = decltype(J)::value;
-          W[pv[j] * C::PITCH + c] = u_[j];
-        });
-      }
+    for (int q = 0; q < 4; ++q) {
+      floatx4 t;
+      t[0] = x[4 * q + 0]; t[1] = x[4 * q + 1]; t[2] = x[4 * q + 2]; t[3] = x[4 * q + 3];
+      *reinterpret_cast<floatx4*>(buf + c * 16 + 4 * q) = t;  // column c of Linv
     }
+  }
+  floatx4 la;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) la[t] = buf[(4 * g + t) * 16 + c];  // Linv[c][4g + t]
+  return la;
+}
+
+// (b) + (c) for the nt <= NTC consecutive column tiles ct0 .. ct0+nt-1 of the rest of panel cb (column
+// tile t covers columns [cb+16+16t, +16)), by one wavefront; la is panel_linv's operand.
+template <int D, int NTC, int PARTS = 7>
+__device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb, int lane, int ct0, int nt, floatx4 la) {
+  using C = Cfg<D>;
+  const int i = lane & 15, g = lane >> 4;
+  floatx4 av[NTC];
+#pragma unroll
+  for (int u = 0; u < NTC; ++u) av[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+  // ---- (b): MFMA k-step t contracts the pivot indices { 4g + t }: lane (i, g) supplies Linv[i][4g+t] and
+  // P[4g+t][column i of the tile]; its four results are U12[4g .. 4g+3][column i].
+  if (PARTS & 2) {
+    int pv[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) pv[t] = S.piv[cb + 4 * g + t] * C::PITCH + cb + 16 + 16 * ct0 + i;
+    float pb[NTC][4];
+#pragma unroll
+    for (int u = 0; u < NTC; ++u)
+      if (u < nt)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) pb[u][t] = W[pv[t] + 16 * u];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int u = 0; u < NTC; ++u)
+        if (u < nt) av[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(la[t], pb[u][t], av[u], 0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < NTC; ++u)
+      if (u < nt) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) W[pv[t] + 16 * u] = av[u][t];
+        av[u] = -av[u];
+      }
   }
   if (!(PARTS & 4)) return;
   // ---- (c): MFMA k-step kk contracts the panel columns { 4g + kk }: lane (i, g) supplies, as A
@@ -526,10 +555,7 @@ __device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb
   // of one row tile do not feed the reads of the next, so a fused loop would serialise on LDS latency.
   float* const rowp = W + i * C::PITCH + cb;
   const int c0 = 16 + 16 * ct0 + 4 * g;
-  floatx4 av[NTC], bl[C::NRT], acc[C::NRT][NTC];
-#pragma unroll
-  for (int u = 0; u < NTC; ++u)
-    if (u < nt) av[u] = *reinterpret_cast<const floatx4*>(S.UbT + (cb + 16 + 16 * (ct0 + u) + i) * SS::UP + 4 * g);
+  floatx4 bl[C::NRT], acc[C::NRT][NTC];
 #pragma unroll
   for (int rt = 0; rt < C::NRT; ++rt) {
     bl[rt] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 4 * g);
@@ -553,14 +579,15 @@ __device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb
 
 // the consecutive column tiles lo .. hi-1 of the rest of panel cb, at most NTC per call
 template <int D, int PARTS = 7>
-__device__ __forceinline__ void solve_tile_range(float* W, SolveScratch<D>& S, int cb, int lane, int lo, int hi) {
+__device__ __forceinline__ void solve_tile_range(float* W, SolveScratch<D>& S, int cb, int lane, int lo, int hi,
+                                                 floatx4 la) {
   constexpr int NTC = TTC_SOLVE_NTC;
   for (int t0 = lo; t0 < hi; t0 += NTC) {
     const int nt = hi - t0 < NTC ? hi - t0 : NTC;
-    if (nt == 1) solve_tiles<D, 1, PARTS>(W, S, cb, lane, t0, 1);
-    else if (nt <= 2) solve_tiles<D, 2, PARTS>(W, S, cb, lane, t0, nt);
-    else if (nt <= 4 || NTC <= 4) solve_tiles<D, (NTC < 4 ? NTC : 4), PARTS>(W, S, cb, lane, t0, nt);
-    else solve_tiles<D, NTC, PARTS>(W, S, cb, lane, t0, nt);
+    if (nt == 1) solve_tiles<D, 1, PARTS>(W, S, cb, lane, t0, 1, la);
+    else if (nt <= 2) solve_tiles<D, 2, PARTS>(W, S, cb, lane, t0, nt, la);
+    else if (nt <= 4 || NTC <= 4) solve_tiles<D, (NTC < 4 ? NTC : 4), PARTS>(W, S, cb, lane, t0, nt, la);
+    else solve_tiles<D, NTC, PARTS>(W, S, cb, lane, t0, nt, la);
   }
 }
 
@@ -583,17 +610,19 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
     const int cb = 16 * p;
     const int nct = (2 * D - cb - 16) / 16;  // column tiles to the right of the panel
     const bool more = (p + 1 < NP);
+    floatx4 la = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (PARTS & 2) la = panel_linv<D>(S, cb, lane, w);
     if (more && w == 0) {
       if (PARTS & 6) {
-        solve_tile_range<D, PARTS>(W, S, cb, lane, 0, 1);                     // the next panel's columns
-        if (C::NW == 1) solve_tile_range<D, PARTS>(W, S, cb, lane, 1, nct);   // nobody else to do the rest
+        solve_tile_range<D, PARTS>(W, S, cb, lane, 0, 1, la);                     // the next panel's columns
+        if (C::NW == 1) solve_tile_range<D, PARTS>(W, S, cb, lane, 1, nct, la);   // nobody else to do the rest
       }
       if (PARTS & 1) solve_panel<D, PIVOT>(W, S, cb + 16, lane, active, bad);
     } else if (PARTS & 6) {
       const int workers = more ? C::NW - 1 : C::NW;
       const int wi = more ? w - 1 : w;
       const int first = more ? 1 : 0, ntile = nct - first;   // a contiguous share of the column tiles each
-      solve_tile_range<D, PARTS>(W, S, cb, lane, first + (wi * ntile) / workers, first + ((wi + 1) * ntile) / workers);
+      solve_tile_range<D, PARTS>(W, S, cb, lane, first + (wi * ntile) / workers, first + ((wi + 1) * ntile) / workers, la);
     }
   }
   if (tid == 0) S.flag = bad;
