@@ -23,8 +23,8 @@ PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 f
 # HBM-side bytes per problem of solve_kernel<128, float> at the llm_adapter workload with the default
 # grouping, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy kernel
 # (profiles/*_d128_T16_llm_adapter_n65536.md): (read + written) KiB / 65536 problems.
-MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (37.00e6 + 26.05e6) * 1024 / 65536,
-                                      ("llm_adapter", "doubling"): (110.3e6 + 75.8e6) * 1024 / 65536}
+MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (38.64e6 + 27.51e6) * 1024 / 65536,
+                                      ("llm_adapter", "doubling"): (112.3e6 + 76.1e6) * 1024 / 65536}
 def default_groups(T, dtype):
     """The library default: number of groups the T factors are split into (one dense solve each)."""
     return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
