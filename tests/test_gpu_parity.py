@@ -70,6 +70,28 @@ def test_shared_matrices_stride_zero():
         assert v <= TOL_F32, (k, v)
 
 
+def _padded(t, pad):
+    """The same values with `pad` unused elements between consecutive problems."""
+    n = t.shape[0]
+    inner = t[0].numel()
+    buf = torch.full((n, inner + pad), float("nan"), dtype=t.dtype, device=t.device)
+    buf[:, :inner] = t.reshape(n, inner)
+    return buf[:, :inner].view(t.shape)
+
+
+@pytest.mark.parametrize("d,T,n,flags", [(32, 6, 45, 0), (16, 8, 2100, 0), (64, 9, 30, binding.TTC_FLAG_DOUBLING),
+                                         (128, 5, 7, 0)])
+def test_padded_problem_strides(d, T, n, flags):
+    """Problem-to-problem strides larger than the matrix (and different per argument); the gaps hold NaN."""
+    b = synth.make_batch(n, d, d, T, seed=31, device=DEV)
+    p = synth.LqrBatch(_padded(b.A, 8), _padded(b.B, 4), _padded(b.Q, 12), _padded(b.R, 8), _padded(b.x0, 3), b.T)
+    assert p.A.stride(0) == d * d + 8 and p.x0.stride(0) == d + 3
+    out = run(p, flags=flags)
+    assert int(out["info"].abs().max()) == 0
+    for k, v in solve_errors(out, oracle_solve(b)).items():
+        assert v <= TOL_F32, (k, v)
+
+
 def test_bf16_inputs():
     for d, T, n in [(16, 8, 64), (64, 8, 64), (128, 32, 24)]:
         b = synth.make_batch(n, d, d, T, seed=8, device=DEV, dtype="bf16")
