@@ -114,6 +114,7 @@ def test_d16_large_batches_four_problems_per_wavefront():
     check(b, TOL_F32, QT=QT, flag=True)
     check(b, TOL_F32, rebase_every=2)
     check(synth.make_batch(n, 16, 16, 1, seed=22, device=DEV), TOL_F32)
+    check(synth.make_batch(n, 16, 16, 4, seed=5, device=DEV), 2e-3, flags=binding.TTC_FLAG_PURE_SYMPLECTIC)
     check(synth.make_batch(n + 1, 16, 16, 12, seed=23, device=DEV, dtype="bf16"), TOL_BF16)
     A = b.A.clone()
     A[1001] = 0.0
