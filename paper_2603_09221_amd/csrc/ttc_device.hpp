@@ -344,13 +344,15 @@ __device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>
 //       unblocked Gauss-Jordan on it: pivot = max |.| over rows never used as a pivot (one DPP max
 //       of a packed key), pivot row broadcast with v_readlane, every other row -- pivoted earlier or
 //       not -- gets its multiplier and is updated.  It leaves in W[:, P] the multiplier matrix Lm
-//       (for the j-th pivot row of the panel: zero up to column j, the later "Jordan" multipliers
-//       after it) and in S.L11 the unit-lower multipliers among the 16 pivot rows.
+//       (for the j-th pivot row of the panel: its multipliers against the earlier pivot rows of the
+//       panel, zero in column j, the later "Jordan" multipliers after it) and in S.L11 a copy of
+//       the unit-lower multipliers among the 16 pivot rows.
 //   (b) U12 = Lf^{-1} P for the 16 pivot rows P of the remaining columns, Lf the unit-lower factor among
 //       the pivot rows (S.L11): every wavefront inverts Lf once per panel (one lane per column, a
 //       forward substitution on the identity) and then forms U12 tile by tile on the matrix cores;
-//       U12 goes back into the pivot rows and, negated, stays in registers as an operand of (c).
-//   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows, in 16 x 16 tiles; the product is
+//       negated, it stays in registers as an operand of (c).
+//   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows, in 16 x 16 tiles (a pivot row holds
+//       P_j = U12_j + sum_{k<j} L_jk U12_k, so the same update serves it); the product is
 //       formed transposed (MFMA M index = column, N index = row) so that a lane's four accumulator
 //       values, and its four operand values of either side, are 16 contiguous bytes of LDS.
 // Schedule: (b) and (c) are done column tile by column tile, so a wavefront needs no one else's
@@ -460,8 +462,8 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
       if (j0 >= 0) {
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
-          if (jj < j0) L11[j0 * 16 + jj] = a[rr][jj];
-          if (jj <= j0) a[rr][jj] = 0.f;
+          if (jj < j0) L11[j0 * 16 + jj] = a[rr][jj];  // (kept in the row as well: see (c))
+          if (jj == j0) a[rr][jj] = 0.f;
         }
       }
 #pragma unroll
@@ -541,12 +543,7 @@ __device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb
       for (int u = 0; u < NTC; ++u)
         if (u < nt) av[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(la[t], pb[u][t], av[u], 0, 0, 0);
 #pragma unroll
-    for (int u = 0; u < NTC; ++u)
-      if (u < nt) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) W[pv[t] + 16 * u] = av[u][t];
-        av[u] = -av[u];
-      }
+    for (int u = 0; u < NTC; ++u) av[u] = -av[u];
   }
   if (!(PARTS & 4)) return;
   // ---- (c): MFMA k-step kk contracts the panel columns { 4g + kk }: lane (i, g) supplies, as A
