@@ -476,9 +476,6 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   }
 }
 
-// (b) + (c) for the nt <= NTC consecutive column tiles ct0 .. ct0+nt-1 of the rest of panel cb (column
-// tile t covers columns [cb+16+16t, +16)), by one wavefront: lane 16u + i first forms column i of a
-// tile of U12 (four tiles per pass), then the wavefront updates its tiles for every row tile.
 // Inverse of the panel's unit-lower factor Lf (rows of multipliers in S.L11), as the matrix-core A
 // operand of U12 = Lf^{-1} P: the lane (i, g) gets Linv[i][4g .. 4g+3].  Lane c computes column c
 // (forward substitution on e_c); the columns pass through this wavefront's own LDS buffer to be read
