@@ -26,6 +26,9 @@ named after the textbook convention used by the library boundary:
 All functions accept either one problem (A: (d,d), x0: (d,)) or a stack of problems
 (A: (n,d,d), x0: (n,d)); everything is evaluated in float64.
 
+Time-heterogeneous problems (the general statement of Prop. 3.1, with A_t, B_t, Q_t, R_t varying over
+the horizon) have their own entry points, riccati_solve_tv / riccati_rollout_tv, below.
+
 Pins (tests/test_oracle_pins.py): scalar closed form (Fibonacci ratios), T=1 closed form,
 decoupled diagonal problems, brute-force stacked KKT system (Thm A.6's matrix form) and
 condensed QP on tiny instances, value == rolled-out cost, DARE fixed point as T grows,
@@ -128,6 +131,71 @@ def riccati_rollout(A, B, Q, R, QT, x0, T, stage_cost_at_x0=False):
         u = (K[t] @ x[..., None])[..., 0]
         x = (A @ x[..., None])[..., 0] + (B @ u[..., None])[..., 0]
         cost = cost + quad(u, Rs) + quad(x, QTs if t == T - 1 else Qs)
+        U.append(u)
+        X.append(x)
+    return np.stack(U, axis=-2), np.stack(X, axis=-2), cost
+
+
+# ------------------------------------------------------------------------------------------------
+# Time-heterogeneous parameters: the statement of Prop. 3.1 as printed, with A_t, B_t, Q_t, R_t.
+#
+# Arrays carry a step axis of length T in front of the matrix axes.  Step s = 0..T-1 is the paper's
+# t = s+1:   x_{s+1} = A[s] x_s + B[s] u_s,   cost  sum_s ( u_s^T R[s] u_s + x_{s+1}^T Q[s] x_{s+1} ),
+# i.e. Q[s] = Q_{s+1} is charged on the state the step arrives at, Q[T-1] = Q_T is the terminal cost,
+# and nothing is charged on x_0 (the paper's Q_0 = 0).
+
+
+def riccati_value_matrices_tv(A, B, Q, R):
+    """P[0..T] and K[0..T-1] for (..., T, d, d)-shaped A, Q, (..., T, d, m) B and (..., T, m, m) R.
+
+    P[T] = Q[T-1];  for s = T-1..0 with Pn = P[s+1]:
+        S = R[s] + B[s]^T Pn B[s],  K[s] = -S^{-1} B[s]^T Pn A[s]                       (Eq. "decode")
+        P[s] = Qprev + A[s]^T Pn A[s] - (B[s]^T Pn A[s])^T S^{-1} (B[s]^T Pn A[s])      (Eq. "riccati")
+    where Qprev = Q[s-1] is the cost on x_s (zero for s = 0).
+    """
+    A, B, Q, R = _f64(A), _f64(B), _sym(_f64(Q)), _sym(_f64(R))
+    T = A.shape[-3]
+    if T < 1 or B.shape[-3] != T or Q.shape[-3] != T or R.shape[-3] != T:
+        raise ValueError("A, B, Q, R must share a step axis of length T >= 1")
+    P = [None] * (T + 1)
+    K = [None] * T
+    P[T] = Q[..., T - 1, :, :]
+    for s in range(T - 1, -1, -1):
+        As, Bs, Rs, Pn = A[..., s, :, :], B[..., s, :, :], R[..., s, :, :], P[s + 1]
+        BtP = _t(Bs) @ Pn
+        S = Rs + BtP @ Bs
+        F = BtP @ As
+        W = _chol_solve(S, F)
+        K[s] = -W
+        Ps = _t(As) @ Pn @ As - _t(F) @ W
+        if s >= 1:
+            Ps = Ps + Q[..., s - 1, :, :]
+        P[s] = _sym(Ps)
+    return P, K
+
+
+def riccati_solve_tv(A, B, Q, R, x0):
+    """P0, K0, u0 = K0 x0 and value = x0^T P0 x0 of the time-heterogeneous problem."""
+    x0 = _f64(x0)
+    P, K = riccati_value_matrices_tv(A, B, Q, R)
+    u0 = (K[0] @ x0[..., None])[..., 0]
+    value = np.einsum("...i,...ij,...j->...", x0, P[0], x0)
+    return {"P0": P[0], "K0": K[0], "u0": u0, "value": value, "P": P, "K": K}
+
+
+def riccati_rollout_tv(A, B, Q, R, x0):
+    """Closed-loop roll-out: U (..., T, m), X (..., T+1, d) and the accumulated cost."""
+    A, B, Qs, Rs = _f64(A), _f64(B), _sym(_f64(Q)), _sym(_f64(R))
+    T = A.shape[-3]
+    x = _f64(x0)
+    _, K = riccati_value_matrices_tv(A, B, Q, R)
+    quad = lambda v, M: np.einsum("...i,...ij,...j->...", v, M, v)
+    cost = np.zeros(x.shape[:-1])
+    X, U = [x], []
+    for s in range(T):
+        u = (K[s] @ x[..., None])[..., 0]
+        x = (A[..., s, :, :] @ x[..., None])[..., 0] + (B[..., s, :, :] @ u[..., None])[..., 0]
+        cost = cost + quad(u, Rs[..., s, :, :]) + quad(x, Qs[..., s, :, :])
         U.append(u)
         X.append(x)
     return np.stack(U, axis=-2), np.stack(X, axis=-2), cost
