@@ -116,6 +116,39 @@ ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t *problem, float *U, float *
                              int32_t *info, void *workspace, size_t workspace_bytes,
                              void *hip_stream);
 
+/* Time-heterogeneous problem: Eq. "ttc" as the paper states it in general, with A_t, B_t, Q_t, R_t
+ * varying over the horizon (Sec. 4 "time-heterogeneous parameterization"; Prop. 3.1 is written for
+ * this case).  Step s = 0..T-1 is the paper's t = s+1:
+ *     x_{s+1} = A[s] x_s + B[s] u_s,    cost  sum_s ( u_s^T R[s] u_s + x_{s+1}^T Q[s] x_{s+1} ),
+ * so Q[s] is charged on the state the step arrives at, Q[T-1] is the terminal cost Q_T and x_0 carries
+ * no cost.  Matrix s of problem p of A starts at A + p*sA + s*tA elements (likewise B, Q, R); a step
+ * stride of 0 shares one matrix between all steps, a problem stride of 0 between all problems.
+ * Same conventions as ttc_lqr_problem_t otherwise (device pointers, row-major, alignment, d = m in
+ * {16, 32, 64, 128}, Q and R read as their symmetric parts, R positive definite); A need not be
+ * invertible.  flags must be 0. */
+typedef struct {
+  int64_t n;
+  int32_t d, m, T;
+  int32_t in_dtype;  /* ttc_dtype_t */
+  int32_t flags;     /* 0 */
+  const void *A;     /* (n, T, d, d) */
+  const void *B;     /* (n, T, d, m) */
+  const void *Q;     /* (n, T, d, d) */
+  const void *R;     /* (n, T, m, m) */
+  const void *x0;    /* (n, d)       */
+  int64_t sA, sB, sQ, sR, sx0; /* elements between consecutive problems */
+  int64_t tA, tB, tQ, tR;      /* elements between consecutive steps of one problem */
+} ttc_lqr_tv_problem_t;
+
+/* P0, K0, u0, value, info of n time-heterogeneous problems (same solution struct and error behaviour
+ * as ttc_lqr_solve).  One backward Riccati step per factor, each in the Moebius form of the symplectic
+ * factor Sigma_t of Thm 3.3 (a re-base after every factor, which needs no A_t^{-1}):
+ *     G_s = B_s R_s^{-1} B_s^T,  M_s = (I + P_{s+1} G_s)^{-1} P_{s+1} A_s,  P_s = Q[s-1] + A_s^T M_s,
+ * and K_0 = -R_0^{-1} B_0^T M_0.  info: dense solve 2s+1 (R_s^{-1} B_s^T) or 2s+2 (the Moebius solve)
+ * counted from the last step backwards.  No workspace is needed: `workspace` may be NULL. */
+ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t *problem, const ttc_lqr_solution_t *solution,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *ttc_status_string(ttc_status_t status);
 

@@ -20,7 +20,8 @@ TTC_FLAG_STAGE_COST_AT_X0 = 1
 TTC_FLAG_PURE_SYMPLECTIC = 2
 TTC_FLAG_DOUBLING = 4
 
-EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_status_string", "ttc_version")
+EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_status_string",
+           "ttc_version")
 
 
 class Problem(ctypes.Structure):
@@ -30,6 +31,14 @@ class Problem(ctypes.Structure):
                 ("x0", c_void_p),
                 ("sA", c_int64), ("sB", c_int64), ("sQ", c_int64), ("sR", c_int64), ("sQT", c_int64),
                 ("sx0", c_int64)]
+
+
+class TvProblem(ctypes.Structure):
+    _fields_ = [("n", c_int64), ("d", c_int32), ("m", c_int32), ("T", c_int32), ("in_dtype", c_int32),
+                ("flags", c_int32),
+                ("A", c_void_p), ("B", c_void_p), ("Q", c_void_p), ("R", c_void_p), ("x0", c_void_p),
+                ("sA", c_int64), ("sB", c_int64), ("sQ", c_int64), ("sR", c_int64), ("sx0", c_int64),
+                ("tA", c_int64), ("tB", c_int64), ("tQ", c_int64), ("tR", c_int64)]
 
 
 class Solution(ctypes.Structure):
@@ -60,6 +69,8 @@ def load():
     lib.ttc_lqr_rollout.restype = c_int
     lib.ttc_lqr_rollout.argtypes = [ctypes.POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                     c_size_t, c_void_p]
+    lib.ttc_lqr_solve_tv.restype = c_int
+    lib.ttc_lqr_solve_tv.argtypes = [ctypes.POINTER(TvProblem), ctypes.POINTER(Solution), c_void_p, c_size_t, c_void_p]
     lib.ttc_status_string.restype = c_char_p
     lib.ttc_status_string.argtypes = [c_int]
     lib.ttc_version.restype = c_int
@@ -169,3 +180,49 @@ def ttc_lqr_rollout(A, B, Q, R, QT, x0, T, *, flags=0, rebase_every=0, workspace
                                c_void_p(cost.data_ptr()), c_void_p(info.data_ptr()),
                                c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
     return {"U": U, "X": X, "cost": cost, "info": info}
+
+
+def _tv_strides(t):
+    """(problem stride, step stride) in elements of a (n, T, r, c) tensor whose matrices are contiguous row-major."""
+    if t.dim() != 4 or (t.shape[3] != 1 and t.stride(3) != 1) or (t.shape[2] != 1 and t.stride(2) != t.shape[3]):
+        raise ValueError("expected (n, T, rows, cols) with contiguous row-major matrices")
+    return t.stride(0), t.stride(1)
+
+
+def make_tv_problem(A, B, Q, R, x0) -> TvProblem:
+    """Descriptor of a time-heterogeneous problem from A (n,T,d,d), B (n,T,d,m), Q (n,T,d,d), R (n,T,m,m), x0 (n,d);
+    an axis expanded with stride 0 is passed through as shared."""
+    dt = A.dtype
+    for t in (B, Q, R, x0):
+        if t.dtype != dt:
+            raise ValueError("all inputs must share one dtype")
+    in_dtype = {torch.float32: TTC_F32, torch.bfloat16: TTC_BF16}.get(dt)
+    if in_dtype is None:
+        raise ValueError("inputs must be float32 or bfloat16")
+    p = TvProblem()
+    p.n, p.T, p.d, p.m = A.shape[0], A.shape[1], A.shape[2], B.shape[3]
+    p.in_dtype, p.flags = in_dtype, 0
+    p.A, p.B, p.Q, p.R, p.x0 = _ptr(A), _ptr(B), _ptr(Q), _ptr(R), _ptr(x0)
+    (p.sA, p.tA), (p.sB, p.tB), (p.sQ, p.tQ), (p.sR, p.tR) = (_tv_strides(t) for t in (A, B, Q, R))
+    p.sx0 = _stride(x0)
+    return p
+
+
+def ttc_lqr_solve_tv(A, B, Q, R, x0, *, want_P0=True, want_K0=True, out=None, stream=None):
+    """P0, K0, u0, value, info of n time-heterogeneous problems: A (n,T,d,d), B (n,T,d,m), R (n,T,m,m) and
+    Q (n,T,d,d) with Q[:, s] the cost on the state step s arrives at (Q[:, T-1] is the terminal cost)."""
+    lib = load()
+    prob = make_tv_problem(A, B, Q, R, x0)
+    n, d, m, dev = prob.n, prob.d, prob.m, A.device
+    out = dict(out or {})
+    f32 = dict(dtype=torch.float32, device=dev)
+    if want_P0 and "P0" not in out:
+        out["P0"] = torch.empty((n, d, d), **f32)
+    if want_K0 and "K0" not in out:
+        out["K0"] = torch.empty((n, m, d), **f32)
+    out.setdefault("u0", torch.empty((n, m), **f32))
+    out.setdefault("value", torch.empty((n,), **f32))
+    out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
+    sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
+    _check(lib.ttc_lqr_solve_tv(ctypes.byref(prob), ctypes.byref(sol), None, 0, _stream_ptr(stream)))
+    return out

@@ -465,6 +465,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
 }  // namespace ttc
 #include "ttc_doubling.hpp"
 #include "ttc_small.hpp"
+#include "ttc_tv.hpp"
 namespace ttc {
 
 // ------------------------------------------------------------------------------------------------
@@ -661,7 +662,7 @@ static int cu_count() {
 // Persistent grids: as many workgroups as are resident at once, CUs x (workgroups per CU), so that no
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
 // (registers and LDS decide it); the table is the fallback when no device can be asked.
-enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3 };
+enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4 };
 static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
 template <int D>
 static int occupancy_of(Kind kind, bool bf16) {
@@ -671,6 +672,9 @@ static int occupancy_of(Kind kind, bool bf16) {
   if (kind == KIND_SOLVE_QUAD)  // the four-problems-per-wavefront kernel (d = 16 only)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
+  else if (kind == KIND_SOLVE_TV)
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_kernel<D, uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_kernel<D, float>, nthr, 0);
   else if (kind == KIND_SOLVE)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_kernel<D, uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_kernel<D, float>, nthr, 0);
@@ -687,7 +691,7 @@ static int occupancy_of(Kind kind, bool bf16) {
   return nb;
 }
 static int blocks_per_cu(Kind kind, int d, bool bf16) {
-  static int cached[4][4][2];  // 0 = not asked yet
+  static int cached[5][4][2];  // 0 = not asked yet
   int& c = cached[kind][dindex(d)][bf16 ? 1 : 0];
   if (c > 0) return c;
   int nb = 0;
@@ -701,7 +705,7 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
     c = nb > 32 ? 32 : nb;
     return c;
   }
-  static const int table[4][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}};
+  static const int table[5][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}, {12, 4, 2, 1}};
   return table[kind][dindex(d)];
 }
 static long long grid_blocks(Kind kind, int d, bool bf16) {
@@ -757,6 +761,18 @@ static hipError_t launch_doubling(const DoublingArgs& a, int d, dim3 grid, hipSt
     case 32: hipLaunchKernelGGL((doubling_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
     case 64: hipLaunchKernelGGL((doubling_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
     case 128: hipLaunchKernelGGL((doubling_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <typename TIn>
+static hipError_t launch_tv(const TvArgs& a, int d, dim3 grid, hipStream_t st) {
+  switch (d) {
+    case 16: hipLaunchKernelGGL((solve_tv_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((solve_tv_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((solve_tv_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((solve_tv_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -894,6 +910,46 @@ ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t* problem, float* U, float* 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const hipError_t e = problem->in_dtype == TTC_F32 ? ttc::launch_rollout<float>(a, problem->d, grid, s)
                                                      : ttc::launch_rollout<uint16_t>(a, problem->d, grid, s);
+  return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+}
+
+ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solution_t* solution, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  if (!q) return TTC_ERR_INVALID_ARG;
+  if (q->n < 0 || q->T < 1 || q->d < 1 || q->m < 1 || q->flags != 0) return TTC_ERR_INVALID_ARG;
+  if (q->in_dtype != TTC_F32 && q->in_dtype != TTC_BF16) return TTC_ERR_INVALID_ARG;
+  if (!(q->d == q->m && (q->d == 16 || q->d == 32 || q->d == 64 || q->d == 128))) return TTC_ERR_UNSUPPORTED;
+  if (!solution) return TTC_ERR_INVALID_ARG;
+  if (q->n == 0) return TTC_OK;
+  if (!q->A || !q->B || !q->Q || !q->R || !q->x0 || !solution->u0) return TTC_ERR_INVALID_ARG;
+  const size_t al = q->in_dtype == TTC_F32 ? 16 : 8;
+  const void* ptrs[] = {q->A, q->B, q->Q, q->R};
+  const int64_t strides[] = {q->sA, q->sB, q->sQ, q->sR, q->tA, q->tB, q->tQ, q->tR};
+  for (int k = 0; k < 4; ++k)
+    if (!ttc::aligned_ptr(ptrs[k], al)) return TTC_ERR_INVALID_ARG;
+  for (int k = 0; k < 8; ++k)
+    if (strides[k] < 0 || strides[k] % 4) return TTC_ERR_INVALID_ARG;
+  if (q->sx0 < 0) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
+  ttc::TvArgs a;
+  a.s.n = q->n;
+  a.s.T = q->T;
+  a.s.flags = 0;
+  a.s.ngroups = q->T;
+  a.s.explicit_groups = 0;
+  a.s.A = q->A; a.s.B = q->B; a.s.Q = q->Q; a.s.R = q->R; a.s.QT = nullptr; a.s.x0 = q->x0;
+  a.s.sA = q->sA; a.s.sB = q->sB; a.s.sQ = q->sQ; a.s.sR = q->sR; a.s.sQT = 0; a.s.sx0 = q->sx0;
+  a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
+  a.s.info = solution->info;
+  a.s.ws = nullptr;
+  a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const long long gb = ttc::grid_blocks(ttc::KIND_SOLVE_TV, q->d, bf16);
+  const dim3 grid((unsigned)(q->n < gb ? q->n : gb));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = bf16 ? ttc::launch_tv<uint16_t>(a, q->d, grid, st) : ttc::launch_tv<float>(a, q->d, grid, st);
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 

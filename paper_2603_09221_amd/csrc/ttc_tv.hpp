@@ -1,0 +1,120 @@
+// Time-heterogeneous problems: A_t, B_t, Q_t, R_t vary over the horizon (the general statement of
+// Prop. 3.1; the paper's "time-heterogeneous parameterization", Sec. 4).
+// Included by ttc_lqr.hip after the helpers it shares with the other kernels.
+//
+// With every factor Sigma_t of Thm 3.3 different, nothing can be prepared once per problem, and each
+// factor would need its own A_t^{-1}.  The kernel therefore re-bases after every factor, which turns a
+// factor into one backward Riccati step in Moebius form and needs no A_t^{-1}:
+//     X_s = R_s^{-1} B_s^T,  G_s = B_s X_s,
+//     M_s = (I + P_{s+1} G_s)^{-1} P_{s+1} A_s,   P_s = Q[s-1] + A_s^T M_s   (P_T = Q[T-1], no Q on x_0),
+//     K_0 = -X_0 M_0                                                         (Eq. "decode").
+// Two dense solves and four products per step; the value matrix stays on chip for the whole horizon
+// (in LDS as the right operand of the products, in registers while the pair serves the R_s solve),
+// the step's matrices are streamed from HBM once each.
+#pragma once
+
+namespace ttc {
+
+struct TvArgs {
+  SolveArgs s;                 // n, T, A, B, Q, R, x0 and their problem strides, outputs (QT, ws, groups unused)
+  long long tA, tB, tQ, tR;    // elements between consecutive steps
+};
+
+template <int D, typename TIn>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta) {
+  using C = Cfg<D>;
+  __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
+  __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
+  __shared__ float s_red[C::NW];
+  const SolveArgs& p = ta.s;
+  float* const WL = W;
+  float* const WR = W + D;
+
+  for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
+    const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
+    const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
+    const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
+    const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
+    const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
+    int info = 0, nsolve = 0;
+    float cX[C::RB][C::KS];  // rows of X_0, for the gain
+
+    {
+      const int tid = threadIdx.x + opaque_zero();
+      load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
+      __syncthreads();
+      symmetrise_half<D>(WR, tid);
+      __syncthreads();
+    }
+    for (int s = p.T - 1; s >= 0; --s) {
+      // (address arithmetic local to the step: see opaque_zero)
+      const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+      floatx4 acc[C::RB][C::NT];
+      float cG[C::RB][C::KS], cAT[C::RB][C::KS];
+      {
+        floatx4 preg[C::RB][C::NT];
+        load_rows<D>(WR, preg, w, i, g);  // P_{s+1} waits in registers while the pair serves the R_s solve
+        __syncthreads();
+        load_half<D, TIn, false>(WL, Rp + (long long)s * ta.tR, tid);
+        load_half<D, TIn, true>(WR, Bp + (long long)s * ta.tB, tid);  // RHS = B_s^T
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);
+        float cB[C::RB][C::KS];
+        load_aopT_lds<D>(WR, cB, w, i, g);  // rows of B_s = columns of B_s^T
+        __syncthreads();
+        ++nsolve;
+        if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;  // R_s is positive definite: no pivot search
+        zero_acc<D>(acc);
+        gemm_acc<D>(acc, cB, WR, i, g);  // rows of G_s = B_s X_s
+        if (s == 0) load_aop_lds<D>(WR, cX, w, i, g);
+        store_rows<D>(WL, acc, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);
+        __syncthreads();
+        load_aop_lds<D>(WL, cG, w, i, g);
+        __syncthreads();
+        store_rows<D>(WR, preg, w, i, g);  // P_{s+1} back as the right operand
+      }
+      load_half<D, TIn, false>(WL, Ap + (long long)s * ta.tA, tid);
+      __syncthreads();
+      load_aopT_lds<D>(WL, cAT, w, i, g);  // rows of A_s^T
+      __syncthreads();
+      eye_acc<D>(acc, w, i, g);
+      gemm_acc<D>(acc, cG, WR, i, g);      // I + G_s P = (I + P G_s)^T
+      store_rows_T<D>(WL, acc, w, i, g);
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, cAT, WR, i, g);     // A_s^T P = (P A_s)^T
+      __syncthreads();
+      store_rows_T<D>(WR, acc, w, i, g);
+      __syncthreads();
+      ++nsolve;
+      if (lds_solve<D>(W, S, tid) && !info) info = nsolve;  // right half: M_s
+      if (s >= 1) {
+        load_half<D, TIn, false>(WL, Qp + (long long)(s - 1) * ta.tQ, tid);  // the cost on x_s
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);
+        __syncthreads();
+        load_rows<D>(WL, acc, w, i, g);
+        gemm_acc<D>(acc, cAT, WR, i, g);   // P_s = Q[s-1] + A_s^T M_s
+        __syncthreads();
+        store_rows<D>(WR, acc, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WR, tid);
+        __syncthreads();
+      } else {
+        zero_acc<D>(acc);
+        gemm_acc<D>(acc, cAT, WR, i, g);   // P_0 = A_0^T M_0
+        store_rows<D>(WL, acc, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);
+        __syncthreads();
+        zero_acc<D>(acc);
+        gemm_acc<D>(acc, cX, WR, i, g);    // -K_0 = X_0 M_0
+        emit_gain<D, TIn>(p, prob, acc, x0p, info, tid);
+        emit_value<D, TIn>(p, prob, WL, Qp, x0p, info, s_red, tid);
+      }
+    }
+  }
+}
+
+}  // namespace ttc

@@ -111,3 +111,33 @@ def make_config(name: str, n: int | None = None, seed: int = 0, device="cpu") ->
     total = config_problems(name)
     return make_batch(total if n is None else n, c["d"], c["m"], c["T"], seed=seed, device=device,
                       dtype=c["dtype"], rho=c["rho"])
+
+
+@dataclass
+class LqrTvBatch:
+    """Time-heterogeneous problems: A (n,T,d,d), B (n,T,d,m), Q (n,T,d,d), R (n,T,m,m), x0 (n,d).  Q[:, s] is the
+    cost on the state that step s arrives at; Q[:, T-1] is the terminal cost."""
+    A: torch.Tensor
+    B: torch.Tensor
+    Q: torch.Tensor
+    R: torch.Tensor
+    x0: torch.Tensor
+
+    @property
+    def T(self):
+        return self.A.shape[1]
+
+    def take(self, idx):
+        return LqrTvBatch(self.A[idx], self.B[idx], self.Q[idx], self.R[idx], self.x0[idx])
+
+    def numpy64(self):
+        f = lambda t: t.detach().to("cpu").to(torch.float64).numpy()
+        return f(self.A), f(self.B), f(self.Q), f(self.R), f(self.x0)
+
+
+def make_tv_batch(n: int, d: int, m: int, T: int, seed: int = 0, device="cpu", dtype: str = "f32") -> LqrTvBatch:
+    """n problems whose T steps each carry their own (A, B, Q, R): the recipe of make_batch, drawn
+    independently for every (problem, step); x0 from the first n draws."""
+    b = make_batch(n * T, d, m, T, seed=seed, device=device, dtype=dtype)
+    return LqrTvBatch(b.A.view(n, T, d, d), b.B.view(n, T, d, m), b.Q.view(n, T, d, d), b.R.view(n, T, m, m),
+                      b.x0[:n].contiguous())
