@@ -24,7 +24,8 @@ PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 f
 # grouping, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy kernel
 # (profiles/*_d128_T16_llm_adapter_n65536.md): (read + written) KiB / 65536 problems.
 MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (38.64e6 + 27.51e6) * 1024 / 65536,
-                                      ("llm_adapter", "doubling"): (112.3e6 + 76.1e6) * 1024 / 65536}
+                                      ("llm_adapter", "doubling"): (112.3e6 + 76.1e6) * 1024 / 65536,
+                                      ("llm_adapter", "tv"): (69.06e6 + 2.107e6) * 1024 / 16384}
 def default_groups(T, dtype):
     """The library default: number of groups the T factors are split into (one dense solve each)."""
     return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
@@ -62,6 +63,12 @@ def alg_flops_doubling(d, T):
     return (f + 8 + 8.0 / 3) * d ** 3
 
 
+def alg_flops_tv(d, T):
+    """Algorithmic flops of one time-heterogeneous problem (ttc_lqr_solve_tv): per step R_s^{-1} B_s^T (7/3 d^3),
+    G_s = B_s X_s, P G_s, P A_s, A_s^T M_s (2 d^3 each) and the Moebius solve (8/3 d^3); 2 d^3 for K_0."""
+    return (T * (7.0 / 3 + 8 + 8.0 / 3) + 2) * d ** 3
+
+
 def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):
     """The oracle, as it stands, on the host cores: one problem chunk per thread, BLAS single-threaded."""
     import numpy as np
@@ -80,7 +87,10 @@ def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):
     def work(ix):
         if len(ix) == 0:
             return None
-        r = lqr_oracle.riccati_solve(A[ix], B[ix], Q[ix], R[ix], None, x0[ix], sub.T)
+        if A.ndim == 4:   # time-heterogeneous batch
+            r = lqr_oracle.riccati_solve_tv(A[ix], B[ix], Q[ix], R[ix], x0[ix])
+        else:
+            r = lqr_oracle.riccati_solve(A[ix], B[ix], Q[ix], R[ix], None, x0[ix], sub.T)
         return ix, {k: r[k] for k in ("P0", "K0", "u0", "value")}
 
     import contextlib
@@ -100,9 +110,11 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="llm_adapter")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling"),
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
-                         "doubling: the long-horizon path, the same product formed by squaring")
+                         "doubling: the long-horizon path, the same product formed by squaring; "
+                         "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
+                         "every step with its own A, B, Q, R (default 16384 problems)")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
     ap.add_argument("--rebase-every", type=int, default=0, help="0 = library default")
@@ -123,7 +135,8 @@ def main():
     from tests.parity import rel_err
 
     cfg = synth.CONFIGS[args.config]
-    n = args.n or synth.config_problems(args.config)
+    n = args.n or (min(16384, synth.config_problems(args.config)) if args.path == "tv"
+                   else synth.config_problems(args.config))
     d, m, T = cfg["d"], cfg["m"], cfg["T"]
     k = args.rebase_every
     groups = math.ceil(T / k) if k else default_groups(T, cfg["dtype"])
@@ -131,7 +144,11 @@ def main():
     torch.cuda.set_device(dev)
     binding.load()
 
-    batch = synth.make_batch(n, d, m, T, seed=0, device=dev, dtype=cfg["dtype"], rho=cfg["rho"])
+    if args.path == "tv":
+        batch = synth.make_tv_batch(n, d, m, T, seed=0, device=dev, dtype=cfg["dtype"])
+        args.no_extra = True
+    else:
+        batch = synth.make_batch(n, d, m, T, seed=0, device=dev, dtype=cfg["dtype"], rho=cfg["rho"])
     out = {
         "P0": torch.empty((n, d, d), dtype=torch.float32, device=dev),
         "K0": torch.empty((n, m, d), dtype=torch.float32, device=dev),
@@ -141,7 +158,7 @@ def main():
     }
     dbl = binding.TTC_FLAG_DOUBLING
     main_flags = dbl if args.path == "doubling" else 0
-    ws_bytes = max(binding.ttc_lqr_workspace_bytes(
+    ws_bytes = 16 if args.path == "tv" else max(binding.ttc_lqr_workspace_bytes(
         binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, f, k)) for f in (0, dbl))
     ws = torch.empty((max(ws_bytes, 16),), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
@@ -149,8 +166,11 @@ def main():
     def timed(flags, steps, warmup):
         """warmup untimed + steps timed launches of the whole workload; (wall s per step, kernel s per launch)"""
         def step():
-            binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, flags=flags, rebase_every=k,
-                                  out=out, workspace=ws, stream=stream)
+            if args.path == "tv":
+                binding.ttc_lqr_solve_tv(batch.A, batch.B, batch.Q, batch.R, batch.x0, out=out, stream=stream)
+            else:
+                binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, flags=flags,
+                                      rebase_every=k, out=out, workspace=ws, stream=stream)
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
@@ -176,24 +196,27 @@ def main():
     ms_per_step = wall_per_step * 1e3
     value = n / wall_per_step
 
-    flops_pp = alg_flops_doubling(d, T) if args.path == "doubling" else alg_flops(d, T, groups)
+    flops_pp = {"doubling": alg_flops_doubling(d, T), "tv": alg_flops_tv(d, T)}.get(args.path) or alg_flops(d, T, groups)
     achieved = flops_pp * n / avg_kernel_s / 1e12
-    in_bytes = n * (2 * d * d + d * m + m * m + d) * batch.A.element_size()
+    steps_in = T if args.path == "tv" else 1          # every step has its own matrices on the tv path
+    in_bytes = n * (steps_in * (2 * d * d + d * m + m * m) + d) * batch.A.element_size()
     out_bytes = n * (d * d + m * d + m + 2) * 4
-    traffic_key = (args.config, groups if args.path == "symplectic" else "doubling")
+    traffic_key = (args.config, groups if args.path == "symplectic" else args.path)
     res = {
         "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d" % (d, T),
         "value": value, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.config, "problems": n, "d": d, "m": m, "T": T, "input_dtype": cfg["dtype"],
-                   "path": args.path, "rebase_every": k or "default", "groups": groups,
+                   "path": args.path, "rebase_every": None if args.path != "symplectic" else (k or "default"),
+                   "groups": groups if args.path == "symplectic" else None,
                    "outputs": "P0,K0,u0,value"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[traffic_key] * n
                                  if traffic_key in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
-                     "kernel": ("doubling_kernel<%d>" if args.path == "doubling" else "solve_kernel<%d>") % d,
+                     "kernel": {"doubling": "doubling_kernel<%d>", "tv": "solve_tv_kernel<%d>"}.get(
+                         args.path, "solve_kernel<%d>") % d,
                      "kernel_ms": avg_kernel_s * 1e3,
                      "alg_flops_per_problem": flops_pp,
                      "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / avg_kernel_s / 1e12,
