@@ -662,7 +662,7 @@ static int cu_count() {
 // Persistent grids: as many workgroups as are resident at once, CUs x (workgroups per CU), so that no
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
 // (registers and LDS decide it); the table is the fallback when no device can be asked.
-enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4 };
+enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4, KIND_TV_QUAD = 5 };
 static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
 template <int D>
 static int occupancy_of(Kind kind, bool bf16) {
@@ -672,6 +672,9 @@ static int occupancy_of(Kind kind, bool bf16) {
   if (kind == KIND_SOLVE_QUAD)  // the four-problems-per-wavefront kernel (d = 16 only)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
+  else if (kind == KIND_TV_QUAD)
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<float>, nthr, 0);
   else if (kind == KIND_SOLVE_TV)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_kernel<D, uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_kernel<D, float>, nthr, 0);
@@ -691,7 +694,7 @@ static int occupancy_of(Kind kind, bool bf16) {
   return nb;
 }
 static int blocks_per_cu(Kind kind, int d, bool bf16) {
-  static int cached[5][4][2];  // 0 = not asked yet
+  static int cached[6][4][2];  // 0 = not asked yet
   int& c = cached[kind][dindex(d)][bf16 ? 1 : 0];
   if (c > 0) return c;
   int nb = 0;
@@ -705,7 +708,7 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
     c = nb > 32 ? 32 : nb;
     return c;
   }
-  static const int table[5][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}, {20, 8, 2, 1}};
+  static const int table[6][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}, {20, 8, 2, 1}, {8, 8, 2, 1}};
   return table[kind][dindex(d)];
 }
 static long long grid_blocks(Kind kind, int d, bool bf16) {
@@ -946,10 +949,20 @@ ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solut
   a.s.ws = nullptr;
   a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
   const bool bf16 = q->in_dtype == TTC_BF16;
-  const long long gb = ttc::grid_blocks(ttc::KIND_SOLVE_TV, q->d, bf16);
-  const dim3 grid((unsigned)(q->n < gb ? q->n : gb));
+  // d = 16: batches that fill the chip go four problems to a wavefront, as in ttc_lqr_solve
+  const bool quad = q->d == 16 && q->n >= 8LL * ttc::cu_count();
+  const long long gb = ttc::grid_blocks(quad ? ttc::KIND_TV_QUAD : ttc::KIND_SOLVE_TV, q->d, bf16);
+  const long long items = quad ? (q->n + 3) / 4 : q->n;
+  const dim3 grid((unsigned)(items < gb ? items : gb));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const hipError_t e = bf16 ? ttc::launch_tv<uint16_t>(a, q->d, grid, st) : ttc::launch_tv<float>(a, q->d, grid, st);
+  hipError_t e;
+  if (quad) {
+    if (bf16) hipLaunchKernelGGL((ttc::solve_tv_small_kernel<uint16_t>), grid, dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((ttc::solve_tv_small_kernel<float>), grid, dim3(64), 0, st, a);
+    e = hipGetLastError();
+  } else {
+    e = bf16 ? ttc::launch_tv<uint16_t>(a, q->d, grid, st) : ttc::launch_tv<float>(a, q->d, grid, st);
+  }
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 

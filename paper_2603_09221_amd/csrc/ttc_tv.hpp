@@ -117,4 +117,157 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta)
   }
 }
 
+// The same at d = 16 with four problems per wavefront (see ttc_small.hpp): products of the four problems
+// interleaved on the matrix cores, their dense solves side by side with one row per lane.
+template <typename TIn>
+__global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
+  constexpr int D = 16;
+  using C = Cfg<D>;
+  constexpr int PPW = 4;
+  __shared__ __attribute__((aligned(16))) float Wm[PPW][D * C::PITCH];
+  __shared__ float s_red[C::NW];
+  const SolveArgs& p = ta.s;
+  const long long nquads = (p.n + PPW - 1) / PPW;
+
+  for (long long quad = blockIdx.x; quad < nquads; quad += gridDim.x) {
+    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, i = lane & 15, g = lane >> 4;
+    constexpr int w = 0;
+    long long prob[PPW];  // a ragged last quad repeats the last problem; only valid ones are written out
+    bool valid[PPW];
+    const TIn *Ap[PPW], *Bp[PPW], *Qp[PPW], *Rp[PPW];
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) {
+      valid[q] = quad * PPW + q < p.n;
+      prob[q] = valid[q] ? quad * PPW + q : p.n - 1;
+      Ap[q] = reinterpret_cast<const TIn*>(p.A) + prob[q] * p.sA;
+      Bp[q] = reinterpret_cast<const TIn*>(p.B) + prob[q] * p.sB;
+      Qp[q] = reinterpret_cast<const TIn*>(p.Q) + prob[q] * p.sQ;
+      Rp[q] = reinterpret_cast<const TIn*>(p.R) + prob[q] * p.sR;
+    }
+    float* const Wmine = Wm[g];  // the problem whose rows this lane holds during the dense solves
+    int info[PPW] = {0, 0, 0, 0};
+    int nsolve = 0;
+    auto note = [&](int bad) {
+      ++nsolve;
+      const unsigned long long m = __ballot(bad != 0);
+#pragma unroll
+      for (int q = 0; q < PPW; ++q)
+        if (!info[q] && ((m >> (16 * q)) & 0xFFFFull)) info[q] = nsolve;
+    };
+    floatx4 acc[PPW][C::RB][C::NT];
+    float cX[PPW][C::RB][C::KS];
+
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q] + D, Qp[q] + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
+    __syncthreads();
+    for (int s = p.T - 1; s >= 0; --s) {
+      float cG[PPW][C::RB][C::KS], cAT[PPW][C::RB][C::KS];
+      {
+        floatx4 preg[PPW][C::RB][C::NT];
+        float cB[PPW][C::RB][C::KS];
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) load_rows<D>(Wm[q] + D, preg[q], w, i, g);  // P_{s+1} waits in registers
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          load_half<D, TIn, false>(Wm[q], Rp[q] + (long long)s * ta.tR, tid);
+          load_half<D, TIn, true>(Wm[q] + D, Bp[q] + (long long)s * ta.tB, tid);  // RHS = B_s^T
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          symmetrise_half<D>(Wm[q], tid);
+          load_aopT_lds<D>(Wm[q] + D, cB[q], w, i, g);
+        }
+        __syncthreads();
+        note(solve_rows16<false>(Wmine, lane));  // R_s is positive definite: no pivot search
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
+        gemm_acc_quad(acc, cB, Wm, D, i, g);  // rows of G_s = B_s X_s
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          if (s == 0) load_aop_lds<D>(Wm[q] + D, cX[q], w, i, g);
+          store_rows<D>(Wm[q], acc[q], w, i, g);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q], cG[q], w, i, g);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          store_rows<D>(Wm[q] + D, preg[q], w, i, g);  // P_{s+1} back as the right operand
+          load_half<D, TIn, false>(Wm[q], Ap[q] + (long long)s * ta.tA, tid);
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) load_aopT_lds<D>(Wm[q], cAT[q], w, i, g);  // rows of A_s^T
+      __syncthreads();
+      {
+        floatx4 acc2[PPW][C::RB][C::NT];
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          eye_acc<D>(acc[q], w, i, g);
+          zero_acc<D>(acc2[q]);
+        }
+        gemm_acc_quad(acc, cG, Wm, D, i, g);    // I + G_s P = (I + P G_s)^T
+        gemm_acc_quad(acc2, cAT, Wm, D, i, g);  // A_s^T P = (P A_s)^T
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          store_rows_T<D>(Wm[q], acc[q], w, i, g);
+          store_rows_T<D>(Wm[q] + D, acc2[q], w, i, g);
+        }
+      }
+      __syncthreads();
+      note(solve_rows16<true>(Wmine, lane));  // right halves: M_s
+      if (s >= 1) {
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q], Qp[q] + (long long)(s - 1) * ta.tQ, tid);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) load_rows<D>(Wm[q], acc[q], w, i, g);
+        gemm_acc_quad(acc, cAT, Wm, D, i, g);  // P_s = Q[s-1] + A_s^T M_s
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q] + D, acc[q], w, i, g);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
+        __syncthreads();
+      } else {
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
+        gemm_acc_quad(acc, cAT, Wm, D, i, g);  // P_0 = A_0^T M_0
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
+        gemm_acc_quad(acc, cX, Wm, D, i, g);   // -K_0 = X_0 M_0
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          if (!valid[q]) continue;  // uniform over the wavefront
+          const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
+          emit_gain<D, TIn>(p, prob[q], acc[q], x0p, info[q], tid);
+          emit_value<D, TIn>(p, prob[q], Wm[q], Qp[q], x0p, info[q], s_red, tid);
+        }
+        __syncthreads();
+      }
+    }
+  }
+}
+
 }  // namespace ttc

@@ -36,6 +36,23 @@ def test_shapes_horizons_and_ragged_batches(d, T, n):
     check(synth.make_tv_batch(n, d, d, T, seed=d + T, device=DEV), TOL_F32)
 
 
+def test_d16_large_batches_four_problems_per_wavefront():
+    """From 8 x CUs problems on, d = 16 runs four problems per wavefront: ragged last quad, bfloat16 inputs, a
+    horizon of one, and a breakdown that must stay with its own problem."""
+    n = 2048 + 37
+    b = synth.make_tv_batch(n, 16, 16, 6, seed=21, device=DEV)
+    out = check(b, TOL_F32)
+    check(synth.make_tv_batch(n, 16, 16, 1, seed=22, device=DEV), TOL_F32)
+    check(synth.make_tv_batch(n + 2, 16, 16, 9, seed=23, device=DEV, dtype="bf16"), TOL_BF16)
+    R = b.R.clone()
+    R[1001, 2] = 0.0                                       # step 2 is the fourth from the end: dense solve 7
+    bad = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, R, b.x0)
+    info = bad["info"].cpu().numpy()
+    assert info[1001] == 7 and (np.delete(info, 1001) == 0).all()
+    keep = torch.tensor([1000, 1002, 1003, 2084], device=DEV)
+    assert torch.equal(bad["u0"][keep], out["u0"][keep]) and torch.isnan(bad["u0"][1001]).all()
+
+
 def test_bf16_inputs():
     for d, T, n in [(16, 8, 64), (64, 8, 64), (128, 12, 24)]:
         check(synth.make_tv_batch(n, d, d, T, seed=8, device=DEV, dtype="bf16"), TOL_BF16)
