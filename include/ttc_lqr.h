@@ -149,6 +149,15 @@ typedef struct {
 ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t *problem, const ttc_lqr_solution_t *solution,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Roll-out of n time-heterogeneous problems (Alg. 1, forward loop, r = 0): U (n, T, m), X (n, T+1, d) and
+ * cost (n) = sum_s u_s^T R[s] u_s + x_{s+1}^T Q[s] x_{s+1}, which equals `value` of ttc_lqr_solve_tv.
+ * The gains K_s are produced by the backward sweep of ttc_lqr_solve_tv and kept in the workspace, a DEVICE
+ * buffer of at least ttc_lqr_tv_rollout_workspace_bytes(problem) bytes, 16-byte aligned.  X, cost and
+ * info may be NULL.  Same conventions and error behaviour as ttc_lqr_rollout. */
+size_t ttc_lqr_tv_rollout_workspace_bytes(const ttc_lqr_tv_problem_t *problem);
+ttc_status_t ttc_lqr_rollout_tv(const ttc_lqr_tv_problem_t *problem, float *U, float *X, float *cost,
+                                int32_t *info, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *ttc_status_string(ttc_status_t status);
 

@@ -20,8 +20,8 @@ TTC_FLAG_STAGE_COST_AT_X0 = 1
 TTC_FLAG_PURE_SYMPLECTIC = 2
 TTC_FLAG_DOUBLING = 4
 
-EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_status_string",
-           "ttc_version")
+EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
+           "ttc_lqr_tv_rollout_workspace_bytes", "ttc_status_string", "ttc_version")
 
 
 class Problem(ctypes.Structure):
@@ -71,6 +71,11 @@ def load():
                                     c_size_t, c_void_p]
     lib.ttc_lqr_solve_tv.restype = c_int
     lib.ttc_lqr_solve_tv.argtypes = [ctypes.POINTER(TvProblem), ctypes.POINTER(Solution), c_void_p, c_size_t, c_void_p]
+    lib.ttc_lqr_tv_rollout_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_tv_rollout_workspace_bytes.argtypes = [ctypes.POINTER(TvProblem)]
+    lib.ttc_lqr_rollout_tv.restype = c_int
+    lib.ttc_lqr_rollout_tv.argtypes = [ctypes.POINTER(TvProblem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                       c_size_t, c_void_p]
     lib.ttc_status_string.restype = c_char_p
     lib.ttc_status_string.argtypes = [c_int]
     lib.ttc_version.restype = c_int
@@ -225,4 +230,21 @@ def ttc_lqr_solve_tv(A, B, Q, R, x0, *, want_P0=True, want_K0=True, out=None, st
     out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
     sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
     _check(lib.ttc_lqr_solve_tv(ctypes.byref(prob), ctypes.byref(sol), None, 0, _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_rollout_tv(A, B, Q, R, x0, *, workspace=None, stream=None):
+    """U (n,T,m), X (n,T+1,d), cost (n), info (n) of n time-heterogeneous problems; float32 device tensors."""
+    lib = load()
+    prob = make_tv_problem(A, B, Q, R, x0)
+    n, d, m, T, dev = prob.n, prob.d, prob.m, prob.T, A.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = {"U": torch.empty((n, T, m), **f32), "X": torch.empty((n, T + 1, d), **f32),
+           "cost": torch.empty((n,), **f32), "info": torch.empty((n,), dtype=torch.int32, device=dev)}
+    need = lib.ttc_lqr_tv_rollout_workspace_bytes(ctypes.byref(prob))
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    _check(lib.ttc_lqr_rollout_tv(ctypes.byref(prob), _ptr(out["U"]), _ptr(out["X"]), _ptr(out["cost"]),
+                                  _ptr(out["info"]), c_void_p(workspace.data_ptr()), workspace.numel(),
+                                  _stream_ptr(stream)))
     return out

@@ -465,7 +465,6 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
 }  // namespace ttc
 #include "ttc_doubling.hpp"
 #include "ttc_small.hpp"
-#include "ttc_tv.hpp"
 namespace ttc {
 
 // ------------------------------------------------------------------------------------------------
@@ -645,6 +644,10 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
   }
 }
 
+}  // namespace ttc
+#include "ttc_tv.hpp"
+namespace ttc {
+
 // ------------------------------------------------------------------------------------------------
 static int cu_count() {
   static int cached = 0;
@@ -662,7 +665,8 @@ static int cu_count() {
 // Persistent grids: as many workgroups as are resident at once, CUs x (workgroups per CU), so that no
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
 // (registers and LDS decide it); the table is the fallback when no device can be asked.
-enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4, KIND_TV_QUAD = 5 };
+enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4, KIND_TV_QUAD = 5,
+            KIND_ROLLOUT_TV = 6 };
 static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
 template <int D>
 static int occupancy_of(Kind kind, bool bf16) {
@@ -672,6 +676,9 @@ static int occupancy_of(Kind kind, bool bf16) {
   if (kind == KIND_SOLVE_QUAD)  // the four-problems-per-wavefront kernel (d = 16 only)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
+  else if (kind == KIND_ROLLOUT_TV)
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, float>, nthr, 0);
   else if (kind == KIND_TV_QUAD)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<float>, nthr, 0);
@@ -694,7 +701,7 @@ static int occupancy_of(Kind kind, bool bf16) {
   return nb;
 }
 static int blocks_per_cu(Kind kind, int d, bool bf16) {
-  static int cached[6][4][2];  // 0 = not asked yet
+  static int cached[7][4][2];  // 0 = not asked yet
   int& c = cached[kind][dindex(d)][bf16 ? 1 : 0];
   if (c > 0) return c;
   int nb = 0;
@@ -708,7 +715,8 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
     c = nb > 32 ? 32 : nb;
     return c;
   }
-  static const int table[6][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}, {20, 8, 2, 1}, {8, 8, 2, 1}};
+  static const int table[7][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1},
+                                  {20, 8, 2, 1}, {8, 8, 2, 1},  {12, 4, 2, 1}};
   return table[kind][dindex(d)];
 }
 static long long grid_blocks(Kind kind, int d, bool bf16) {
@@ -776,6 +784,18 @@ static hipError_t launch_tv(const TvArgs& a, int d, dim3 grid, hipStream_t st) {
     case 32: hipLaunchKernelGGL((solve_tv_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
     case 64: hipLaunchKernelGGL((solve_tv_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
     case 128: hipLaunchKernelGGL((solve_tv_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <typename TIn>
+static hipError_t launch_rollout_tv(const TvRolloutArgs& a, int d, dim3 grid, hipStream_t st) {
+  switch (d) {
+    case 16: hipLaunchKernelGGL((rollout_tv_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((rollout_tv_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((rollout_tv_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((rollout_tv_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -916,17 +936,13 @@ ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t* problem, float* U, float* 
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 
-ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solution_t* solution, void* workspace,
-                              size_t workspace_bytes, void* hip_stream) {
-  (void)workspace;
-  (void)workspace_bytes;
+static ttc_status_t validate_tv(const ttc_lqr_tv_problem_t* q) {
   if (!q) return TTC_ERR_INVALID_ARG;
   if (q->n < 0 || q->T < 1 || q->d < 1 || q->m < 1 || q->flags != 0) return TTC_ERR_INVALID_ARG;
   if (q->in_dtype != TTC_F32 && q->in_dtype != TTC_BF16) return TTC_ERR_INVALID_ARG;
   if (!(q->d == q->m && (q->d == 16 || q->d == 32 || q->d == 64 || q->d == 128))) return TTC_ERR_UNSUPPORTED;
-  if (!solution) return TTC_ERR_INVALID_ARG;
   if (q->n == 0) return TTC_OK;
-  if (!q->A || !q->B || !q->Q || !q->R || !q->x0 || !solution->u0) return TTC_ERR_INVALID_ARG;
+  if (!q->A || !q->B || !q->Q || !q->R || !q->x0) return TTC_ERR_INVALID_ARG;
   const size_t al = q->in_dtype == TTC_F32 ? 16 : 8;
   const void* ptrs[] = {q->A, q->B, q->Q, q->R};
   const int64_t strides[] = {q->sA, q->sB, q->sQ, q->sR, q->tA, q->tB, q->tQ, q->tR};
@@ -935,6 +951,50 @@ ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solut
   for (int k = 0; k < 8; ++k)
     if (strides[k] < 0 || strides[k] % 4) return TTC_ERR_INVALID_ARG;
   if (q->sx0 < 0) return TTC_ERR_INVALID_ARG;
+  return TTC_OK;
+}
+
+size_t ttc_lqr_tv_rollout_workspace_bytes(const ttc_lqr_tv_problem_t* q) {
+  if (!q || q->T < 1 || !(q->d == q->m && (q->d == 16 || q->d == 32 || q->d == 64 || q->d == 128))) return 0;
+  const size_t slots = (size_t)ttc::grid_blocks(ttc::KIND_ROLLOUT_TV, q->d, q->in_dtype == TTC_BF16);
+  return slots * (size_t)q->T * q->d * q->m * sizeof(float);
+}
+
+ttc_status_t ttc_lqr_rollout_tv(const ttc_lqr_tv_problem_t* q, float* U, float* X, float* cost, int32_t* info,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t stv = validate_tv(q);
+  if (stv != TTC_OK) return stv;
+  if (q->n == 0) return TTC_OK;
+  if (!U) return TTC_ERR_INVALID_ARG;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_tv_rollout_workspace_bytes(q))
+    return TTC_ERR_WORKSPACE;
+  ttc::TvRolloutArgs a;
+  a.r.n = q->n;
+  a.r.T = q->T;
+  a.r.flags = 0;
+  a.r.A = q->A; a.r.B = q->B; a.r.Q = q->Q; a.r.R = q->R; a.r.QT = nullptr; a.r.x0 = q->x0;
+  a.r.sA = q->sA; a.r.sB = q->sB; a.r.sQ = q->sQ; a.r.sR = q->sR; a.r.sQT = 0; a.r.sx0 = q->sx0;
+  a.r.U = U; a.r.X = X; a.r.cost = cost; a.r.info = info;
+  a.r.ws = static_cast<float*>(workspace);
+  a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const long long gb = ttc::grid_blocks(ttc::KIND_ROLLOUT_TV, q->d, bf16);
+  const dim3 grid((unsigned)(q->n < gb ? q->n : gb));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = bf16 ? ttc::launch_rollout_tv<uint16_t>(a, q->d, grid, st)
+                            : ttc::launch_rollout_tv<float>(a, q->d, grid, st);
+  return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+}
+
+ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solution_t* solution, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  const ttc_status_t stv = validate_tv(q);
+  if (stv != TTC_OK) return stv;
+  if (!solution) return TTC_ERR_INVALID_ARG;
+  if (q->n == 0) return TTC_OK;
+  if (!solution->u0) return TTC_ERR_INVALID_ARG;
   if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
   ttc::TvArgs a;
   a.s.n = q->n;

@@ -117,6 +117,148 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta)
   }
 }
 
+struct TvRolloutArgs {
+  RolloutArgs r;               // n, T, A, B, Q, R, x0 and their problem strides, U, X, cost, info, ws (QT unused)
+  long long tA, tB, tQ, tR;    // elements between consecutive steps
+};
+
+// Roll-out of a time-heterogeneous problem (Alg. 1 with r = 0): the backward sweep of solve_tv_kernel
+// keeping every gain K_s = -X_s M_s in the workspace, then the closed-loop forward sweep
+// u_s = K_s x_s, x_{s+1} = A_s x_s + B_s u_s with the cost sum_s u_s^T R_s u_s + x_{s+1}^T Q[s] x_{s+1}.
+template <int D, typename TIn>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_tv_kernel(const TvRolloutArgs ta) {
+  using C = Cfg<D>;
+  __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
+  __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
+  __shared__ float s_red[C::NW];
+  __shared__ float s_x[D], s_u[D], s_xn[D];
+  const RolloutArgs& p = ta.r;
+  float* const WL = W;
+  float* const WR = W + D;
+  float* const wsK = p.ws + (long)blockIdx.x * p.T * D * D;  // K_0 .. K_{T-1}, row-major
+
+  for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
+    const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
+    const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
+    const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
+    const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
+    const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
+    int info = 0, nsolve = 0;
+    {
+      const int tid = threadIdx.x + opaque_zero();
+      load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
+      __syncthreads();
+      symmetrise_half<D>(WR, tid);
+      __syncthreads();
+    }
+    // ---- backward sweep
+    for (int s = p.T - 1; s >= 0; --s) {
+      const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+      floatx4 acc[C::RB][C::NT];
+      float cG[C::RB][C::KS], cAT[C::RB][C::KS], cX[C::RB][C::KS];
+      {
+        floatx4 preg[C::RB][C::NT];
+        load_rows<D>(WR, preg, w, i, g);
+        __syncthreads();
+        load_half<D, TIn, false>(WL, Rp + (long long)s * ta.tR, tid);
+        load_half<D, TIn, true>(WR, Bp + (long long)s * ta.tB, tid);
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);
+        float cB[C::RB][C::KS];
+        load_aopT_lds<D>(WR, cB, w, i, g);
+        __syncthreads();
+        ++nsolve;
+        if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;
+        zero_acc<D>(acc);
+        gemm_acc<D>(acc, cB, WR, i, g);  // rows of G_s
+        load_aop_lds<D>(WR, cX, w, i, g);  // rows of X_s, for the gain
+        store_rows<D>(WL, acc, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);
+        __syncthreads();
+        load_aop_lds<D>(WL, cG, w, i, g);
+        __syncthreads();
+        store_rows<D>(WR, preg, w, i, g);
+      }
+      load_half<D, TIn, false>(WL, Ap + (long long)s * ta.tA, tid);
+      __syncthreads();
+      load_aopT_lds<D>(WL, cAT, w, i, g);
+      __syncthreads();
+      eye_acc<D>(acc, w, i, g);
+      gemm_acc<D>(acc, cG, WR, i, g);
+      store_rows_T<D>(WL, acc, w, i, g);
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, cAT, WR, i, g);
+      __syncthreads();
+      store_rows_T<D>(WR, acc, w, i, g);
+      __syncthreads();
+      ++nsolve;
+      if (lds_solve<D>(W, S, tid) && !info) info = nsolve;  // right half: M_s
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, cX, WR, i, g);  // -K_s
+#pragma unroll
+      for (int rb = 0; rb < C::RB; ++rb) {
+#pragma unroll
+        for (int cc = 0; cc < C::NT; ++cc) acc[rb][cc] = -acc[rb][cc];
+        write_rows_global<D>(wsK + (long)s * D * D, acc[rb], C::RB * w + rb, i, g);
+      }
+      if (s >= 1) {
+        load_half<D, TIn, false>(WL, Qp + (long long)(s - 1) * ta.tQ, tid);
+        __syncthreads();
+        symmetrise_half<D>(WL, tid);
+        __syncthreads();
+        load_rows<D>(WL, acc, w, i, g);
+        gemm_acc<D>(acc, cAT, WR, i, g);  // P_s
+        __syncthreads();
+        store_rows<D>(WR, acc, w, i, g);
+        __syncthreads();
+        symmetrise_half<D>(WR, tid);
+        __syncthreads();
+      }
+    }
+    __syncthreads();  // gains visible to the whole workgroup
+
+    // ---- forward sweep
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r = tid / (C::NTHR / D), part = tid % (C::NTHR / D);
+    if (tid < D) s_x[tid] = ld1<TIn>(x0p, tid);
+    __syncthreads();
+    float cpart = 0.f;
+    if (p.X && tid < D) p.X[prob * (long)(p.T + 1) * D + tid] = s_x[tid];
+    for (int t = 0; t < p.T; ++t) {
+      const float u = matvec_row<D, float>(wsK + (long)t * D * D, s_x, tid);
+      if (part == 0) s_u[r] = u;
+      __syncthreads();
+      const float ru = matvec_row<D, TIn>(Rp + (long long)t * ta.tR, s_u, tid);
+      const float xn = matvec_row<D, TIn>(Ap + (long long)t * ta.tA, s_x, tid) +
+                       matvec_row<D, TIn>(Bp + (long long)t * ta.tB, s_u, tid);
+      if (part == 0) {
+        cpart += s_u[r] * ru;
+        s_xn[r] = xn;
+        p.U[(prob * p.T + t) * (long)D + r] = info ? __builtin_nanf("") : u;
+      }
+      __syncthreads();
+      const float qx = matvec_row<D, TIn>(Qp + (long long)t * ta.tQ, s_xn, tid);
+      if (part == 0) {
+        cpart += s_xn[r] * qx;
+        s_x[r] = xn;
+        if (p.X) p.X[(prob * (p.T + 1) + t + 1) * (long)D + r] = info ? __builtin_nanf("") : xn;
+      }
+      __syncthreads();
+    }
+    cpart = sum64(cpart);
+    if (lane == 0) s_red[w] = cpart;
+    __syncthreads();
+    if (tid == 0) {
+      float cst = 0.f;
+      for (int ww = 0; ww < C::NW; ++ww) cst += s_red[ww];
+      if (p.cost) p.cost[prob] = info ? __builtin_nanf("") : cst;
+      if (p.info) p.info[prob] = info;
+    }
+    __syncthreads();
+  }
+}
+
 // The same at d = 16 with four problems per wavefront (see ttc_small.hpp): products of the four problems
 // interleaved on the matrix cores, their dense solves side by side with one row per lane.
 template <typename TIn>

@@ -114,3 +114,43 @@ def test_empty_batch():
     b = synth.make_tv_batch(1, 16, 16, 3, seed=0, device=DEV)
     out = binding.ttc_lqr_solve_tv(b.A[:0], b.B[:0], b.Q[:0], b.R[:0], b.x0[:0])
     assert out["u0"].shape == (0, 16)
+
+
+# ---------------------------------------------------------------- roll-out
+def rollout_check(batch, tol):
+    out = binding.ttc_lqr_rollout_tv(batch.A, batch.B, batch.Q, batch.R, batch.x0)
+    torch.cuda.synchronize()
+    assert int(out["info"].abs().max()) == 0
+    U, X, cost = lqr_oracle.riccati_rollout_tv(*batch.numpy64())
+    errs = {"U": rel_err(out["U"].cpu().numpy(), U).max(), "X": rel_err(out["X"].cpu().numpy(), X).max(),
+            "cost": rel_err(out["cost"].cpu().numpy(), cost).max()}
+    print({k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= tol, (k, v)
+    assert torch.equal(out["X"][:, 0], batch.x0.float())
+    return out
+
+
+@pytest.mark.parametrize("d,T,n", [(16, 8, 256), (16, 1, 3), (32, 5, 40), (64, 8, 300), (128, 16, 20)])
+def test_rollout_matches_oracle(d, T, n):
+    rollout_check(synth.make_tv_batch(n, d, d, T, seed=20 + d, device=DEV), TOL_F32)
+
+
+def test_rollout_cost_equals_solve_value_and_first_control():
+    b = synth.make_tv_batch(48, 64, 64, 6, seed=31, device=DEV)
+    ro = rollout_check(b, TOL_F32)
+    so = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, b.R, b.x0)
+    torch.cuda.synchronize()
+    assert rel_err(ro["cost"].cpu().numpy(), so["value"].double().cpu().numpy()).max() <= 2e-4
+    assert rel_err(ro["U"][:, 0].cpu().numpy(), so["u0"].double().cpu().numpy()).max() <= 2e-4
+
+
+def test_rollout_bf16_and_breakdown():
+    rollout_check(synth.make_tv_batch(24, 128, 128, 8, seed=8, device=DEV, dtype="bf16"), TOL_BF16)
+    b = synth.make_tv_batch(6, 16, 16, 4, seed=10, device=DEV)
+    R = b.R.clone()
+    R[4, 3] = 0.0
+    out = binding.ttc_lqr_rollout_tv(b.A, b.B, b.Q, R, b.x0)
+    info = out["info"].cpu().numpy()
+    assert info[4] == 1 and (np.delete(info, 4) == 0).all()
+    assert torch.isnan(out["U"][4]).all() and torch.isnan(out["cost"][4])
