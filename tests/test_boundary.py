@@ -94,3 +94,43 @@ def test_binding_rejects_mixed_dtypes():
         binding.make_problem(A, A.bfloat16(), A, A, None, torch.zeros(1, 16), 4)
     with pytest.raises(ValueError):
         binding.make_problem(A.double(), A.double(), A.double(), A.double(), None, torch.zeros(1, 16).double(), 4)
+
+
+def _tv_problem(**kw):
+    p = binding.TvProblem()
+    p.n, p.d, p.m, p.T = 4, 16, 16, 8
+    fake = 0x1000  # never dereferenced: validation fails or n == 0 before any launch
+    p.A = p.B = p.Q = p.R = p.x0 = fake
+    p.sA = p.sB = p.sQ = p.sR = 8 * 256
+    p.tA = p.tB = p.tQ = p.tR = 256
+    p.sx0 = 16
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_time_heterogeneous_argument_validation_without_device(lib):
+    sol = binding.Solution(0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+
+    def solve(p, s=sol):
+        return lib.ttc_lqr_solve_tv(ctypes.byref(p), ctypes.byref(s), None, 0, None)
+
+    def rollout(p, U=0x1000, ws=0x1000, ws_bytes=1 << 40):
+        return lib.ttc_lqr_rollout_tv(ctypes.byref(p), U, None, None, None, ws, ws_bytes, None)
+
+    for call in (solve, rollout):
+        assert call(_tv_problem(T=0)) == binding.TTC_ERR_INVALID_ARG
+        assert call(_tv_problem(flags=1)) == binding.TTC_ERR_INVALID_ARG           # no flags on this entry point
+        assert call(_tv_problem(in_dtype=3)) == binding.TTC_ERR_INVALID_ARG
+        assert call(_tv_problem(R=None)) == binding.TTC_ERR_INVALID_ARG
+        assert call(_tv_problem(B=0x1008)) == binding.TTC_ERR_INVALID_ARG          # misaligned
+        assert call(_tv_problem(tQ=250)) == binding.TTC_ERR_INVALID_ARG            # step stride not a multiple of 4
+        assert call(_tv_problem(d=48, m=48)) == binding.TTC_ERR_UNSUPPORTED
+        assert call(_tv_problem(n=0)) == binding.TTC_OK
+    assert solve(_tv_problem(), binding.Solution(None, None, None, None, None)) == binding.TTC_ERR_INVALID_ARG
+    assert rollout(_tv_problem(), U=None) == binding.TTC_ERR_INVALID_ARG
+    assert rollout(_tv_problem(), ws=None) == binding.TTC_ERR_WORKSPACE
+    assert rollout(_tv_problem(), ws_bytes=64) == binding.TTC_ERR_WORKSPACE
+    w = lib.ttc_lqr_tv_rollout_workspace_bytes(ctypes.byref(_tv_problem(d=128, m=128, T=16)))
+    assert w > 0 and w % (16 * 128 * 128 * 4) == 0                                   # T matrices per resident workgroup
+    assert lib.ttc_lqr_tv_rollout_workspace_bytes(ctypes.byref(_tv_problem(d=48, m=48))) == 0
