@@ -7,6 +7,10 @@ Prints ONE JSON line: problems/s plus a roofline object for the solve kernel (fp
 oracle timed on the host cores on a bounded sample of the same inputs.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llm_adapter] [--n N] [--rebase-every k]
+                    [--path symplectic|doubling|tv]
+
+The headline value is the paper's sequential symplectic product (--path symplectic, the default); the same
+inputs are also timed on the squaring path and reported under "other_path".
 """
 import argparse
 import json
@@ -125,8 +129,8 @@ def main():
                          "to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (problems are independent; see DESIGN.md for the "
-              "sharding note). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (problems are independent: a multi-GPU run would split "
+              "the batch and exchange nothing). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
