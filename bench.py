@@ -29,7 +29,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 f
 # (profiles/*_d128_T16_llm_adapter_n65536.md): (read + written) KiB / 65536 problems.
 MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (38.64e6 + 27.51e6) * 1024 / 65536,
                                       ("llm_adapter", "doubling"): (112.3e6 + 76.1e6) * 1024 / 65536,
-                                      ("llm_adapter", "tv"): (69.06e6 + 2.107e6) * 1024 / 16384}
+                                      ("llm_adapter", "tv"): (82.69e6 + 3.090e6) * 1024 / 16384}
 def default_groups(T, dtype):
     """The library default: number of groups the T factors are split into (one dense solve each)."""
     return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
@@ -68,9 +68,10 @@ def alg_flops_doubling(d, T):
 
 
 def alg_flops_tv(d, T):
-    """Algorithmic flops of one time-heterogeneous problem (ttc_lqr_solve_tv): per step R_s^{-1} B_s^T (7/3 d^3),
-    G_s = B_s X_s, P G_s, P A_s, A_s^T M_s (2 d^3 each) and the Moebius solve (8/3 d^3); 2 d^3 for K_0."""
-    return (T * (7.0 / 3 + 8 + 8.0 / 3) + 2) * d ** 3
+    """Algorithmic flops of one time-heterogeneous problem (ttc_lqr_solve_tv): per step the six products of the
+    printed Riccati step (P A, P B, B^T P A, B^T P B, A^T P A, F^T W: 2 d^3 each) and the solve with the positive
+    definite S (factor d^3/3, d right-hand sides 2 d^3)."""
+    return T * (12 + 7.0 / 3) * d ** 3
 
 
 def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):

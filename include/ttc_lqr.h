@@ -141,11 +141,13 @@ typedef struct {
 } ttc_lqr_tv_problem_t;
 
 /* P0, K0, u0, value, info of n time-heterogeneous problems (same solution struct and error behaviour
- * as ttc_lqr_solve).  One backward Riccati step per factor, each in the Moebius form of the symplectic
- * factor Sigma_t of Thm 3.3 (a re-base after every factor, which needs no A_t^{-1}):
- *     G_s = B_s R_s^{-1} B_s^T,  M_s = (I + P_{s+1} G_s)^{-1} P_{s+1} A_s,  P_s = Q[s-1] + A_s^T M_s,
- * and K_0 = -R_0^{-1} B_0^T M_0.  info: dense solve 2s+1 (R_s^{-1} B_s^T) or 2s+2 (the Moebius solve)
- * counted from the last step backwards.  No workspace is needed: `workspace` may be NULL. */
+ * as ttc_lqr_solve).  With every factor Sigma_t of Thm 3.3 different, the iteration is re-based after
+ * every factor, which is the backward recursion of Prop. 3.1 as printed, one step per factor:
+ *     S_s = R[s] + B[s]^T P_{s+1} B[s],  K_s = -S_s^{-1} B[s]^T P_{s+1} A[s]                  (Eq. "decode")
+ *     P_s = Q[s-1] + A[s]^T P_{s+1} A[s] - (B[s]^T P_{s+1} A[s])^T S_s^{-1} (B[s]^T P_{s+1} A[s])   (Eq. "riccati")
+ * with P_T = Q[T-1] and no Q on x_0.  One dense solve per step, S_s positive definite (no pivoting; a
+ * pivot that is not positive is a breakdown): info = T - s for the step s whose solve broke down.
+ * No workspace is needed: `workspace` may be NULL. */
 ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t *problem, const ttc_lqr_solution_t *solution,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 

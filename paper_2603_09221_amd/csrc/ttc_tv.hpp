@@ -2,15 +2,15 @@
 // Prop. 3.1; the paper's "time-heterogeneous parameterization", Sec. 4).
 // Included by ttc_lqr.hip after the helpers it shares with the other kernels.
 //
-// With every factor Sigma_t of Thm 3.3 different, nothing can be prepared once per problem, and each
-// factor would need its own A_t^{-1}.  The kernel therefore re-bases after every factor, which turns a
-// factor into one backward Riccati step in Moebius form and needs no A_t^{-1}:
-//     X_s = R_s^{-1} B_s^T,  G_s = B_s X_s,
-//     M_s = (I + P_{s+1} G_s)^{-1} P_{s+1} A_s,   P_s = Q[s-1] + A_s^T M_s   (P_T = Q[T-1], no Q on x_0),
-//     K_0 = -X_0 M_0                                                         (Eq. "decode").
-// Two dense solves and four products per step; the value matrix stays on chip for the whole horizon
-// (in LDS as the right operand of the products, in registers while the pair serves the R_s solve),
-// the step's matrices are streamed from HBM once each.
+// With every factor Sigma_t of Thm 3.3 different, nothing can be prepared once per problem: each factor
+// would need its own A_t^{-1} and G_t = B_t R_t^{-1} B_t^T, two dense solves before the factor is even
+// applied, and a re-base on top.  Re-basing after every factor turns the iteration into the backward
+// recursion of Prop. 3.1 itself, and its printed form needs one solve per step, with a positive
+// definite matrix (no pivot search):
+//     S_s = R_s + B_s^T P_{s+1} B_s,   W_s = S_s^{-1} B_s^T P_{s+1} A_s,   K_s = -W_s        (Eq. "decode")
+//     P_s = Q[s-1] + A_s^T P_{s+1} A_s - (B_s^T P_{s+1} A_s)^T W_s   (P_T = Q[T-1], no Q on x_0)  (Eq. "riccati")
+// Six products and one dense solve per step; the value matrix stays on chip for the whole horizon, the
+// step's matrices are streamed from HBM once each.
 #pragma once
 
 namespace ttc {
@@ -19,6 +19,112 @@ struct TvArgs {
   SolveArgs s;                 // n, T, A, B, Q, R, x0 and their problem strides, outputs (QT, ws, groups unused)
   long long tA, tB, tQ, tR;    // elements between consecutive steps
 };
+
+// accumulator rows of this wavefront <- row-major global matrix of input element type
+template <int D, typename TIn>
+__device__ __forceinline__ void load_rows_input(const TIn* src, floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT], int w, int i, int g) {
+  using C = Cfg<D>;
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int h = 0; h < C::NH; ++h) {
+        const long off = (long)(16 * (C::RB * w + rb) + 4 * g + v) * D + 16 * C::VEC * h + C::VEC * i;
+        if constexpr (C::VEC == 4) {
+          const floatx4 t = ld4<TIn>(src, off);
+#pragma unroll
+          for (int tp = 0; tp < 4; ++tp) acc[rb][h * 4 + tp][v] = t[tp];
+        } else {
+#pragma unroll
+          for (int tp = 0; tp < C::VEC; ++tp) acc[rb][h * C::VEC + tp][v] = ld1<TIn>(src, off + tp);
+        }
+      }
+}
+
+// One backward step of Prop. 3.1 with the matrices of one step.  On entry the right half of the pair
+// holds P_{s+1} (symmetric); on exit it holds W = S^{-1} B^T P A = -K_s, S = R + B^T P B, and pn holds this
+// wavefront's rows of A^T P A - (B^T P A)^T W, which is P_s up to the stage cost.  Six products and one
+// unpivoted solve (S is positive definite).  Returns the solve's breakdown flag.
+template <int D, typename TIn>
+__device__ __forceinline__ int riccati_step(float* W, SolveScratch<D>& S, const TIn* As, const TIn* Bs, const TIn* Rs,
+                                            floatx4 (&pn)[Cfg<D>::RB][Cfg<D>::NT], int tid) {
+  using C = Cfg<D>;
+  tid += opaque_zero();
+  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  float* const WL = W;
+  float* const WR = W + D;
+  float cFT[C::RB][C::KS];
+  {
+    float cAT[C::RB][C::KS], cBT[C::RB][C::KS];
+    {
+      floatx4 accPA[C::RB][C::NT], accPB[C::RB][C::NT];
+      {
+        float cP[C::RB][C::KS];
+        load_aop_lds<D>(WR, cP, w, i, g);  // rows of P (symmetric)
+        load_half<D, TIn, false>(WL, As, tid);
+        __syncthreads();
+        load_half<D, TIn, false>(WR, Bs, tid);  // P is in registers now
+        zero_acc<D>(accPA);
+        gemm_acc<D>(accPA, cP, WL, i, g);  // P A
+        __syncthreads();
+        zero_acc<D>(accPB);
+        gemm_acc<D>(accPB, cP, WR, i, g);  // P B
+      }
+      load_aopT_lds<D>(WL, cAT, w, i, g);  // rows of A^T
+      load_aopT_lds<D>(WR, cBT, w, i, g);  // rows of B^T
+      __syncthreads();
+      store_rows<D>(WL, accPA, w, i, g);
+      store_rows<D>(WR, accPB, w, i, g);
+      __syncthreads();
+    }
+    floatx4 accS[C::RB][C::NT], accF[C::RB][C::NT];
+    load_rows_input<D, TIn>(Rs, accS, w, i, g);
+    gemm_acc<D>(accS, cBT, WR, i, g);  // S = R + B^T P B
+    zero_acc<D>(accF);
+    gemm_acc<D>(accF, cBT, WL, i, g);  // F = B^T P A
+    zero_acc<D>(pn);
+    gemm_acc<D>(pn, cAT, WL, i, g);    // A^T P A
+    __syncthreads();
+    store_rows<D>(WL, accS, w, i, g);
+    store_rows<D>(WR, accF, w, i, g);
+    __syncthreads();
+  }
+  symmetrise_half<D>(WL, tid);  // R is read as its symmetric part
+  load_aopT_lds<D>(WR, cFT, w, i, g);  // rows of F^T
+  __syncthreads();
+  const int flag = lds_solve<D, 7, false>(W, S, tid);  // right half: W = S^{-1} F
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int k = 0; k < C::KS; ++k) cFT[rb][k] = -cFT[rb][k];
+  gemm_acc<D>(pn, cFT, WR, i, g);  // - F^T W
+  return flag;
+}
+
+// pn += the symmetric part of the stage cost Qs (staged through the left half), then P_s = pn goes to the
+// right half, exactly symmetric.  Contains the barriers it needs; the right half must no longer be read.
+template <int D, typename TIn>
+__device__ __forceinline__ void next_value_matrix(float* W, const TIn* Qs, floatx4 (&pn)[Cfg<D>::RB][Cfg<D>::NT], int tid) {
+  using C = Cfg<D>;
+  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  float* const WL = W;
+  float* const WR = W + D;
+  load_half<D, TIn, false>(WL, Qs, tid);
+  __syncthreads();
+  symmetrise_half<D>(WL, tid);
+  __syncthreads();
+  floatx4 q[C::RB][C::NT];
+  load_rows<D>(WL, q, w, i, g);
+#pragma unroll
+  for (int rb = 0; rb < C::RB; ++rb)
+#pragma unroll
+    for (int c = 0; c < C::NT; ++c) pn[rb][c] += q[rb][c];
+  store_rows<D>(WR, pn, w, i, g);
+  __syncthreads();
+  symmetrise_half<D>(WR, tid);
+  __syncthreads();
+}
 
 template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta) {
@@ -31,85 +137,32 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta)
   float* const WR = W + D;
 
   for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
+    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
     const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
     const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
     const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
     const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
-    int info = 0, nsolve = 0;
-    float cX[C::RB][C::KS];  // rows of X_0, for the gain
-
-    {
-      const int tid = threadIdx.x + opaque_zero();
-      load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
-      __syncthreads();
-      symmetrise_half<D>(WR, tid);
-      __syncthreads();
-    }
+    int info = 0;
+    load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
+    __syncthreads();
+    symmetrise_half<D>(WR, tid);
+    __syncthreads();
     for (int s = p.T - 1; s >= 0; --s) {
-      // (address arithmetic local to the step: see opaque_zero)
-      const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
-      floatx4 acc[C::RB][C::NT];
-      float cG[C::RB][C::KS], cAT[C::RB][C::KS];
-      {
-        floatx4 preg[C::RB][C::NT];
-        load_rows<D>(WR, preg, w, i, g);  // P_{s+1} waits in registers while the pair serves the R_s solve
-        __syncthreads();
-        load_half<D, TIn, false>(WL, Rp + (long long)s * ta.tR, tid);
-        load_half<D, TIn, true>(WR, Bp + (long long)s * ta.tB, tid);  // RHS = B_s^T
-        __syncthreads();
-        symmetrise_half<D>(WL, tid);
-        float cB[C::RB][C::KS];
-        load_aopT_lds<D>(WR, cB, w, i, g);  // rows of B_s = columns of B_s^T
-        __syncthreads();
-        ++nsolve;
-        if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;  // R_s is positive definite: no pivot search
-        zero_acc<D>(acc);
-        gemm_acc<D>(acc, cB, WR, i, g);  // rows of G_s = B_s X_s
-        if (s == 0) load_aop_lds<D>(WR, cX, w, i, g);
-        store_rows<D>(WL, acc, w, i, g);
-        __syncthreads();
-        symmetrise_half<D>(WL, tid);
-        __syncthreads();
-        load_aop_lds<D>(WL, cG, w, i, g);
-        __syncthreads();
-        store_rows<D>(WR, preg, w, i, g);  // P_{s+1} back as the right operand
-      }
-      load_half<D, TIn, false>(WL, Ap + (long long)s * ta.tA, tid);
-      __syncthreads();
-      load_aopT_lds<D>(WL, cAT, w, i, g);  // rows of A_s^T
-      __syncthreads();
-      eye_acc<D>(acc, w, i, g);
-      gemm_acc<D>(acc, cG, WR, i, g);      // I + G_s P = (I + P G_s)^T
-      store_rows_T<D>(WL, acc, w, i, g);
-      zero_acc<D>(acc);
-      gemm_acc<D>(acc, cAT, WR, i, g);     // A_s^T P = (P A_s)^T
-      __syncthreads();
-      store_rows_T<D>(WR, acc, w, i, g);
-      __syncthreads();
-      ++nsolve;
-      if (lds_solve<D>(W, S, tid) && !info) info = nsolve;  // right half: M_s
+      floatx4 pn[C::RB][C::NT];
+      const int flag = riccati_step<D, TIn>(W, S, Ap + (long long)s * ta.tA, Bp + (long long)s * ta.tB,
+                                            Rp + (long long)s * ta.tR, pn, tid);
+      if (flag && !info) info = p.T - s;
       if (s >= 1) {
-        load_half<D, TIn, false>(WL, Qp + (long long)(s - 1) * ta.tQ, tid);  // the cost on x_s
-        __syncthreads();
-        symmetrise_half<D>(WL, tid);
-        __syncthreads();
-        load_rows<D>(WL, acc, w, i, g);
-        gemm_acc<D>(acc, cAT, WR, i, g);   // P_s = Q[s-1] + A_s^T M_s
-        __syncthreads();
-        store_rows<D>(WR, acc, w, i, g);
-        __syncthreads();
-        symmetrise_half<D>(WR, tid);
-        __syncthreads();
+        __syncthreads();  // every wavefront is done reading W = -K_s
+        next_value_matrix<D, TIn>(W, Qp + (long long)(s - 1) * ta.tQ, pn, tid);
       } else {
-        zero_acc<D>(acc);
-        gemm_acc<D>(acc, cAT, WR, i, g);   // P_0 = A_0^T M_0
-        store_rows<D>(WL, acc, w, i, g);
+        store_rows<D>(WL, pn, w, i, g);  // P_0 (no cost on x_0)
         __syncthreads();
         symmetrise_half<D>(WL, tid);
         __syncthreads();
-        zero_acc<D>(acc);
-        gemm_acc<D>(acc, cX, WR, i, g);    // -K_0 = X_0 M_0
+        floatx4 acc[C::RB][C::NT];
+        load_rows<D>(WR, acc, w, i, g);  // rows of -K_0
         emit_gain<D, TIn>(p, prob, acc, x0p, info, tid);
         emit_value<D, TIn>(p, prob, WL, Qp, x0p, info, s_red, tid);
       }
@@ -123,7 +176,7 @@ struct TvRolloutArgs {
 };
 
 // Roll-out of a time-heterogeneous problem (Alg. 1 with r = 0): the backward sweep of solve_tv_kernel
-// keeping every gain K_s = -X_s M_s in the workspace, then the closed-loop forward sweep
+// keeping every gain K_s in the workspace, then the closed-loop forward sweep
 // u_s = K_s x_s, x_{s+1} = A_s x_s + B_s u_s with the cost sum_s u_s^T R_s u_s + x_{s+1}^T Q[s] x_{s+1}.
 template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_tv_kernel(const TvRolloutArgs ta) {
@@ -133,7 +186,6 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_tv_kernel(const TvRollou
   __shared__ float s_red[C::NW];
   __shared__ float s_x[D], s_u[D], s_xn[D];
   const RolloutArgs& p = ta.r;
-  float* const WL = W;
   float* const WR = W + D;
   float* const wsK = p.ws + (long)blockIdx.x * p.T * D * D;  // K_0 .. K_{T-1}, row-major
 
@@ -143,77 +195,31 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_tv_kernel(const TvRollou
     const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
     const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
-    int info = 0, nsolve = 0;
+    int info = 0;
     {
-      const int tid = threadIdx.x + opaque_zero();
+      const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
       load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
       __syncthreads();
       symmetrise_half<D>(WR, tid);
       __syncthreads();
-    }
-    // ---- backward sweep
-    for (int s = p.T - 1; s >= 0; --s) {
-      const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
-      floatx4 acc[C::RB][C::NT];
-      float cG[C::RB][C::KS], cAT[C::RB][C::KS], cX[C::RB][C::KS];
-      {
-        floatx4 preg[C::RB][C::NT];
-        load_rows<D>(WR, preg, w, i, g);
-        __syncthreads();
-        load_half<D, TIn, false>(WL, Rp + (long long)s * ta.tR, tid);
-        load_half<D, TIn, true>(WR, Bp + (long long)s * ta.tB, tid);
-        __syncthreads();
-        symmetrise_half<D>(WL, tid);
-        float cB[C::RB][C::KS];
-        load_aopT_lds<D>(WR, cB, w, i, g);
-        __syncthreads();
-        ++nsolve;
-        if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;
-        zero_acc<D>(acc);
-        gemm_acc<D>(acc, cB, WR, i, g);  // rows of G_s
-        load_aop_lds<D>(WR, cX, w, i, g);  // rows of X_s, for the gain
-        store_rows<D>(WL, acc, w, i, g);
-        __syncthreads();
-        symmetrise_half<D>(WL, tid);
-        __syncthreads();
-        load_aop_lds<D>(WL, cG, w, i, g);
-        __syncthreads();
-        store_rows<D>(WR, preg, w, i, g);
-      }
-      load_half<D, TIn, false>(WL, Ap + (long long)s * ta.tA, tid);
-      __syncthreads();
-      load_aopT_lds<D>(WL, cAT, w, i, g);
-      __syncthreads();
-      eye_acc<D>(acc, w, i, g);
-      gemm_acc<D>(acc, cG, WR, i, g);
-      store_rows_T<D>(WL, acc, w, i, g);
-      zero_acc<D>(acc);
-      gemm_acc<D>(acc, cAT, WR, i, g);
-      __syncthreads();
-      store_rows_T<D>(WR, acc, w, i, g);
-      __syncthreads();
-      ++nsolve;
-      if (lds_solve<D>(W, S, tid) && !info) info = nsolve;  // right half: M_s
-      zero_acc<D>(acc);
-      gemm_acc<D>(acc, cX, WR, i, g);  // -K_s
+      // ---- backward sweep
+      for (int s = p.T - 1; s >= 0; --s) {
+        floatx4 pn[C::RB][C::NT];
+        const int flag = riccati_step<D, TIn>(W, S, Ap + (long long)s * ta.tA, Bp + (long long)s * ta.tB,
+                                              Rp + (long long)s * ta.tR, pn, tid);
+        if (flag && !info) info = p.T - s;
+        {
+          floatx4 acc[C::RB][C::NT];
+          load_rows<D>(WR, acc, w, i, g);
 #pragma unroll
-      for (int rb = 0; rb < C::RB; ++rb) {
+          for (int rb = 0; rb < C::RB; ++rb) {
 #pragma unroll
-        for (int cc = 0; cc < C::NT; ++cc) acc[rb][cc] = -acc[rb][cc];
-        write_rows_global<D>(wsK + (long)s * D * D, acc[rb], C::RB * w + rb, i, g);
-      }
-      if (s >= 1) {
-        load_half<D, TIn, false>(WL, Qp + (long long)(s - 1) * ta.tQ, tid);
+            for (int cc = 0; cc < C::NT; ++cc) acc[rb][cc] = -acc[rb][cc];
+            write_rows_global<D>(wsK + (long)s * D * D, acc[rb], C::RB * w + rb, i, g);  // K_s
+          }
+        }
         __syncthreads();
-        symmetrise_half<D>(WL, tid);
-        __syncthreads();
-        load_rows<D>(WL, acc, w, i, g);
-        gemm_acc<D>(acc, cAT, WR, i, g);  // P_s
-        __syncthreads();
-        store_rows<D>(WR, acc, w, i, g);
-        __syncthreads();
-        symmetrise_half<D>(WR, tid);
-        __syncthreads();
+        if (s >= 1) next_value_matrix<D, TIn>(W, Qp + (long long)(s - 1) * ta.tQ, pn, tid);
       }
     }
     __syncthreads();  // gains visible to the whole workgroup
@@ -296,9 +302,6 @@ __global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
       for (int q = 0; q < PPW; ++q)
         if (!info[q] && ((m >> (16 * q)) & 0xFFFFull)) info[q] = nsolve;
     };
-    floatx4 acc[PPW][C::RB][C::NT];
-    float cX[PPW][C::RB][C::KS];
-
 #pragma unroll
     for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q] + D, Qp[q] + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
     __syncthreads();
@@ -306,69 +309,75 @@ __global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
     for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
     __syncthreads();
     for (int s = p.T - 1; s >= 0; --s) {
-      float cG[PPW][C::RB][C::KS], cAT[PPW][C::RB][C::KS];
+      // the step of riccati_step, for four problems at once
+      floatx4 pn[PPW][C::RB][C::NT];
+      float cFT[PPW][C::RB][C::KS];
       {
-        floatx4 preg[PPW][C::RB][C::NT];
-        float cB[PPW][C::RB][C::KS];
+        float cAT[PPW][C::RB][C::KS], cBT[PPW][C::RB][C::KS];
+        {
+          floatx4 accPA[PPW][C::RB][C::NT], accPB[PPW][C::RB][C::NT];
+          {
+            float cP[PPW][C::RB][C::KS];
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) load_rows<D>(Wm[q] + D, preg[q], w, i, g);  // P_{s+1} waits in registers
+            for (int q = 0; q < PPW; ++q) {
+              load_aop_lds<D>(Wm[q] + D, cP[q], w, i, g);  // rows of P
+              load_half<D, TIn, false>(Wm[q], Ap[q] + (long long)s * ta.tA, tid);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < PPW; ++q) {
+              load_half<D, TIn, false>(Wm[q] + D, Bp[q] + (long long)s * ta.tB, tid);  // P is in registers now
+              zero_acc<D>(accPA[q]);
+              zero_acc<D>(accPB[q]);
+            }
+            gemm_acc_quad(accPA, cP, Wm, 0, i, g);  // P A
+            __syncthreads();
+            gemm_acc_quad(accPB, cP, Wm, D, i, g);  // P B
+          }
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) {
+            load_aopT_lds<D>(Wm[q], cAT[q], w, i, g);      // rows of A^T
+            load_aopT_lds<D>(Wm[q] + D, cBT[q], w, i, g);  // rows of B^T
+          }
+          __syncthreads();
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) {
+            store_rows<D>(Wm[q], accPA[q], w, i, g);
+            store_rows<D>(Wm[q] + D, accPB[q], w, i, g);
+          }
+          __syncthreads();
+        }
+        floatx4 accS[PPW][C::RB][C::NT], accF[PPW][C::RB][C::NT];
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          load_rows_input<D, TIn>(Rp[q] + (long long)s * ta.tR, accS[q], w, i, g);
+          zero_acc<D>(accF[q]);
+          zero_acc<D>(pn[q]);
+        }
+        gemm_acc_quad(accS, cBT, Wm, D, i, g);  // S = R + B^T P B
+        gemm_acc_quad(accF, cBT, Wm, 0, i, g);  // F = B^T P A
+        gemm_acc_quad(pn, cAT, Wm, 0, i, g);    // A^T P A
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
-          load_half<D, TIn, false>(Wm[q], Rp[q] + (long long)s * ta.tR, tid);
-          load_half<D, TIn, true>(Wm[q] + D, Bp[q] + (long long)s * ta.tB, tid);  // RHS = B_s^T
+          store_rows<D>(Wm[q], accS[q], w, i, g);
+          store_rows<D>(Wm[q] + D, accF[q], w, i, g);
         }
         __syncthreads();
+      }
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          symmetrise_half<D>(Wm[q], tid);
-          load_aopT_lds<D>(Wm[q] + D, cB[q], w, i, g);
-        }
-        __syncthreads();
-        note(solve_rows16<false>(Wmine, lane));  // R_s is positive definite: no pivot search
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-        gemm_acc_quad(acc, cB, Wm, D, i, g);  // rows of G_s = B_s X_s
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          if (s == 0) load_aop_lds<D>(Wm[q] + D, cX[q], w, i, g);
-          store_rows<D>(Wm[q], acc[q], w, i, g);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q], cG[q], w, i, g);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          store_rows<D>(Wm[q] + D, preg[q], w, i, g);  // P_{s+1} back as the right operand
-          load_half<D, TIn, false>(Wm[q], Ap[q] + (long long)s * ta.tA, tid);
-        }
+      for (int q = 0; q < PPW; ++q) {
+        symmetrise_half<D>(Wm[q], tid);  // R is read as its symmetric part
+        load_aopT_lds<D>(Wm[q] + D, cFT[q], w, i, g);  // rows of F^T
       }
       __syncthreads();
+      note(solve_rows16<false>(Wmine, lane));  // right halves: W = S^{-1} F = -K_s
 #pragma unroll
-      for (int q = 0; q < PPW; ++q) load_aopT_lds<D>(Wm[q], cAT[q], w, i, g);  // rows of A_s^T
+      for (int q = 0; q < PPW; ++q)
+#pragma unroll
+        for (int k = 0; k < C::KS; ++k) cFT[q][0][k] = -cFT[q][0][k];
+      gemm_acc_quad(pn, cFT, Wm, D, i, g);  // - F^T W
       __syncthreads();
-      {
-        floatx4 acc2[PPW][C::RB][C::NT];
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          eye_acc<D>(acc[q], w, i, g);
-          zero_acc<D>(acc2[q]);
-        }
-        gemm_acc_quad(acc, cG, Wm, D, i, g);    // I + G_s P = (I + P G_s)^T
-        gemm_acc_quad(acc2, cAT, Wm, D, i, g);  // A_s^T P = (P A_s)^T
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          store_rows_T<D>(Wm[q], acc[q], w, i, g);
-          store_rows_T<D>(Wm[q] + D, acc2[q], w, i, g);
-        }
-      }
-      __syncthreads();
-      note(solve_rows16<true>(Wmine, lane));  // right halves: M_s
       if (s >= 1) {
 #pragma unroll
         for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q], Qp[q] + (long long)(s - 1) * ta.tQ, tid);
@@ -377,33 +386,30 @@ __global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
         for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) load_rows<D>(Wm[q], acc[q], w, i, g);
-        gemm_acc_quad(acc, cAT, Wm, D, i, g);  // P_s = Q[s-1] + A_s^T M_s
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q] + D, acc[q], w, i, g);
+        for (int q = 0; q < PPW; ++q) {
+          floatx4 qs[C::RB][C::NT];
+          load_rows<D>(Wm[q], qs, w, i, g);
+          pn[q][0][0] += qs[0][0];
+          store_rows<D>(Wm[q] + D, pn[q], w, i, g);  // P_s
+        }
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
         __syncthreads();
       } else {
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-        gemm_acc_quad(acc, cAT, Wm, D, i, g);  // P_0 = A_0^T M_0
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
+        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], pn[q], w, i, g);  // P_0 (no cost on x_0)
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-        gemm_acc_quad(acc, cX, Wm, D, i, g);   // -K_0 = X_0 M_0
-#pragma unroll
         for (int q = 0; q < PPW; ++q) {
           if (!valid[q]) continue;  // uniform over the wavefront
           const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
-          emit_gain<D, TIn>(p, prob[q], acc[q], x0p, info[q], tid);
+          floatx4 acc[C::RB][C::NT];
+          load_rows<D>(Wm[q] + D, acc, w, i, g);  // rows of -K_0
+          emit_gain<D, TIn>(p, prob[q], acc, x0p, info[q], tid);
           emit_value<D, TIn>(p, prob[q], Wm[q], Qp[q], x0p, info[q], s_red, tid);
         }
         __syncthreads();

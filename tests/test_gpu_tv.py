@@ -45,10 +45,10 @@ def test_d16_large_batches_four_problems_per_wavefront():
     check(synth.make_tv_batch(n, 16, 16, 1, seed=22, device=DEV), TOL_F32)
     check(synth.make_tv_batch(n + 2, 16, 16, 9, seed=23, device=DEV, dtype="bf16"), TOL_BF16)
     R = b.R.clone()
-    R[1001, 2] = 0.0                                       # step 2 is the fourth from the end: dense solve 7
+    R[1001, 2] = -100.0 * torch.eye(16, device=DEV)        # S not positive definite at step 2, the fourth solve
     bad = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, R, b.x0)
     info = bad["info"].cpu().numpy()
-    assert info[1001] == 7 and (np.delete(info, 1001) == 0).all()
+    assert info[1001] == 4 and (np.delete(info, 1001) == 0).all()
     keep = torch.tensor([1000, 1002, 1003, 2084], device=DEV)
     assert torch.equal(bad["u0"][keep], out["u0"][keep]) and torch.isnan(bad["u0"][1001]).all()
 
@@ -100,7 +100,7 @@ def test_padded_strides_and_singular_A():
 def test_info_reports_breakdown_and_outputs_are_optional():
     b = synth.make_tv_batch(6, 16, 16, 4, seed=10, device=DEV)
     R = b.R.clone()
-    R[4, 3] = 0.0                                          # the first dense solve (last step's R) must fail
+    R[4, 3] = -100.0 * torch.eye(16, device=DEV)           # S = R + B^T P B not positive definite at the last step
     out = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, R, b.x0, want_P0=False)
     info = out["info"].cpu().numpy()
     assert info[4] == 1 and (np.delete(info, 4) == 0).all() and "P0" not in out
@@ -149,7 +149,7 @@ def test_rollout_bf16_and_breakdown():
     rollout_check(synth.make_tv_batch(24, 128, 128, 8, seed=8, device=DEV, dtype="bf16"), TOL_BF16)
     b = synth.make_tv_batch(6, 16, 16, 4, seed=10, device=DEV)
     R = b.R.clone()
-    R[4, 3] = 0.0
+    R[4, 3] = -100.0 * torch.eye(16, device=DEV)
     out = binding.ttc_lqr_rollout_tv(b.A, b.B, b.Q, R, b.x0)
     info = out["info"].cpu().numpy()
     assert info[4] == 1 and (np.delete(info, 4) == 0).all()
