@@ -27,7 +27,11 @@ All functions accept either one problem (A: (d,d), x0: (d,)) or a stack of probl
 (A: (n,d,d), x0: (n,d)); everything is evaluated in float64.
 
 Time-heterogeneous problems (the general statement of Prop. 3.1, with A_t, B_t, Q_t, R_t varying over
-the horizon) have their own entry points, riccati_solve_tv / riccati_rollout_tv, below.
+the horizon) have their own entry points, riccati_solve_tv / riccati_rollout_tv, below.  The structured,
+contextualised parameters of Sec. 4 (diagonal A_t and R_t, B_t and Q_t from shared bases with exponential
+time modulation) are expanded to dense steps by contextual_parameters and solved by contextual_solve
+(pins: tests/test_oracle_pins_contextual.py: an expansion worked out by hand, ratio properties, a scalar
+problem by hand, the time-invariant problem when nothing is modulated, the stacked KKT system).
 
 Pins (tests/test_oracle_pins.py): scalar closed form (Fibonacci ratios), T=1 closed form,
 decoupled diagonal problems, brute-force stacked KKT system (Thm A.6's matrix form) and
@@ -199,3 +203,43 @@ def riccati_rollout_tv(A, B, Q, R, x0):
         U.append(u)
         X.append(x)
     return np.stack(U, axis=-2), np.stack(X, axis=-2), cost
+
+
+# ------------------------------------------------------------------------------------------------------
+# Contextualised, structured parameters (Sec. 4, "Contextualization" and "Parameterization"; Sec. 3.3,
+# "Structured Parameterization"): the T steps of one problem are synthesised from a few per-problem
+# vectors and two shared groups of basis matrices,
+#     Gamma_X^t = diag(exp(-t * lg_X)),  X in {A, B, Q},                 t = 1..T
+#     A_t = I + Gamma_A^t diag(s_A)                       (diagonal)
+#     B_t = (sum_i s_B[i] Bbasis[i]) Gamma_B^t            (columns scaled)
+#     Q_t = Gamma_Q^t (sum_i s_Q[i] Qbasis[i]) Gamma_Q^t  for t < T,   Q_T = sum_i s_Qf[i] Qbasis[i]
+#     R_t = diag(1 / rinv)                                (the layer hands over the diagonal of R^{-1})
+# Step s of the arrays below is the paper's t = s + 1.
+
+def contextual_parameters(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, T):
+    """Dense A, B, Q, R of shape (..., T, d, d) from the structured inputs.
+
+    sA, rinv, lgA, lgB, lgQ: (..., d);  sB, sQ, sQf: (..., r);  Bbasis, Qbasis: (r, d, d), shared.
+    """
+    sA, sB, sQ, sQf, rinv = _f64(sA), _f64(sB), _f64(sQ), _f64(sQf), _f64(rinv)
+    lgA, lgB, lgQ, Bbasis, Qbasis = _f64(lgA), _f64(lgB), _f64(lgQ), _f64(Bbasis), _f64(Qbasis)
+    d = sA.shape[-1]
+    eye = np.eye(d)
+    Bbar = np.einsum("...i,ijk->...jk", sB, Bbasis)
+    Qbar = np.einsum("...i,ijk->...jk", sQ, Qbasis)
+    Qf = np.einsum("...i,ijk->...jk", sQf, Qbasis)
+    As, Bs, Qs, Rs = [], [], [], []
+    for t in range(1, T + 1):
+        gA, gB, gQ = np.exp(-t * lgA), np.exp(-t * lgB), np.exp(-t * lgQ)
+        As.append(eye + (gA * sA)[..., :, None] * eye)
+        Bs.append(Bbar * gB[..., None, :])
+        Qs.append(Qf if t == T else gQ[..., :, None] * Qbar * gQ[..., None, :])
+        Rs.append((1.0 / rinv)[..., :, None] * eye)
+    stack = lambda Ms: np.stack(Ms, axis=-3)
+    return stack(As), stack(Bs), stack(Qs), stack(Rs)
+
+
+def contextual_solve(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T):
+    """P0, K0, u0, value of the problem whose steps are contextual_parameters(...)."""
+    A, B, Q, R = contextual_parameters(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, T)
+    return riccati_solve_tv(A, B, Q, R, x0)
