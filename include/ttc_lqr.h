@@ -160,6 +160,37 @@ size_t ttc_lqr_tv_rollout_workspace_bytes(const ttc_lqr_tv_problem_t *problem);
 ttc_status_t ttc_lqr_rollout_tv(const ttc_lqr_tv_problem_t *problem, float *U, float *X, float *cost,
                                 int32_t *info, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Structured, contextualised problems (Sec. 4, "Contextualization" and "Parameterization"; Sec. 3.3,
+ * "Structured Parameterization"): the T steps of a problem are not stored anywhere; the kernel builds them
+ * from per-problem vectors and two groups of r basis matrices shared by all problems.  With t = 1..T the
+ * paper's step index (step s = t - 1 of ttc_lqr_solve_tv) and Gamma_X^t = diag(exp(-t * lgX)):
+ *     A_t = I + Gamma_A^t diag(sA)                                   (diagonal)
+ *     B_t = (sum_i sB[i] Bbasis[i]) Gamma_B^t                        (columns scaled)
+ *     Q_t = Gamma_Q^t (sum_i sQ[i] Qbasis[i]) Gamma_Q^t   for t < T
+ *     Q_T = sum_i sQf[i] Qbasis[i]                                   (terminal cost, not modulated)
+ *     R_t = diag(1 / rinv)                                           (the diagonal of R^{-1} is the input)
+ * All pointers are DEVICE pointers, borrowed and read-only, of element type in_dtype, contiguous:
+ * sA, rinv, lgA, lgB, lgQ, x0 are (n, d); sB, sQ, sQf are (n, r); Bbasis, Qbasis are (r, d, d) row-major.
+ * The problem solved needs rinv > 0 and the combined Q matrices positive semi-definite (they are read as
+ * their symmetric parts); lgX >= 0 gives the discounting of the paper, any finite value is accepted. */
+typedef struct {
+  int64_t n;        /* problems = batch * heads * tokens */
+  int32_t d;        /* state = control dimension; 16 is supported */
+  int32_t r;        /* basis matrices per group, 1..64 */
+  int32_t T;        /* horizon, >= 1 */
+  int32_t in_dtype; /* ttc_dtype_t */
+  int32_t flags;    /* 0 */
+  const void *sA, *sB, *sQ, *sQf, *rinv, *lgA, *lgB, *lgQ, *x0;
+  const void *Bbasis, *Qbasis;
+} ttc_lqr_cxt_problem_t;
+
+/* P0, K0, u0, value, info of n structured problems: the recursion of ttc_lqr_solve_tv (Prop. 3.1) on the
+ * steps defined above, with the same solution struct, conventions (no cost on x_0) and error behaviour;
+ * info = T - s for the step whose S_s = R + B^T P B was not positive definite.  Needs no workspace,
+ * allocates nothing, is asynchronous on hip_stream.  d other than 16 or r above 64: TTC_ERR_UNSUPPORTED. */
+ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t *problem, const ttc_lqr_solution_t *solution,
+                               void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *ttc_status_string(ttc_status_t status);
 

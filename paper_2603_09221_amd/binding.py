@@ -21,7 +21,7 @@ TTC_FLAG_PURE_SYMPLECTIC = 2
 TTC_FLAG_DOUBLING = 4
 
 EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
-           "ttc_lqr_tv_rollout_workspace_bytes", "ttc_status_string", "ttc_version")
+           "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_status_string", "ttc_version")
 
 
 class Problem(ctypes.Structure):
@@ -39,6 +39,14 @@ class TvProblem(ctypes.Structure):
                 ("A", c_void_p), ("B", c_void_p), ("Q", c_void_p), ("R", c_void_p), ("x0", c_void_p),
                 ("sA", c_int64), ("sB", c_int64), ("sQ", c_int64), ("sR", c_int64), ("sx0", c_int64),
                 ("tA", c_int64), ("tB", c_int64), ("tQ", c_int64), ("tR", c_int64)]
+
+
+class CxtProblem(ctypes.Structure):
+    _fields_ = [("n", c_int64), ("d", c_int32), ("r", c_int32), ("T", c_int32), ("in_dtype", c_int32),
+                ("flags", c_int32),
+                ("sA", c_void_p), ("sB", c_void_p), ("sQ", c_void_p), ("sQf", c_void_p), ("rinv", c_void_p),
+                ("lgA", c_void_p), ("lgB", c_void_p), ("lgQ", c_void_p), ("x0", c_void_p),
+                ("Bbasis", c_void_p), ("Qbasis", c_void_p)]
 
 
 class Solution(ctypes.Structure):
@@ -76,6 +84,8 @@ def load():
     lib.ttc_lqr_rollout_tv.restype = c_int
     lib.ttc_lqr_rollout_tv.argtypes = [ctypes.POINTER(TvProblem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                        c_size_t, c_void_p]
+    lib.ttc_lqr_solve_cxt.restype = c_int
+    lib.ttc_lqr_solve_cxt.argtypes = [ctypes.POINTER(CxtProblem), ctypes.POINTER(Solution), c_void_p]
     lib.ttc_status_string.restype = c_char_p
     lib.ttc_status_string.argtypes = [c_int]
     lib.ttc_version.restype = c_int
@@ -247,4 +257,45 @@ def ttc_lqr_rollout_tv(A, B, Q, R, x0, *, workspace=None, stream=None):
     _check(lib.ttc_lqr_rollout_tv(ctypes.byref(prob), _ptr(out["U"]), _ptr(out["X"]), _ptr(out["cost"]),
                                   _ptr(out["info"]), c_void_p(workspace.data_ptr()), workspace.numel(),
                                   _stream_ptr(stream)))
+    return out
+
+
+def make_cxt_problem(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T) -> CxtProblem:
+    """Descriptor of n structured problems: sA, rinv, lgA, lgB, lgQ, x0 (n,d); sB, sQ, sQf (n,r); Bbasis, Qbasis
+    (r,d,d); all contiguous and of one dtype."""
+    n, d = sA.shape
+    r = Bbasis.shape[0]
+    shapes = {"sA": (n, d), "rinv": (n, d), "lgA": (n, d), "lgB": (n, d), "lgQ": (n, d), "x0": (n, d),
+              "sB": (n, r), "sQ": (n, r), "sQf": (n, r), "Bbasis": (r, d, d), "Qbasis": (r, d, d)}
+    given = dict(sA=sA, sB=sB, sQ=sQ, sQf=sQf, rinv=rinv, lgA=lgA, lgB=lgB, lgQ=lgQ, Bbasis=Bbasis, Qbasis=Qbasis, x0=x0)
+    for k, t in given.items():
+        if tuple(t.shape) != shapes[k] or not t.is_contiguous() or t.dtype != sA.dtype:
+            raise ValueError(f"{k}: expected a contiguous {shapes[k]} tensor of dtype {sA.dtype}")
+    in_dtype = {torch.float32: TTC_F32, torch.bfloat16: TTC_BF16}.get(sA.dtype)
+    if in_dtype is None:
+        raise ValueError("inputs must be float32 or bfloat16")
+    p = CxtProblem()
+    p.n, p.d, p.r, p.T, p.in_dtype, p.flags = n, d, r, T, in_dtype, 0
+    for k, t in given.items():
+        setattr(p, k, _ptr(t))
+    return p
+
+
+def ttc_lqr_solve_cxt(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T, *, want_P0=True, want_K0=True,
+                      out=None, stream=None):
+    """P0, K0, u0, value, info of n structured, contextualised problems (float32 device tensors)."""
+    lib = load()
+    prob = make_cxt_problem(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T)
+    n, d, dev = prob.n, prob.d, sA.device
+    out = dict(out or {})
+    f32 = dict(dtype=torch.float32, device=dev)
+    if want_P0 and "P0" not in out:
+        out["P0"] = torch.empty((n, d, d), **f32)
+    if want_K0 and "K0" not in out:
+        out["K0"] = torch.empty((n, d, d), **f32)
+    out.setdefault("u0", torch.empty((n, d), **f32))
+    out.setdefault("value", torch.empty((n,), **f32))
+    out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
+    sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
+    _check(lib.ttc_lqr_solve_cxt(ctypes.byref(prob), ctypes.byref(sol), _stream_ptr(stream)))
     return out

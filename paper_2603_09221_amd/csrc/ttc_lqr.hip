@@ -646,6 +646,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
 
 }  // namespace ttc
 #include "ttc_tv.hpp"
+#include "ttc_cxt.hpp"
 namespace ttc {
 
 // ------------------------------------------------------------------------------------------------
@@ -666,7 +667,7 @@ static int cu_count() {
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
 // (registers and LDS decide it); the table is the fallback when no device can be asked.
 enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4, KIND_TV_QUAD = 5,
-            KIND_ROLLOUT_TV = 6 };
+            KIND_ROLLOUT_TV = 6, KIND_CXT = 7 };
 static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
 template <int D>
 static int occupancy_of(Kind kind, bool bf16) {
@@ -676,6 +677,9 @@ static int occupancy_of(Kind kind, bool bf16) {
   if (kind == KIND_SOLVE_QUAD)  // the four-problems-per-wavefront kernel (d = 16 only)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
+  else if (kind == KIND_CXT)  // structured parameters (d = 16 only)
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<uint16_t>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<float>, nthr, 0);
   else if (kind == KIND_ROLLOUT_TV)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, float>, nthr, 0);
@@ -701,7 +705,7 @@ static int occupancy_of(Kind kind, bool bf16) {
   return nb;
 }
 static int blocks_per_cu(Kind kind, int d, bool bf16) {
-  static int cached[7][4][2];  // 0 = not asked yet
+  static int cached[8][4][2];  // 0 = not asked yet
   int& c = cached[kind][dindex(d)][bf16 ? 1 : 0];
   if (c > 0) return c;
   int nb = 0;
@@ -715,8 +719,8 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
     c = nb > 32 ? 32 : nb;
     return c;
   }
-  static const int table[7][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1},
-                                  {20, 8, 2, 1}, {8, 8, 2, 1},  {12, 4, 2, 1}};
+  static const int table[8][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1},
+                                  {20, 8, 2, 1}, {8, 8, 2, 1},  {12, 4, 2, 1}, {8, 8, 2, 1}};
   return table[kind][dindex(d)];
 }
 static long long grid_blocks(Kind kind, int d, bool bf16) {
@@ -1024,6 +1028,44 @@ ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solut
     e = bf16 ? ttc::launch_tv<uint16_t>(a, q->d, grid, st) : ttc::launch_tv<float>(a, q->d, grid, st);
   }
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+}
+
+ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_solution_t* solution, void* hip_stream) {
+  if (!q || !solution || q->n < 0 || q->T < 1 || q->r < 1 || q->d < 1 || q->flags != 0) return TTC_ERR_INVALID_ARG;
+  if (q->in_dtype != TTC_F32 && q->in_dtype != TTC_BF16) return TTC_ERR_INVALID_ARG;
+  if (q->d != 16 || q->r > ttc::CXT_RMAX) return TTC_ERR_UNSUPPORTED;
+  if (q->n == 0) return TTC_OK;
+  const void* ins[] = {q->sA, q->sB, q->sQ, q->sQf, q->rinv, q->lgA, q->lgB, q->lgQ, q->x0, q->Bbasis, q->Qbasis};
+  const size_t esz = q->in_dtype == TTC_BF16 ? 2 : 4;
+  for (const void* ptr : ins)
+    if (!ptr || !ttc::aligned_ptr(ptr, esz)) return TTC_ERR_INVALID_ARG;
+  if (!solution->u0) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
+  ttc::CxtArgs a;
+  a.s.n = q->n;
+  a.s.T = q->T;
+  a.s.flags = 0;
+  a.s.ngroups = q->T;
+  a.s.explicit_groups = 0;
+  a.s.A = a.s.B = a.s.Q = a.s.R = a.s.QT = nullptr;
+  a.s.x0 = q->x0;
+  a.s.sA = a.s.sB = a.s.sQ = a.s.sR = a.s.sQT = 0;
+  a.s.sx0 = q->d;
+  a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
+  a.s.info = solution->info;
+  a.s.ws = nullptr;
+  a.r = q->r;
+  a.sA = q->sA; a.sB = q->sB; a.sQ = q->sQ; a.sQf = q->sQf; a.rinv = q->rinv;
+  a.lgA = q->lgA; a.lgB = q->lgB; a.lgQ = q->lgQ;
+  a.Bbasis = q->Bbasis; a.Qbasis = q->Qbasis;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const long long gb = ttc::grid_blocks(ttc::KIND_CXT, 16, bf16);
+  const long long items = (q->n + 3) / 4;
+  const dim3 grid((unsigned)(items < gb ? items : gb));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (bf16) hipLaunchKernelGGL((ttc::solve_cxt_kernel<uint16_t>), grid, dim3(64), 0, st, a);
+  else hipLaunchKernelGGL((ttc::solve_cxt_kernel<float>), grid, dim3(64), 0, st, a);
+  return hipGetLastError() == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 
 const char* ttc_status_string(ttc_status_t status) {

@@ -141,3 +141,73 @@ def make_tv_batch(n: int, d: int, m: int, T: int, seed: int = 0, device="cpu", d
     b = make_batch(n * T, d, m, T, seed=seed, device=device, dtype=dtype)
     return LqrTvBatch(b.A.view(n, T, d, d), b.B.view(n, T, d, m), b.Q.view(n, T, d, d), b.R.view(n, T, m, m),
                       b.x0[:n].contiguous())
+
+
+@dataclass
+class ContextualBatch:
+    """n problems in the structured, contextualised parameterisation (Sec. 4): per-problem vectors
+    sA, rinv, lgA, lgB, lgQ (n,d), coefficients sB, sQ, sQf (n,r), x0 (n,d) and the two groups of basis
+    matrices Bbasis, Qbasis (r,d,d) shared by all problems."""
+    sA: torch.Tensor
+    sB: torch.Tensor
+    sQ: torch.Tensor
+    sQf: torch.Tensor
+    rinv: torch.Tensor
+    lgA: torch.Tensor
+    lgB: torch.Tensor
+    lgQ: torch.Tensor
+    Bbasis: torch.Tensor
+    Qbasis: torch.Tensor
+    x0: torch.Tensor
+    T: int
+
+    PER_PROBLEM = ("sA", "sB", "sQ", "sQf", "rinv", "lgA", "lgB", "lgQ")
+
+    @property
+    def n(self):
+        return self.sA.shape[0]
+
+    @property
+    def d(self):
+        return self.sA.shape[1]
+
+    @property
+    def r(self):
+        return self.sB.shape[1]
+
+    def take(self, index) -> "ContextualBatch":
+        kw = {k: getattr(self, k)[index] for k in self.PER_PROBLEM}
+        return ContextualBatch(Bbasis=self.Bbasis, Qbasis=self.Qbasis, x0=self.x0[index], T=self.T, **kw)
+
+    def numpy64(self):
+        """Stored values widened to float64 numpy arrays, in the oracle's argument order (x0 last)."""
+        f = lambda t: t.detach().to("cpu", torch.float64).numpy()
+        return tuple(f(getattr(self, k)) for k in self.PER_PROBLEM) + (f(self.Bbasis), f(self.Qbasis), f(self.x0))
+
+
+def make_contextual_batch(n: int, d: int, r: int, T: int, seed: int = 0, device="cpu",
+                          dtype: str = "f32") -> ContextualBatch:
+    """Draws standing in for the outputs of the layer's linear maps s_X(h_0) (no trained weights exist):
+        sA = 0.1 N(0,1)^d;  sB = N(0,1)^r / sqrt(r);  sQ, sQf = softplus(N(0,1)^r) / r;
+        rinv = softplus(N(0,1)^d);  lgA, lgB, lgQ = 0.25 softplus(N(0,1)^d);  x0 = N(0,1)^d;
+        Bbasis = N(0,1)^{r x d x d} / sqrt(d);  Qbasis[i] = Qc[i] Qc[i]^T / sqrt(d), Qc ~ N(0,1)^{r x d x d}.
+    Draw order: Bbasis, Qc, then sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, x0 for all problems."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    store = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+    rn = lambda *s: torch.randn(*s, generator=gen, device=dev, dtype=torch.float32)
+    sp = torch.nn.functional.softplus
+    Bb = rn(r, d, d) / d ** 0.5
+    Qc = rn(r, d, d)
+    Qb = Qc @ Qc.transpose(1, 2) / d ** 0.5
+    Qb = 0.5 * (Qb + Qb.transpose(1, 2))
+    sA = 0.1 * rn(n, d)
+    sB = rn(n, r) / r ** 0.5
+    sQ = sp(rn(n, r)) / r
+    sQf = sp(rn(n, r)) / r
+    rinv = sp(rn(n, d))
+    lgA, lgB, lgQ = (0.25 * sp(rn(n, d)) for _ in range(3))
+    x0 = rn(n, d)
+    c = lambda t: t.to(store).contiguous()
+    return ContextualBatch(c(sA), c(sB), c(sQ), c(sQf), c(rinv), c(lgA), c(lgB), c(lgQ), c(Bb), c(Qb), c(x0), T)

@@ -1,0 +1,122 @@
+"""GPU parity of the structured, contextualised solve (ttc_lqr_solve_cxt) against the CPU float64 oracle
+(oracle.lqr_oracle.contextual_solve: the parameters expanded to dense steps, then the recursion of Prop. 3.1),
+element by element on the same seeded inputs; 1e-4 for float32 inputs, 2e-2 for bfloat16 inputs (per problem,
+Frobenius / 2-norm)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lqr_oracle
+from paper_2603_09221_amd import binding, synth
+from tests.parity import rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL_F32, TOL_BF16 = 1e-4, 2e-2
+KEYS = synth.ContextualBatch.PER_PROBLEM + ("Bbasis", "Qbasis", "x0")
+
+
+def solve(b, **kw):
+    return binding.ttc_lqr_solve_cxt(*(getattr(b, k) for k in KEYS), b.T, **kw)
+
+
+def check(b, tol):
+    out = solve(b)
+    torch.cuda.synchronize()
+    assert int(out["info"].abs().max()) == 0
+    ref = lqr_oracle.contextual_solve(*b.numpy64(), b.T)
+    errs = {k: float(rel_err(out[k].cpu().numpy(), ref[k]).max()) for k in ("P0", "K0", "u0", "value")}
+    print({k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= tol, (k, v)
+    return out
+
+
+@pytest.mark.parametrize("n,r,T", [(1, 16, 1), (5, 16, 8), (1027, 16, 8), (300, 3, 33), (66, 64, 5), (130, 1, 2),
+                                    (64, 16, 128), (4098, 16, 16)])
+def test_ranks_horizons_and_ragged_batches(n, r, T):
+    check(synth.make_contextual_batch(n, 16, r, T, seed=n + r + T, device=DEV), TOL_F32)
+
+
+def test_bf16_inputs():
+    check(synth.make_contextual_batch(515, 16, 16, 8, seed=4, device=DEV, dtype="bf16"), TOL_BF16)
+    check(synth.make_contextual_batch(31, 16, 5, 32, seed=5, device=DEV, dtype="bf16"), TOL_BF16)
+
+
+def test_agrees_with_the_dense_time_heterogeneous_solve():
+    """The same problems handed over as dense steps to ttc_lqr_solve_tv."""
+    b = synth.make_contextual_batch(203, 16, 16, 12, seed=9, device=DEV)
+    out = solve(b)
+    A, B, Q, R = (torch.tensor(M, dtype=torch.float32, device=DEV)
+                  for M in lqr_oracle.contextual_parameters(*b.numpy64()[:-1], T=b.T))
+    tv = binding.ttc_lqr_solve_tv(A, B, Q, R, b.x0)
+    torch.cuda.synchronize()
+    for k in ("P0", "K0", "u0", "value"):
+        assert float(rel_err(out[k].cpu().numpy(), tv[k].cpu().numpy()).max()) <= 2e-5, k
+
+
+def test_breakdown_stays_with_its_problem():
+    """A negative entry of rinv makes R_t indefinite: S_T is not positive definite for that problem alone."""
+    b = synth.make_contextual_batch(777, 16, 16, 6, seed=11, device=DEV)
+    good = solve(b)
+    rinv = b.rinv.clone()
+    rinv[402] = -0.01                                     # R = -100 I
+    b.rinv = rinv
+    bad = solve(b)
+    torch.cuda.synchronize()
+    info = bad["info"].cpu().numpy()
+    assert info[402] == 1 and (np.delete(info, 402) == 0).all()
+    keep = torch.tensor([400, 401, 403, 776], device=DEV)
+    assert torch.equal(bad["u0"][keep], good["u0"][keep]) and torch.equal(bad["P0"][keep], good["P0"][keep])
+    for k in ("P0", "K0", "u0", "value"):
+        assert torch.isnan(bad[k][402]).all()
+
+
+def test_optional_outputs_and_empty_batch():
+    b = synth.make_contextual_batch(50, 16, 16, 7, seed=2, device=DEV)
+    full = solve(b)
+    part = solve(b, want_P0=False, want_K0=False)
+    torch.cuda.synchronize()
+    assert "P0" not in part and "K0" not in part
+    assert torch.equal(part["u0"], full["u0"]) and torch.equal(part["value"], full["value"])
+    e = synth.make_contextual_batch(0, 16, 16, 7, seed=2, device=DEV)
+    out = solve(e)
+    assert out["u0"].shape == (0, 16)
+
+
+def test_no_modulation_is_the_time_invariant_problem():
+    """lg = 0: every step carries the same A, B, Q, R: the time-invariant oracle applies, and ttc_lqr_solve takes
+    the same problems as dense matrices (its re-based symplectic product is looser on these inputs, whose R^{-1}
+    is not the one its group schedule was tuned on)."""
+    b = synth.make_contextual_batch(90, 16, 16, 9, seed=6, device=DEV)
+    z = torch.zeros_like(b.lgA)
+    b.lgA, b.lgB, b.lgQ = z, z, z
+    out = solve(b)
+    eye = torch.eye(16, device=DEV)
+    A = eye + torch.diag_embed(b.sA)
+    B = torch.einsum("ni,ijk->njk", b.sB, b.Bbasis)
+    Q = torch.einsum("ni,ijk->njk", b.sQ, b.Qbasis)
+    QT = torch.einsum("ni,ijk->njk", b.sQf, b.Qbasis)
+    R = torch.diag_embed(1.0 / b.rinv)
+    ti = binding.ttc_lqr_solve(A, B, Q, R, QT, b.x0, b.T)
+    torch.cuda.synchronize()
+    f = lambda t: t.cpu().double().numpy()
+    ref = lqr_oracle.riccati_solve(f(A), f(B), f(Q), f(R), f(QT), f(b.x0), b.T)
+    for k in ("P0", "K0", "u0", "value"):
+        assert float(rel_err(out[k].cpu().numpy(), ref[k]).max()) <= TOL_F32, k
+        assert float(rel_err(ti[k].cpu().numpy(), ref[k]).max()) <= 1e-3, k
+
+
+def test_full_size_sample():
+    """1M problems (batch 8 x 16 heads x 8192 tokens), r = 16, T = 8, in the launch configuration the benchmark
+    times; 2048 sampled problems against the oracle, all outputs finite."""
+    n = 8 * 16 * 8192
+    b = synth.make_contextual_batch(n, 16, 16, 8, seed=0, device=DEV)
+    out = solve(b)
+    torch.cuda.synchronize()
+    assert int(out["info"].abs().max()) == 0
+    assert bool(torch.isfinite(out["u0"]).all()) and bool(torch.isfinite(out["P0"]).all())
+    idx = torch.randperm(n, generator=torch.Generator().manual_seed(1))[:2048].sort().values.to(DEV)
+    ref = lqr_oracle.contextual_solve(*b.take(idx).numpy64(), b.T)
+    for k in ("P0", "K0", "u0", "value"):
+        assert float(rel_err(out[k][idx].cpu().numpy(), ref[k]).max()) <= TOL_F32, k
