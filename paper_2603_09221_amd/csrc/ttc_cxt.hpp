@@ -7,8 +7,9 @@
 // and runs the Riccati step of Prop. 3.1 on them.  A diagonal A_t turns two of the step's products into
 // scalings:  with V = P B_t (P = P_{t}, symmetric) and a = diag(A_t),
 //     S = R + B_t^T V,   F = B_t^T P A_t = V^T diag(a),   A_t^T P A_t = diag(a) P diag(a),
-//     W = S^{-1} F = -K,   P_{t-1} = Q_{t-1} + diag(a) P diag(a) - F^T W,
-// three products and one positive definite solve per step.  Four problems share a wavefront, as in the
+//     K = -S^{-1} F,   P_{t-1} = Q_{t-1} + diag(a) P diag(a) + F^T K,
+// four products and one inverse of a positive definite matrix per step (S^{-1} is formed in place, half
+// the eliminations of a solve with sixteen right-hand sides; the product S^{-1} F goes to the matrix cores).  Four problems share a wavefront, as in the
 // other d = 16 kernels.  At d = 16 the accumulator layout of a matrix (lane (i, g): column i, rows
 // 4g..4g+3) is the A-operand layout of its transpose, which is what lets Bbar, V and P be used in both
 // roles without a trip through LDS.
@@ -25,14 +26,22 @@ struct CxtArgs {
   const void *Bbasis, *Qbasis;                              // (r,16,16), shared by all problems
 };
 
+#ifndef TTC_CXT_WAVES
+#define TTC_CXT_WAVES 2  // wavefronts per SIMD the register allocation aims at
+#endif
 template <typename TIn>
-__global__ void __launch_bounds__(64) solve_cxt_kernel(const CxtArgs ca) {
+__global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtArgs ca) {
   constexpr int D = 16;
   using C = Cfg<D>;
   constexpr int PPW = 4;
   __shared__ __attribute__((aligned(16))) float Wm[PPW][D * C::PITCH];
-  __shared__ __attribute__((aligned(16))) float vec[PPW][4][D];         // a_t, gamma_B^t, gamma_Q^(t-1), 1/rinv
-  __shared__ __attribute__((aligned(16))) float coef[PPW][3][CXT_RMAX];  // s_B, s_Q, s_Qf
+  // Wm[q]: left half S and then S^{-1} (at the end P_0), right half the value matrix between steps
+  constexpr int PT = D + 4;                                              // row pitch of Vt
+  __shared__ __attribute__((aligned(16))) float Vt[PPW][D * PT];         // V^T; during set-up: s_B, s_Q, s_Qf
+  static_assert(PPW * D * PT >= PPW * 3 * CXT_RMAX, "the coefficients are staged in Vt");
+  float (*const coef)[3][CXT_RMAX] = reinterpret_cast<float (*)[3][CXT_RMAX]>(&Vt[0][0]);
+  __shared__ __attribute__((aligned(16))) float vecs[2][PPW][4][D];      // a_t, gamma_B^t, gamma_Q^(t-1), 1/rinv;
+                                                                         // steps alternate between the two copies
   __shared__ float s_red[C::NW];
   const SolveArgs& p = ca.s;
   const int r = ca.r;
@@ -61,13 +70,14 @@ __global__ void __launch_bounds__(64) solve_cxt_kernel(const CxtArgs ca) {
         if (!info[q] && ((m >> (16 * q)) & 0xFFFFull)) info[q] = nsolve;
     };
 
+    PhaseTimers tm;  // phases: 0 set-up, 1 dense solves, 2 products and scalings, 3 outputs
     // ---- per-problem vectors: lane (i, g) keeps entry i of problem g's
     const long long pg = (quad * PPW + g < p.n) ? quad * PPW + g : p.n - 1;
     const float sA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sA), pg * D + i);
     const float lgA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgA), pg * D + i);
     const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgB), pg * D + i);
     const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgQ), pg * D + i);
-    vec[g][3][i] = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(ca.rinv), pg * D + i);
+    vecs[0][g][3][i] = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(ca.rinv), pg * D + i);
     for (int k = i; k < r; k += 16) {
       coef[g][0][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sB), pg * r + k);
       coef[g][1][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQ), pg * r + k);
@@ -76,137 +86,167 @@ __global__ void __launch_bounds__(64) solve_cxt_kernel(const CxtArgs ca) {
     __syncthreads();
 
     // ---- Bbar, Qbar, Q_T in the accumulator layout: element (4g+v, i) of each of the four problems
-    floatx4 Bbar[PPW], Qbar[PPW];
+    floatx4 Bbar[PPW], Qbar[PPW], pn[PPW][C::RB][C::NT];
     float rI[PPW];
-    {
-      floatx4 Qf[PPW];
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) {
+      Bbar[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+      Qbar[q] = Bbar[q];
+      pn[q][0][0] = Bbar[q];
+      rI[q] = vecs[0][q][3][i];
+    }
+#pragma unroll 2
+    for (int k = 0; k < r; ++k) {
+      floatx4 bb, qb;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        bb[v] = ld1<TIn>(Bbasis, (long)k * D * D + (4 * g + v) * D + i);
+        qb[v] = ld1<TIn>(Qbasis, (long)k * D * D + (4 * g + v) * D + i);
+      }
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
-        Bbar[q] = floatx4{0.f, 0.f, 0.f, 0.f};
-        Qbar[q] = Bbar[q];
-        Qf[q] = Bbar[q];
-        rI[q] = vec[q][3][i];
-      }
-#pragma unroll 2
-      for (int k = 0; k < r; ++k) {
-        floatx4 bb, qb;
+        const float cb = coef[q][0][k], cq = coef[q][1][k], cf = coef[q][2][k];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          bb[v] = ld1<TIn>(Bbasis, (long)k * D * D + (4 * g + v) * D + i);
-          qb[v] = ld1<TIn>(Qbasis, (long)k * D * D + (4 * g + v) * D + i);
-        }
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          const float cb = coef[q][0][k], cq = coef[q][1][k], cf = coef[q][2][k];
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            Bbar[q][v] += cb * bb[v];
-            Qbar[q][v] += cq * qb[v];
-            Qf[q][v] += cf * qb[v];
-          }
+          Bbar[q][v] += cb * bb[v];
+          Qbar[q][v] += cq * qb[v];
+          pn[q][0][0][v] += cf * qb[v];  // P_T = Q_T
         }
       }
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q] + D, reinterpret_cast<floatx4(&)[1]>(Qf[q]), w, i, g);  // P_T = Q_T
     }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-    __syncthreads();
-
-    for (int s = p.T - 1; s >= 0; --s) {  // step s is the paper's t = s + 1; it turns P_t into P_{t-1}
+    // the modulation of step s (the paper's t = s + 1), entry i of problem g: a_t, gamma_B^t, gamma_Q^(t-1)
+    auto write_vec = [&](int s) {
       const float tf = (float)(s + 1);
+      float (*vec)[4][D] = vecs[s & 1];
       vec[g][0][i] = 1.f + expf(-tf * lgA_m) * sA_m;
       vec[g][1][i] = expf(-tf * lgB_m);
-      vec[g][2][i] = expf(-(float)s * lgQ_m);  // for Q_{t-1}
-      float cP[PPW][C::RB][C::KS];
+      vec[g][2][i] = expf(-(float)s * lgQ_m);
+    };
+    // a 16 x 16 matrix in LDS: written from the accumulator layout, read back a row
+    // per lane, which is the accumulator layout of the transpose
+    auto put_acc = [&](float* M, int pitch, const floatx4& x) {
 #pragma unroll
-      for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q] + D, cP[q], w, i, g);  // rows of P
-      __syncthreads();
-      float aI[PPW], qI[PPW];
-      floatx4 aG[PPW], qG[PPW];
-      floatx4 pn[PPW][C::RB][C::NT];
-      float cBT[PPW][C::RB][C::KS];
+      for (int v = 0; v < 4; ++v) M[(4 * g + v) * pitch + i] = x[v];
+    };
+    auto get_row = [&](const float* M, int pitch) { return *reinterpret_cast<const floatx4*>(M + i * pitch + 4 * g); };
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) put_acc(Wm[q] + D, C::PITCH, pn[q][0][0]);
+    write_vec(p.T - 1);
+    __syncthreads();
+    tm.toc(0);
+
+    for (int s = p.T - 1; s >= 0; --s) {  // step s turns P_t (pn, also in LDS) into P_{t-1}
+      const float (*vec)[4][D] = vecs[s & 1];
+      float cP[PPW][C::RB][C::KS], cBT[PPW][C::RB][C::KS], cFT[PPW][C::RB][C::KS];
+      floatx4 aG[PPW];
+      floatx4 accVT[PPW][C::RB][C::NT];
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
-        aI[q] = vec[q][0][i];
-        qI[q] = vec[q][2][i];
+        const floatx4 pt = get_row(Wm[q] + D, C::PITCH);  // P[i][4g+v]; pn holds P[4g+v][i]
+        const float aI = vec[q][0][i], bI = vec[q][1][i];
         aG[q] = *reinterpret_cast<const floatx4*>(&vec[q][0][4 * g]);
-        qG[q] = *reinterpret_cast<const floatx4*>(&vec[q][2][4 * g]);
-        const float bI = vec[q][1][i];
-        floatx4 bt[1];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          bt[0][v] = Bbar[q][v] * bI;                    // B_t: column i scaled
-          cBT[q][0][v] = bt[0][v];                       // = rows of B_t^T as the A operand
-          pn[q][0][0][v] = aG[q][v] * cP[q][0][v] * aI[q];  // diag(a) P diag(a): P is symmetric
+          cP[q][0][v] = 0.5f * (pn[q][0][0][v] + pt[v]);   // symmetric part: both the rows of P as the A
+                                                          // operand and P in the accumulator layout
+          cBT[q][0][v] = Bbar[q][v] * bI;                  // B_t (column i scaled) = rows of B_t^T as the A operand
+          pn[q][0][0][v] = aG[q][v] * cP[q][0][v] * aI;    // diag(a) P diag(a)
         }
-        store_rows<D>(Wm[q], bt, w, i, g);
+        zero_acc<D>(accVT[q]);
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t)  // V^T = B_t^T P; P symmetric: its B operand is cP itself
+#pragma unroll
+        for (int q = 0; q < PPW; ++q)
+          accVT[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cBT[q][0][t], cP[q][0][t], accVT[q][0][0], 0, 0, 0);
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+        const float aI = vec[q][0][i];
+        put_acc(Vt[q], PT, accVT[q][0][0]);  // V^T[4g+v][i] = V[i][4g+v]
+#pragma unroll
+        for (int v = 0; v < 4; ++v) cFT[q][0][v] = -aI * accVT[q][0][0][v];  // rows of -F^T = -diag(a) V
       }
       __syncthreads();
-      floatx4 accV[PPW][C::RB][C::NT];
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) zero_acc<D>(accV[q]);
-      gemm_acc_quad(accV, cP, Wm, 0, i, g);  // V = P B_t
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q] + D, accV[q], w, i, g);  // every lane has its rows of P
-      __syncthreads();
-      float cFT[PPW][C::RB][C::KS];
+      floatx4 accW[PPW][C::RB][C::NT];
       {
         floatx4 accS[PPW][C::RB][C::NT];
-        float Fa[PPW][C::RB][C::KS];
+        floatx4 bV[PPW];
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
-          load_aop_lds<D>(Wm[q] + D, cFT[q], w, i, g);  // rows of V
+          bV[q] = get_row(Vt[q], PT);  // V[4g+t][i]
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            cFT[q][0][v] *= -aI[q];                     // rows of -F^T = -diag(a) V
-            Fa[q][0][v] = accV[q][0][0][v] * aG[q][v];  // rows of F = V^T diag(a)
-            accS[q][0][0][v] = (4 * g + v == i) ? rI[q] : 0.f;
-          }
+          for (int v = 0; v < 4; ++v) accS[q][0][0][v] = (4 * g + v == i) ? rI[q] : 0.f;
         }
-        gemm_acc_quad(accS, cBT, Wm, D, i, g);  // S = R + B_t^T V
-        __syncthreads();
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          store_rows<D>(Wm[q], accS[q], w, i, g);
-          store_aop_lds<D>(Wm[q] + D, Fa[q], w, i, g);
-        }
-        __syncthreads();
+        for (int t = 0; t < 4; ++t)  // S = R + B_t^T V
+#pragma unroll
+          for (int q = 0; q < PPW; ++q)
+            accS[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cBT[q][0][t], bV[q][t], accS[q][0][0], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], accS[q], w, i, g);
       }
-      note(solve_rows16<false>(Wmine, lane));  // right halves: W = S^{-1} F = -K
-      gemm_acc_quad(pn, cFT, Wm, D, i, g);     // - F^T W
       __syncthreads();
+      tm.toc(2);
+      note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
+      tm.toc(1);
+      {
+        float cSi[PPW][C::RB][C::KS];
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          load_aop_lds<D>(Wm[q], cSi[q], w, i, g);  // rows of S^{-1}
+          zero_acc<D>(accW[q]);
+        }
+        // cFT holds -F^T in the A-operand layout, which is the accumulator layout of -F: B operand of W
+#pragma unroll
+        for (int t = 0; t < 4; ++t)  // K = -W = S^{-1} (-F)
+#pragma unroll
+          for (int q = 0; q < PPW; ++q)
+            accW[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cSi[q][0][t], cFT[q][0][t], accW[q][0][0], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)  // P += (-F^T) W: the accumulator layout of W = -K is its B operand
+#pragma unroll
+          for (int q = 0; q < PPW; ++q)
+            pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cFT[q][0][t], -accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
+      }
       if (s >= 1) {
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
+          const float qI = vec[q][2][i];
+          const floatx4 qG = *reinterpret_cast<const floatx4*>(&vec[q][2][4 * g]);
 #pragma unroll
-          for (int v = 0; v < 4; ++v) pn[q][0][0][v] += qG[q][v] * Qbar[q][v] * qI[q];  // + Q_{t-1}
-          store_rows<D>(Wm[q] + D, pn[q], w, i, g);
+          for (int v = 0; v < 4; ++v) pn[q][0][0][v] += qG[v] * Qbar[q][v] * qI;  // + Q_{t-1}
+          put_acc(Wm[q] + D, C::PITCH, pn[q][0][0]);
         }
+        write_vec(s - 1);
         __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-        __syncthreads();
+        tm.toc(2);
       } else {
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], pn[q], w, i, g);  // P_0 (no cost on x_0)
+        for (int q = 0; q < PPW; ++q) put_acc(Wm[q] + D, C::PITCH, pn[q][0][0]);  // P_0 (no cost on x_0)
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
+        for (int q = 0; q < PPW; ++q) {
+          const floatx4 pt = get_row(Wm[q] + D, C::PITCH);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) pn[q][0][0][v] = 0.5f * (pn[q][0][0][v] + pt[v]);
+          store_rows<D>(Wm[q], pn[q], w, i, g);  // symmetric P_0
+        }
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
           if (!valid[q]) continue;  // uniform over the wavefront
           const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
           floatx4 acc[C::RB][C::NT];
-          load_rows<D>(Wm[q] + D, acc, w, i, g);  // rows of -K_0
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[0][0][v] = -accW[q][0][0][v];  // rows of -K_0
           emit_gain<D, TIn>(p, prob[q], acc, x0p, info[q], tid);
           emit_value<D, TIn>(p, prob[q], Wm[q], static_cast<const TIn*>(nullptr), x0p, info[q], s_red, tid);
         }
         __syncthreads();
+        tm.toc(3);
       }
     }
+    if (quad + gridDim.x >= nquads) tm.dump(reinterpret_cast<long long*>(p.P0) + p.n * (D * D / 2));
   }
 }
 

@@ -28,7 +28,8 @@ __device__ __forceinline__ uint32_t row16_max_u32(uint32_t x) {
 // of a column is found by a 16-lane DPP max of a packed key (|value| with the row index in the low
 // mantissa bits), the pivot row is broadcast with ds_bpermute, every other row of that problem is
 // eliminated.  Rows never move; the row that was the pivot of column c ends up as row c of X, written
-// to the right half.  PIVOT = false takes the diagonal (symmetric positive definite M).
+// to the right half.  PIVOT = false takes the diagonal (symmetric positive definite M); the pivot row is
+// then known at compile time and is broadcast by DPP (row_newbcast) instead.
 // Returns, per lane, whether its problem broke down (zero / non-finite / non-positive pivot).
 template <bool PIVOT>
 __device__ __forceinline__ int solve_rows16(float* Wq, int lane) {
@@ -57,23 +58,32 @@ __device__ __forceinline__ int solve_rows16(float* Wq, int lane) {
     } else {
       pr = j;
     }
-    const int src = ((lane & 48) | pr) << 2;  // byte address of the pivot row's lane
     float prow[32];
-    static_for<j, 32>([&](auto K) {
-      constexpr int k = decltype(K)::value;
-      prow[k] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, a[k])));
-    });
+    if constexpr (PIVOT) {
+      const int src = ((lane & 48) | pr) << 2;  // byte address of the pivot row's lane
+      static_for<j, 32>([&](auto K) {
+        constexpr int k = decltype(K)::value;
+        prow[k] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, a[k])));
+      });
+    } else {
+      // the pivot row is lane j of every row of 16 lanes: a DPP broadcast within the row, no LDS crossbar
+      static_for<j, 32>([&](auto K) {
+        constexpr int k = decltype(K)::value;
+        prow[k] = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, a[k]), 0x150 + j, 0xF, 0xF,
+                                                                      true));  // row_newbcast:j
+      });
+    }
     const float pv = prow[j];
     const float apv = PIVOT ? fabsf(pv) : pv;
     if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
     const bool mine = (r == pr);
-    const float l = mine ? 0.f : a[j] * __builtin_amdgcn_rcpf(pv);
+    const float nl = mine ? 0.f : -a[j] * __builtin_amdgcn_rcpf(pv);
     act = act && !mine;
     myj = mine ? j : myj;
     mypiv = mine ? pv : mypiv;
     static_for<j + 1, 32>([&](auto K) {
       constexpr int k = decltype(K)::value;
-      a[k] -= l * prow[k];  // l = 0 for the pivot row itself
+      a[k] = __builtin_fmaf(prow[k], nl, a[k]);  // nl = 0 for the pivot row itself
     });
   });
   const float s = __builtin_amdgcn_rcpf(mypiv);
@@ -82,6 +92,54 @@ __device__ __forceinline__ int solve_rows16(float* Wq, int lane) {
     floatx4 t;
     t[0] = a[16 + 4 * k + 0] * s; t[1] = a[16 + 4 * k + 1] * s; t[2] = a[16 + 4 * k + 2] * s; t[3] = a[16 + 4 * k + 3] * s;
     *reinterpret_cast<floatx4*>(Wq + myj * C::PITCH + 16 + 4 * k) = t;
+  }
+  __syncthreads();
+  return bad;
+}
+
+// In-place inverses of the four symmetric positive definite 16 x 16 matrices in the left halves of
+// Wm[q] (row r at Wq + r*PITCH), all at once, a lane holding one row: Gauss-Jordan without pivoting on
+// [M | I], where the column of the right part that becomes non-trivial at step j takes the place of
+// column j of M, which has just become a unit vector.  Rows are scaled by their pivots at the end.
+// The pivot row is broadcast within each row of 16 lanes by DPP.  The caller synchronises before (M
+// complete in LDS); the function ends with a barrier.  Returns, per lane, whether its problem broke
+// down (a pivot that is not positive and finite).
+__device__ __forceinline__ int invert_rows16(float* Wq, int lane) {
+  using C = Cfg<16>;
+  const int r = lane & 15;
+  float a[16];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const floatx4 t = *reinterpret_cast<const floatx4*>(Wq + r * C::PITCH + 4 * k);
+    a[4 * k + 0] = t[0]; a[4 * k + 1] = t[1]; a[4 * k + 2] = t[2]; a[4 * k + 3] = t[3];
+  }
+  float mypiv = 1.f;
+  int bad = 0;
+  static_for<0, 16>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    float prow[16];
+    static_for<0, 16>([&](auto K) {
+      constexpr int k = decltype(K)::value;
+      prow[k] = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, a[k]), 0x150 + j, 0xF, 0xF,
+                                                                    true));  // row_newbcast:j
+    });
+    const float pv = prow[j];
+    if (!(pv > 0.f && pv < __builtin_inff())) bad = 1;
+    const bool mine = (r == j);
+    const float nl = mine ? 0.f : -a[j] * __builtin_amdgcn_rcpf(pv);
+    mypiv = mine ? pv : mypiv;
+    static_for<0, 16>([&](auto K) {
+      constexpr int k = decltype(K)::value;
+      if constexpr (k != j) a[k] = __builtin_fmaf(prow[k], nl, a[k]);  // nl = 0 for the pivot row itself
+    });
+    a[j] = mine ? 1.f : nl;  // column j of the right part
+  });
+  const float s = __builtin_amdgcn_rcpf(mypiv);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    floatx4 t;
+    t[0] = a[4 * k + 0] * s; t[1] = a[4 * k + 1] * s; t[2] = a[4 * k + 2] * s; t[3] = a[4 * k + 3] * s;
+    *reinterpret_cast<floatx4*>(Wq + r * C::PITCH + 4 * k) = t;
   }
   __syncthreads();
   return bad;
