@@ -7,7 +7,7 @@ Prints ONE JSON line: problems/s plus a roofline object for the solve kernel (fp
 oracle timed on the host cores on a bounded sample of the same inputs.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llm_adapter] [--n N] [--rebase-every k]
-                    [--path symplectic|doubling|tv]
+                    [--path symplectic|doubling|tv|cxt]
 
 The headline value is the paper's sequential symplectic product (--path symplectic, the default); the same
 inputs are also timed on the squaring path and reported under "other_path".
@@ -74,6 +74,98 @@ def alg_flops_tv(d, T):
     return T * (12 + 7.0 / 3) * d ** 3
 
 
+def alg_flops_cxt(d, r, T):
+    """Algorithmic flops of one structured problem (ttc_lqr_solve_cxt): combining the bases (three sums of r
+    matrices, 2 r d^2 each), then per step four products (P B, B^T V, S^{-1} F, F^T K: 2 d^3 each) and the
+    in-place inverse of S (2 d^3); the diagonal scalings are O(d^2) and not counted."""
+    return 6 * r * d * d + T * 10 * d ** 3
+
+
+def bench_cxt(args):
+    """The structured, contextualised layer shape of the paper's language-model runs: d = 16, 16 heads, r = 16
+    basis matrices, horizon 8 (the mean of its training horizons); batch 8 x 16 heads x 8192 tokens."""
+    import numpy as np
+    import torch
+    from paper_2603_09221_amd import binding, synth
+    from tests.parity import rel_err
+
+    d, r, T = 16, 16, args.horizon or 8
+    n = args.n or 8 * 16 * 8192
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    binding.load()
+    b = synth.make_contextual_batch(n, d, r, T, seed=0, device=dev)
+    keys = synth.ContextualBatch.PER_PROBLEM + ("Bbasis", "Qbasis", "x0")
+    ins = [getattr(b, k) for k in keys]
+    out = {"P0": torch.empty((n, d, d), dtype=torch.float32, device=dev),
+           "K0": torch.empty((n, d, d), dtype=torch.float32, device=dev),
+           "u0": torch.empty((n, d), dtype=torch.float32, device=dev),
+           "value": torch.empty((n,), dtype=torch.float32, device=dev),
+           "info": torch.empty((n,), dtype=torch.int32, device=dev)}
+    stream = torch.cuda.current_stream()
+    step = lambda: binding.ttc_lqr_solve_cxt(*ins, T, out=out, stream=stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record(stream)
+        step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps
+    kernel_s = sum(e0.elapsed_time(e1) for e0, e1 in evs) / len(evs) / 1e3
+    assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
+    flops_pp = alg_flops_cxt(d, r, T)
+    achieved = flops_pp * n / kernel_s / 1e12
+    in_bytes = n * (6 * d + 3 * r) * 4 + 2 * r * d * d * 4
+    out_bytes = n * (2 * d * d + d + 2) * 4
+    key = ("ttc_layer_d16", T)
+    res = {
+        "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d, structured parameters" % (d, T),
+        "value": n / wall, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "ttc_layer_d16", "problems": n, "d": d, "m": d, "r": r, "T": T, "input_dtype": "f32",
+                   "path": "cxt", "outputs": "P0,K0,u0,value"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[key] * n
+                                 if key in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
+                     "kernel": "solve_cxt_kernel", "kernel_ms": kernel_s * 1e3, "alg_flops_per_problem": flops_pp,
+                     "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / kernel_s / 1e12,
+                     "alg_bytes_per_launch": in_bytes + out_bytes,
+                     "alg_GBps": (in_bytes + out_bytes) / kernel_s / 1e9},
+    }
+    if not args.no_cpu:
+        from concurrent.futures import ThreadPoolExecutor
+        from oracle import lqr_oracle
+        cores = min(16, os.cpu_count() or 1)
+
+        def run(sample):
+            a = b.take(slice(0, sample)).numpy64()
+            chunks = [ix for ix in np.array_split(np.arange(sample), cores * 4) if len(ix)]
+
+            def work(ix):
+                r_ = lqr_oracle.contextual_solve(*(x[ix] for x in a[:8]), a[8], a[9], a[10][ix], T)
+                return {k: r_[k] for k in ("P0", "K0", "u0", "value")}
+            t1 = time.perf_counter()
+            with ThreadPoolExecutor(max_workers=cores) as ex:
+                parts = list(ex.map(work, chunks))
+            return {k: np.concatenate([p_[k] for p_ in parts]) for k in parts[0]}, time.perf_counter() - t1
+        pilot = min(n, 4096)
+        _, pdt = run(pilot)
+        sample = min(n, args.cpu_sample or int(max(pilot, pilot * 15.0 / max(pdt, 1e-3))))
+        ref, dt = run(sample)
+        errs = {k: float(rel_err(out[k][:sample].cpu().numpy(), ref[k]).max()) for k in ("P0", "K0", "u0", "value")}
+        res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": cores, "kind": "oracle",
+                               "sample": "first %d problems of the same workload, float64 numpy (parameters "
+                                         "expanded to dense steps, then Riccati), %.1f s wall" % (sample, dt)}
+        res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": 1e-4}
+    print(json.dumps(res))
+
+
 def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):
     """The oracle, as it stands, on the host cores: one problem chunk per thread, BLAS single-threaded."""
     import numpy as np
@@ -115,11 +207,14 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="llm_adapter")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv"),
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
                          "doubling: the long-horizon path, the same product formed by squaring; "
                          "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
-                         "every step with its own A, B, Q, R (default 16384 problems)")
+                         "every step with its own A, B, Q, R (default 16384 problems); "
+                         "cxt: structured, contextualised parameters (ttc_lqr_solve_cxt) at d = 16, r = 16, "
+                         "1048576 problems, --config ignored")
+    ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt path (default 8)")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
     ap.add_argument("--rebase-every", type=int, default=0, help="0 = library default")
@@ -133,6 +228,9 @@ def main():
         print("bench.py: this build runs on one GPU only (problems are independent: a multi-GPU run would split "
               "the batch and exchange nothing). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+
+    if args.path == "cxt":
+        return bench_cxt(args)
 
     import numpy as np
     import torch

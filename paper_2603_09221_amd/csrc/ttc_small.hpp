@@ -117,21 +117,40 @@ __device__ __forceinline__ int invert_rows16(float* Wq, int lane) {
   int bad = 0;
   static_for<0, 16>([&](auto J) {
     constexpr int j = decltype(J)::value;
-    float prow[16];
-    static_for<0, 16>([&](auto K) {
-      constexpr int k = decltype(K)::value;
-      prow[k] = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, a[k]), 0x150 + j, 0xF, 0xF,
-                                                                    true));  // row_newbcast:j
-    });
-    const float pv = prow[j];
+    const float pv = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, a[j]), 0x150 + j, 0xF, 0xF,
+                                                                         true));  // row_newbcast:j: the pivot
     if (!(pv > 0.f && pv < __builtin_inff())) bad = 1;
     const bool mine = (r == j);
-    const float nl = mine ? 0.f : -a[j] * __builtin_amdgcn_rcpf(pv);
+    const float nl = mine ? 0.f : -a[j] * __builtin_amdgcn_rcpf(pv);  // 0 for the pivot row itself
     mypiv = mine ? pv : mypiv;
-    static_for<0, 16>([&](auto K) {
-      constexpr int k = decltype(K)::value;
-      if constexpr (k != j) a[k] = __builtin_fmaf(prow[k], nl, a[k]);  // nl = 0 for the pivot row itself
-    });
+    // a[k] += nl * (a[k] of the pivot row, lane j of this row of 16 lanes), k != j: the broadcast rides on the
+    // multiply-add as its DPP operand.  Written as one block so that the wait states a DPP read needs after a
+    // vector write of the same register are in our hands: within the block every instruction touches its own
+    // register, and the block starts and ends with the two idle states.
+#define TTC_AK(n) a[(n) < j ? (n) : (n) + 1]  // the 15 registers other than a[j], in ascending order
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %4, %4, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %5, %5, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %6, %6, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %7, %7, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %8, %8, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %9, %9, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %10, %10, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %11, %11, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %12, %12, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %13, %13, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %14, %14, %15 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(TTC_AK(0)), "+v"(TTC_AK(1)), "+v"(TTC_AK(2)), "+v"(TTC_AK(3)), "+v"(TTC_AK(4)), "+v"(TTC_AK(5)),
+          "+v"(TTC_AK(6)), "+v"(TTC_AK(7)), "+v"(TTC_AK(8)), "+v"(TTC_AK(9)), "+v"(TTC_AK(10)), "+v"(TTC_AK(11)),
+          "+v"(TTC_AK(12)), "+v"(TTC_AK(13)), "+v"(TTC_AK(14))
+        : "v"(nl), "n"(j));
+#undef TTC_AK
     a[j] = mine ? 1.f : nl;  // column j of the right part
   });
   const float s = __builtin_amdgcn_rcpf(mypiv);
