@@ -103,6 +103,12 @@ def bench_cxt(args):
            "value": torch.empty((n,), dtype=torch.float32, device=dev),
            "info": torch.empty((n,), dtype=torch.int32, device=dev)}
     stream = torch.cuda.current_stream()
+    if args.calib_copy_mib:
+        src = torch.ones((args.calib_copy_mib << 18,), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
     step = lambda: binding.ttc_lqr_solve_cxt(*ins, T, out=out, stream=stream)
     for _ in range(args.warmup):
         step()

@@ -310,8 +310,7 @@ __global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
     __syncthreads();
     for (int s = p.T - 1; s >= 0; --s) {
       // the step of riccati_step, for four problems at once
-      floatx4 pn[PPW][C::RB][C::NT];
-      float cFT[PPW][C::RB][C::KS];
+      floatx4 pn[PPW][C::RB][C::NT], accF[PPW][C::RB][C::NT], accW[PPW][C::RB][C::NT];
       {
         float cAT[PPW][C::RB][C::KS], cBT[PPW][C::RB][C::KS];
         {
@@ -347,7 +346,7 @@ __global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
           }
           __syncthreads();
         }
-        floatx4 accS[PPW][C::RB][C::NT], accF[PPW][C::RB][C::NT];
+        floatx4 accS[PPW][C::RB][C::NT];
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
           load_rows_input<D, TIn>(Rp[q] + (long long)s * ta.tR, accS[q], w, i, g);
@@ -359,24 +358,32 @@ __global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
         gemm_acc_quad(pn, cAT, Wm, 0, i, g);    // A^T P A
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          store_rows<D>(Wm[q], accS[q], w, i, g);
-          store_rows<D>(Wm[q] + D, accF[q], w, i, g);
-        }
+        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], accS[q], w, i, g);
         __syncthreads();
       }
 #pragma unroll
-      for (int q = 0; q < PPW; ++q) {
-        symmetrise_half<D>(Wm[q], tid);  // R is read as its symmetric part
-        load_aopT_lds<D>(Wm[q] + D, cFT[q], w, i, g);  // rows of F^T
-      }
+      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);  // R is read as its symmetric part
       __syncthreads();
-      note(solve_rows16<false>(Wmine, lane));  // right halves: W = S^{-1} F = -K_s
+      note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
+      {
+        // At d = 16 the accumulator layout of F is both the B operand of F and the A operand of F^T.
+        float cSi[PPW][C::RB][C::KS];
 #pragma unroll
-      for (int q = 0; q < PPW; ++q)
+        for (int q = 0; q < PPW; ++q) {
+          load_aop_lds<D>(Wm[q], cSi[q], w, i, g);  // rows of S^{-1}
+          zero_acc<D>(accW[q]);
+        }
 #pragma unroll
-        for (int k = 0; k < C::KS; ++k) cFT[q][0][k] = -cFT[q][0][k];
-      gemm_acc_quad(pn, cFT, Wm, D, i, g);  // - F^T W
+        for (int t = 0; t < 4; ++t)  // W = S^{-1} F = -K_s
+#pragma unroll
+          for (int q = 0; q < PPW; ++q)
+            accW[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cSi[q][0][t], accF[q][0][0][t], accW[q][0][0], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)  // - F^T W
+#pragma unroll
+          for (int q = 0; q < PPW; ++q)
+            pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(-accF[q][0][0][t], accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
+      }
       __syncthreads();
       if (s >= 1) {
 #pragma unroll
@@ -407,9 +414,7 @@ __global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
         for (int q = 0; q < PPW; ++q) {
           if (!valid[q]) continue;  // uniform over the wavefront
           const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
-          floatx4 acc[C::RB][C::NT];
-          load_rows<D>(Wm[q] + D, acc, w, i, g);  // rows of -K_0
-          emit_gain<D, TIn>(p, prob[q], acc, x0p, info[q], tid);
+          emit_gain<D, TIn>(p, prob[q], accW[q], x0p, info[q], tid);  // rows of -K_0
           emit_value<D, TIn>(p, prob[q], Wm[q], Qp[q], x0p, info[q], s_red, tid);
         }
         __syncthreads();

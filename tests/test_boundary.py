@@ -5,8 +5,9 @@ import os
 import re
 
 import pytest
+import torch
 
-from paper_2603_09221_amd import binding
+from paper_2603_09221_amd import binding, synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -134,3 +135,45 @@ def test_time_heterogeneous_argument_validation_without_device(lib):
     w = lib.ttc_lqr_tv_rollout_workspace_bytes(ctypes.byref(_tv_problem(d=128, m=128, T=16)))
     assert w > 0 and w % (16 * 128 * 128 * 4) == 0                                   # T matrices per resident workgroup
     assert lib.ttc_lqr_tv_rollout_workspace_bytes(ctypes.byref(_tv_problem(d=48, m=48))) == 0
+
+
+def _cxt_problem(**kw):
+    p = binding.CxtProblem()
+    p.n, p.d, p.r, p.T, p.in_dtype, p.flags = 8, 16, 16, 4, binding.TTC_F32, 0
+    for k in ("sA", "sB", "sQ", "sQf", "rinv", "lgA", "lgB", "lgQ", "x0", "Bbasis", "Qbasis"):
+        setattr(p, k, 0x1000)
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_structured_argument_validation_without_device(lib):
+    s = binding.Solution(0x2000, 0x3000, 0x4000, 0x5000, 0x6000)
+    call = lambda p, sol=s: lib.ttc_lqr_solve_cxt(ctypes.byref(p), ctypes.byref(sol), None)
+    assert call(_cxt_problem(T=0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(r=0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(flags=4)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(in_dtype=2)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(n=-1)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(lgB=None)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(Qbasis=0x1002)) == binding.TTC_ERR_INVALID_ARG        # misaligned for float32
+    assert call(_cxt_problem(Qbasis=0x1002, in_dtype=binding.TTC_BF16, n=0)) == binding.TTC_OK
+    assert call(_cxt_problem(d=32)) == binding.TTC_ERR_UNSUPPORTED
+    assert call(_cxt_problem(r=65)) == binding.TTC_ERR_UNSUPPORTED
+    assert call(_cxt_problem(n=0)) == binding.TTC_OK
+    assert call(_cxt_problem(), binding.Solution(None, None, None, None, None)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(), binding.Solution(0x2004, 0x3000, 0x4000, None, None)) == binding.TTC_ERR_INVALID_ARG
+
+
+def test_structured_binding_checks_shapes():
+    b = synth.make_contextual_batch(6, 16, 4, 5, seed=0)
+    keys = synth.ContextualBatch.PER_PROBLEM + ("Bbasis", "Qbasis", "x0")
+    args = {k: getattr(b, k) for k in keys}
+    p = binding.make_cxt_problem(*(args[k] for k in keys), 5)
+    assert (p.n, p.d, p.r, p.T, p.in_dtype) == (6, 16, 4, 5, binding.TTC_F32)
+    bad = dict(args, sQ=args["sQ"][:, :3].contiguous())
+    with pytest.raises(ValueError):
+        binding.make_cxt_problem(*(bad[k] for k in keys), 5)
+    bad = dict(args, lgA=args["lgA"].to(torch.bfloat16))
+    with pytest.raises(ValueError):
+        binding.make_cxt_problem(*(bad[k] for k in keys), 5)
