@@ -29,7 +29,8 @@ PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 f
 # (profiles/*_d128_T16_llm_adapter_n65536.md): (read + written) KiB / 65536 problems.
 MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (38.64e6 + 27.51e6) * 1024 / 65536,
                                       ("llm_adapter", "doubling"): (112.3e6 + 76.1e6) * 1024 / 65536,
-                                      ("llm_adapter", "tv"): (82.69e6 + 3.090e6) * 1024 / 16384}
+                                      ("llm_adapter", "tv"): (82.69e6 + 3.090e6) * 1024 / 16384,
+                                      ("ttc_layer_d16", 8): (645.6e3 + 2.747e6) * 1024 / 1048576}
 def default_groups(T, dtype):
     """The library default: number of groups the T factors are split into (one dense solve each)."""
     return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
