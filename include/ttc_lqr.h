@@ -160,6 +160,21 @@ size_t ttc_lqr_tv_rollout_workspace_bytes(const ttc_lqr_tv_problem_t *problem);
 ttc_status_t ttc_lqr_rollout_tv(const ttc_lqr_tv_problem_t *problem, float *U, float *X, float *cost,
                                 int32_t *info, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same outputs as ttc_lqr_solve_tv with the product of the T factors of Thm 3.3 formed pairwise instead
+ * of one after the other (the paper's product is sequential, Sec. 3.3; composition of the factors is
+ * associative): every step becomes an element (A_s, G_s = B_s R_s^{-1} B_s^T, Q_{s-1}) of the map
+ * P -> Q_{s-1} + A_s^T P (I + G_s P)^{-1} A_s, neighbouring elements are composed in ceil(log2 T) rounds of
+ * one launch each, and the step s = 0 is taken as printed (Prop. 3.1) to obtain K_0.  For small batches
+ * with long horizons, where ttc_lqr_solve_tv leaves most of the chip idle: the rounds run n*T/2, n*T/4, ...
+ * compositions side by side.  It does about three times the arithmetic of ttc_lqr_solve_tv and needs a
+ * workspace of ttc_lqr_tv_scan_workspace_bytes(problem) = n*T*3*d*d*4 bytes (DEVICE, 16-byte aligned;
+ * TTC_ERR_WORKSPACE otherwise).  info is 1 for a problem with a breakdown anywhere (an R[s] that is not
+ * positive definite, a singular I + G_1 H_2 in a composition, S_0 not positive definite), outputs NaN.
+ * Launches 2 + ceil(log2 T) kernels on hip_stream; allocates nothing; asynchronous. */
+size_t ttc_lqr_tv_scan_workspace_bytes(const ttc_lqr_tv_problem_t *problem);
+ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t *problem, const ttc_lqr_solution_t *solution,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Structured, contextualised problems (Sec. 4, "Contextualization" and "Parameterization"; Sec. 3.3,
  * "Structured Parameterization"): the T steps of a problem are not stored anywhere; the kernel builds them
  * from per-problem vectors and two groups of r basis matrices shared by all problems.  With t = 1..T the

@@ -21,7 +21,8 @@ TTC_FLAG_PURE_SYMPLECTIC = 2
 TTC_FLAG_DOUBLING = 4
 
 EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
-           "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_status_string", "ttc_version")
+           "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_lqr_solve_tv_scan",
+           "ttc_lqr_tv_scan_workspace_bytes", "ttc_status_string", "ttc_version")
 
 
 class Problem(ctypes.Structure):
@@ -84,6 +85,11 @@ def load():
     lib.ttc_lqr_rollout_tv.restype = c_int
     lib.ttc_lqr_rollout_tv.argtypes = [ctypes.POINTER(TvProblem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                        c_size_t, c_void_p]
+    lib.ttc_lqr_tv_scan_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_tv_scan_workspace_bytes.argtypes = [ctypes.POINTER(TvProblem)]
+    lib.ttc_lqr_solve_tv_scan.restype = c_int
+    lib.ttc_lqr_solve_tv_scan.argtypes = [ctypes.POINTER(TvProblem), ctypes.POINTER(Solution), c_void_p, c_size_t,
+                                          c_void_p]
     lib.ttc_lqr_solve_cxt.restype = c_int
     lib.ttc_lqr_solve_cxt.argtypes = [ctypes.POINTER(CxtProblem), ctypes.POINTER(Solution), c_void_p]
     lib.ttc_status_string.restype = c_char_p
@@ -240,6 +246,29 @@ def ttc_lqr_solve_tv(A, B, Q, R, x0, *, want_P0=True, want_K0=True, out=None, st
     out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
     sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
     _check(lib.ttc_lqr_solve_tv(ctypes.byref(prob), ctypes.byref(sol), None, 0, _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_solve_tv_scan(A, B, Q, R, x0, *, want_P0=True, want_K0=True, out=None, workspace=None, stream=None):
+    """ttc_lqr_solve_tv with the factors composed pairwise over the horizon (small batches, long horizons)."""
+    lib = load()
+    prob = make_tv_problem(A, B, Q, R, x0)
+    n, d, m, dev = prob.n, prob.d, prob.m, A.device
+    out = dict(out or {})
+    f32 = dict(dtype=torch.float32, device=dev)
+    if want_P0 and "P0" not in out:
+        out["P0"] = torch.empty((n, d, d), **f32)
+    if want_K0 and "K0" not in out:
+        out["K0"] = torch.empty((n, m, d), **f32)
+    out.setdefault("u0", torch.empty((n, m), **f32))
+    out.setdefault("value", torch.empty((n,), **f32))
+    out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
+    need = lib.ttc_lqr_tv_scan_workspace_bytes(ctypes.byref(prob))
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
+    _check(lib.ttc_lqr_solve_tv_scan(ctypes.byref(prob), ctypes.byref(sol), c_void_p(workspace.data_ptr()),
+                                     workspace.numel(), _stream_ptr(stream)))
     return out
 
 

@@ -646,6 +646,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_kernel(const RolloutArgs
 
 }  // namespace ttc
 #include "ttc_tv.hpp"
+#include "ttc_scan.hpp"
 #include "ttc_cxt.hpp"
 namespace ttc {
 
@@ -667,7 +668,7 @@ static int cu_count() {
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
 // (registers and LDS decide it); the table is the fallback when no device can be asked.
 enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4, KIND_TV_QUAD = 5,
-            KIND_ROLLOUT_TV = 6, KIND_CXT = 7 };
+            KIND_ROLLOUT_TV = 6, KIND_CXT = 7, KIND_SCAN = 8 };
 static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
 template <int D>
 static int occupancy_of(Kind kind, bool bf16) {
@@ -677,6 +678,8 @@ static int occupancy_of(Kind kind, bool bf16) {
   if (kind == KIND_SOLVE_QUAD)  // the four-problems-per-wavefront kernel (d = 16 only)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
+  else if (kind == KIND_SCAN)  // the pairwise compositions (the leaf kernel uses fewer registers)
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, scan_combine_kernel<D>, nthr, 0);
   else if (kind == KIND_CXT)  // structured parameters (d = 16 only)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<float>, nthr, 0);
@@ -705,7 +708,7 @@ static int occupancy_of(Kind kind, bool bf16) {
   return nb;
 }
 static int blocks_per_cu(Kind kind, int d, bool bf16) {
-  static int cached[8][4][2];  // 0 = not asked yet
+  static int cached[9][4][2];  // 0 = not asked yet
   int& c = cached[kind][dindex(d)][bf16 ? 1 : 0];
   if (c > 0) return c;
   int nb = 0;
@@ -719,8 +722,8 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
     c = nb > 32 ? 32 : nb;
     return c;
   }
-  static const int table[8][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1},
-                                  {20, 8, 2, 1}, {8, 8, 2, 1},  {12, 4, 2, 1}, {8, 8, 2, 1}};
+  static const int table[9][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}, {20, 8, 2, 1},
+                                  {8, 8, 2, 1},  {12, 4, 2, 1}, {8, 8, 2, 1},  {16, 8, 2, 1}};
   return table[kind][dindex(d)];
 }
 static long long grid_blocks(Kind kind, int d, bool bf16) {
@@ -788,6 +791,28 @@ static hipError_t launch_tv(const TvArgs& a, int d, dim3 grid, hipStream_t st) {
     case 32: hipLaunchKernelGGL((solve_tv_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
     case 64: hipLaunchKernelGGL((solve_tv_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
     case 128: hipLaunchKernelGGL((solve_tv_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <typename TIn>
+static hipError_t launch_scan_leaf(const ScanArgs& a, int d, dim3 grid, hipStream_t st) {
+  switch (d) {
+    case 16: hipLaunchKernelGGL((scan_leaf_kernel<16, TIn>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((scan_leaf_kernel<32, TIn>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((scan_leaf_kernel<64, TIn>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((scan_leaf_kernel<128, TIn>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+static hipError_t launch_scan_combine(const ScanArgs& a, int d, dim3 grid, hipStream_t st) {
+  switch (d) {
+    case 16: hipLaunchKernelGGL((scan_combine_kernel<16>), grid, dim3(Cfg<16>::NTHR), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((scan_combine_kernel<32>), grid, dim3(Cfg<32>::NTHR), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((scan_combine_kernel<64>), grid, dim3(Cfg<64>::NTHR), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((scan_combine_kernel<128>), grid, dim3(Cfg<128>::NTHR), 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -1027,6 +1052,62 @@ ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solut
   } else {
     e = bf16 ? ttc::launch_tv<uint16_t>(a, q->d, grid, st) : ttc::launch_tv<float>(a, q->d, grid, st);
   }
+  return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+}
+
+size_t ttc_lqr_tv_scan_workspace_bytes(const ttc_lqr_tv_problem_t* q) {
+  if (validate_tv(q) != TTC_OK) return 0;
+  return (size_t)q->n * (size_t)q->T * 3 * (size_t)q->d * (size_t)q->d * sizeof(float);
+}
+
+ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solution_t* solution, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t stv = validate_tv(q);
+  if (stv != TTC_OK) return stv;
+  if (!solution) return TTC_ERR_INVALID_ARG;
+  if (q->n == 0) return TTC_OK;
+  if (!solution->u0) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_tv_scan_workspace_bytes(q))
+    return TTC_ERR_WORKSPACE;
+  ttc::ScanArgs sa;
+  ttc::TvArgs& a = sa.tv;
+  a.s.n = q->n;
+  a.s.T = q->T;
+  a.s.flags = 0;
+  a.s.ngroups = q->T;
+  a.s.explicit_groups = 0;
+  a.s.A = q->A; a.s.B = q->B; a.s.Q = q->Q; a.s.R = q->R; a.s.QT = nullptr; a.s.x0 = q->x0;
+  a.s.sA = q->sA; a.s.sB = q->sB; a.s.sQ = q->sQ; a.s.sR = q->sR; a.s.sQT = 0; a.s.sx0 = q->sx0;
+  a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
+  a.s.info = solution->info;
+  a.s.ws = nullptr;
+  a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
+  sa.ws = static_cast<float*>(workspace);
+  sa.stride = 0;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const int d = q->d;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const long long gb = ttc::grid_blocks(ttc::KIND_SCAN, d, bf16);
+  auto grid_for = [&](long long items) { return dim3((unsigned)(items < gb ? items : gb)); };
+  hipError_t e = bf16 ? ttc::launch_scan_leaf<uint16_t>(sa, d, grid_for(q->n * q->T), st)
+                      : ttc::launch_scan_leaf<float>(sa, d, grid_for(q->n * q->T), st);
+  if (e != hipSuccess) return TTC_ERR_DEVICE;
+  for (long long stride = 1; stride < q->T; stride *= 2) {
+    sa.stride = (int)stride;
+    const long long per = (q->T - stride + 2 * stride - 1) / (2 * stride);
+    e = ttc::launch_scan_combine(sa, d, grid_for(q->n * per), st);
+    if (e != hipSuccess) return TTC_ERR_DEVICE;
+  }
+  // the step s = 0 as printed, from P_1 = H of the first element
+  ttc::TvArgs last = a;
+  last.s.T = 1;
+  last.s.ngroups = 1;
+  last.PT = sa.ws + 2 * (size_t)d * d;
+  last.sPT = (long long)q->T * 3 * d * d;
+  const long long gt = ttc::grid_blocks(ttc::KIND_SOLVE_TV, d, bf16);
+  const dim3 grid((unsigned)(q->n < gt ? q->n : gt));
+  e = bf16 ? ttc::launch_tv<uint16_t>(last, d, grid, st) : ttc::launch_tv<float>(last, d, grid, st);
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 

@@ -1,0 +1,183 @@
+// Time-heterogeneous problems with the backward recursion taken as a tree over the horizon.
+// Included by ttc_lqr.hip after ttc_tv.hpp.
+//
+// One backward step of Prop. 3.1, with G_s = B_s R_s^{-1} B_s^T (the G_t of Thm 3.3), is the map
+//     f_e(P) = H_e + A_e^T P (I + G_e P)^{-1} A_e        of the element e = (A_e, G_e, H_e) = (A_s, G_s, Q_{s-1}),
+// the symplectic transfer matrix Sigma_t of Thm 3.3 in a form that needs no A^{-1}.  The maps are closed
+// under composition: with e1 the earlier step, f_{e1} o f_{e2} = f_e for
+//     M = (I + G_1 H_2)^{-1},   A = A_2 M A_1,   G = G_2 + A_2 M G_1 A_2^T,   H = H_1 + A_1^T H_2 M A_1,
+// and composition is associative, so the product of the T factors, which the paper forms one factor
+// after the other (Sec. 3.3), can be formed pairwise in ceil(log2 T) rounds, every round one launch over
+// all pairs of all problems.  The terminal cost enters as one more element, the constant map
+// (0, 0, Q_T): composed on the right of the steps s = 1..T-1 it leaves H = P_1 in the first element.
+// The step s = 0, which also yields the gain, is then taken as printed (riccati_step).
+//
+// Elements live in the workspace as plain row-major fp32 matrices, element k of problem p at
+// ws + ((p*T + k)*3) d^2: A, G, H; k = 0..T-2 is step s = k+1, k = T-1 the terminal element.
+// A round with stride st rewrites element j (j a multiple of 2 st) as e_j o e_{j+st}; no other element
+// is written in that round.  A breakdown (R_s not positive definite, I + G_1 H_2 singular) poisons the H it
+// produces with NaN, which the last step turns into info = 1 and NaN outputs for that problem alone.
+#pragma once
+
+namespace ttc {
+
+struct ScanArgs {
+  TvArgs tv;   // the problems (inputs only)
+  float* ws;   // n*T elements of 3 d^2 floats
+  int stride;  // combine rounds: the stride st
+};
+
+template <int D>
+__device__ __forceinline__ void poison(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT]) {
+  const float nanv = __builtin_nanf("");
+#pragma unroll
+  for (int rb = 0; rb < Cfg<D>::RB; ++rb)
+#pragma unroll
+    for (int c = 0; c < Cfg<D>::NT; ++c) acc[rb][c] = floatx4{nanv, nanv, nanv, nanv};
+}
+
+// the elements of every step of every problem
+template <int D, typename TIn>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) scan_leaf_kernel(const ScanArgs a) {
+  using C = Cfg<D>;
+  __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
+  __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
+  const SolveArgs& p = a.tv.s;
+  float* const WL = W;
+  float* const WR = W + D;
+  const long long items = p.n * p.T;
+  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+    const long long prob = item / p.T;
+    const int k = (int)(item % p.T);
+    float* const gA = a.ws + item * 3 * D * D;
+    float* const gG = gA + D * D;
+    float* const gH = gG + D * D;
+    const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ + (long long)k * a.tv.tQ;  // Q[k] = Q_{s-1}, s = k+1
+    floatx4 acc[C::RB][C::NT];
+    load_half<D, TIn, false>(WL, Qp, tid);
+    __syncthreads();
+    symmetrise_half<D>(WL, tid);
+    __syncthreads();
+    store_half_global<D>(gH, WL, tid);
+    if (k == p.T - 1) {  // the terminal element (0, 0, Q_T)
+      zero_acc<D>(acc);
+      write_rows_global<D>(gA, acc, w, i, g);
+      write_rows_global<D>(gG, acc, w, i, g);
+      __syncthreads();
+      continue;
+    }
+    const int s = k + 1;
+    const TIn* As = reinterpret_cast<const TIn*>(p.A) + prob * p.sA + (long long)s * a.tv.tA;
+    const TIn* Bs = reinterpret_cast<const TIn*>(p.B) + prob * p.sB + (long long)s * a.tv.tB;
+    const TIn* Rs = reinterpret_cast<const TIn*>(p.R) + prob * p.sR + (long long)s * a.tv.tR;
+    load_rows_input<D, TIn>(As, acc, w, i, g);
+    write_rows_global<D>(gA, acc, w, i, g);
+    __syncthreads();  // H has left the left half
+    load_half<D, TIn, false>(WL, Rs, tid);
+    load_half<D, TIn, true>(WR, Bs, tid);  // right-hand sides: B^T
+    __syncthreads();
+    symmetrise_half<D>(WL, tid);
+    float rB[C::RB][C::KS];
+    load_aopT_lds<D>(WR, rB, w, i, g);  // rows of B = columns of B^T
+    __syncthreads();
+    const int flag = lds_solve<D, 7, false>(W, S, tid);  // right half: X = R^{-1} B^T
+    zero_acc<D>(acc);
+    gemm_acc<D>(acc, rB, WR, i, g);  // G = B X
+    if (flag) poison<D>(acc);
+    write_rows_global<D>(gG, acc, w, i, g);
+    if (flag) {  // make sure the breakdown reaches P_1 whatever the other elements are
+      poison<D>(acc);
+      write_rows_global<D>(gH, acc, w, i, g);
+    }
+    __syncthreads();
+  }
+}
+
+// one round of pairwise compositions
+template <int D>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) scan_combine_kernel(const ScanArgs a) {
+  using C = Cfg<D>;
+  __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
+  __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
+  const SolveArgs& p = a.tv.s;
+  float* const WL = W;
+  float* const WR = W + D;
+  const int st = a.stride;
+  const long long per = (p.T - st + 2LL * st - 1) / (2LL * st);  // pairs per problem in this round
+  const long long items = p.n * per;
+  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+    const long long prob = item / per;
+    const long long j = (item % per) * 2 * st;
+    float* const e1 = a.ws + (prob * p.T + j) * 3 * D * D;
+    const float* const e2 = a.ws + (prob * p.T + j + st) * 3 * D * D;
+    float* const A1 = e1;
+    float* const G1 = e1 + D * D;
+    float* const H1 = e1 + 2 * D * D;
+    const float* const A2 = e2;
+    const float* const G2 = e2 + D * D;
+    const float* const H2 = e2 + 2 * D * D;
+    floatx4 acc[C::RB][C::NT], accY[C::RB][C::NT];
+    float rM[C::RB][C::KS], rA1T[C::RB][C::KS], rA2[C::RB][C::KS];
+    {
+      float rG1[C::RB][C::KS];
+      load_half<D, float, false>(WR, H2, tid);
+      load_aop_global<D, float>(G1, rG1, w, i, g);
+      __syncthreads();
+      eye_acc<D>(acc, w, i, g);
+      gemm_acc<D>(acc, rG1, WR, i, g);  // I + G1 H2
+      store_rows<D>(WL, acc, w, i, g);
+      __syncthreads();
+    }
+    set_half_identity<D>(WR, tid);
+    __syncthreads();
+    const int flag = lds_solve<D>(W, S, tid);  // right half: M = (I + G1 H2)^{-1}
+    load_aop_lds<D>(WR, rM, w, i, g);
+    load_half<D, float, false>(WL, A1, tid);
+    __syncthreads();
+    zero_acc<D>(acc);
+    gemm_acc<D>(acc, rM, WL, i, g);  // X1 = M A1
+    load_aopT_lds<D>(WL, rA1T, w, i, g);
+    load_half<D, float, false>(WR, G1, tid);  // M is in registers
+    __syncthreads();
+    store_rows<D>(WL, acc, w, i, g);  // left half: X1
+    zero_acc<D>(accY);
+    gemm_acc<D>(accY, rM, WR, i, g);  // Y = M G1
+    __syncthreads();
+    load_aop_global<D, float>(A2, rA2, w, i, g);
+    zero_acc<D>(acc);
+    gemm_acc<D>(acc, rA2, WL, i, g);  // A = A2 X1
+    write_rows_global<D>(A1, acc, w, i, g);
+    {
+      float rH2[C::RB][C::KS];
+      load_aop_global<D, float>(H2, rH2, w, i, g);
+      zero_acc<D>(acc);
+      gemm_acc<D>(acc, rH2, WL, i, g);  // V = H2 X1
+    }
+    store_rows<D>(WR, acc, w, i, g);  // right half: V
+    __syncthreads();
+    load_rows_global<D>(H1, acc, w, i, g);
+    gemm_acc<D>(acc, rA1T, WR, i, g);  // H = H1 + A1^T V
+    if (flag) poison<D>(acc);
+    write_rows_global<D>(H1, acc, w, i, g);
+    store_rows<D>(WL, accY, w, i, g);  // left half: Y
+    __syncthreads();
+    zero_acc<D>(acc);
+    gemm_acc<D>(acc, rA2, WL, i, g);  // Z = A2 Y
+    load_half<D, float, true>(WR, A2, tid);  // right half: A2^T
+    __syncthreads();
+    store_rows<D>(WL, acc, w, i, g);  // left half: Z
+    __syncthreads();
+    {
+      float rZ[C::RB][C::KS];
+      load_aop_lds<D>(WL, rZ, w, i, g);
+      load_rows_global<D>(G2, acc, w, i, g);
+      gemm_acc<D>(acc, rZ, WR, i, g);  // G = G2 + Z A2^T
+      write_rows_global<D>(G1, acc, w, i, g);
+    }
+    __syncthreads();
+  }
+}
+
+}  // namespace ttc

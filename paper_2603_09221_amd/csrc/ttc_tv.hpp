@@ -18,6 +18,8 @@ namespace ttc {
 struct TvArgs {
   SolveArgs s;                 // n, T, A, B, Q, R, x0 and their problem strides, outputs (QT, ws, groups unused)
   long long tA, tB, tQ, tR;    // elements between consecutive steps
+  const float* PT = nullptr;   // if set: the terminal value matrix, fp32, instead of Q[T-1] (solve_tv_kernel only)
+  long long sPT = 0;           // elements between consecutive problems of PT
 };
 
 // accumulator rows of this wavefront <- row-major global matrix of input element type
@@ -144,7 +146,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta)
     const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
     int info = 0;
-    load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
+    if (ta.PT) load_half<D, float, false>(WR, ta.PT + prob * ta.sPT, tid);
+    else load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
     __syncthreads();
     symmetrise_half<D>(WR, tid);
     __syncthreads();

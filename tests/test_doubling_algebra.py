@@ -64,3 +64,37 @@ def test_square_is_the_map_applied_twice():
     L = rng.standard_normal(Q.shape)
     P = L @ np.swapaxes(L, -1, -2)
     np.testing.assert_allclose(apply(square(e), P), apply(e, apply(e, P)), rtol=1e-10, atol=1e-10)
+
+
+def compose(e1, e2):
+    """f_{e1} o f_{e2}: e1 is the earlier step (applied last in the backward recursion)."""
+    A1, G1, H1 = e1
+    A2, G2, H2 = e2
+    I = np.eye(A1.shape[-1])
+    M = np.linalg.inv(I + G1 @ H2)
+    return A2 @ M @ A1, G2 + A2 @ M @ G1 @ np.swapaxes(A2, -1, -2), H1 + np.swapaxes(A1, -1, -2) @ H2 @ M @ A1
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 5, 8, 13, 33])
+def test_pairwise_composition_of_distinct_steps_reproduces_the_recursion(T):
+    """The tree the time-heterogeneous long-horizon entry point walks: elements of the steps s = 1..T-1 and the
+    terminal cost as the constant map (0, 0, Q_T), composed pairwise with strides 1, 2, 4, ...; H of the first
+    element is then P_1 of the oracle."""
+    tv = synth.make_tv_batch(3, 8, 8, T, seed=T)
+    A, B, Q, R, x0 = tv.numpy64()
+    ref = lqr_oracle.riccati_solve_tv(A, B, Q, R, x0)
+    els = [(A[:, s], B[:, s] @ np.linalg.solve(R[:, s], np.swapaxes(B[:, s], -1, -2)), Q[:, s - 1]) for s in range(1, T)]
+    Z = np.zeros_like(Q[:, 0])
+    els.append((Z, Z, Q[:, T - 1]))
+    st = 1
+    while st < len(els):
+        for j in range(0, len(els), 2 * st):
+            if j + st < len(els):
+                els[j] = compose(els[j], els[j + st])
+        st *= 2
+    np.testing.assert_allclose(els[0][2], ref["P"][1], rtol=0, atol=1e-11 * np.abs(ref["P"][1]).max())
+    e = (A[:, 1], els[0][1] * 0 + B[:, 1] @ np.linalg.solve(R[:, 1], np.swapaxes(B[:, 1], -1, -2)), Q[:, 0]) if T > 2 else None
+    if e is not None:   # composition agrees with applying the two maps one after the other
+        P3 = ref["P"][3]
+        e12 = compose(e, (A[:, 2], B[:, 2] @ np.linalg.solve(R[:, 2], np.swapaxes(B[:, 2], -1, -2)), Q[:, 1]))
+        np.testing.assert_allclose(apply(e12, P3), ref["P"][1], rtol=0, atol=1e-11 * np.abs(ref["P"][1]).max())
