@@ -7,7 +7,7 @@ Prints ONE JSON line: problems/s plus a roofline object for the solve kernel (fp
 oracle timed on the host cores on a bounded sample of the same inputs.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llm_adapter] [--n N] [--rebase-every k]
-                    [--path symplectic|doubling|tv|cxt]
+                    [--path symplectic|doubling|tv|cxt|scan]
 
 The headline value is the paper's sequential symplectic product (--path symplectic, the default); the same
 inputs are also timed on the squaring path and reported under "other_path".
@@ -173,6 +173,86 @@ def bench_cxt(args):
     print(json.dumps(res))
 
 
+def alg_flops_scan(d, T):
+    """Algorithmic flops of one problem on the pairwise path (ttc_lqr_solve_tv_scan): T-1 elements (R^{-1}B^T:
+    d^3/3 + 2 d^3, G: 2 d^3), T-1 compositions (eight products and a dense solve with d right-hand sides:
+    16 d^3 + 8/3 d^3) and the last step as printed (6 products and a positive definite solve)."""
+    return ((T - 1) * (13.0 / 3 + 16 + 8.0 / 3) + 12 + 7.0 / 3) * d ** 3
+
+
+def bench_scan(args):
+    """The small-batch, long-horizon corner of the paper's solver benchmark grid (d = 16, B = 16, T = 2048),
+    time-heterogeneous dense parameters, factors composed pairwise over the horizon."""
+    import numpy as np
+    import torch
+    from oracle import lqr_oracle
+    from paper_2603_09221_amd import binding, synth
+    from tests.parity import rel_err
+
+    d, T = 16, args.horizon or 2048
+    n = args.n or 16
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    binding.load()
+    b = synth.make_tv_batch(n, d, d, T, seed=0, device=dev)
+    ws = torch.empty((n * T * 3 * d * d * 4,), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    out = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, b.R, b.x0, workspace=ws, stream=stream)
+    seq = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, b.R, b.x0, stream=stream)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for e0, e1 in evs:
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps, sum(e0.elapsed_time(e1) for e0, e1 in evs) / len(evs) / 1e3
+    steps = max(args.steps, 20)
+    wall, dev_s = timed(lambda: binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, b.R, b.x0, out=out, workspace=ws,
+                                                              stream=stream), steps, max(args.warmup, 3))
+    swall, sdev_s = timed(lambda: binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, b.R, b.x0, out=seq, stream=stream), 3, 1)
+    assert int(out["info"].abs().max()) == 0
+    flops_pp = alg_flops_scan(d, T)
+    achieved = flops_pp * n / dev_s / 1e12
+    rounds = max(0, math.ceil(math.log2(T)))
+    in_bytes = n * (T * 4 * d * d + d) * 4
+    out_bytes = n * (2 * d * d + d + 2) * 4
+    res = {
+        "metric": "LQR solves/sec at d=%d, T=%d, batch %d, time-heterogeneous, pairwise product" % (d, T, n),
+        "value": n / wall, "unit": "problems/s", "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 3),
+        "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "paper_grid_d16_B%d_T%d" % (n, T), "problems": n, "d": d, "m": d, "T": T,
+                   "input_dtype": "f32", "path": "scan", "outputs": "P0,K0,u0,value"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "kernel": "scan_leaf_kernel<16> + %d x scan_combine_kernel<16> + solve_tv_kernel<16> "
+                               "(one call; latency-bound: %d dependent launches)" % (rounds, rounds + 2),
+                     "kernel_ms": dev_s * 1e3, "alg_flops_per_problem": flops_pp,
+                     "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / dev_s / 1e12,
+                     "alg_bytes_per_launch": in_bytes + out_bytes,
+                     "alg_GBps": (in_bytes + out_bytes) / dev_s / 1e9},
+        "other_path": {"path": "sequential (ttc_lqr_solve_tv)", "value": n / swall, "unit": "problems/s",
+                       "kernel_ms": sdev_s * 1e3},
+    }
+    if not args.no_cpu:
+        A, B, Q, R, x0 = b.numpy64()
+        t1 = time.perf_counter()
+        ref = lqr_oracle.riccati_solve_tv(A, B, Q, R, x0)
+        dt = time.perf_counter() - t1
+        errs = {k: float(rel_err(out[k].cpu().numpy(), ref[k]).max()) for k in ("P0", "K0", "u0", "value")}
+        res["cpu_baseline"] = {"value": n / dt, "unit": "problems/s", "cores": 1, "kind": "oracle",
+                               "sample": "all %d problems, float64 numpy Riccati, batched over problems in one "
+                                         "thread, %.2f s wall" % (n, dt)}
+        res["parity"] = {"sample": n, "max_rel_err": errs, "tolerance": 1e-4}
+    print(json.dumps(res))
+
+
 def cpu_baseline(batch, sample, want_seconds=(10.0, 30.0)):
     """The oracle, as it stands, on the host cores: one problem chunk per thread, BLAS single-threaded."""
     import numpy as np
@@ -214,14 +294,15 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="llm_adapter")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt"),
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
                          "doubling: the long-horizon path, the same product formed by squaring; "
                          "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
                          "every step with its own A, B, Q, R (default 16384 problems); "
                          "cxt: structured, contextualised parameters (ttc_lqr_solve_cxt) at d = 16, r = 16, "
-                         "1048576 problems, --config ignored")
-    ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt path (default 8)")
+                         "1048576 problems, --config ignored; "
+                         "scan: ttc_lqr_solve_tv_scan at d = 16, 16 problems, horizon 2048, --config ignored")
+    ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt (default 8) and scan (default 2048) paths")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
     ap.add_argument("--rebase-every", type=int, default=0, help="0 = library default")
@@ -238,6 +319,8 @@ def main():
 
     if args.path == "cxt":
         return bench_cxt(args)
+    if args.path == "scan":
+        return bench_scan(args)
 
     import numpy as np
     import torch
