@@ -177,3 +177,21 @@ def test_structured_binding_checks_shapes():
     bad = dict(args, lgA=args["lgA"].to(torch.bfloat16))
     with pytest.raises(ValueError):
         binding.make_cxt_problem(*(bad[k] for k in keys), 5)
+
+
+def test_pairwise_long_horizon_argument_validation_without_device(lib):
+    s = binding.Solution(0x2000, 0x3000, 0x4000, 0x5000, 0x6000)
+    call = lambda p, sol=s, ws=0x1000, nbytes=1 << 40: lib.ttc_lqr_solve_tv_scan(ctypes.byref(p), ctypes.byref(sol), ws,
+                                                                                nbytes, None)
+    need = lib.ttc_lqr_tv_scan_workspace_bytes(ctypes.byref(_tv_problem()))
+    assert need == 4 * 8 * 3 * 256 * 4                      # n * T * 3 * d * d floats
+    assert lib.ttc_lqr_tv_scan_workspace_bytes(ctypes.byref(_tv_problem(d=48, m=48))) == 0
+    assert call(_tv_problem(T=0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_tv_problem(flags=1)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_tv_problem(A=None)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_tv_problem(d=48, m=48)) == binding.TTC_ERR_UNSUPPORTED
+    assert call(_tv_problem(n=0)) == binding.TTC_OK
+    assert call(_tv_problem(), ws=None) == binding.TTC_ERR_WORKSPACE
+    assert call(_tv_problem(), ws=0x1008) == binding.TTC_ERR_WORKSPACE          # misaligned
+    assert call(_tv_problem(), nbytes=need - 1) == binding.TTC_ERR_WORKSPACE
+    assert call(_tv_problem(), binding.Solution(None, None, None, None, None)) == binding.TTC_ERR_INVALID_ARG
