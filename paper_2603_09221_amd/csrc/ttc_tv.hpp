@@ -271,7 +271,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_tv_kernel(const TvRollou
 // The same at d = 16 with four problems per wavefront (see ttc_small.hpp): products of the four problems
 // interleaved on the matrix cores, their dense solves side by side with one row per lane.
 template <typename TIn>
-__global__ void __launch_bounds__(64) solve_tv_small_kernel(const TvArgs ta) {
+__global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) {
   constexpr int D = 16;
   using C = Cfg<D>;
   constexpr int PPW = 4;
