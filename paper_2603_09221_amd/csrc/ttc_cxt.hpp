@@ -29,11 +29,14 @@ struct CxtArgs {
 #ifndef TTC_CXT_WAVES
 #define TTC_CXT_WAVES 2  // wavefronts per SIMD the register allocation aims at
 #endif
-template <typename TIn>
+// PPW = problems per wavefront: 4 for batches that fill the chip; 1 for small batches, where a wavefront's
+// latency is what counts: the four rows of 16 lanes then all hold the same problem (they compute, and
+// write, the same values), and every per-problem loop below runs once instead of four times.
+template <typename TIn, int PPW>
 __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtArgs ca) {
   constexpr int D = 16;
   using C = Cfg<D>;
-  constexpr int PPW = 4;
+  static_assert(PPW == 1 || PPW == 4, "one problem or four per wavefront");
   __shared__ __attribute__((aligned(16))) float Wm[PPW][D * C::PITCH];
   // Wm[q]: left half S and then S^{-1} (at the end P_0), right half the value matrix between steps
   constexpr int PT = D + 4;                                              // row pitch of Vt
@@ -51,6 +54,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 
   for (long long quad = blockIdx.x; quad < nquads; quad += gridDim.x) {
     const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, i = lane & 15, g = lane >> 4;
+    const int gq = g & (PPW - 1);  // the problem, among the wavefront's, that this lane's row of 16 lanes works on
     constexpr int w = 0;
     long long prob[PPW];  // a ragged last quad repeats the last problem; only valid ones are written out
     bool valid[PPW];
@@ -59,8 +63,8 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
       valid[q] = quad * PPW + q < p.n;
       prob[q] = valid[q] ? quad * PPW + q : p.n - 1;
     }
-    float* const Wmine = Wm[g];  // the problem whose rows this lane holds during the dense solves
-    int info[PPW] = {0, 0, 0, 0};
+    float* const Wmine = Wm[gq];  // the problem whose rows this lane holds during the dense solves
+    int info[PPW] = {};
     int nsolve = 0;
     auto note = [&](int bad) {
       ++nsolve;
@@ -72,16 +76,16 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 
     PhaseTimers tm;  // phases: 0 set-up, 1 dense solves, 2 products and scalings, 3 outputs
     // ---- per-problem vectors: lane (i, g) keeps entry i of problem g's
-    const long long pg = (quad * PPW + g < p.n) ? quad * PPW + g : p.n - 1;
+    const long long pg = (quad * PPW + gq < p.n) ? quad * PPW + gq : p.n - 1;
     const float sA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sA), pg * D + i);
     const float lgA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgA), pg * D + i);
     const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgB), pg * D + i);
     const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgQ), pg * D + i);
-    vecs[0][g][3][i] = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(ca.rinv), pg * D + i);
+    vecs[0][gq][3][i] = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(ca.rinv), pg * D + i);
     for (int k = i; k < r; k += 16) {
-      coef[g][0][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sB), pg * r + k);
-      coef[g][1][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQ), pg * r + k);
-      coef[g][2][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQf), pg * r + k);
+      coef[gq][0][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sB), pg * r + k);
+      coef[gq][1][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQ), pg * r + k);
+      coef[gq][2][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQf), pg * r + k);
     }
     __syncthreads();
 
@@ -118,9 +122,9 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
     auto write_vec = [&](int s) {
       const float tf = (float)(s + 1);
       float (*vec)[4][D] = vecs[s & 1];
-      vec[g][0][i] = 1.f + expf(-tf * lgA_m) * sA_m;
-      vec[g][1][i] = expf(-tf * lgB_m);
-      vec[g][2][i] = expf(-(float)s * lgQ_m);
+      vec[gq][0][i] = 1.f + expf(-tf * lgA_m) * sA_m;
+      vec[gq][1][i] = expf(-tf * lgB_m);
+      vec[gq][2][i] = expf(-(float)s * lgQ_m);
     };
     // a 16 x 16 matrix in LDS: written from the accumulator layout, read back a row
     // per lane, which is the accumulator layout of the transpose

@@ -681,8 +681,8 @@ static int occupancy_of(Kind kind, bool bf16) {
   else if (kind == KIND_SCAN)  // the pairwise compositions (the leaf kernel uses fewer registers)
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, scan_combine_kernel<D>, nthr, 0);
   else if (kind == KIND_CXT)  // structured parameters (d = 16 only)
-    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<uint16_t>, nthr, 0)
-             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<float>, nthr, 0);
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<uint16_t, 4>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_cxt_kernel<float, 4>, nthr, 0);
   else if (kind == KIND_ROLLOUT_TV)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, float>, nthr, 0);
@@ -1141,11 +1141,18 @@ ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_sol
   a.Bbasis = q->Bbasis; a.Qbasis = q->Qbasis;
   const bool bf16 = q->in_dtype == TTC_BF16;
   const long long gb = ttc::grid_blocks(ttc::KIND_CXT, 16, bf16);
-  const long long items = (q->n + 3) / 4;
+  // batches that do not fill the resident wavefronts four problems at a time go one problem to a wavefront
+  const bool single = q->n <= gb;
+  const long long items = single ? q->n : (q->n + 3) / 4;
   const dim3 grid((unsigned)(items < gb ? items : gb));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (bf16) hipLaunchKernelGGL((ttc::solve_cxt_kernel<uint16_t>), grid, dim3(64), 0, st, a);
-  else hipLaunchKernelGGL((ttc::solve_cxt_kernel<float>), grid, dim3(64), 0, st, a);
+  if (single) {
+    if (bf16) hipLaunchKernelGGL((ttc::solve_cxt_kernel<uint16_t, 1>), grid, dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((ttc::solve_cxt_kernel<float, 1>), grid, dim3(64), 0, st, a);
+  } else {
+    if (bf16) hipLaunchKernelGGL((ttc::solve_cxt_kernel<uint16_t, 4>), grid, dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((ttc::solve_cxt_kernel<float, 4>), grid, dim3(64), 0, st, a);
+  }
   return hipGetLastError() == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 
@@ -1160,6 +1167,6 @@ const char* ttc_status_string(ttc_status_t status) {
   return "unknown status";
 }
 
-int ttc_version(void) { return 100; }
+int ttc_version(void) { return 200; }
 
 }  // extern "C"

@@ -33,13 +33,14 @@ def check(b, tol):
 
 
 @pytest.mark.parametrize("n,r,T", [(1, 16, 1), (5, 16, 8), (1027, 16, 8), (300, 3, 33), (66, 64, 5), (130, 1, 2),
-                                    (64, 16, 128), (4098, 16, 16)])
+                                    (64, 16, 128), (4098, 16, 16), (2049, 5, 3), (2501, 64, 1)])
 def test_ranks_horizons_and_ragged_batches(n, r, T):
     check(synth.make_contextual_batch(n, 16, r, T, seed=n + r + T, device=DEV), TOL_F32)
 
 
 def test_bf16_inputs():
     check(synth.make_contextual_batch(515, 16, 16, 8, seed=4, device=DEV, dtype="bf16"), TOL_BF16)
+    check(synth.make_contextual_batch(2601, 16, 16, 8, seed=14, device=DEV, dtype="bf16"), TOL_BF16)   # four per wavefront
     check(synth.make_contextual_batch(31, 16, 5, 32, seed=5, device=DEV, dtype="bf16"), TOL_BF16)
 
 
@@ -55,9 +56,10 @@ def test_agrees_with_the_dense_time_heterogeneous_solve():
         assert float(rel_err(out[k].cpu().numpy(), tv[k].cpu().numpy()).max()) <= 2e-5, k
 
 
-def test_breakdown_stays_with_its_problem():
+@pytest.mark.parametrize("n", [777, 3003])      # one problem per wavefront, four per wavefront
+def test_breakdown_stays_with_its_problem(n):
     """A negative entry of rinv makes R_t indefinite: S_T is not positive definite for that problem alone."""
-    b = synth.make_contextual_batch(777, 16, 16, 6, seed=11, device=DEV)
+    b = synth.make_contextual_batch(n, 16, 16, 6, seed=11, device=DEV)
     good = solve(b)
     rinv = b.rinv.clone()
     rinv[402] = -0.01                                     # R = -100 I
@@ -66,7 +68,7 @@ def test_breakdown_stays_with_its_problem():
     torch.cuda.synchronize()
     info = bad["info"].cpu().numpy()
     assert info[402] == 1 and (np.delete(info, 402) == 0).all()
-    keep = torch.tensor([400, 401, 403, 776], device=DEV)
+    keep = torch.tensor([400, 401, 403, n - 1], device=DEV)
     assert torch.equal(bad["u0"][keep], good["u0"][keep]) and torch.equal(bad["P0"][keep], good["P0"][keep])
     for k in ("P0", "K0", "u0", "value"):
         assert torch.isnan(bad[k][402]).all()
