@@ -676,8 +676,8 @@ static int occupancy_of(Kind kind, bool bf16) {
   hipError_t e;
   const int nthr = Cfg<D>::NTHR;
   if (kind == KIND_SOLVE_QUAD)  // the four-problems-per-wavefront kernel (d = 16 only)
-    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t>, nthr, 0)
-             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float>, nthr, 0);
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<uint16_t, 4>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_small_kernel<float, 4>, nthr, 0);
   else if (kind == KIND_SCAN)  // the pairwise compositions (the leaf kernel uses fewer registers)
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, scan_combine_kernel<D>, nthr, 0);
   else if (kind == KIND_CXT)  // structured parameters (d = 16 only)
@@ -687,8 +687,8 @@ static int occupancy_of(Kind kind, bool bf16) {
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, rollout_tv_kernel<D, float>, nthr, 0);
   else if (kind == KIND_TV_QUAD)
-    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<uint16_t>, nthr, 0)
-             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<float>, nthr, 0);
+    e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<uint16_t, 4>, nthr, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_small_kernel<float, 4>, nthr, 0);
   else if (kind == KIND_SOLVE_TV)
     e = bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_kernel<D, uint16_t>, nthr, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, solve_tv_kernel<D, float>, nthr, 0);
@@ -912,7 +912,8 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   a.ws = static_cast<float*>(workspace);
   const bool doubling = (problem->flags & TTC_FLAG_DOUBLING) != 0;
   const bool quad = ttc::use_quad_kernel(problem);
-  const long long gb = ttc::grid_blocks(doubling ? ttc::KIND_DOUBLING : quad ? ttc::KIND_SOLVE_QUAD : ttc::KIND_SOLVE,
+  const bool small = problem->d == 16 && !doubling;  // d = 16: the kernel with a lane per row of the dense solves
+  const long long gb = ttc::grid_blocks(doubling ? ttc::KIND_DOUBLING : small ? ttc::KIND_SOLVE_QUAD : ttc::KIND_SOLVE,
                                         problem->d, problem->in_dtype == TTC_BF16);
   // work items of the persistent grid: problems, or quads of problems
   const long long items = quad ? (problem->n + 3) / 4 : problem->n;
@@ -929,8 +930,12 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
     e = problem->in_dtype == TTC_F32 ? ttc::launch_doubling<float>(da, problem->d, grid, s)
                                      : ttc::launch_doubling<uint16_t>(da, problem->d, grid, s);
   } else if (quad) {
-    if (problem->in_dtype == TTC_F32) hipLaunchKernelGGL((ttc::solve_small_kernel<float>), grid, dim3(64), 0, s, a);
-    else hipLaunchKernelGGL((ttc::solve_small_kernel<uint16_t>), grid, dim3(64), 0, s, a);
+    if (problem->in_dtype == TTC_F32) hipLaunchKernelGGL((ttc::solve_small_kernel<float, 4>), grid, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL((ttc::solve_small_kernel<uint16_t, 4>), grid, dim3(64), 0, s, a);
+    e = hipGetLastError();
+  } else if (small) {  // a batch that does not fill the chip: one problem to a wavefront
+    if (problem->in_dtype == TTC_F32) hipLaunchKernelGGL((ttc::solve_small_kernel<float, 1>), grid, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL((ttc::solve_small_kernel<uint16_t, 1>), grid, dim3(64), 0, s, a);
     e = hipGetLastError();
   } else {
     e = problem->in_dtype == TTC_F32 ? ttc::launch_solve<float>(a, problem->d, grid, s)
@@ -1038,16 +1043,22 @@ ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solut
   a.s.ws = nullptr;
   a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
   const bool bf16 = q->in_dtype == TTC_BF16;
-  // d = 16: batches that fill the chip go four problems to a wavefront, as in ttc_lqr_solve
-  const bool quad = q->d == 16 && q->n >= 8LL * ttc::cu_count();
-  const long long gb = ttc::grid_blocks(quad ? ttc::KIND_TV_QUAD : ttc::KIND_SOLVE_TV, q->d, bf16);
+  // d = 16: the kernel with a lane per row of the dense solves; batches that fill the chip go four problems
+  // to a wavefront, smaller ones one problem to a wavefront
+  const bool small = q->d == 16;
+  const bool quad = small && q->n >= 8LL * ttc::cu_count();
+  const long long gb = ttc::grid_blocks(small ? ttc::KIND_TV_QUAD : ttc::KIND_SOLVE_TV, q->d, bf16);
   const long long items = quad ? (q->n + 3) / 4 : q->n;
   const dim3 grid((unsigned)(items < gb ? items : gb));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
   if (quad) {
-    if (bf16) hipLaunchKernelGGL((ttc::solve_tv_small_kernel<uint16_t>), grid, dim3(64), 0, st, a);
-    else hipLaunchKernelGGL((ttc::solve_tv_small_kernel<float>), grid, dim3(64), 0, st, a);
+    if (bf16) hipLaunchKernelGGL((ttc::solve_tv_small_kernel<uint16_t, 4>), grid, dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((ttc::solve_tv_small_kernel<float, 4>), grid, dim3(64), 0, st, a);
+    e = hipGetLastError();
+  } else if (small) {
+    if (bf16) hipLaunchKernelGGL((ttc::solve_tv_small_kernel<uint16_t, 1>), grid, dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((ttc::solve_tv_small_kernel<float, 1>), grid, dim3(64), 0, st, a);
     e = hipGetLastError();
   } else {
     e = bf16 ? ttc::launch_tv<uint16_t>(a, q->d, grid, st) : ttc::launch_tv<float>(a, q->d, grid, st);

@@ -164,29 +164,32 @@ __device__ __forceinline__ int invert_rows16(float* Wq, int lane) {
   return bad;
 }
 
-// acc[q] += C_q Z_q for the four problems at once, Z_q = the half of Wm[q] starting at column `half`.
+// acc[q] += C_q Z_q for the wavefront's PPW problems at once, Z_q = the half of Wm[q] starting at column `half`.
 // At d = 16 a product is four dependent matrix-core instructions; taking the k-steps of the four
 // problems in turn keeps the pipe busy, and all sixteen B-operand reads are in flight together.
-__device__ __forceinline__ void gemm_acc_quad(floatx4 (&acc)[4][1][1], const float (&a)[4][1][4],
+template <int PPW = 4>
+__device__ __forceinline__ void gemm_acc_quad(floatx4 (&acc)[PPW][1][1], const float (&a)[PPW][1][4],
                                               float (*Wm)[16 * Cfg<16>::PITCH], int half, int i, int g) {
   using C = Cfg<16>;
-  float b[4][4];
+  float b[PPW][4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+  for (int q = 0; q < PPW; ++q)
 #pragma unroll
     for (int t = 0; t < 4; ++t) b[q][t] = Wm[q][half + (4 * g + t) * C::PITCH + i];
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < PPW; ++q)
       acc[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q][0][t], b[q][t], acc[q][0][0], 0, 0, 0);
 }
 
-template <typename TIn>
+// PPW = problems per wavefront: 4 for batches that fill the chip, 1 for small ones (the four rows of 16 lanes
+// then all hold the same problem and compute, and write, the same values; every per-problem loop runs once).
+template <typename TIn, int PPW>
 __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
   constexpr int D = 16;
   using C = Cfg<D>;
-  constexpr int PPW = 4;  // problems per wavefront
+  static_assert(PPW == 1 || PPW == 4, "one problem or four per wavefront");
   __shared__ __attribute__((aligned(16))) float Wm[PPW][D * C::PITCH];
   __shared__ float s_red[C::NW];
   const bool pure = (p.flags & TTC_FLAG_PURE_SYMPLECTIC) != 0;
@@ -202,8 +205,8 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
       valid[q] = quad * PPW + q < p.n;
       prob[q] = valid[q] ? quad * PPW + q : p.n - 1;
     }
-    float* const Wmine = Wm[g];  // the problem whose rows this lane holds during the dense solves
-    int info[PPW] = {0, 0, 0, 0};
+    float* const Wmine = Wm[g & (PPW - 1)];  // the problem whose rows this lane holds during the dense solves
+    int info[PPW] = {};
     int nsolve = 0;
     auto note = [&](int bad) {   // fold a dense solve's per-lane breakdown flags into the per-problem info
       ++nsolve;
@@ -236,7 +239,7 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
       tm.toc(1);
 #pragma unroll
       for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-      gemm_acc_quad(acc, cB, Wm, D, i, g);  // rows of G = B X
+      gemm_acc_quad<PPW>(acc, cB, Wm, D, i, g);  // rows of G = B X
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
         load_aop_lds<D>(Wm[q] + D, cX[q], w, i, g);
@@ -282,7 +285,7 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
       __syncthreads();
 #pragma unroll
       for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-      gemm_acc_quad(acc, cX, Wm, D, i, g);  // rows of C_K = X A^{-T}
+      gemm_acc_quad<PPW>(acc, cX, Wm, D, i, g);  // rows of C_K = X A^{-T}
 #pragma unroll
       for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
       __syncthreads();
@@ -316,21 +319,21 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
         for (int q = 0; q < PPW; ++q) {
           if (fresh) eye_acc<D>(acc[q], w, i, g); else load_rows<D>(Wm[q], acc[q], w, i, g);
         }
-        gemm_acc_quad(acc, cG, Wm, D, i, g);   // Z1 + G Z2
+        gemm_acc_quad<PPW>(acc, cG, Wm, D, i, g);   // Z1 + G Z2
 #pragma unroll
         for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-        gemm_acc_quad(acc, cAi, Wm, 0, i, g);  // A^{-1} (.) = new Z1
+        gemm_acc_quad<PPW>(acc, cAi, Wm, 0, i, g);  // A^{-1} (.) = new Z1
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-        gemm_acc_quad(acc, cAT, Wm, D, i, g);              // A^T Z2
-        if (s < p.T) gemm_acc_quad(acc, cQ, Wm, 0, i, g);  // + Q Z1; Q_0 = 0 for the last factor
+        gemm_acc_quad<PPW>(acc, cAT, Wm, D, i, g);              // A^T Z2
+        if (s < p.T) gemm_acc_quad<PPW>(acc, cQ, Wm, 0, i, g);  // + Q Z1; Q_0 = 0 for the last factor
         __syncthreads();
         fresh = false;
         if (!last) {

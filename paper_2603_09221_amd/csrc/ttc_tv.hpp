@@ -270,11 +270,13 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_tv_kernel(const TvRollou
 
 // The same at d = 16 with four problems per wavefront (see ttc_small.hpp): products of the four problems
 // interleaved on the matrix cores, their dense solves side by side with one row per lane.
-template <typename TIn>
+// PPW = problems per wavefront: 4 for batches that fill the chip, 1 for small ones (the four rows of 16 lanes
+// then all hold the same problem; every per-problem loop runs once).
+template <typename TIn, int PPW>
 __global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) {
   constexpr int D = 16;
   using C = Cfg<D>;
-  constexpr int PPW = 4;
+  static_assert(PPW == 1 || PPW == 4, "one problem or four per wavefront");
   __shared__ __attribute__((aligned(16))) float Wm[PPW][D * C::PITCH];
   __shared__ float s_red[C::NW];
   const SolveArgs& p = ta.s;
@@ -295,8 +297,8 @@ __global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) 
       Qp[q] = reinterpret_cast<const TIn*>(p.Q) + prob[q] * p.sQ;
       Rp[q] = reinterpret_cast<const TIn*>(p.R) + prob[q] * p.sR;
     }
-    float* const Wmine = Wm[g];  // the problem whose rows this lane holds during the dense solves
-    int info[PPW] = {0, 0, 0, 0};
+    float* const Wmine = Wm[g & (PPW - 1)];  // the problem whose rows this lane holds during the dense solves
+    int info[PPW] = {};
     int nsolve = 0;
     auto note = [&](int bad) {
       ++nsolve;
@@ -332,9 +334,9 @@ __global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) 
               zero_acc<D>(accPA[q]);
               zero_acc<D>(accPB[q]);
             }
-            gemm_acc_quad(accPA, cP, Wm, 0, i, g);  // P A
+            gemm_acc_quad<PPW>(accPA, cP, Wm, 0, i, g);  // P A
             __syncthreads();
-            gemm_acc_quad(accPB, cP, Wm, D, i, g);  // P B
+            gemm_acc_quad<PPW>(accPB, cP, Wm, D, i, g);  // P B
           }
 #pragma unroll
           for (int q = 0; q < PPW; ++q) {
@@ -356,9 +358,9 @@ __global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) 
           zero_acc<D>(accF[q]);
           zero_acc<D>(pn[q]);
         }
-        gemm_acc_quad(accS, cBT, Wm, D, i, g);  // S = R + B^T P B
-        gemm_acc_quad(accF, cBT, Wm, 0, i, g);  // F = B^T P A
-        gemm_acc_quad(pn, cAT, Wm, 0, i, g);    // A^T P A
+        gemm_acc_quad<PPW>(accS, cBT, Wm, D, i, g);  // S = R + B^T P B
+        gemm_acc_quad<PPW>(accF, cBT, Wm, 0, i, g);  // F = B^T P A
+        gemm_acc_quad<PPW>(pn, cAT, Wm, 0, i, g);    // A^T P A
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], accS[q], w, i, g);
