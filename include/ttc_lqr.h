@@ -206,6 +206,16 @@ typedef struct {
 ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t *problem, const ttc_lqr_solution_t *solution,
                                void *hip_stream);
 
+/* Roll-out of n structured problems (Alg. 1, forward loop, r = 0) under the optimal feedback: U (n, T, d),
+ * X (n, T+1, d) and cost (n) = sum_t u_t^T R_t u_t + x_t^T Q_t x_t over t = 1..T, which equals `value` of
+ * ttc_lqr_solve_cxt.  Two launches: the backward sweep of ttc_lqr_solve_cxt keeping every gain K_t, then the
+ * closed loop forward.  The workspace is a DEVICE buffer of at least
+ * ttc_lqr_cxt_rollout_workspace_bytes(problem) bytes (n*(T+3)*d*d floats and n flags), 16-byte aligned
+ * (TTC_ERR_WORKSPACE otherwise).  X, cost and info may be NULL; info and NaN outputs as for ttc_lqr_solve_cxt. */
+size_t ttc_lqr_cxt_rollout_workspace_bytes(const ttc_lqr_cxt_problem_t *problem);
+ttc_status_t ttc_lqr_rollout_cxt(const ttc_lqr_cxt_problem_t *problem, float *U, float *X, float *cost,
+                                 int32_t *info, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *ttc_status_string(ttc_status_t status);
 

@@ -243,3 +243,9 @@ def contextual_solve(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T
     """P0, K0, u0, value of the problem whose steps are contextual_parameters(...)."""
     A, B, Q, R = contextual_parameters(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, T)
     return riccati_solve_tv(A, B, Q, R, x0)
+
+
+def contextual_rollout(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T):
+    """Closed-loop roll-out (U, X, cost) of the problem whose steps are contextual_parameters(...)."""
+    A, B, Q, R = contextual_parameters(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, T)
+    return riccati_rollout_tv(A, B, Q, R, x0)

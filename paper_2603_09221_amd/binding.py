@@ -21,7 +21,8 @@ TTC_FLAG_PURE_SYMPLECTIC = 2
 TTC_FLAG_DOUBLING = 4
 
 EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
-           "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_lqr_solve_tv_scan",
+           "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_lqr_rollout_cxt",
+           "ttc_lqr_cxt_rollout_workspace_bytes", "ttc_lqr_solve_tv_scan",
            "ttc_lqr_tv_scan_workspace_bytes", "ttc_status_string", "ttc_version")
 
 
@@ -92,6 +93,11 @@ def load():
                                           c_void_p]
     lib.ttc_lqr_solve_cxt.restype = c_int
     lib.ttc_lqr_solve_cxt.argtypes = [ctypes.POINTER(CxtProblem), ctypes.POINTER(Solution), c_void_p]
+    lib.ttc_lqr_cxt_rollout_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_cxt_rollout_workspace_bytes.argtypes = [ctypes.POINTER(CxtProblem)]
+    lib.ttc_lqr_rollout_cxt.restype = c_int
+    lib.ttc_lqr_rollout_cxt.argtypes = [ctypes.POINTER(CxtProblem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        c_size_t, c_void_p]
     lib.ttc_status_string.restype = c_char_p
     lib.ttc_status_string.argtypes = [c_int]
     lib.ttc_version.restype = c_int
@@ -327,4 +333,21 @@ def ttc_lqr_solve_cxt(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, 
     out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
     sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
     _check(lib.ttc_lqr_solve_cxt(ctypes.byref(prob), ctypes.byref(sol), _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_rollout_cxt(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T, *, workspace=None, stream=None):
+    """U (n,T,d), X (n,T+1,d), cost (n), info (n) of n structured problems under the optimal feedback."""
+    lib = load()
+    prob = make_cxt_problem(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T)
+    n, d, dev = prob.n, prob.d, sA.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = {"U": torch.empty((n, T, d), **f32), "X": torch.empty((n, T + 1, d), **f32),
+           "cost": torch.empty((n,), **f32), "info": torch.empty((n,), dtype=torch.int32, device=dev)}
+    need = lib.ttc_lqr_cxt_rollout_workspace_bytes(ctypes.byref(prob))
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    _check(lib.ttc_lqr_rollout_cxt(ctypes.byref(prob), _ptr(out["U"]), _ptr(out["X"]), _ptr(out["cost"]),
+                                   _ptr(out["info"]), c_void_p(workspace.data_ptr()), workspace.numel(),
+                                   _stream_ptr(stream)))
     return out

@@ -24,6 +24,8 @@ struct CxtArgs {
   int r;
   const void *sA, *sB, *sQ, *sQf, *rinv, *lgA, *lgB, *lgQ;  // (n,16) vectors, (n,r) coefficients
   const void *Bbasis, *Qbasis;                              // (r,16,16), shared by all problems
+  // roll-out only: per problem (T+3) matrices of 256 floats: Bbar, Qbar, Q_T, K_0 .. K_{T-1}; NULL for a plain solve
+  float* roll_ws = nullptr;
 };
 
 #ifndef TTC_CXT_WAVES
@@ -116,6 +118,16 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
           Qbar[q][v] += cq * qb[v];
           pn[q][0][0][v] += cf * qb[v];  // P_T = Q_T
         }
+      }
+    }
+    if (ca.roll_ws) {
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+        if (!valid[q]) continue;
+        float* const e = ca.roll_ws + prob[q] * (long long)(p.T + 3) * D * D;
+        write_rows_global<D>(e, reinterpret_cast<const floatx4(&)[1]>(Bbar[q]), 0, i, g);
+        write_rows_global<D>(e + D * D, reinterpret_cast<const floatx4(&)[1]>(Qbar[q]), 0, i, g);
+        write_rows_global<D>(e + 2 * D * D, pn[q][0], 0, i, g);
       }
     }
     // the modulation of step s (the paper's t = s + 1), entry i of problem g: a_t, gamma_B^t, gamma_Q^(t-1)
@@ -214,6 +226,12 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
           for (int q = 0; q < PPW; ++q)
             pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cFT[q][0][t], -accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
       }
+      if (ca.roll_ws) {  // the gain K_s of this step, for the forward sweep
+#pragma unroll
+        for (int q = 0; q < PPW; ++q)
+          if (valid[q])
+            write_rows_global<D>(ca.roll_ws + (prob[q] * (long long)(p.T + 3) + 3 + s) * D * D, accW[q][0], 0, i, g);
+      }
       if (s >= 1) {
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
@@ -241,6 +259,10 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
           if (!valid[q]) continue;  // uniform over the wavefront
+          if (ca.roll_ws) {         // the roll-out wants the gains (written above) and info only
+            if (tid == 0 && p.info) p.info[prob[q]] = info[q];
+            continue;
+          }
           const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
           floatx4 acc[C::RB][C::NT];
 #pragma unroll
@@ -253,6 +275,72 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
       }
     }
     if (quad + gridDim.x >= nquads) tm.dump(reinterpret_cast<long long*>(p.P0) + p.n * (D * D / 2));
+  }
+}
+
+struct CxtRolloutArgs {
+  CxtArgs c;  // the problems; c.roll_ws filled by solve_cxt_kernel, c.s.info written by it
+  float *U, *X, *cost;
+};
+
+// Closed-loop forward sweep of the structured problems (Alg. 1, forward loop, r = 0), 16 lanes per problem,
+// lane i owning entry i of the state and of the control:  u_s = K_s x_s,  x_{s+1} = a_t x_s + Bbar (gamma_B^t u_s)
+// (t = s + 1),  cost += u_s^T R u_s + x_{s+1}^T Q_t x_{s+1}  with  Q_t = Gamma_Q^t Qbar Gamma_Q^t  for t < T and Q_T.
+template <typename TIn>
+__global__ void __launch_bounds__(64) rollout_cxt_forward_kernel(const CxtRolloutArgs ra) {
+  constexpr int D = 16;
+  __shared__ float xs[4][D], us[4][D];
+  const CxtArgs& ca = ra.c;
+  const SolveArgs& p = ca.s;
+  const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+  const long long ngroups = (p.n + 3) / 4;
+  const float nanv = __builtin_nanf("");
+  auto row_dot = [&](const float* M, const float* v) {  // sum_j M[i][j] v[j], M row-major in global memory
+    float acc = 0.f;
+#pragma unroll
+    for (int j4 = 0; j4 < D; j4 += 4) {
+      const floatx4 m = *reinterpret_cast<const floatx4*>(M + i * D + j4);
+      acc += m[0] * v[j4] + m[1] * v[j4 + 1] + m[2] * v[j4 + 2] + m[3] * v[j4 + 3];
+    }
+    return acc;
+  };
+  for (long long grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+    const bool valid = grp * 4 + g < p.n;
+    const long long prob = valid ? grp * 4 + g : p.n - 1;
+    const float* const e = ca.roll_ws + prob * (long long)(p.T + 3) * D * D;
+    const float sA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sA), prob * D + i);
+    const float lgA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgA), prob * D + i);
+    const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgB), prob * D + i);
+    const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgQ), prob * D + i);
+    const float r_m = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(ca.rinv), prob * D + i);
+    const bool bad = p.info && p.info[prob] != 0;
+    float x = ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), prob * p.sx0 + i);
+    float cost = 0.f;
+    if (valid && ra.X) ra.X[prob * (long long)(p.T + 1) * D + i] = bad ? nanv : x;
+    for (int s = 0; s < p.T; ++s) {
+      const float tf = -1.44269504f * (float)(s + 1);
+      __syncthreads();  // the previous step's reads of xs, us are done
+      xs[g][i] = x;
+      __syncthreads();
+      const float u = row_dot(e + (long long)(3 + s) * D * D, xs[g]);
+      us[g][i] = __builtin_amdgcn_exp2f(tf * lgB_m) * u;
+      __syncthreads();
+      const float a = 1.f + __builtin_amdgcn_exp2f(tf * lgA_m) * sA_m;
+      x = a * x + row_dot(e, us[g]);
+      __syncthreads();  // reads of xs are done
+      const bool last = (s == p.T - 1);
+      const float y = last ? x : __builtin_amdgcn_exp2f(tf * lgQ_m) * x;
+      xs[g][i] = y;
+      __syncthreads();
+      const float qy = row_dot(last ? e + 2 * D * D : e + D * D, xs[g]);
+      cost += sum16(u * u * r_m + y * qy);
+      if (valid) {
+        ra.U[(prob * (long long)p.T + s) * D + i] = bad ? nanv : u;
+        if (ra.X) ra.X[(prob * (long long)(p.T + 1) + s + 1) * D + i] = bad ? nanv : x;
+      }
+    }
+    if (valid && i == 0 && ra.cost) ra.cost[prob] = bad ? nanv : cost;
+    __syncthreads();
   }
 }
 

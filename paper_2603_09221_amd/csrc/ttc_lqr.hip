@@ -1122,8 +1122,8 @@ ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t* q, const ttc_lqr_
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 
-ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_solution_t* solution, void* hip_stream) {
-  if (!q || !solution || q->n < 0 || q->T < 1 || q->r < 1 || q->d < 1 || q->flags != 0) return TTC_ERR_INVALID_ARG;
+static ttc_status_t validate_cxt(const ttc_lqr_cxt_problem_t* q) {
+  if (!q || q->n < 0 || q->T < 1 || q->r < 1 || q->d < 1 || q->flags != 0) return TTC_ERR_INVALID_ARG;
   if (q->in_dtype != TTC_F32 && q->in_dtype != TTC_BF16) return TTC_ERR_INVALID_ARG;
   if (q->d != 16 || q->r > ttc::CXT_RMAX) return TTC_ERR_UNSUPPORTED;
   if (q->n == 0) return TTC_OK;
@@ -1131,9 +1131,10 @@ ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_sol
   const size_t esz = q->in_dtype == TTC_BF16 ? 2 : 4;
   for (const void* ptr : ins)
     if (!ptr || !ttc::aligned_ptr(ptr, esz)) return TTC_ERR_INVALID_ARG;
-  if (!solution->u0) return TTC_ERR_INVALID_ARG;
-  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
-  ttc::CxtArgs a;
+  return TTC_OK;
+}
+
+static void fill_cxt_args(ttc::CxtArgs& a, const ttc_lqr_cxt_problem_t* q) {
   a.s.n = q->n;
   a.s.T = q->T;
   a.s.flags = 0;
@@ -1143,20 +1144,22 @@ ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_sol
   a.s.x0 = q->x0;
   a.s.sA = a.s.sB = a.s.sQ = a.s.sR = a.s.sQT = 0;
   a.s.sx0 = q->d;
-  a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
-  a.s.info = solution->info;
+  a.s.P0 = a.s.K0 = a.s.u0 = a.s.value = nullptr;
+  a.s.info = nullptr;
   a.s.ws = nullptr;
   a.r = q->r;
   a.sA = q->sA; a.sB = q->sB; a.sQ = q->sQ; a.sQf = q->sQf; a.rinv = q->rinv;
   a.lgA = q->lgA; a.lgB = q->lgB; a.lgQ = q->lgQ;
   a.Bbasis = q->Bbasis; a.Qbasis = q->Qbasis;
-  const bool bf16 = q->in_dtype == TTC_BF16;
+  a.roll_ws = nullptr;
+}
+
+static hipError_t launch_cxt(const ttc::CxtArgs& a, bool bf16, hipStream_t st) {
   const long long gb = ttc::grid_blocks(ttc::KIND_CXT, 16, bf16);
   // batches that do not fill the resident wavefronts four problems at a time go one problem to a wavefront
-  const bool single = q->n <= gb;
-  const long long items = single ? q->n : (q->n + 3) / 4;
+  const bool single = a.s.n <= gb;
+  const long long items = single ? a.s.n : (a.s.n + 3) / 4;
   const dim3 grid((unsigned)(items < gb ? items : gb));
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (single) {
     if (bf16) hipLaunchKernelGGL((ttc::solve_cxt_kernel<uint16_t, 1>), grid, dim3(64), 0, st, a);
     else hipLaunchKernelGGL((ttc::solve_cxt_kernel<float, 1>), grid, dim3(64), 0, st, a);
@@ -1164,6 +1167,52 @@ ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_sol
     if (bf16) hipLaunchKernelGGL((ttc::solve_cxt_kernel<uint16_t, 4>), grid, dim3(64), 0, st, a);
     else hipLaunchKernelGGL((ttc::solve_cxt_kernel<float, 4>), grid, dim3(64), 0, st, a);
   }
+  return hipGetLastError();
+}
+
+ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_solution_t* solution, void* hip_stream) {
+  const ttc_status_t sv = validate_cxt(q);
+  if (sv != TTC_OK) return sv;
+  if (!solution) return TTC_ERR_INVALID_ARG;
+  if (q->n == 0) return TTC_OK;
+  if (!solution->u0) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(solution->P0, 16) || !ttc::aligned_ptr(solution->K0, 16)) return TTC_ERR_INVALID_ARG;
+  ttc::CxtArgs a;
+  fill_cxt_args(a, q);
+  a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
+  a.s.info = solution->info;
+  return launch_cxt(a, q->in_dtype == TTC_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TTC_OK
+                                                                                                     : TTC_ERR_DEVICE;
+}
+
+size_t ttc_lqr_cxt_rollout_workspace_bytes(const ttc_lqr_cxt_problem_t* q) {
+  if (validate_cxt(q) != TTC_OK) return 0;
+  // per problem: Bbar, Qbar, Q_T and the T gains (256 floats each), then one breakdown flag per problem
+  const size_t mats = (size_t)q->n * (size_t)(q->T + 3) * 256 * sizeof(float);
+  return mats + (((size_t)q->n * sizeof(int32_t) + 15) & ~(size_t)15);
+}
+
+ttc_status_t ttc_lqr_rollout_cxt(const ttc_lqr_cxt_problem_t* q, float* U, float* X, float* cost, int32_t* info,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t sv = validate_cxt(q);
+  if (sv != TTC_OK) return sv;
+  if (q->n == 0) return TTC_OK;
+  if (!U) return TTC_ERR_INVALID_ARG;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_cxt_rollout_workspace_bytes(q))
+    return TTC_ERR_WORKSPACE;
+  ttc::CxtRolloutArgs ra;
+  fill_cxt_args(ra.c, q);
+  ra.c.roll_ws = static_cast<float*>(workspace);
+  ra.c.s.info = info ? info : reinterpret_cast<int*>(ra.c.roll_ws + (size_t)q->n * (size_t)(q->T + 3) * 256);
+  ra.U = U; ra.X = X; ra.cost = cost;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (launch_cxt(ra.c, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;  // backward sweep: gains into the workspace
+  const long long groups = (q->n + 3) / 4;
+  const long long gb = 32LL * ttc::cu_count();
+  const dim3 grid((unsigned)(groups < gb ? groups : gb));
+  if (bf16) hipLaunchKernelGGL((ttc::rollout_cxt_forward_kernel<uint16_t>), grid, dim3(64), 0, st, ra);
+  else hipLaunchKernelGGL((ttc::rollout_cxt_forward_kernel<float>), grid, dim3(64), 0, st, ra);
   return hipGetLastError() == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 

@@ -195,3 +195,17 @@ def test_pairwise_long_horizon_argument_validation_without_device(lib):
     assert call(_tv_problem(), ws=0x1008) == binding.TTC_ERR_WORKSPACE          # misaligned
     assert call(_tv_problem(), nbytes=need - 1) == binding.TTC_ERR_WORKSPACE
     assert call(_tv_problem(), binding.Solution(None, None, None, None, None)) == binding.TTC_ERR_INVALID_ARG
+
+
+def test_structured_rollout_argument_validation_without_device(lib):
+    call = lambda p, U=0x2000, ws=0x1000, nbytes=1 << 40: lib.ttc_lqr_rollout_cxt(ctypes.byref(p), U, None, None, None, ws,
+                                                                                 nbytes, None)
+    need = lib.ttc_lqr_cxt_rollout_workspace_bytes(ctypes.byref(_cxt_problem()))
+    assert need == 8 * (4 + 3) * 256 * 4 + 32              # gains and combined bases, then 8 flags rounded to 16 bytes
+    assert lib.ttc_lqr_cxt_rollout_workspace_bytes(ctypes.byref(_cxt_problem(d=32))) == 0
+    assert call(_cxt_problem(T=0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(d=32)) == binding.TTC_ERR_UNSUPPORTED
+    assert call(_cxt_problem(n=0)) == binding.TTC_OK
+    assert call(_cxt_problem(), U=None) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(), ws=None) == binding.TTC_ERR_WORKSPACE
+    assert call(_cxt_problem(), nbytes=need - 1) == binding.TTC_ERR_WORKSPACE

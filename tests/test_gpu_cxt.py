@@ -122,3 +122,44 @@ def test_full_size_sample():
     ref = lqr_oracle.contextual_solve(*b.take(idx).numpy64(), b.T)
     for k in ("P0", "K0", "u0", "value"):
         assert float(rel_err(out[k][idx].cpu().numpy(), ref[k]).max()) <= TOL_F32, k
+
+
+def rollout(b, **kw):
+    return binding.ttc_lqr_rollout_cxt(*(getattr(b, k) for k in KEYS), b.T, **kw)
+
+
+@pytest.mark.parametrize("n,r,T,dtype,tol", [(1, 16, 1, "f32", TOL_F32), (37, 16, 8, "f32", TOL_F32),
+                                              (300, 3, 33, "f32", TOL_F32), (2600, 16, 6, "f32", TOL_F32),
+                                              (130, 16, 12, "bf16", TOL_BF16)])
+def test_rollout_matches_the_oracle_trajectory(n, r, T, dtype, tol):
+    b = synth.make_contextual_batch(n, 16, r, T, seed=n + T, device=DEV, dtype=dtype)
+    out = rollout(b)
+    sol = solve(b)
+    torch.cuda.synchronize()
+    assert int(out["info"].abs().max()) == 0
+    U, X, cost = lqr_oracle.contextual_rollout(*b.numpy64(), b.T)
+    assert float(rel_err(out["U"].cpu().numpy().reshape(n, -1), U.reshape(n, -1)).max()) <= tol
+    assert float(rel_err(out["X"].cpu().numpy().reshape(n, -1), X.reshape(n, -1)).max()) <= tol
+    assert float(rel_err(out["cost"].cpu().numpy(), cost).max()) <= tol
+    # the accumulated cost is the value of the solve, and the first control is u_0
+    assert float(rel_err(out["cost"].cpu().numpy(), sol["value"].cpu().numpy()).max()) <= 10 * tol
+    assert float(rel_err(out["U"][:, 0].cpu().numpy(), sol["u0"].cpu().numpy()).max()) <= tol
+
+
+def test_rollout_breakdown_and_workspace():
+    b = synth.make_contextual_batch(50, 16, 16, 5, seed=3, device=DEV)
+    good = rollout(b)
+    rinv = b.rinv.clone()
+    rinv[17] = -0.01
+    b.rinv = rinv
+    bad = rollout(b)
+    torch.cuda.synchronize()
+    info = bad["info"].cpu().numpy()
+    assert info[17] == 1 and (np.delete(info, 17) == 0).all()
+    assert torch.isnan(bad["U"][17]).all() and torch.isnan(bad["cost"][17])
+    keep = torch.tensor([0, 16, 18, 49], device=DEV)
+    assert torch.equal(bad["U"][keep], good["U"][keep])
+    small = torch.empty((50 * 8 * 256 * 4,), dtype=torch.uint8, device=DEV)   # the flags do not fit
+    with pytest.raises(binding.TtcError) as e:
+        rollout(b, workspace=small)
+    assert e.value.status == binding.TTC_ERR_WORKSPACE

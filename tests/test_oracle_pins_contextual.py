@@ -147,3 +147,16 @@ def test_batched_equals_single():
         one = orc.contextual_solve(*(a[j] if a.ndim == 2 and a.shape[0] == 6 else a for a in args), x0[j], 4)
         np.testing.assert_allclose(s["P0"][j], one["P0"], rtol=1e-12)
         np.testing.assert_allclose(s["u0"][j], one["u0"], rtol=1e-12)
+
+
+def test_rollout_cost_is_the_value_and_follows_the_dynamics():
+    args, x0 = draw(4, 3, 7, n=5)
+    T = 6
+    U, X, cost = orc.contextual_rollout(*args, x0, T)
+    s = orc.contextual_solve(*args, x0, T)
+    np.testing.assert_allclose(cost, s["value"], rtol=1e-10)
+    np.testing.assert_allclose(U[:, 0], s["u0"], rtol=1e-12)
+    A, B, Q, R = orc.contextual_parameters(*args, T=T)
+    for t in range(T):
+        np.testing.assert_allclose(X[:, t + 1], np.einsum("nij,nj->ni", A[:, t], X[:, t]) +
+                                   np.einsum("nij,nj->ni", B[:, t], U[:, t]), rtol=1e-12, atol=1e-13)
