@@ -30,7 +30,8 @@ PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 f
 MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (38.64e6 + 27.51e6) * 1024 / 65536,
                                       ("llm_adapter", "doubling"): (112.3e6 + 76.1e6) * 1024 / 65536,
                                       ("llm_adapter", "tv"): (82.69e6 + 3.090e6) * 1024 / 16384,
-                                      ("ttc_layer_d16", 8): (645.6e3 + 2.747e6) * 1024 / 1048576}
+                                      ("ttc_layer_d16", 8): (645.6e3 + 2.747e6) * 1024 / 1048576,
+                                      ("tiny", 3): (1.0657e6 + 0.5448e6) * 1024 / 262144}
 def default_groups(T, dtype):
     """The library default: number of groups the T factors are split into (one dense solve each)."""
     return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
@@ -409,7 +410,8 @@ def main():
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[traffic_key] * n
                                  if traffic_key in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
                      "kernel": {"doubling": "doubling_kernel<%d>", "tv": "solve_tv_kernel<%d>"}.get(
-                         args.path, "solve_kernel<%d>") % d,
+                         args.path, "solve_kernel<%d>") % d if d != 16 or args.path == "doubling" else
+                     ("solve_tv_small_kernel" if args.path == "tv" else "solve_small_kernel"),
                      "kernel_ms": avg_kernel_s * 1e3,
                      "alg_flops_per_problem": flops_pp,
                      "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / avg_kernel_s / 1e12,
