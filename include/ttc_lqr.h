@@ -187,7 +187,10 @@ ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t *problem, const tt
  * All pointers are DEVICE pointers, borrowed and read-only, of element type in_dtype, contiguous:
  * sA, rinv, lgA, lgB, lgQ, x0 are (n, d); sB, sQ, sQf are (n, r); Bbasis, Qbasis are (r, d, d) row-major.
  * The problem solved needs rinv > 0 and the combined Q matrices positive semi-definite (they are read as
- * their symmetric parts); lgX >= 0 gives the discounting of the paper, any finite value is accepted. */
+ * their symmetric parts); lgX >= 0 gives the discounting of the paper, any finite value is accepted.
+ * Accuracy: float32 throughout; when control is nearly free (rinv several orders of magnitude above the
+ * state costs) P_0 is a small difference of large terms in the recursion of Prop. 3.1 and digits are lost
+ * in proportion, as in any float32 evaluation of it. */
 typedef struct {
   int64_t n;        /* problems = batch * heads * tokens */
   int32_t d;        /* state = control dimension; 16 is supported */

@@ -163,3 +163,20 @@ def test_rollout_breakdown_and_workspace():
     with pytest.raises(binding.TtcError) as e:
         rollout(b, workspace=small)
     assert e.value.status == binding.TTC_ERR_WORKSPACE
+
+
+def test_extreme_modulation_and_weights():
+    """Modulation that underflows to zero within the horizon, very large and small control weights.  (Much cheaper
+    control, rinv of 1e4 against costs of order one, leaves P_0 as a small difference of large terms: the recursion
+    of Prop. 3.1 evaluated in float32 by numpy then loses three digits as well; that is outside the 1e-4 claim.)"""
+    b = synth.make_contextual_batch(96, 16, 16, 8, seed=21, device=DEV)
+    b.lgA = torch.full_like(b.lgA, 50.0)
+    b.lgB = b.lgB.clone()
+    b.lgB[:32] = 40.0
+    b.lgQ = b.lgQ.clone()
+    b.lgQ[32:64] = 60.0
+    rinv = b.rinv.clone()
+    rinv[64:80] = 1e-5
+    rinv[80:] = 30.0
+    b.rinv = rinv
+    check(b, TOL_F32)
