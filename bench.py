@@ -89,7 +89,7 @@ def bench_cxt(args):
     import numpy as np
     import torch
     from paper_2603_09221_amd import binding, synth
-    from tests.parity import rel_err
+    from paper_2603_09221_amd.errors import rel_err
 
     d, r, T = 16, 16, args.horizon or 8
     n = args.n or 8 * 16 * 8192
@@ -188,7 +188,7 @@ def bench_scan(args):
     import torch
     from oracle import lqr_oracle
     from paper_2603_09221_amd import binding, synth
-    from tests.parity import rel_err
+    from paper_2603_09221_amd.errors import rel_err
 
     d, T = 16, args.horizon or 2048
     n = args.n or 16
@@ -326,7 +326,7 @@ def main():
     import numpy as np
     import torch
     from paper_2603_09221_amd import binding, synth
-    from tests.parity import rel_err
+    from paper_2603_09221_amd.errors import rel_err
 
     cfg = synth.CONFIGS[args.config]
     n = args.n or (min(16384, synth.config_problems(args.config)) if args.path == "tv"

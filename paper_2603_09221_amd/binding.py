@@ -164,6 +164,16 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
+def _scratch(nbytes, dev, stream):
+    """A workspace the wrapper owns: allocated for, and only released to, the stream the kernels run on (the
+    caching allocator would otherwise hand the block to other work on the current stream while the launch,
+    on another stream, still uses it)."""
+    if stream is None or stream == torch.cuda.current_stream():
+        return torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=dev)
+    with torch.cuda.stream(stream):
+        return torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=dev)
+
+
 def ttc_lqr_solve(A, B, Q, R, QT, x0, T, *, flags=0, rebase_every=0, want_P0=True, want_K0=True,
                   out=None, workspace=None, stream=None):
     """P0 (n,d,d), K0 (n,m,d), u0 (n,m), value (n), info (n) of n LQR problems; all float32 device tensors.
@@ -184,7 +194,7 @@ def ttc_lqr_solve(A, B, Q, R, QT, x0, T, *, flags=0, rebase_every=0, want_P0=Tru
     sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
     need = lib.ttc_lqr_workspace_bytes(ctypes.byref(prob), 0)
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     _check(lib.ttc_lqr_solve(ctypes.byref(prob), ctypes.byref(sol), c_void_p(workspace.data_ptr()),
                              workspace.numel(), _stream_ptr(stream)))
     return out
@@ -202,7 +212,7 @@ def ttc_lqr_rollout(A, B, Q, R, QT, x0, T, *, flags=0, rebase_every=0, workspace
     info = torch.empty((n,), dtype=torch.int32, device=dev)
     need = lib.ttc_lqr_workspace_bytes(ctypes.byref(prob), 1)
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     _check(lib.ttc_lqr_rollout(ctypes.byref(prob), c_void_p(U.data_ptr()), c_void_p(X.data_ptr()),
                                c_void_p(cost.data_ptr()), c_void_p(info.data_ptr()),
                                c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
@@ -271,7 +281,7 @@ def ttc_lqr_solve_tv_scan(A, B, Q, R, x0, *, want_P0=True, want_K0=True, out=Non
     out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
     need = lib.ttc_lqr_tv_scan_workspace_bytes(ctypes.byref(prob))
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
     _check(lib.ttc_lqr_solve_tv_scan(ctypes.byref(prob), ctypes.byref(sol), c_void_p(workspace.data_ptr()),
                                      workspace.numel(), _stream_ptr(stream)))
@@ -288,7 +298,7 @@ def ttc_lqr_rollout_tv(A, B, Q, R, x0, *, workspace=None, stream=None):
            "cost": torch.empty((n,), **f32), "info": torch.empty((n,), dtype=torch.int32, device=dev)}
     need = lib.ttc_lqr_tv_rollout_workspace_bytes(ctypes.byref(prob))
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     _check(lib.ttc_lqr_rollout_tv(ctypes.byref(prob), _ptr(out["U"]), _ptr(out["X"]), _ptr(out["cost"]),
                                   _ptr(out["info"]), c_void_p(workspace.data_ptr()), workspace.numel(),
                                   _stream_ptr(stream)))
@@ -346,7 +356,7 @@ def ttc_lqr_rollout_cxt(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0
            "cost": torch.empty((n,), **f32), "info": torch.empty((n,), dtype=torch.int32, device=dev)}
     need = lib.ttc_lqr_cxt_rollout_workspace_bytes(ctypes.byref(prob))
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+        workspace = _scratch(need, dev, stream)
     _check(lib.ttc_lqr_rollout_cxt(ctypes.byref(prob), _ptr(out["U"]), _ptr(out["X"]), _ptr(out["cost"]),
                                    _ptr(out["info"]), c_void_p(workspace.data_ptr()), workspace.numel(),
                                    _stream_ptr(stream)))

@@ -1,0 +1,17 @@
+// solve_kernel<TTC_D> (ttc_lqr_solve, default path, d >= 32): one translation unit per state size.
+#include "ttc_solve.hpp"
+#include "ttc_launch.hpp"
+
+namespace ttc {
+template <>
+hipError_t launch_solve<TTC_D>(const SolveArgs& a, bool bf16, dim3 grid, hipStream_t st) {
+  if (bf16) hipLaunchKernelGGL((solve_kernel<TTC_D, uint16_t>), grid, dim3(Cfg<TTC_D>::NTHR), 0, st, a);
+  else hipLaunchKernelGGL((solve_kernel<TTC_D, float>), grid, dim3(Cfg<TTC_D>::NTHR), 0, st, a);
+  return hipGetLastError();
+}
+template <>
+int occupancy_solve<TTC_D>(bool bf16) {
+  return bf16 ? occupancy_query(solve_kernel<TTC_D, uint16_t>, Cfg<TTC_D>::NTHR)
+              : occupancy_query(solve_kernel<TTC_D, float>, Cfg<TTC_D>::NTHR);
+}
+}  // namespace ttc

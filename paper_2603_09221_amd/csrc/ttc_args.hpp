@@ -1,0 +1,74 @@
+// Kernel argument blocks (plain structs passed by value at launch), shared by the host entry points and
+// the kernel translation units.
+#pragma once
+#include <stdint.h>
+
+namespace ttc {
+
+struct SolveArgs {
+  long long n;
+  int T, flags, ngroups;  // the T factors are applied in ngroups groups, one dense solve each
+  const void *A, *B, *Q, *R, *QT, *x0;
+  long long sA, sB, sQ, sR, sQT, sx0;
+  float *P0, *K0, *u0, *value;
+  int* info;
+  float* ws;  // gridDim.x slots of d*d floats (C_K of the problem in flight, register layout); more for doubling
+#ifdef TTC_PHASE_TIMERS
+  long long* dbg = nullptr;  // development builds only: 8 cycle counters, accumulated by workgroup 0
+#endif
+};
+
+struct RolloutArgs {
+  long long n;
+  int T, flags;
+  const void *A, *B, *Q, *R, *QT, *x0;
+  long long sA, sB, sQ, sR, sQT, sx0;
+  float *U, *X, *cost;
+  int* info;
+  float* ws;  // gridDim.x slots of (T+3) d*d floats: G, R^{-1} B^T, A^T (register layout), K_0 .. K_{T-1}
+};
+
+struct DoublingArgs {
+  SolveArgs s;  // problem, outputs, workspace (ngroups unused)
+  int m;        // number of one-step maps composed before the last step (T, or T-1 when Q_T is given)
+  int p_from_qt;  // 1: the backward recursion starts at Q_T; 0: it starts at 0 (Q_T is Q = f(0))
+};
+
+// workspace slots of a workgroup, d*d floats each
+enum { DBL_A = 0, DBL_G = 1, DBL_H = 2, DBL_G0 = 3, DBL_P = 4, DBL_X = 5, DBL_SLOTS = 6 };
+
+struct TvArgs {
+  SolveArgs s;                 // n, T, A, B, Q, R, x0 and their problem strides, outputs (QT, ws, groups unused)
+  long long tA, tB, tQ, tR;    // elements between consecutive steps
+  const float* PT = nullptr;   // if set: the terminal value matrix, fp32, instead of Q[T-1] (solve_tv_kernel only)
+  long long sPT = 0;           // elements between consecutive problems of PT
+};
+
+struct TvRolloutArgs {
+  RolloutArgs r;               // n, T, A, B, Q, R, x0 and their problem strides, U, X, cost, info, ws (QT unused)
+  long long tA, tB, tQ, tR;    // elements between consecutive steps
+};
+
+struct ScanArgs {
+  TvArgs tv;   // the problems (inputs only)
+  float* ws;   // n*T elements of 3 d^2 floats
+  int stride;  // combine rounds: the stride st
+};
+
+constexpr int CXT_RMAX = 64;  // most basis matrices per group
+
+struct CxtArgs {
+  SolveArgs s;  // n, T, x0 (stride 16), outputs; flags = 0; the matrix inputs are unused
+  int r;
+  const void *sA, *sB, *sQ, *sQf, *rinv, *lgA, *lgB, *lgQ;  // (n,16) vectors, (n,r) coefficients
+  const void *Bbasis, *Qbasis;                              // (r,16,16), shared by all problems
+  // roll-out only: per problem (T+3) matrices of 256 floats: Bbar, Qbar, Q_T, K_0 .. K_{T-1}; NULL for a plain solve
+  float* roll_ws = nullptr;
+};
+
+struct CxtRolloutArgs {
+  CxtArgs c;  // the problems; c.roll_ws filled by solve_cxt_kernel, c.s.info written by it
+  float *U, *X, *cost;
+};
+
+}  // namespace ttc

@@ -14,19 +14,11 @@
 // 4g..4g+3) is the A-operand layout of its transpose, which is what lets Bbar, V and P be used in both
 // roles without a trip through LDS.
 #pragma once
+#include "ttc_common.hpp"
+#include "ttc_small.hpp"
 
 namespace ttc {
 
-constexpr int CXT_RMAX = 64;  // most basis matrices per group
-
-struct CxtArgs {
-  SolveArgs s;  // n, T, x0 (stride 16), outputs; flags = 0; the matrix inputs are unused
-  int r;
-  const void *sA, *sB, *sQ, *sQf, *rinv, *lgA, *lgB, *lgQ;  // (n,16) vectors, (n,r) coefficients
-  const void *Bbasis, *Qbasis;                              // (r,16,16), shared by all problems
-  // roll-out only: per problem (T+3) matrices of 256 floats: Bbar, Qbar, Q_T, K_0 .. K_{T-1}; NULL for a plain solve
-  float* roll_ws = nullptr;
-};
 
 #ifndef TTC_CXT_WAVES
 #define TTC_CXT_WAVES 2  // wavefronts per SIMD the register allocation aims at
@@ -274,14 +266,10 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
         tm.toc(3);
       }
     }
-    if (quad + gridDim.x >= nquads) tm.dump(reinterpret_cast<long long*>(p.P0) + p.n * (D * D / 2));
+    if (quad + gridDim.x >= nquads) tm.dump(p);
   }
 }
 
-struct CxtRolloutArgs {
-  CxtArgs c;  // the problems; c.roll_ws filled by solve_cxt_kernel, c.s.info written by it
-  float *U, *X, *cost;
-};
 
 // Closed-loop forward sweep of the structured problems (Alg. 1, forward loop, r = 0), 16 lanes per problem,
 // lane i owning entry i of the state and of the control:  u_s = K_s x_s,  x_{s+1} = a_t x_s + Bbar (gamma_B^t u_s)

@@ -1,5 +1,4 @@
 // Long-horizon path of the solver: the Riccati steps of a time-invariant problem composed by squaring.
-// Included by ttc_lqr.hip after the helpers it shares with the symplectic kernel.
 //
 // One backward step of Prop. 3.1, written with G = B R^{-1} B^T (the G of Thm 3.3), is the map
 //     f_e(P) = H_e + A_e^T P (I + G_e P)^{-1} A_e          of the element e = (A_e, G_e, H_e) = (A, G, Q).
@@ -21,6 +20,7 @@
 // (L2/Infinity-Cache resident, 64 KB each at d = 128) and is pulled into LDS or registers in the role
 // each product needs; a wavefront only ever rewrites the rows it alone reads in that phase.
 #pragma once
+#include "ttc_common.hpp"
 
 namespace ttc {
 
@@ -209,14 +209,6 @@ __device__ __forceinline__ int mobius_solve(float* W, SolveScratch<D>& S, const 
   return flag;
 }
 
-struct DoublingArgs {
-  SolveArgs s;  // problem, outputs, workspace (gend / ngroups unused)
-  int m;        // number of one-step maps composed before the last step (T, or T-1 when Q_T is given)
-  int p_from_qt;  // 1: the backward recursion starts at Q_T; 0: it starts at 0 (Q_T is Q = f(0))
-};
-
-// workspace slots of a workgroup, d*d floats each
-enum { DBL_A = 0, DBL_G = 1, DBL_H = 2, DBL_G0 = 3, DBL_P = 4, DBL_X = 5, DBL_SLOTS = 6 };
 
 template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingArgs da) {
@@ -345,7 +337,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) doubling_kernel(const DoublingAr
     emit_gain<D, TIn>(p, prob, acc, x0p, info, tid);
     emit_value<D, TIn>(p, prob, WL, Qp, x0p, info, s_red, tid);
     tm.toc(4);
-    tm.dump(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * DBL_SLOTS * D * D / 2);
+    tm.dump(p);
   }
 }
 

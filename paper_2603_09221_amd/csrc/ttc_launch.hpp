@@ -1,0 +1,46 @@
+// Host-side interface between the C-ABI entry points (ttc_api.hip) and the kernel families, each of which
+// is compiled in its own translation unit, once per state size D (the kernels are templates over D and
+// the input element type; a translation unit defines the specialisations for its -DTTC_D).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "ttc_args.hpp"
+
+namespace ttc {
+
+// launch_*: enqueue the kernel on `st` with `grid` workgroups; bf16 selects the bfloat16-input instance.
+// occupancy_*: resident workgroups per compute unit the runtime reports for that instance (0 on error).
+template <int D> hipError_t launch_solve(const SolveArgs& a, bool bf16, dim3 grid, hipStream_t st);
+template <int D> int occupancy_solve(bool bf16);
+template <int D> hipError_t launch_doubling(const DoublingArgs& a, bool bf16, dim3 grid, hipStream_t st);
+template <int D> int occupancy_doubling(bool bf16);
+template <int D> hipError_t launch_rollout(const RolloutArgs& a, bool bf16, dim3 grid, hipStream_t st);
+template <int D> int occupancy_rollout(bool bf16);
+template <int D> hipError_t launch_tv(const TvArgs& a, bool bf16, dim3 grid, hipStream_t st);
+template <int D> int occupancy_tv(bool bf16);
+template <int D> hipError_t launch_rollout_tv(const TvRolloutArgs& a, bool bf16, dim3 grid, hipStream_t st);
+template <int D> int occupancy_rollout_tv(bool bf16);
+template <int D> hipError_t launch_scan_leaf(const ScanArgs& a, bool bf16, dim3 grid, hipStream_t st);
+template <int D> hipError_t launch_scan_combine(const ScanArgs& a, dim3 grid, hipStream_t st);
+template <int D> int occupancy_scan();
+
+// d = 16 only; ppw = problems per wavefront (1 or 4)
+hipError_t launch_small(const SolveArgs& a, bool bf16, int ppw, dim3 grid, hipStream_t st);
+int occupancy_small(bool bf16);
+hipError_t launch_tv_small(const TvArgs& a, bool bf16, int ppw, dim3 grid, hipStream_t st);
+int occupancy_tv_small(bool bf16);
+hipError_t launch_cxt(const CxtArgs& a, bool bf16, int ppw, dim3 grid, hipStream_t st);
+int occupancy_cxt(bool bf16);
+hipError_t launch_rollout_cxt_forward(const CxtRolloutArgs& a, bool bf16, dim3 grid, hipStream_t st);
+
+template <typename K>
+inline int occupancy_query(K kernel, int nthr) {
+  int nb = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, nthr, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  return nb;
+}
+
+}  // namespace ttc

@@ -1,5 +1,4 @@
 // Time-heterogeneous problems with the backward recursion taken as a tree over the horizon.
-// Included by ttc_lqr.hip after ttc_tv.hpp.
 //
 // One backward step of Prop. 3.1, with G_s = B_s R_s^{-1} B_s^T (the G_t of Thm 3.3), is the map
 //     f_e(P) = H_e + A_e^T P (I + G_e P)^{-1} A_e        of the element e = (A_e, G_e, H_e) = (A_s, G_s, Q_{s-1}),
@@ -18,14 +17,12 @@
 // is written in that round.  A breakdown (R_s not positive definite, I + G_1 H_2 singular) poisons the H it
 // produces with NaN, which the last step turns into info = 1 and NaN outputs for that problem alone.
 #pragma once
+#include "ttc_common.hpp"
+#include "ttc_doubling.hpp"
+#include "ttc_tv.hpp"
 
 namespace ttc {
 
-struct ScanArgs {
-  TvArgs tv;   // the problems (inputs only)
-  float* ws;   // n*T elements of 3 d^2 floats
-  int stride;  // combine rounds: the stride st
-};
 
 template <int D>
 __device__ __forceinline__ void poison(floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT]) {

@@ -1,5 +1,4 @@
 // The d = 16 shape of the solver: four problems per wavefront.
-// Included by ttc_lqr.hip after the helpers it shares with the other kernels.
 //
 // At d = 16 a problem fills a quarter of a wavefront, and the dense solves (one pivot after the other,
 // each a reduction and a broadcast) are most of the instructions.  This kernel gives a workgroup of one
@@ -10,6 +9,7 @@
 // App. C "Kernel Fusion") in groups, a pivoted solve re-basing the pair after each group (Alg. 4's
 // P = Y1^{-1} Y2), the last factor with Q_0 = 0, K_0 = -R^{-1} B^T A^{-T} P_0 (Thm A.4).
 #pragma once
+#include "ttc_common.hpp"
 
 namespace ttc {
 
@@ -311,8 +311,7 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
     int s = 1;
     bool fresh = true;
     for (int grp = 0;; ++grp) {
-      const int gend = p.explicit_groups ? p.gend[grp]
-                                         : p.T - (int)(((long long)(p.ngroups - 1 - grp) * p.T) / p.ngroups);
+      const int gend = p.T - (int)(((long long)(p.ngroups - 1 - grp) * p.T) / p.ngroups);
       for (;; ++s) {
         const bool last = (s >= gend);
 #pragma unroll
@@ -385,7 +384,7 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
     }
     __syncthreads();
     tm.toc(3);
-    tm.dump(reinterpret_cast<long long*>(p.ws) + (long)gridDim.x * D * D / 2);
+    tm.dump(p);
   }
 }
 

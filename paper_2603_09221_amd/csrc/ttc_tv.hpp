@@ -1,6 +1,5 @@
 // Time-heterogeneous problems: A_t, B_t, Q_t, R_t vary over the horizon (the general statement of
 // Prop. 3.1; the paper's "time-heterogeneous parameterization", Sec. 4).
-// Included by ttc_lqr.hip after the helpers it shares with the other kernels.
 //
 // With every factor Sigma_t of Thm 3.3 different, nothing can be prepared once per problem: each factor
 // would need its own A_t^{-1} and G_t = B_t R_t^{-1} B_t^T, two dense solves before the factor is even
@@ -12,15 +11,12 @@
 // Six products and one dense solve per step; the value matrix stays on chip for the whole horizon, the
 // step's matrices are streamed from HBM once each.
 #pragma once
+#include "ttc_common.hpp"
+#include "ttc_small.hpp"
+#include "ttc_rollout.hpp"
 
 namespace ttc {
 
-struct TvArgs {
-  SolveArgs s;                 // n, T, A, B, Q, R, x0 and their problem strides, outputs (QT, ws, groups unused)
-  long long tA, tB, tQ, tR;    // elements between consecutive steps
-  const float* PT = nullptr;   // if set: the terminal value matrix, fp32, instead of Q[T-1] (solve_tv_kernel only)
-  long long sPT = 0;           // elements between consecutive problems of PT
-};
 
 // accumulator rows of this wavefront <- row-major global matrix of input element type
 template <int D, typename TIn>
@@ -173,10 +169,6 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta)
   }
 }
 
-struct TvRolloutArgs {
-  RolloutArgs r;               // n, T, A, B, Q, R, x0 and their problem strides, U, X, cost, info, ws (QT unused)
-  long long tA, tB, tQ, tR;    // elements between consecutive steps
-};
 
 // Roll-out of a time-heterogeneous problem (Alg. 1 with r = 0): the backward sweep of solve_tv_kernel
 // keeping every gain K_s in the workspace, then the closed-loop forward sweep

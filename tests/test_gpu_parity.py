@@ -53,6 +53,34 @@ def test_pure_symplectic_short_horizon():
     check(b, 2e-3, flags=binding.TTC_FLAG_PURE_SYMPLECTIC)
 
 
+@pytest.mark.parametrize("d,n", [(16, 9), (16, 2100), (32, 21), (64, 300), (128, 270)])
+@pytest.mark.parametrize("T", [2, 3])
+def test_pure_symplectic_row_normalisation_every_size(d, n, T):
+    """Alg. 4 with row normalisation after every factor (App. C "Numerical Stability"), at every state size
+    (each has its own thread mapping of the normalisation) and over several passes of the persistent grid.
+    Two or three factors keep cond(Y1) small enough for the float32 tolerance.  The same product without
+    normalisation (one group, rebase_every = T) must agree to rounding: the scales are powers of two, so the
+    rows of [Y1 Y2] are the same numbers up to their exponents; the dense solve may then pick other pivots
+    (it compares magnitudes across rows), so the two results are close, not bit-identical."""
+    b = synth.make_batch(n, d, d, T, seed=40 + d + T, device=DEV)
+    check(b, TOL_F32, flags=binding.TTC_FLAG_PURE_SYMPLECTIC)
+    pure = run(b, flags=binding.TTC_FLAG_PURE_SYMPLECTIC)
+    one_group = run(b, rebase_every=T)
+    assert int(pure["info"].abs().max()) == 0 and int(one_group["info"].abs().max()) == 0
+    for k in ("P0", "K0", "u0", "value"):
+        assert rel_err(pure[k].cpu().numpy(), one_group[k].cpu().numpy()).max() <= 2e-5, k
+
+
+def test_pure_symplectic_rows_of_very_different_scale():
+    """A terminal cost spanning eight orders of magnitude makes the rows of [Y1 Y2] differ by as much; the
+    normalisation must bring every row back to order one without changing Y1^{-1} Y2."""
+    d, T, n = 64, 2, 40
+    b = synth.make_batch(n, d, d, T, seed=77, device=DEV)
+    scale = torch.logspace(-4, 4, d, device=DEV)
+    QT = (b.Q * scale[None, :, None].sqrt() * scale[None, None, :].sqrt()).contiguous()
+    check(b, TOL_F32, QT=QT, flags=binding.TTC_FLAG_PURE_SYMPLECTIC)
+
+
 def test_terminal_cost_and_stage_flag():
     b = synth.make_batch(40, 64, 64, 6, seed=6, device=DEV)
     QT = (2.0 * b.Q + 0.1 * torch.eye(64, device=DEV)).contiguous()
@@ -169,3 +197,25 @@ def test_empty_batch():
     b = synth.make_batch(1, 16, 16, 4, seed=0, device=DEV)
     out = binding.ttc_lqr_solve(b.A[:0], b.B[:0], b.Q[:0], b.R[:0], None, b.x0[:0], 4)
     assert out["u0"].shape == (0, 16)
+
+
+def test_launch_on_a_side_stream():
+    """The call runs on the stream it is given; outputs and the workspace the wrapper allocates must be safe
+    to use although that stream is not the current one."""
+    b = synth.make_batch(300, 128, 128, 6, seed=14, device=DEV)
+    ref = run(b)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    out = binding.ttc_lqr_solve(b.A, b.B, b.Q, b.R, None, b.x0, b.T, stream=side)
+    junk = [torch.full((1 << 22,), float("nan"), device=DEV) for _ in range(8)]   # allocator traffic on the current stream
+    side.synchronize()
+    del junk
+    for k in ("P0", "K0", "u0", "value"):
+        assert torch.equal(out[k], ref[k]), k
+    ro = binding.ttc_lqr_rollout(b.A, b.B, b.Q, b.R, None, b.x0, b.T, stream=side)
+    junk = [torch.full((1 << 22,), float("nan"), device=DEV) for _ in range(8)]
+    side.synchronize()
+    del junk
+    ro_ref = binding.ttc_lqr_rollout(b.A, b.B, b.Q, b.R, None, b.x0, b.T)
+    torch.cuda.synchronize()
+    assert torch.equal(ro["U"], ro_ref["U"]) and torch.equal(ro["cost"], ro_ref["cost"])
