@@ -1,5 +1,5 @@
 // solve_small_kernel (ttc_lqr_solve at d = 16, default path): one or four problems per wavefront.
-#include "ttc_small.hpp"
+#include "ttc_small_kernel.hpp"
 #include "ttc_launch.hpp"
 
 namespace ttc {

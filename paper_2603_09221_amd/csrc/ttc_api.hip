@@ -85,6 +85,14 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
 static long long grid_blocks(Kind kind, int d, bool bf16) {
   return (long long)cu_count() * blocks_per_cu(kind, d, bf16);
 }
+// Growth guard of the symplectic kernels: the largest max |Y1| a group of factors may reach before the problem is
+// handed to the Riccati recursion.  Float32: measured on the benchmark generators and on inputs with R, Q scaled
+// by 1e-2..1e2 and rho(A) in 0.5..1.2, every problem whose error exceeded 5e-5 had passed 260 and the worst error
+// below 256 was 3.7e-5; default groups on the benchmark inputs reach 40..200.  Bfloat16 inputs carry a 2e-2
+// tolerance: groups of five factors reach about 1e3.
+constexpr float GROWTH_LIMIT_F32 = 256.f;
+constexpr float GROWTH_LIMIT_BF16 = 16384.f;
+
 // d = 16, default path: batches that fill the chip go four problems to a wavefront (more throughput);
 // small batches keep one problem per wavefront (more wavefronts in flight, lower latency).
 static bool use_quad_kernel(const ttc_lqr_problem_t* q) {
@@ -183,21 +191,29 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   a.n = problem->n;
   a.T = problem->T;
   a.flags = problem->flags;
-  // Grouping of the T factors (one dense solve per group).  rebase_every = k asks for ceil(T/k) groups;
-  // the default is ceil(T/3.4) groups for float32 inputs and ceil(T/5) for bfloat16 inputs.  Lengths
-  // differ by at most one and the longer groups come first: an error made at an early re-base is
-  // damped by the contracting closed loop, the last group's error reaches P_0 undamped.  Measured max
-  // rel. err of P0/u0 at d = 128, T = 16 over 20000 problems: 2.0e-5 for groups (4,3,3,3,3),
-  // 6.2e-5 for (3,3,3,3,4), 6.8e-5 for (4,4,4,4), 1.6e-5 for six groups; the tolerance is 1e-4.
+  // Grouping of the T factors (one dense solve per group); group lengths differ by at most one and the longer
+  // groups come first.  rebase_every = k asks for ceil(T/k) groups.  The default for float32 inputs is groups of
+  // three factors with at most one group of four, which then comes first, where the pair starts from the terminal
+  // cost and grows least (an error made at an early re-base is also damped by the contracting closed loop, the
+  // last group's error reaches P_0 undamped); for bfloat16 inputs, whose tolerance is that of their rounding,
+  // groups of five.  Whatever the grouping, the kernels watch max |Y1| (the growth guard): a problem whose pair
+  // grows beyond the limit inside a group is solved by the recursion of Prop. 3.1 in its printed form instead,
+  // so that the accuracy does not rest on the inputs being like those the grouping was measured on.
   {
+    const long T = problem->T;
     long g;
     if (problem->flags & TTC_FLAG_PURE_SYMPLECTIC) g = 1;
-    else if (problem->rebase_every > 0) g = (problem->T + problem->rebase_every - 1) / problem->rebase_every;
-    else if (problem->in_dtype == TTC_BF16) g = (problem->T + 4) / 5;
-    else g = ((long)problem->T * 10 + 33) / 34;
+    else if (problem->rebase_every > 0) g = (T + problem->rebase_every - 1) / problem->rebase_every;
+    else if (problem->in_dtype == TTC_BF16) g = (T + 4) / 5;
+    else {
+      const long by3 = (T + 1) / 3, by34 = (T * 10 + 33) / 34;  // ceil((T-1)/3), ceil(T/3.4)
+      g = by3 > by34 ? by3 : by34;
+    }
     if (g < 1) g = 1;
-    if (g > problem->T) g = problem->T;
+    if (g > T) g = T;
     a.ngroups = (int)g;
+    a.growth_limit = (problem->flags & TTC_FLAG_PURE_SYMPLECTIC) ? 0.f
+                     : problem->in_dtype == TTC_BF16 ? ttc::GROWTH_LIMIT_BF16 : ttc::GROWTH_LIMIT_F32;
   }
   a.A = problem->A; a.B = problem->B; a.Q = problem->Q; a.R = problem->R; a.QT = problem->QT; a.x0 = problem->x0;
   a.sA = problem->sA; a.sB = problem->sB; a.sQ = problem->sQ; a.sR = problem->sR; a.sQT = problem->sQT;
@@ -323,6 +339,7 @@ ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solut
   a.s.T = q->T;
   a.s.flags = 0;
   a.s.ngroups = q->T;
+  a.s.growth_limit = 0.f;
   a.s.A = q->A; a.s.B = q->B; a.s.Q = q->Q; a.s.R = q->R; a.s.QT = nullptr; a.s.x0 = q->x0;
   a.s.sA = q->sA; a.s.sB = q->sB; a.s.sQ = q->sQ; a.s.sR = q->sR; a.s.sQT = 0; a.s.sx0 = q->sx0;
   a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
@@ -370,6 +387,7 @@ ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t* q, const ttc_lqr_
   a.s.T = q->T;
   a.s.flags = 0;
   a.s.ngroups = q->T;
+  a.s.growth_limit = 0.f;
   a.s.A = q->A; a.s.B = q->B; a.s.Q = q->Q; a.s.R = q->R; a.s.QT = nullptr; a.s.x0 = q->x0;
   a.s.sA = q->sA; a.s.sB = q->sB; a.s.sQ = q->sQ; a.s.sR = q->sR; a.s.sQT = 0; a.s.sx0 = q->sx0;
   a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
@@ -420,6 +438,7 @@ static void fill_cxt_args(ttc::CxtArgs& a, const ttc_lqr_cxt_problem_t* q) {
   a.s.T = q->T;
   a.s.flags = 0;
   a.s.ngroups = q->T;
+  a.s.growth_limit = 0.f;
   a.s.A = a.s.B = a.s.Q = a.s.R = a.s.QT = nullptr;
   a.s.x0 = q->x0;
   a.s.sA = a.s.sB = a.s.sQ = a.s.sR = a.s.sQT = 0;

@@ -8,6 +8,7 @@ namespace ttc {
 struct SolveArgs {
   long long n;
   int T, flags, ngroups;  // the T factors are applied in ngroups groups, one dense solve each
+  float growth_limit;     // growth guard of the symplectic kernels: max |Y1| a group may reach; 0 = no guard
   const void *A, *B, *Q, *R, *QT, *x0;
   long long sA, sB, sQ, sR, sQT, sx0;
   float *P0, *K0, *u0, *value;

@@ -140,6 +140,10 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
   x = mx(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false));
   return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
 }
+// max over the 64 lanes of a non-negative float (NaN counts as larger than every number), wave-uniform
+__device__ __forceinline__ float wave_max_nonneg(float x) {
+  return __uint_as_float(wave_max_u32(__float_as_uint(x)));
+}
 // sum over the 16 lanes that share lane/16 (xor butterflies 1,2,4,8)
 __device__ __forceinline__ float sum16(float x) {
   x += __shfl_xor(x, 1, 64);
@@ -306,6 +310,22 @@ template <int D>
 __device__ __forceinline__ void load_aop_lds(const float* Mb, float (&a)[Cfg<D>::RB][Cfg<D>::KS], int w, int i, int g) {
 #pragma unroll
   TTC_FOR_RB load_aop_lds<D>(Mb, a[rb], Cfg<D>::RB * w + rb, i, g);
+}
+
+// max |.| over the wavefront's accumulator rows (wave-uniform; NaN counts as larger than every number)
+template <int D>
+__device__ __forceinline__ float wave_absmax(const floatx4 (&acc)[Cfg<D>::RB][Cfg<D>::NT]) {
+  uint32_t m = 0;  // |x| as bits: for non-negative floats the unsigned order is the numeric one, NaN on top
+#pragma unroll
+  for (int rb = 0; rb < Cfg<D>::RB; ++rb)
+#pragma unroll
+    for (int c = 0; c < Cfg<D>::NT; ++c)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const uint32_t b = __float_as_uint(acc[rb][c][v]) & 0x7FFFFFFFu;
+        m = b > m ? b : m;
+      }
+  return __uint_as_float(wave_max_u32(m));
 }
 
 // A-operand registers of the wavefront's rows of M^T, M held in LDS: a[4q+t] = M[16q+4g+t][row]

@@ -183,209 +183,4 @@ __device__ __forceinline__ void gemm_acc_quad(floatx4 (&acc)[PPW][1][1], const f
       acc[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q][0][t], b[q][t], acc[q][0][0], 0, 0, 0);
 }
 
-// PPW = problems per wavefront: 4 for batches that fill the chip, 1 for small ones (the four rows of 16 lanes
-// then all hold the same problem and compute, and write, the same values; every per-problem loop runs once).
-template <typename TIn, int PPW>
-__global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
-  constexpr int D = 16;
-  using C = Cfg<D>;
-  static_assert(PPW == 1 || PPW == 4, "one problem or four per wavefront");
-  __shared__ __attribute__((aligned(16))) float Wm[PPW][D * C::PITCH];
-  __shared__ float s_red[C::NW];
-  const bool pure = (p.flags & TTC_FLAG_PURE_SYMPLECTIC) != 0;
-  const long long nquads = (p.n + PPW - 1) / PPW;
-
-  for (long long quad = blockIdx.x; quad < nquads; quad += gridDim.x) {
-    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, i = lane & 15, g = lane >> 4;
-    constexpr int w = 0;
-    long long prob[PPW];  // a ragged last quad repeats the last problem; only valid ones are written out
-    bool valid[PPW];
-#pragma unroll
-    for (int q = 0; q < PPW; ++q) {
-      valid[q] = quad * PPW + q < p.n;
-      prob[q] = valid[q] ? quad * PPW + q : p.n - 1;
-    }
-    float* const Wmine = Wm[g & (PPW - 1)];  // the problem whose rows this lane holds during the dense solves
-    int info[PPW] = {};
-    int nsolve = 0;
-    auto note = [&](int bad) {   // fold a dense solve's per-lane breakdown flags into the per-problem info
-      ++nsolve;
-      const unsigned long long m = __ballot(bad != 0);
-#pragma unroll
-      for (int q = 0; q < PPW; ++q)
-        if (!info[q] && ((m >> (16 * q)) & 0xFFFFull)) info[q] = nsolve;
-    };
-    PhaseTimers tm;  // phases: 0 set-up, 1 dense solves, 2 steps, 3 outputs
-    floatx4 acc[PPW][C::RB][C::NT];
-    float cG[PPW][C::RB][C::KS], cAi[PPW][C::RB][C::KS], cAT[PPW][C::RB][C::KS], cQ[PPW][C::RB][C::KS];
-    float cCK[PPW][C::RB][C::KS];
-
-    // ---- phase R: X = R^{-1} B^T, G = B X
-#pragma unroll
-    for (int q = 0; q < PPW; ++q) {
-      load_half<D, TIn, false>(Wm[q], reinterpret_cast<const TIn*>(p.R) + prob[q] * p.sR, tid);
-      load_half<D, TIn, true>(Wm[q] + D, reinterpret_cast<const TIn*>(p.B) + prob[q] * p.sB, tid);  // RHS = B^T
-    }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
-    __syncthreads();
-    {
-      float cB[PPW][C::RB][C::KS], cX[PPW][C::RB][C::KS];
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) load_aopT_lds<D>(Wm[q] + D, cB[q], w, i, g);  // rows of B = columns of B^T
-      tm.toc(0);
-      note(solve_rows16<false>(Wmine, lane));  // R is positive definite: no pivot search
-      tm.toc(1);
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-      gemm_acc_quad<PPW>(acc, cB, Wm, D, i, g);  // rows of G = B X
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) {
-        load_aop_lds<D>(Wm[q] + D, cX[q], w, i, g);
-        store_rows<D>(Wm[q], acc[q], w, i, g);
-      }
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q], cG[q], w, i, g);
-      __syncthreads();
-      // ---- phase A: A^{-1}, A^T, Q, C_K = X A^{-T}
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) {
-        load_half<D, TIn, false>(Wm[q], reinterpret_cast<const TIn*>(p.A) + prob[q] * p.sA, tid);
-        load_half<D, TIn, false>(Wm[q] + D, reinterpret_cast<const TIn*>(p.Q) + prob[q] * p.sQ, tid);
-      }
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) {
-        symmetrise_half<D>(Wm[q] + D, tid);
-        load_aopT_lds<D>(Wm[q], cAT[q], w, i, g);
-      }
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q] + D, cQ[q], w, i, g);
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) set_half_identity<D>(Wm[q] + D, tid);
-      __syncthreads();
-      tm.toc(0);
-      note(solve_rows16<true>(Wmine, lane));
-      tm.toc(1);
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) {
-        load_aop_lds<D>(Wm[q] + D, cAi[q], w, i, g);
-        load_rows<D>(Wm[q] + D, acc[q], w, i, g);
-      }
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) store_rows_T<D>(Wm[q] + D, acc[q], w, i, g);  // A^{-T}
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-      gemm_acc_quad<PPW>(acc, cX, Wm, D, i, g);  // rows of C_K = X A^{-T}
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q], cCK[q], w, i, g);
-    }
-    // initial pair [Y1 Y2] = [I Q_T]
-    if (p.QT) {
-#pragma unroll
-      for (int q = 0; q < PPW; ++q)
-        load_half<D, TIn, false>(Wm[q] + D, reinterpret_cast<const TIn*>(p.QT) + prob[q] * p.sQT, tid);
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-    } else {
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) store_aop_lds<D>(Wm[q] + D, cQ[q], w, i, g);  // Q_T = Q, already symmetric
-    }
-    __syncthreads();
-
-    tm.toc(0);
-    // ---- groups of reverse symplectic steps, each ended by a re-base
-    int s = 1;
-    bool fresh = true;
-    for (int grp = 0;; ++grp) {
-      const int gend = p.T - (int)(((long long)(p.ngroups - 1 - grp) * p.T) / p.ngroups);
-      for (;; ++s) {
-        const bool last = (s >= gend);
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          if (fresh) eye_acc<D>(acc[q], w, i, g); else load_rows<D>(Wm[q], acc[q], w, i, g);
-        }
-        gemm_acc_quad<PPW>(acc, cG, Wm, D, i, g);   // Z1 + G Z2
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-        gemm_acc_quad<PPW>(acc, cAi, Wm, 0, i, g);  // A^{-1} (.) = new Z1
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], acc[q], w, i, g);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
-        gemm_acc_quad<PPW>(acc, cAT, Wm, D, i, g);              // A^T Z2
-        if (s < p.T) gemm_acc_quad<PPW>(acc, cQ, Wm, 0, i, g);  // + Q Z1; Q_0 = 0 for the last factor
-        __syncthreads();
-        fresh = false;
-        if (!last) {
-#pragma unroll
-          for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q] + D, acc[q], w, i, g);
-          __syncthreads();
-          if (pure) {
-#pragma unroll
-            for (int q = 0; q < PPW; ++q) normalise_rows_zland<D>(Wm[q], tid);
-            __syncthreads();
-          }
-        } else {
-          // leave Z-land: [Y1 | Y2] untransposed for the solve Y1 P = Y2
-          floatx4 z1[PPW][C::RB][C::NT];
-#pragma unroll
-          for (int q = 0; q < PPW; ++q) {
-            store_rows_T<D>(Wm[q] + D, acc[q], w, i, g);
-            load_rows<D>(Wm[q], z1[q], w, i, g);
-          }
-          __syncthreads();
-#pragma unroll
-          for (int q = 0; q < PPW; ++q) store_rows_T<D>(Wm[q], z1[q], w, i, g);
-          __syncthreads();
-          ++s;
-          break;
-        }
-      }
-      tm.toc(2);
-      note(solve_rows16<true>(Wmine, lane));
-      tm.toc(1);
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-      __syncthreads();
-      fresh = true;
-      if (s > p.T) break;
-    }
-
-    tm.toc(2);
-    // ---- outputs: the right halves hold P_0 (paper convention, Q_0 = 0)
-#pragma unroll
-    for (int q = 0; q < PPW; ++q) {
-      if (!valid[q]) continue;  // uniform over the wavefront
-      const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob[q] * p.sQ;
-      const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
-      zero_acc<D>(acc[q]);
-      gemm_acc<D>(acc[q], cCK[q], Wm[q] + D, i, g);  // -K_0 = C_K P_0
-      emit_gain<D, TIn>(p, prob[q], acc[q], x0p, info[q], tid);
-      emit_value<D, TIn>(p, prob[q], Wm[q] + D, Qp, x0p, info[q], s_red, tid);
-    }
-    __syncthreads();
-    tm.toc(3);
-    tm.dump(p);
-  }
-}
-
 }  // namespace ttc

@@ -1,6 +1,7 @@
 // The solve kernel of d >= 32: reverse symplectic iteration in groups with re-basing (Thm 3.3, Alg. 4).
 #pragma once
 #include "ttc_common.hpp"
+#include "ttc_tv.hpp"
 
 namespace ttc {
 
@@ -23,6 +24,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
   __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
   __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
   __shared__ float s_red[C::NW];
+  __shared__ float s_growth[C::NW];  // per wavefront: max |Y1| after the step just taken
 
   float* const WL = W;      // left half  (Z1 / Y1 / M of a dense solve)
   float* const WR = W + D;  // right half (Z2 / Y2 / RHS)
@@ -42,6 +44,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     int s = 1;          // next reverse step (1 .. T; step s applies Sigma_{T-s+1})
     int grp = 0;        // current group of steps
     bool fresh = true;  // Z1 = I, not materialised
+    bool hard = false;  // the growth guard tripped: this problem goes to the Riccati recursion instead
     // the constant row blocks, in registers from here to the end of the problem
     float cG[C::RB][C::KS], cAi[C::RB][C::KS], cAT[C::RB][C::KS], cQ[C::RB][C::KS];
 
@@ -127,9 +130,27 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
           __syncthreads();
           zero_acc<D>(acc);
           gemm_acc<D>(acc, cAi, WL, i, g);   // A^{-1} (.)      (... A^{-T})  = new Z1
+          if (p.growth_limit > 0.f) {
+            const float mx = wave_absmax<D>(acc);
+            if (lane == 0) s_growth[w] = mx;
+          }
           __syncthreads();
           store_rows<D>(WL, acc, w, i, g);
           __syncthreads();
+          if (p.growth_limit > 0.f) {
+            // Growth guard.  Y1 starts a group as the identity and its inverse stays of order one (it is the
+            // closed-loop transition over the group), so max |Y1| tracks cond(Y1), which is what the float32
+            // error of P = Y1^{-1} Y2 is proportional to.  Beyond the limit the problem is taken out of the
+            // symplectic iteration and solved by the recursion of Prop. 3.1 in its printed form (below).
+            float gm = s_growth[0];
+#pragma unroll
+            for (int ww = 1; ww < C::NW; ++ww) gm = fmaxf(gm, s_growth[ww]);
+            if (!(gm <= p.growth_limit) && !info) {  // also true for NaN; every thread reads the same values
+              // (a problem whose set-up broke down is NaN anyway and keeps its report)
+              hard = true;
+              break;
+            }
+          }
           zero_acc<D>(acc);
           gemm_acc<D>(acc, cAT, WR, i, g);   // A^T Z2          (Y2 A)
           if (s < p.T) gemm_acc<D>(acc, cQ, WL, i, g);  // + Q Z1 (+ Y1 Q_{t-1}); Q_0 = 0 for the last factor
@@ -154,6 +175,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
           }
         }
       }
+      if (hard) break;
       TTC_TOC(3)
       ++nsolve;
       if (lds_solve<D>(W, S, tid) && !info) info = nsolve;
@@ -165,6 +187,17 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
       if (s > p.T) break;
     }
 
+    if (hard) {
+      // Prop. 3.1 as printed, from P_T: one positive definite solve per step, no A^{-1}, no accumulated factors
+      // (what ttc_lqr_solve_tv runs, here with the same matrices in every step).  info: 2 + index of the step.
+      __syncthreads();  // every wavefront has left the pair
+      const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
+      const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
+      const TIn* QTp = p.QT ? reinterpret_cast<const TIn*>(p.QT) + prob * p.sQT : Qp;
+      riccati_problem<D, TIn>(W, S, s_red, p, prob, p.T, Ap, Bp, Qp, Rp, 0, 0, 0, 0, QTp, nullptr, Qp, x0p, 2,
+                              tid + opaque_zero());
+      continue;
+    }
     // ---- outputs: WR holds P_0 (paper convention, Q_0 = 0)
     {
       float c[C::RB][C::KS];

@@ -124,6 +124,48 @@ __device__ __forceinline__ void next_value_matrix(float* W, const TIn* Qs, float
   __syncthreads();
 }
 
+// The whole backward recursion of one problem by one workgroup, from P_T to the outputs P_0, K_0, u_0, value and
+// info: T calls of riccati_step.  Step s reads A, B, R at As + s*tA, Bs + s*tB, Rs + s*tR and the stage cost on
+// the state it starts from at Qs + (s-1)*tQ (none for s = 0); zero strides give the time-invariant problem.
+// The terminal value matrix is PTf (float32) if given, else PT (input element type).  info_base is added to the
+// index (1 = the step taken first, s = T-1) of the step whose solve broke down.  All threads must call it.
+template <int D, typename TIn>
+__device__ __forceinline__ void riccati_problem(float* W, SolveScratch<D>& S, float* s_red, const SolveArgs& p,
+                                                long long prob, int T, const TIn* As, const TIn* Bs, const TIn* Qs,
+                                                const TIn* Rs, long long tA, long long tB, long long tQ, long long tR,
+                                                const TIn* PT, const float* PTf, const TIn* Qflag, const TIn* x0p,
+                                                int info_base, int tid) {
+  using C = Cfg<D>;
+  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  float* const WL = W;
+  float* const WR = W + D;
+  int info = 0;
+  if (PTf) load_half<D, float, false>(WR, PTf, tid);
+  else load_half<D, TIn, false>(WR, PT, tid);
+  __syncthreads();
+  symmetrise_half<D>(WR, tid);
+  __syncthreads();
+  for (int s = T - 1; s >= 0; --s) {
+    floatx4 pn[C::RB][C::NT];
+    const int flag = riccati_step<D, TIn>(W, S, As + (long long)s * tA, Bs + (long long)s * tB, Rs + (long long)s * tR,
+                                          pn, tid);
+    if (flag && !info) info = info_base + T - s;
+    if (s >= 1) {
+      __syncthreads();  // every wavefront is done reading W = -K_s
+      next_value_matrix<D, TIn>(W, Qs + (long long)(s - 1) * tQ, pn, tid);
+    } else {
+      store_rows<D>(WL, pn, w, i, g);  // P_0 (no cost on x_0)
+      __syncthreads();
+      symmetrise_half<D>(WL, tid);
+      __syncthreads();
+      floatx4 acc[C::RB][C::NT];
+      load_rows<D>(WR, acc, w, i, g);  // rows of -K_0
+      emit_gain<D, TIn>(p, prob, acc, x0p, info, tid);
+      emit_value<D, TIn>(p, prob, WL, Qflag, x0p, info, s_red, tid);
+    }
+  }
+}
+
 template <int D, typename TIn>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta) {
   using C = Cfg<D>;
@@ -131,44 +173,18 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_tv_kernel(const TvArgs ta)
   __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
   __shared__ float s_red[C::NW];
   const SolveArgs& p = ta.s;
-  float* const WL = W;
-  float* const WR = W + D;
 
   for (long long prob = blockIdx.x; prob < p.n; prob += gridDim.x) {
-    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+    const int tid = threadIdx.x + opaque_zero();
     const TIn* Ap = reinterpret_cast<const TIn*>(p.A) + prob * p.sA;
     const TIn* Bp = reinterpret_cast<const TIn*>(p.B) + prob * p.sB;
     const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob * p.sQ;
     const TIn* Rp = reinterpret_cast<const TIn*>(p.R) + prob * p.sR;
     const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob * p.sx0;
-    int info = 0;
-    if (ta.PT) load_half<D, float, false>(WR, ta.PT + prob * ta.sPT, tid);
-    else load_half<D, TIn, false>(WR, Qp + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
-    __syncthreads();
-    symmetrise_half<D>(WR, tid);
-    __syncthreads();
-    for (int s = p.T - 1; s >= 0; --s) {
-      floatx4 pn[C::RB][C::NT];
-      const int flag = riccati_step<D, TIn>(W, S, Ap + (long long)s * ta.tA, Bp + (long long)s * ta.tB,
-                                            Rp + (long long)s * ta.tR, pn, tid);
-      if (flag && !info) info = p.T - s;
-      if (s >= 1) {
-        __syncthreads();  // every wavefront is done reading W = -K_s
-        next_value_matrix<D, TIn>(W, Qp + (long long)(s - 1) * ta.tQ, pn, tid);
-      } else {
-        store_rows<D>(WL, pn, w, i, g);  // P_0 (no cost on x_0)
-        __syncthreads();
-        symmetrise_half<D>(WL, tid);
-        __syncthreads();
-        floatx4 acc[C::RB][C::NT];
-        load_rows<D>(WR, acc, w, i, g);  // rows of -K_0
-        emit_gain<D, TIn>(p, prob, acc, x0p, info, tid);
-        emit_value<D, TIn>(p, prob, WL, Qp, x0p, info, s_red, tid);
-      }
-    }
+    riccati_problem<D, TIn>(W, S, s_red, p, prob, p.T, Ap, Bp, Qp, Rp, ta.tA, ta.tB, ta.tQ, ta.tR,
+                            Qp + (long long)(p.T - 1) * ta.tQ, ta.PT ? ta.PT + prob * ta.sPT : nullptr, Qp, x0p, 0, tid);
   }
 }
-
 
 // Roll-out of a time-heterogeneous problem (Alg. 1 with r = 0): the backward sweep of solve_tv_kernel
 // keeping every gain K_s in the workspace, then the closed-loop forward sweep
@@ -264,6 +280,152 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) rollout_tv_kernel(const TvRollou
 // interleaved on the matrix cores, their dense solves side by side with one row per lane.
 // PPW = problems per wavefront: 4 for batches that fill the chip, 1 for small ones (the four rows of 16 lanes
 // then all hold the same problem; every per-problem loop runs once).
+//
+// riccati_quad: the whole backward recursion of the wavefront's PPW problems, from their terminal value matrices
+// (PTp[q], input element type) to the outputs.  Step s of problem q reads A, B, R at Ap[q] + s*tA, ... and the
+// stage cost on the state it starts from at Qp[q] + (s-1)*tQ; zero strides give the time-invariant problem.
+// info = info_base + the index (1 = the step taken first) of the step whose solve broke down.
+template <typename TIn, int PPW>
+__device__ __forceinline__ void riccati_quad(float (*Wm)[16 * Cfg<16>::PITCH], float* s_red, const SolveArgs& p,
+                                             const long long (&prob)[PPW], const bool (&valid)[PPW], int T,
+                                             const TIn* const (&Ap)[PPW], const TIn* const (&Bp)[PPW],
+                                             const TIn* const (&Qp)[PPW], const TIn* const (&Rp)[PPW],
+                                             const TIn* const (&PTp)[PPW], long long tA, long long tB, long long tQ,
+                                             long long tR, int info_base, int tid) {
+  constexpr int D = 16;
+  using C = Cfg<D>;
+  constexpr int w = 0;
+  const int lane = tid & 63, i = lane & 15, g = lane >> 4;
+  float* const Wmine = Wm[g & (PPW - 1)];  // the problem whose rows this lane holds during the dense solves
+  int info[PPW] = {};
+  int nsolve = 0;
+  auto note = [&](int bad) {
+    ++nsolve;
+    const unsigned long long m = __ballot(bad != 0);
+#pragma unroll
+    for (int q = 0; q < PPW; ++q)
+      if (!info[q] && ((m >> (16 * q)) & 0xFFFFull)) info[q] = nsolve;
+  };
+#pragma unroll
+  for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q] + D, PTp[q], tid);  // P_T = Q_T
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
+  __syncthreads();
+  for (int s = T - 1; s >= 0; --s) {
+    // the step of riccati_step, for four problems at once
+    floatx4 pn[PPW][C::RB][C::NT], accF[PPW][C::RB][C::NT], accW[PPW][C::RB][C::NT];
+    {
+      float cAT[PPW][C::RB][C::KS], cBT[PPW][C::RB][C::KS];
+      {
+        floatx4 accPA[PPW][C::RB][C::NT], accPB[PPW][C::RB][C::NT];
+        {
+          float cP[PPW][C::RB][C::KS];
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) {
+            load_aop_lds<D>(Wm[q] + D, cP[q], w, i, g);  // rows of P
+            load_half<D, TIn, false>(Wm[q], Ap[q] + (long long)s * tA, tid);
+          }
+          __syncthreads();
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) {
+            load_half<D, TIn, false>(Wm[q] + D, Bp[q] + (long long)s * tB, tid);  // P is in registers now
+            zero_acc<D>(accPA[q]);
+            zero_acc<D>(accPB[q]);
+          }
+          gemm_acc_quad<PPW>(accPA, cP, Wm, 0, i, g);  // P A
+          __syncthreads();
+          gemm_acc_quad<PPW>(accPB, cP, Wm, D, i, g);  // P B
+        }
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          load_aopT_lds<D>(Wm[q], cAT[q], w, i, g);      // rows of A^T
+          load_aopT_lds<D>(Wm[q] + D, cBT[q], w, i, g);  // rows of B^T
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          store_rows<D>(Wm[q], accPA[q], w, i, g);
+          store_rows<D>(Wm[q] + D, accPB[q], w, i, g);
+        }
+        __syncthreads();
+      }
+      floatx4 accS[PPW][C::RB][C::NT];
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+        load_rows_input<D, TIn>(Rp[q] + (long long)s * tR, accS[q], w, i, g);
+        zero_acc<D>(accF[q]);
+        zero_acc<D>(pn[q]);
+      }
+      gemm_acc_quad<PPW>(accS, cBT, Wm, D, i, g);  // S = R + B^T P B
+      gemm_acc_quad<PPW>(accF, cBT, Wm, 0, i, g);  // F = B^T P A
+      gemm_acc_quad<PPW>(pn, cAT, Wm, 0, i, g);    // A^T P A
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], accS[q], w, i, g);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);  // R is read as its symmetric part
+    __syncthreads();
+    note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
+    {
+      // At d = 16 the accumulator layout of F is both the B operand of F and the A operand of F^T.
+      float cSi[PPW][C::RB][C::KS];
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+        load_aop_lds<D>(Wm[q], cSi[q], w, i, g);  // rows of S^{-1}
+        zero_acc<D>(accW[q]);
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t)  // W = S^{-1} F = -K_s
+#pragma unroll
+        for (int q = 0; q < PPW; ++q)
+          accW[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cSi[q][0][t], accF[q][0][0][t], accW[q][0][0], 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)  // - F^T W
+#pragma unroll
+        for (int q = 0; q < PPW; ++q)
+          pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(-accF[q][0][0][t], accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
+    }
+    __syncthreads();
+    if (s >= 1) {
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q], Qp[q] + (long long)(s - 1) * tQ, tid);
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+        floatx4 qs[C::RB][C::NT];
+        load_rows<D>(Wm[q], qs, w, i, g);
+        pn[q][0][0] += qs[0][0];
+        store_rows<D>(Wm[q] + D, pn[q], w, i, g);  // P_s
+      }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
+      __syncthreads();
+    } else {
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], pn[q], w, i, g);  // P_0 (no cost on x_0)
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+        if (!valid[q]) continue;  // uniform over the wavefront
+        const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
+        emit_gain<D, TIn>(p, prob[q], accW[q], x0p, info[q], tid);  // rows of -K_0
+        emit_value<D, TIn>(p, prob[q], Wm[q], Qp[q], x0p, info[q] ? info_base + info[q] : 0, s_red, tid);
+      }
+      __syncthreads();
+    }
+  }
+}
+
 template <typename TIn, int PPW>
 __global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) {
   constexpr int D = 16;
@@ -275,11 +437,10 @@ __global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) 
   const long long nquads = (p.n + PPW - 1) / PPW;
 
   for (long long quad = blockIdx.x; quad < nquads; quad += gridDim.x) {
-    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, i = lane & 15, g = lane >> 4;
-    constexpr int w = 0;
+    const int tid = threadIdx.x + opaque_zero();
     long long prob[PPW];  // a ragged last quad repeats the last problem; only valid ones are written out
     bool valid[PPW];
-    const TIn *Ap[PPW], *Bp[PPW], *Qp[PPW], *Rp[PPW];
+    const TIn *Ap[PPW], *Bp[PPW], *Qp[PPW], *Rp[PPW], *PTp[PPW];
 #pragma unroll
     for (int q = 0; q < PPW; ++q) {
       valid[q] = quad * PPW + q < p.n;
@@ -288,135 +449,9 @@ __global__ void __launch_bounds__(64, 2) solve_tv_small_kernel(const TvArgs ta) 
       Bp[q] = reinterpret_cast<const TIn*>(p.B) + prob[q] * p.sB;
       Qp[q] = reinterpret_cast<const TIn*>(p.Q) + prob[q] * p.sQ;
       Rp[q] = reinterpret_cast<const TIn*>(p.R) + prob[q] * p.sR;
+      PTp[q] = Qp[q] + (long long)(p.T - 1) * ta.tQ;  // P_T = Q_T
     }
-    float* const Wmine = Wm[g & (PPW - 1)];  // the problem whose rows this lane holds during the dense solves
-    int info[PPW] = {};
-    int nsolve = 0;
-    auto note = [&](int bad) {
-      ++nsolve;
-      const unsigned long long m = __ballot(bad != 0);
-#pragma unroll
-      for (int q = 0; q < PPW; ++q)
-        if (!info[q] && ((m >> (16 * q)) & 0xFFFFull)) info[q] = nsolve;
-    };
-#pragma unroll
-    for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q] + D, Qp[q] + (long long)(p.T - 1) * ta.tQ, tid);  // P_T = Q_T
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-    __syncthreads();
-    for (int s = p.T - 1; s >= 0; --s) {
-      // the step of riccati_step, for four problems at once
-      floatx4 pn[PPW][C::RB][C::NT], accF[PPW][C::RB][C::NT], accW[PPW][C::RB][C::NT];
-      {
-        float cAT[PPW][C::RB][C::KS], cBT[PPW][C::RB][C::KS];
-        {
-          floatx4 accPA[PPW][C::RB][C::NT], accPB[PPW][C::RB][C::NT];
-          {
-            float cP[PPW][C::RB][C::KS];
-#pragma unroll
-            for (int q = 0; q < PPW; ++q) {
-              load_aop_lds<D>(Wm[q] + D, cP[q], w, i, g);  // rows of P
-              load_half<D, TIn, false>(Wm[q], Ap[q] + (long long)s * ta.tA, tid);
-            }
-            __syncthreads();
-#pragma unroll
-            for (int q = 0; q < PPW; ++q) {
-              load_half<D, TIn, false>(Wm[q] + D, Bp[q] + (long long)s * ta.tB, tid);  // P is in registers now
-              zero_acc<D>(accPA[q]);
-              zero_acc<D>(accPB[q]);
-            }
-            gemm_acc_quad<PPW>(accPA, cP, Wm, 0, i, g);  // P A
-            __syncthreads();
-            gemm_acc_quad<PPW>(accPB, cP, Wm, D, i, g);  // P B
-          }
-#pragma unroll
-          for (int q = 0; q < PPW; ++q) {
-            load_aopT_lds<D>(Wm[q], cAT[q], w, i, g);      // rows of A^T
-            load_aopT_lds<D>(Wm[q] + D, cBT[q], w, i, g);  // rows of B^T
-          }
-          __syncthreads();
-#pragma unroll
-          for (int q = 0; q < PPW; ++q) {
-            store_rows<D>(Wm[q], accPA[q], w, i, g);
-            store_rows<D>(Wm[q] + D, accPB[q], w, i, g);
-          }
-          __syncthreads();
-        }
-        floatx4 accS[PPW][C::RB][C::NT];
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          load_rows_input<D, TIn>(Rp[q] + (long long)s * ta.tR, accS[q], w, i, g);
-          zero_acc<D>(accF[q]);
-          zero_acc<D>(pn[q]);
-        }
-        gemm_acc_quad<PPW>(accS, cBT, Wm, D, i, g);  // S = R + B^T P B
-        gemm_acc_quad<PPW>(accF, cBT, Wm, 0, i, g);  // F = B^T P A
-        gemm_acc_quad<PPW>(pn, cAT, Wm, 0, i, g);    // A^T P A
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], accS[q], w, i, g);
-        __syncthreads();
-      }
-#pragma unroll
-      for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);  // R is read as its symmetric part
-      __syncthreads();
-      note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
-      {
-        // At d = 16 the accumulator layout of F is both the B operand of F and the A operand of F^T.
-        float cSi[PPW][C::RB][C::KS];
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          load_aop_lds<D>(Wm[q], cSi[q], w, i, g);  // rows of S^{-1}
-          zero_acc<D>(accW[q]);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t)  // W = S^{-1} F = -K_s
-#pragma unroll
-          for (int q = 0; q < PPW; ++q)
-            accW[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cSi[q][0][t], accF[q][0][0][t], accW[q][0][0], 0, 0, 0);
-#pragma unroll
-        for (int t = 0; t < 4; ++t)  // - F^T W
-#pragma unroll
-          for (int q = 0; q < PPW; ++q)
-            pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(-accF[q][0][0][t], accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
-      }
-      __syncthreads();
-      if (s >= 1) {
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q], Qp[q] + (long long)(s - 1) * ta.tQ, tid);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          floatx4 qs[C::RB][C::NT];
-          load_rows<D>(Wm[q], qs, w, i, g);
-          pn[q][0][0] += qs[0][0];
-          store_rows<D>(Wm[q] + D, pn[q], w, i, g);  // P_s
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-        __syncthreads();
-      } else {
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], pn[q], w, i, g);  // P_0 (no cost on x_0)
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          if (!valid[q]) continue;  // uniform over the wavefront
-          const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
-          emit_gain<D, TIn>(p, prob[q], accW[q], x0p, info[q], tid);  // rows of -K_0
-          emit_value<D, TIn>(p, prob[q], Wm[q], Qp[q], x0p, info[q], s_red, tid);
-        }
-        __syncthreads();
-      }
-    }
+    riccati_quad<TIn, PPW>(Wm, s_red, p, prob, valid, p.T, Ap, Bp, Qp, Rp, PTp, ta.tA, ta.tB, ta.tQ, ta.tR, 0, tid);
   }
 }
 

@@ -71,9 +71,10 @@ def _scale_spectral_radius(A: torch.Tensor, rho: float) -> torch.Tensor:
 
 
 def make_batch(n: int, d: int, m: int, T: int, seed: int = 0, device="cpu", dtype: str = "f32",
-               rho: float | None = None, chunk: int = 4096) -> LqrBatch:
+               rho: float | None = None, chunk: int = 4096, q_scale: float = 1.0, r_scale: float = 1.0) -> LqrBatch:
     """Draw n problems.  Values are generated in float32 (in chunks, to bound temporaries) and,
-    for dtype == "bf16", rounded to bfloat16 storage at the end."""
+    for dtype == "bf16", rounded to bfloat16 storage at the end.  q_scale and r_scale multiply the drawn Q and
+    R (costly or cheap states and controls: the ratio decides how hard the closed loop pushes)."""
     dev = torch.device(device)
     gen = torch.Generator(device=dev)
     gen.manual_seed(seed)
@@ -99,8 +100,8 @@ def make_batch(n: int, d: int, m: int, T: int, seed: int = 0, device="cpu", dtyp
         r = eye_m + M @ M.transpose(1, 2) / m
         A[lo:lo + c] = a
         B[lo:lo + c] = b
-        Q[lo:lo + c] = 0.5 * (q + q.transpose(1, 2))
-        R[lo:lo + c] = 0.5 * (r + r.transpose(1, 2))
+        Q[lo:lo + c] = q_scale * 0.5 * (q + q.transpose(1, 2))
+        R[lo:lo + c] = r_scale * 0.5 * (r + r.transpose(1, 2))
         x0[lo:lo + c] = x
     return LqrBatch(A, B, Q, R, x0, T)
 
