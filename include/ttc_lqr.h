@@ -13,6 +13,13 @@
  * Because cond(Y1) grows geometrically with the number of accumulated factors, the T factors are
  * applied in groups and the pair is re-based to [I P] after each group: rebase_every = k asks for
  * ceil(T/k) groups of nearly equal length (the paper's algorithm is one group, rebase_every >= T).
+ * A growth guard watches max |Y1| inside every group (Y1 starts a group as the identity): a group that
+ * is about to pass the limit is ended early, and a problem whose pair has passed it is solved instead
+ * by the recursion of Prop. 3.1 in its printed form (one positive definite solve per step, as
+ * ttc_lqr_solve_tv does), inside the same launch.  The accuracy therefore does not depend on the inputs
+ * resembling those the default grouping was measured on; what remains is float32 itself: with state
+ * costs some 1e4 times the control costs P0 is a small difference of large terms and every float32
+ * evaluation of the recursion loses digits in proportion.
  *
  * Conventions
  *   - All matrix arguments are DEVICE pointers to row-major, problem-major arrays: problem p of A
@@ -58,7 +65,8 @@ enum {
   TTC_FLAG_STAGE_COST_AT_X0 = 1,
   /* Never re-base inside the horizon: accumulate all T factors Sigma_T..Sigma_1 with row
    * normalisation after every step (App. C "Numerical Stability") and do the dense solve once,
-   * as Alg. 4 does.  For study: accuracy degrades quickly with T on dense problems. */
+   * as Alg. 4 does, without the growth guard.  For study: accuracy degrades quickly with T on dense
+   * problems. */
   TTC_FLAG_PURE_SYMPLECTIC = 2,
   /* Long-horizon path (ttc_lqr_solve only): the parameters are time-invariant (the paper's "Homo."
    * setting), so the T factors of Thm 3.3 are T copies of one matrix and their product (Sec. 3.3)
@@ -93,7 +101,9 @@ typedef struct {
   float *u0;     /* (n, m)    first optimal control u0 = K0 x0 (the layer's output o)               */
   float *value;  /* (n)       x0^T P0 x0 = 2x the optimal objective of Eq. "ttc"                    */
   int32_t *info; /* (n)       0 = ok; s > 0 = the s-th dense solve of that problem broke down
-                               (1: R^{-1}B^T, 2: A^{-1}, 3..: re-bases in order; the last yields P0)  */
+                               (1: R^{-1}B^T, 2: A^{-1}, 3..: re-bases in order; the last yields P0;
+                               for a problem the growth guard handed to the recursion of Prop. 3.1:
+                               2 + the index of the step, counted from the end of the horizon)      */
 } ttc_lqr_solution_t;
 
 /* Bytes of device workspace ttc_lqr_solve (for_rollout = 0) or ttc_lqr_rollout (for_rollout = 1)

@@ -135,10 +135,12 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
     int s = 1;
     bool fresh = true;
     bool hard = false;  // the growth guard tripped
+    int plan_base = 0, plan_T = p.T, plan_ng = p.ngroups;  // grouping of the steps after plan_base
     for (int grp = 0;; ++grp) {
-      const int gend = p.T - (int)(((long long)(p.ngroups - 1 - grp) * p.T) / p.ngroups);
-      for (;; ++s) {
-        const bool last = (s >= gend);
+      const int gend = plan_base + plan_T - (int)(((long long)(plan_ng - 1 - grp) * plan_T) / plan_ng);
+      float g_prev = 1.f;  // max |Y1| before the step: a group starts from Y1 = I
+      for (int k = 1;; ++s, ++k) {
+        bool last = (s >= gend);
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
           if (fresh) eye_acc<D>(acc[q], w, i, g); else load_rows<D>(Wm[q], acc[q], w, i, g);
@@ -151,8 +153,10 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
         for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
         gemm_acc_quad<PPW>(acc, cAi, Wm, 0, i, g);  // A^{-1} (.) = new Z1
         if (p.growth_limit > 0.f) {
-          // Growth guard (see solve_kernel): max |Y1| over the wavefront's problems; beyond the limit all of them
-          // leave the symplectic iteration for the recursion of Prop. 3.1 in its printed form (below).
+          // Growth guard (see solve_kernel): max |Y1| over the wavefront's problems.  A group about to pass the
+          // limit ends with this step and the rest of the horizon is re-planned with groups no longer than it;
+          // beyond the limit all the wavefront's problems leave the symplectic iteration for the recursion of
+          // Prop. 3.1 in its printed form (below).
           uint32_t m = 0;
 #pragma unroll
           for (int q = 0; q < PPW; ++q) {
@@ -168,6 +172,14 @@ __global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
             hard = true;
             break;
           }
+          if (!last && k >= 2 && s < p.T && gm * (gm / g_prev) > p.growth_limit) {
+            last = true;
+            plan_base = s;
+            plan_T = p.T - s;
+            plan_ng = (plan_T + k - 1) / k;
+            grp = -1;  // the next group is the first of the new plan
+          }
+          g_prev = gm;
         }
         __syncthreads();
 #pragma unroll

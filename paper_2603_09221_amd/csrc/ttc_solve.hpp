@@ -45,6 +45,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
     int grp = 0;        // current group of steps
     bool fresh = true;  // Z1 = I, not materialised
     bool hard = false;  // the growth guard tripped: this problem goes to the Riccati recursion instead
+    int plan_base = 0, plan_T = p.T, plan_ng = p.ngroups;  // grouping of the steps after plan_base
     // the constant row blocks, in registers from here to the end of the problem
     float cG[C::RB][C::KS], cAi[C::RB][C::KS], cAT[C::RB][C::KS], cQ[C::RB][C::KS];
 
@@ -120,10 +121,12 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
       {
         TTC_TOC(2)
         const int tg = tid + opaque_zero(), lane = tg & 63, w = tg >> 6, i = lane & 15, g = lane >> 4;
-        // last step of this group: lengths differ by at most one, the longer groups first
-        const int gend = p.T - (int)(((long long)(p.ngroups - 1 - grp) * p.T) / p.ngroups);
-        for (;; ++s) {
-          const bool last = (s >= gend);
+        // last step of this group: the plan_T steps from plan_base on are cut into plan_ng groups whose lengths
+        // differ by at most one, the longer groups first
+        const int gend = plan_base + plan_T - (int)(((long long)(plan_ng - 1 - grp) * plan_T) / plan_ng);
+        float g_prev = 1.f;  // max |Y1| before the step: the group starts from Y1 = I
+        for (int k = 1;; ++s, ++k) {
+          bool last = (s >= gend);
           if (fresh) eye_acc<D>(acc, w, i, g); else load_rows<D>(WL, acc, w, i, g);
           gemm_acc<D>(acc, cG, WR, i, g);    // Z1 + G Z2       (Y1 + Y2 G)
           store_rows<D>(WL, acc, w, i, g);
@@ -140,8 +143,10 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
           if (p.growth_limit > 0.f) {
             // Growth guard.  Y1 starts a group as the identity and its inverse stays of order one (it is the
             // closed-loop transition over the group), so max |Y1| tracks cond(Y1), which is what the float32
-            // error of P = Y1^{-1} Y2 is proportional to.  Beyond the limit the problem is taken out of the
-            // symplectic iteration and solved by the recursion of Prop. 3.1 in its printed form (below).
+            // error of P = Y1^{-1} Y2 is proportional to.  A group that is about to pass the limit (the last
+            // step's growth repeated) ends here, and the rest of the horizon is re-planned with groups no
+            // longer than this one; a pair that has passed it takes the problem out of the symplectic
+            // iteration, to the recursion of Prop. 3.1 in its printed form (below).
             float gm = s_growth[0];
 #pragma unroll
             for (int ww = 1; ww < C::NW; ++ww) gm = fmaxf(gm, s_growth[ww]);
@@ -150,6 +155,14 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) 
               hard = true;
               break;
             }
+            if (!last && k >= 2 && s < p.T && gm * (gm / g_prev) > p.growth_limit) {
+              last = true;
+              plan_base = s;
+              plan_T = p.T - s;
+              plan_ng = (plan_T + k - 1) / k;
+              grp = -1;  // the next group is the first of the new plan
+            }
+            g_prev = gm;
           }
           zero_acc<D>(acc);
           gemm_acc<D>(acc, cAT, WR, i, g);   // A^T Z2          (Y2 A)

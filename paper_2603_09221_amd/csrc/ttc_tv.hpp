@@ -368,20 +368,38 @@ __device__ __forceinline__ void riccati_quad(float (*Wm)[16 * Cfg<16>::PITCH], f
 #pragma unroll
     for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);  // R is read as its symmetric part
     __syncthreads();
+    float cS[PPW][C::RB][C::KS];
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q], cS[q], w, i, g);  // rows of S, for the refinement below
     note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
     {
       // At d = 16 the accumulator layout of F is both the B operand of F and the A operand of F^T.
       float cSi[PPW][C::RB][C::KS];
+      floatx4 res[PPW];
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
         load_aop_lds<D>(Wm[q], cSi[q], w, i, g);  // rows of S^{-1}
         zero_acc<D>(accW[q]);
+        res[q] = accF[q][0][0];
       }
 #pragma unroll
       for (int t = 0; t < 4; ++t)  // W = S^{-1} F = -K_s
 #pragma unroll
         for (int q = 0; q < PPW; ++q)
           accW[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cSi[q][0][t], accF[q][0][0][t], accW[q][0][0], 0, 0, 0);
+      // One step of refinement, W += S^{-1} (F - S W): an explicitly formed inverse leaves an error proportional
+      // to cond(S) in W, which the cancellation in A^T P A - F^T W magnifies when control is cheap; the corrected
+      // W is as good as a factor-and-solve.
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int q = 0; q < PPW; ++q)
+          res[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(-cS[q][0][t], accW[q][0][0][t], res[q], 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int q = 0; q < PPW; ++q)
+          accW[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cSi[q][0][t], res[q][t], accW[q][0][0], 0, 0, 0);
 #pragma unroll
       for (int t = 0; t < 4; ++t)  // - F^T W
 #pragma unroll
