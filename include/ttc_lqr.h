@@ -117,6 +117,20 @@ size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t *problem, int for_rollout
 ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t *problem, const ttc_lqr_solution_t *solution,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ttc_lqr_solve for callers that cannot allocate device memory or pass a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same inputs, outputs, conventions and
+ * error behaviour as ttc_lqr_solve; the kernels' workspace (the per-workgroup slots that ttc_lqr_solve takes
+ * from the caller) is a fixed array of ttc_lqr_noalloc_scratch_bytes() = 24 MiB inside the library's device
+ * image, one copy per GPU, held until the process ends.  The call allocates nothing and frees nothing, on the
+ * host or on the device.  A problem whose workspace (ttc_lqr_workspace_bytes(problem, 0)) exceeds the array
+ * returns TTC_ERR_WORKSPACE and launches nothing; TTC_FLAG_DOUBLING, whose six slots per workgroup never fit,
+ * returns TTC_ERR_UNSUPPORTED.  Every call on a GPU uses that GPU's one array: calls that overlap in time on the
+ * same GPU (two streams, two threads) race on it and must be serialised by the caller; consecutive calls on one
+ * stream are fine (nothing in the array needs to start at zero or to survive between calls). */
+ttc_status_t ttc_lqr_solve_noalloc(const ttc_lqr_problem_t *problem, const ttc_lqr_solution_t *solution,
+                                   void *hip_stream);
+size_t ttc_lqr_noalloc_scratch_bytes(void);
+
 /* Full optimal trajectory (Alg. 1, forward loop, r = 0): U (n, T, m) controls u_0..u_{T-1},
  * X (n, T+1, d) states x_0..x_T, cost (n) = sum_t u_t^T R u_t + sum_{t=1}^{T-1} x_t^T Q x_t +
  * x_T^T Q_T x_T (+ x_0^T Q x_0 with TTC_FLAG_STAGE_COST_AT_X0), which equals `value` of

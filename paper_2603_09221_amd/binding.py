@@ -20,7 +20,8 @@ TTC_FLAG_STAGE_COST_AT_X0 = 1
 TTC_FLAG_PURE_SYMPLECTIC = 2
 TTC_FLAG_DOUBLING = 4
 
-EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
+EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_solve_noalloc", "ttc_lqr_noalloc_scratch_bytes",
+           "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
            "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_lqr_rollout_cxt",
            "ttc_lqr_cxt_rollout_workspace_bytes", "ttc_lqr_solve_tv_scan",
            "ttc_lqr_tv_scan_workspace_bytes", "ttc_status_string", "ttc_version")
@@ -76,6 +77,10 @@ def load():
     lib.ttc_lqr_workspace_bytes.argtypes = [ctypes.POINTER(Problem), c_int]
     lib.ttc_lqr_solve.restype = c_int
     lib.ttc_lqr_solve.argtypes = [ctypes.POINTER(Problem), ctypes.POINTER(Solution), c_void_p, c_size_t, c_void_p]
+    lib.ttc_lqr_solve_noalloc.restype = c_int
+    lib.ttc_lqr_solve_noalloc.argtypes = [ctypes.POINTER(Problem), ctypes.POINTER(Solution), c_void_p]
+    lib.ttc_lqr_noalloc_scratch_bytes.restype = c_size_t
+    lib.ttc_lqr_noalloc_scratch_bytes.argtypes = []
     lib.ttc_lqr_rollout.restype = c_int
     lib.ttc_lqr_rollout.argtypes = [ctypes.POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                     c_size_t, c_void_p]
@@ -197,6 +202,17 @@ def ttc_lqr_solve(A, B, Q, R, QT, x0, T, *, flags=0, rebase_every=0, want_P0=Tru
         workspace = _scratch(need, dev, stream)
     _check(lib.ttc_lqr_solve(ctypes.byref(prob), ctypes.byref(sol), c_void_p(workspace.data_ptr()),
                              workspace.numel(), _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_solve_noalloc(A, B, Q, R, QT, x0, T, out, *, flags=0, rebase_every=0, stream=None):
+    """ttc_lqr_solve through the entry point that allocates nothing: `out` must carry preallocated u0 (n,m) and,
+    optionally, P0, K0, value, info; the library's own fixed scratch array serves as the workspace."""
+    lib = load()
+    prob = make_problem(A, B, Q, R, QT, x0, T, flags, rebase_every)
+    sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out.get("value")),
+                   _ptr(out.get("info")))
+    _check(lib.ttc_lqr_solve_noalloc(ctypes.byref(prob), ctypes.byref(sol), _stream_ptr(stream)))
     return out
 
 

@@ -8,6 +8,12 @@
 #include "../../include/ttc_lqr.h"
 #include "ttc_launch.hpp"
 
+// Scratch of ttc_lqr_solve_noalloc: a fixed array in device memory, one copy per GPU the library is loaded
+// on, held until the process ends.  Host code never uses the array's name as an address: it asks the runtime
+// for the device address once per device (scratch_for_current_device) and passes that pointer on.
+#define TTC_NOALLOC_SCRATCH_BYTES (24u << 20)
+static __device__ __align__(256) unsigned char scratch[TTC_NOALLOC_SCRATCH_BYTES];
+
 namespace ttc {
 
 // Per-device facts, asked once per device (thread-safe): the compute-unit count and, per kernel instance,
@@ -34,6 +40,22 @@ static int cu_count() {
     count[dev] = n;
   });
   return count[dev];
+}
+// Device address of this GPU's copy of the scratch array (nullptr if the runtime refuses): asked once per
+// device, with that device current, and kept.
+static void* scratch_for_current_device() {
+  static std::once_flag once[MAX_DEVICES];
+  static void* ptr[MAX_DEVICES];
+  const int dev = current_device();
+  std::call_once(once[dev], [dev] {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      q = nullptr;
+    }
+    ptr[dev] = q;
+  });
+  return ptr[dev];
 }
 // Persistent grids: as many workgroups as are resident at once, CUs x (workgroups per CU), so that no
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
@@ -249,6 +271,20 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   }
   return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
+
+ttc_status_t ttc_lqr_solve_noalloc(const ttc_lqr_problem_t* problem, const ttc_lqr_solution_t* solution,
+                                   void* hip_stream) {
+  const ttc_status_t st = ttc::validate(problem);
+  if (st != TTC_OK) return st;
+  if (problem->flags & TTC_FLAG_DOUBLING) return TTC_ERR_UNSUPPORTED;  // its six slots per workgroup do not fit
+  const size_t need = ttc_lqr_workspace_bytes(problem, 0);
+  if (need > (size_t)TTC_NOALLOC_SCRATCH_BYTES) return TTC_ERR_WORKSPACE;
+  void* const ws = ttc::scratch_for_current_device();
+  if (!ws) return TTC_ERR_DEVICE;
+  return ttc_lqr_solve(problem, solution, ws, (size_t)TTC_NOALLOC_SCRATCH_BYTES, hip_stream);
+}
+
+size_t ttc_lqr_noalloc_scratch_bytes(void) { return (size_t)TTC_NOALLOC_SCRATCH_BYTES; }
 
 ttc_status_t ttc_lqr_rollout(const ttc_lqr_problem_t* problem, float* U, float* X, float* cost,
                              int32_t* info, void* workspace, size_t workspace_bytes, void* hip_stream) {
