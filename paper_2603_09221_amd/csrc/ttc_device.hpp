@@ -368,34 +368,34 @@ __device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>
 //       panel, zero in column j, the later "Jordan" multipliers after it) and in S.L11 a copy of
 //       the unit-lower multipliers among the 16 pivot rows.
 //   (b) U12 = Lf^{-1} P for the 16 pivot rows P of the remaining columns, Lf the unit-lower factor among
-//       the pivot rows (S.L11): every wavefront inverts Lf once per panel (one lane per column, a
-//       forward substitution on the identity) and then forms U12 tile by tile on the matrix cores;
-//       negated, it stays in registers as an operand of (c).
+//       the pivot rows (S.L11): every wavefront inverts Lf once per panel and then forms U12 tile by tile
+//       on the matrix cores; negated, it stays in registers as an operand of (c).
 //   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows, in 16 x 16 tiles (a pivot row holds
 //       P_j = U12_j + sum_{k<j} L_jk U12_k, so the same update serves it); the product is
 //       formed transposed (MFMA M index = column, N index = row) so that a lane's four accumulator
 //       values, and its four operand values of either side, are 16 contiguous bytes of LDS.
-// Schedule: (b) and (c) are done column tile by column tile, so a wavefront needs no one else's
-// results.  Wavefront 0 takes the first column tile of the rest (= the next panel) and then factors
-// panel p+1, while the other wavefronts share the remaining column tiles of panel p: one workgroup
-// barrier per panel.
+// Schedule.  A single wavefront issues about one instruction every five cycles whatever its kind, and a
+// column of (a) is a chain of some 300 cycles (six DPP steps, broadcasts, a reciprocal), so (a) is the
+// critical path: the next panel's columns are updated first, by all wavefronts together (each its own
+// row tiles), then wavefront 0 factors panel p+1 while the others share the remaining column tiles of
+// panel p, each software-pipelined over its tiles: three workgroup barriers per panel.
 // Returns nonzero (uniformly) if a pivot was zero or not finite.  All threads must call it; W must be
 // visible on entry (caller synchronised); the result is visible to every thread on return.
 template <int D>
 struct SolveScratch {
-  float LinvT[Cfg<D>::NW][16 * 16];  // per wavefront: its copy of the inverse of the panel's unit-lower factor, by columns
-  float L11[2][16 * 16];            // double-buffered: panel p+1 is factored while p's is still read
+  float L11[2][16 * 16];  // double-buffered: panel p+1 is factored while p's is still read
   float inv[D];
   int piv[D];
   int flag;
 };
 
-// (a): Gauss-Jordan on the d x 16 panel starting at column cb, by one wavefront.  PIVOT = false takes
-// the diagonal element as the pivot of every column (for symmetric positive definite M, whose Schur
-// complements stay positive definite: no search, and a pivot that is not positive is a breakdown).
-template <int D, bool PIVOT = true>
+// (a) Gauss-Jordan on the d x 16 panel at column cb by one wavefront, rows in registers (a lane owns rows
+// lane and lane + 64).  Branch-free: the pivot row's values are picked by a select on the (uniform) half it
+// lies in and broadcast with v_readlane.  amask/atag: per row, 0x7FFFFF80 / (127 - row) while the row has not
+// been a pivot, 0 afterwards.
+template <int D, bool PIVOT>
 __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb, int lane,
-                                            bool (&active)[(D + 63) / 64], int& bad) {
+                                             uint32_t (&amask)[(D + 63) / 64], uint32_t (&atag)[(D + 63) / 64], int& bad) {
   using C = Cfg<D>;
   constexpr int NRL = (D + 63) / 64;
   float a[NRL][16];
@@ -403,7 +403,7 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
 #pragma unroll
   for (int rr = 0; rr < NRL; ++rr) {
     const int r = lane + 64 * rr;
-    myj[rr] = -1;
+    myj[rr] = 16;  // 16 = not a pivot row of this panel
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       floatx4 t = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -415,18 +415,12 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   float lane_pv = 1.f;  // lane j: its pivot value
   static_for<0, 16>([&](auto J) {
     constexpr int j = decltype(J)::value;
-    // every row's reciprocal is formed while the max is being reduced; the pivot row's one is used
-    float rinv[NRL];
-#pragma unroll
-    for (int rr = 0; rr < NRL; ++rr) rinv[rr] = __builtin_amdgcn_rcpf(a[rr][j]);
     int pr;
     if constexpr (PIVOT) {
-      // key = |value| with the low 7 mantissa bits replaced by (127 - row): one unsigned max = argmax
-      uint32_t key = 0;
-#pragma unroll
-      for (int rr = 0; rr < NRL; ++rr) {
-        const uint32_t k = (__float_as_uint(a[rr][j]) & 0x7FFFFF80u) | (uint32_t)(127 - (lane + 64 * rr));
-        key = (active[rr] && k > key) ? k : key;
+      uint32_t key = (__float_as_uint(a[0][j]) & amask[0]) | atag[0];
+      if constexpr (NRL > 1) {
+        const uint32_t k1 = (__float_as_uint(a[1][j]) & amask[1]) | atag[1];
+        key = k1 > key ? k1 : key;
       }
       key = wave_max_u32(key);
       pr = 127 - (int)(key & 0x7Fu);
@@ -437,32 +431,28 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
     const int pl = pr & 63;
     const bool ps = (NRL > 1) && (pr >= 64);
     float prow[16];
-    float inv;
-    if (ps) {
-      inv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rinv[NRL - 1]), pl));  // uniform branch: which of the lane's rows holds the pivot row
-      static_for<j, 16>([&](auto JJ) {
-        constexpr int jj = decltype(JJ)::value;
-        prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[NRL - 1][jj]), pl));
-      });
-    } else {
-      inv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rinv[0]), pl));
-      static_for<j, 16>([&](auto JJ) {
-        constexpr int jj = decltype(JJ)::value;
-        prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[0][jj]), pl));
-      });
-    }
+    static_for<j, 16>([&](auto JJ) {
+      constexpr int jj = decltype(JJ)::value;
+      float sel = a[0][jj];
+      if constexpr (NRL > 1) sel = ps ? a[NRL - 1][jj] : sel;
+      prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sel), pl));
+    });
+    const float inv = __builtin_amdgcn_rcpf(prow[j]);
     lane_piv = (lane == j) ? pr : lane_piv;
     lane_pv = (lane == j) ? prow[j] : lane_pv;
 #pragma unroll
     for (int rr = 0; rr < NRL; ++rr) {
-      const bool mine = (lane == pl) && ((rr == NRL - 1 && NRL > 1) == ps);
-      const float l = mine ? 0.f : a[rr][j] * inv;
-      active[rr] = active[rr] && !mine;
-      myj[rr] = mine ? j : myj[rr];
-      a[rr][j] = mine ? a[rr][j] : l;
+      // keep = all ones except in the lane and slot of the pivot row: plain bit masks instead of selects, so that
+      // the compiler has no reason to branch around the (rare) pivot-row case
+      const uint32_t keep = ((lane == pl) && ((rr == NRL - 1 && NRL > 1) == ps)) ? 0u : 0xFFFFFFFFu;
+      const float l = __uint_as_float(__float_as_uint(a[rr][j]) & keep) * inv;  // 0 for the pivot row itself
+      amask[rr] &= keep;
+      atag[rr] &= keep;
+      myj[rr] = (myj[rr] & (int)keep) | (j & (int)~keep);
+      a[rr][j] = l;
       static_for<j + 1, 16>([&](auto JJ) {
         constexpr int jj = decltype(JJ)::value;
-        a[rr][jj] -= l * prow[jj];  // l = 0 for the pivot row itself
+        a[rr][jj] = __builtin_fmaf(-l, prow[jj], a[rr][jj]);
       });
     }
   });
@@ -479,11 +469,10 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
     const int r = lane + 64 * rr;
     if (r < D) {
       const int j0 = myj[rr];
-      if (j0 >= 0) {
+      if (j0 < 16) {
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
-          if (jj < j0) L11[j0 * 16 + jj] = a[rr][jj];  // (kept in the row as well: see (c))
-          if (jj == j0) a[rr][jj] = 0.f;
+          if (jj < j0) L11[j0 * 16 + jj] = a[rr][jj];
         }
       }
 #pragma unroll
@@ -496,116 +485,331 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   }
 }
 
-// Inverse of the panel's unit-lower factor Lf (rows of multipliers in S.L11), as the matrix-core A
-// operand of U12 = Lf^{-1} P: the lane (i, g) gets Linv[i][4g .. 4g+3].  Lane c computes column c
-// (forward substitution on e_c); the columns pass through this wavefront's own LDS buffer to be read
-// back by rows.  Every wavefront does this for itself, once per panel.
+// Inverse of the panel's unit-lower factor Lf (rows of multipliers in S.L11) as the matrix-core A operand of
+// U12 = Lf^{-1} P: the lane (i, g) gets Linv[i][4g .. 4g+3].  Lane i of every row of 16 lanes holds row i of Lf
+// (its own registers, read from LDS without broadcasts) and builds row i of the inverse by forward substitution
+// over the pivots k: Linv[i][:] -= Lf[i][k] Linv[k][:], with row k of the inverse taken from lane k by a DPP row
+// broadcast (the four rows of lanes do the same work).
 template <int D>
 __device__ __forceinline__ floatx4 panel_linv(SolveScratch<D>& S, int cb, int lane, int w) {
+  (void)w;
   const float* L11 = S.L11[(cb >> 4) & 1];
-  float* buf = S.LinvT[w];
-  const int c = lane & 15, g = lane >> 4;
-  float x[16];
-  static_for<0, 16>([&](auto J) {
-    constexpr int j = decltype(J)::value;
-    float sacc = (j == c) ? 1.f : 0.f;
-    static_for<0, (j + 3) / 4>([&](auto Q) {
-      constexpr int q = decltype(Q)::value;
-      const floatx4 l = *reinterpret_cast<const floatx4*>(L11 + j * 16 + 4 * q);
-      static_for<0, 4>([&](auto E) {
-        constexpr int e = decltype(E)::value;
-        if constexpr (4 * q + e < j) sacc -= l[e] * x[4 * q + e];
-      });
-    });
-    x[j] = sacc;
-  });
-  if (g == 0) {
+  const int i = lane & 15, g = lane >> 4;
+  float l[16], x[16];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      floatx4 t;
-      t[0] = x[4 * q + 0]; t[1] = x[4 * q + 1]; t[2] = x[4 * q + 2]; t[3] = x[4 * q + 3];
-      *reinterpret_cast<floatx4*>(buf + c * 16 + 4 * q) = t;  // column c of Linv
-    }
+  for (int q = 0; q < 4; ++q) {
+    const floatx4 t = *reinterpret_cast<const floatx4*>(L11 + i * 16 + 4 * q);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) l[4 * q + e] = (4 * q + e < i) ? -t[e] : 0.f;  // strictly lower part only, negated
   }
+#pragma unroll
+  for (int c = 0; c < 16; ++c) x[c] = (c == i) ? 1.f : 0.f;
+  // x[c] += l[k] * (x[c] of lane k), c = 0..k, for k = 0..14: the broadcast rides on the multiply-add as its DPP
+  // operand.  One block per k, so that the wait states a DPP read needs after a vector write of the same
+  // register are in our hands: within a block every instruction touches its own register, and each block
+  // starts and ends with the two idle states.
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %1 row_newbcast:0 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0])
+      : "v"(l[0]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %2 row_newbcast:1 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %2 row_newbcast:1 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1])
+      : "v"(l[1]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %3 row_newbcast:2 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %3 row_newbcast:2 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %3 row_newbcast:2 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2])
+      : "v"(l[2]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %4 row_newbcast:3 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %4 row_newbcast:3 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %4 row_newbcast:3 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %4 row_newbcast:3 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])
+      : "v"(l[3]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %5 row_newbcast:4 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %5 row_newbcast:4 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %5 row_newbcast:4 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %5 row_newbcast:4 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %5 row_newbcast:4 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4])
+      : "v"(l[4]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %6 row_newbcast:5 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %6 row_newbcast:5 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %6 row_newbcast:5 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %6 row_newbcast:5 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %6 row_newbcast:5 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %6 row_newbcast:5 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5])
+      : "v"(l[5]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %7 row_newbcast:6 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %7 row_newbcast:6 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %7 row_newbcast:6 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %7 row_newbcast:6 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %7 row_newbcast:6 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %7 row_newbcast:6 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %7 row_newbcast:6 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6])
+      : "v"(l[6]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %8 row_newbcast:7 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+      : "v"(l[7]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %8, %8, %9 row_newbcast:8 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8])
+      : "v"(l[8]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %8, %8, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %9, %9, %10 row_newbcast:9 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8]), "+v"(x[9])
+      : "v"(l[9]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %8, %8, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %9, %9, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %10, %10, %11 row_newbcast:10 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8]), "+v"(x[9]), "+v"(x[10])
+      : "v"(l[10]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %8, %8, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %9, %9, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %10, %10, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %11, %11, %12 row_newbcast:11 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11])
+      : "v"(l[11]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %8, %8, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %9, %9, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %10, %10, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %11, %11, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %12, %12, %13 row_newbcast:12 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12])
+      : "v"(l[12]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %8, %8, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %9, %9, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %10, %10, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %11, %11, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %12, %12, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %13, %13, %14 row_newbcast:13 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13])
+      : "v"(l[13]));
+  asm volatile(
+      "s_nop 1\n\t"
+      "v_fmac_f32_dpp %0, %0, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %1, %1, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %2, %2, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %3, %3, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %4, %4, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %5, %5, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %6, %6, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %7, %7, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %8, %8, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %9, %9, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %10, %10, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %11, %11, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %12, %12, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %13, %13, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "v_fmac_f32_dpp %14, %14, %15 row_newbcast:14 row_mask:0xf bank_mask:0xf\n\t"
+      "s_nop 1"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14])
+      : "v"(l[14]));
   floatx4 la;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) la[t] = buf[(4 * g + t) * 16 + c];  // Linv[c][4g + t]
+  for (int t = 0; t < 4; ++t) {
+    const float a01 = (g & 1) ? x[4 + t] : x[t];
+    const float a23 = (g & 1) ? x[12 + t] : x[8 + t];
+    la[t] = (g & 2) ? a23 : a01;
+  }
   return la;
 }
 
-// (b) + (c) for the nt <= NTC consecutive column tiles ct0 .. ct0+nt-1 of the rest of panel cb (column
-// tile t covers columns [cb+16+16t, +16)), by one wavefront; la is panel_linv's operand.
-template <int D, int NTC, int PARTS = 7>
-__device__ __forceinline__ void solve_tiles(float* W, SolveScratch<D>& S, int cb, int lane, int ct0, int nt, floatx4 la) {
+// (b) + (c) for the column tiles [lo, hi) of the rest of panel cb (tile t = columns [cb+16+16t, +16)), all row
+// tiles, by one wavefront, software-pipelined: while the matrix cores update tile t, the rows of tile t+1 and
+// its pivot rows are read and tile t-1 has been written.
+template <int D>
+__device__ __forceinline__ void solve_update(float* W, SolveScratch<D>& S, int cb, int lane, int lo, int hi, floatx4 la) {
   using C = Cfg<D>;
+  if (lo >= hi) return;
   const int i = lane & 15, g = lane >> 4;
-  floatx4 av[NTC];
+  float* const rowp = W + i * C::PITCH + cb;  // row i of a row tile, at the panel's first column
+  floatx4 bl[C::NRT];                         // Lm[row i of the row tile][4g .. 4g+3]: the same for every column tile
 #pragma unroll
-  for (int u = 0; u < NTC; ++u) av[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-  // ---- (b): MFMA k-step t contracts the pivot indices { 4g + t }: lane (i, g) supplies Linv[i][4g+t] and
-  // P[4g+t][column i of the tile]; its four results are U12[4g .. 4g+3][column i].
-  if (PARTS & 2) {
-    int pv[4];
+  for (int rt = 0; rt < C::NRT; ++rt) bl[rt] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 4 * g);
+  int pv[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) pv[t] = S.piv[cb + 4 * g + t] * C::PITCH + cb + 16 + 16 * ct0 + i;
-    float pb[NTC][4];
+  for (int t = 0; t < 4; ++t) pv[t] = S.piv[cb + 4 * g + t] * C::PITCH + cb + 16 + i;
+  floatx4 acc[2][C::NRT];
+  float pb[2][4];
+  auto issue = [&](int buf, int ct) {
 #pragma unroll
-    for (int u = 0; u < NTC; ++u)
-      if (u < nt)
+    for (int t = 0; t < 4; ++t) pb[buf][t] = W[pv[t] + 16 * ct];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) pb[u][t] = W[pv[t] + 16 * u];
+    for (int rt = 0; rt < C::NRT; ++rt)
+      acc[buf][rt] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct + 4 * g);
+  };
+  auto u12 = [&](int buf) {
+    floatx4 av = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) av = __builtin_amdgcn_mfma_f32_16x16x4f32(la[t], pb[buf][t], av, 0, 0, 0);
+    return -av;
+  };
+  issue(0, lo);
+  floatx4 av = u12(0);
+  for (int ct = lo; ct < hi; ct += 2) {
+    // even step: tile ct in buffer 0, prefetch ct+1 into buffer 1
+    const bool more1 = ct + 1 < hi;
+    if (more1) issue(1, ct + 1);
+    TTC_SCHED_BARRIER();
 #pragma unroll
-      for (int u = 0; u < NTC; ++u)
-        if (u < nt) av[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(la[t], pb[u][t], av[u], 0, 0, 0);
+    for (int rt = 0; rt < C::NRT; ++rt)
 #pragma unroll
-    for (int u = 0; u < NTC; ++u) av[u] = -av[u];
+      for (int kk = 0; kk < 4; ++kk) acc[0][rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[kk], bl[rt][kk], acc[0][rt], 0, 0, 0);
+    floatx4 av1 = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (more1) av1 = u12(1);
+    TTC_SCHED_BARRIER();
+#pragma unroll
+    for (int rt = 0; rt < C::NRT; ++rt)
+      *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct + 4 * g) = acc[0][rt];
+    if (!more1) break;
+    const bool more2 = ct + 2 < hi;
+    if (more2) issue(0, ct + 2);
+    TTC_SCHED_BARRIER();
+#pragma unroll
+    for (int rt = 0; rt < C::NRT; ++rt)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) acc[1][rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av1[kk], bl[rt][kk], acc[1][rt], 0, 0, 0);
+    if (more2) av = u12(0);
+    TTC_SCHED_BARRIER();
+#pragma unroll
+    for (int rt = 0; rt < C::NRT; ++rt)
+      *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * (ct + 1) + 4 * g) = acc[1][rt];
   }
-  if (!(PARTS & 4)) return;
-  // ---- (c): MFMA k-step kk contracts the panel columns { 4g + kk }: lane (i, g) supplies, as A
-  // operand, -U12[4g+kk][column i of the tile] and, as B operand, Lm[row i of the row tile][4g+kk].
-  // All reads, then all matrix-core work, then all writes: the compiler cannot tell that the writes
-  // of one row tile do not feed the reads of the next, so a fused loop would serialise on LDS latency.
+}
+
+// The next panel's columns (column tile 0 of the rest of panel cb), which the next panel's factorisation waits
+// for, shared by all wavefronts: every wavefront forms the tile's U12 (b), then, after a barrier (the pivot rows
+// read by (b) are rows that (c) rewrites), updates its own RT0 row tiles (c).
+template <int D>
+__device__ __forceinline__ void solve_update_first(float* W, SolveScratch<D>& S, int cb, int lane, int w, floatx4 la) {
+  using C = Cfg<D>;
+  constexpr int RT0 = C::NRT / C::NW;  // row tiles per wavefront
+  const int i = lane & 15, g = lane >> 4;
   float* const rowp = W + i * C::PITCH + cb;
-  const int c0 = 16 + 16 * ct0 + 4 * g;
-  floatx4 bl[C::NRT], acc[C::NRT][NTC];
+  floatx4 bl[RT0], acc[RT0];
+  float pb[4];
 #pragma unroll
-  for (int rt = 0; rt < C::NRT; ++rt) {
-    bl[rt] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 4 * g);
+  for (int t = 0; t < 4; ++t) pb[t] = W[S.piv[cb + 4 * g + t] * C::PITCH + cb + 16 + i];
 #pragma unroll
-    for (int u = 0; u < NTC; ++u)
-      if (u < nt) acc[rt][u] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + c0 + 16 * u);
+  for (int r = 0; r < RT0; ++r) {
+    const int rt = RT0 * w + r;
+    bl[r] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 4 * g);
+    acc[r] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 4 * g);
   }
+  floatx4 av = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int rt = 0; rt < C::NRT; ++rt)
+  for (int t = 0; t < 4; ++t) av = __builtin_amdgcn_mfma_f32_16x16x4f32(la[t], pb[t], av, 0, 0, 0);
+  av = -av;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
+  for (int r = 0; r < RT0; ++r)
 #pragma unroll
-      for (int u = 0; u < NTC; ++u)
-        if (u < nt) acc[rt][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][kk], bl[rt][kk], acc[rt][u], 0, 0, 0);
+    for (int kk = 0; kk < 4; ++kk) acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[kk], bl[r][kk], acc[r], 0, 0, 0);
+  __syncthreads();  // every wavefront has read the tile's pivot rows
 #pragma unroll
-  for (int rt = 0; rt < C::NRT; ++rt)
-#pragma unroll
-    for (int u = 0; u < NTC; ++u)
-      if (u < nt) *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + c0 + 16 * u) = acc[rt][u];
+  for (int r = 0; r < RT0; ++r)
+    *reinterpret_cast<floatx4*>(rowp + 16 * (RT0 * w + r) * C::PITCH + 16 + 4 * g) = acc[r];
 }
 
-// the consecutive column tiles lo .. hi-1 of the rest of panel cb, at most NTC per call
-template <int D, int PARTS = 7>
-__device__ __forceinline__ void solve_tile_range(float* W, SolveScratch<D>& S, int cb, int lane, int lo, int hi,
-                                                 floatx4 la) {
-  constexpr int NTC = TTC_SOLVE_NTC;
-  for (int t0 = lo; t0 < hi; t0 += NTC) {
-    const int nt = hi - t0 < NTC ? hi - t0 : NTC;
-    if (nt == 1) solve_tiles<D, 1, PARTS>(W, S, cb, lane, t0, 1, la);
-    else if (nt <= 2) solve_tiles<D, 2, PARTS>(W, S, cb, lane, t0, nt, la);
-    else if (nt <= 4 || NTC <= 4) solve_tiles<D, (NTC < 4 ? NTC : 4), PARTS>(W, S, cb, lane, t0, nt, la);
-    else solve_tiles<D, NTC, PARTS>(W, S, cb, lane, t0, nt, la);
-  }
-}
-
-// PARTS is a development switch (bit 0: panels, bit 1: U12, bit 2: trailing updates); 7 = everything.
+// PARTS is kept for the callers' template argument lists (always 7).
 template <int D, int PARTS = 7, bool PIVOT = true>
 __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) {
   using C = Cfg<D>;
@@ -613,49 +817,66 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
   constexpr int NRL = (D + 63) / 64;
   tid += opaque_zero();
   const int lane = tid & 63, w = tid >> 6;
-  bool active[NRL];
+  uint32_t amask[NRL], atag[NRL];
 #pragma unroll
-  for (int rr = 0; rr < NRL; ++rr) active[rr] = (lane + 64 * rr) < D;
+  for (int rr = 0; rr < NRL; ++rr) {
+    const bool act = (lane + 64 * rr) < D;
+    amask[rr] = act ? 0x7FFFFF80u : 0u;
+    atag[rr] = act ? (uint32_t)(127 - (lane + 64 * rr)) : 0u;
+  }
   int bad = 0;
-
-  if ((PARTS & 1) && w == 0) solve_panel<D, PIVOT>(W, S, 0, lane, active, bad);
+  if (w == 0) solve_panel<D, PIVOT>(W, S, 0, lane, amask, atag, bad);
   for (int p = 0; p < NP; ++p) {
     __syncthreads();  // panel p is in place; every update of panel p-1 is done
     const int cb = 16 * p;
     const int nct = (2 * D - cb - 16) / 16;  // column tiles to the right of the panel
     const bool more = (p + 1 < NP);
-    floatx4 la = floatx4{0.f, 0.f, 0.f, 0.f};
-    if (PARTS & 2) la = panel_linv<D>(S, cb, lane, w);
-    if (more && w == 0) {
-      if (PARTS & 6) {
-        solve_tile_range<D, PARTS>(W, S, cb, lane, 0, 1, la);                     // the next panel's columns
-        if (C::NW == 1) solve_tile_range<D, PARTS>(W, S, cb, lane, 1, nct, la);   // nobody else to do the rest
+    const floatx4 la = panel_linv<D>(S, cb, lane, w);
+    if (more && C::NW > 1) {
+      solve_update_first<D>(W, S, cb, lane, w, la);
+      __syncthreads();  // the next panel's columns are up to date
+      if (w == 0) {
+        solve_panel<D, PIVOT>(W, S, cb + 16, lane, amask, atag, bad);
+      } else {
+        const int ntile = nct - 1;  // a contiguous share of the other column tiles each
+        solve_update<D>(W, S, cb, lane, 1 + ((w - 1) * ntile) / (C::NW - 1), 1 + (w * ntile) / (C::NW - 1), la);
       }
-      if (PARTS & 1) solve_panel<D, PIVOT>(W, S, cb + 16, lane, active, bad);
-    } else if (PARTS & 6) {
-      const int workers = more ? C::NW - 1 : C::NW;
-      const int wi = more ? w - 1 : w;
-      const int first = more ? 1 : 0, ntile = nct - first;   // a contiguous share of the column tiles each
-      solve_tile_range<D, PARTS>(W, S, cb, lane, first + (wi * ntile) / workers, first + ((wi + 1) * ntile) / workers, la);
+    } else if (more) {  // one wavefront: everything in turn
+      solve_update<D>(W, S, cb, lane, 0, nct, la);
+      solve_panel<D, PIVOT>(W, S, cb + 16, lane, amask, atag, bad);
+    } else {
+      solve_update<D>(W, S, cb, lane, (w * nct) / C::NW, ((w + 1) * nct) / C::NW, la);
     }
   }
   if (tid == 0) S.flag = bad;
   __syncthreads();
-  // gather + scale into the (now dead) left half, then copy back to the right half
-  for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
-    const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
-    const floatx4 x = *reinterpret_cast<const floatx4*>(W + S.piv[c] * C::PITCH + D + j4);
-    *reinterpret_cast<floatx4*>(W + c * C::PITCH + j4) = x * S.inv[c];
-  }
-  __syncthreads();
-  for (int idx = tid; idx < D * D / 4; idx += C::NTHR) {
-    const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
-    *reinterpret_cast<floatx4*>(W + c * C::PITCH + D + j4) = *reinterpret_cast<const floatx4*>(W + c * C::PITCH + j4);
+  // gather: row c of the solution is the right half of row piv[c], scaled by 1/pivot; through registers
+  {
+    constexpr int NV = (D * D / 4 + C::NTHR - 1) / C::NTHR;
+    floatx4 xv[NV];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int idx = tid + k * C::NTHR;
+      if (idx < D * D / 4) {
+        const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
+        xv[k] = *reinterpret_cast<const floatx4*>(W + S.piv[c] * C::PITCH + D + j4) * S.inv[c];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int idx = tid + k * C::NTHR;
+      if (idx < D * D / 4) {
+        const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
+        *reinterpret_cast<floatx4*>(W + c * C::PITCH + D + j4) = xv[k];
+      }
+    }
   }
   const int flag = S.flag;
   __syncthreads();
   return flag;
 }
+
 
 // Row normalisation of [Y1 Y2] (App. C "Numerical Stability") in Z-land: column c of Z is row c of
 // the pair.  The scale is the power of two just below max(||Y1_c||_1, ||Y2_c||_1), so the scaling
