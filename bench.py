@@ -33,8 +33,9 @@ MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (38.64e6 + 27.51e6) * 
                                       ("ttc_layer_d16", 8): (645.6e3 + 2.747e6) * 1024 / 1048576,
                                       ("tiny", 3): (1.0657e6 + 0.5448e6) * 1024 / 262144}
 def default_groups(T, dtype):
-    """The library default: number of groups the T factors are split into (one dense solve each)."""
-    return (T + 4) // 5 if dtype == "bf16" else (T * 10 + 33) // 34
+    """The library default: number of groups the T factors are split into (one dense solve each): groups of five
+    factors for bfloat16 inputs; for float32 inputs groups of three with at most one group of four."""
+    return (T + 4) // 5 if dtype == "bf16" else max((T + 1) // 3, (T * 10 + 33) // 34)
 
 
 def alg_flops(d, T, groups):

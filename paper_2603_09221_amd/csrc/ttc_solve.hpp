@@ -3,6 +3,9 @@
 #include "ttc_common.hpp"
 #include "ttc_tv.hpp"
 
+#ifndef TTC_D64_WAVES
+#define TTC_D64_WAVES 2  // d = 64: two wavefronts per SIMD (four workgroups per compute unit): one problem's dense solve overlaps another's products
+#endif
 namespace ttc {
 
 // Solve kernel.  Persistent workgroups: workgroup b handles problems b, b + gridDim.x, ...
@@ -19,7 +22,7 @@ namespace ttc {
 // stay there to the end of the problem; only C_K, needed once at the very end, waits in the workspace.
 // Global reads are started a phase ahead of their use where registers allow.
 template <int D, typename TIn>
-__global__ void __launch_bounds__(Cfg<D>::NTHR) solve_kernel(const SolveArgs p) {
+__global__ void __launch_bounds__(Cfg<D>::NTHR, (D == 64 ? TTC_D64_WAVES : 1)) solve_kernel(const SolveArgs p) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
   __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
