@@ -243,6 +243,41 @@ size_t ttc_lqr_cxt_rollout_workspace_bytes(const ttc_lqr_cxt_problem_t *problem)
 ttc_status_t ttc_lqr_rollout_cxt(const ttc_lqr_cxt_problem_t *problem, float *U, float *X, float *cost,
                                  int32_t *info, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Backward pass of the layer (Thm 3.2; appendix: Thm A.6, Alg. 5): gradients of a loss l of the layer's output
+ * u0 = u_1^* with respect to the parameters and the initial state, given grad_u0 = dl/du0 (n, m), float32.
+ * With (x, u, lam) the states, controls and co-states of the problem itself (the "primal LQR") and (xt, ut, lamt)
+ * those of the "dual LQR" (the same dynamics and quadratic costs from the initial state 0, plus the linear cost
+ * grad_u0^T ut_0 on the first control), step s = 0..T-1 being the paper's t = s+1:
+ *     dl/dA[s] = lam_{s+1} xt_s^T + lamt_{s+1} x_s^T          dl/dB[s] = lam_{s+1} ut_s^T + lamt_{s+1} u_s^T
+ *     dl/dQ[s] = (xt_{s+1} x_{s+1}^T + x_{s+1} xt_{s+1}^T)/2    dl/dR[s] = (ut_s u_s^T + u_s ut_s^T)/2
+ *     dl/dx0   = lamt_0
+ * (Q and R are read as their symmetric parts; their gradients are the symmetric ones of Thm 3.2).  The call is
+ * self-contained: it repeats the backward recursion of Prop. 3.1 (keeping the gains of the problems in flight in
+ * the workspace), rolls both closed loops forward (Alg. 1) and the co-states backward (Alg. 2), instead of running
+ * the forward symplectic recursion of Alg. 5 from cached factors, which loses all accuracy in float32 on dense
+ * problems.  All gradient pointers are DEVICE pointers, float32, caller-owned, 16-byte aligned, required (info may
+ * be NULL).  info and NaN gradients as for ttc_lqr_solve_tv (info = T - s for the step whose solve broke down). */
+typedef struct {
+  float *gA, *gB, *gQ, *gR; /* ttc_lqr_backward_tv: (n, T, d, d) per step; ttc_lqr_backward: (n, d, d), summed over steps */
+  float *gQT;               /* ttc_lqr_backward only: (n, d, d) gradient of the terminal cost; required exactly when
+                               the problem gives QT (then gQ sums the steps before the last); NULL otherwise        */
+  float *gx0;               /* (n, d)                                                                              */
+  int32_t *info;            /* (n) or NULL                                                                         */
+} ttc_lqr_grads_t;
+
+/* Time-invariant parameters (ttc_lqr_problem_t, flags must be 0): every matrix serves in all T steps and collects
+ * the sum of the steps' gradients.  Workspace: ttc_lqr_backward_workspace_bytes(problem) bytes, DEVICE, 16-byte
+ * aligned (per resident workgroup (T-1) d^2 + 6 (T+1) d floats; independent of n). */
+size_t ttc_lqr_backward_workspace_bytes(const ttc_lqr_problem_t *problem);
+ttc_status_t ttc_lqr_backward(const ttc_lqr_problem_t *problem, const float *grad_u0, const ttc_lqr_grads_t *grads,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Time-heterogeneous parameters (ttc_lqr_tv_problem_t): one gradient per step and matrix. */
+size_t ttc_lqr_backward_tv_workspace_bytes(const ttc_lqr_tv_problem_t *problem);
+ttc_status_t ttc_lqr_backward_tv(const ttc_lqr_tv_problem_t *problem, const float *grad_u0,
+                                 const ttc_lqr_grads_t *grads, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *ttc_status_string(ttc_status_t status);
 

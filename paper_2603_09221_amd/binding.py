@@ -24,7 +24,8 @@ EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_solve_noalloc", 
            "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
            "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_lqr_rollout_cxt",
            "ttc_lqr_cxt_rollout_workspace_bytes", "ttc_lqr_solve_tv_scan",
-           "ttc_lqr_tv_scan_workspace_bytes", "ttc_status_string", "ttc_version")
+           "ttc_lqr_tv_scan_workspace_bytes", "ttc_lqr_backward", "ttc_lqr_backward_workspace_bytes",
+           "ttc_lqr_backward_tv", "ttc_lqr_backward_tv_workspace_bytes", "ttc_status_string", "ttc_version")
 
 
 class Problem(ctypes.Structure):
@@ -54,6 +55,11 @@ class CxtProblem(ctypes.Structure):
 
 class Solution(ctypes.Structure):
     _fields_ = [("P0", c_void_p), ("K0", c_void_p), ("u0", c_void_p), ("value", c_void_p), ("info", c_void_p)]
+
+
+class Grads(ctypes.Structure):
+    _fields_ = [("gA", c_void_p), ("gB", c_void_p), ("gQ", c_void_p), ("gR", c_void_p), ("gQT", c_void_p),
+                ("gx0", c_void_p), ("info", c_void_p)]
 
 
 class TtcError(RuntimeError):
@@ -103,6 +109,16 @@ def load():
     lib.ttc_lqr_rollout_cxt.restype = c_int
     lib.ttc_lqr_rollout_cxt.argtypes = [ctypes.POINTER(CxtProblem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_size_t, c_void_p]
+    lib.ttc_lqr_backward_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_backward_workspace_bytes.argtypes = [ctypes.POINTER(Problem)]
+    lib.ttc_lqr_backward.restype = c_int
+    lib.ttc_lqr_backward.argtypes = [ctypes.POINTER(Problem), c_void_p, ctypes.POINTER(Grads), c_void_p, c_size_t,
+                                     c_void_p]
+    lib.ttc_lqr_backward_tv_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_backward_tv_workspace_bytes.argtypes = [ctypes.POINTER(TvProblem)]
+    lib.ttc_lqr_backward_tv.restype = c_int
+    lib.ttc_lqr_backward_tv.argtypes = [ctypes.POINTER(TvProblem), c_void_p, ctypes.POINTER(Grads), c_void_p, c_size_t,
+                                        c_void_p]
     lib.ttc_status_string.restype = c_char_p
     lib.ttc_status_string.argtypes = [c_int]
     lib.ttc_version.restype = c_int
@@ -376,4 +392,50 @@ def ttc_lqr_rollout_cxt(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0
     _check(lib.ttc_lqr_rollout_cxt(ctypes.byref(prob), _ptr(out["U"]), _ptr(out["X"]), _ptr(out["cost"]),
                                    _ptr(out["info"]), c_void_p(workspace.data_ptr()), workspace.numel(),
                                    _stream_ptr(stream)))
+    return out
+
+
+def _grads_struct(out):
+    return Grads(_ptr(out["gA"]), _ptr(out["gB"]), _ptr(out["gQ"]), _ptr(out["gR"]), _ptr(out.get("gQT")),
+                 _ptr(out["gx0"]), _ptr(out.get("info")))
+
+
+def ttc_lqr_backward(A, B, Q, R, QT, x0, T, grad_u0, *, out=None, workspace=None, stream=None):
+    """Gradients of a loss of u0 for n time-invariant problems, from grad_u0 = dl/du0 (n,m) float32: gA, gB, gQ, gR
+    (n,d,d), summed over the steps, gQT (n,d,d) when QT is given, gx0 (n,d), info (n)."""
+    lib = load()
+    prob = make_problem(A, B, Q, R, QT, x0, T)
+    n, d, dev = prob.n, prob.d, A.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = dict(out or {})
+    for k in ("gA", "gB", "gQ", "gR") + (("gQT",) if QT is not None else ()):
+        out.setdefault(k, torch.empty((n, d, d), **f32))
+    out.setdefault("gx0", torch.empty((n, d), **f32))
+    out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
+    need = lib.ttc_lqr_backward_workspace_bytes(ctypes.byref(prob))
+    if workspace is None:
+        workspace = _scratch(need, dev, stream)
+    gr = _grads_struct(out)
+    _check(lib.ttc_lqr_backward(ctypes.byref(prob), c_void_p(grad_u0.data_ptr()), ctypes.byref(gr),
+                                c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_backward_tv(A, B, Q, R, x0, grad_u0, *, out=None, workspace=None, stream=None):
+    """Gradients of a loss of u0 for n time-heterogeneous problems: gA, gB, gQ, gR (n,T,d,d), gx0 (n,d), info (n)."""
+    lib = load()
+    prob = make_tv_problem(A, B, Q, R, x0)
+    n, d, T, dev = prob.n, prob.d, prob.T, A.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = dict(out or {})
+    for k in ("gA", "gB", "gQ", "gR"):
+        out.setdefault(k, torch.empty((n, T, d, d), **f32))
+    out.setdefault("gx0", torch.empty((n, d), **f32))
+    out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
+    need = lib.ttc_lqr_backward_tv_workspace_bytes(ctypes.byref(prob))
+    if workspace is None:
+        workspace = _scratch(need, dev, stream)
+    gr = _grads_struct(out)
+    _check(lib.ttc_lqr_backward_tv(ctypes.byref(prob), c_void_p(grad_u0.data_ptr()), ctypes.byref(gr),
+                                   c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
     return out

@@ -30,6 +30,7 @@ UNITS = [("ttc_api.hip", None),
          ("k_rollout.hip", (16, 32, 64, 128)),
          ("k_tv.hip", (16, 32, 64, 128)),
          ("k_scan.hip", (16, 32, 64, 128)),
+         ("k_backward.hip", (16, 32, 64, 128)),
          ("k_small.hip", None),
          ("k_tv_small.hip", None),
          ("k_cxt.hip", None)]

@@ -61,7 +61,7 @@ static void* scratch_for_current_device() {
 // workgroup waits for another to finish.  The per-CU number is what the runtime reports for the kernel
 // (registers and LDS decide it); the table is the fallback when no device can be asked.
 enum Kind { KIND_SOLVE = 0, KIND_DOUBLING = 1, KIND_ROLLOUT = 2, KIND_SOLVE_QUAD = 3, KIND_SOLVE_TV = 4, KIND_TV_QUAD = 5,
-            KIND_ROLLOUT_TV = 6, KIND_CXT = 7, KIND_SCAN = 8, KIND_COUNT = 9 };
+            KIND_ROLLOUT_TV = 6, KIND_CXT = 7, KIND_SCAN = 8, KIND_BACKWARD = 9, KIND_COUNT = 10 };
 static int dindex(int d) { return d == 16 ? 0 : d == 32 ? 1 : d == 64 ? 2 : 3; }
 template <int D>
 static int occupancy_of(Kind kind, bool bf16) {
@@ -74,6 +74,7 @@ static int occupancy_of(Kind kind, bool bf16) {
     case KIND_SOLVE_TV: return occupancy_tv<D>(bf16);
     case KIND_ROLLOUT_TV: return occupancy_rollout_tv<D>(bf16);
     case KIND_SCAN: return occupancy_scan<D>();
+    case KIND_BACKWARD: return occupancy_backward<D>(bf16);
     case KIND_SOLVE_QUAD: return occupancy_small(bf16);  // the d = 16 kernels
     case KIND_TV_QUAD: return occupancy_tv_small(bf16);
     case KIND_CXT: return occupancy_cxt(bf16);
@@ -97,7 +98,8 @@ static int blocks_per_cu(Kind kind, int d, bool bf16) {
     }
     if (nb <= 0) {
       static const int table[KIND_COUNT][4] = {{20, 8, 2, 1}, {16, 8, 2, 1}, {12, 4, 2, 1}, {8, 8, 2, 1}, {20, 8, 2, 1},
-                                               {8, 8, 2, 1},  {12, 4, 2, 1}, {8, 8, 2, 1},  {16, 8, 2, 1}};
+                                               {8, 8, 2, 1},  {12, 4, 2, 1}, {8, 8, 2, 1},  {16, 8, 2, 1},
+                                               {12, 4, 2, 1}};
       nb = table[kind][dindex(d)];
     }
     c.value = nb > 32 ? 32 : nb;
@@ -179,6 +181,9 @@ static hipError_t run_scan_leaf(const ScanArgs& a, int d, bool bf16, dim3 grid, 
 }
 static hipError_t run_scan_combine(const ScanArgs& a, int d, dim3 grid, hipStream_t st) {
   TTC_BY_D(d, launch_scan_combine<D>(a, grid, st))
+}
+static hipError_t run_backward(const BackwardArgs& a, int d, bool bf16, dim3 grid, hipStream_t st) {
+  TTC_BY_D(d, launch_backward<D>(a, bf16, grid, st))
 }
 #undef TTC_BY_D
 
@@ -539,6 +544,87 @@ ttc_status_t ttc_lqr_rollout_cxt(const ttc_lqr_cxt_problem_t* q, float* U, float
   const long long gb = 32LL * ttc::cu_count();
   const dim3 grid((unsigned)(groups < gb ? groups : gb));
   return ttc::launch_rollout_cxt_forward(ra, bf16, grid, st) == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+}
+
+// ---- backward pass -------------------------------------------------------------------------------------------
+static size_t backward_ws_bytes(int d, int T, bool bf16) {
+  const size_t slots = (size_t)ttc::grid_blocks(ttc::KIND_BACKWARD, d, bf16);
+  return slots * ((size_t)(T - 1) * d * d + 6 * (size_t)(T + 1) * d) * sizeof(float);
+}
+
+size_t ttc_lqr_backward_workspace_bytes(const ttc_lqr_problem_t* q) {
+  if (!q || q->T < 1 || !ttc::shape_supported(q)) return 0;
+  return backward_ws_bytes(q->d, q->T, q->in_dtype == TTC_BF16);
+}
+
+size_t ttc_lqr_backward_tv_workspace_bytes(const ttc_lqr_tv_problem_t* q) {
+  if (!q || q->T < 1 || !ttc::shape_supported_dm(q->d, q->m)) return 0;
+  return backward_ws_bytes(q->d, q->T, q->in_dtype == TTC_BF16);
+}
+
+static ttc_status_t check_grads(const float* grad_u0, const ttc_lqr_grads_t* gr) {
+  if (!grad_u0 || !gr || !gr->gA || !gr->gB || !gr->gQ || !gr->gR || !gr->gx0) return TTC_ERR_INVALID_ARG;
+  const void* ptrs[] = {gr->gA, gr->gB, gr->gQ, gr->gR, gr->gQT};
+  for (const void* ptr : ptrs)
+    if (!ttc::aligned_ptr(ptr, 16)) return TTC_ERR_INVALID_ARG;
+  return TTC_OK;
+}
+
+ttc_status_t ttc_lqr_backward(const ttc_lqr_problem_t* q, const float* grad_u0, const ttc_lqr_grads_t* gr,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t st = ttc::validate(q);
+  if (st != TTC_OK) return st;
+  if (q->flags != 0) return TTC_ERR_INVALID_ARG;
+  if (q->n == 0) return TTC_OK;
+  const ttc_status_t sg = check_grads(grad_u0, gr);
+  if (sg != TTC_OK) return sg;
+  if ((q->QT != nullptr) != (gr->gQT != nullptr)) return TTC_ERR_INVALID_ARG;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_backward_workspace_bytes(q))
+    return TTC_ERR_WORKSPACE;
+  ttc::BackwardArgs a;
+  a.r.n = q->n; a.r.T = q->T; a.r.flags = 0;
+  a.r.A = q->A; a.r.B = q->B; a.r.Q = q->Q; a.r.R = q->R; a.r.QT = q->QT; a.r.x0 = q->x0;
+  a.r.sA = q->sA; a.r.sB = q->sB; a.r.sQ = q->sQ; a.r.sR = q->sR; a.r.sQT = q->sQT; a.r.sx0 = q->sx0;
+  a.r.U = a.r.X = a.r.cost = nullptr;
+  a.r.info = gr->info;
+  a.r.ws = static_cast<float*>(workspace);
+  a.tA = a.tB = a.tQ = a.tR = 0;
+  a.g = grad_u0; a.sg = q->m;
+  a.gA = gr->gA; a.gB = gr->gB; a.gQ = gr->gQ; a.gR = gr->gR; a.gQT = gr->gQT; a.gx0 = gr->gx0;
+  a.sum_steps = 1;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const long long gb = ttc::grid_blocks(ttc::KIND_BACKWARD, q->d, bf16);
+  const dim3 grid((unsigned)(q->n < gb ? q->n : gb));
+  return ttc::run_backward(a, q->d, bf16, grid, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TTC_OK
+                                                                                                     : TTC_ERR_DEVICE;
+}
+
+ttc_status_t ttc_lqr_backward_tv(const ttc_lqr_tv_problem_t* q, const float* grad_u0, const ttc_lqr_grads_t* gr,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t st = validate_tv(q);
+  if (st != TTC_OK) return st;
+  if (q->n == 0) return TTC_OK;
+  const ttc_status_t sg = check_grads(grad_u0, gr);
+  if (sg != TTC_OK) return sg;
+  if (gr->gQT) return TTC_ERR_INVALID_ARG;  // the terminal cost is Q of the last step here
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_backward_tv_workspace_bytes(q))
+    return TTC_ERR_WORKSPACE;
+  ttc::BackwardArgs a;
+  a.r.n = q->n; a.r.T = q->T; a.r.flags = 0;
+  a.r.A = q->A; a.r.B = q->B; a.r.Q = q->Q; a.r.R = q->R; a.r.QT = nullptr; a.r.x0 = q->x0;
+  a.r.sA = q->sA; a.r.sB = q->sB; a.r.sQ = q->sQ; a.r.sR = q->sR; a.r.sQT = 0; a.r.sx0 = q->sx0;
+  a.r.U = a.r.X = a.r.cost = nullptr;
+  a.r.info = gr->info;
+  a.r.ws = static_cast<float*>(workspace);
+  a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
+  a.g = grad_u0; a.sg = q->m;
+  a.gA = gr->gA; a.gB = gr->gB; a.gQ = gr->gQ; a.gR = gr->gR; a.gQT = nullptr; a.gx0 = gr->gx0;
+  a.sum_steps = 0;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const long long gb = ttc::grid_blocks(ttc::KIND_BACKWARD, q->d, bf16);
+  const dim3 grid((unsigned)(q->n < gb ? q->n : gb));
+  return ttc::run_backward(a, q->d, bf16, grid, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TTC_OK
+                                                                                                     : TTC_ERR_DEVICE;
 }
 
 const char* ttc_status_string(ttc_status_t status) {

@@ -56,6 +56,17 @@ struct ScanArgs {
   int stride;  // combine rounds: the stride st
 };
 
+struct BackwardArgs {
+  RolloutArgs r;              // n, T, A, B, Q, R, QT (time-invariant problems only), x0, strides, info, ws; U, X, cost unused
+  long long tA, tB, tQ, tR;   // elements between consecutive steps (0: the same matrix in every step)
+  const float* g;             // (n, m) dl/du_0
+  long long sg;
+  float *gA, *gB, *gQ, *gR;   // (n, T, d, d), or (n, d, d) when sum_steps
+  float* gQT;                 // (n, d, d) or NULL: the terminal cost's gradient when it is its own matrix (sum_steps)
+  float* gx0;                 // (n, d)
+  int sum_steps;              // 1: time-invariant parameters, gradients summed over the steps
+};
+
 constexpr int CXT_RMAX = 64;  // most basis matrices per group
 
 struct CxtArgs {

@@ -24,6 +24,9 @@ template <int D> hipError_t launch_scan_leaf(const ScanArgs& a, bool bf16, dim3 
 template <int D> hipError_t launch_scan_combine(const ScanArgs& a, dim3 grid, hipStream_t st);
 template <int D> int occupancy_scan();
 
+template <int D> hipError_t launch_backward(const BackwardArgs& a, bool bf16, dim3 grid, hipStream_t st);
+template <int D> int occupancy_backward(bool bf16);
+
 // d = 16 only; ppw = problems per wavefront (1 or 4)
 hipError_t launch_small(const SolveArgs& a, bool bf16, int ppw, dim3 grid, hipStream_t st);
 int occupancy_small(bool bf16);
