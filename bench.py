@@ -24,14 +24,55 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak (256 CUs x 256 flop/clk x 2.4 GHz)
-# HBM-side bytes per problem of solve_kernel<128, float> at the llm_adapter workload with the default
-# grouping, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy kernel
-# (profiles/*_d128_T16_llm_adapter_n65536.md): (read + written) KiB / 65536 problems.
-MEASURED_TRAFFIC_BYTES_PER_PROBLEM = {("llm_adapter", 5): (38.64e6 + 27.51e6) * 1024 / 65536,
-                                      ("llm_adapter", "doubling"): (112.3e6 + 76.1e6) * 1024 / 65536,
-                                      ("llm_adapter", "tv"): (82.69e6 + 3.090e6) * 1024 / 16384,
-                                      ("ttc_layer_d16", 8): (645.6e3 + 2.747e6) * 1024 / 1048576,
-                                      ("tiny", 3): (1.0657e6 + 0.5448e6) * 1024 / 262144}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def source_hash():
+    """Identifies the build of the kernels: a hash over the HIP sources (what a measured traffic figure belongs to)."""
+    import hashlib
+    h = hashlib.sha256()
+    folder = os.path.join(ROOT, "paper_2603_09221_amd", "csrc")
+    for name in sorted(os.listdir(folder)):
+        with open(os.path.join(folder, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, path, n):
+    """HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE summaries recorded in profiles/traffic.json
+    (bytes per problem x n), or None when no row matches this workload and path or the row was measured on
+    another build of the kernels."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rows = json.load(f)["rows"]
+    except (OSError, ValueError, KeyError):
+        return None
+    cur = source_hash()
+    for r in rows:
+        if r.get("workload") == workload and r.get("path") == path and r.get("source_hash") == cur:
+            return r["bytes_per_problem"] * n
+    return None
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def spread(kernel_ms):
+    """Median and 20 / 80 % percentiles of the per-launch durations (the paper reports its timings this way)."""
+    import numpy as np
+    a = np.asarray(kernel_ms, dtype=np.float64)
+    return {"kernel_ms_median": float(np.median(a)), "kernel_ms_p20": float(np.percentile(a, 20)),
+            "kernel_ms_p80": float(np.percentile(a, 80))}
+
+
 def default_groups(T, dtype):
     """The library default: number of groups the T factors are split into (one dense solve each): groups of five
     factors for bfloat16 inputs; for float32 inputs groups of three with at most one group of four."""
@@ -75,6 +116,14 @@ def alg_flops_tv(d, T):
     printed Riccati step (P A, P B, B^T P A, B^T P B, A^T P A, F^T W: 2 d^3 each) and the solve with the positive
     definite S (factor d^3/3, d right-hand sides 2 d^3)."""
     return T * (12 + 7.0 / 3) * d ** 3
+
+
+def alg_flops_bwd(d, T):
+    """Algorithmic flops of one backward pass (ttc_lqr_backward): T-1 steps of the backward recursion of Prop. 3.1
+    (six products and a positive definite solve with d right-hand sides, as alg_flops_tv), the first step's
+    S_0 = R + B^T P_1 B (two products) and its solve with two right-hand sides (factor d^3/3); the closed loops, the
+    co-states and the outer products are O(T d^2) and not counted."""
+    return ((T - 1) * (12 + 7.0 / 3) + 4 + 1.0 / 3) * d ** 3
 
 
 def alg_flops_cxt(d, r, T):
@@ -124,13 +173,13 @@ def bench_cxt(args):
         e1.record(stream)
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / args.steps
-    kernel_s = sum(e0.elapsed_time(e1) for e0, e1 in evs) / len(evs) / 1e3
+    kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+    kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
     assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
     flops_pp = alg_flops_cxt(d, r, T)
     achieved = flops_pp * n / kernel_s / 1e12
     in_bytes = n * (6 * d + 3 * r) * 4 + 2 * r * d * d * 4
     out_bytes = n * (2 * d * d + d + 2) * 4
-    key = ("ttc_layer_d16", T)
     res = {
         "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d, structured parameters" % (d, T),
         "value": n / wall, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -140,9 +189,9 @@ def bench_cxt(args):
                    "path": "cxt", "outputs": "P0,K0,u0,value"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[key] * n
-                                 if key in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
-                     "kernel": "solve_cxt_kernel", "kernel_ms": kernel_s * 1e3, "alg_flops_per_problem": flops_pp,
+                     "traffic": measured_traffic("ttc_layer_d16_T%d" % T, "cxt", n),
+                     "kernel": "solve_cxt_kernel", "kernel_ms": kernel_s * 1e3, **spread(kernel_ms),
+                     "alg_flops_per_problem": flops_pp,
                      "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / kernel_s / 1e12,
                      "alg_bytes_per_launch": in_bytes + out_bytes,
                      "alg_GBps": (in_bytes + out_bytes) / kernel_s / 1e9},
@@ -169,6 +218,7 @@ def bench_cxt(args):
         ref, dt = run(sample)
         errs = {k: float(rel_err(out[k][:sample].cpu().numpy(), ref[k]).max()) for k in ("P0", "K0", "u0", "value")}
         res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": cores, "kind": "oracle",
+                               "cpu_model": cpu_model(),
                                "sample": "first %d problems of the same workload, float64 numpy (parameters "
                                          "expanded to dense steps, then Riccati), %.1f s wall" % (sample, dt)}
         res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": 1e-4}
@@ -249,6 +299,7 @@ def bench_scan(args):
         dt = time.perf_counter() - t1
         errs = {k: float(rel_err(out[k].cpu().numpy(), ref[k]).max()) for k in ("P0", "K0", "u0", "value")}
         res["cpu_baseline"] = {"value": n / dt, "unit": "problems/s", "cores": 1, "kind": "oracle",
+                               "cpu_model": cpu_model(),
                                "sample": "all %d problems, float64 numpy Riccati, batched over problems in one "
                                          "thread, %.2f s wall" % (n, dt)}
         res["parity"] = {"sample": n, "max_rel_err": errs, "tolerance": 1e-4}
@@ -296,14 +347,18 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="llm_adapter")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan"),
+    ap.add_argument("--chunk", type=int, default=None, help="problems per launch (default: the whole workload, or "
+                    "the largest power-of-two split whose outputs fit the card)")
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
                          "doubling: the long-horizon path, the same product formed by squaring; "
                          "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
                          "every step with its own A, B, Q, R (default 16384 problems); "
                          "cxt: structured, contextualised parameters (ttc_lqr_solve_cxt) at d = 16, r = 16, "
                          "1048576 problems, --config ignored; "
-                         "scan: ttc_lqr_solve_tv_scan at d = 16, 16 problems, horizon 2048, --config ignored")
+                         "scan: ttc_lqr_solve_tv_scan at d = 16, 16 problems, horizon 2048, --config ignored; "
+                         "bwd: the backward pass (ttc_lqr_backward) on the configuration's shape (default up to "
+                         "131072 problems)")
     ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt (default 8) and scan (default 2048) paths")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
@@ -330,8 +385,9 @@ def main():
     from paper_2603_09221_amd.errors import rel_err
 
     cfg = synth.CONFIGS[args.config]
-    n = args.n or (min(16384, synth.config_problems(args.config)) if args.path == "tv"
-                   else synth.config_problems(args.config))
+    path = args.path
+    full = synth.config_problems(args.config)
+    n = args.n or (min(16384, full) if path == "tv" else min(131072, full) if path == "bwd" else full)
     d, m, T = cfg["d"], cfg["m"], cfg["T"]
     k = args.rebase_every
     groups = math.ceil(T / k) if k else default_groups(T, cfg["dtype"])
@@ -339,47 +395,84 @@ def main():
     torch.cuda.set_device(dev)
     binding.load()
 
-    if args.path == "tv":
+    if path == "tv":
         batch = synth.make_tv_batch(n, d, m, T, seed=0, device=dev, dtype=cfg["dtype"])
         args.no_extra = True
     else:
         batch = synth.make_batch(n, d, m, T, seed=0, device=dev, dtype=cfg["dtype"], rho=cfg["rho"])
-    out = {
-        "P0": torch.empty((n, d, d), dtype=torch.float32, device=dev),
-        "K0": torch.empty((n, m, d), dtype=torch.float32, device=dev),
-        "u0": torch.empty((n, m), dtype=torch.float32, device=dev),
-        "value": torch.empty((n,), dtype=torch.float32, device=dev),
-        "info": torch.empty((n,), dtype=torch.int32, device=dev),
-    }
+    if path == "bwd":
+        args.no_extra = True
+    esize = batch.A.element_size()
+    # Outputs are held for one chunk of problems at a time (inputs for the whole workload stay resident): a step
+    # launches the chunks one after the other on the same stream.  One chunk unless inputs plus outputs of the
+    # whole workload would not fit the card.
+    out_pp = (4 * d * d + d + 1) * 4 if path == "bwd" else (d * d + m * d + m + 2) * 4
+    free_bytes = torch.cuda.mem_get_info(dev)[0]
+    chunk = n
+    while chunk > 1 and chunk * out_pp > 0.85 * free_bytes:
+        chunk = (chunk + 1) // 2
+    if args.chunk:
+        chunk = min(n, args.chunk)
+    nchunks = (n + chunk - 1) // chunk
+    f32 = dict(dtype=torch.float32, device=dev)
+    if path == "bwd":
+        out = {kk: torch.empty((chunk, d, d), **f32) for kk in ("gA", "gB", "gQ", "gR")}
+        out["gx0"] = torch.empty((chunk, d), **f32)
+        out["info"] = torch.empty((chunk,), dtype=torch.int32, device=dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1)
+        grad_u0 = torch.randn((n, m), generator=gen, **f32)
+    else:
+        out = {"P0": torch.empty((chunk, d, d), **f32), "K0": torch.empty((chunk, m, d), **f32),
+               "u0": torch.empty((chunk, m), **f32), "value": torch.empty((chunk,), **f32),
+               "info": torch.empty((chunk,), dtype=torch.int32, device=dev)}
     dbl = binding.TTC_FLAG_DOUBLING
-    main_flags = dbl if args.path == "doubling" else 0
-    ws_bytes = 16 if args.path == "tv" else max(binding.ttc_lqr_workspace_bytes(
-        binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, f, k)) for f in (0, dbl))
+    main_flags = dbl if path == "doubling" else 0
+    if path == "tv":
+        ws_bytes = 16
+    elif path == "bwd":
+        ws_bytes = binding.load().ttc_lqr_backward_workspace_bytes(
+            binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T))
+    else:
+        ws_bytes = max(binding.ttc_lqr_workspace_bytes(
+            binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, f, k)) for f in (0, dbl))
     ws = torch.empty((max(ws_bytes, 16),), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
+    def view(t, lo, hi):
+        return {kk: v[:hi - lo] for kk, v in t.items()}
+
+    def launch(flags, lo, hi):
+        sub = batch.take(slice(lo, hi))
+        o = view(out, lo, hi)
+        if path == "tv":
+            binding.ttc_lqr_solve_tv(sub.A, sub.B, sub.Q, sub.R, sub.x0, out=o, stream=stream)
+        elif path == "bwd":
+            binding.ttc_lqr_backward(sub.A, sub.B, sub.Q, sub.R, None, sub.x0, T, grad_u0[lo:hi], out=o, workspace=ws,
+                                     stream=stream)
+        else:
+            binding.ttc_lqr_solve(sub.A, sub.B, sub.Q, sub.R, None, sub.x0, T, flags=flags, rebase_every=k, out=o,
+                                  workspace=ws, stream=stream)
+
     def timed(flags, steps, warmup):
-        """warmup untimed + steps timed launches of the whole workload; (wall s per step, kernel s per launch)"""
+        """warmup untimed + steps timed passes over the whole workload; (wall s per step, kernel ms per step)"""
         def step():
-            if args.path == "tv":
-                binding.ttc_lqr_solve_tv(batch.A, batch.B, batch.Q, batch.R, batch.x0, out=out, stream=stream)
-            else:
-                binding.ttc_lqr_solve(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T, flags=flags,
-                                      rebase_every=k, out=out, workspace=ws, stream=stream)
+            for c in range(nchunks):
+                launch(flags, c * chunk, min(n, (c + 1) * chunk))
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         t0 = time.perf_counter()
         for e0, e1 in evs:
-            e0.record(stream)      # HIP events on the stream the kernel is launched on
+            e0.record(stream)      # HIP events on the stream the kernels are launched on
             step()
             e1.record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]   # one kernel launch per step
+        kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]   # nchunks kernel launches per step, back to back
         assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
-        return wall / steps, sum(kernel_ms) / len(kernel_ms) / 1e3
+        return wall / steps, kernel_ms
 
     if args.calib_copy_mib:
         src = torch.ones((args.calib_copy_mib << 18,), dtype=torch.float32, device=dev)
@@ -387,60 +480,86 @@ def main():
         dst.copy_(src)          # reads and writes calib_copy_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    wall_per_step, avg_kernel_s = timed(main_flags, args.steps, args.warmup)
+    wall_per_step, kernel_ms = timed(main_flags, args.steps, args.warmup)
+    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
     ms_per_step = wall_per_step * 1e3
     value = n / wall_per_step
 
-    flops_pp = {"doubling": alg_flops_doubling(d, T), "tv": alg_flops_tv(d, T)}.get(args.path) or alg_flops(d, T, groups)
+    flops_pp = {"doubling": alg_flops_doubling(d, T), "tv": alg_flops_tv(d, T), "bwd": alg_flops_bwd(d, T)}.get(path) \
+        or alg_flops(d, T, groups)
     achieved = flops_pp * n / avg_kernel_s / 1e12
-    steps_in = T if args.path == "tv" else 1          # every step has its own matrices on the tv path
-    in_bytes = n * (steps_in * (2 * d * d + d * m + m * m) + d) * batch.A.element_size()
-    out_bytes = n * (d * d + m * d + m + 2) * 4
-    traffic_key = (args.config, groups if args.path == "symplectic" else args.path)
+    steps_in = T if path == "tv" else 1          # every step has its own matrices on the tv path
+    in_bytes = n * (steps_in * (2 * d * d + d * m + m * m) + d) * esize + (n * m * 4 if path == "bwd" else 0)
+    out_bytes = n * out_pp
+    kernel_name = {"doubling": "doubling_kernel<%d>", "tv": "solve_tv_kernel<%d>", "bwd": "backward_kernel<%d>"}.get(
+        path, "solve_kernel<%d>") % d if d != 16 or path in ("doubling", "bwd") else (
+        "solve_tv_small_kernel" if path == "tv" else "solve_small_kernel")
     res = {
-        "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d" % (d, T),
+        "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d" % (d, T) if path != "bwd" else
+                  "LQR backward passes/sec (gradients of a loss of u0) at d=%d, T=%d" % (d, T),
         "value": value, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.config, "problems": n, "d": d, "m": m, "T": T, "input_dtype": cfg["dtype"],
-                   "path": args.path, "rebase_every": None if args.path != "symplectic" else (k or "default"),
-                   "groups": groups if args.path == "symplectic" else None,
-                   "outputs": "P0,K0,u0,value"},
+                   "path": path, "rebase_every": None if path != "symplectic" else (k or "default"),
+                   "groups": groups if path == "symplectic" else None, "chunks": nchunks,
+                   "outputs": "gA,gB,gQ,gR,gx0" if path == "bwd" else "P0,K0,u0,value"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_PROBLEM[traffic_key] * n
-                                 if traffic_key in MEASURED_TRAFFIC_BYTES_PER_PROBLEM else None),
-                     "kernel": {"doubling": "doubling_kernel<%d>", "tv": "solve_tv_kernel<%d>"}.get(
-                         args.path, "solve_kernel<%d>") % d if d != 16 or args.path == "doubling" else
-                     ("solve_tv_small_kernel" if args.path == "tv" else "solve_small_kernel"),
-                     "kernel_ms": avg_kernel_s * 1e3,
+                     "traffic": measured_traffic(args.config, path, n),
+                     "kernel": kernel_name, "launches_per_step": nchunks,
+                     "kernel_ms": avg_kernel_s * 1e3, **spread(kernel_ms),
                      "alg_flops_per_problem": flops_pp,
                      "nominal_TFLOPs_N_T_d3": n * T * d ** 3 / avg_kernel_s / 1e12,
-                     "alg_bytes_per_launch": in_bytes + out_bytes,
+                     "alg_bytes_per_launch": (in_bytes + out_bytes) / nchunks,
                      "alg_GBps": (in_bytes + out_bytes) / avg_kernel_s / 1e9},
     }
     tol = 1e-4 if cfg["dtype"] == "f32" else 2e-2
     sample, ref = 0, None
-    if not args.no_cpu:
+    if not args.no_cpu and path == "bwd":
+        from oracle import lqr_grad_oracle
+        sample = min(n, chunk, args.cpu_sample or {16: 4096, 32: 1024, 64: 256, 128: 48}[d])
+        launch(0, 0, sample)
+        torch.cuda.synchronize()
+        sub = batch.take(slice(0, sample))
+        A, B, Q, R, x0 = sub.numpy64()
+        g64 = grad_u0[:sample].cpu().double().numpy()
+        t1 = time.perf_counter()
+        ref = lqr_grad_oracle.lqr_gradients(A, B, Q, R, None, x0, T, g64)
+        dt = time.perf_counter() - t1
+        errs = {kk: float(rel_err(out[kk][:sample].cpu().numpy().reshape(sample, -1), ref[kk].reshape(sample, -1)).max())
+                for kk in ("gA", "gB", "gQ", "gR", "gx0")}
+        res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": 1, "kind": "oracle",
+                               "cpu_model": cpu_model(),
+                               "sample": "first %d problems of the same workload, float64 numpy (Thm 3.2: primal and "
+                                         "dual LQR), batched over problems in one thread, %.1f s wall" % (sample, dt)}
+        res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": 2e-5 if cfg["dtype"] == "f32" else 2e-3}
+    elif not args.no_cpu:
         cores_guess = min(16, os.cpu_count() or 1)
         pilot = min(n, cores_guess * 8)
         _, pilot_dt, _ = cpu_baseline(batch, pilot)             # calibrate: aim at ~15 s of wall-clock
-        sample = min(n, args.cpu_sample or int(max(pilot, pilot * 15.0 / max(pilot_dt, 1e-3))))
+        sample = min(n, chunk, args.cpu_sample or int(max(pilot, pilot * 15.0 / max(pilot_dt, 1e-3))))
         ref, dt, cores = cpu_baseline(batch, sample)
+        launch(main_flags, 0, sample)                            # the first chunk again: its outputs are compared
+        torch.cuda.synchronize()
         errs = {kk: float(rel_err(out[kk][:sample].cpu().numpy(), ref[kk]).max()) for kk in ("P0", "K0", "u0", "value")}
         res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": cores, "kind": "oracle",
+                               "cpu_model": cpu_model(),
                                "sample": "first %d problems of the same workload, float64 numpy Riccati, "
                                          "%.1f s wall" % (sample, dt)}
         res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": tol}
     if not args.no_extra:
         # the other path on the same inputs, for comparison (never the headline value)
-        other = "doubling" if args.path == "symplectic" else "symplectic"
-        o_wall, o_kernel = timed(dbl if other == "doubling" else 0, max(1, min(args.steps, 2)), 1)
+        other = "doubling" if path == "symplectic" else "symplectic"
+        o_wall, o_ms = timed(dbl if other == "doubling" else 0, max(1, min(args.steps, 2)), 1)
+        o_kernel = sum(o_ms) / len(o_ms) / 1e3
         o_flops = alg_flops_doubling(d, T) if other == "doubling" else alg_flops(d, T, groups)
         extra = {"path": other, "value": n / o_wall, "unit": "problems/s", "kernel_ms": o_kernel * 1e3,
                  "alg_flops_per_problem": o_flops, "achieved_TFLOPs": o_flops * n / o_kernel / 1e12,
                  "frac_of_peak": o_flops * n / o_kernel / 1e12 / PEAK_FP32_MFMA_TFLOPS}
         if ref is not None:
+            launch(dbl if other == "doubling" else 0, 0, sample)
+            torch.cuda.synchronize()
             extra["max_rel_err"] = {kk: float(rel_err(out[kk][:sample].cpu().numpy(), ref[kk]).max())
                                     for kk in ("P0", "K0", "u0", "value")}
         res["other_path"] = extra

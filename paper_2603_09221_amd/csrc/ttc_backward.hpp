@@ -26,60 +26,59 @@
 
 namespace ttc {
 
-// y[j] = sum_r M[r][j] x[r] (the transposed product) for a row-major global d x d matrix: thread (part, j) sums its
-// share of the rows (consecutive threads read consecutive columns), the parts are added through LDS (red: TPR x D
-// floats).  Contains two barriers; every thread gets y[tid % D].
-template <int D, typename TM>
-__device__ __forceinline__ float matvecT_row(const TM* M, const float* xs, float* red, int tid) {
-  constexpr int TPR = Cfg<D>::NTHR / D;
-  const int j = tid % D, part = tid / D;
-  float s = 0.f;
-#pragma unroll 8
-  for (int r = part * (D / TPR); r < (part + 1) * (D / TPR); ++r) s += ld1<TM>(M, (long)r * D + j) * xs[r];
-  red[part * D + j] = s;
-  __syncthreads();
-  float y = 0.f;
-#pragma unroll
-  for (int q = 0; q < TPR; ++q) y += red[q * D + j];
-  __syncthreads();
-  return y;
-}
-
-// the same products with the matrix in one half of the LDS pair (row r at Wh + r*PITCH)
-template <int D>
-__device__ __forceinline__ float matvec_lds(const float* Wh, const float* xs, int tid) {
-  using C = Cfg<D>;
-  constexpr int TPR = C::NTHR / D;
+// Two matrix-vector products at once (the primal and the dual trajectory always need the same matrix): for the
+// row r = tid / TPR of a row-major d x d matrix, ya = sum_c M[r][c] xa[c] and yb likewise; the TPR threads of a
+// row each take a share of the columns and all of them get the sums.  MatLoad(r, c4) returns M[r][c4 .. c4+3].
+template <int D, typename MatLoad>
+__device__ __forceinline__ void matvec2(MatLoad&& row4, const float* xa, const float* xb, int tid, float& ya, float& yb) {
+  constexpr int TPR = Cfg<D>::NTHR / D;  // 2 or 4
   const int r = tid / TPR, part = tid % TPR;
-  float s = 0.f;
+  float sa = 0.f, sb = 0.f;
 #pragma unroll
   for (int c4 = part * (D / TPR); c4 < (part + 1) * (D / TPR); c4 += 4) {
-    const floatx4 mv = *reinterpret_cast<const floatx4*>(Wh + r * C::PITCH + c4);
-    s += mv[0] * xs[c4] + mv[1] * xs[c4 + 1] + mv[2] * xs[c4 + 2] + mv[3] * xs[c4 + 3];
+    const floatx4 mv = row4(r, c4);
+    sa += mv[0] * xa[c4] + mv[1] * xa[c4 + 1] + mv[2] * xa[c4 + 2] + mv[3] * xa[c4 + 3];
+    sb += mv[0] * xb[c4] + mv[1] * xb[c4 + 1] + mv[2] * xb[c4 + 2] + mv[3] * xb[c4 + 3];
   }
 #pragma unroll
-  for (int m = 1; m < TPR; m <<= 1) s += __shfl_xor(s, m, 64);
-  return s;
+  for (int m = 1; m < TPR; m <<= 1) {
+    sa += __shfl_xor(sa, m, 64);
+    sb += __shfl_xor(sb, m, 64);
+  }
+  ya = sa;
+  yb = sb;
 }
-template <int D>
-__device__ __forceinline__ float matvecT_lds(const float* Wh, const float* xs, float* red, int tid) {
-  using C = Cfg<D>;
-  constexpr int TPR = C::NTHR / D;
+// The transposed products ya[j] = sum_r M[r][j] xa[r], yb likewise: thread (part, j) sums its share of the rows
+// (consecutive threads read consecutive columns), the parts are added through LDS (red: 2 x TPR x D floats).
+// Contains two barriers; every thread gets the sums for j = tid % D.  MatLoad1(r, j) returns M[r][j].
+template <int D, typename MatLoad1>
+__device__ __forceinline__ void matvecT2(MatLoad1&& elem, const float* xa, const float* xb, float* red, int tid, float& ya,
+                                         float& yb) {
+  constexpr int TPR = Cfg<D>::NTHR / D;
   const int j = tid % D, part = tid / D;
-  float s = 0.f;
+  float sa = 0.f, sb = 0.f;
 #pragma unroll 8
-  for (int r = part * (D / TPR); r < (part + 1) * (D / TPR); ++r) s += Wh[r * C::PITCH + j] * xs[r];
-  red[part * D + j] = s;
+  for (int r = part * (D / TPR); r < (part + 1) * (D / TPR); ++r) {
+    const float mv = elem(r, j);
+    sa += mv * xa[r];
+    sb += mv * xb[r];
+  }
+  red[part * D + j] = sa;
+  red[(TPR + part) * D + j] = sb;
   __syncthreads();
-  float y = 0.f;
+  float a = 0.f, b = 0.f;
 #pragma unroll
-  for (int q = 0; q < TPR; ++q) y += red[q * D + j];
+  for (int q = 0; q < TPR; ++q) {
+    a += red[q * D + j];
+    b += red[(TPR + q) * D + j];
+  }
   __syncthreads();
-  return y;
+  ya = a;
+  yb = b;
 }
 
-// out (d x d, row-major, global) = or += a b^T + c e^T, vectors in LDS; each thread a share of the 16-byte pieces
-template <int D, bool ACCUMULATE>
+// out (d x d, row-major, global) = scale (a b^T + c e^T), vectors in LDS; each thread a share of the 16-byte pieces
+template <int D>
 __device__ __forceinline__ void outer2_global(float* out, const float* a, const float* b, const float* c, const float* e,
                                               float scale, int tid) {
   using C = Cfg<D>;
@@ -89,9 +88,7 @@ __device__ __forceinline__ void outer2_global(float* out, const float* a, const 
     floatx4 v;
 #pragma unroll
     for (int k = 0; k < 4; ++k) v[k] = ar * b[c4 + k] + cr * e[c4 + k];
-    floatx4* dst = reinterpret_cast<floatx4*>(out + (long)r * D + c4);
-    if (ACCUMULATE) v += *dst;
-    *dst = v;
+    *reinterpret_cast<floatx4*>(out + (long)r * D + c4) = v;
   }
 }
 
@@ -101,7 +98,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) backward_kernel(const BackwardAr
   constexpr int TPR = C::NTHR / D;
   __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
   __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
-  __shared__ float s_red[TPR * D];
+  __shared__ float s_red[2 * TPR * D];
   __shared__ float s_v[8][D];  // working vectors
   const RolloutArgs& p = ba.r;
   float* const WL = W;
@@ -156,21 +153,36 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) backward_kernel(const BackwardAr
 
     // ---- step 0: S_0 = R_0 + B_0^T P_1 B_0 and the two right-hand sides F x_0 = B_0^T P_1 A_0 x_0 and g
     float* const v_x = s_v[0];
-    float* const v_y = s_v[1];
-    float* const v_z = s_v[2];
-    float* const v_u = s_v[3];
-    float* const v_ut = s_v[4];
-    float* const v_xt = s_v[5];
-    if (tid < D) v_x[tid] = ld1<TIn>(x0p, tid);
-    __syncthreads();
-    {
-      const float y = matvec_row<D, TIn>(Ap, v_x, tid);  // A_0 x_0
-      if (tid % TPR == 0) v_y[tid / TPR] = y;
+    float* const v_xt = s_v[1];
+    float* const v_u = s_v[2];
+    float* const v_ut = s_v[3];
+    float* const v_l = s_v[4];
+    float* const v_lt = s_v[5];
+    float* const v_y = s_v[6];
+    float* const v_z = s_v[7];
+    auto glob4 = [](const TIn* M) { return [M](int r, int c4) { return ld4<TIn>(M, (long)r * D + c4); }; };
+    auto glob1 = [](const TIn* M) { return [M](int r, int j) { return ld1<TIn>(M, (long)r * D + j); }; };
+    auto lds4 = [](const float* Wh) {
+      return [Wh](int r, int c4) { return *reinterpret_cast<const floatx4*>(Wh + r * C::PITCH + c4); };
+    };
+    auto lds1 = [](const float* Wh) { return [Wh](int r, int j) { return Wh[r * C::PITCH + j]; }; };
+    const bool lead = (tid % TPR == 0);  // one thread of each row's group
+    const int row = tid / TPR;
+    if (tid < D) {
+      v_x[tid] = ld1<TIn>(x0p, tid);
+      v_xt[tid] = 0.f;
     }
     __syncthreads();
     {
-      const float z = matvec_lds<D>(WR, v_y, tid);  // P_1 A_0 x_0
-      if (tid % TPR == 0) v_z[tid / TPR] = z;
+      float y, dummy;
+      matvec2<D>(glob4(Ap), v_x, v_xt, tid, y, dummy);  // A_0 x_0
+      if (lead) v_y[row] = y;
+    }
+    __syncthreads();
+    {
+      float z, dummy;
+      matvec2<D>(lds4(WR), v_y, v_xt, tid, z, dummy);  // P_1 A_0 x_0
+      if (lead) v_z[row] = z;
     }
     __syncthreads();
     {
@@ -182,7 +194,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) backward_kernel(const BackwardAr
       zero_acc<D>(acc);
       gemm_acc<D>(acc, cP, WL, i, g);  // P_1 B_0
       load_aopT_lds<D>(WL, cBT, w, i, g);  // rows of B_0^T
-      const float fx = matvecT_lds<D>(WL, v_z, s_red, tid);  // B_0^T P_1 A_0 x_0 (contains barriers)
+      float fx, dummy;
+      matvecT2<D>(lds1(WL), v_z, v_xt, s_red, tid, fx, dummy);  // B_0^T P_1 A_0 x_0 (contains barriers)
       store_rows<D>(WR, acc, w, i, g);  // right half: P_1 B_0 (every wavefront holds its rows of P_1)
       __syncthreads();
       load_rows_input<D, TIn>(Rp, acc, w, i, g);
@@ -208,14 +221,20 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) backward_kernel(const BackwardAr
       if (flag && !info) info = T;
     }
     if (tid < D) {
-      const float u = -WR[tid * C::PITCH + 0], ut = -WR[tid * C::PITCH + 1];
-      v_u[tid] = u;
-      v_ut[tid] = ut;
-      v_xt[tid] = 0.f;
+      v_u[tid] = -WR[tid * C::PITCH + 0];
+      v_ut[tid] = -WR[tid * C::PITCH + 1];
       tX[tid] = v_x[tid];
       tXt[tid] = 0.f;
     }
     __syncthreads();
+    // Time-invariant parameters: A and B stay in the two halves of the pair (free from here on) for the closed
+    // loops and the co-states, so that only the gains are read from memory in the loops below.
+    const bool resident = ba.sum_steps != 0;
+    if (resident) {
+      load_half<D, TIn, false>(WL, Ap, tid);
+      load_half<D, TIn, false>(WR, Bp, tid);
+      __syncthreads();
+    }
 
     // ---- both closed loops forward (Alg. 1): states and controls of every step to the workspace
     for (int s = 0; s < T; ++s) {
@@ -223,77 +242,100 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) backward_kernel(const BackwardAr
       const TIn* Bs = Bp + (long long)s * ba.tB;
       if (s >= 1) {
         const float* Ks = wsK + (long)(s - 1) * D * D;
-        const float u = matvec_row<D, float>(Ks, v_x, tid);
-        const float ut = matvec_row<D, float>(Ks, v_xt, tid);
-        if (tid % TPR == 0) {
-          v_u[tid / TPR] = u;
-          v_ut[tid / TPR] = ut;
+        float u, ut;
+        matvec2<D>([Ks](int r, int c4) { return *reinterpret_cast<const floatx4*>(Ks + (long)r * D + c4); }, v_x, v_xt,
+                   tid, u, ut);
+        if (lead) {
+          v_u[row] = u;
+          v_ut[row] = ut;
         }
         __syncthreads();
       }
-      const float xn = matvec_row<D, TIn>(As, v_x, tid) + matvec_row<D, TIn>(Bs, v_u, tid);
-      const float xtn = matvec_row<D, TIn>(As, v_xt, tid) + matvec_row<D, TIn>(Bs, v_ut, tid);
+      float ax, axt, bu, but;
+      if (resident) {
+        matvec2<D>(lds4(WL), v_x, v_xt, tid, ax, axt);
+        matvec2<D>(lds4(WR), v_u, v_ut, tid, bu, but);
+      } else {
+        matvec2<D>(glob4(As), v_x, v_xt, tid, ax, axt);
+        matvec2<D>(glob4(Bs), v_u, v_ut, tid, bu, but);
+      }
       if (tid < D) {
         tU[(long)s * D + tid] = v_u[tid];
         tUt[(long)s * D + tid] = v_ut[tid];
       }
       __syncthreads();  // every thread has read the old states
-      if (tid % TPR == 0) {
-        const int r = tid / TPR;
-        v_x[r] = xn;
-        v_xt[r] = xtn;
-        tX[(long)(s + 1) * D + r] = xn;
-        tXt[(long)(s + 1) * D + r] = xtn;
+      if (lead) {
+        v_x[row] = ax + bu;
+        v_xt[row] = axt + but;
+        tX[(long)(s + 1) * D + row] = ax + bu;
+        tXt[(long)(s + 1) * D + row] = axt + but;
       }
       __syncthreads();
     }
 
-    // ---- co-states backward (Alg. 2), for both trajectories; dl/dx_0 = lamt_0
-    float* const v_l = s_v[6];
-    float* const v_lt = s_v[7];
-    {
-      const float l = matvec_row<D, TIn>(stage_cost(T - 1), v_x, tid);  // lam_T = Q_T x_T (Q read as its symmetric
-      const float lT = matvecT_row<D, TIn>(stage_cost(T - 1), v_x, s_red, tid);  // part: half of Q x + Q^T x)
-      const float lt = matvec_row<D, TIn>(stage_cost(T - 1), v_xt, tid);
-      const float ltT = matvecT_row<D, TIn>(stage_cost(T - 1), v_xt, s_red, tid);
-      if (tid % TPR == 0) {
-        v_y[tid / TPR] = 0.5f * l;
-        v_z[tid / TPR] = 0.5f * lt;
+    // ---- co-states backward (Alg. 2), for both trajectories; dl/dx_0 = lamt_0.  A cost matrix is read as its
+    // symmetric part: half of Q x + Q^T x from memory, or the symmetrised copy when it stays in LDS.
+    auto sym_cost_times = [&](const TIn* Qm, float& qa, float& qb) {  // for j = tid < D: (sym(Q) v_x)[j], (sym(Q) v_xt)[j]
+      float r1, r2, c1, c2;
+      matvec2<D>(glob4(Qm), v_x, v_xt, tid, r1, r2);
+      matvecT2<D>(glob1(Qm), v_x, v_xt, s_red, tid, c1, c2);
+      if (lead) {
+        v_y[row] = r1;
+        v_z[row] = r2;
       }
       __syncthreads();
+      qa = qb = 0.f;
       if (tid < D) {
-        v_l[tid] = v_y[tid] + 0.5f * lT;
-        v_lt[tid] = v_z[tid] + 0.5f * ltT;
-        tL[(long)T * D + tid] = v_l[tid];
-        tLt[(long)T * D + tid] = v_lt[tid];
+        qa = 0.5f * (v_y[tid] + c1);
+        qb = 0.5f * (v_z[tid] + c2);
       }
+      __syncthreads();
+    };
+    {
+      float qa, qb;
+      sym_cost_times(stage_cost(T - 1), qa, qb);  // lam_T = Q_T x_T
+      if (tid < D) {
+        v_l[tid] = qa;
+        v_lt[tid] = qb;
+        tL[(long)T * D + tid] = qa;
+        tLt[(long)T * D + tid] = qb;
+      }
+      __syncthreads();
+    }
+    if (resident && T >= 2) {  // the stage cost Q, symmetrised, takes B's place
+      load_half<D, TIn, false>(WR, Qp, tid);
+      __syncthreads();
+      symmetrise_half<D>(WR, tid);
       __syncthreads();
     }
     for (int t = T - 1; t >= 0; --t) {
       // lam_t = Q[t-1] x_t + A_t^T lam_{t+1} (no state cost for t = 0)
       const TIn* At = Ap + (long long)t * ba.tA;
-      float al = matvecT_row<D, TIn>(At, v_l, s_red, tid);
-      float alt = matvecT_row<D, TIn>(At, v_lt, s_red, tid);
+      float al, alt;
+      if (resident) matvecT2<D>(lds1(WL), v_l, v_lt, s_red, tid, al, alt);
+      else matvecT2<D>(glob1(At), v_l, v_lt, s_red, tid, al, alt);
       if (t >= 1) {
         if (tid < D) {
           v_x[tid] = tX[(long)t * D + tid];
           v_xt[tid] = tXt[(long)t * D + tid];
         }
         __syncthreads();
-        const TIn* Qt = stage_cost(t - 1);
-        const float q1 = matvec_row<D, TIn>(Qt, v_x, tid), q2 = matvec_row<D, TIn>(Qt, v_xt, tid);
-        const float q1T = matvecT_row<D, TIn>(Qt, v_x, s_red, tid), q2T = matvecT_row<D, TIn>(Qt, v_xt, s_red, tid);
-        if (tid % TPR == 0) {
-          v_y[tid / TPR] = 0.5f * q1;
-          v_z[tid / TPR] = 0.5f * q2;
+        float qa, qb;
+        if (resident) {
+          float r1, r2;
+          matvec2<D>(lds4(WR), v_x, v_xt, tid, r1, r2);
+          if (lead) {
+            v_y[row] = r1;
+            v_z[row] = r2;
+          }
+          __syncthreads();
+          qa = tid < D ? v_y[tid] : 0.f;
+          qb = tid < D ? v_z[tid] : 0.f;
+        } else {
+          sym_cost_times(stage_cost(t - 1), qa, qb);
         }
-        __syncthreads();
-        al += 0.5f * q1T;
-        alt += 0.5f * q2T;
-        if (tid < D) {
-          al += v_y[tid];
-          alt += v_z[tid];
-        }
+        al += qa;
+        alt += qb;
       }
       __syncthreads();
       if (tid < D) {
@@ -307,8 +349,8 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) backward_kernel(const BackwardAr
     if (tid < D) ba.gx0[prob * D + tid] = info ? nanv : v_lt[tid];
     if (tid == 0 && p.info) p.info[prob] = info;
 
-    // ---- gradients: per step, or summed over the steps for time-invariant parameters
-    for (int s = 0; s < T; ++s) {
+    // ---- gradients: per step, or summed over the steps (in registers) for time-invariant parameters
+    auto stage_vectors = [&](int s) {  // lam, lamt of s+1; x, xt, u, ut of s; x, xt of s+1
       __syncthreads();
       if (tid < D) {
         s_v[0][tid] = info ? nanv : tL[(long)(s + 1) * D + tid];
@@ -321,33 +363,76 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) backward_kernel(const BackwardAr
         s_v[7][tid] = tXt[(long)(s + 1) * D + tid];
       }
       __syncthreads();
-      const long long mat = (long long)D * D;
-      if (ba.sum_steps) {
-        const long long o = prob * mat;
-        const bool lastq = (s == T - 1) && ba.gQT;  // a terminal cost that is its own matrix has its own gradient
-        if (s == 0) {
-          outer2_global<D, false>(ba.gA + o, s_v[0], s_v[3], s_v[1], s_v[2], 1.f, tid);
-          outer2_global<D, false>(ba.gB + o, s_v[0], s_v[5], s_v[1], s_v[4], 1.f, tid);
-          outer2_global<D, false>(ba.gR + o, s_v[5], s_v[4], s_v[4], s_v[5], 0.5f, tid);
-          if (lastq) {  // T = 1: nothing is charged at Q
-            outer2_global<D, false>(ba.gQT + o, s_v[7], s_v[6], s_v[6], s_v[7], 0.5f, tid);
-            outer2_global<D, false>(ba.gQ + o, s_v[7], s_v[6], s_v[6], s_v[7], 0.f, tid);
-          } else {
-            outer2_global<D, false>(ba.gQ + o, s_v[7], s_v[6], s_v[6], s_v[7], 0.5f, tid);
-          }
-        } else {
-          outer2_global<D, true>(ba.gA + o, s_v[0], s_v[3], s_v[1], s_v[2], 1.f, tid);
-          outer2_global<D, true>(ba.gB + o, s_v[0], s_v[5], s_v[1], s_v[4], 1.f, tid);
-          outer2_global<D, true>(ba.gR + o, s_v[5], s_v[4], s_v[4], s_v[5], 0.5f, tid);
-          if (lastq) outer2_global<D, false>(ba.gQT + o, s_v[7], s_v[6], s_v[6], s_v[7], 0.5f, tid);
-          else outer2_global<D, true>(ba.gQ + o, s_v[7], s_v[6], s_v[6], s_v[7], 0.5f, tid);
+    };
+    const long long mat = (long long)D * D;
+    if (ba.sum_steps) {
+      constexpr int NV = (D * D / 4 + C::NTHR - 1) / C::NTHR;  // 16-byte pieces of a matrix per thread
+      const long long o = prob * mat;
+      auto put = [&](float* dst, const floatx4 (&v)[NV]) {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          const int idx = tid + k * C::NTHR;
+          if (idx < D * D / 4)
+            *reinterpret_cast<floatx4*>(dst + o + (long long)(idx / (D / 4)) * D + (idx % (D / 4)) * 4) = v[k];
         }
-      } else {
+      };
+      {  // first pass over the steps: dl/dA and dl/dB (two passes keep the accumulators within the register file)
+        floatx4 sA[NV], sB[NV];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) sA[k] = sB[k] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < T; ++s) {
+          stage_vectors(s);
+#pragma unroll
+          for (int k = 0; k < NV; ++k) {
+            const int idx = tid + k * C::NTHR;
+            if (idx < D * D / 4) {
+              const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
+              const float l = s_v[0][r], lt = s_v[1][r];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                sA[k][e] += l * s_v[3][c4 + e] + lt * s_v[2][c4 + e];
+                sB[k][e] += l * s_v[5][c4 + e] + lt * s_v[4][c4 + e];
+              }
+            }
+          }
+        }
+        put(ba.gA, sA);
+        put(ba.gB, sB);
+      }
+      {  // second pass: dl/dR, dl/dQ and the terminal cost's own gradient
+        floatx4 sQ[NV], sR[NV], sQT[NV];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) sQ[k] = sR[k] = sQT[k] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < T; ++s) {
+          stage_vectors(s);
+          const bool terminal_own = (s == T - 1) && ba.gQT;  // a terminal cost that is its own matrix
+#pragma unroll
+          for (int k = 0; k < NV; ++k) {
+            const int idx = tid + k * C::NTHR;
+            if (idx < D * D / 4) {
+              const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
+              const float ur = 0.5f * s_v[4][r], utr = 0.5f * s_v[5][r], xr = 0.5f * s_v[6][r], xtr = 0.5f * s_v[7][r];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                sR[k][e] += utr * s_v[4][c4 + e] + ur * s_v[5][c4 + e];
+                const float q = xtr * s_v[6][c4 + e] + xr * s_v[7][c4 + e];
+                if (terminal_own) sQT[k][e] += q; else sQ[k][e] += q;
+              }
+            }
+          }
+        }
+        put(ba.gQ, sQ);
+        put(ba.gR, sR);
+        if (ba.gQT) put(ba.gQT, sQT);
+      }
+    } else {
+      for (int s = 0; s < T; ++s) {
+        stage_vectors(s);
         const long long o = (prob * T + s) * mat;
-        outer2_global<D, false>(ba.gA + o, s_v[0], s_v[3], s_v[1], s_v[2], 1.f, tid);
-        outer2_global<D, false>(ba.gB + o, s_v[0], s_v[5], s_v[1], s_v[4], 1.f, tid);
-        outer2_global<D, false>(ba.gQ + o, s_v[7], s_v[6], s_v[6], s_v[7], 0.5f, tid);
-        outer2_global<D, false>(ba.gR + o, s_v[5], s_v[4], s_v[4], s_v[5], 0.5f, tid);
+        outer2_global<D>(ba.gA + o, s_v[0], s_v[3], s_v[1], s_v[2], 1.f, tid);
+        outer2_global<D>(ba.gB + o, s_v[0], s_v[5], s_v[1], s_v[4], 1.f, tid);
+        outer2_global<D>(ba.gQ + o, s_v[7], s_v[6], s_v[6], s_v[7], 0.5f, tid);
+        outer2_global<D>(ba.gR + o, s_v[5], s_v[4], s_v[4], s_v[5], 0.5f, tid);
       }
     }
     __syncthreads();
