@@ -225,6 +225,53 @@ def bench_cxt(args):
     print(json.dumps(res))
 
 
+def bench_grid(args):
+    """The paper's solver benchmark grid (App. "Efficiency Benchmark": d = 16, horizon 2^4 .. 2^11 at batch 1024, batch
+    2^4 .. 2^13 at horizon 64), forward and backward, time-heterogeneous dense steps: milliseconds per call (median
+    of the timed calls) and the paper's nominal rate B T d^3 / time."""
+    import numpy as np
+    import torch
+    from paper_2603_09221_amd import binding, synth
+
+    d = 16
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    binding.load()
+    stream = torch.cuda.current_stream()
+    combos = [(1024, 2 ** e) for e in range(4, 12)] + [(2 ** e, 64) for e in range(4, 14) if 2 ** e != 1024]
+    rows = []
+    for B, T in combos:
+        b = synth.make_tv_batch(B, d, d, T, seed=0, device=dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1)
+        g = torch.randn((B, d), generator=gen, dtype=torch.float32, device=dev)
+        fwd = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, b.R, b.x0, stream=stream)
+        need = binding.load().ttc_lqr_backward_tv_workspace_bytes(binding.make_tv_problem(b.A, b.B, b.Q, b.R, b.x0))
+        ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+        bwd = binding.ttc_lqr_backward_tv(b.A, b.B, b.Q, b.R, b.x0, g, workspace=ws, stream=stream)
+
+        def med(fn):
+            for _ in range(max(args.warmup, 2)):
+                fn()
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.steps, 5))]
+            for e0, e1 in evs:
+                e0.record(stream)
+                fn()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            return float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+        f_ms = med(lambda: binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, b.R, b.x0, out=fwd, stream=stream))
+        b_ms = med(lambda: binding.ttc_lqr_backward_tv(b.A, b.B, b.Q, b.R, b.x0, g, out=bwd, workspace=ws, stream=stream))
+        assert int(fwd["info"].abs().max()) == 0 and int(bwd["info"].abs().max()) == 0
+        nominal = B * T * d ** 3 / 1e9   # GFLOP in the paper's unit
+        rows.append({"B": B, "T": T, "fwd_ms": f_ms, "bwd_ms": b_ms, "fwd_bwd_ms": f_ms + b_ms,
+                     "nominal_TFLOPs_fwd_bwd": nominal / (f_ms + b_ms)})
+        del b, fwd, bwd, ws
+    print(json.dumps({"metric": "paper solver benchmark grid, d=16, forward + backward, time-heterogeneous dense steps",
+                      "unit": "ms per call", "n_gpus": 1, "dtype": "f32", "data": "synthetic", "rows": rows}))
+
+
 def alg_flops_scan(d, T):
     """Algorithmic flops of one problem on the pairwise path (ttc_lqr_solve_tv_scan): T-1 elements (R^{-1}B^T:
     d^3/3 + 2 d^3, G: 2 d^3), T-1 compositions (eight products and a dense solve with d right-hand sides:
@@ -349,7 +396,7 @@ def main():
     ap.add_argument("--config", default="llm_adapter")
     ap.add_argument("--chunk", type=int, default=None, help="problems per launch (default: the whole workload, or "
                     "the largest power-of-two split whose outputs fit the card)")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd"),
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd", "grid"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
                          "doubling: the long-horizon path, the same product formed by squaring; "
                          "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
@@ -358,7 +405,8 @@ def main():
                          "1048576 problems, --config ignored; "
                          "scan: ttc_lqr_solve_tv_scan at d = 16, 16 problems, horizon 2048, --config ignored; "
                          "bwd: the backward pass (ttc_lqr_backward) on the configuration's shape (default up to "
-                         "131072 problems)")
+                         "131072 problems); grid: the paper's solver benchmark grid at d = 16, forward and backward "
+                         "(prints a table, not a bench line)")
     ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt (default 8) and scan (default 2048) paths")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
@@ -378,6 +426,8 @@ def main():
         return bench_cxt(args)
     if args.path == "scan":
         return bench_scan(args)
+    if args.path == "grid":
+        return bench_grid(args)
 
     import numpy as np
     import torch

@@ -117,10 +117,16 @@ static long long grid_blocks(Kind kind, int d, bool bf16) {
 constexpr float GROWTH_LIMIT_F32 = 256.f;
 constexpr float GROWTH_LIMIT_BF16 = 16384.f;
 
-// d = 16, default path: batches that fill the chip go four problems to a wavefront (more throughput);
-// small batches keep one problem per wavefront (more wavefronts in flight, lower latency).
+// d = 16: large batches go four problems to a wavefront (more throughput per instruction issued), small ones
+// one problem to a wavefront (more wavefronts in flight, lower latency).  Crossover measured on MI355X, in
+// problems per compute unit: 12 for the symplectic kernel (T = 8), 24 for the Riccati kernel (T = 64).
+constexpr long long QUAD_MIN_PER_CU_SOLVE = 12;
+constexpr long long QUAD_MIN_PER_CU_TV = 24;
 static bool use_quad_kernel(const ttc_lqr_problem_t* q) {
-  return q->d == 16 && !(q->flags & TTC_FLAG_DOUBLING) && q->n >= 8LL * cu_count();
+  return q->d == 16 && !(q->flags & TTC_FLAG_DOUBLING) && q->n >= QUAD_MIN_PER_CU_SOLVE * cu_count();
+}
+static bool use_quad_kernel_tv(const ttc_lqr_tv_problem_t* q) {
+  return q->d == 16 && q->n >= QUAD_MIN_PER_CU_TV * cu_count();
 }
 
 static bool shape_supported_dm(int d, int m) { return d == m && (d == 16 || d == 32 || d == 64 || d == 128); }
@@ -391,7 +397,7 @@ ttc_status_t ttc_lqr_solve_tv(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solut
   // d = 16: the kernel with a lane per row of the dense solves; batches that fill the chip go four problems
   // to a wavefront, smaller ones one problem to a wavefront
   const bool small = q->d == 16;
-  const bool quad = small && q->n >= 8LL * ttc::cu_count();
+  const bool quad = ttc::use_quad_kernel_tv(q);
   const long long gb = ttc::grid_blocks(small ? ttc::KIND_TV_QUAD : ttc::KIND_SOLVE_TV, q->d, bf16);
   const long long items = quad ? (q->n + 3) / 4 : q->n;
   const dim3 grid((unsigned)(items < gb ? items : gb));

@@ -91,7 +91,7 @@ def test_no_modulation_is_the_time_invariant_problem():
     the same problems as dense matrices, at the same tolerance (problems whose pair grows faster than its
     grouping allows are caught by its growth guard)."""
     run_no_modulation(90)
-    run_no_modulation(2100)      # four problems per wavefront on the dense path too
+    run_no_modulation(3100)      # four problems per wavefront on the dense path too
 
 
 def run_no_modulation(n):

@@ -43,7 +43,7 @@ def solve(b, **kw):
 SCALES = (1e-2, 1.0, 1e2)
 
 
-@pytest.mark.parametrize("d,n,T", [(16, 2100, 9), (16, 60, 9), (64, 80, 9), (128, 24, 6)])
+@pytest.mark.parametrize("d,n,T", [(16, 3100, 9), (16, 60, 9), (64, 80, 9), (128, 24, 6)])
 @pytest.mark.parametrize("rho", [0.5, None, 1.2])
 def test_cost_scales_and_spectral_radii(d, n, T, rho):
     """R and Q scaled by 1e-2 .. 1e2 (all nine combinations), rho(A) from 0.5 to 1.2: 1e-4 with info == 0
@@ -69,7 +69,7 @@ def test_cost_scales_and_spectral_radii(d, n, T, rho):
             assert v <= tol, (d, rho, qs, rs, k, v)
 
 
-@pytest.mark.parametrize("d,n", [(16, 2100), (16, 40), (64, 64), (128, 20)])
+@pytest.mark.parametrize("d,n", [(16, 3100), (16, 40), (64, 64), (128, 20)])
 def test_fast_growing_problems_take_the_riccati_recursion(d, n):
     """Cheap control (R scaled by 1e-2): the pair grows a thousandfold per factor, far beyond the guard's limit,
     so every problem must come out exactly as ttc_lqr_solve_tv computes it on the same matrices repeated over
@@ -115,7 +115,7 @@ def test_hard_and_easy_problems_side_by_side(d, n):
 def test_breakdown_next_to_a_hard_problem_keeps_its_report():
     """A singular A (set-up breakdown, info = 2, NaN outputs) in the same wavefront as a problem the guard hands
     to the Riccati recursion."""
-    n, d, T = 2100, 16, 6
+    n, d, T = 3100, 16, 6
     b = synth.make_batch(n, d, d, T, seed=8, device=DEV)
     A, R = b.A.clone(), b.R.clone()
     A[1001] = 0.0

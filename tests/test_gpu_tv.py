@@ -37,9 +37,9 @@ def test_shapes_horizons_and_ragged_batches(d, T, n):
 
 
 def test_d16_large_batches_four_problems_per_wavefront():
-    """From 8 x CUs problems on, d = 16 runs four problems per wavefront: ragged last quad, bfloat16 inputs, a
+    """From 24 x CUs problems on, d = 16 runs four problems per wavefront: ragged last quad, bfloat16 inputs, a
     horizon of one, and a breakdown that must stay with its own problem."""
-    n = 2048 + 37
+    n = 6144 + 37
     b = synth.make_tv_batch(n, 16, 16, 6, seed=21, device=DEV)
     out = check(b, TOL_F32)
     check(synth.make_tv_batch(n, 16, 16, 1, seed=22, device=DEV), TOL_F32)
@@ -49,7 +49,7 @@ def test_d16_large_batches_four_problems_per_wavefront():
     bad = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, R, b.x0)
     info = bad["info"].cpu().numpy()
     assert info[1001] == 4 and (np.delete(info, 1001) == 0).all()
-    keep = torch.tensor([1000, 1002, 1003, 2084], device=DEV)
+    keep = torch.tensor([1000, 1002, 1003, n - 1], device=DEV)
     assert torch.equal(bad["u0"][keep], out["u0"][keep]) and torch.isnan(bad["u0"][1001]).all()
 
 
