@@ -389,13 +389,27 @@ struct SolveScratch {
   int flag;
 };
 
-// (a) Gauss-Jordan on the d x 16 panel at column cb by one wavefront, rows in registers (a lane owns rows
-// lane and lane + 64).  Branch-free: the pivot row's values are picked by a select on the (uniform) half it
-// lies in and broadcast with v_readlane.  amask/atag: per row, 0x7FFFFF80 / (127 - row) while the row has not
-// been a pivot, 0 afterwards.
+// signed max over the 64 lanes of keys that are either non-negative or to be ignored (negative), wave-uniform
+__device__ __forceinline__ int wave_max_nonneg_i32(int x) {
+  auto mx = [](int a, int b) { return a > b ? a : b; };
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false));  // row_mirror
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false));  // row_bcast15 into rows 1 and 3
+  x = mx(x, __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false));  // row_bcast31 into rows 2 and 3
+  return __builtin_amdgcn_readlane(x, 63);
+}
+
+// (a) Gauss-Jordan on the d x 16 panel at column cb by one wavefront, rows in registers (a lane owns rows lane
+// and lane + 64).  A lone wavefront is bound by the number of instructions it issues, so a column costs as few
+// as possible: the pivot search is one signed DPP max of the key (|value| bits above 7 | atag), atag = 127 - row
+// while the row has not been a pivot and the sign bit afterwards (such a key loses against every live row);
+// the pivot row is broadcast with v_readlane from the half of the rows it lies in (a uniform branch: the code
+// of a column exists once per half, and only the pivot's half pays for the masks that exempt the pivot row).
 template <int D, bool PIVOT>
 __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb, int lane,
-                                             uint32_t (&amask)[(D + 63) / 64], uint32_t (&atag)[(D + 63) / 64], int& bad) {
+                                             int (&atag)[(D + 63) / 64], int& bad) {
   using C = Cfg<D>;
   constexpr int NRL = (D + 63) / 64;
   float a[NRL][16];
@@ -413,47 +427,72 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   }
   int lane_piv = 0;     // lane j: pivot row of column cb + j
   float lane_pv = 1.f;  // lane j: its pivot value
-  static_for<0, 16>([&](auto J) {
-    constexpr int j = decltype(J)::value;
-    int pr;
+  // pivot row of column cb + j: the live row with the largest |value| (ties and zeros: the lowest row)
+  auto search = [&](auto JC) {
+    constexpr int j = decltype(JC)::value;
     if constexpr (PIVOT) {
-      uint32_t key = (__float_as_uint(a[0][j]) & amask[0]) | atag[0];
+      int key = (int)(__float_as_uint(a[0][j]) & 0x7FFFFF80u) | atag[0];
       if constexpr (NRL > 1) {
-        const uint32_t k1 = (__float_as_uint(a[1][j]) & amask[1]) | atag[1];
+        const int k1 = (int)(__float_as_uint(a[1][j]) & 0x7FFFFF80u) | atag[1];
         key = k1 > key ? k1 : key;
       }
-      key = wave_max_u32(key);
-      pr = 127 - (int)(key & 0x7Fu);
-      pr = pr < D ? pr : D - 1;  // never leave the array, whatever the data
+      key = wave_max_nonneg_i32(key);
+      const int pr = 127 - (key & 0x7F);
+      return pr < D ? pr : D - 1;  // never leave the array, whatever the data
     } else {
-      pr = cb + j;
+      return cb + j;
     }
+  };
+  int pr = search(IntC<0>{});
+  static_for<0, 16>([&](auto J) {
+    constexpr int j = decltype(J)::value;
     const int pl = pr & 63;
-    const bool ps = (NRL > 1) && (pr >= 64);
-    float prow[16];
-    static_for<j, 16>([&](auto JJ) {
-      constexpr int jj = decltype(JJ)::value;
-      float sel = a[0][jj];
-      if constexpr (NRL > 1) sel = ps ? a[NRL - 1][jj] : sel;
-      prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sel), pl));
-    });
-    const float inv = __builtin_amdgcn_rcpf(prow[j]);
-    lane_piv = (lane == j) ? pr : lane_piv;
-    lane_pv = (lane == j) ? prow[j] : lane_pv;
-#pragma unroll
-    for (int rr = 0; rr < NRL; ++rr) {
-      // keep = all ones except in the lane and slot of the pivot row: plain bit masks instead of selects, so that
-      // the compiler has no reason to branch around the (rare) pivot-row case
-      const uint32_t keep = ((lane == pl) && ((rr == NRL - 1 && NRL > 1) == ps)) ? 0u : 0xFFFFFFFFu;
-      const float l = __uint_as_float(__float_as_uint(a[rr][j]) & keep) * inv;  // 0 for the pivot row itself
-      amask[rr] &= keep;
-      atag[rr] &= keep;
-      myj[rr] = (myj[rr] & (int)keep) | (j & (int)~keep);
-      a[rr][j] = l;
-      static_for<j + 1, 16>([&](auto JJ) {
+    // one column step with the pivot row in half PH of the rows; it ends with the search of the next column,
+    // which only needs that column updated and can therefore run beside the other columns' updates
+    auto step = [&](auto PHC) {
+      constexpr int PH = decltype(PHC)::value;
+      float prow[16];
+      static_for<j, 16>([&](auto JJ) {
         constexpr int jj = decltype(JJ)::value;
-        a[rr][jj] = __builtin_fmaf(-l, prow[jj], a[rr][jj]);
+        prow[jj] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a[PH][jj]), pl));
       });
+      const float inv = __builtin_amdgcn_rcpf(prow[j]);
+      asm("v_writelane_b32 %0, %1, %2" : "+v"(lane_piv) : "s"(pr), "n"(j));
+      asm("v_writelane_b32 %0, %1, %2" : "+v"(lane_pv) : "s"(prow[j]), "n"(j));
+      const bool hot = (lane == pl);  // in half PH, this lane's row is the pivot row
+      float l[NRL];
+#pragma unroll
+      for (int rr = 0; rr < NRL; ++rr) {
+        if (rr == PH) {
+          l[rr] = (hot ? 0.f : a[rr][j]) * inv;  // the pivot row itself is not updated
+          atag[rr] = hot ? (int)0x80000000 : atag[rr];
+          myj[rr] = hot ? j : myj[rr];
+        } else {
+          l[rr] = a[rr][j] * inv;
+        }
+        a[rr][j] = l[rr];
+        if constexpr (j + 1 < 16) a[rr][j + 1] = __builtin_fmaf(-l[rr], prow[j + 1], a[rr][j + 1]);
+      }
+      int next = 0;
+      if constexpr (j + 1 < 16) next = search(IntC<j + 1>{});
+#pragma unroll
+      for (int rr = 0; rr < NRL; ++rr) {
+        static_for<j + 2, 16>([&](auto JJ) {
+          constexpr int jj = decltype(JJ)::value;
+          a[rr][jj] = __builtin_fmaf(-l[rr], prow[jj], a[rr][jj]);
+        });
+        // the column's updates end here, inside their branch: otherwise the compiler moves them behind the point
+        // where the two branches meet and copies the broadcast row into vector registers to get them there
+#pragma unroll
+        for (int jj = j; jj < 16; ++jj) asm volatile("" : "+v"(a[rr][jj]));
+      }
+      return next;
+    };
+    if constexpr (NRL > 1) {
+      if (pr >= 64) pr = step(IntC<NRL - 1>{});
+      else pr = step(IntC<0>{});
+    } else {
+      pr = step(IntC<0>{});
     }
   });
   if (lane < 16) {
@@ -469,16 +508,12 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
     const int r = lane + 64 * rr;
     if (r < D) {
       const int j0 = myj[rr];
-      if (j0 < 16) {
-#pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-          if (jj < j0) L11[j0 * 16 + jj] = a[rr][jj];
-        }
-      }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         floatx4 t;
         t[0] = a[rr][4 * q + 0]; t[1] = a[rr][4 * q + 1]; t[2] = a[rr][4 * q + 2]; t[3] = a[rr][4 * q + 3];
+        // row j0 of the unit-lower factor: only its entries left of the diagonal are read back
+        if (j0 < 16) *reinterpret_cast<floatx4*>(L11 + j0 * 16 + 4 * q) = t;
         *reinterpret_cast<floatx4*>(W + r * C::PITCH + cb + 4 * q) = t;
       }
     }
@@ -817,15 +852,11 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
   constexpr int NRL = (D + 63) / 64;
   tid += opaque_zero();
   const int lane = tid & 63, w = tid >> 6;
-  uint32_t amask[NRL], atag[NRL];
+  int atag[NRL];
 #pragma unroll
-  for (int rr = 0; rr < NRL; ++rr) {
-    const bool act = (lane + 64 * rr) < D;
-    amask[rr] = act ? 0x7FFFFF80u : 0u;
-    atag[rr] = act ? (uint32_t)(127 - (lane + 64 * rr)) : 0u;
-  }
+  for (int rr = 0; rr < NRL; ++rr) atag[rr] = (lane + 64 * rr) < D ? 127 - (lane + 64 * rr) : (int)0x80000000;
   int bad = 0;
-  if (w == 0) solve_panel<D, PIVOT>(W, S, 0, lane, amask, atag, bad);
+  if (w == 0) solve_panel<D, PIVOT>(W, S, 0, lane, atag, bad);
   for (int p = 0; p < NP; ++p) {
     __syncthreads();  // panel p is in place; every update of panel p-1 is done
     const int cb = 16 * p;
@@ -836,14 +867,14 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
       solve_update_first<D>(W, S, cb, lane, w, la);
       __syncthreads();  // the next panel's columns are up to date
       if (w == 0) {
-        solve_panel<D, PIVOT>(W, S, cb + 16, lane, amask, atag, bad);
+        solve_panel<D, PIVOT>(W, S, cb + 16, lane, atag, bad);
       } else {
         const int ntile = nct - 1;  // a contiguous share of the other column tiles each
         solve_update<D>(W, S, cb, lane, 1 + ((w - 1) * ntile) / (C::NW - 1), 1 + (w * ntile) / (C::NW - 1), la);
       }
     } else if (more) {  // one wavefront: everything in turn
       solve_update<D>(W, S, cb, lane, 0, nct, la);
-      solve_panel<D, PIVOT>(W, S, cb + 16, lane, amask, atag, bad);
+      solve_panel<D, PIVOT>(W, S, cb + 16, lane, atag, bad);
     } else {
       solve_update<D>(W, S, cb, lane, (w * nct) / C::NW, ((w + 1) * nct) / C::NW, la);
     }
