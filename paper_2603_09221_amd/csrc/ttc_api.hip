@@ -195,6 +195,12 @@ static hipError_t run_backward(const BackwardArgs& a, int d, bool bf16, dim3 gri
 
 }  // namespace ttc
 
+#ifdef TTC_PHASE_TIMERS
+// Development builds only: device buffer of eight cycle counters that workgroup 0 of ttc_lqr_solve adds to.
+static long long* g_phase_timers = nullptr;
+extern "C" void ttc_debug_set_phase_timers(long long* device_counters) { g_phase_timers = device_counters; }
+#endif
+
 extern "C" {
 
 size_t ttc_lqr_workspace_bytes(const ttc_lqr_problem_t* problem, int for_rollout) {
@@ -254,6 +260,9 @@ ttc_status_t ttc_lqr_solve(const ttc_lqr_problem_t* problem, const ttc_lqr_solut
   a.P0 = solution->P0; a.K0 = solution->K0; a.u0 = solution->u0; a.value = solution->value;
   a.info = solution->info;
   a.ws = static_cast<float*>(workspace);
+#ifdef TTC_PHASE_TIMERS
+  a.dbg = g_phase_timers;
+#endif
   const bool doubling = (problem->flags & TTC_FLAG_DOUBLING) != 0;
   const bool bf16 = problem->in_dtype == TTC_BF16;
   const bool quad = ttc::use_quad_kernel(problem);

@@ -368,8 +368,8 @@ __device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>
 //       panel, zero in column j, the later "Jordan" multipliers after it) and in S.L11 a copy of
 //       the unit-lower multipliers among the 16 pivot rows.
 //   (b) U12 = Lf^{-1} P for the 16 pivot rows P of the remaining columns, Lf the unit-lower factor among
-//       the pivot rows (S.L11): every wavefront inverts Lf once per panel and then forms U12 tile by tile
-//       on the matrix cores; negated, it stays in registers as an operand of (c).
+//       the pivot rows (S.L11): wavefront 0 inverts Lf right after factoring the panel (S.Linv), and every
+//       wavefront forms U12 tile by tile on the matrix cores; negated, it stays in registers as an operand of (c).
 //   (c) W[:, rest] -= Lm * U12 on the matrix cores, all d rows, in 16 x 16 tiles (a pivot row holds
 //       P_j = U12_j + sum_{k<j} L_jk U12_k, so the same update serves it); the product is
 //       formed transposed (MFMA M index = column, N index = row) so that a lane's four accumulator
@@ -383,7 +383,8 @@ __device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>
 // visible on entry (caller synchronised); the result is visible to every thread on return.
 template <int D>
 struct SolveScratch {
-  float L11[2][16 * 16];  // double-buffered: panel p+1 is factored while p's is still read
+  float L11[16 * 16];      // unit-lower factor among the panel's pivot rows (the factoring wavefront's own)
+  float Linv[2][16 * 16];  // its inverse; double-buffered: panel p+1 is factored while p's is still read
   float inv[D];
   int piv[D];
   int flag;
@@ -502,7 +503,7 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
     if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
   }
   bad = __any(bad) ? 1 : 0;
-  float* L11 = S.L11[(cb >> 4) & 1];
+  float* L11 = S.L11;
 #pragma unroll
   for (int rr = 0; rr < NRL; ++rr) {
     const int r = lane + 64 * rr;
@@ -520,15 +521,15 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   }
 }
 
-// Inverse of the panel's unit-lower factor Lf (rows of multipliers in S.L11) as the matrix-core A operand of
-// U12 = Lf^{-1} P: the lane (i, g) gets Linv[i][4g .. 4g+3].  Lane i of every row of 16 lanes holds row i of Lf
+// Inverse of the panel's unit-lower factor Lf (rows of multipliers in S.L11), by the wavefront that factored the
+// panel, into S.Linv, from where every wavefront reads its matrix-core A operand of U12 = Lf^{-1} P (the lane
+// (i, g) takes Linv[i][4g .. 4g+3]).  Lane i of every row of 16 lanes holds row i of Lf
 // (its own registers, read from LDS without broadcasts) and builds row i of the inverse by forward substitution
 // over the pivots k: Linv[i][:] -= Lf[i][k] Linv[k][:], with row k of the inverse taken from lane k by a DPP row
 // broadcast (the four rows of lanes do the same work).
 template <int D>
-__device__ __forceinline__ floatx4 panel_linv(SolveScratch<D>& S, int cb, int lane, int w) {
-  (void)w;
-  const float* L11 = S.L11[(cb >> 4) & 1];
+__device__ __forceinline__ void panel_linv(SolveScratch<D>& S, int cb, int lane) {
+  const float* L11 = S.L11;  // written by this wavefront just now (LDS serves a wavefront's operations in order)
   const int i = lane & 15, g = lane >> 4;
   float l[16], x[16];
 #pragma unroll
@@ -745,7 +746,7 @@ __device__ __forceinline__ floatx4 panel_linv(SolveScratch<D>& S, int cb, int la
     const float a23 = (g & 1) ? x[12 + t] : x[8 + t];
     la[t] = (g & 2) ? a23 : a01;
   }
-  return la;
+  *reinterpret_cast<floatx4*>(S.Linv[(cb >> 4) & 1] + i * 16 + 4 * g) = la;
 }
 
 // (b) + (c) for the column tiles [lo, hi) of the rest of panel cb (tile t = columns [cb+16+16t, +16)), all row
@@ -780,9 +781,16 @@ __device__ __forceinline__ void solve_update(float* W, SolveScratch<D>& S, int c
   };
   issue(0, lo);
   floatx4 av = u12(0);
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the loop starts with nothing in flight
   for (int ct = lo; ct < hi; ct += 2) {
     // even step: tile ct in buffer 0, prefetch ct+1 into buffer 1
     const bool more1 = ct + 1 < hi;
+    // The tile's reads have arrived: waited for here, by hand, because the compiler, which cannot count the
+    // LDS operations in flight around the loop, would otherwise wait for all of them after the next tile's reads
+    // have been issued, that is for the very reads the matrix-core work below is meant to hide.  LDS operations
+    // complete in order, and the only ones issued after the tile's reads are the NRT writes of the tile before
+    // it, which need not be waited for.
+    __builtin_amdgcn_s_waitcnt(0xC07F | (C::NRT << 8));  // lgkmcnt(NRT)
     if (more1) issue(1, ct + 1);
     TTC_SCHED_BARRIER();
 #pragma unroll
@@ -790,13 +798,14 @@ __device__ __forceinline__ void solve_update(float* W, SolveScratch<D>& S, int c
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) acc[0][rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[kk], bl[rt][kk], acc[0][rt], 0, 0, 0);
     floatx4 av1 = floatx4{0.f, 0.f, 0.f, 0.f};
-    if (more1) av1 = u12(1);
+    if (more1) av1 = u12(1);  // a chain of dependent matrix-core instructions runs at the full rate
     TTC_SCHED_BARRIER();
 #pragma unroll
     for (int rt = 0; rt < C::NRT; ++rt)
       *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct + 4 * g) = acc[0][rt];
     if (!more1) break;
     const bool more2 = ct + 2 < hi;
+    __builtin_amdgcn_s_waitcnt(0xC07F | (C::NRT << 8));  // lgkmcnt(NRT), as above
     if (more2) issue(0, ct + 2);
     TTC_SCHED_BARRIER();
 #pragma unroll
@@ -856,25 +865,31 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
 #pragma unroll
   for (int rr = 0; rr < NRL; ++rr) atag[rr] = (lane + 64 * rr) < D ? 127 - (lane + 64 * rr) : (int)0x80000000;
   int bad = 0;
-  if (w == 0) solve_panel<D, PIVOT>(W, S, 0, lane, atag, bad);
+  if (w == 0) {
+    solve_panel<D, PIVOT>(W, S, 0, lane, atag, bad);
+    panel_linv<D>(S, 0, lane);
+  }
   for (int p = 0; p < NP; ++p) {
     __syncthreads();  // panel p is in place; every update of panel p-1 is done
     const int cb = 16 * p;
     const int nct = (2 * D - cb - 16) / 16;  // column tiles to the right of the panel
     const bool more = (p + 1 < NP);
-    const floatx4 la = panel_linv<D>(S, cb, lane, w);
+    const floatx4 la = *reinterpret_cast<const floatx4*>(S.Linv[p & 1] + (lane & 15) * 16 + 4 * (lane >> 4));
     if (more && C::NW > 1) {
       solve_update_first<D>(W, S, cb, lane, w, la);
       __syncthreads();  // the next panel's columns are up to date
       if (w == 0) {
         solve_panel<D, PIVOT>(W, S, cb + 16, lane, atag, bad);
+        panel_linv<D>(S, cb + 16, lane);
       } else {
-        const int ntile = nct - 1;  // a contiguous share of the other column tiles each
-        solve_update<D>(W, S, cb, lane, 1 + ((w - 1) * ntile) / (C::NW - 1), 1 + (w * ntile) / (C::NW - 1), la);
+        // a contiguous share of the other column tiles each; which wavefront gets the larger share rotates
+        const int ntile = nct - 1, u = (w - 1 + p) % (C::NW - 1);
+        solve_update<D>(W, S, cb, lane, 1 + (u * ntile) / (C::NW - 1), 1 + ((u + 1) * ntile) / (C::NW - 1), la);
       }
     } else if (more) {  // one wavefront: everything in turn
       solve_update<D>(W, S, cb, lane, 0, nct, la);
       solve_panel<D, PIVOT>(W, S, cb + 16, lane, atag, bad);
+      panel_linv<D>(S, cb + 16, lane);
     } else {
       solve_update<D>(W, S, cb, lane, (w * nct) / C::NW, ((w + 1) * nct) / C::NW, la);
     }
