@@ -130,15 +130,19 @@ __device__ __forceinline__ void load_half(float* Wh, const TIn* M, int tid) {
   commit_half<D, TRANS>(Wh, h, tid);
 }
 // replace one half by its symmetric part (caller synchronises before and after).  The matrix is cut
-// into 4 x 4 blocks; a thread takes the block pair (bi, bj), bi <= bj, reads both blocks with 16-byte
-// LDS reads, averages each with the other's transpose in registers and writes them back.
+// into 4 x 4 blocks; a thread takes a block pair (bi, bj), reads both blocks with 16-byte LDS reads, averages
+// each with the other's transpose in registers and writes them back.  Consecutive lanes take consecutive
+// pairs of one diagonal, (bi, bj) = ((j + s) mod NB, j) for j = 0, 1, ...: both blocks then move by four rows
+// and four columns from lane to lane, 4 * PITCH + 4 = 20 (mod 64) words, which spreads sixteen lanes' 16-byte
+// accesses over all banks (walking along a row of blocks instead, the lower blocks of a wavefront would share
+// four banks).  Diagonals s = 0 .. NB/2 hold every unordered pair once (the last one only its first half).
 template <int D>
 __device__ __forceinline__ void symmetrise_half(float* Wh, int tid) {
   using C = Cfg<D>;
   constexpr int NB = D / 4;
-  for (int idx = tid; idx < NB * NB; idx += C::NTHR) {
-    const int bi = idx / NB, bj = idx % NB;
-    if (bi > bj) continue;
+  constexpr int NITEM = NB * (NB / 2) + NB / 2;  // diagonals 0 .. NB/2-1 in full, half of diagonal NB/2
+  for (int idx = tid; idx < NITEM; idx += C::NTHR) {
+    const int sd = idx / NB, bj = idx % NB, bi = (bj + sd) % NB;
     floatx4 u[4], l[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -150,9 +154,9 @@ __device__ __forceinline__ void symmetrise_half(float* Wh, int tid) {
     for (int r = 0; r < 4; ++r)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const float s = 0.5f * (u[r][c] + l[c][r]);
-        un[r][c] = s;
-        ln[c][r] = s;
+        const float sy = 0.5f * (u[r][c] + l[c][r]);
+        un[r][c] = sy;
+        ln[c][r] = sy;
       }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {

@@ -357,7 +357,8 @@ __device__ __forceinline__ void store_aop_lds(float* Mb, const float (&a)[Cfg<D>
 // Dense solve M X = RHS inside LDS: blocked Gauss-Jordan elimination with partial (row) pivoting on
 // the augmented d x 2d array W = [M | RHS] (row r at W + r*PITCH; M = columns [0,d), RHS = [d,2d)),
 // 16 columns per panel.  Rows are never moved: the pivot row of column c is remembered in S.piv[c]
-// (implicit pivoting) and the solution is gathered at the end, X[c][:] = RHS[S.piv[c]][:] / pivot_c.
+// (implicit pivoting) and the solution, X[c][:] = RHS[S.piv[c]][:] / pivot_c, is put in order by the last panel's
+// update as it writes its rows.
 //
 // Per panel P = [16p, 16p+16):
 //   (a) wavefront 0 holds the d x 16 panel in registers (a lane owns rows lane, lane+64) and runs
@@ -385,8 +386,9 @@ template <int D>
 struct SolveScratch {
   float L11[16 * 16];      // unit-lower factor among the panel's pivot rows (the factoring wavefront's own)
   float Linv[2][16 * 16];  // its inverse; double-buffered: panel p+1 is factored while p's is still read
-  float inv[D];
-  int piv[D];
+  float rinv[D];  // 1 / pivot, by pivot row
+  int piv[D];     // pivot row of column c
+  int ipiv[D];    // column whose pivot row r is
   int flag;
 };
 
@@ -499,7 +501,8 @@ __device__ __forceinline__ void solve_panel(float* W, SolveScratch<D>& S, int cb
   if (lane < 16) {
     const float apv = PIVOT ? fabsf(lane_pv) : lane_pv;
     S.piv[cb + lane] = lane_piv;
-    S.inv[cb + lane] = __builtin_amdgcn_rcpf(lane_pv);
+    S.ipiv[lane_piv] = cb + lane;
+    S.rinv[lane_piv] = __builtin_amdgcn_rcpf(lane_pv);
     if (!(apv > 0.f && apv < __builtin_inff())) bad = 1;
   }
   bad = __any(bad) ? 1 : 0;
@@ -752,12 +755,27 @@ __device__ __forceinline__ void panel_linv(SolveScratch<D>& S, int cb, int lane)
 // (b) + (c) for the column tiles [lo, hi) of the rest of panel cb (tile t = columns [cb+16+16t, +16)), all row
 // tiles, by one wavefront, software-pipelined: while the matrix cores update tile t, the rows of tile t+1 and
 // its pivot rows are read and tile t-1 has been written.
-template <int D>
+// FINAL (the last panel, whose remaining columns are exactly the right-hand sides): the updated rows are the
+// solution up to order and scale, row r being pivot^{-1} times row ipiv[r] of X; they are written there directly.
+// Within a column tile every row has been read before the first is written, and no other wavefront touches
+// the tile, so the permutation needs no second buffer.
+template <int D, bool FINAL = false>
 __device__ __forceinline__ void solve_update(float* W, SolveScratch<D>& S, int cb, int lane, int lo, int hi, floatx4 la) {
   using C = Cfg<D>;
   if (lo >= hi) return;
   const int i = lane & 15, g = lane >> 4;
   float* const rowp = W + i * C::PITCH + cb;  // row i of a row tile, at the panel's first column
+  float* dst[C::NRT];                         // where row i of each row tile goes, at the panel's first column
+  float scl[C::NRT];
+#pragma unroll
+  for (int rt = 0; rt < C::NRT; ++rt) {
+    dst[rt] = rowp + 16 * rt * C::PITCH;
+    scl[rt] = 1.f;
+    if constexpr (FINAL) {
+      dst[rt] = W + S.ipiv[16 * rt + i] * C::PITCH + cb;
+      scl[rt] = S.rinv[16 * rt + i];
+    }
+  }
   floatx4 bl[C::NRT];                         // Lm[row i of the row tile][4g .. 4g+3]: the same for every column tile
 #pragma unroll
   for (int rt = 0; rt < C::NRT; ++rt) bl[rt] = *reinterpret_cast<const floatx4*>(rowp + 16 * rt * C::PITCH + 4 * g);
@@ -802,7 +820,7 @@ __device__ __forceinline__ void solve_update(float* W, SolveScratch<D>& S, int c
     TTC_SCHED_BARRIER();
 #pragma unroll
     for (int rt = 0; rt < C::NRT; ++rt)
-      *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * ct + 4 * g) = acc[0][rt];
+      *reinterpret_cast<floatx4*>(dst[rt] + 16 + 16 * ct + 4 * g) = FINAL ? acc[0][rt] * scl[rt] : acc[0][rt];
     if (!more1) break;
     const bool more2 = ct + 2 < hi;
     __builtin_amdgcn_s_waitcnt(0xC07F | (C::NRT << 8));  // lgkmcnt(NRT), as above
@@ -816,7 +834,7 @@ __device__ __forceinline__ void solve_update(float* W, SolveScratch<D>& S, int c
     TTC_SCHED_BARRIER();
 #pragma unroll
     for (int rt = 0; rt < C::NRT; ++rt)
-      *reinterpret_cast<floatx4*>(rowp + 16 * rt * C::PITCH + 16 + 16 * (ct + 1) + 4 * g) = acc[1][rt];
+      *reinterpret_cast<floatx4*>(dst[rt] + 16 + 16 * (ct + 1) + 4 * g) = FINAL ? acc[1][rt] * scl[rt] : acc[1][rt];
   }
 }
 
@@ -891,33 +909,11 @@ __device__ __forceinline__ int lds_solve(float* W, SolveScratch<D>& S, int tid) 
       solve_panel<D, PIVOT>(W, S, cb + 16, lane, atag, bad);
       panel_linv<D>(S, cb + 16, lane);
     } else {
-      solve_update<D>(W, S, cb, lane, (w * nct) / C::NW, ((w + 1) * nct) / C::NW, la);
+      solve_update<D, true>(W, S, cb, lane, (w * nct) / C::NW, ((w + 1) * nct) / C::NW, la);
     }
   }
   if (tid == 0) S.flag = bad;
   __syncthreads();
-  // gather: row c of the solution is the right half of row piv[c], scaled by 1/pivot; through registers
-  {
-    constexpr int NV = (D * D / 4 + C::NTHR - 1) / C::NTHR;
-    floatx4 xv[NV];
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      const int idx = tid + k * C::NTHR;
-      if (idx < D * D / 4) {
-        const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
-        xv[k] = *reinterpret_cast<const floatx4*>(W + S.piv[c] * C::PITCH + D + j4) * S.inv[c];
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      const int idx = tid + k * C::NTHR;
-      if (idx < D * D / 4) {
-        const int c = idx / (D / 4), j4 = (idx % (D / 4)) * 4;
-        *reinterpret_cast<floatx4*>(W + c * C::PITCH + D + j4) = xv[k];
-      }
-    }
-  }
   const int flag = S.flag;
   __syncthreads();
   return flag;
