@@ -118,6 +118,12 @@ def alg_flops_tv(d, T):
     return T * (12 + 7.0 / 3) * d ** 3
 
 
+def alg_flops_rollout(d, T):
+    """Rollout (Alg. 1): the backward recursion of Prop. 3.1 with every gain kept (the per-step work of
+    alg_flops_tv), then the forward pass: K_t x, A x + B u and the stage cost per step."""
+    return alg_flops_tv(d, T) + T * 8 * d * d
+
+
 def alg_flops_bwd(d, T):
     """Algorithmic flops of one backward pass (ttc_lqr_backward): T-1 steps of the backward recursion of Prop. 3.1
     (six products and a positive definite solve with d right-hand sides, as alg_flops_tv), the first step's
@@ -396,7 +402,7 @@ def main():
     ap.add_argument("--config", default="llm_adapter")
     ap.add_argument("--chunk", type=int, default=None, help="problems per launch (default: the whole workload, or "
                     "the largest power-of-two split whose outputs fit the card)")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd", "grid"),
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd", "rollout", "grid"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
                          "doubling: the long-horizon path, the same product formed by squaring; "
                          "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
@@ -406,7 +412,8 @@ def main():
                          "scan: ttc_lqr_solve_tv_scan at d = 16, 16 problems, horizon 2048, --config ignored; "
                          "bwd: the backward pass (ttc_lqr_backward) on the configuration's shape (default up to "
                          "131072 problems); grid: the paper's solver benchmark grid at d = 16, forward and backward "
-                         "(prints a table, not a bench line)")
+                         "(prints a table, not a bench line); rollout: ttc_lqr_rollout (all T controls, states and the cost) "
+                         "on the configuration's shape (default up to 16384 problems)")
     ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt (default 8) and scan (default 2048) paths")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
@@ -437,7 +444,7 @@ def main():
     cfg = synth.CONFIGS[args.config]
     path = args.path
     full = synth.config_problems(args.config)
-    n = args.n or (min(16384, full) if path == "tv" else min(131072, full) if path == "bwd" else full)
+    n = args.n or (min(16384, full) if path in ("tv", "rollout") else min(131072, full) if path == "bwd" else full)
     d, m, T = cfg["d"], cfg["m"], cfg["T"]
     k = args.rebase_every
     groups = math.ceil(T / k) if k else default_groups(T, cfg["dtype"])
@@ -450,13 +457,14 @@ def main():
         args.no_extra = True
     else:
         batch = synth.make_batch(n, d, m, T, seed=0, device=dev, dtype=cfg["dtype"], rho=cfg["rho"])
-    if path == "bwd":
+    if path in ("bwd", "rollout"):
         args.no_extra = True
     esize = batch.A.element_size()
     # Outputs are held for one chunk of problems at a time (inputs for the whole workload stay resident): a step
     # launches the chunks one after the other on the same stream.  One chunk unless inputs plus outputs of the
     # whole workload would not fit the card.
-    out_pp = (4 * d * d + d + 1) * 4 if path == "bwd" else (d * d + m * d + m + 2) * 4
+    out_pp = (4 * d * d + d + 1) * 4 if path == "bwd" else (T * m + (T + 1) * d + 2) * 4 if path == "rollout" else \
+        (d * d + m * d + m + 2) * 4
     free_bytes = torch.cuda.mem_get_info(dev)[0]
     chunk = n
     while chunk > 1 and chunk * out_pp > 0.85 * free_bytes:
@@ -480,6 +488,9 @@ def main():
     main_flags = dbl if path == "doubling" else 0
     if path == "tv":
         ws_bytes = 16
+    elif path == "rollout":
+        ws_bytes = binding.ttc_lqr_workspace_bytes(
+            binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T), True)
     elif path == "bwd":
         ws_bytes = binding.load().ttc_lqr_backward_workspace_bytes(
             binding.make_problem(batch.A, batch.B, batch.Q, batch.R, None, batch.x0, T))
@@ -500,6 +511,8 @@ def main():
         elif path == "bwd":
             binding.ttc_lqr_backward(sub.A, sub.B, sub.Q, sub.R, None, sub.x0, T, grad_u0[lo:hi], out=o, workspace=ws,
                                      stream=stream)
+        elif path == "rollout":
+            out.update(binding.ttc_lqr_rollout(sub.A, sub.B, sub.Q, sub.R, None, sub.x0, T, workspace=ws, stream=stream))
         else:
             binding.ttc_lqr_solve(sub.A, sub.B, sub.Q, sub.R, None, sub.x0, T, flags=flags, rebase_every=k, out=o,
                                   workspace=ws, stream=stream)
@@ -535,25 +548,28 @@ def main():
     ms_per_step = wall_per_step * 1e3
     value = n / wall_per_step
 
-    flops_pp = {"doubling": alg_flops_doubling(d, T), "tv": alg_flops_tv(d, T), "bwd": alg_flops_bwd(d, T)}.get(path) \
+    flops_pp = {"doubling": alg_flops_doubling(d, T), "tv": alg_flops_tv(d, T), "bwd": alg_flops_bwd(d, T),
+                "rollout": alg_flops_rollout(d, T)}.get(path) \
         or alg_flops(d, T, groups)
     achieved = flops_pp * n / avg_kernel_s / 1e12
     steps_in = T if path == "tv" else 1          # every step has its own matrices on the tv path
     in_bytes = n * (steps_in * (2 * d * d + d * m + m * m) + d) * esize + (n * m * 4 if path == "bwd" else 0)
     out_bytes = n * out_pp
-    kernel_name = {"doubling": "doubling_kernel<%d>", "tv": "solve_tv_kernel<%d>", "bwd": "backward_kernel<%d>"}.get(
-        path, "solve_kernel<%d>") % d if d != 16 or path in ("doubling", "bwd") else (
+    kernel_name = {"doubling": "doubling_kernel<%d>", "tv": "solve_tv_kernel<%d>", "bwd": "backward_kernel<%d>",
+                   "rollout": "rollout_kernel<%d>"}.get(
+        path, "solve_kernel<%d>") % d if d != 16 or path in ("doubling", "bwd", "rollout") else (
         "solve_tv_small_kernel" if path == "tv" else "solve_small_kernel")
     res = {
-        "metric": "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d" % (d, T) if path != "bwd" else
-                  "LQR backward passes/sec (gradients of a loss of u0) at d=%d, T=%d" % (d, T),
+        "metric": "LQR backward passes/sec (gradients of a loss of u0) at d=%d, T=%d" % (d, T) if path == "bwd" else
+                  "LQR rollouts/sec (all controls, states and the cost) at d=%d, T=%d" % (d, T) if path == "rollout" else
+                  "LQR solves/sec (tokens x heads x batch problems) at d=%d, T=%d" % (d, T),
         "value": value, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.config, "problems": n, "d": d, "m": m, "T": T, "input_dtype": cfg["dtype"],
                    "path": path, "rebase_every": None if path != "symplectic" else (k or "default"),
                    "groups": groups if path == "symplectic" else None, "chunks": nchunks,
-                   "outputs": "gA,gB,gQ,gR,gx0" if path == "bwd" else "P0,K0,u0,value"},
+                   "outputs": "gA,gB,gQ,gR,gx0" if path == "bwd" else "U,X,cost" if path == "rollout" else "P0,K0,u0,value"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                      "traffic": measured_traffic(args.config, path, n),
@@ -584,6 +600,22 @@ def main():
                                "sample": "first %d problems of the same workload, float64 numpy (Thm 3.2: primal and "
                                          "dual LQR), batched over problems in one thread, %.1f s wall" % (sample, dt)}
         res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": 2e-5 if cfg["dtype"] == "f32" else 2e-3}
+    elif not args.no_cpu and path == "rollout":
+        from oracle import lqr_oracle
+        sample = min(n, chunk, args.cpu_sample or {16: 8192, 32: 2048, 64: 512, 128: 96}[d])
+        launch(0, 0, sample)
+        torch.cuda.synchronize()
+        A, B, Q, R, x0 = batch.take(slice(0, sample)).numpy64()
+        t1 = time.perf_counter()
+        ref = lqr_oracle.riccati_rollout(A, B, Q, R, None, x0, T)
+        dt = time.perf_counter() - t1
+        errs = {kk: float(rel_err(out[kk][:sample].cpu().numpy().reshape(sample, -1),
+                                  np.asarray(ref[kk]).reshape(sample, -1)).max()) for kk in ("U", "X", "cost")}
+        res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": 1, "kind": "oracle",
+                               "cpu_model": cpu_model(),
+                               "sample": "first %d problems of the same workload, float64 numpy (Alg. 1), batched "
+                                         "over problems in one thread, %.1f s wall" % (sample, dt)}
+        res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": tol}
     elif not args.no_cpu:
         cores_guess = min(16, os.cpu_count() or 1)
         pilot = min(n, cores_guess * 8)

@@ -742,14 +742,14 @@ __device__ __forceinline__ void panel_linv(SolveScratch<D>& S, int cb, int lane)
       "s_nop 1"
       : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14])
       : "v"(l[14]));
-  floatx4 la;
+  // the first row of lanes writes the inverse, row i by lane i (picking a lane's own quarter of its row out of
+  // x[] would be an indexed access to a register array, which the compiler serves from scratch memory)
+  if (g == 0) {
+    float* dst = S.Linv[(cb >> 4) & 1] + i * 16;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const float a01 = (g & 1) ? x[4 + t] : x[t];
-    const float a23 = (g & 1) ? x[12 + t] : x[8 + t];
-    la[t] = (g & 2) ? a23 : a01;
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<floatx4*>(dst + 4 * q) = floatx4{x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]};
   }
-  *reinterpret_cast<floatx4*>(S.Linv[(cb >> 4) & 1] + i * 16 + 4 * g) = la;
 }
 
 // (b) + (c) for the column tiles [lo, hi) of the rest of panel cb (tile t = columns [cb+16+16t, +16)), all row
