@@ -607,7 +607,7 @@ def main():
         torch.cuda.synchronize()
         A, B, Q, R, x0 = batch.take(slice(0, sample)).numpy64()
         t1 = time.perf_counter()
-        ref = lqr_oracle.riccati_rollout(A, B, Q, R, None, x0, T)
+        ref = dict(zip(("U", "X", "cost"), lqr_oracle.riccati_rollout(A, B, Q, R, None, x0, T)))
         dt = time.perf_counter() - t1
         errs = {kk: float(rel_err(out[kk][:sample].cpu().numpy().reshape(sample, -1),
                                   np.asarray(ref[kk]).reshape(sample, -1)).max()) for kk in ("U", "X", "cost")}
