@@ -10,7 +10,7 @@ namespace ttc {
 // PPW = problems per wavefront: 4 for batches that fill the chip, 1 for small ones (the four rows of 16 lanes
 // then all hold the same problem and compute, and write, the same values; every per-problem loop runs once).
 template <typename TIn, int PPW>
-__global__ void __launch_bounds__(64) solve_small_kernel(const SolveArgs p) {
+__global__ void __launch_bounds__(64, PPW == 4 ? 2 : 1) solve_small_kernel(const SolveArgs p) {
   constexpr int D = 16;
   using C = Cfg<D>;
   static_assert(PPW == 1 || PPW == 4, "one problem or four per wavefront");
