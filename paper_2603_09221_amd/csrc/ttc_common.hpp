@@ -97,22 +97,27 @@ struct HalfRegs {
   static constexpr int NV = (D * D / 4 + Cfg<D>::NTHR - 1) / Cfg<D>::NTHR;  // float4 pieces per thread
   floatx4 v[NV];
 };
+// (A matrix is a whole number of pieces per thread, so a thread reads all its pieces or none: one test around the
+// reads instead of one per piece, inside which the compiler waits for every 16-byte read on its own.)
 template <int D, typename TIn>
 __device__ __forceinline__ void issue_half(HalfRegs<D>& h, const TIn* M, int tid) {
   using C = Cfg<D>;
+  static_assert((D * D / 4) % C::NTHR == 0, "a matrix is a whole number of 16-byte pieces per thread");
+  if (tid < C::NTHR) {
 #pragma unroll
-  for (int k = 0; k < HalfRegs<D>::NV; ++k) {
-    const int idx = tid + k * C::NTHR;
-    if (idx < D * D / 4) h.v[k] = ld4<TIn>(M, (long)(idx / (D / 4)) * D + (idx % (D / 4)) * 4);
+    for (int k = 0; k < HalfRegs<D>::NV; ++k) {
+      const int idx = tid + k * C::NTHR;
+      h.v[k] = ld4<TIn>(M, (long)(idx / (D / 4)) * D + (idx % (D / 4)) * 4);
+    }
   }
 }
 template <int D, bool TRANS>
 __device__ __forceinline__ void commit_half(float* Wh, const HalfRegs<D>& h, int tid) {
   using C = Cfg<D>;
+  if (tid < C::NTHR) {
 #pragma unroll
-  for (int k = 0; k < HalfRegs<D>::NV; ++k) {
-    const int idx = tid + k * C::NTHR;
-    if (idx < D * D / 4) {
+    for (int k = 0; k < HalfRegs<D>::NV; ++k) {
+      const int idx = tid + k * C::NTHR;
       const int r = idx / (D / 4), c4 = (idx % (D / 4)) * 4;
       if constexpr (TRANS) {
 #pragma unroll

@@ -67,9 +67,6 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR, (D == 64 ? TTC_D64_WAVES : 1)) s
         ++nsolve;
         if (lds_solve<D, 7, false>(W, S, tid) && !info) info = nsolve;  // R is positive definite: no pivot search
         TTC_TOC(1)
-        HalfRegs<D> hA, hQ;
-        issue_half<D, TIn>(hA, Ap, tid);         // wanted after the product below
-        issue_half<D, TIn>(hQ, Qp, tid);
         zero_acc<D>(acc);
         gemm_acc<D>(acc, cB, WR, i, g);          // rows of G = B X
         load_aop_lds<D>(WR, cX, w, i, g);        // rows of X, for C_K
@@ -81,8 +78,11 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR, (D == 64 ? TTC_D64_WAVES : 1)) s
         __syncthreads();
         TTC_TOC(7)
         // ------------------------------------------------------------ phase A: A^{-1}, A^T, Q, C_K
-        commit_half<D, false>(WL, hA, tid);
-        commit_half<D, false>(WR, hQ, tid);
+        // (read here, one matrix after the other: started before the product above, the sixteen pieces a thread
+        // holds of each matrix do not fit the registers next to its operands and are spilled one by one, each
+        // read waited for on its own)
+        load_half<D, TIn, false>(WL, Ap, tid + opaque_zero());
+        load_half<D, TIn, false>(WR, Qp, tid + opaque_zero());
       }
       __syncthreads();
       symmetrise_half<D>(WR, tid);
