@@ -322,6 +322,12 @@ def bench_scan(args):
                                                               stream=stream), steps, max(args.warmup, 3))
     swall, sdev_s = timed(lambda: binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, b.R, b.x0, out=seq, stream=stream), 3, 1)
     assert int(out["info"].abs().max()) == 0
+    # every P_t and K_t by the up-sweep and the down-sweep (ttc_lqr_tv_scan_values), and the sequential roll-out's
+    # backward part for comparison is the sequential solve above
+    need = binding.load().ttc_lqr_tv_scan_values_workspace_bytes(binding.make_tv_problem(b.A, b.B, b.Q, b.R, b.x0))
+    wsv = torch.empty((need,), dtype=torch.uint8, device=dev)
+    vwall, vdev_s = timed(lambda: binding.ttc_lqr_tv_scan_values(b.A, b.B, b.Q, b.R, b.x0, workspace=wsv, stream=stream),
+                          max(3, steps // 4), 2)
     flops_pp = alg_flops_scan(d, T)
     achieved = flops_pp * n / dev_s / 1e12
     rounds = max(0, math.ceil(math.log2(T)))
@@ -344,6 +350,8 @@ def bench_scan(args):
                      "alg_GBps": (in_bytes + out_bytes) / dev_s / 1e9},
         "other_path": {"path": "sequential (ttc_lqr_solve_tv)", "value": n / swall, "unit": "problems/s",
                        "kernel_ms": sdev_s * 1e3},
+        "all_values": {"call": "ttc_lqr_tv_scan_values (every P_t and K_t: up-sweep, down-sweep, gains)",
+                       "kernel_ms": vdev_s * 1e3, "launches": 3 + 2 * rounds},
     }
     if not args.no_cpu:
         A, B, Q, R, x0 = b.numpy64()

@@ -199,6 +199,24 @@ size_t ttc_lqr_tv_scan_workspace_bytes(const ttc_lqr_tv_problem_t *problem);
 ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t *problem, const ttc_lqr_solution_t *solution,
                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Every value matrix and every gain of n time-heterogeneous problems, with the work spread over the horizon as
+ * well as over the problems (Prop. 3.1, Eq. "riccati" and Eq. "decode"; the factors of Thm 3.3 composed as in
+ * ttc_lqr_solve_tv_scan): after the rounds of pairwise compositions a second pass walks the same tree downwards,
+ * applying the composition kept at every right child to the value on its right, ceil(log2 T) rounds of one
+ * launch each, after which P_t is known for every t.  For small batches with long horizons whose roll-out or
+ * backward pass needs all of them.
+ *   P  (n, T, d, d) or NULL: P[:, k] = P_{k+1}, the value matrix after step k + 1 (P[:, T-1] = the terminal cost);
+ *                            symmetric parts.
+ *   K  (n, T, m, d) or NULL: K[:, s] = K_s, the gain of step s, u_s = K_s x_s (computed from P_{s+1} as n*T one-step
+ *                            problems; needs sA = T*tA, sB = T*tB, sR = T*tR, TTC_ERR_UNSUPPORTED otherwise).
+ * DEVICE pointers, 16-byte aligned, written; at least one of them.  workspace: DEVICE, 16-byte aligned,
+ * ttc_lqr_tv_scan_values_workspace_bytes(problem) bytes (TTC_ERR_WORKSPACE otherwise).  A breakdown (an R[s] that is
+ * not positive definite, a singular matrix in a composition) shows as NaN in the matrices it reaches.
+ * Launches up to 3 + 2 ceil(log2 T) kernels on hip_stream; allocates nothing; asynchronous. */
+size_t ttc_lqr_tv_scan_values_workspace_bytes(const ttc_lqr_tv_problem_t *problem);
+ttc_status_t ttc_lqr_tv_scan_values(const ttc_lqr_tv_problem_t *problem, float *P, float *K, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream);
+
 /* Structured, contextualised problems (Sec. 4, "Contextualization" and "Parameterization"; Sec. 3.3,
  * "Structured Parameterization"): the T steps of a problem are not stored anywhere; the kernel builds them
  * from per-problem vectors and two groups of r basis matrices shared by all problems.  With t = 1..T the

@@ -24,7 +24,8 @@ EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_solve_noalloc", 
            "ttc_lqr_rollout", "ttc_lqr_solve_tv", "ttc_lqr_rollout_tv",
            "ttc_lqr_tv_rollout_workspace_bytes", "ttc_lqr_solve_cxt", "ttc_lqr_rollout_cxt",
            "ttc_lqr_cxt_rollout_workspace_bytes", "ttc_lqr_solve_tv_scan",
-           "ttc_lqr_tv_scan_workspace_bytes", "ttc_lqr_backward", "ttc_lqr_backward_workspace_bytes",
+           "ttc_lqr_tv_scan_workspace_bytes", "ttc_lqr_tv_scan_values", "ttc_lqr_tv_scan_values_workspace_bytes",
+           "ttc_lqr_backward", "ttc_lqr_backward_workspace_bytes",
            "ttc_lqr_backward_tv", "ttc_lqr_backward_tv_workspace_bytes", "ttc_status_string", "ttc_version")
 
 
@@ -102,6 +103,10 @@ def load():
     lib.ttc_lqr_solve_tv_scan.restype = c_int
     lib.ttc_lqr_solve_tv_scan.argtypes = [ctypes.POINTER(TvProblem), ctypes.POINTER(Solution), c_void_p, c_size_t,
                                           c_void_p]
+    lib.ttc_lqr_tv_scan_values_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_tv_scan_values_workspace_bytes.argtypes = [ctypes.POINTER(TvProblem)]
+    lib.ttc_lqr_tv_scan_values.restype = c_int
+    lib.ttc_lqr_tv_scan_values.argtypes = [ctypes.POINTER(TvProblem), c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.ttc_lqr_solve_cxt.restype = c_int
     lib.ttc_lqr_solve_cxt.argtypes = [ctypes.POINTER(CxtProblem), ctypes.POINTER(Solution), c_void_p]
     lib.ttc_lqr_cxt_rollout_workspace_bytes.restype = c_size_t
@@ -294,6 +299,26 @@ def ttc_lqr_solve_tv(A, B, Q, R, x0, *, want_P0=True, want_K0=True, out=None, st
     out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
     sol = Solution(_ptr(out.get("P0")), _ptr(out.get("K0")), _ptr(out["u0"]), _ptr(out["value"]), _ptr(out["info"]))
     _check(lib.ttc_lqr_solve_tv(ctypes.byref(prob), ctypes.byref(sol), None, 0, _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_tv_scan_values(A, B, Q, R, x0, *, want_P=True, want_K=True, workspace=None, stream=None):
+    """P (n, T, d, d) with P[:, k] = P_{k+1} and K (n, T, m, d) with K[:, s] = K_s of n time-heterogeneous problems,
+    by the tree over the horizon (up-sweep and down-sweep)."""
+    lib = load()
+    prob = make_tv_problem(A, B, Q, R, x0)
+    n, d, m, T, dev = prob.n, prob.d, prob.m, prob.T, A.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = {}
+    if want_P:
+        out["P"] = torch.empty((n, T, d, d), **f32)
+    if want_K:
+        out["K"] = torch.empty((n, T, m, d), **f32)
+    need = lib.ttc_lqr_tv_scan_values_workspace_bytes(ctypes.byref(prob))
+    if workspace is None:
+        workspace = _scratch(need, dev, stream)
+    _check(lib.ttc_lqr_tv_scan_values(ctypes.byref(prob), _ptr(out.get("P")), _ptr(out.get("K")),
+                                      c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
     return out
 
 

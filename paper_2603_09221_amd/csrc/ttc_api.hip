@@ -188,6 +188,12 @@ static hipError_t run_scan_leaf(const ScanArgs& a, int d, bool bf16, dim3 grid, 
 static hipError_t run_scan_combine(const ScanArgs& a, int d, dim3 grid, hipStream_t st) {
   TTC_BY_D(d, launch_scan_combine<D>(a, grid, st))
 }
+static hipError_t run_scan_apply(const ScanArgs& a, int d, dim3 grid, hipStream_t st) {
+  TTC_BY_D(d, launch_scan_apply<D>(a, grid, st))
+}
+static hipError_t run_scan_gather(const ScanArgs& a, float* P, int d, dim3 grid, hipStream_t st) {
+  TTC_BY_D(d, launch_scan_gather<D>(a, P, grid, st))
+}
 static hipError_t run_backward(const BackwardArgs& a, int d, bool bf16, dim3 grid, hipStream_t st) {
   TTC_BY_D(d, launch_backward<D>(a, bf16, grid, st))
 }
@@ -427,6 +433,37 @@ size_t ttc_lqr_tv_scan_workspace_bytes(const ttc_lqr_tv_problem_t* q) {
   return (size_t)q->n * (size_t)q->T * 3 * (size_t)q->d * (size_t)q->d * sizeof(float);
 }
 
+// The elements of every step and the rounds of pairwise compositions (the up-sweep), common to
+// ttc_lqr_solve_tv_scan and ttc_lqr_tv_scan_values; fills sa for the launches that follow.
+static hipError_t scan_up_sweep(const ttc_lqr_tv_problem_t* q, ttc::ScanArgs& sa, void* workspace, hipStream_t st) {
+  ttc::TvArgs& a = sa.tv;
+  a.s.n = q->n;
+  a.s.T = q->T;
+  a.s.flags = 0;
+  a.s.ngroups = q->T;
+  a.s.growth_limit = 0.f;
+  a.s.A = q->A; a.s.B = q->B; a.s.Q = q->Q; a.s.R = q->R; a.s.QT = nullptr; a.s.x0 = q->x0;
+  a.s.sA = q->sA; a.s.sB = q->sB; a.s.sQ = q->sQ; a.s.sR = q->sR; a.s.sQT = 0; a.s.sx0 = q->sx0;
+  a.s.P0 = nullptr; a.s.K0 = nullptr; a.s.u0 = nullptr; a.s.value = nullptr; a.s.info = nullptr;
+  a.s.ws = nullptr;
+  a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
+  sa.ws = static_cast<float*>(workspace);
+  sa.stride = 0;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const int d = q->d;
+  const long long gb = ttc::grid_blocks(ttc::KIND_SCAN, d, bf16);
+  auto grid_for = [&](long long items) { return dim3((unsigned)(items < gb ? items : gb)); };
+  hipError_t e = ttc::run_scan_leaf(sa, d, bf16, grid_for(q->n * q->T), st);
+  if (e != hipSuccess) return e;
+  for (long long stride = 1; stride < q->T; stride *= 2) {
+    sa.stride = (int)stride;
+    const long long per = (q->T - stride + 2 * stride - 1) / (2 * stride);
+    e = ttc::run_scan_combine(sa, d, grid_for(q->n * per), st);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t* q, const ttc_lqr_solution_t* solution, void* workspace,
                                    size_t workspace_bytes, void* hip_stream) {
   const ttc_status_t stv = validate_tv(q);
@@ -438,43 +475,75 @@ ttc_status_t ttc_lqr_solve_tv_scan(const ttc_lqr_tv_problem_t* q, const ttc_lqr_
   if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_tv_scan_workspace_bytes(q))
     return TTC_ERR_WORKSPACE;
   ttc::ScanArgs sa;
-  ttc::TvArgs& a = sa.tv;
-  a.s.n = q->n;
-  a.s.T = q->T;
-  a.s.flags = 0;
-  a.s.ngroups = q->T;
-  a.s.growth_limit = 0.f;
-  a.s.A = q->A; a.s.B = q->B; a.s.Q = q->Q; a.s.R = q->R; a.s.QT = nullptr; a.s.x0 = q->x0;
-  a.s.sA = q->sA; a.s.sB = q->sB; a.s.sQ = q->sQ; a.s.sR = q->sR; a.s.sQT = 0; a.s.sx0 = q->sx0;
-  a.s.P0 = solution->P0; a.s.K0 = solution->K0; a.s.u0 = solution->u0; a.s.value = solution->value;
-  a.s.info = solution->info;
-  a.s.ws = nullptr;
-  a.tA = q->tA; a.tB = q->tB; a.tQ = q->tQ; a.tR = q->tR;
-  sa.ws = static_cast<float*>(workspace);
-  sa.stride = 0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (scan_up_sweep(q, sa, workspace, st) != hipSuccess) return TTC_ERR_DEVICE;
   const bool bf16 = q->in_dtype == TTC_BF16;
   const int d = q->d;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const long long gb = ttc::grid_blocks(ttc::KIND_SCAN, d, bf16);
-  auto grid_for = [&](long long items) { return dim3((unsigned)(items < gb ? items : gb)); };
-  hipError_t e = ttc::run_scan_leaf(sa, d, bf16, grid_for(q->n * q->T), st);
-  if (e != hipSuccess) return TTC_ERR_DEVICE;
-  for (long long stride = 1; stride < q->T; stride *= 2) {
-    sa.stride = (int)stride;
-    const long long per = (q->T - stride + 2 * stride - 1) / (2 * stride);
-    e = ttc::run_scan_combine(sa, d, grid_for(q->n * per), st);
-    if (e != hipSuccess) return TTC_ERR_DEVICE;
-  }
   // the step s = 0 as printed, from P_1 = H of the first element
-  ttc::TvArgs last = a;
+  ttc::TvArgs last = sa.tv;
+  last.s.P0 = solution->P0; last.s.K0 = solution->K0; last.s.u0 = solution->u0; last.s.value = solution->value;
+  last.s.info = solution->info;
   last.s.T = 1;
   last.s.ngroups = 1;
   last.PT = sa.ws + 2 * (size_t)d * d;
   last.sPT = (long long)q->T * 3 * d * d;
   const long long gt = ttc::grid_blocks(ttc::KIND_SOLVE_TV, d, bf16);
   const dim3 grid((unsigned)(q->n < gt ? q->n : gt));
-  e = ttc::run_tv(last, d, bf16, grid, st);
-  return e == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+  return ttc::run_tv(last, d, bf16, grid, st) == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
+}
+
+size_t ttc_lqr_tv_scan_values_workspace_bytes(const ttc_lqr_tv_problem_t* q) {
+  if (!q || q->n < 0 || q->T < 1 || !ttc::shape_supported_dm(q->d, q->m)) return 0;
+  // the elements, then one control vector per (problem, step) that the gains' launch writes and nobody reads
+  return ttc_lqr_tv_scan_workspace_bytes(q) + (size_t)q->n * (size_t)q->T * (size_t)q->m * sizeof(float);
+}
+
+ttc_status_t ttc_lqr_tv_scan_values(const ttc_lqr_tv_problem_t* q, float* P, float* K, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t stv = validate_tv(q);
+  if (stv != TTC_OK) return stv;
+  if (!P && !K) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(P, 16) || !ttc::aligned_ptr(K, 16)) return TTC_ERR_INVALID_ARG;
+  // the gains are computed as n*T one-step problems, which needs the steps of a problem to follow each other at the
+  // problems' own spacing
+  if (K && q->T > 1 && (q->sA != q->T * q->tA || q->sB != q->T * q->tB || q->sR != q->T * q->tR)) return TTC_ERR_UNSUPPORTED;
+  if (q->n == 0) return TTC_OK;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_tv_scan_values_workspace_bytes(q))
+    return TTC_ERR_WORKSPACE;
+  ttc::ScanArgs sa;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (scan_up_sweep(q, sa, workspace, st) != hipSuccess) return TTC_ERR_DEVICE;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const int d = q->d;
+  const long long gb = ttc::grid_blocks(ttc::KIND_SCAN, d, bf16);
+  auto grid_for = [&](long long items) { return dim3((unsigned)(items < gb ? items : gb)); };
+  long long top = 1;
+  while (top * 2 < q->T) top *= 2;
+  for (long long stride = top; stride >= 1; stride /= 2) {  // the down-sweep
+    sa.stride = (int)stride;
+    if (stride >= q->T) continue;  // T = 1: a single, constant element
+    const long long per = (q->T - stride + 2 * stride - 1) / (2 * stride);
+    if (ttc::run_scan_apply(sa, d, grid_for(q->n * per), st) != hipSuccess) return TTC_ERR_DEVICE;
+  }
+  if (P && ttc::run_scan_gather(sa, P, d, grid_for(q->n * q->T), st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (K) {
+    // step s of problem p, from P_{s+1} = the H slot of element s: K_s = -S_s^{-1} B_s^T P_{s+1} A_s (Eq. "decode")
+    ttc::TvArgs g = sa.tv;
+    g.s.n = q->n * q->T;
+    g.s.T = 1;
+    g.s.ngroups = 1;
+    g.s.sA = q->tA; g.s.sB = q->tB; g.s.sQ = q->tQ; g.s.sR = q->tR;
+    if (q->T == 1) { g.s.sA = q->sA; g.s.sB = q->sB; g.s.sQ = q->sQ; g.s.sR = q->sR; }
+    g.s.sx0 = 0;
+    g.s.K0 = K;
+    g.s.u0 = reinterpret_cast<float*>(static_cast<char*>(workspace) + ttc_lqr_tv_scan_workspace_bytes(q));
+    g.PT = sa.ws + 2 * (size_t)d * d;
+    g.sPT = 3LL * d * d;
+    const long long gt = ttc::grid_blocks(ttc::KIND_SOLVE_TV, d, bf16);
+    const dim3 grid((unsigned)(g.s.n < gt ? g.s.n : gt));
+    if (ttc::run_tv(g, d, bf16, grid, st) != hipSuccess) return TTC_ERR_DEVICE;
+  }
+  return TTC_OK;
 }
 
 static ttc_status_t validate_cxt(const ttc_lqr_cxt_problem_t* q) {

@@ -22,6 +22,8 @@ template <int D> hipError_t launch_rollout_tv(const TvRolloutArgs& a, bool bf16,
 template <int D> int occupancy_rollout_tv(bool bf16);
 template <int D> hipError_t launch_scan_leaf(const ScanArgs& a, bool bf16, dim3 grid, hipStream_t st);
 template <int D> hipError_t launch_scan_combine(const ScanArgs& a, dim3 grid, hipStream_t st);
+template <int D> hipError_t launch_scan_apply(const ScanArgs& a, dim3 grid, hipStream_t st);
+template <int D> hipError_t launch_scan_gather(const ScanArgs& a, float* P, dim3 grid, hipStream_t st);
 template <int D> int occupancy_scan();
 
 template <int D> hipError_t launch_backward(const BackwardArgs& a, bool bf16, dim3 grid, hipStream_t st);

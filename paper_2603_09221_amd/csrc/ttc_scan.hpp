@@ -177,4 +177,58 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) scan_combine_kernel(const ScanAr
   }
 }
 
+
+// Down-sweep of the tree: after the rounds of scan_combine_kernel element j + st (st the round's stride, j a
+// multiple of 2 st) still holds the composition of the steps [j + st, j + 2 st), and the value entering it from
+// the right, P after the step of element j + 2 st, is final (it was produced one level up, or that element's range
+// reaches the terminal cost and its map is constant).  One level of the down-sweep applies every such element to
+// the value on its right, P <- H_e + A_e^T (I + P G_e)^{-1} P A_e, and leaves the result in the element's H slot;
+// levels run from the largest stride down to 1, after which the H slot of element k holds P after step k + 1,
+// P_{k+1} in the paper's numbering, for every k.  Elements whose range reaches the terminal cost are constant maps
+// (A_e = G_e = 0): their H is final as it stands.  A round writes only H slots of odd multiples of st and reads
+// only those of even multiples.
+template <int D>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) scan_apply_kernel(const ScanArgs a) {
+  using C = Cfg<D>;
+  __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
+  __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
+  const SolveArgs& p = a.tv.s;
+  float* const WR = W + D;
+  const int st = a.stride;
+  const long long per = (p.T - st + 2LL * st - 1) / (2LL * st);  // elements j + st per problem in this round
+  const long long items = p.n * per;
+  PhaseTimers tm;
+  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+    const long long prob = item / per;
+    const long long j = (item % per) * 2 * st;
+    if (j + 2 * st >= p.T) continue;  // the element's range reaches the terminal cost: its H is P already (uniform)
+    float* const e = a.ws + (prob * p.T + j + st) * 3 * D * D;
+    const float* const gP = a.ws + ((prob * p.T + j + 2 * st) * 3 + 2) * D * D;
+    floatx4 acc[C::RB][C::NT];
+    float rAT[C::RB][C::KS];
+    const int flag = mobius_solve<D, float>(W, S, e, e + D * D, gP, rAT, tid, tm);  // right half: (I + P G)^{-1} P A
+    load_rows_global<D>(e + 2 * D * D, acc, w, i, g);
+    gemm_acc<D>(acc, rAT, WR, i, g);
+    if (flag) poison<D>(acc);
+    write_rows_global<D>(e + 2 * D * D, acc, w, i, g);
+    __syncthreads();
+  }
+}
+
+// the H slots of all elements, P_1 .. P_T of every problem, as one (n, T, d, d) array (symmetric parts)
+template <int D>
+__global__ void __launch_bounds__(Cfg<D>::NTHR) scan_gather_kernel(const ScanArgs a, float* __restrict__ P) {
+  using C = Cfg<D>;
+  const long long items = a.tv.s.n * a.tv.s.T;
+  for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+    const float* src = a.ws + (item * 3 + 2) * D * D;
+    float* dst = P + item * D * D;
+    for (int idx = threadIdx.x; idx < D * D; idx += C::NTHR) {
+      const int r = idx / D, c = idx % D;
+      dst[idx] = 0.5f * (src[idx] + src[c * D + r]);
+    }
+  }
+}
+
 }  // namespace ttc

@@ -69,3 +69,44 @@ def test_workspace_is_checked_and_empty_batches_pass():
     e0 = synth.make_tv_batch(0, 16, 16, 6, seed=1, device=DEV)
     out = binding.ttc_lqr_solve_tv_scan(e0.A, e0.B, e0.Q, e0.R, e0.x0)
     assert out["u0"].shape == (0, 16)
+
+
+def check_values(batch, tol):
+    """ttc_lqr_tv_scan_values: every P_t (t = 1..T) and every gain K_s (s = 0..T-1) against the oracle's recursion."""
+    out = binding.ttc_lqr_tv_scan_values(batch.A, batch.B, batch.Q, batch.R, batch.x0)
+    torch.cuda.synchronize()
+    P_ref, K_ref = lqr_oracle.riccati_value_matrices_tv(*batch.numpy64()[:4])
+    n, T = batch.A.shape[0], batch.A.shape[1]
+    P = out["P"].cpu().numpy()
+    K = out["K"].cpu().numpy()
+    eP = max(float(rel_err(P[:, k], P_ref[k + 1]).max()) for k in range(T))
+    eK = max(float(rel_err(K[:, s], K_ref[s]).max()) for s in range(T))
+    print(f"P {eP:.2e} K {eK:.2e}")
+    assert eP <= tol and eK <= tol, (eP, eK)
+    return out
+
+
+@pytest.mark.parametrize("d,T,n", [(16, 1, 3), (16, 2, 5), (16, 3, 4), (16, 7, 9), (16, 64, 33), (16, 300, 3),
+                                    (32, 20, 6), (64, 33, 5), (128, 5, 2), (128, 16, 3)])
+def test_all_value_matrices_and_gains(d, T, n):
+    check_values(synth.make_tv_batch(n, d, d, T, seed=2 * d + T, device=DEV), TOL_F32)
+
+
+def test_all_value_matrices_long_horizon_small_batch():
+    check_values(synth.make_tv_batch(16, 16, 16, 2048, seed=6, device=DEV), TOL_F32)
+
+
+def test_values_bf16_inputs_and_single_outputs():
+    b = synth.make_tv_batch(6, 16, 16, 13, seed=4, device=DEV, dtype="bf16")
+    check_values(b, TOL_BF16)
+    b = synth.make_tv_batch(5, 32, 32, 9, seed=5, device=DEV)
+    both = binding.ttc_lqr_tv_scan_values(b.A, b.B, b.Q, b.R, b.x0)
+    onlyP = binding.ttc_lqr_tv_scan_values(b.A, b.B, b.Q, b.R, b.x0, want_K=False)
+    onlyK = binding.ttc_lqr_tv_scan_values(b.A, b.B, b.Q, b.R, b.x0, want_P=False)
+    torch.cuda.synchronize()
+    assert "K" not in onlyP and "P" not in onlyK
+    assert torch.equal(onlyP["P"], both["P"]) and torch.equal(onlyK["K"], both["K"])
+    # the first gain and the first value matrix agree with the reduction's outputs
+    red = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, b.R, b.x0)
+    torch.cuda.synchronize()
+    assert float(rel_err(both["K"][:, 0].cpu().numpy(), red["K0"].cpu().numpy()).max()) <= 1e-6
