@@ -212,3 +212,47 @@ def make_contextual_batch(n: int, d: int, r: int, T: int, seed: int = 0, device=
     x0 = rn(n, d)
     c = lambda t: t.to(store).contiguous()
     return ContextualBatch(c(sA), c(sB), c(sQ), c(sQf), c(rinv), c(lgA), c(lgB), c(lgQ), c(Bb), c(Qb), c(x0), T)
+
+
+BLOCK_WEIGHTS = ("ln_in_gain", "ln_in_offset", "W_in", "b_in", "W_head", "b_head", "W_shared", "b_shared", "Bbasis", "Qc",
+                 "ln_out_gain", "ln_out_offset", "W_out", "b_out")
+
+
+def make_block_weights(C: int, H: int, d: int, r: int, seed: int = 0, device="cpu") -> dict:
+    """Random weights of one TTC block (Sec. 4, "Hybrid with Memory Layers"): no trained weights exist, so the draws
+    are scaled to give the solver inputs the ranges of make_contextual_batch.  float32, in the order of BLOCK_WEIGHTS:
+        ln_in_gain = 1 + 0.1 N^C, ln_in_offset = 0.1 N^C;  W_in = N^{Hd x C} / sqrt(C), b_in = 0.1 N^{Hd};
+        W_head (H, 5d + r, d): rows of s_A 0.1 N / sqrt(d); of s_R, s_Qf N / sqrt(d); of the three s_Gamma 0.5 N / sqrt(d);
+        b_head: 0 for s_A, 0.1 N for s_R and s_Qf, -1 + 0.1 N for the three s_Gamma;
+        W_shared (2r, d): rows of s_B N / sqrt(d r), of s_Q N / sqrt(d);  b_shared = 0.1 N^{2r};
+        Bbasis = N^{r x d x d} / sqrt(d);  Qc = N^{r x d x d} / sqrt(r);
+        ln_out_gain = 1 + 0.1 N^{Hd}, ln_out_offset = 0.1 N^{Hd};  W_out = N^{C x Hd} / sqrt(Hd), b_out = 0.1 N^C."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    rn = lambda *s: torch.randn(*s, generator=gen, device=dev, dtype=torch.float32)
+    w = {}
+    w["ln_in_gain"], w["ln_in_offset"] = 1 + 0.1 * rn(C), 0.1 * rn(C)
+    w["W_in"], w["b_in"] = rn(H * d, C) / C ** 0.5, 0.1 * rn(H * d)
+    Wh, bh = rn(H, 5 * d + r, d) / d ** 0.5, 0.1 * rn(H, 5 * d + r)
+    Wh[:, 0:d] *= 0.1
+    bh[:, 0:d] = 0
+    Wh[:, 2 * d:5 * d] *= 0.5
+    bh[:, 2 * d:5 * d] -= 1
+    w["W_head"], w["b_head"] = Wh, bh
+    Ws = rn(2 * r, d) / d ** 0.5
+    Ws[0:r] /= r ** 0.5
+    w["W_shared"], w["b_shared"] = Ws, 0.1 * rn(2 * r)
+    w["Bbasis"], w["Qc"] = rn(r, d, d) / d ** 0.5, rn(r, d, d) / r ** 0.5
+    w["ln_out_gain"], w["ln_out_offset"] = 1 + 0.1 * rn(H * d), 0.1 * rn(H * d)
+    w["W_out"], w["b_out"] = rn(C, H * d) / (H * d) ** 0.5, 0.1 * rn(C)
+    return {k: w[k].contiguous() for k in BLOCK_WEIGHTS}
+
+
+def make_block_input(n_tokens: int, C: int, seed: int = 0, device="cpu") -> torch.Tensor:
+    """Token features standing in for the attention output: 0.5 + 2 N(0,1)^{n x C} (a mean away from zero, so that a
+    layer normalisation that forgot to centre would show), float32."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed + 7919)
+    return (0.5 + 2 * torch.randn(n_tokens, C, generator=gen, device=dev, dtype=torch.float32)).contiguous()
