@@ -296,6 +296,46 @@ ttc_status_t ttc_lqr_backward_tv(const ttc_lqr_tv_problem_t *problem, const floa
                                  const ttc_lqr_grads_t *grads, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
 
+/* The whole Test-Time Control block for n_tokens token features, each on its own (Sec. 4, "Hybrid with Memory
+ * Layers", "Multi-Head Structure", "Contextualization", "Parameterization"), float32:
+ *     h_0   = W_in LN(x_in) + b_in, split into H heads of d = 16 numbers;
+ *     per head, from its 16 numbers v:  sA = W_A v + b_A,  rinv = softplus(W_R v + b_R),
+ *         lgA, lgB, lgQ = softplus(W_g. v + b_g.),  sQf = softplus(W_Qf v + b_Qf)   (maps of the head's own),
+ *         sB = W_B v + b_B,  sQ = softplus(W_Q v + b_Q)                              (maps shared by all heads),
+ *         Q^(i) = Qc^(i) Qc^(i)^T / sqrt(d);
+ *     o     = side by side, the u_1^* of the heads' structured problems (ttc_lqr_cxt_problem_t with these vectors,
+ *             Bbasis, Q^(i), x0 = the head's part of h_0, horizon T);
+ *     x_out = x_in + W_out LN(o) + b_out.
+ * LN normalises over the last axis (biased variance, eps under the root) and applies a gain and an offset per entry.
+ * The structured steps are built in the solve kernel, never stored; the per-problem vectors (80 + 3r floats) are.
+ * All weights are DEVICE pointers, float32, contiguous, row-major, borrowed and read-only, 16-byte aligned:
+ *   ln_in_gain, ln_in_offset (C);  W_in (H*16, C), b_in (H*16);
+ *   W_head (H, 80 + r, 16), b_head (H, 80 + r): rows sA, rinv, lgA, lgB, lgQ (16 each), then sQf (r);
+ *   W_shared (2r, 16), b_shared (2r): rows sB (r), then sQ (r);
+ *   Bbasis, Qc (r, 16, 16);  ln_out_gain, ln_out_offset (H*16);  W_out (C, H*16), b_out (C).
+ * d other than 16, r above 64 or not a multiple of 4, C not a multiple of 4: TTC_ERR_UNSUPPORTED. */
+typedef struct {
+  int64_t n_tokens;
+  int32_t C;     /* width of a token feature */
+  int32_t H;     /* heads */
+  int32_t d;     /* state and control size of a head: 16 */
+  int32_t r;     /* basis matrices per group */
+  int32_t T;     /* horizon, >= 1 */
+  int32_t flags; /* 0 */
+  float eps;     /* of both layer normalisations, > 0 */
+  const float *ln_in_gain, *ln_in_offset, *W_in, *b_in, *W_head, *b_head, *W_shared, *b_shared, *Bbasis, *Qc,
+      *ln_out_gain, *ln_out_offset, *W_out, *b_out;
+} ttc_block_t;
+
+/* x_in (n_tokens, C) DEVICE, read; x_out (n_tokens, C) DEVICE, written, may be x_in itself.  Optional DEVICE outputs
+ * (NULL to skip): h0 (n_tokens, H*16); o (n_tokens, H*16); info (n_tokens*H), as ttc_lqr_solve_cxt reports it for
+ * the problem of token t, head h at [t*H + h] (a problem that broke down gives NaN in its token's x_out).
+ * workspace: DEVICE, 16-byte aligned, ttc_block_workspace_bytes(block) bytes (TTC_ERR_WORKSPACE otherwise; the size
+ * depends on n_tokens, H, r only).  Seven launches on hip_stream; allocates nothing; asynchronous. */
+size_t ttc_block_workspace_bytes(const ttc_block_t *block);
+ttc_status_t ttc_block_forward(const ttc_block_t *block, const float *x_in, float *x_out, float *h0, float *o,
+                               int32_t *info, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *ttc_status_string(ttc_status_t status);
 

@@ -26,7 +26,8 @@ EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_solve_noalloc", 
            "ttc_lqr_cxt_rollout_workspace_bytes", "ttc_lqr_solve_tv_scan",
            "ttc_lqr_tv_scan_workspace_bytes", "ttc_lqr_tv_scan_values", "ttc_lqr_tv_scan_values_workspace_bytes",
            "ttc_lqr_backward", "ttc_lqr_backward_workspace_bytes",
-           "ttc_lqr_backward_tv", "ttc_lqr_backward_tv_workspace_bytes", "ttc_status_string", "ttc_version")
+           "ttc_lqr_backward_tv", "ttc_lqr_backward_tv_workspace_bytes", "ttc_block_workspace_bytes", "ttc_block_forward",
+           "ttc_status_string", "ttc_version")
 
 
 class Problem(ctypes.Structure):
@@ -52,6 +53,15 @@ class CxtProblem(ctypes.Structure):
                 ("sA", c_void_p), ("sB", c_void_p), ("sQ", c_void_p), ("sQf", c_void_p), ("rinv", c_void_p),
                 ("lgA", c_void_p), ("lgB", c_void_p), ("lgQ", c_void_p), ("x0", c_void_p),
                 ("Bbasis", c_void_p), ("Qbasis", c_void_p)]
+
+
+BLOCK_WEIGHTS = ("ln_in_gain", "ln_in_offset", "W_in", "b_in", "W_head", "b_head", "W_shared", "b_shared", "Bbasis", "Qc",
+                 "ln_out_gain", "ln_out_offset", "W_out", "b_out")
+
+
+class Block(ctypes.Structure):
+    _fields_ = [("n_tokens", c_int64), ("C", c_int32), ("H", c_int32), ("d", c_int32), ("r", c_int32), ("T", c_int32),
+                ("flags", c_int32), ("eps", ctypes.c_float)] + [(k, c_void_p) for k in BLOCK_WEIGHTS]
 
 
 class Solution(ctypes.Structure):
@@ -124,6 +134,11 @@ def load():
     lib.ttc_lqr_backward_tv.restype = c_int
     lib.ttc_lqr_backward_tv.argtypes = [ctypes.POINTER(TvProblem), c_void_p, ctypes.POINTER(Grads), c_void_p, c_size_t,
                                         c_void_p]
+    lib.ttc_block_workspace_bytes.restype = c_size_t
+    lib.ttc_block_workspace_bytes.argtypes = [ctypes.POINTER(Block)]
+    lib.ttc_block_forward.restype = c_int
+    lib.ttc_block_forward.argtypes = [ctypes.POINTER(Block), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                      c_size_t, c_void_p]
     lib.ttc_status_string.restype = c_char_p
     lib.ttc_status_string.argtypes = [c_int]
     lib.ttc_version.restype = c_int
@@ -463,4 +478,50 @@ def ttc_lqr_backward_tv(A, B, Q, R, x0, grad_u0, *, out=None, workspace=None, st
     gr = _grads_struct(out)
     _check(lib.ttc_lqr_backward_tv(ctypes.byref(prob), c_void_p(grad_u0.data_ptr()), ctypes.byref(gr),
                                    c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
+    return out
+
+
+def make_block(weights, n_tokens, T, eps=1e-5) -> Block:
+    """Descriptor of a TTC block from a dict of float32 device tensors (keys BLOCK_WEIGHTS); shapes are checked here,
+    values never touched."""
+    w = weights
+    for k in BLOCK_WEIGHTS:
+        if w[k].dtype != torch.float32 or not w[k].is_contiguous():
+            raise ValueError("block weight %s must be a contiguous float32 tensor" % k)
+    r, d = int(w["Bbasis"].shape[0]), int(w["Bbasis"].shape[-1])
+    HD, C = (int(v) for v in w["W_in"].shape)
+    H = HD // d
+    want = {"ln_in_gain": (C,), "ln_in_offset": (C,), "W_in": (H * d, C), "b_in": (H * d,),
+            "W_head": (H, 5 * d + r, d), "b_head": (H, 5 * d + r), "W_shared": (2 * r, d), "b_shared": (2 * r,),
+            "Bbasis": (r, d, d), "Qc": (r, d, d), "ln_out_gain": (H * d,), "ln_out_offset": (H * d,),
+            "W_out": (C, H * d), "b_out": (C,)}
+    for k, shape in want.items():
+        if tuple(w[k].shape) != shape:
+            raise ValueError("block weight %s has shape %s, expected %s" % (k, tuple(w[k].shape), shape))
+    return Block(n_tokens, C, H, d, r, T, 0, eps, *(w[k].data_ptr() for k in BLOCK_WEIGHTS))
+
+
+def ttc_block_forward(x_in, weights, T, *, eps=1e-5, want_h0=False, want_o=False, out=None, workspace=None, stream=None):
+    """x_out (n_tokens, C) of the whole TTC block for token features x_in (n_tokens, C) float32 on the device; info
+    (n_tokens, H); optionally the intermediate h0 and o (n_tokens, H*d)."""
+    lib = load()
+    if x_in.dtype != torch.float32 or not x_in.is_contiguous() or x_in.dim() != 2:
+        raise ValueError("x_in must be a contiguous (n_tokens, C) float32 tensor")
+    n, dev = int(x_in.shape[0]), x_in.device
+    blk = make_block(weights, n, T, eps)
+    if int(x_in.shape[1]) != blk.C:
+        raise ValueError("x_in has %d features, the block expects %d" % (x_in.shape[1], blk.C))
+    out = dict(out or {})
+    f32 = dict(dtype=torch.float32, device=dev)
+    out.setdefault("x_out", torch.empty((n, blk.C), **f32))
+    if want_h0:
+        out.setdefault("h0", torch.empty((n, blk.H * blk.d), **f32))
+    if want_o:
+        out.setdefault("o", torch.empty((n, blk.H * blk.d), **f32))
+    out.setdefault("info", torch.empty((n, blk.H), dtype=torch.int32, device=dev))
+    need = lib.ttc_block_workspace_bytes(ctypes.byref(blk))
+    if workspace is None:
+        workspace = _scratch(need, dev, stream)
+    _check(lib.ttc_block_forward(ctypes.byref(blk), _ptr(x_in), _ptr(out["x_out"]), _ptr(out.get("h0")), _ptr(out.get("o")),
+                                 _ptr(out["info"]), c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
     return out

@@ -33,7 +33,8 @@ UNITS = [("ttc_api.hip", None),
          ("k_backward.hip", (16, 32, 64, 128)),
          ("k_small.hip", None),
          ("k_tv_small.hip", None),
-         ("k_cxt.hip", None)]
+         ("k_cxt.hip", None),
+         ("k_block.hip", None)]
 
 _NOISE = "is not a recognized feature for this target"
 

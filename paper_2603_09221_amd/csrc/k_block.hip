@@ -1,0 +1,25 @@
+// ln_stats_kernel, gemm_ln_kernel, cxt_maps_kernel, qbasis_kernel (ttc_block_forward).
+#include "ttc_block.hpp"
+#include "ttc_launch.hpp"
+
+namespace ttc {
+hipError_t launch_ln_stats(const LnStatsArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(ln_stats_kernel, dim3((unsigned)((a.M + 3) / 4)), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_gemm_ln(const GemmLnArgs& a, hipStream_t st) {
+  const long long total = ((a.M + GEMM_BM - 1) / GEMM_BM) * ((a.N + GEMM_BN - 1) / GEMM_BN);
+  const long long per = (total + 7) / 8;
+  hipLaunchKernelGGL(gemm_ln_kernel, dim3((unsigned)(8 * per)), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_cxt_maps(const CxtMapsArgs& a, int blocks, hipStream_t st) {
+  const int nout = 80 + 3 * a.r;
+  hipLaunchKernelGGL(cxt_maps_kernel, dim3((unsigned)blocks), dim3((unsigned)(64 * ((nout + 63) / 64))), 0, st, a);
+  return hipGetLastError();
+}
+hipError_t launch_qbasis(const float* Qc, float* Qb, int r, hipStream_t st) {
+  hipLaunchKernelGGL(qbasis_kernel, dim3((unsigned)r), dim3(256), 0, st, Qc, Qb);
+  return hipGetLastError();
+}
+}  // namespace ttc

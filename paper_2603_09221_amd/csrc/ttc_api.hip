@@ -601,6 +601,99 @@ ttc_status_t ttc_lqr_solve_cxt(const ttc_lqr_cxt_problem_t* q, const ttc_lqr_sol
   return run_cxt(a, q->in_dtype == TTC_BF16, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? TTC_OK : TTC_ERR_DEVICE;
 }
 
+// ---- the whole block around the structured solver ------------------------------------------------------------
+namespace {
+struct BlockLayout {  // offsets into the workspace, in floats, each a multiple of 64
+  size_t stats_in, h0, sA, rinv, lgA, lgB, lgQ, sQf, sB, sQ, qbasis, o, stats_out, info, total;
+};
+size_t round64(size_t x) { return (x + 63) / 64 * 64; }
+BlockLayout block_layout(long long M, int H, int r) {
+  BlockLayout L;
+  const size_t P = (size_t)M * H;
+  size_t at = 0;
+  auto take = [&](size_t nfloats) { const size_t here = at; at += round64(nfloats); return here; };
+  L.stats_in = take(2 * (size_t)M);
+  L.h0 = take(P * 16);
+  L.sA = take(P * 16); L.rinv = take(P * 16); L.lgA = take(P * 16); L.lgB = take(P * 16); L.lgQ = take(P * 16);
+  L.sQf = take(P * r); L.sB = take(P * r); L.sQ = take(P * r);
+  L.qbasis = take((size_t)r * 256);
+  L.o = take(P * 16);
+  L.stats_out = take(2 * (size_t)M);
+  L.info = take(P);
+  L.total = at;
+  return L;
+}
+ttc_status_t validate_block(const ttc_block_t* b) {
+  if (!b || b->n_tokens < 0 || b->C < 1 || b->H < 1 || b->d < 1 || b->r < 1 || b->T < 1 || b->flags != 0)
+    return TTC_ERR_INVALID_ARG;
+  if (!(b->eps > 0.f)) return TTC_ERR_INVALID_ARG;
+  if (b->d != 16 || b->r > ttc::CXT_RMAX || b->r % 4 != 0 || b->C % 4 != 0) return TTC_ERR_UNSUPPORTED;
+  if ((long long)b->n_tokens * b->H > (1LL << 40)) return TTC_ERR_INVALID_ARG;
+  return TTC_OK;
+}
+}  // namespace
+
+size_t ttc_block_workspace_bytes(const ttc_block_t* b) {
+  if (validate_block(b) != TTC_OK) return 0;
+  return block_layout(b->n_tokens, b->H, b->r).total * sizeof(float);
+}
+
+ttc_status_t ttc_block_forward(const ttc_block_t* b, const float* x_in, float* x_out, float* h0, float* o, int32_t* info,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t sv = validate_block(b);
+  if (sv != TTC_OK) return sv;
+  if (b->n_tokens == 0) return TTC_OK;
+  const void* ptrs[] = {b->ln_in_gain, b->ln_in_offset, b->W_in, b->b_in, b->W_head, b->b_head, b->W_shared, b->b_shared,
+                        b->Bbasis, b->Qc, b->ln_out_gain, b->ln_out_offset, b->W_out, b->b_out, x_in, x_out};
+  for (const void* ptr : ptrs)
+    if (!ptr || !ttc::aligned_ptr(ptr, 16)) return TTC_ERR_INVALID_ARG;
+  if (!ttc::aligned_ptr(h0, 16) || !ttc::aligned_ptr(o, 16)) return TTC_ERR_INVALID_ARG;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_block_workspace_bytes(b))
+    return TTC_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const long long M = b->n_tokens;
+  const int H = b->H, r = b->r, HD = 16 * b->H;
+  const BlockLayout L = block_layout(M, H, r);
+  float* ws = static_cast<float*>(workspace);
+  float* const h0p = h0 ? h0 : ws + L.h0;
+  float* const op = o ? o : ws + L.o;
+
+  // h_0 = W_in LN(x_in) + b_in
+  ttc::LnStatsArgs s1{x_in, ws + L.stats_in, M, b->C, b->eps};
+  if (ttc::launch_ln_stats(s1, st) != hipSuccess) return TTC_ERR_DEVICE;
+  ttc::GemmLnArgs g1{x_in, ws + L.stats_in, b->ln_in_gain, b->ln_in_offset, b->W_in, b->b_in, nullptr, h0p, M, HD, b->C};
+  if (ttc::launch_gemm_ln(g1, st) != hipSuccess) return TTC_ERR_DEVICE;
+  // the contextualisation maps and the Q basis
+  ttc::CxtMapsArgs c;
+  c.H0 = h0p;
+  c.W_head = b->W_head; c.b_head = b->b_head; c.W_shared = b->W_shared; c.b_shared = b->b_shared;
+  c.sA = ws + L.sA; c.rinv = ws + L.rinv; c.lgA = ws + L.lgA; c.lgB = ws + L.lgB; c.lgQ = ws + L.lgQ;
+  c.sQf = ws + L.sQf; c.sB = ws + L.sB; c.sQ = ws + L.sQ;
+  c.M = M; c.H = H; c.r = r;
+  long long chunks = (8LL * ttc::cu_count() + H - 1) / H;  // about eight workgroups per compute unit
+  chunks = chunks < 1 ? 1 : chunks > M ? M : chunks;
+  c.tokens_per_block = (int)((M + chunks - 1) / chunks);
+  chunks = (M + c.tokens_per_block - 1) / c.tokens_per_block;
+  if (ttc::launch_cxt_maps(c, (int)(chunks * H), st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (ttc::launch_qbasis(b->Qc, ws + L.qbasis, r, st) != hipSuccess) return TTC_ERR_DEVICE;
+  // o = the heads' first optimal controls
+  ttc_lqr_cxt_problem_t q;
+  q.n = M * H; q.d = 16; q.r = r; q.T = b->T; q.in_dtype = TTC_F32; q.flags = 0;
+  q.sA = c.sA; q.sB = c.sB; q.sQ = c.sQ; q.sQf = c.sQf; q.rinv = c.rinv; q.lgA = c.lgA; q.lgB = c.lgB; q.lgQ = c.lgQ;
+  q.x0 = h0p; q.Bbasis = b->Bbasis; q.Qbasis = ws + L.qbasis;
+  ttc::CxtArgs a;
+  fill_cxt_args(a, &q);
+  a.s.u0 = op;
+  a.s.info = info ? info : reinterpret_cast<int32_t*>(ws + L.info);
+  if (run_cxt(a, false, st) != hipSuccess) return TTC_ERR_DEVICE;
+  // x_out = x_in + W_out LN(o) + b_out
+  ttc::LnStatsArgs s2{op, ws + L.stats_out, M, HD, b->eps};
+  if (ttc::launch_ln_stats(s2, st) != hipSuccess) return TTC_ERR_DEVICE;
+  ttc::GemmLnArgs g2{op, ws + L.stats_out, b->ln_out_gain, b->ln_out_offset, b->W_out, b->b_out, x_in, x_out, M, b->C, HD};
+  if (ttc::launch_gemm_ln(g2, st) != hipSuccess) return TTC_ERR_DEVICE;
+  return TTC_OK;
+}
+
 size_t ttc_lqr_cxt_rollout_workspace_bytes(const ttc_lqr_cxt_problem_t* q) {
   if (!q || q->n < 0 || q->T < 1 || q->d != 16) return 0;
   // per problem: Bbar, Qbar, Q_T and the T gains (256 floats each), then one breakdown flag per problem

@@ -83,4 +83,39 @@ struct CxtRolloutArgs {
   float *U, *X, *cost;
 };
 
+// ---- the block around the structured solver (ttc_block.hpp)
+struct LnStatsArgs {
+  const float* X;  // (M, L) row-major
+  float* stats;    // (M, 2): mean, 1 / sqrt(biased variance + eps)
+  long long M;
+  int L;           // multiple of 4
+  float eps;
+};
+
+struct GemmLnArgs {
+  const float* X;       // (M, K) row-major, rows normalised on load with stats, gain, offset
+  const float* stats;   // (M, 2)
+  const float* gain;    // (K)
+  const float* offset;  // (K)
+  const float* W;       // (N, K) row-major
+  const float* bias;    // (N) or NULL
+  const float* Res;     // (M, N) or NULL: added to the result (may be Y itself)
+  float* Y;             // (M, N)
+  long long M;
+  int N, K;             // multiples of 4
+};
+
+struct CxtMapsArgs {
+  const float* H0;        // (M, H, 16)
+  const float* W_head;    // (H, 80 + r, 16): rows sA, rinv, lgA, lgB, lgQ (16 each), sQf (r)
+  const float* b_head;    // (H, 80 + r)
+  const float* W_shared;  // (2r, 16): rows sB (r), sQ (r)
+  const float* b_shared;  // (2r)
+  float *sA, *rinv, *lgA, *lgB, *lgQ;  // (M*H, 16)
+  float *sQf, *sB, *sQ;                // (M*H, r)
+  long long M;
+  int H, r;
+  int tokens_per_block;
+};
+
 }  // namespace ttc

@@ -38,6 +38,12 @@ hipError_t launch_cxt(const CxtArgs& a, bool bf16, int ppw, dim3 grid, hipStream
 int occupancy_cxt(bool bf16);
 hipError_t launch_rollout_cxt_forward(const CxtRolloutArgs& a, bool bf16, dim3 grid, hipStream_t st);
 
+// the block around the structured solver (ttc_block.hpp)
+hipError_t launch_ln_stats(const LnStatsArgs& a, hipStream_t st);
+hipError_t launch_gemm_ln(const GemmLnArgs& a, hipStream_t st);
+hipError_t launch_cxt_maps(const CxtMapsArgs& a, int blocks, hipStream_t st);
+hipError_t launch_qbasis(const float* Qc, float* Qb, int r, hipStream_t st);
+
 template <typename K>
 inline int occupancy_query(K kernel, int nthr) {
   int nb = 0;
