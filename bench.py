@@ -7,7 +7,7 @@ Prints ONE JSON line: problems/s plus a roofline object for the solve kernel (fp
 oracle timed on the host cores on a bounded sample of the same inputs.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llm_adapter] [--n N] [--rebase-every k]
-                    [--path symplectic|doubling|tv|cxt|scan]
+                    [--path symplectic|doubling|tv|cxt|scan|bwd|rollout|grid|block]
 
 The headline value is the paper's sequential symplectic product (--path symplectic, the default); the same
 inputs are also timed on the squaring path and reported under "other_path".
@@ -231,6 +231,99 @@ def bench_cxt(args):
     print(json.dumps(res))
 
 
+def alg_flops_block(C, H, d, r, T):
+    """Algorithmic flops of the whole block for one token: the two projections (2 C H d each), the contextualisation
+    maps of every head (2 d (5 d + 3 r)), the heads' structured problems; normalisations and activations are O(C)
+    and not counted."""
+    return 4 * C * H * d + H * (2 * d * (5 * d + 3 * r) + alg_flops_cxt(d, r, T))
+
+
+def bench_block(args):
+    """The whole TTC block at the width of the paper's 7B language-model runs: token features of 4096 numbers, 16
+    heads of d = 16, r = 16 basis matrices, horizon 8; 8 x 8192 tokens (the problems of --path cxt, with the layer
+    normalisations, projections and contextualisation maps around them)."""
+    import numpy as np
+    import torch
+    from paper_2603_09221_amd import binding, synth
+    from paper_2603_09221_amd.errors import rel_err
+
+    C, H, d, r, T = 4096, 16, 16, 16, args.horizon or 8
+    n = args.n or 8 * 8192
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    lib = binding.load()
+    w = synth.make_block_weights(C, H, d, r, seed=0, device=dev)
+    x = synth.make_block_input(n, C, seed=0, device=dev)
+    out = {"x_out": torch.empty_like(x), "info": torch.empty((n, H), dtype=torch.int32, device=dev)}
+    blk = binding.make_block(w, n, T)
+    ws = torch.empty(lib.ttc_block_workspace_bytes(blk), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    if args.calib_copy_mib:
+        src = torch.ones((args.calib_copy_mib << 18,), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    step = lambda: binding.ttc_block_forward(x, w, T, out=out, workspace=ws, stream=stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record(stream)
+        step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps
+    kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+    kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+    assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
+    flops_pt = alg_flops_block(C, H, d, r, T)
+    achieved = flops_pt * n / kernel_s / 1e12
+    alg_bytes = 2 * n * C * 4 + 2 * C * H * d * 4
+    res = {
+        "metric": "TTC block forward tokens/sec at C=%d, %d heads of d=%d, T=%d" % (C, H, d, T),
+        "value": n / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "ttc_block_c4096", "tokens": n, "C": C, "heads": H, "d": d, "r": r, "T": T,
+                   "problems": n * H, "path": "block"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": measured_traffic("ttc_block_c4096_T%d" % T, "block", n),
+                     "kernel": "ttc_block_forward (7 launches: ln_stats, gemm_ln, cxt_maps, qbasis, solve_cxt, ln_stats, gemm_ln)",
+                     "kernel_ms": kernel_s * 1e3, **spread(kernel_ms),
+                     "alg_flops_per_token": flops_pt,
+                     "alg_flops_split": {"projections": 4 * C * H * d, "maps": H * 2 * d * (5 * d + 3 * r),
+                                         "solves": H * alg_flops_cxt(d, r, T)},
+                     "alg_bytes_per_launch": alg_bytes, "alg_GBps": alg_bytes / kernel_s / 1e9},
+    }
+    if not args.no_cpu:
+        from concurrent.futures import ThreadPoolExecutor
+        from oracle import ttc_block_oracle
+        cores = min(16, os.cpu_count() or 1)
+        w64 = {k: v.cpu().double().numpy() for k, v in w.items()}
+
+        def run(sample):
+            xs = x[:sample].cpu().double().numpy()
+            chunks = [ix for ix in np.array_split(np.arange(sample), cores * 4) if len(ix)]
+            t1 = time.perf_counter()
+            with ThreadPoolExecutor(max_workers=cores) as ex:
+                parts = list(ex.map(lambda ix: ttc_block_oracle.ttc_block(xs[ix], w64, T)["x_out"], chunks))
+            return np.concatenate(parts), time.perf_counter() - t1
+        pilot = min(n, 256)
+        _, pdt = run(pilot)
+        sample = min(n, args.cpu_sample or int(max(pilot, pilot * 15.0 / max(pdt, 1e-3))))
+        ref, dt = run(sample)
+        err = float(rel_err(out["x_out"][:sample].cpu().numpy(), ref).max())
+        res["cpu_baseline"] = {"value": sample / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                               "cpu_model": cpu_model(),
+                               "sample": "first %d tokens of the same workload, float64 numpy, %.1f s wall" % (sample, dt)}
+        res["parity"] = {"sample": sample, "max_rel_err": {"x_out": err}, "tolerance": 1e-4}
+    print(json.dumps(res))
+
+
 def bench_grid(args):
     """The paper's solver benchmark grid (App. "Efficiency Benchmark": d = 16, horizon 2^4 .. 2^11 at batch 1024, batch
     2^4 .. 2^13 at horizon 64), forward and backward, time-heterogeneous dense steps: milliseconds per call (median
@@ -410,7 +503,7 @@ def main():
     ap.add_argument("--config", default="llm_adapter")
     ap.add_argument("--chunk", type=int, default=None, help="problems per launch (default: the whole workload, or "
                     "the largest power-of-two split whose outputs fit the card)")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd", "rollout", "grid"),
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd", "rollout", "grid", "block"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
                          "doubling: the long-horizon path, the same product formed by squaring; "
                          "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
@@ -421,7 +514,8 @@ def main():
                          "bwd: the backward pass (ttc_lqr_backward) on the configuration's shape (default up to "
                          "131072 problems); grid: the paper's solver benchmark grid at d = 16, forward and backward "
                          "(prints a table, not a bench line); rollout: ttc_lqr_rollout (all T controls, states and the cost) "
-                         "on the configuration's shape (default up to 16384 problems)")
+                         "on the configuration's shape (default up to 16384 problems); block: the whole TTC block (ttc_block_forward) at "
+                         "4096 features, 16 heads of d = 16, 65536 tokens, --config ignored")
     ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt (default 8) and scan (default 2048) paths")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
@@ -437,6 +531,8 @@ def main():
               "the batch and exchange nothing). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    if args.path == "block":
+        return bench_block(args)
     if args.path == "cxt":
         return bench_cxt(args)
     if args.path == "scan":

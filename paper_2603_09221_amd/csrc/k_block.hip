@@ -14,6 +14,10 @@ hipError_t launch_gemm_ln(const GemmLnArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 hipError_t launch_cxt_maps(const CxtMapsArgs& a, int blocks, hipStream_t st) {
+  if (a.r == 16 && a.H % 4 == 0) {  // `blocks` counts (token chunk, group of four heads) pairs here
+    hipLaunchKernelGGL(cxt_maps16_kernel, dim3((unsigned)blocks), dim3(512), 0, st, a);
+    return hipGetLastError();
+  }
   const int nout = 80 + 3 * a.r;
   hipLaunchKernelGGL(cxt_maps_kernel, dim3((unsigned)blocks), dim3((unsigned)(64 * ((nout + 63) / 64))), 0, st, a);
   return hipGetLastError();

@@ -670,11 +670,13 @@ ttc_status_t ttc_block_forward(const ttc_block_t* b, const float* x_in, float* x
   c.sA = ws + L.sA; c.rinv = ws + L.rinv; c.lgA = ws + L.lgA; c.lgB = ws + L.lgB; c.lgQ = ws + L.lgQ;
   c.sQf = ws + L.sQf; c.sB = ws + L.sB; c.sQ = ws + L.sQ;
   c.M = M; c.H = H; c.r = r;
-  long long chunks = (8LL * ttc::cu_count() + H - 1) / H;  // about eight workgroups per compute unit
+  // workgroups per token chunk: one per head, or one per four heads in the coalesced variant (r = 16, H % 4 = 0)
+  const int per_chunk = (r == 16 && H % 4 == 0) ? H / 4 : H;
+  long long chunks = (8LL * ttc::cu_count() + per_chunk - 1) / per_chunk;  // about eight workgroups per compute unit
   chunks = chunks < 1 ? 1 : chunks > M ? M : chunks;
   c.tokens_per_block = (int)((M + chunks - 1) / chunks);
   chunks = (M + c.tokens_per_block - 1) / c.tokens_per_block;
-  if (ttc::launch_cxt_maps(c, (int)(chunks * H), st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (ttc::launch_cxt_maps(c, (int)(chunks * per_chunk), st) != hipSuccess) return TTC_ERR_DEVICE;
   if (ttc::launch_qbasis(b->Qc, ws + L.qbasis, r, st) != hipSuccess) return TTC_ERR_DEVICE;
   // o = the heads' first optimal controls
   ttc_lqr_cxt_problem_t q;

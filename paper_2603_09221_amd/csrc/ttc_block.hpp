@@ -79,10 +79,14 @@ __global__ void __launch_bounds__(256) gemm_ln_kernel(const GemmLnArgs p) {
     mean[j] = row < p.M ? p.stats[2 * row] : 0.f;
     rstd[j] = row < p.M ? p.stats[2 * row + 1] : 0.f;
   }
-  blk_floatx4 rw[4], rx[4];
+  // a slice on its way: fetch() only issues the global reads, stash() normalises the rows of X and writes both slices
+  // to LDS; the matrix-core work on the slice before sits between the two, so the reads' latency is covered
+  blk_floatx4 rw[4], rx[4], gn, of;
+  bool live[4];
   auto fetch = [&](int k0) {
     const int k = k0 + lc;
-    blk_floatx4 gn = {0.f, 0.f, 0.f, 0.f}, of = {0.f, 0.f, 0.f, 0.f};
+    gn = blk_floatx4{0.f, 0.f, 0.f, 0.f};
+    of = blk_floatx4{0.f, 0.f, 0.f, 0.f};
     if (k < p.K) {
       gn = *reinterpret_cast<const blk_floatx4*>(p.gain + k);
       of = *reinterpret_cast<const blk_floatx4*>(p.offset + k);
@@ -93,19 +97,21 @@ __global__ void __launch_bounds__(256) gemm_ln_kernel(const GemmLnArgs p) {
       const long long row = m0 + lr + 32 * j;
       rw[j] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
       rx[j] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
+      live[j] = k < p.K && row < p.M;
       if (k < p.K && o < p.N) rw[j] = *reinterpret_cast<const blk_floatx4*>(p.W + (long long)o * p.K + k);
-      if (k < p.K && row < p.M) {
-        const blk_floatx4 v = *reinterpret_cast<const blk_floatx4*>(p.X + row * p.K + k);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) rx[j][e] = (v[e] - mean[j]) * rstd[j] * gn[e] + of[e];
-      }
+      if (live[j]) rx[j] = *reinterpret_cast<const blk_floatx4*>(p.X + row * p.K + k);
     }
   };
   auto stash = [&](int buf) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      blk_floatx4 v = {0.f, 0.f, 0.f, 0.f};
+      if (live[j]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (rx[j][e] - mean[j]) * rstd[j] * gn[e] + of[e];
+      }
       *reinterpret_cast<blk_floatx4*>(Ws(buf) + (lr + 32 * j) * GEMM_PITCH + lc) = rw[j];
-      *reinterpret_cast<blk_floatx4*>(Xs(buf) + (lr + 32 * j) * GEMM_PITCH + lc) = rx[j];
+      *reinterpret_cast<blk_floatx4*>(Xs(buf) + (lr + 32 * j) * GEMM_PITCH + lc) = v;
     }
   };
 
@@ -115,13 +121,7 @@ __global__ void __launch_bounds__(256) gemm_ln_kernel(const GemmLnArgs p) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = (p.K + GEMM_BK - 1) / GEMM_BK;
-  fetch(0);
-  stash(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) fetch((kt + 1) * GEMM_BK);
+  auto compute = [&](int buf) {
     const float* wsb = Ws(buf) + (64 * wo + i) * GEMM_PITCH + 4 * g;
     const float* xsb = Xs(buf) + (64 * wn + i) * GEMM_PITCH + 4 * g;
 #pragma unroll
@@ -140,9 +140,29 @@ __global__ void __launch_bounds__(256) gemm_ln_kernel(const GemmLnArgs p) {
           for (int nb = 0; nb < 4; ++nb)
             acc[ob][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ob][e], b[nb][e], acc[ob][nb], 0, 0, 0);
     }
-    if (kt + 1 < nk) stash(buf ^ 1);
+  };
+  const int nk = (p.K + GEMM_BK - 1) / GEMM_BK;
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int kt = 0; kt + 1 < nk; ++kt) {
+    fetch((kt + 1) * GEMM_BK);
+    compute(kt & 1);
+    stash((kt & 1) ^ 1);
     __syncthreads();
   }
+  // the last slice has nothing to fetch: the residual is read under its matrix-core work instead
+  blk_floatx4 res[4][4];
+#pragma unroll
+  for (int ob = 0; ob < 4; ++ob)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const int o = n0 + 64 * wo + 16 * ob + 4 * g;
+      const long long row = m0 + 64 * wn + 16 * nb + i;
+      res[ob][nb] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
+      if (p.Res && o < p.N && row < p.M) res[ob][nb] = *reinterpret_cast<const blk_floatx4*>(p.Res + row * p.N + o);
+    }
+  compute((nk - 1) & 1);
 
   // acc[ob][nb][v] = Y[m0 + 64 wn + 16 nb + i][n0 + 64 wo + 16 ob + 4 g + v]
 #pragma unroll
@@ -156,7 +176,7 @@ __global__ void __launch_bounds__(256) gemm_ln_kernel(const GemmLnArgs p) {
       const long long row = m0 + 64 * wn + 16 * nb + i;
       if (row >= p.M) continue;
       blk_floatx4 y = acc[ob][nb] + bs;
-      if (p.Res) y += *reinterpret_cast<const blk_floatx4*>(p.Res + row * p.N + o);
+      y += res[ob][nb];
       *reinterpret_cast<blk_floatx4*>(p.Y + row * p.N + o) = y;
     }
   }
@@ -219,6 +239,66 @@ __global__ void __launch_bounds__(320) cxt_maps_kernel(const CxtMapsArgs p) {
     }
     const float z = s0 + s1;
     dst[prob * len + col] = act ? softplus_f32(z) : z;
+  }
+}
+
+// The same maps for r = 16 and a multiple of four heads, with coalesced stores: wavefront a of a workgroup of eight
+// owns array a (sA, rinv, lgA, lgB, lgQ, sQf, sB, sQ), its lanes four consecutive heads times sixteen columns, so that a
+// store writes 256 consecutive bytes; the workgroup walks its tokens for one group of four heads.
+__global__ void __launch_bounds__(512) cxt_maps16_kernel(const CxtMapsArgs p) {
+  const int groups = p.H / 4;
+  const int hg = blockIdx.x % groups;
+  const long long t0 = (long long)(blockIdx.x / groups) * p.tokens_per_block;
+  const int a = threadIdx.x >> 6, lane = threadIdx.x & 63, q = lane >> 4, col = lane & 15;
+  const int h = 4 * hg + q;
+  const float* wrow;
+  float bias;
+  if (a < 6) {
+    const int j = a < 5 ? 16 * a + col : 80 + col;
+    wrow = p.W_head + ((long long)h * 96 + j) * 16;
+    bias = p.b_head[(long long)h * 96 + j];
+  } else {
+    const int j = 16 * (a - 6) + col;
+    wrow = p.W_shared + (long long)j * 16;
+    bias = p.b_shared[j];
+  }
+  float w[16];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const blk_floatx4 v = *reinterpret_cast<const blk_floatx4*>(wrow + 4 * k);
+    w[4 * k] = v[0]; w[4 * k + 1] = v[1]; w[4 * k + 2] = v[2]; w[4 * k + 3] = v[3];
+  }
+  float* const arrays[8] = {p.sA, p.rinv, p.lgA, p.lgB, p.lgQ, p.sQf, p.sB, p.sQ};
+  float* dst = arrays[0];
+#pragma unroll
+  for (int k = 1; k < 8; ++k) dst = a == k ? arrays[k] : dst;
+  const bool act = !(a == 0 || a == 6);
+  long long t1 = t0 + p.tokens_per_block;
+  t1 = t1 < p.M ? t1 : p.M;
+  // four tokens at a time, so that their reads are in flight together
+  for (long long t = t0; t < t1; t += 4) {
+    blk_floatx4 v[4][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long tt = t + u < t1 ? t + u : t1 - 1;
+      const float* x = p.H0 + (tt * p.H + h) * 16;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[u][k] = *reinterpret_cast<const blk_floatx4*>(x + 4 * k);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (t + u >= t1) break;
+      float s0 = bias, s1 = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        s0 = __builtin_fmaf(w[4 * k], v[u][k][0], s0);
+        s1 = __builtin_fmaf(w[4 * k + 1], v[u][k][1], s1);
+        s0 = __builtin_fmaf(w[4 * k + 2], v[u][k][2], s0);
+        s1 = __builtin_fmaf(w[4 * k + 3], v[u][k][3], s1);
+      }
+      const float z = s0 + s1;
+      dst[((t + u) * p.H + h) * 16 + col] = act ? softplus_f32(z) : z;
+    }
   }
 }
 
