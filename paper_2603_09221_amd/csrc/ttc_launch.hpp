@@ -20,9 +20,10 @@ template <int D> hipError_t launch_tv(const TvArgs& a, bool bf16, dim3 grid, hip
 template <int D> int occupancy_tv(bool bf16);
 template <int D> hipError_t launch_rollout_tv(const TvRolloutArgs& a, bool bf16, dim3 grid, hipStream_t st);
 template <int D> int occupancy_rollout_tv(bool bf16);
-template <int D> hipError_t launch_scan_leaf(const ScanArgs& a, bool bf16, dim3 grid, hipStream_t st);
-template <int D> hipError_t launch_scan_combine(const ScanArgs& a, dim3 grid, hipStream_t st);
-template <int D> hipError_t launch_scan_apply(const ScanArgs& a, dim3 grid, hipStream_t st);
+// ipw = items per workgroup: 1, or 4 (d = 16 only: the kernels that take four items per wavefront)
+template <int D> hipError_t launch_scan_leaf(const ScanArgs& a, bool bf16, int ipw, dim3 grid, hipStream_t st);
+template <int D> hipError_t launch_scan_combine(const ScanArgs& a, int ipw, dim3 grid, hipStream_t st);
+template <int D> hipError_t launch_scan_apply(const ScanArgs& a, int ipw, dim3 grid, hipStream_t st);
 template <int D> hipError_t launch_scan_gather(const ScanArgs& a, float* P, dim3 grid, hipStream_t st);
 template <int D> int occupancy_scan();
 

@@ -110,3 +110,22 @@ def test_values_bf16_inputs_and_single_outputs():
     red = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, b.R, b.x0)
     torch.cuda.synchronize()
     assert float(rel_err(both["K"][:, 0].cpu().numpy(), red["K0"].cpu().numpy()).max()) <= 1e-6
+
+
+def test_many_items_at_d16_four_per_wavefront():
+    """Rounds with more items than twice the resident workgroups run the kernels that take four items per wavefront
+    (d = 16): a ragged last group, terminal elements inside a group, bfloat16 inputs, and a breakdown that must stay
+    with its problem."""
+    b = synth.make_tv_batch(41, 16, 16, 333, seed=12, device=DEV)      # 13653 items, not a multiple of four
+    check(b, TOL_F32)
+    check_values(b, TOL_F32)
+    check(synth.make_tv_batch(41, 16, 16, 333, seed=13, device=DEV, dtype="bf16"), TOL_BF16)
+    good = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, b.R, b.x0)
+    R = b.R.clone()
+    R[17, 200] = -100.0 * torch.eye(16, device=DEV)
+    bad = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, R, b.x0)
+    torch.cuda.synchronize()
+    info = bad["info"].cpu().numpy()
+    assert info[17] == 1 and (np.delete(info, 17) == 0).all()
+    keep = torch.tensor([k for k in range(41) if k != 17], device=DEV)
+    assert torch.equal(bad["u0"][keep], good["u0"][keep]) and torch.isnan(bad["u0"][17]).all()
