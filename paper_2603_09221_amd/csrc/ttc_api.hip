@@ -434,14 +434,15 @@ size_t ttc_lqr_tv_scan_workspace_bytes(const ttc_lqr_tv_problem_t* q) {
 }
 
 // Launch shapes of the tree kernels: a round with `items` independent items runs one item per workgroup, except at
-// d = 16 when there are at least half as many items as the one-item kernels have resident workgroups: from there on
-// the kernels that take four items per wavefront are faster (measured on 256 compute units: 16.8 against 17.7 us at
-// 4096 items, 41 against 50 us at 16384; with 2048 items the one-item kernels finish the round sooner, 13 against 15.5).
+// d = 16 when there are at least fourteen items per compute unit: from there on the kernels that take four items per
+// wavefront are faster (measured on 256 compute units: 16.8 against 17.7 us at 4096 items, 41 against 50 us at 16384;
+// with 2048 items the one-item kernels finish the round sooner, 13 against 15.5).
 struct ScanPlan {
   long long gb;   // resident workgroups of the one-item kernels
   long long gb4;  // of the four-item kernels (d = 16)
+  long long cus;  // compute units
   bool quads;
-  int ipw(long long items) const { return quads && 2 * items >= gb ? 4 : 1; }
+  int ipw(long long items) const { return quads && items >= 14 * cus ? 4 : 1; }
   dim3 grid(long long items) const {
     if (ipw(items) == 4) {
       const long long groups = (items + 3) / 4;
@@ -454,6 +455,7 @@ static ScanPlan scan_plan(int d, bool bf16) {
   ScanPlan p;
   p.gb = ttc::grid_blocks(ttc::KIND_SCAN, d, bf16);
   p.gb4 = 12LL * ttc::cu_count();  // three wavefronts per SIMD (registers)
+  p.cus = ttc::cu_count();
   p.quads = d == 16;
   return p;
 }
@@ -479,11 +481,12 @@ static hipError_t scan_up_sweep(const ttc_lqr_tv_problem_t* q, ttc::ScanArgs& sa
   const ScanPlan plan = scan_plan(d, bf16);
   hipError_t e = ttc::run_scan_leaf(sa, d, bf16, plan.ipw(q->n * q->T), plan.grid(q->n * q->T), st);
   if (e != hipSuccess) return e;
-  for (long long stride = 1; stride < q->T; stride *= 2) {
+  for (long long stride = 1; stride < q->T;) {
     sa.stride = (int)stride;
     const long long per = (q->T - stride + 2 * stride - 1) / (2 * stride);
     e = ttc::run_scan_combine(sa, d, plan.ipw(q->n * per), plan.grid(q->n * per), st);
     if (e != hipSuccess) return e;
+    stride *= 2;
   }
   return hipSuccess;
 }

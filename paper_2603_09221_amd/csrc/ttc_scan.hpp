@@ -91,92 +91,114 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) scan_leaf_kernel(const ScanArgs 
   }
 }
 
+// e1 <- e1 o e2 for one pair of elements in the workspace, by the Cfg<D>::NTHR threads of a workgroup (tid = the
+// thread's index).  Ends with the results written but no barrier.
+template <int D>
+__device__ __forceinline__ void scan_compose(float* W, SolveScratch<D>& S, float* St, float* e1, const float* e2,
+                                             int tid) {
+  using C = Cfg<D>;
+  float* const WL = W;
+  float* const WR = W + D;
+  const int lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+  float* const oA = e1;  // the composition replaces the first element
+  float* const oG = e1 + D * D;
+  float* const oH = e1 + 2 * D * D;
+  const float *A1 = e1, *G1 = e1 + D * D, *H1 = e1 + 2 * D * D;
+  const float *A2 = e2, *G2 = e2 + D * D, *H2 = e2 + 2 * D * D;
+  if constexpr (D == 16) {
+    // a matrix is one 16-byte piece per lane: all six are requested at once and kept in LDS, one trip to memory
+    // for the whole composition instead of one per use (a round with few items is bound by these trips)
+    floatx4 v[6];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      v[k] = *reinterpret_cast<const floatx4*>(e1 + k * D * D + 4 * lane);
+      v[3 + k] = *reinterpret_cast<const floatx4*>(e2 + k * D * D + 4 * lane);
+    }
+#pragma unroll
+    for (int k = 0; k < 6; ++k) *reinterpret_cast<floatx4*>(&St[k * D * D + 4 * lane]) = v[k];
+    __syncthreads();
+    A1 = St; G1 = St + D * D; H1 = St + 2 * D * D;
+    A2 = St + 3 * D * D; G2 = St + 4 * D * D; H2 = St + 5 * D * D;
+  }
+  floatx4 acc[C::RB][C::NT], accY[C::RB][C::NT];
+  float rM[C::RB][C::KS], rA1T[C::RB][C::KS], rA2[C::RB][C::KS];
+  {
+    float rG1[C::RB][C::KS];
+    load_half<D, float, false>(WR, H2, tid);
+    load_aop_global<D, float>(G1, rG1, w, i, g);
+    __syncthreads();
+    eye_acc<D>(acc, w, i, g);
+    gemm_acc<D>(acc, rG1, WR, i, g);  // I + G1 H2
+    store_rows<D>(WL, acc, w, i, g);
+    __syncthreads();
+  }
+  set_half_identity<D>(WR, tid);
+  __syncthreads();
+  const int flag = lds_solve<D>(W, S, tid);  // right half: M = (I + G1 H2)^{-1}
+  load_aop_lds<D>(WR, rM, w, i, g);
+  load_half<D, float, false>(WL, A1, tid);
+  __syncthreads();
+  zero_acc<D>(acc);
+  gemm_acc<D>(acc, rM, WL, i, g);  // X1 = M A1
+  load_aopT_lds<D>(WL, rA1T, w, i, g);
+  load_half<D, float, false>(WR, G1, tid);  // M is in registers
+  __syncthreads();
+  store_rows<D>(WL, acc, w, i, g);  // left half: X1
+  zero_acc<D>(accY);
+  gemm_acc<D>(accY, rM, WR, i, g);  // Y = M G1
+  __syncthreads();
+  load_aop_global<D, float>(A2, rA2, w, i, g);
+  zero_acc<D>(acc);
+  gemm_acc<D>(acc, rA2, WL, i, g);  // A = A2 X1
+  write_rows_global<D>(oA, acc, w, i, g);
+  {
+    float rH2[C::RB][C::KS];
+    load_aop_global<D, float>(H2, rH2, w, i, g);
+    zero_acc<D>(acc);
+    gemm_acc<D>(acc, rH2, WL, i, g);  // V = H2 X1
+  }
+  store_rows<D>(WR, acc, w, i, g);  // right half: V
+  __syncthreads();
+  load_rows_global<D>(H1, acc, w, i, g);
+  gemm_acc<D>(acc, rA1T, WR, i, g);  // H = H1 + A1^T V
+  if (flag) poison<D>(acc);
+  write_rows_global<D>(oH, acc, w, i, g);
+  store_rows<D>(WL, accY, w, i, g);  // left half: Y
+  __syncthreads();
+  zero_acc<D>(acc);
+  gemm_acc<D>(acc, rA2, WL, i, g);  // Z = A2 Y
+  load_half<D, float, true>(WR, A2, tid);  // right half: A2^T
+  __syncthreads();
+  store_rows<D>(WL, acc, w, i, g);  // left half: Z
+  __syncthreads();
+  {
+    float rZ[C::RB][C::KS];
+    load_aop_lds<D>(WL, rZ, w, i, g);
+    load_rows_global<D>(G2, acc, w, i, g);
+    gemm_acc<D>(acc, rZ, WR, i, g);  // G = G2 + Z A2^T
+    write_rows_global<D>(oG, acc, w, i, g);
+  }
+}
+
 // one round of pairwise compositions
 template <int D>
 __global__ void __launch_bounds__(Cfg<D>::NTHR) scan_combine_kernel(const ScanArgs a) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
   __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
+  __shared__ __attribute__((aligned(16))) float St[D == 16 ? 6 * D * D : 4];  // d = 16: the two elements, as read
   const SolveArgs& p = a.tv.s;
-  float* const WL = W;
-  float* const WR = W + D;
   const int st = a.stride;
   const long long per = (p.T - st + 2LL * st - 1) / (2LL * st);  // pairs per problem in this round
   const long long items = p.n * per;
   for (long long item = blockIdx.x; item < items; item += gridDim.x) {
-    const int tid = threadIdx.x + opaque_zero(), lane = tid & 63, w = tid >> 6, i = lane & 15, g = lane >> 4;
+    const int tid = threadIdx.x + opaque_zero();
     const long long prob = item / per;
     const long long j = (item % per) * 2 * st;
-    float* const e1 = a.ws + (prob * p.T + j) * 3 * D * D;
-    const float* const e2 = a.ws + (prob * p.T + j + st) * 3 * D * D;
-    float* const A1 = e1;
-    float* const G1 = e1 + D * D;
-    float* const H1 = e1 + 2 * D * D;
-    const float* const A2 = e2;
-    const float* const G2 = e2 + D * D;
-    const float* const H2 = e2 + 2 * D * D;
-    floatx4 acc[C::RB][C::NT], accY[C::RB][C::NT];
-    float rM[C::RB][C::KS], rA1T[C::RB][C::KS], rA2[C::RB][C::KS];
-    {
-      float rG1[C::RB][C::KS];
-      load_half<D, float, false>(WR, H2, tid);
-      load_aop_global<D, float>(G1, rG1, w, i, g);
-      __syncthreads();
-      eye_acc<D>(acc, w, i, g);
-      gemm_acc<D>(acc, rG1, WR, i, g);  // I + G1 H2
-      store_rows<D>(WL, acc, w, i, g);
-      __syncthreads();
-    }
-    set_half_identity<D>(WR, tid);
-    __syncthreads();
-    const int flag = lds_solve<D>(W, S, tid);  // right half: M = (I + G1 H2)^{-1}
-    load_aop_lds<D>(WR, rM, w, i, g);
-    load_half<D, float, false>(WL, A1, tid);
-    __syncthreads();
-    zero_acc<D>(acc);
-    gemm_acc<D>(acc, rM, WL, i, g);  // X1 = M A1
-    load_aopT_lds<D>(WL, rA1T, w, i, g);
-    load_half<D, float, false>(WR, G1, tid);  // M is in registers
-    __syncthreads();
-    store_rows<D>(WL, acc, w, i, g);  // left half: X1
-    zero_acc<D>(accY);
-    gemm_acc<D>(accY, rM, WR, i, g);  // Y = M G1
-    __syncthreads();
-    load_aop_global<D, float>(A2, rA2, w, i, g);
-    zero_acc<D>(acc);
-    gemm_acc<D>(acc, rA2, WL, i, g);  // A = A2 X1
-    write_rows_global<D>(A1, acc, w, i, g);
-    {
-      float rH2[C::RB][C::KS];
-      load_aop_global<D, float>(H2, rH2, w, i, g);
-      zero_acc<D>(acc);
-      gemm_acc<D>(acc, rH2, WL, i, g);  // V = H2 X1
-    }
-    store_rows<D>(WR, acc, w, i, g);  // right half: V
-    __syncthreads();
-    load_rows_global<D>(H1, acc, w, i, g);
-    gemm_acc<D>(acc, rA1T, WR, i, g);  // H = H1 + A1^T V
-    if (flag) poison<D>(acc);
-    write_rows_global<D>(H1, acc, w, i, g);
-    store_rows<D>(WL, accY, w, i, g);  // left half: Y
-    __syncthreads();
-    zero_acc<D>(acc);
-    gemm_acc<D>(acc, rA2, WL, i, g);  // Z = A2 Y
-    load_half<D, float, true>(WR, A2, tid);  // right half: A2^T
-    __syncthreads();
-    store_rows<D>(WL, acc, w, i, g);  // left half: Z
-    __syncthreads();
-    {
-      float rZ[C::RB][C::KS];
-      load_aop_lds<D>(WL, rZ, w, i, g);
-      load_rows_global<D>(G2, acc, w, i, g);
-      gemm_acc<D>(acc, rZ, WR, i, g);  // G = G2 + Z A2^T
-      write_rows_global<D>(G1, acc, w, i, g);
-    }
+    scan_compose<D>(W, S, St, a.ws + (prob * p.T + j) * 3 * D * D, a.ws + (prob * p.T + j + st) * 3 * D * D, tid);
     __syncthreads();
   }
 }
-
 
 // Down-sweep of the tree: after the rounds of scan_combine_kernel element j + st (st the round's stride, j a
 // multiple of 2 st) still holds the composition of the steps [j + st, j + 2 st), and the value entering it from
@@ -192,6 +214,7 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) scan_apply_kernel(const ScanArgs
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) float W[D * C::PITCH];
   __shared__ __attribute__((aligned(16))) SolveScratch<D> S;
+  __shared__ __attribute__((aligned(16))) float St[D == 16 ? 4 * D * D : 4];  // d = 16: A, G, H, P as read
   const SolveArgs& p = a.tv.s;
   float* const WR = W + D;
   const int st = a.stride;
@@ -204,11 +227,22 @@ __global__ void __launch_bounds__(Cfg<D>::NTHR) scan_apply_kernel(const ScanArgs
     const long long j = (item % per) * 2 * st;
     if (j + 2 * st >= p.T) continue;  // the element's range reaches the terminal cost: its H is P already (uniform)
     float* const e = a.ws + (prob * p.T + j + st) * 3 * D * D;
-    const float* const gP = a.ws + ((prob * p.T + j + 2 * st) * 3 + 2) * D * D;
+    const float* gP = a.ws + ((prob * p.T + j + 2 * st) * 3 + 2) * D * D;
+    const float *eA = e, *eG = e + D * D, *eH = e + 2 * D * D;
+    if constexpr (D == 16) {  // as in scan_combine_kernel: the four matrices in one trip
+      floatx4 v[4];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) v[k] = *reinterpret_cast<const floatx4*>(e + k * D * D + 4 * lane);
+      v[3] = *reinterpret_cast<const floatx4*>(gP + 4 * lane);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) *reinterpret_cast<floatx4*>(&St[k * D * D + 4 * lane]) = v[k];
+      __syncthreads();
+      eA = St; eG = St + D * D; eH = St + 2 * D * D; gP = St + 3 * D * D;
+    }
     floatx4 acc[C::RB][C::NT];
     float rAT[C::RB][C::KS];
-    const int flag = mobius_solve<D, float>(W, S, e, e + D * D, gP, rAT, tid, tm);  // right half: (I + P G)^{-1} P A
-    load_rows_global<D>(e + 2 * D * D, acc, w, i, g);
+    const int flag = mobius_solve<D, float>(W, S, eA, eG, gP, rAT, tid, tm);  // right half: (I + P G)^{-1} P A
+    load_rows_global<D>(eH, acc, w, i, g);
     gemm_acc<D>(acc, rAT, WR, i, g);
     if (flag) poison<D>(acc);
     write_rows_global<D>(e + 2 * D * D, acc, w, i, g);
