@@ -36,6 +36,12 @@ UNITS = [("ttc_api.hip", None),
          ("k_cxt.hip", None),
          ("k_block.hip", None)]
 
+# Per (source, state size) compile flags.  The backward kernel at d = 64 runs four wavefronts of one 16-row block each
+# per problem instead of two of two (measured 1.98M against 1.79M problems/s at d = 64, T = 8): its dense solve is a
+# third of the time and three wavefronts share its tiles; the forward kernels are faster with two (fewer, fatter
+# wavefronts leave room for four problems per compute unit).
+UNIT_FLAGS = {("k_backward.hip", 64): ["-DTTC_ROW_BLOCKS(D)=((D)==64?1:((D)>=32?2:1))"]}
+
 _NOISE = "is not a recognized feature for this target"
 
 
@@ -69,8 +75,8 @@ def build(force: bool = True, jobs: int | None = None, extra_flags=()) -> str:
             obj = os.path.join(OBJDIR, stem + ".o")
             objs.append(obj)
             if force or not os.path.exists(obj) or os.path.getmtime(obj) < newest:
-                cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + (["-DTTC_D=%d" % d] if d else []) + \
-                      ["-c", os.path.join(CSRC, src), "-o", obj]
+                cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + UNIT_FLAGS.get((src, d), []) + \
+                      (["-DTTC_D=%d" % d] if d else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
                 work.append(cmd)
     # the largest state sizes take longest: start them first
     work.sort(key=lambda c: -max([int(a[8:]) for a in c if a.startswith("-DTTC_D=")] or [0]))
