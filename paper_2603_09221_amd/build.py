@@ -36,11 +36,16 @@ UNITS = [("ttc_api.hip", None),
          ("k_cxt.hip", None),
          ("k_block.hip", None)]
 
-# Per (source, state size) compile flags.  The backward kernel at d = 64 runs four wavefronts of one 16-row block each
-# per problem instead of two of two (measured 1.98M against 1.79M problems/s at d = 64, T = 8): its dense solve is a
-# third of the time and three wavefronts share its tiles; the forward kernels are faster with two (fewer, fatter
-# wavefronts leave room for four problems per compute unit).
-UNIT_FLAGS = {("k_backward.hip", 64): ["-DTTC_ROW_BLOCKS(D)=((D)==64?1:((D)>=32?2:1))"]}
+# Per (source, state size) compile flags: wavefronts of one 16-row block each (twice as many per problem) instead of
+# two row blocks, where measured faster.  The dense solve inside these kernels is a third or more of their time and
+# all but one wavefront share its tiles; the default forward kernel is faster with fewer, fatter wavefronts (its
+# constant operands stay in registers; at d = 64 four problems fit a compute unit).  Measured, problems/s:
+# backward d = 64, T = 8: 1.99M against 1.79M; time-heterogeneous d = 128, T = 16: 179k against 170k; squaring path
+# d = 128, T = 16: 501k against 488k (T = 32, bf16 inputs: 421k against 404k).
+_ONE_ROW_BLOCK = "-DTTC_ROW_BLOCKS(D)=((D)==%d?1:((D)>=32?2:1))"
+UNIT_FLAGS = {("k_backward.hip", 64): [_ONE_ROW_BLOCK % 64],
+              ("k_tv.hip", 128): [_ONE_ROW_BLOCK % 128],
+              ("k_doubling.hip", 128): [_ONE_ROW_BLOCK % 128]}
 
 _NOISE = "is not a recognized feature for this target"
 

@@ -72,9 +72,11 @@ def test_cost_scales_and_spectral_radii(d, n, T, rho):
 @pytest.mark.parametrize("d,n", [(16, 3100), (16, 40), (64, 64), (128, 20)])
 def test_fast_growing_problems_take_the_riccati_recursion(d, n):
     """Cheap control (R scaled by 1e-2): the pair grows a thousandfold per factor, far beyond the guard's limit,
-    so every problem must come out exactly as ttc_lqr_solve_tv computes it on the same matrices repeated over
-    the horizon (the same code runs); on the benchmark inputs the guard must stay silent and the symplectic
-    path's own results differ from that recursion in the last bits."""
+    so every problem must come out as ttc_lqr_solve_tv computes it on the same matrices repeated over the horizon
+    (the same code runs: P0 and K0 bit for bit; u0 and value are sums over the wavefronts of a workgroup, and the two
+    kernels may be built with different numbers of wavefronts per problem, so these agree to rounding); on the
+    benchmark inputs the guard must stay silent and the symplectic path's own results differ from that recursion in
+    the last bits."""
     T = 7
     hard = synth.make_batch(n, d, d, T, seed=3, device=DEV, r_scale=1e-2)
     out = solve(hard)
@@ -82,8 +84,10 @@ def test_fast_growing_problems_take_the_riccati_recursion(d, n):
     tv = binding.ttc_lqr_solve_tv(rep(hard.A), rep(hard.B), rep(hard.Q), rep(hard.R), hard.x0)
     torch.cuda.synchronize()
     assert int(out["info"].abs().max()) == 0
-    for k in ("P0", "K0", "u0", "value"):
+    for k in ("P0", "K0"):
         assert torch.equal(out[k], tv[k]), k
+    for k in ("u0", "value"):
+        assert float(rel_err(out[k].cpu().numpy(), tv[k].cpu().numpy()).max()) <= 2e-6, k
     easy = synth.make_batch(n, d, d, T, seed=3, device=DEV)
     out = solve(easy)
     tv = binding.ttc_lqr_solve_tv(rep(easy.A), rep(easy.B), rep(easy.Q), rep(easy.R), easy.x0)
