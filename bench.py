@@ -28,13 +28,15 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
 
 def source_hash():
-    """Identifies the build of the kernels: a hash over the HIP sources (what a measured traffic figure belongs to)."""
+    """Identifies the build of the kernels: a hash over the HIP sources and their build script (what a measured traffic figure belongs to)."""
     import hashlib
     h = hashlib.sha256()
     folder = os.path.join(ROOT, "paper_2603_09221_amd", "csrc")
-    for name in sorted(os.listdir(folder)):
-        with open(os.path.join(folder, name), "rb") as f:
-            h.update(name.encode() + b"\0" + f.read())
+    files = [os.path.join(folder, name) for name in sorted(os.listdir(folder))]
+    files.append(os.path.join(ROOT, "paper_2603_09221_amd", "build.py"))   # the compile flags of every unit
+    for path in files:
+        with open(path, "rb") as f:
+            h.update(os.path.basename(path).encode() + b"\0" + f.read())
     return h.hexdigest()[:16]
 
 
