@@ -26,3 +26,19 @@ def test_flop_counts():
     assert bench.alg_flops_tv(d, T) == pytest.approx(T * (6 * 2 + 1.0 / 3 + 2) * d ** 3)
     assert bench.alg_flops_cxt(16, 16, 8) == 3 * 2 * 16 * 256 + 8 * 5 * 2 * 16 ** 3 == 352256
     assert bench.alg_flops_scan(16, 1) == pytest.approx((12 + 7.0 / 3) * 16 ** 3)
+
+
+def test_block_and_rollout_flop_counts_and_build_hash():
+    C, H, d, r, T = 4096, 16, 16, 16, 8
+    # per token: two projections of 2 C H d each, per head the eight maps (5 d + 3 r outputs of d terms) and the solve
+    want = 2 * (2 * C * H * d) + H * (2 * d * (5 * d + 3 * r) + 352256)
+    assert bench.alg_flops_block(C, H, d, r, T) == want == 9895936
+    assert bench.alg_flops_rollout(64, 8) > bench.alg_flops_tv(64, 8) * 0.9   # a Riccati sweep plus the mat-vecs
+    # the build script is part of what identifies a build of the kernels
+    import hashlib
+    h = hashlib.sha256()
+    folder = os.path.join(ROOT, "paper_2603_09221_amd", "csrc")
+    for path in [os.path.join(folder, n) for n in sorted(os.listdir(folder))] + [os.path.join(ROOT, "paper_2603_09221_amd", "build.py")]:
+        with open(path, "rb") as f:
+            h.update(os.path.basename(path).encode() + b"\0" + f.read())
+    assert bench.source_hash() == h.hexdigest()[:16]
