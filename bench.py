@@ -293,7 +293,7 @@ def bench_block(args):
                    "problems": n * H, "path": "block"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": measured_traffic("ttc_block_c4096_T%d" % T, "block", n),
+                     "traffic": measured_traffic("ttc_block_c4096_T%d" % T, "block", n * H),   # the table's unit is the (token, head) problem
                      "kernel": "ttc_block_forward (7 launches: ln_stats, gemm_ln, cxt_maps, qbasis, solve_cxt, ln_stats, gemm_ln)",
                      "kernel_ms": kernel_s * 1e3, **spread(kernel_ms),
                      "alg_flops_per_token": flops_pt,
