@@ -25,8 +25,9 @@ with respect to the symmetric part, which is what Thm 3.2 states).
 Pins (tests/test_grad_oracle_pins.py): central finite differences of lqr_oracle.riccati_solve_tv on tiny
 instances, the stacked KKT system of the proof of Thm A.6 solved densely (for both trajectories), a scalar
 problem differentiated by hand, dl/dh_0 = K_1^T g, and two invariances of the layer (common scaling of all costs;
-change of state coordinates) that force linear identities between the gradients.  The paper prints no numeric
-example of a gradient: parity against printed values is unpinned.
+change of state coordinates) that force linear identities between the gradients; for the structured parameters
+(contextual_gradients, at the end of this file) central finite differences of lqr_oracle.contextual_solve in every
+input.  The paper prints no numeric example of a gradient: parity against printed values is unpinned.
 """
 from __future__ import annotations
 
@@ -135,3 +136,59 @@ def lqr_gradients(A, B, Q, R, QT, x0, T, g):
     else:
         out["gQ"], out["gQT"] = tv["gQ"][..., :T - 1, :, :].sum(axis=-3), tv["gQ"][..., T - 1, :, :]
     return out
+
+
+# ------------------------------------------------------------------------------------------------------
+# Structured, contextualised parameters (Sec. 4, "Contextualization" and "Parameterization"): the gradients of Thm 3.2
+# carried on, by the chain rule, to the per-problem vectors and the shared basis matrices the steps are built from
+# (lqr_oracle.contextual_parameters), in the quantities the layer hands over: the log-scale modulation
+# coefficients lg_X and the diagonal of R^{-1} (Sec. 4, "Parameterization", last sentence).  With t = 1..T and
+# gam_X^t = exp(-t lg_X):
+#     A_t = I + diag(gam_A^t sA)                  dl/dsA_i  = sum_t gam_A,i^t gA_t[i,i]
+#                                                 dl/dlgA_i = sum_t (-t) gam_A,i^t sA_i gA_t[i,i]
+#     B_t = Bbar diag(gam_B^t)                    dl/dBbar  = sum_t gB_t diag(gam_B^t)
+#                                                 dl/dlgB_j = sum_t (-t) gam_B,j^t sum_i Bbar[i,j] gB_t[i,j]
+#     Q_t = diag(gam_Q^t) Qbar diag(gam_Q^t)      dl/dQbar  = sum_{t<T} diag(gam_Q^t) gQ_t diag(gam_Q^t)
+#          (t < T)                                dl/dlgQ_i = sum_{t<T} (-t) (row i + column i sums of Q_t o gQ_t)
+#     Q_T = Qf                                    dl/dQf    = gQ_T
+#     R_t = diag(1 / rinv)                        dl/drinv_i = -sum_t gR_t[i,i] / rinv_i^2
+#     Bbar = sum_k sB_k B^(k) etc.                dl/dsB_k = <B^(k), dl/dBbar>,  dl/dB^(k) = sum over problems sB_k dl/dBbar
+# and likewise for sQ, sQf and Q^(k).
+# Pin (tests/test_grad_oracle_pins.py): central finite differences of lqr_oracle.contextual_solve in every one of these
+# inputs on tiny instances.
+
+def contextual_gradients(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T, g):
+    """Gradients of a loss l(u_0), dl/du_0 = g (..., d), for the structured problems of lqr_oracle.contextual_solve.
+
+    Returns gsA, grinv, glgA, glgB, glgQ, gx0 (..., d), gsB, gsQ, gsQf (..., r) and, summed over all leading axes,
+    gBbasis, gQbasis (r, d, d)."""
+    from . import lqr_oracle
+    sA, sB, sQ, sQf, rinv = _f64(sA), _f64(sB), _f64(sQ), _f64(sQf), _f64(rinv)
+    lgA, lgB, lgQ, Bbasis, Qbasis = _f64(lgA), _f64(lgB), _f64(lgQ), _f64(Bbasis), _f64(Qbasis)
+    A, B, Q, R = lqr_oracle.contextual_parameters(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, T)
+    dense = lqr_gradients_tv(A, B, Q, R, x0, g)
+    gA, gB, gQ, gR = dense["gA"], dense["gB"], dense["gQ"], dense["gR"]
+    Bbar = np.einsum("...k,kij->...ij", sB, Bbasis)
+    diag = lambda M: np.diagonal(M, axis1=-2, axis2=-1)
+    gsA, glgA, glgB, glgQ = (np.zeros_like(sA) for _ in range(4))
+    gBbar, gQbar = np.zeros_like(Bbar), np.zeros_like(Bbar)
+    for t in range(1, T + 1):
+        s = t - 1
+        gamA, gamB, gamQ = np.exp(-t * lgA), np.exp(-t * lgB), np.exp(-t * lgQ)
+        gsA += gamA * diag(gA[..., s, :, :])
+        glgA += -t * gamA * sA * diag(gA[..., s, :, :])
+        gBbar += gB[..., s, :, :] * gamB[..., None, :]
+        glgB += -t * gamB * (Bbar * gB[..., s, :, :]).sum(axis=-2)
+        if t < T:
+            gQbar += gamQ[..., :, None] * gQ[..., s, :, :] * gamQ[..., None, :]
+            had = Q[..., s, :, :] * gQ[..., s, :, :]
+            glgQ += -t * (had.sum(axis=-1) + had.sum(axis=-2))
+    gQf = gQ[..., T - 1, :, :]
+    grinv = -diag(gR.sum(axis=-3)) / rinv ** 2
+    r, d = Bbasis.shape[0], Bbasis.shape[-1]
+    over = lambda c, M: np.einsum("nk,nij->kij", c.reshape(-1, r), M.reshape(-1, d, d))   # sum over the problems
+    return {"gsA": gsA, "glgA": glgA, "glgB": glgB, "glgQ": glgQ, "grinv": grinv, "gx0": dense["gx0"],
+            "gsB": np.einsum("kij,...ij->...k", Bbasis, gBbar),
+            "gsQ": np.einsum("kij,...ij->...k", Qbasis, gQbar),
+            "gsQf": np.einsum("kij,...ij->...k", Qbasis, gQf),
+            "gBbasis": over(sB, gBbar), "gQbasis": over(sQ, gQbar) + over(sQf, gQf)}

@@ -156,3 +156,44 @@ def test_time_invariant_gradients_against_finite_differences():
             assert np.abs(fd - G["g" + name]).max() <= 2e-7 * max(1.0, np.abs(fd).max()), name
         if qt is None:
             assert G["gQT"] is None
+
+
+@pytest.mark.parametrize("d,r,T,seed", [(3, 2, 3, 0), (2, 3, 1, 1), (4, 2, 2, 2)])
+def test_structured_gradients_against_finite_differences(d, r, T, seed):
+    """contextual_gradients against central differences of contextual_solve's u0 in every input: the per-problem
+    vectors (the log-scale modulation coefficients and the diagonal of R^{-1} among them), x0 and both groups of
+    basis matrices (whose gradients sum over the problems)."""
+    from oracle import lqr_oracle
+    rng = np.random.default_rng(seed)
+    n = 2
+    sp = lambda z: np.logaddexp(0.0, z)
+    args = {"sA": 0.3 * rng.normal(size=(n, d)), "sB": rng.normal(size=(n, r)), "sQ": sp(rng.normal(size=(n, r))),
+            "sQf": sp(rng.normal(size=(n, r))), "rinv": sp(rng.normal(size=(n, d))) + 0.2,
+            "lgA": 0.3 * sp(rng.normal(size=(n, d))), "lgB": 0.3 * sp(rng.normal(size=(n, d))),
+            "lgQ": 0.3 * sp(rng.normal(size=(n, d))), "Bbasis": rng.normal(size=(r, d, d)) / np.sqrt(d)}
+    Qc = rng.normal(size=(r, d, d))
+    args["Qbasis"] = Qc @ np.swapaxes(Qc, -1, -2) / np.sqrt(d)
+    args["x0"] = rng.normal(size=(n, d))
+    g = rng.normal(size=(n, d))
+    order = ("sA", "sB", "sQ", "sQf", "rinv", "lgA", "lgB", "lgQ", "Bbasis", "Qbasis", "x0")
+    loss = lambda a: float((lqr_oracle.contextual_solve(*(a[k] for k in order), T)["u0"] * g).sum())
+    got = go.contextual_gradients(*(args[k] for k in order), T, g)
+    names = {"sA": "gsA", "sB": "gsB", "sQ": "gsQ", "sQf": "gsQf", "rinv": "grinv", "lgA": "glgA", "lgB": "glgB",
+             "lgQ": "glgQ", "Bbasis": "gBbasis", "Qbasis": "gQbasis", "x0": "gx0"}
+    eps = 1e-6
+    for key, gname in names.items():
+        fd = np.zeros_like(args[key])
+        for idx in np.ndindex(*args[key].shape):
+            if key == "Qbasis" and idx[1] > idx[2]:
+                continue                       # Q^(k) is symmetric: move the pair of entries together
+            hi, lo = {k: v.copy() for k, v in args.items()}, {k: v.copy() for k, v in args.items()}
+            pairs = [idx] if key != "Qbasis" or idx[1] == idx[2] else [idx, (idx[0], idx[2], idx[1])]
+            for ix in pairs:
+                hi[key][ix] += eps
+                lo[key][ix] -= eps
+            fd[idx] = (loss(hi) - loss(lo)) / (2 * eps)
+        want = got[gname]
+        if key == "Qbasis":                     # the derivative along a symmetric pair is the sum of the two entries
+            want = np.triu(want + np.swapaxes(want, -1, -2)) - np.einsum("kij,ij->kij", want, np.eye(d))
+        scale = max(np.abs(want).max(), 1e-12)
+        assert np.abs(fd - want).max() <= 2e-6 * scale + 1e-9, (key, np.abs(fd - want).max(), scale)
