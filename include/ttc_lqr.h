@@ -296,6 +296,30 @@ ttc_status_t ttc_lqr_backward_tv(const ttc_lqr_tv_problem_t *problem, const floa
                                  const ttc_lqr_grads_t *grads, void *workspace, size_t workspace_bytes,
                                  void *hip_stream);
 
+/* Backward pass of the structured, contextualised problems (Thm 3.2 carried on to the parameterisation of Sec. 4,
+ * "Contextualization", "Parameterization"): gradients of a loss of u0 = u_1^*, given grad_u0 = dl/du0 (n, 16) float32,
+ * with respect to the inputs of ttc_lqr_cxt_problem_t, in the quantities the layer hands over (the log-scale
+ * modulation coefficients lgA, lgB, lgQ and rinv, the diagonal of R^{-1}).  All outputs DEVICE, float32, contiguous,
+ * written: gsA, grinv, glgA, glgB, glgQ, gx0 (n, 16); gsB, gsQ, gsQf (n, r); gBbasis, gQbasis (r, 16, 16), the sums
+ * over all n problems (cleared by the call, then accumulated with atomic additions: their last bits may differ from
+ * run to run); info (n) or NULL, as ttc_lqr_backward_tv reports it.  The basis gradients are with respect to the
+ * matrices as given (every entry on its own); Qbasis has to be symmetric. */
+typedef struct {
+  float *gsA, *gsB, *gsQ, *gsQf, *grinv, *glgA, *glgB, *glgQ, *gx0;
+  float *gBbasis, *gQbasis;
+  int32_t *info;
+} ttc_lqr_cxt_grads_t;
+
+/* The problems are taken a chunk at a time: their T steps are written out densely into the workspace, the kernel of
+ * ttc_lqr_backward_tv produces the per-step gradients there, and two small kernels carry them on to the outputs
+ * (four launches per chunk, after one that clears the basis gradients).  workspace: DEVICE, 16-byte aligned,
+ * ttc_lqr_backward_cxt_workspace_bytes(problem) bytes (about 1 GiB for large batches; TTC_ERR_WORKSPACE otherwise).
+ * Allocates nothing; asynchronous on hip_stream. */
+size_t ttc_lqr_backward_cxt_workspace_bytes(const ttc_lqr_cxt_problem_t *problem);
+ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t *problem, const float *grad_u0,
+                                  const ttc_lqr_cxt_grads_t *grads, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
 /* The whole Test-Time Control block for n_tokens token features, each on its own (Sec. 4, "Hybrid with Memory
  * Layers", "Multi-Head Structure", "Contextualization", "Parameterization"), float32:
  *     h_0   = W_in LN(x_in) + b_in, split into H heads of d = 16 numbers;

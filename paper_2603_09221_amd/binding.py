@@ -26,7 +26,7 @@ EXPORTS = ("ttc_lqr_workspace_bytes", "ttc_lqr_solve", "ttc_lqr_solve_noalloc", 
            "ttc_lqr_cxt_rollout_workspace_bytes", "ttc_lqr_solve_tv_scan",
            "ttc_lqr_tv_scan_workspace_bytes", "ttc_lqr_tv_scan_values", "ttc_lqr_tv_scan_values_workspace_bytes",
            "ttc_lqr_backward", "ttc_lqr_backward_workspace_bytes",
-           "ttc_lqr_backward_tv", "ttc_lqr_backward_tv_workspace_bytes", "ttc_block_workspace_bytes", "ttc_block_forward",
+           "ttc_lqr_backward_tv", "ttc_lqr_backward_tv_workspace_bytes", "ttc_lqr_backward_cxt", "ttc_lqr_backward_cxt_workspace_bytes", "ttc_block_workspace_bytes", "ttc_block_forward",
            "ttc_status_string", "ttc_version")
 
 
@@ -71,6 +71,13 @@ class Solution(ctypes.Structure):
 class Grads(ctypes.Structure):
     _fields_ = [("gA", c_void_p), ("gB", c_void_p), ("gQ", c_void_p), ("gR", c_void_p), ("gQT", c_void_p),
                 ("gx0", c_void_p), ("info", c_void_p)]
+
+
+CXT_GRADS = ("gsA", "gsB", "gsQ", "gsQf", "grinv", "glgA", "glgB", "glgQ", "gx0", "gBbasis", "gQbasis", "info")
+
+
+class CxtGrads(ctypes.Structure):
+    _fields_ = [(k, c_void_p) for k in CXT_GRADS]
 
 
 class TtcError(RuntimeError):
@@ -134,6 +141,11 @@ def load():
     lib.ttc_lqr_backward_tv.restype = c_int
     lib.ttc_lqr_backward_tv.argtypes = [ctypes.POINTER(TvProblem), c_void_p, ctypes.POINTER(Grads), c_void_p, c_size_t,
                                         c_void_p]
+    lib.ttc_lqr_backward_cxt_workspace_bytes.restype = c_size_t
+    lib.ttc_lqr_backward_cxt_workspace_bytes.argtypes = [ctypes.POINTER(CxtProblem)]
+    lib.ttc_lqr_backward_cxt.restype = c_int
+    lib.ttc_lqr_backward_cxt.argtypes = [ctypes.POINTER(CxtProblem), c_void_p, ctypes.POINTER(CxtGrads), c_void_p, c_size_t,
+                                         c_void_p]
     lib.ttc_block_workspace_bytes.restype = c_size_t
     lib.ttc_block_workspace_bytes.argtypes = [ctypes.POINTER(Block)]
     lib.ttc_block_forward.restype = c_int
@@ -478,6 +490,33 @@ def ttc_lqr_backward_tv(A, B, Q, R, x0, grad_u0, *, out=None, workspace=None, st
     gr = _grads_struct(out)
     _check(lib.ttc_lqr_backward_tv(ctypes.byref(prob), c_void_p(grad_u0.data_ptr()), ctypes.byref(gr),
                                    c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr(stream)))
+    return out
+
+
+def ttc_lqr_backward_cxt(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T, grad_u0, *, out=None, workspace=None,
+                         stream=None):
+    """Gradients of a loss of u0 for n structured problems, from grad_u0 = dl/du0 (n, d) float32: gsA, grinv, glgA,
+    glgB, glgQ, gx0 (n, d), gsB, gsQ, gsQf (n, r), gBbasis, gQbasis (r, d, d) summed over the problems, info (n)."""
+    lib = load()
+    prob = make_cxt_problem(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x0, T)
+    n, d, r, dev = prob.n, prob.d, prob.r, sA.device
+    if grad_u0.dtype != torch.float32 or not grad_u0.is_contiguous() or tuple(grad_u0.shape) != (n, d):
+        raise ValueError("grad_u0 must be a contiguous (n, d) float32 tensor")
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = dict(out or {})
+    for k in ("gsA", "grinv", "glgA", "glgB", "glgQ", "gx0"):
+        out.setdefault(k, torch.empty((n, d), **f32))
+    for k in ("gsB", "gsQ", "gsQf"):
+        out.setdefault(k, torch.empty((n, r), **f32))
+    for k in ("gBbasis", "gQbasis"):
+        out.setdefault(k, torch.empty((r, d, d), **f32))
+    out.setdefault("info", torch.empty((n,), dtype=torch.int32, device=dev))
+    need = lib.ttc_lqr_backward_cxt_workspace_bytes(ctypes.byref(prob))
+    if workspace is None:
+        workspace = _scratch(need, dev, stream)
+    grads = CxtGrads(*(_ptr(out[k]) for k in CXT_GRADS))
+    _check(lib.ttc_lqr_backward_cxt(ctypes.byref(prob), _ptr(grad_u0), ctypes.byref(grads), c_void_p(workspace.data_ptr()),
+                                    workspace.numel(), _stream_ptr(stream)))
     return out
 
 

@@ -34,6 +34,7 @@ UNITS = [("ttc_api.hip", None),
          ("k_small.hip", None),
          ("k_tv_small.hip", None),
          ("k_cxt.hip", None),
+         ("k_cxt_bwd.hip", None),
          ("k_block.hip", None)]
 
 # Per (source, state size) compile flags: wavefronts of one 16-row block each (twice as many per problem) instead of

@@ -834,6 +834,82 @@ ttc_status_t ttc_lqr_backward_tv(const ttc_lqr_tv_problem_t* q, const float* gra
                                                                                                      : TTC_ERR_DEVICE;
 }
 
+// ---- backward pass of the structured problems ------------------------------------------------------------------
+namespace {
+// problems per chunk: the dense steps and their gradients take 8 T matrices of 1 KiB per problem; about 1 GiB per chunk
+long long cxt_bwd_chunk(long long n, int T) {
+  long long ch = (1LL << 30) / (8LL * T * 1024);
+  ch = ch < 256 ? 256 : ch;
+  return n < ch ? n : ch;
+}
+size_t cxt_bwd_floats_per_problem(int T) { return (size_t)8 * T * 256 + 16 + 768; }
+}  // namespace
+
+size_t ttc_lqr_backward_cxt_workspace_bytes(const ttc_lqr_cxt_problem_t* q) {
+  if (!q || q->n < 0 || q->T < 1 || q->d != 16) return 0;
+  const size_t chunk = (size_t)cxt_bwd_chunk(q->n, q->T);
+  return round64(chunk * cxt_bwd_floats_per_problem(q->T)) * sizeof(float) + backward_ws_bytes(16, q->T, false);
+}
+
+ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* grad_u0, const ttc_lqr_cxt_grads_t* gr,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const ttc_status_t sv = validate_cxt(q);
+  if (sv != TTC_OK) return sv;
+  if (!gr || !gr->gBbasis || !gr->gQbasis) return TTC_ERR_INVALID_ARG;
+  float* const outs[] = {gr->gsA, gr->gsB, gr->gsQ, gr->gsQf, gr->grinv, gr->glgA, gr->glgB, gr->glgQ, gr->gx0,
+                         gr->gBbasis, gr->gQbasis};
+  for (const float* ptr : outs)
+    if ((q->n > 0 && !ptr) || !ttc::aligned_ptr(ptr, 4)) return TTC_ERR_INVALID_ARG;  // an empty batch has no per-problem arrays
+  if (q->n > 0 && !grad_u0) return TTC_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // the sums over the problems start from zero (a fill kernel: also safe under stream capture)
+  if (ttc::launch_zero_floats(gr->gBbasis, (long long)q->r * 256, st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (ttc::launch_zero_floats(gr->gQbasis, (long long)q->r * 256, st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (q->n == 0) return TTC_OK;
+  if (!workspace || !ttc::aligned_ptr(workspace, 16) || workspace_bytes < ttc_lqr_backward_cxt_workspace_bytes(q))
+    return TTC_ERR_WORKSPACE;
+  const int T = q->T;
+  const bool bf16 = q->in_dtype == TTC_BF16;
+  const long long chunk = cxt_bwd_chunk(q->n, T);
+  float* ws = static_cast<float*>(workspace);
+  const size_t mat = (size_t)chunk * T * 256;
+  ttc::CxtBackwardArgs a;
+  fill_cxt_args(a.c, q);
+  a.dA = ws; a.dB = ws + mat; a.dQ = ws + 2 * mat; a.dR = ws + 3 * mat;
+  a.gA = ws + 4 * mat; a.gB = ws + 5 * mat; a.gQ = ws + 6 * mat; a.gR = ws + 7 * mat;
+  a.x0f = ws + 8 * mat;
+  a.keep = a.x0f + (size_t)chunk * 16;
+  float* const bws = ws + round64((size_t)chunk * cxt_bwd_floats_per_problem(T));  // the backward kernel's own workspace
+  a.gsA = gr->gsA; a.gsB = gr->gsB; a.gsQ = gr->gsQ; a.gsQf = gr->gsQf; a.grinv = gr->grinv;
+  a.glgA = gr->glgA; a.glgB = gr->glgB; a.glgQ = gr->glgQ;
+  a.gBbasis = gr->gBbasis; a.gQbasis = gr->gQbasis;
+  const long long per_problem_grid = 16LL * ttc::cu_count();  // workgroups of 256 threads, one problem at a time each
+  const long long gb = ttc::grid_blocks(ttc::KIND_BACKWARD, 16, false);
+  for (long long first = 0; first < q->n; first += chunk) {
+    a.first = first;
+    a.count = q->n - first < chunk ? q->n - first : chunk;
+    const dim3 pgrid((unsigned)(a.count < per_problem_grid ? a.count : per_problem_grid));
+    if (ttc::launch_cxt_expand(a, bf16, pgrid, st) != hipSuccess) return TTC_ERR_DEVICE;
+    ttc::BackwardArgs b;
+    b.r.n = a.count; b.r.T = T; b.r.flags = 0;
+    b.r.A = a.dA; b.r.B = a.dB; b.r.Q = a.dQ; b.r.R = a.dR; b.r.QT = nullptr; b.r.x0 = a.x0f;
+    b.r.sA = b.r.sB = b.r.sQ = b.r.sR = (long long)T * 256; b.r.sQT = 0; b.r.sx0 = 16;
+    b.r.U = b.r.X = b.r.cost = nullptr;
+    b.r.info = gr->info ? gr->info + first : nullptr;
+    b.r.ws = bws;
+    b.tA = b.tB = b.tQ = b.tR = 256;
+    b.g = grad_u0 + first * 16; b.sg = 16;
+    b.gA = a.gA; b.gB = a.gB; b.gQ = a.gQ; b.gR = a.gR; b.gQT = nullptr; b.gx0 = gr->gx0 + first * 16;
+    b.sum_steps = 0;
+    const dim3 bgrid((unsigned)(a.count < gb ? a.count : gb));
+    if (ttc::run_backward(b, 16, false, bgrid, st) != hipSuccess) return TTC_ERR_DEVICE;
+    if (ttc::launch_cxt_contract(a, bf16, pgrid, st) != hipSuccess) return TTC_ERR_DEVICE;
+    if (ttc::launch_cxt_basis(a, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;
+  }
+  return TTC_OK;
+}
+
+
 const char* ttc_status_string(ttc_status_t status) {
   switch (status) {
     case TTC_OK: return "ok";

@@ -83,6 +83,19 @@ struct CxtRolloutArgs {
   float *U, *X, *cost;
 };
 
+// ---- backward pass of the structured problems (ttc_cxt_backward.hpp)
+struct CxtBackwardArgs {
+  CxtArgs c;             // the problems (inputs only; c.s.n = all problems)
+  long long first;       // the chunk: problems first .. first + count - 1
+  long long count;
+  float *dA, *dB, *dQ, *dR;      // (count, T, 256) each: the dense steps
+  float* x0f;                    // (count, 16): x0 widened to float32
+  float *gA, *gB, *gQ, *gR;      // (count, T, 256) each: the per-step gradients
+  float* keep;                   // (count, 3, 256): dl/dBbar, dl/dQbar, dl/dQ_T
+  float *gsA, *gsB, *gsQ, *gsQf, *grinv, *glgA, *glgB, *glgQ;  // the caller's arrays, (n, 16) or (n, r)
+  float *gBbasis, *gQbasis;      // the caller's arrays, (r, 256), accumulated
+};
+
 // ---- the block around the structured solver (ttc_block.hpp)
 struct LnStatsArgs {
   const float* X;  // (M, L) row-major

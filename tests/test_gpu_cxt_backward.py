@@ -1,0 +1,86 @@
+"""GPU parity of the backward pass of the structured, contextualised problems (ttc_lqr_backward_cxt) against the CPU
+float64 oracle (oracle.lqr_grad_oracle.contextual_gradients: Thm 3.2's per-step gradients of the dense steps, then
+the chain rule to the parameterisation of Sec. 4), on the same seeded inputs.  Tolerance as for the dense gradients:
+2e-5 for float32 inputs, 2e-3 for bfloat16 inputs, per problem, the larger of the 2-norm and the element-wise measure.
+The gradients of the coefficients sB, sQ, sQf are inner products of 256 terms of both signs (with one basis matrix
+a single such number per problem, which may nearly cancel): their error is bounded relative to the terms, not to the
+sum, so they are measured against the largest entry of the whole array, as are the basis gradients (sums over the
+problems)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lqr_grad_oracle as go
+from paper_2603_09221_amd import binding, synth
+from tests.parity import rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+KEYS = synth.ContextualBatch.PER_PROBLEM + ("Bbasis", "Qbasis", "x0")
+PER_PROBLEM = ("gsA", "gsB", "gsQ", "gsQf", "grinv", "glgA", "glgB", "glgQ", "gx0")
+
+
+def run(b, seed=0, **kw):
+    g = torch.randn((b.n, 16), generator=torch.Generator(device=DEV).manual_seed(seed), device=DEV)
+    out = binding.ttc_lqr_backward_cxt(*(getattr(b, k) for k in KEYS), b.T, g, **kw)
+    torch.cuda.synchronize()
+    return g, out
+
+
+def check(b, tol, seed=0):
+    g, out = run(b, seed)
+    assert int(out["info"].abs().max()) == 0
+    ref = go.contextual_gradients(*b.numpy64(), b.T, g.cpu().double().numpy())
+    errs = {k: float(rel_err(out[k].cpu().numpy(), ref[k]).max()) for k in PER_PROBLEM if k not in ("gsB", "gsQ", "gsQf")}
+    for k in ("gsB", "gsQ", "gsQf", "gBbasis", "gQbasis"):
+        got, want = out[k].cpu().double().numpy(), ref[k]
+        errs[k] = float(np.abs(got - want).max() / max(np.abs(want).max(), 1e-30))   # an all-zero gradient must be exactly zero
+    print({k: f"{v:.1e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= tol, (k, v)
+    return out
+
+
+@pytest.mark.parametrize("n,r,T", [(1, 16, 1), (7, 16, 8), (300, 16, 8), (130, 4, 5), (66, 64, 3), (41, 1, 2), (20, 16, 40)])
+def test_ranks_horizons_and_batches(n, r, T):
+    check(synth.make_contextual_batch(n, 16, r, T, seed=n + r + T, device=DEV), 2e-5)
+
+
+def test_bf16_inputs():
+    check(synth.make_contextual_batch(150, 16, 16, 8, seed=3, device=DEV, dtype="bf16"), 2e-3)
+
+
+def test_several_chunks_give_what_one_chunk_gives():
+    # at this horizon a chunk holds 256 problems: five chunks, the last one ragged
+    b = synth.make_contextual_batch(1100, 16, 8, 600, seed=5, device=DEV)
+    _, out = run(b, seed=1)
+    sub = b.take(slice(600, 900))
+    g = torch.randn((b.n, 16), generator=torch.Generator(device=DEV).manual_seed(1), device=DEV)
+    one = binding.ttc_lqr_backward_cxt(*(getattr(sub, k) for k in KEYS), sub.T, g[600:900].contiguous())
+    torch.cuda.synchronize()
+    for k in PER_PROBLEM:
+        assert torch.equal(out[k][600:900], one[k]), k
+    assert int(out["info"].abs().max()) == 0
+
+
+def test_called_twice_the_basis_gradients_do_not_accumulate():
+    b = synth.make_contextual_batch(500, 16, 16, 6, seed=7, device=DEV)
+    _, first = run(b)
+    keep = {k: first[k].clone() for k in ("gBbasis", "gQbasis")}
+    _, second = run(b, out=first)
+    for k in keep:
+        assert float((second[k] - keep[k]).abs().max() / keep[k].abs().max()) <= 1e-5, k
+
+
+def test_workspace_and_arguments_are_checked():
+    b = synth.make_contextual_batch(9, 16, 16, 4, seed=2, device=DEV)
+    g = torch.zeros((9, 16), device=DEV)
+    with pytest.raises(binding.TtcError) as e:
+        binding.ttc_lqr_backward_cxt(*(getattr(b, k) for k in KEYS), b.T, g, workspace=torch.empty(1024, dtype=torch.uint8, device=DEV))
+    assert e.value.status == binding.TTC_ERR_WORKSPACE
+    with pytest.raises(ValueError):
+        binding.ttc_lqr_backward_cxt(*(getattr(b, k) for k in KEYS), b.T, g[:5])
+    e0 = synth.make_contextual_batch(0, 16, 16, 4, seed=2, device=DEV)
+    out = binding.ttc_lqr_backward_cxt(*(getattr(e0, k) for k in KEYS), e0.T, torch.zeros((0, 16), device=DEV))
+    torch.cuda.synchronize()
+    assert out["gsA"].shape == (0, 16) and float(out["gBbasis"].abs().max()) == 0.0
