@@ -7,7 +7,7 @@ Prints ONE JSON line: problems/s plus a roofline object for the solve kernel (fp
 oracle timed on the host cores on a bounded sample of the same inputs.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config llm_adapter] [--n N] [--rebase-every k]
-                    [--path symplectic|doubling|tv|cxt|scan|bwd|rollout|grid|block]
+                    [--path symplectic|doubling|tv|cxt|scan|bwd|rollout|grid|block|cxtbwd]
 
 The headline value is the paper's sequential symplectic product (--path symplectic, the default); the same
 inputs are also timed on the squaring path and reported under "other_path".
@@ -326,6 +326,75 @@ def bench_block(args):
     print(json.dumps(res))
 
 
+def bench_cxt_bwd(args):
+    """Backward pass of the structured layer shape (ttc_lqr_backward_cxt): d = 16, r = 16, horizon 8, 16 heads x 8192
+    tokens.  The path writes the dense steps of a chunk of problems and their per-step gradients through HBM (8 T
+    matrices of 1 KiB per problem) around the time-heterogeneous backward kernel, so its bound is the memory system."""
+    import numpy as np
+    import torch
+    from paper_2603_09221_amd import binding, synth
+    from paper_2603_09221_amd.errors import rel_err
+
+    d, r, T = 16, 16, args.horizon or 8
+    n = args.n or 16 * 8192
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    lib = binding.load()
+    b = synth.make_contextual_batch(n, d, r, T, seed=0, device=dev)
+    keys = synth.ContextualBatch.PER_PROBLEM + ("Bbasis", "Qbasis", "x0")
+    ins = [getattr(b, k) for k in keys]
+    g = torch.randn((n, d), generator=torch.Generator(device=dev).manual_seed(1), device=dev)
+    out = binding.ttc_lqr_backward_cxt(*ins, T, g)          # allocates the outputs once
+    prob = binding.make_cxt_problem(*ins, T)
+    ws = torch.empty(lib.ttc_lqr_backward_cxt_workspace_bytes(prob), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    step = lambda: binding.ttc_lqr_backward_cxt(*ins, T, g, out=out, workspace=ws, stream=stream)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record(stream)
+        step()
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps
+    kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+    kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+    assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
+    # bytes the path moves by construction: the dense steps written and read, the per-step gradients written and read
+    path_bytes = n * (2 * 8 * T * d * d * 4 + (6 * d + 3 * r) * 4 + (6 * d + 3 * r) * 4 + 2 * 3 * d * d * 4)
+    achieved = path_bytes / kernel_s / 1e9
+    res = {
+        "metric": "LQR backward passes/sec at d=%d, T=%d, structured parameters" % (d, T),
+        "value": n / wall, "unit": "problems/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "ttc_layer_d16", "problems": n, "d": d, "m": d, "r": r, "T": T, "input_dtype": "f32",
+                   "path": "cxtbwd", "outputs": "gsA,gsB,gsQ,gsQf,grinv,glgA,glgB,glgQ,gx0,gBbasis,gQbasis"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
+                     "traffic": None,
+                     "kernel": "ttc_lqr_backward_cxt (cxt_expand, backward_kernel<16>, cxt_contract, cxt_basis per chunk)",
+                     "kernel_ms": kernel_s * 1e3, **spread(kernel_ms),
+                     "alg_bytes_per_launch": path_bytes,
+                     "alg_flops_per_problem": alg_flops_bwd(d, T),
+                     "alg_TFLOPs": alg_flops_bwd(d, T) * n / kernel_s / 1e12},
+    }
+    if not args.no_cpu:
+        from oracle import lqr_grad_oracle
+        sample = min(n, args.cpu_sample or 2048)
+        sub = b.take(slice(0, sample))
+        t1 = time.perf_counter()
+        ref = lqr_grad_oracle.contextual_gradients(*sub.numpy64(), T, g[:sample].cpu().double().numpy())
+        dt = time.perf_counter() - t1
+        errs = {k: float(rel_err(out[k][:sample].cpu().numpy(), ref[k]).max()) for k in ("gsA", "grinv", "glgA", "glgB", "glgQ", "gx0")}
+        res["cpu_baseline"] = {"value": sample / dt, "unit": "problems/s", "cores": 1, "kind": "oracle", "cpu_model": cpu_model(),
+                               "sample": "first %d problems of the same workload, float64 numpy, %.1f s wall" % (sample, dt)}
+        res["parity"] = {"sample": sample, "max_rel_err": errs, "tolerance": 2e-5}
+    print(json.dumps(res))
+
+
 def bench_grid(args):
     """The paper's solver benchmark grid (App. "Efficiency Benchmark": d = 16, horizon 2^4 .. 2^11 at batch 1024, batch
     2^4 .. 2^13 at horizon 64), forward and backward, time-heterogeneous dense steps: milliseconds per call (median
@@ -505,7 +574,7 @@ def main():
     ap.add_argument("--config", default="llm_adapter")
     ap.add_argument("--chunk", type=int, default=None, help="problems per launch (default: the whole workload, or "
                     "the largest power-of-two split whose outputs fit the card)")
-    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd", "rollout", "grid", "block"),
+    ap.add_argument("--path", default="symplectic", choices=("symplectic", "doubling", "tv", "cxt", "scan", "bwd", "rollout", "grid", "block", "cxtbwd"),
                     help="symplectic: the paper's reverse symplectic iteration with re-basing (headline); "
                          "doubling: the long-horizon path, the same product formed by squaring; "
                          "tv: time-heterogeneous parameters (ttc_lqr_solve_tv) on the configuration's shape, "
@@ -517,7 +586,8 @@ def main():
                          "131072 problems); grid: the paper's solver benchmark grid at d = 16, forward and backward "
                          "(prints a table, not a bench line); rollout: ttc_lqr_rollout (all T controls, states and the cost) "
                          "on the configuration's shape (default up to 16384 problems); block: the whole TTC block (ttc_block_forward) at "
-                         "4096 features, 16 heads of d = 16, 65536 tokens, --config ignored")
+                         "4096 features, 16 heads of d = 16, 65536 tokens, --config ignored; cxtbwd: the backward pass of the structured "
+                         "problems (ttc_lqr_backward_cxt), d = 16, r = 16, 131072 problems, --config ignored")
     ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt (default 8) and scan (default 2048) paths")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra timing of the other path")
     ap.add_argument("--n", type=int, default=None, help="number of problems (default: the whole configuration)")
@@ -535,6 +605,8 @@ def main():
 
     if args.path == "block":
         return bench_block(args)
+    if args.path == "cxtbwd":
+        return bench_cxt_bwd(args)
     if args.path == "cxt":
         return bench_cxt(args)
     if args.path == "scan":

@@ -124,14 +124,17 @@ __global__ void __launch_bounds__(256) cxt_contract_kernel(const CxtBackwardArgs
     keep[256 + e] = dQbar;
     keep[512 + e] = dQf;
     __syncthreads();
-    // the 3 r inner products with the basis matrices: thread (which, k) walks its matrix
-    for (int o = e; o < 3 * r; o += 256) {
-      const int which = o / r, k = o % r;
+    // the 3 r inner products with the basis matrices: a wavefront per product, four entries per lane
+    for (int o = e >> 6; o < 3 * r; o += 4) {
+      const int which = o / r, k = o % r, lane = e & 63;
       const TIn* basis = which == 0 ? Bb : Qb;
       float s = 0.f;
-      for (int x = 0; x < 256; ++x) s = __builtin_fmaf(ld1<TIn>(basis, (long)k * 256 + x), M[which][x], s);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) s = __builtin_fmaf(ld1<TIn>(basis, (long)k * 256 + lane + 64 * x), M[which][lane + 64 * x], s);
+#pragma unroll
+      for (int sh = 1; sh < 64; sh <<= 1) s += __shfl_xor(s, sh, 64);
       float* dst = which == 0 ? a.gsB : which == 1 ? a.gsQ : a.gsQf;
-      dst[p * r + k] = s;
+      if (lane == 0) dst[p * r + k] = s;
     }
   }
 }
@@ -139,7 +142,7 @@ __global__ void __launch_bounds__(256) cxt_contract_kernel(const CxtBackwardArgs
 // gBbasis[k] += sum_p sB[p][k] dBbar[p], gQbasis[k] += sum_p (sQ[p][k] dQbar[p] + sQf[p][k] dQ_T[p]) over a slab of
 // the chunk's problems per workgroup; thread e owns entry e of every basis matrix, the sums of a slab are added to the
 // caller's arrays with one atomic addition per entry (the order of the slabs, and with it the last bits, may vary).
-constexpr int CXT_BASIS_SLAB = 128;
+constexpr int CXT_BASIS_SLAB = 32;
 template <typename TIn>
 __global__ void __launch_bounds__(256) cxt_basis_kernel(const CxtBackwardArgs a) {
   const int e = threadIdx.x;
