@@ -348,6 +348,12 @@ def bench_cxt_bwd(args):
     prob = binding.make_cxt_problem(*ins, T)
     ws = torch.empty(lib.ttc_lqr_backward_cxt_workspace_bytes(prob), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+    if args.calib_copy_mib:
+        src = torch.ones((args.calib_copy_mib << 18,), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     step = lambda: binding.ttc_lqr_backward_cxt(*ins, T, g, out=out, workspace=ws, stream=stream)
     for _ in range(args.warmup):
         step()
@@ -374,7 +380,7 @@ def bench_cxt_bwd(args):
         "config": {"workload": "ttc_layer_d16", "problems": n, "d": d, "m": d, "r": r, "T": T, "input_dtype": "f32",
                    "path": "cxtbwd", "outputs": "gsA,gsB,gsQ,gsQf,grinv,glgA,glgB,glgQ,gx0,gBbasis,gQbasis"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
-                     "traffic": None,
+                     "traffic": measured_traffic("ttc_layer_d16_T%d" % T, "cxtbwd", n),
                      "kernel": "ttc_lqr_backward_cxt (cxt_expand, backward_kernel<16>, cxt_contract, cxt_basis per chunk)",
                      "kernel_ms": kernel_s * 1e3, **spread(kernel_ms),
                      "alg_bytes_per_launch": path_bytes,
