@@ -337,7 +337,11 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t *problem, const fl
  *   W_head (H, 80 + r, 16), b_head (H, 80 + r): rows sA, rinv, lgA, lgB, lgQ (16 each), then sQf (r);
  *   W_shared (2r, 16), b_shared (2r): rows sB (r), then sQ (r);
  *   Bbasis, Qc (r, 16, 16);  ln_out_gain, ln_out_offset (H*16);  W_out (C, H*16), b_out (C).
- * d other than 16, r above 64 or not a multiple of 4, C not a multiple of 4: TTC_ERR_UNSUPPORTED. */
+ * d other than 16, r above 64 or not a multiple of 4, C not a multiple of 4: TTC_ERR_UNSUPPORTED.
+ * With TTC_BLOCK_FLAG_BF16 in flags the token features x_in, x_out and the two projection matrices W_in, W_out are
+ * bfloat16 (everything else stays float32): the projections then run on the bfloat16 matrix cores with float32
+ * accumulation, LN(x) rounded to bfloat16 on the way in; C has to be a multiple of 8. */
+#define TTC_BLOCK_FLAG_BF16 1
 typedef struct {
   int64_t n_tokens;
   int32_t C;     /* width of a token feature */
@@ -345,19 +349,23 @@ typedef struct {
   int32_t d;     /* state and control size of a head: 16 */
   int32_t r;     /* basis matrices per group */
   int32_t T;     /* horizon, >= 1 */
-  int32_t flags; /* 0 */
+  int32_t flags; /* 0 or TTC_BLOCK_FLAG_BF16 */
   float eps;     /* of both layer normalisations, > 0 */
-  const float *ln_in_gain, *ln_in_offset, *W_in, *b_in, *W_head, *b_head, *W_shared, *b_shared, *Bbasis, *Qc,
-      *ln_out_gain, *ln_out_offset, *W_out, *b_out;
+  const float *ln_in_gain, *ln_in_offset;
+  const void *W_in; /* float32, or bfloat16 with TTC_BLOCK_FLAG_BF16 */
+  const float *b_in, *W_head, *b_head, *W_shared, *b_shared, *Bbasis, *Qc, *ln_out_gain, *ln_out_offset;
+  const void *W_out; /* as W_in */
+  const float *b_out;
 } ttc_block_t;
 
-/* x_in (n_tokens, C) DEVICE, read; x_out (n_tokens, C) DEVICE, written, may be x_in itself.  Optional DEVICE outputs
+/* x_in (n_tokens, C) DEVICE, read; x_out (n_tokens, C) DEVICE, written, may be x_in itself; float32, or bfloat16 with
+ * TTC_BLOCK_FLAG_BF16.  Optional DEVICE float32 outputs
  * (NULL to skip): h0 (n_tokens, H*16); o (n_tokens, H*16); info (n_tokens*H), as ttc_lqr_solve_cxt reports it for
  * the problem of token t, head h at [t*H + h] (a problem that broke down gives NaN in its token's x_out).
  * workspace: DEVICE, 16-byte aligned, ttc_block_workspace_bytes(block) bytes (TTC_ERR_WORKSPACE otherwise; the size
  * depends on n_tokens, H, r only).  Seven launches on hip_stream; allocates nothing; asynchronous. */
 size_t ttc_block_workspace_bytes(const ttc_block_t *block);
-ttc_status_t ttc_block_forward(const ttc_block_t *block, const float *x_in, float *x_out, float *h0, float *o,
+ttc_status_t ttc_block_forward(const ttc_block_t *block, const void *x_in, void *x_out, float *h0, float *o,
                                int32_t *info, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code. */

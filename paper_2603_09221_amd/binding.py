@@ -520,13 +520,19 @@ def ttc_lqr_backward_cxt(sA, sB, sQ, sQf, rinv, lgA, lgB, lgQ, Bbasis, Qbasis, x
     return out
 
 
+TTC_BLOCK_FLAG_BF16 = 1
+
+
 def make_block(weights, n_tokens, T, eps=1e-5) -> Block:
-    """Descriptor of a TTC block from a dict of float32 device tensors (keys BLOCK_WEIGHTS); shapes are checked here,
+    """Descriptor of a TTC block from a dict of device tensors (keys BLOCK_WEIGHTS), float32 except that W_in and W_out
+    may both be bfloat16 (then the block takes bfloat16 token features: TTC_BLOCK_FLAG_BF16); shapes are checked here,
     values never touched."""
     w = weights
+    bf16 = w["W_in"].dtype == torch.bfloat16
     for k in BLOCK_WEIGHTS:
-        if w[k].dtype != torch.float32 or not w[k].is_contiguous():
-            raise ValueError("block weight %s must be a contiguous float32 tensor" % k)
+        want_dtype = torch.bfloat16 if bf16 and k in ("W_in", "W_out") else torch.float32
+        if w[k].dtype != want_dtype or not w[k].is_contiguous():
+            raise ValueError("block weight %s must be a contiguous %s tensor" % (k, want_dtype))
     r, d = int(w["Bbasis"].shape[0]), int(w["Bbasis"].shape[-1])
     HD, C = (int(v) for v in w["W_in"].shape)
     H = HD // d
@@ -537,22 +543,23 @@ def make_block(weights, n_tokens, T, eps=1e-5) -> Block:
     for k, shape in want.items():
         if tuple(w[k].shape) != shape:
             raise ValueError("block weight %s has shape %s, expected %s" % (k, tuple(w[k].shape), shape))
-    return Block(n_tokens, C, H, d, r, T, 0, eps, *(w[k].data_ptr() for k in BLOCK_WEIGHTS))
+    return Block(n_tokens, C, H, d, r, T, TTC_BLOCK_FLAG_BF16 if bf16 else 0, eps, *(w[k].data_ptr() for k in BLOCK_WEIGHTS))
 
 
 def ttc_block_forward(x_in, weights, T, *, eps=1e-5, want_h0=False, want_o=False, out=None, workspace=None, stream=None):
-    """x_out (n_tokens, C) of the whole TTC block for token features x_in (n_tokens, C) float32 on the device; info
-    (n_tokens, H); optionally the intermediate h0 and o (n_tokens, H*d)."""
+    """x_out (n_tokens, C) of the whole TTC block for token features x_in (n_tokens, C) on the device, float32 or
+    (with bfloat16 W_in, W_out) bfloat16; info (n_tokens, H); optionally the intermediate h0 and o (n_tokens, H*d), float32."""
     lib = load()
-    if x_in.dtype != torch.float32 or not x_in.is_contiguous() or x_in.dim() != 2:
-        raise ValueError("x_in must be a contiguous (n_tokens, C) float32 tensor")
     n, dev = int(x_in.shape[0]), x_in.device
     blk = make_block(weights, n, T, eps)
+    xdt = torch.bfloat16 if blk.flags & TTC_BLOCK_FLAG_BF16 else torch.float32
+    if x_in.dtype != xdt or not x_in.is_contiguous() or x_in.dim() != 2:
+        raise ValueError("x_in must be a contiguous (n_tokens, C) %s tensor" % xdt)
     if int(x_in.shape[1]) != blk.C:
         raise ValueError("x_in has %d features, the block expects %d" % (x_in.shape[1], blk.C))
     out = dict(out or {})
     f32 = dict(dtype=torch.float32, device=dev)
-    out.setdefault("x_out", torch.empty((n, blk.C), **f32))
+    out.setdefault("x_out", torch.empty((n, blk.C), dtype=xdt, device=dev))
     if want_h0:
         out.setdefault("h0", torch.empty((n, blk.H * blk.d), **f32))
     if want_o:

@@ -652,10 +652,12 @@ BlockLayout block_layout(long long M, int H, int r) {
   return L;
 }
 ttc_status_t validate_block(const ttc_block_t* b) {
-  if (!b || b->n_tokens < 0 || b->C < 1 || b->H < 1 || b->d < 1 || b->r < 1 || b->T < 1 || b->flags != 0)
+  if (!b || b->n_tokens < 0 || b->C < 1 || b->H < 1 || b->d < 1 || b->r < 1 || b->T < 1 ||
+      (b->flags & ~TTC_BLOCK_FLAG_BF16) != 0)
     return TTC_ERR_INVALID_ARG;
   if (!(b->eps > 0.f)) return TTC_ERR_INVALID_ARG;
   if (b->d != 16 || b->r > ttc::CXT_RMAX || b->r % 4 != 0 || b->C % 4 != 0) return TTC_ERR_UNSUPPORTED;
+  if ((b->flags & TTC_BLOCK_FLAG_BF16) && b->C % 8 != 0) return TTC_ERR_UNSUPPORTED;
   if ((long long)b->n_tokens * b->H > (1LL << 40)) return TTC_ERR_INVALID_ARG;
   return TTC_OK;
 }
@@ -666,7 +668,7 @@ size_t ttc_block_workspace_bytes(const ttc_block_t* b) {
   return block_layout(b->n_tokens, b->H, b->r).total * sizeof(float);
 }
 
-ttc_status_t ttc_block_forward(const ttc_block_t* b, const float* x_in, float* x_out, float* h0, float* o, int32_t* info,
+ttc_status_t ttc_block_forward(const ttc_block_t* b, const void* x_in, void* x_out, float* h0, float* o, int32_t* info,
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   const ttc_status_t sv = validate_block(b);
   if (sv != TTC_OK) return sv;
@@ -687,10 +689,18 @@ ttc_status_t ttc_block_forward(const ttc_block_t* b, const float* x_in, float* x
   float* const op = o ? o : ws + L.o;
 
   // h_0 = W_in LN(x_in) + b_in
+  const bool bf16 = (b->flags & TTC_BLOCK_FLAG_BF16) != 0;
   ttc::LnStatsArgs s1{x_in, ws + L.stats_in, M, b->C, b->eps};
-  if (ttc::launch_ln_stats(s1, st) != hipSuccess) return TTC_ERR_DEVICE;
-  ttc::GemmLnArgs g1{x_in, ws + L.stats_in, b->ln_in_gain, b->ln_in_offset, b->W_in, b->b_in, nullptr, h0p, M, HD, b->C};
-  if (ttc::launch_gemm_ln(g1, st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (ttc::launch_ln_stats(s1, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (bf16) {
+    ttc::GemmLnBf16Args g1{x_in, ws + L.stats_in, b->ln_in_gain, b->ln_in_offset, static_cast<const uint16_t*>(b->W_in),
+                           b->b_in, nullptr, h0p, M, HD, b->C};
+    if (ttc::launch_gemm_ln_bf16(g1, true, false, st) != hipSuccess) return TTC_ERR_DEVICE;
+  } else {
+    ttc::GemmLnArgs g1{static_cast<const float*>(x_in), ws + L.stats_in, b->ln_in_gain, b->ln_in_offset,
+                       static_cast<const float*>(b->W_in), b->b_in, nullptr, h0p, M, HD, b->C};
+    if (ttc::launch_gemm_ln(g1, st) != hipSuccess) return TTC_ERR_DEVICE;
+  }
   // the contextualisation maps and the Q basis
   ttc::CxtMapsArgs c;
   c.H0 = h0p;
@@ -718,9 +728,16 @@ ttc_status_t ttc_block_forward(const ttc_block_t* b, const float* x_in, float* x
   if (run_cxt(a, false, st) != hipSuccess) return TTC_ERR_DEVICE;
   // x_out = x_in + W_out LN(o) + b_out
   ttc::LnStatsArgs s2{op, ws + L.stats_out, M, HD, b->eps};
-  if (ttc::launch_ln_stats(s2, st) != hipSuccess) return TTC_ERR_DEVICE;
-  ttc::GemmLnArgs g2{op, ws + L.stats_out, b->ln_out_gain, b->ln_out_offset, b->W_out, b->b_out, x_in, x_out, M, b->C, HD};
-  if (ttc::launch_gemm_ln(g2, st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (ttc::launch_ln_stats(s2, false, st) != hipSuccess) return TTC_ERR_DEVICE;
+  if (bf16) {
+    ttc::GemmLnBf16Args g2{op, ws + L.stats_out, b->ln_out_gain, b->ln_out_offset, static_cast<const uint16_t*>(b->W_out),
+                           b->b_out, static_cast<const uint16_t*>(x_in), x_out, M, b->C, HD};
+    if (ttc::launch_gemm_ln_bf16(g2, false, true, st) != hipSuccess) return TTC_ERR_DEVICE;
+  } else {
+    ttc::GemmLnArgs g2{op, ws + L.stats_out, b->ln_out_gain, b->ln_out_offset, static_cast<const float*>(b->W_out),
+                       b->b_out, static_cast<const float*>(x_in), static_cast<float*>(x_out), M, b->C, HD};
+    if (ttc::launch_gemm_ln(g2, st) != hipSuccess) return TTC_ERR_DEVICE;
+  }
   return TTC_OK;
 }
 

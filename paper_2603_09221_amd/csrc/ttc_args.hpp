@@ -98,7 +98,7 @@ struct CxtBackwardArgs {
 
 // ---- the block around the structured solver (ttc_block.hpp)
 struct LnStatsArgs {
-  const float* X;  // (M, L) row-major
+  const void* X;   // (M, L) row-major, float32 or bfloat16
   float* stats;    // (M, 2): mean, 1 / sqrt(biased variance + eps)
   long long M;
   int L;           // multiple of 4
@@ -116,6 +116,21 @@ struct GemmLnArgs {
   float* Y;             // (M, N)
   long long M;
   int N, K;             // multiples of 4
+};
+
+// the bfloat16 variant of the projections (the block's TTC_BLOCK_FLAG_BF16): X float32 or bfloat16, W bfloat16,
+// Res bfloat16 or NULL, Y float32 or bfloat16 (bfloat16 values are stored as uint16_t)
+struct GemmLnBf16Args {
+  const void* X;        // (M, K): element type by the kernel's template argument
+  const float* stats;   // (M, 2)
+  const float* gain;    // (K) float32
+  const float* offset;  // (K) float32
+  const uint16_t* W;    // (N, K) bfloat16
+  const float* bias;    // (N) float32 or NULL
+  const uint16_t* Res;  // (M, N) bfloat16 or NULL (may be Y itself)
+  void* Y;              // (M, N): element type by the kernel's template argument
+  long long M;
+  int N, K;             // multiples of 8
 };
 
 struct CxtMapsArgs {

@@ -16,16 +16,38 @@ namespace ttc {
 
 typedef float blk_floatx4 __attribute__((ext_vector_type(4)));
 
-// mean and reciprocal standard deviation of every row, one wavefront per row, two passes over the row (the second
-// one reads what the first has just brought into the caches): no cancellation whatever the row's mean
+// mean and reciprocal standard deviation of every row (float32 or bfloat16), one wavefront per row, two passes over
+// the row (the second one reads what the first has just brought into the caches): no cancellation whatever the mean
+typedef unsigned short blk_u16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short blk_u16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 blk_bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ unsigned short f32_to_bf16(float x) {  // round to nearest, ties to even (the hardware conversion)
+  return __builtin_bit_cast(unsigned short, static_cast<__bf16>(x));
+}
+// four consecutive elements of a float32 or bfloat16 row, widened
+template <typename T>
+__device__ __forceinline__ blk_floatx4 blk_ld4(const T* p, long long i);
+template <>
+__device__ __forceinline__ blk_floatx4 blk_ld4<float>(const float* p, long long i) {
+  return *reinterpret_cast<const blk_floatx4*>(p + i);
+}
+template <>
+__device__ __forceinline__ blk_floatx4 blk_ld4<unsigned short>(const unsigned short* p, long long i) {
+  const blk_u16x4 v = *reinterpret_cast<const blk_u16x4*>(p + i);
+  return blk_floatx4{bf16_to_f32(v[0]), bf16_to_f32(v[1]), bf16_to_f32(v[2]), bf16_to_f32(v[3])};
+}
+
+template <typename TX>
 __global__ void __launch_bounds__(256) ln_stats_kernel(const LnStatsArgs p) {
   const int lane = threadIdx.x & 63;
   const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= p.M) return;
-  const float* x = p.X + row * p.L;
+  const TX* x = reinterpret_cast<const TX*>(p.X) + row * p.L;
   float s = 0.f;
   for (int k = 4 * lane; k < p.L; k += 256) {
-    const blk_floatx4 v = *reinterpret_cast<const blk_floatx4*>(x + k);
+    const blk_floatx4 v = blk_ld4<TX>(x, k);
     s += (v[0] + v[1]) + (v[2] + v[3]);
   }
 #pragma unroll
@@ -33,7 +55,7 @@ __global__ void __launch_bounds__(256) ln_stats_kernel(const LnStatsArgs p) {
   const float mean = s / (float)p.L;
   float q = 0.f;
   for (int k = 4 * lane; k < p.L; k += 256) {
-    const blk_floatx4 v = *reinterpret_cast<const blk_floatx4*>(x + k);
+    const blk_floatx4 v = blk_ld4<TX>(x, k);
     const float a = v[0] - mean, b = v[1] - mean, c = v[2] - mean, d = v[3] - mean;
     q += (a * a + b * b) + (c * c + d * d);
   }
@@ -178,6 +200,145 @@ __global__ void __launch_bounds__(256) gemm_ln_kernel(const GemmLnArgs p) {
       blk_floatx4 y = acc[ob][nb] + bs;
       y += res[ob][nb];
       *reinterpret_cast<blk_floatx4*>(p.Y + row * p.N + o) = y;
+    }
+  }
+}
+
+// The same projection with bfloat16 operands on the matrix cores (v_mfma_f32_16x16x32_bf16, float32 accumulation),
+// for blocks whose token features and projection weights are stored in bfloat16: X float32 or bfloat16 (normalised in
+// float32, then rounded to bfloat16), W bfloat16, the result float32 or bfloat16, the residual bfloat16.  Same tiling as
+// gemm_ln_kernel with slices of 64: a lane reads eight consecutive k of a row (16 bytes) per instruction, rows 72
+// bfloat16 apart in LDS (the sixteen lanes of a k-group hit all banks).
+constexpr int GEMMB_BK = 64, GEMMB_PITCH = GEMMB_BK + 8;
+
+template <typename TX, bool OUT_BF16>
+__global__ void __launch_bounds__(256) gemm_ln_bf16_kernel(const GemmLnBf16Args p) {
+  __shared__ __attribute__((aligned(16))) unsigned short lds[2 * (GEMM_BM + GEMM_BN) * GEMMB_PITCH];
+  auto Ws = [&](int buf) { return lds + buf * (GEMM_BM + GEMM_BN) * GEMMB_PITCH; };
+  auto Xs = [&](int buf) { return lds + buf * (GEMM_BM + GEMM_BN) * GEMMB_PITCH + GEMM_BN * GEMMB_PITCH; };
+  const TX* const X = reinterpret_cast<const TX*>(p.X);
+  const long long nMt = (p.M + GEMM_BM - 1) / GEMM_BM;
+  const int nNt = (p.N + GEMM_BN - 1) / GEMM_BN;
+  const long long total = nMt * nNt;
+  const long long per = (total + 7) / 8;  // a contiguous run of tiles per die, as in gemm_ln_kernel
+  const long long tile = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((long long)(blockIdx.x >> 3) >= per || tile >= total) return;
+  const long long m0 = (tile / nNt) * GEMM_BM;
+  const int n0 = (int)(tile % nNt) * GEMM_BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = lane & 15, g = lane >> 4;
+  const int wo = wave & 1, wn = wave >> 1;
+  const int lr = tid >> 3, lc = 8 * (tid & 7);  // this thread's rows lr + 32 j and columns lc .. lc + 7 of a slice
+
+  float mean[4], rstd[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const long long row = m0 + lr + 32 * j;
+    mean[j] = row < p.M ? p.stats[2 * row] : 0.f;
+    rstd[j] = row < p.M ? p.stats[2 * row + 1] : 0.f;
+  }
+  blk_u16x8 rw[4];
+  blk_floatx4 rx[4][2], gn[2], of[2];
+  bool live[4];
+  auto fetch = [&](int k0) {
+    const int k = k0 + lc;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      gn[h] = of[h] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
+      if (k < p.K) {
+        gn[h] = *reinterpret_cast<const blk_floatx4*>(p.gain + k + 4 * h);
+        of[h] = *reinterpret_cast<const blk_floatx4*>(p.offset + k + 4 * h);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int o = n0 + lr + 32 * j;
+      const long long row = m0 + lr + 32 * j;
+      rw[j] = blk_u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      rx[j][0] = rx[j][1] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
+      live[j] = k < p.K && row < p.M;
+      if (k < p.K && o < p.N) rw[j] = *reinterpret_cast<const blk_u16x8*>(p.W + (long long)o * p.K + k);
+      if (live[j]) {
+        rx[j][0] = blk_ld4<TX>(X, row * p.K + k);
+        rx[j][1] = blk_ld4<TX>(X, row * p.K + k + 4);
+      }
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      blk_u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (live[j]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[4 * h + e] = f32_to_bf16((rx[j][h][e] - mean[j]) * rstd[j] * gn[h][e] + of[h][e]);
+      }
+      *reinterpret_cast<blk_u16x8*>(Ws(buf) + (lr + 32 * j) * GEMMB_PITCH + lc) = rw[j];
+      *reinterpret_cast<blk_u16x8*>(Xs(buf) + (lr + 32 * j) * GEMMB_PITCH + lc) = v;
+    }
+  };
+  blk_floatx4 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](int buf) {
+    const unsigned short* wsb = Ws(buf) + (64 * wo + i) * GEMMB_PITCH + 8 * g;
+    const unsigned short* xsb = Xs(buf) + (64 * wn + i) * GEMMB_PITCH + 8 * g;
+#pragma unroll
+    for (int h = 0; h < GEMMB_BK / 32; ++h) {
+      blk_bf16x8 a[4], b[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        a[t] = *reinterpret_cast<const blk_bf16x8*>(wsb + 16 * t * GEMMB_PITCH + 32 * h);
+        b[t] = *reinterpret_cast<const blk_bf16x8*>(xsb + 16 * t * GEMMB_PITCH + 32 * h);
+      }
+#pragma unroll
+      for (int ob = 0; ob < 4; ++ob)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+          acc[ob][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ob], b[nb], acc[ob][nb], 0, 0, 0);
+    }
+  };
+  const int nk = (p.K + GEMMB_BK - 1) / GEMMB_BK;
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int kt = 0; kt + 1 < nk; ++kt) {
+    fetch((kt + 1) * GEMMB_BK);
+    compute(kt & 1);
+    stash((kt & 1) ^ 1);
+    __syncthreads();
+  }
+  blk_floatx4 res[4][4];  // the residual, read under the last slice's matrix-core work
+#pragma unroll
+  for (int ob = 0; ob < 4; ++ob)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const int o = n0 + 64 * wo + 16 * ob + 4 * g;
+      const long long row = m0 + 64 * wn + 16 * nb + i;
+      res[ob][nb] = blk_floatx4{0.f, 0.f, 0.f, 0.f};
+      if (p.Res && o < p.N && row < p.M) res[ob][nb] = blk_ld4<unsigned short>(p.Res, row * p.N + o);
+    }
+  compute((nk - 1) & 1);
+  // acc[ob][nb][v] = Y[m0 + 64 wn + 16 nb + i][n0 + 64 wo + 16 ob + 4 g + v]
+#pragma unroll
+  for (int ob = 0; ob < 4; ++ob) {
+    const int o = n0 + 64 * wo + 16 * ob + 4 * g;
+    if (o >= p.N) continue;
+    blk_floatx4 bs = {0.f, 0.f, 0.f, 0.f};
+    if (p.bias) bs = *reinterpret_cast<const blk_floatx4*>(p.bias + o);
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      const long long row = m0 + 64 * wn + 16 * nb + i;
+      if (row >= p.M) continue;
+      const blk_floatx4 y = acc[ob][nb] + bs + res[ob][nb];
+      if constexpr (OUT_BF16) {
+        const blk_u16x4 v = {f32_to_bf16(y[0]), f32_to_bf16(y[1]), f32_to_bf16(y[2]), f32_to_bf16(y[3])};
+        *reinterpret_cast<blk_u16x4*>(reinterpret_cast<unsigned short*>(p.Y) + row * p.N + o) = v;
+      } else {
+        *reinterpret_cast<blk_floatx4*>(reinterpret_cast<float*>(p.Y) + row * p.N + o) = y;
+      }
     }
   }
 }

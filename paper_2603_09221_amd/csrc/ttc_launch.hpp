@@ -46,7 +46,8 @@ hipError_t launch_cxt_contract(const CxtBackwardArgs& a, bool bf16, dim3 grid, h
 hipError_t launch_cxt_basis(const CxtBackwardArgs& a, bool bf16, hipStream_t st);
 hipError_t launch_zero_floats(float* dst, long long n, hipStream_t st);
 // the block around the structured solver (ttc_block.hpp)
-hipError_t launch_ln_stats(const LnStatsArgs& a, hipStream_t st);
+hipError_t launch_ln_stats(const LnStatsArgs& a, bool bf16, hipStream_t st);
+hipError_t launch_gemm_ln_bf16(const GemmLnBf16Args& a, bool x_bf16, bool out_bf16, hipStream_t st);
 hipError_t launch_gemm_ln(const GemmLnArgs& a, hipStream_t st);
 hipError_t launch_cxt_maps(const CxtMapsArgs& a, int blocks, hipStream_t st);
 hipError_t launch_qbasis(const float* Qc, float* Qb, int r, hipStream_t st);

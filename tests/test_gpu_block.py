@@ -110,3 +110,48 @@ def test_unsupported_shapes_are_refused():
     with pytest.raises(binding.TtcError):
         binding.ttc_block_forward(x, w, 0)                                  # no horizon
     assert binding.ttc_block_forward(x[:0], w, 5)["x_out"].shape == (0, 64)  # no tokens: nothing to do
+
+
+def bf16_case(n, C, H, r, T, seed):
+    w = synth.make_block_weights(C, H, 16, r, seed=seed, device=DEV)
+    w["W_in"], w["W_out"] = w["W_in"].bfloat16().contiguous(), w["W_out"].bfloat16().contiguous()
+    x = synth.make_block_input(n, C, seed=seed, device=DEV).bfloat16().contiguous()
+    return x, w
+
+
+@pytest.mark.parametrize("n,C,H,r,T", [(300, 256, 4, 16, 8), (1, 64, 1, 16, 4), (131, 104, 3, 4, 5), (517, 512, 16, 16, 3),
+                                        (70, 40, 9, 64, 2)])
+def test_bf16_block_against_oracle(n, C, H, r, T):
+    """bfloat16 token features and projection weights (TTC_BLOCK_FLAG_BF16): the oracle consumes the stored (rounded)
+    values; 2e-2, the bar for bfloat16 inputs, on h0, o and x_out (x_out is itself rounded to bfloat16)."""
+    x, w = bf16_case(n, C, H, r, T, seed=n + C + H + r + T)
+    out = binding.ttc_block_forward(x, w, T, want_h0=True, want_o=True)
+    torch.cuda.synchronize()
+    assert out["x_out"].dtype == torch.bfloat16 and int(out["info"].abs().max()) == 0
+    ref = oracle(x.float(), {k: v.float() for k, v in w.items()}, T)
+    errs = {"h0": float(rel_err(out["h0"].cpu().numpy(), ref["h0"].reshape(n, -1)).max()),
+            "o": float(rel_err(out["o"].cpu().numpy(), ref["o"]).max()),
+            "x_out": float(rel_err(out["x_out"].float().cpu().numpy(), ref["x_out"]).max())}
+    print({k: f"{v:.2e}" for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= 2e-2, (k, v)
+
+
+def test_bf16_block_in_place_zero_projection_and_refusals():
+    x, w = bf16_case(200, 128, 4, 16, 6, seed=11)
+    ref = binding.ttc_block_forward(x, w, 6)
+    y = x.clone()
+    out = binding.ttc_block_forward(y, w, 6, out={"x_out": y})
+    torch.cuda.synchronize()
+    assert torch.equal(out["x_out"], ref["x_out"])
+    w0 = dict(w)
+    w0["W_out"] = torch.zeros_like(w["W_out"])
+    w0["b_out"] = torch.zeros_like(w["b_out"])
+    same = binding.ttc_block_forward(x, w0, 6)
+    torch.cuda.synchronize()
+    assert torch.equal(same["x_out"], x)                      # a zero output projection returns the input bit for bit
+    with pytest.raises(ValueError):
+        binding.ttc_block_forward(x.float(), w, 6)            # float32 features with bfloat16 projections
+    xw, ww = bf16_case(4, 68, 2, 16, 3, seed=12)              # C a multiple of 4 but not of 8
+    with pytest.raises(binding.TtcError):
+        binding.ttc_block_forward(xw, ww, 3)
