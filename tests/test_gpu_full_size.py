@@ -78,22 +78,26 @@ def test_config2_llm_adapter_full():
     full_size_check("llm_adapter", n, 1e-4, sample=256)
 
 
-def test_block_at_the_benchmark_size():
+@pytest.mark.parametrize("dtype,tol", [("f32", 1e-4), ("bf16", 2e-2)])
+def test_block_at_the_benchmark_size(dtype, tol):
     """ttc_block_forward on the workload of `bench.py --path block` (65 536 tokens of 4096 features, 16 heads, r = 16,
-    T = 8): the oracle on tokens sampled over the whole batch (first and last tiles included), info == 0 and finite
-    outputs on every token."""
+    T = 8; float32, and bfloat16 token features and projection matrices): the oracle, on the stored values, for tokens
+    sampled over the whole batch (first and last tiles included), info == 0 and finite outputs on every token."""
     from oracle import ttc_block_oracle
     from tests.parity import rel_err
     n, C, H, r, T = 8 * 8192, 4096, 16, 16, 8
     w = synth.make_block_weights(C, H, 16, r, seed=0, device=DEV)
     x = synth.make_block_input(n, C, seed=0, device=DEV)
+    if dtype == "bf16":
+        w["W_in"], w["W_out"] = w["W_in"].bfloat16().contiguous(), w["W_out"].bfloat16().contiguous()
+        x = x.bfloat16().contiguous()
     out = binding.ttc_block_forward(x, w, T)
     torch.cuda.synchronize()
-    assert int(out["info"].abs().max()) == 0 and bool(torch.isfinite(out["x_out"]).all())
+    assert int(out["info"].abs().max()) == 0 and bool(torch.isfinite(out["x_out"].float()).all())
     g = torch.Generator().manual_seed(321)
     idx = torch.cat([torch.tensor([0, 1, 127, 128, n - 129, n - 2, n - 1]), torch.randperm(n, generator=g)[:57]]).sort().values
-    ref = ttc_block_oracle.ttc_block(x[idx.to(DEV)].cpu().double().numpy(),
-                                     {k: v.cpu().double().numpy() for k, v in w.items()}, T)
-    err = float(rel_err(out["x_out"][idx.to(DEV)].cpu().numpy(), ref["x_out"]).max())
-    print("block", n, f"{err:.2e}")
-    assert err <= 1e-4
+    ref = ttc_block_oracle.ttc_block(x[idx.to(DEV)].float().cpu().double().numpy(),
+                                     {k: v.float().cpu().double().numpy() for k, v in w.items()}, T)
+    err = float(rel_err(out["x_out"][idx.to(DEV)].float().cpu().numpy(), ref["x_out"]).max())
+    print("block", dtype, n, f"{err:.2e}")
+    assert err <= tol
