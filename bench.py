@@ -332,16 +332,15 @@ def bench_block(args):
 
 
 def bench_cxt_bwd(args):
-    """Backward pass of the structured layer shape (ttc_lqr_backward_cxt): d = 16, r = 16, horizon 8, 16 heads x 8192
-    tokens.  The path writes the dense steps of a chunk of problems and their per-step gradients through HBM (8 T
-    matrices of 1 KiB per problem) around the time-heterogeneous backward kernel, so its bound is the memory system."""
+    """Backward pass of the structured layer shape (ttc_lqr_backward_cxt): d = 16, r = 16, horizon 8, 8 x 16 heads x 8192
+    tokens.  Its arithmetic is the forward pass's recursion once more (on the matrix cores) and a sweep on vectors."""
     import numpy as np
     import torch
     from paper_2603_09221_amd import binding, synth
     from paper_2603_09221_amd.errors import rel_err
 
     d, r, T = 16, 16, args.horizon or 8
-    n = args.n or 16 * 8192
+    n = args.n or 8 * 16 * 8192
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     lib = binding.load()
@@ -374,8 +373,9 @@ def bench_cxt_bwd(args):
     kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
     kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
     assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
-    # bytes the path moves by construction: the dense steps written and read, the per-step gradients written and read
-    path_bytes = n * (2 * 8 * T * d * d * 4 + (6 * d + 3 * r) * 4 + (6 * d + 3 * r) * 4 + 2 * 3 * d * d * 4)
+    # bytes the path moves by construction: per problem the T + 5 matrices the solve kernel leaves and the sweep reads,
+    # the four trajectories written and read, the three kept matrices written and read, inputs and outputs
+    path_bytes = n * (2 * (T + 5) * d * d * 4 + 2 * 4 * (T + 1) * d * 4 + 2 * 3 * d * d * 4 + 2 * (6 * d + 3 * r) * 4 + 2 * (6 * d + 3 * r) * 4)
     achieved = path_bytes / kernel_s / 1e9
     res = {
         "metric": "LQR backward passes/sec at d=%d, T=%d, structured parameters" % (d, T),
@@ -386,11 +386,11 @@ def bench_cxt_bwd(args):
                    "path": "cxtbwd", "outputs": "gsA,gsB,gsQ,gsQf,grinv,glgA,glgB,glgQ,gx0,gBbasis,gQbasis"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
                      "traffic": measured_traffic("ttc_layer_d16_T%d" % T, "cxtbwd", n),
-                     "kernel": "ttc_lqr_backward_cxt (cxt_expand, backward_kernel<16>, cxt_contract, cxt_basis per chunk)",
+                     "kernel": "ttc_lqr_backward_cxt (solve_cxt_kernel, backward_cxt_vec_kernel, cxt_basis_kernel per chunk)",
                      "kernel_ms": kernel_s * 1e3, **spread(kernel_ms),
                      "alg_bytes_per_launch": path_bytes,
-                     "alg_flops_per_problem": alg_flops_bwd(d, T),
-                     "alg_TFLOPs": alg_flops_bwd(d, T) * n / kernel_s / 1e12},
+                     "alg_flops_per_problem": alg_flops_cxt(d, r, T),
+                     "alg_TFLOPs": alg_flops_cxt(d, r, T) * n / kernel_s / 1e12},
     }
     if not args.no_cpu:
         from oracle import lqr_grad_oracle
@@ -598,7 +598,7 @@ def main():
                          "(prints a table, not a bench line); rollout: ttc_lqr_rollout (all T controls, states and the cost) "
                          "on the configuration's shape (default up to 16384 problems); block: the whole TTC block (ttc_block_forward) at "
                          "4096 features, 16 heads of d = 16, 65536 tokens, --config ignored; cxtbwd: the backward pass of the structured "
-                         "problems (ttc_lqr_backward_cxt), d = 16, r = 16, 131072 problems, --config ignored")
+                         "problems (ttc_lqr_backward_cxt), d = 16, r = 16, 1048576 problems, --config ignored")
     ap.add_argument("--horizon", type=int, default=None, help="horizon of the cxt (default 8) and scan (default 2048) paths")
     ap.add_argument("--block-dtype", default="f32", choices=("f32", "bf16"),
                     help="--path block: token features and projection matrices in float32 or bfloat16")

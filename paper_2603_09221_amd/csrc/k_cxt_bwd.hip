@@ -1,16 +1,11 @@
-// cxt_expand_kernel, cxt_contract_kernel, cxt_basis_kernel (ttc_lqr_backward_cxt).
+// backward_cxt_vec_kernel, cxt_basis_kernel (ttc_lqr_backward_cxt).
 #include "ttc_cxt_backward.hpp"
 #include "ttc_launch.hpp"
 
 namespace ttc {
-hipError_t launch_cxt_expand(const CxtBackwardArgs& a, bool bf16, dim3 grid, hipStream_t st) {
-  if (bf16) hipLaunchKernelGGL((cxt_expand_kernel<uint16_t>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((cxt_expand_kernel<float>), grid, dim3(256), 0, st, a);
-  return hipGetLastError();
-}
-hipError_t launch_cxt_contract(const CxtBackwardArgs& a, bool bf16, dim3 grid, hipStream_t st) {
-  if (bf16) hipLaunchKernelGGL((cxt_contract_kernel<uint16_t>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((cxt_contract_kernel<float>), grid, dim3(256), 0, st, a);
+hipError_t launch_cxt_backward_vec(const CxtBackwardArgs& a, bool bf16, dim3 grid, hipStream_t st) {
+  if (bf16) hipLaunchKernelGGL((backward_cxt_vec_kernel<uint16_t>), grid, dim3(64), 0, st, a);
+  else hipLaunchKernelGGL((backward_cxt_vec_kernel<float>), grid, dim3(64), 0, st, a);
   return hipGetLastError();
 }
 hipError_t launch_cxt_basis(const CxtBackwardArgs& a, bool bf16, hipStream_t st) {

@@ -853,19 +853,21 @@ ttc_status_t ttc_lqr_backward_tv(const ttc_lqr_tv_problem_t* q, const float* gra
 
 // ---- backward pass of the structured problems ------------------------------------------------------------------
 namespace {
-// problems per chunk: the dense steps and their gradients take 8 T matrices of 1 KiB per problem; about 1 GiB per chunk
+// floats of workspace per problem of a chunk: T + 5 matrices left by the solve kernel, four trajectories of T + 1
+// vectors, three matrices kept for the bases' sums, one int
+size_t cxt_bwd_floats_per_problem(int T) { return (size_t)(T + 5) * 256 + 4 * (size_t)(T + 1) * 16 + 768 + 1; }
+// problems per chunk: about 1 GiB of workspace
 long long cxt_bwd_chunk(long long n, int T) {
-  long long ch = (1LL << 30) / (8LL * T * 1024);
+  long long ch = (long long)((1ull << 28) / cxt_bwd_floats_per_problem(T));
   ch = ch < 256 ? 256 : ch;
   return n < ch ? n : ch;
 }
-size_t cxt_bwd_floats_per_problem(int T) { return (size_t)8 * T * 256 + 16 + 768; }
 }  // namespace
 
 size_t ttc_lqr_backward_cxt_workspace_bytes(const ttc_lqr_cxt_problem_t* q) {
   if (!q || q->n < 0 || q->T < 1 || q->d != 16) return 0;
   const size_t chunk = (size_t)cxt_bwd_chunk(q->n, q->T);
-  return round64(chunk * cxt_bwd_floats_per_problem(q->T)) * sizeof(float) + backward_ws_bytes(16, q->T, false);
+  return round64(chunk * cxt_bwd_floats_per_problem(q->T)) * sizeof(float);
 }
 
 ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* grad_u0, const ttc_lqr_cxt_grads_t* gr,
@@ -887,45 +889,45 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
     return TTC_ERR_WORKSPACE;
   const int T = q->T;
   const bool bf16 = q->in_dtype == TTC_BF16;
+  const size_t esz = bf16 ? 2 : 4;
   const long long chunk = cxt_bwd_chunk(q->n, T);
   float* ws = static_cast<float*>(workspace);
-  const size_t mat = (size_t)chunk * T * 256;
   ttc::CxtBackwardArgs a;
   fill_cxt_args(a.c, q);
-  a.dA = ws; a.dB = ws + mat; a.dQ = ws + 2 * mat; a.dR = ws + 3 * mat;
-  a.gA = ws + 4 * mat; a.gB = ws + 5 * mat; a.gQ = ws + 6 * mat; a.gR = ws + 7 * mat;
-  a.x0f = ws + 8 * mat;
-  a.keep = a.x0f + (size_t)chunk * 16;
-  float* const bws = ws + round64((size_t)chunk * cxt_bwd_floats_per_problem(T));  // the backward kernel's own workspace
+  a.roll = ws;
+  a.traj = a.roll + (size_t)chunk * (T + 5) * 256;
+  a.keep = a.traj + (size_t)chunk * 4 * (T + 1) * 16;
+  int* const info_ws = reinterpret_cast<int*>(a.keep + (size_t)chunk * 768);  // the chunk's info when the caller wants none
+  a.g = grad_u0;
   a.gsA = gr->gsA; a.gsB = gr->gsB; a.gsQ = gr->gsQ; a.gsQf = gr->gsQf; a.grinv = gr->grinv;
-  a.glgA = gr->glgA; a.glgB = gr->glgB; a.glgQ = gr->glgQ;
+  a.glgA = gr->glgA; a.glgB = gr->glgB; a.glgQ = gr->glgQ; a.gx0 = gr->gx0;
   a.gBbasis = gr->gBbasis; a.gQbasis = gr->gQbasis;
-  const long long per_problem_grid = 16LL * ttc::cu_count();  // workgroups of 256 threads, one problem at a time each
-  const long long gb = ttc::grid_blocks(ttc::KIND_BACKWARD, 16, false);
+  const long long vgrid = 16LL * ttc::cu_count();  // wavefronts of the vector kernel, four problems at a time each
+  auto shifted = [&](const void* base, long long elems) {
+    return static_cast<const void*>(static_cast<const char*>(base) + (size_t)elems * esz);
+  };
   for (long long first = 0; first < q->n; first += chunk) {
     a.first = first;
     a.count = q->n - first < chunk ? q->n - first : chunk;
-    const dim3 pgrid((unsigned)(a.count < per_problem_grid ? a.count : per_problem_grid));
-    if (ttc::launch_cxt_expand(a, bf16, pgrid, st) != hipSuccess) return TTC_ERR_DEVICE;
-    ttc::BackwardArgs b;
-    b.r.n = a.count; b.r.T = T; b.r.flags = 0;
-    b.r.A = a.dA; b.r.B = a.dB; b.r.Q = a.dQ; b.r.R = a.dR; b.r.QT = nullptr; b.r.x0 = a.x0f;
-    b.r.sA = b.r.sB = b.r.sQ = b.r.sR = (long long)T * 256; b.r.sQT = 0; b.r.sx0 = 16;
-    b.r.U = b.r.X = b.r.cost = nullptr;
-    b.r.info = gr->info ? gr->info + first : nullptr;
-    b.r.ws = bws;
-    b.tA = b.tB = b.tQ = b.tR = 256;
-    b.g = grad_u0 + first * 16; b.sg = 16;
-    b.gA = a.gA; b.gB = a.gB; b.gQ = a.gQ; b.gR = a.gR; b.gQT = nullptr; b.gx0 = gr->gx0 + first * 16;
-    b.sum_steps = 0;
-    const dim3 bgrid((unsigned)(a.count < gb ? a.count : gb));
-    if (ttc::run_backward(b, 16, false, bgrid, st) != hipSuccess) return TTC_ERR_DEVICE;
-    if (ttc::launch_cxt_contract(a, bf16, pgrid, st) != hipSuccess) return TTC_ERR_DEVICE;
+    // the backward recursion on the chunk's problems (their inputs start at `first`), keeping what the sweep below needs
+    ttc::CxtArgs sc = a.c;
+    sc.s.n = a.count;
+    sc.s.x0 = shifted(q->x0, first * 16);
+    sc.sA = shifted(q->sA, first * 16); sc.rinv = shifted(q->rinv, first * 16);
+    sc.lgA = shifted(q->lgA, first * 16); sc.lgB = shifted(q->lgB, first * 16); sc.lgQ = shifted(q->lgQ, first * 16);
+    sc.sB = shifted(q->sB, first * q->r); sc.sQ = shifted(q->sQ, first * q->r); sc.sQf = shifted(q->sQf, first * q->r);
+    sc.roll_ws = a.roll;
+    sc.roll_slots = T + 5;
+    sc.s.info = gr->info ? gr->info + first : info_ws;
+    a.info = gr->info ? gr->info : info_ws - first;  // indexed by the problem's number in the batch
+    if (run_cxt(sc, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;
+    const long long groups = (a.count + 3) / 4;
+    if (ttc::launch_cxt_backward_vec(a, bf16, dim3((unsigned)(groups < vgrid ? groups : vgrid)), st) != hipSuccess)
+      return TTC_ERR_DEVICE;
     if (ttc::launch_cxt_basis(a, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;
   }
   return TTC_OK;
 }
-
 
 const char* ttc_status_string(ttc_status_t status) {
   switch (status) {

@@ -74,8 +74,10 @@ struct CxtArgs {
   int r;
   const void *sA, *sB, *sQ, *sQf, *rinv, *lgA, *lgB, *lgQ;  // (n,16) vectors, (n,r) coefficients
   const void *Bbasis, *Qbasis;                              // (r,16,16), shared by all problems
-  // roll-out only: per problem (T+3) matrices of 256 floats: Bbar, Qbar, Q_T, K_0 .. K_{T-1}; NULL for a plain solve
+  // roll-out and backward pass: per problem roll_slots matrices of 256 floats: Bbar, Qbar, Q_T, K_0 .. K_{T-1} and, for
+  // the backward pass (roll_slots = T + 5), S_0 and S_0^{-1}; NULL for a plain solve
   float* roll_ws = nullptr;
+  int roll_slots = 0;  // 0 stands for T + 3
 };
 
 struct CxtRolloutArgs {
@@ -85,15 +87,16 @@ struct CxtRolloutArgs {
 
 // ---- backward pass of the structured problems (ttc_cxt_backward.hpp)
 struct CxtBackwardArgs {
-  CxtArgs c;             // the problems (inputs only; c.s.n = all problems)
+  CxtArgs c;             // the problems (inputs only, the whole batch; c.s.n = all problems)
   long long first;       // the chunk: problems first .. first + count - 1
   long long count;
-  float *dA, *dB, *dQ, *dR;      // (count, T, 256) each: the dense steps
-  float* x0f;                    // (count, 16): x0 widened to float32
-  float *gA, *gB, *gQ, *gR;      // (count, T, 256) each: the per-step gradients
-  float* keep;                   // (count, 3, 256): dl/dBbar, dl/dQbar, dl/dQ_T
-  float *gsA, *gsB, *gsQ, *gsQf, *grinv, *glgA, *glgB, *glgQ;  // the caller's arrays, (n, 16) or (n, r)
-  float *gBbasis, *gQbasis;      // the caller's arrays, (r, 256), accumulated
+  float* roll;           // (count, T + 5, 256): what solve_cxt_kernel leaves for the backward pass (c.roll_ws layout)
+  float* traj;           // (count, 4, T + 1, 16): the primal and dual states and controls
+  float* keep;           // (count, 3, 256): dl/dBbar, dl/dQbar, dl/dQ_T
+  const float* g;        // (n, 16) dl/du_0
+  const int* info;       // (n) as written by the solve kernel
+  float *gsA, *gsB, *gsQ, *gsQf, *grinv, *glgA, *glgB, *glgQ, *gx0;  // the caller's arrays, (n, 16) or (n, r)
+  float *gBbasis, *gQbasis;                                          // the caller's arrays, (r, 256), accumulated
 };
 
 // ---- the block around the structured solver (ttc_block.hpp)

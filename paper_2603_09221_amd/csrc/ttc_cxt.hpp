@@ -42,6 +42,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
   __shared__ float s_red[C::NW];
   const SolveArgs& p = ca.s;
   const int r = ca.r;
+  const long long slots = ca.roll_slots ? ca.roll_slots : p.T + 3;  // matrices per problem in roll_ws
   const long long nquads = (p.n + PPW - 1) / PPW;
   const TIn* const Bbasis = reinterpret_cast<const TIn*>(ca.Bbasis);
   const TIn* const Qbasis = reinterpret_cast<const TIn*>(ca.Qbasis);
@@ -116,7 +117,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
         if (!valid[q]) continue;
-        float* const e = ca.roll_ws + prob[q] * (long long)(p.T + 3) * D * D;
+        float* const e = ca.roll_ws + prob[q] * slots * D * D;
         write_rows_global<D>(e, reinterpret_cast<const floatx4(&)[1]>(Bbar[q]), 0, i, g);
         write_rows_global<D>(e + D * D, reinterpret_cast<const floatx4(&)[1]>(Qbar[q]), 0, i, g);
         write_rows_global<D>(e + 2 * D * D, pn[q][0], 0, i, g);
@@ -193,12 +194,23 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
           for (int q = 0; q < PPW; ++q)
             accS[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cBT[q][0][t], bV[q][t], accS[q][0][0], 0, 0, 0);
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], accS[q], w, i, g);
+        for (int q = 0; q < PPW; ++q) {
+          store_rows<D>(Wm[q], accS[q], w, i, g);
+          if (s == 0 && slots == p.T + 5 && valid[q])  // the backward pass solves with S_0 once more
+            write_rows_global<D>(ca.roll_ws + (prob[q] * slots + p.T + 3) * D * D, accS[q][0], 0, i, g);
+        }
       }
       __syncthreads();
       tm.toc(2);
       note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
       tm.toc(1);
+      if (s == 0 && slots == p.T + 5) {  // and S_0^{-1}: one 16-byte piece per lane, row-major
+#pragma unroll
+        for (int q = 0; q < PPW; ++q)
+          if (valid[q])
+            *reinterpret_cast<floatx4*>(ca.roll_ws + (prob[q] * slots + p.T + 4) * D * D + 4 * lane) =
+                *reinterpret_cast<const floatx4*>(Wm[q] + (lane >> 2) * C::PITCH + 4 * (lane & 3));
+      }
       {
         float cSi[PPW][C::RB][C::KS];
 #pragma unroll
@@ -222,7 +234,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 #pragma unroll
         for (int q = 0; q < PPW; ++q)
           if (valid[q])
-            write_rows_global<D>(ca.roll_ws + (prob[q] * (long long)(p.T + 3) + 3 + s) * D * D, accW[q][0], 0, i, g);
+            write_rows_global<D>(ca.roll_ws + (prob[q] * slots + 3 + s) * D * D, accW[q][0], 0, i, g);
       }
       if (s >= 1) {
 #pragma unroll
@@ -295,7 +307,7 @@ __global__ void __launch_bounds__(64) rollout_cxt_forward_kernel(const CxtRollou
   for (long long grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
     const bool valid = grp * 4 + g < p.n;
     const long long prob = valid ? grp * 4 + g : p.n - 1;
-    const float* const e = ca.roll_ws + prob * (long long)(p.T + 3) * D * D;
+    const float* const e = ca.roll_ws + prob * (long long)(ca.roll_slots ? ca.roll_slots : p.T + 3) * D * D;
     const float sA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sA), prob * D + i);
     const float lgA_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgA), prob * D + i);
     const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgB), prob * D + i);

@@ -2,17 +2,18 @@
 // "Contextualization", "Parameterization"): the gradients of a loss of u_0 with respect to the per-problem vectors
 // (the log-scale modulation coefficients and the diagonal of R^{-1} among them), x0 and the shared basis matrices.
 //
-// The per-step gradients are those of the time-heterogeneous backward kernel (ttc_backward.hpp), which this path
-// runs on the problems' steps written out densely, a chunk of problems at a time, between two small kernels:
-//   cxt_expand_kernel    the T steps (A_t, B_t, Q_t, R_t) of every problem of the chunk, float32, into the workspace
-//   backward_kernel<16>  gA_t, gB_t, gQ_t, gR_t of every step into the workspace; gx0, info straight to the caller
-//   cxt_contract_kernel  the chain rule from the steps to the problem's vectors; dl/dBbar, dl/dQbar, dl/dQ_T kept
-//   cxt_basis_kernel     the bases' gradients: sums over the problems of the chunk, added to the caller's arrays
-// With t = 1..T, gam_X^t = exp(-t lg_X), Bbar = sum_k sB_k B^(k), Qbar = sum_k sQ_k Q^(k):
+// Three launches per chunk of problems:
+//   solve_cxt_kernel         the backward recursion of the forward pass again (ttc_cxt.hpp), leaving per problem
+//                            Bbar, Qbar, Q_T, every gain K_s, S_0 and S_0^{-1} in the workspace
+//   backward_cxt_vec_kernel  both closed loops, both co-state recursions and the gradients, on vectors (below)
+//   cxt_basis_kernel         the bases' gradients: sums over the problems of the chunk, added to the caller's arrays
+// With t = 1..T, gam_X^t = exp(-t lg_X), Bbar = sum_k sB_k B^(k), Qbar = sum_k sQ_k Q^(k), and the per-step gradients
+// of Thm 3.2, gA_t = lam_t xt_{t-1}^T + lamt_t x_{t-1}^T, gB_t = lam_t ut_t^T + lamt_t u_t^T, gQ_t = sym(xt_t x_t^T),
+// gR_t = sym(ut_t u_t^T) (primal x, u, lam; dual xt, ut, lamt):
 //   A_t = I + diag(gam_A^t sA):            dsA_i = sum_t gam_A,i^t gA_t[i,i],   dlgA_i = sum_t -t gam_A,i^t sA_i gA_t[i,i]
 //   B_t = Bbar diag(gam_B^t):              dBbar = sum_t gB_t diag(gam_B^t),    dlgB_j = sum_t -t gam_B,j^t sum_i Bbar[i,j] gB_t[i,j]
 //   Q_t = diag(gam_Q^t) Qbar diag(gam_Q^t) (t < T):  dQbar = sum_t diag(gam_Q^t) gQ_t diag(gam_Q^t),
-//                                          dlgQ_i = sum_t -t (row i + column i sums of Q_t o gQ_t)
+//                                          dlgQ_i = sum_t -2 t sum_j Q_t[i,j] gQ_t[i,j]   (both symmetric)
 //   Q_T = sum_k sQf_k Q^(k):               dQ_T = gQ_T;      R_t = diag(1/rinv):  drinv_i = -sum_t gR_t[i,i] / rinv_i^2
 //   dsB_k = <B^(k), dBbar>, dsQ_k = <Q^(k), dQbar>, dsQf_k = <Q^(k), dQ_T>;
 //   dB^(k) = sum_p sB_k dBbar,  dQ^(k) = sum_p (sQ_k dQbar + sQf_k dQ_T).
@@ -21,121 +22,233 @@
 
 namespace ttc {
 
-// a workgroup of 256 threads per problem, thread e = 16 i + j owning entry (i, j) of every matrix
+// The backward pass proper, on vectors: sixteen lanes per problem (four problems per wavefront), lane i owning entry
+// i of every vector and row i of every 16 x 16 matrix it accumulates.  solve_cxt_kernel has left, per problem,
+// Bbar, Qbar, Q_T, the gains K_0 .. K_{T-1}, S_0 and S_0^{-1}.  Forward: both closed loops (Alg. 1; the dual one starts
+// from ut_0 = -S_0^{-1} g, refined once with S_0, from the state 0), states and controls to the workspace.  Backward:
+// the co-states of both (Alg. 2) with A_t diagonal and Q_t = Gamma^t Qbar Gamma^t, and in the same sweep the
+// gradients of Thm 3.2 contracted straight onto the parameterisation: no per-step gradient matrix is ever formed.
 template <typename TIn>
-__global__ void __launch_bounds__(256) cxt_expand_kernel(const CxtBackwardArgs a) {
-  const int e = threadIdx.x, i = e >> 4, j = e & 15;
-  const int r = a.c.r, T = a.c.s.T;
+__global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardArgs a) {
+  constexpr int D = 16;
+  __shared__ float vb[4][6][D];  // per problem: vectors every lane of the problem reads
+  const SolveArgs& p = a.c.s;
+  const int T = p.T, r = a.c.r;
+  const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+  const long long slots = T + 5;
+  const long long ngroups = (a.count + 3) / 4;
+  const float nanv = __builtin_nanf("");
   const TIn* const Bb = reinterpret_cast<const TIn*>(a.c.Bbasis);
   const TIn* const Qb = reinterpret_cast<const TIn*>(a.c.Qbasis);
-  for (long long q = blockIdx.x; q < a.count; q += gridDim.x) {
-    const long long p = a.first + q;
-    float bbar = 0.f, qbar = 0.f, qf = 0.f;
-    for (int k = 0; k < r; ++k) {
-      const float bk = ld1<TIn>(Bb, (long)k * 256 + e), qk = ld1<TIn>(Qb, (long)k * 256 + e);
-      bbar = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sB), p * r + k), bk, bbar);
-      qbar = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sQ), p * r + k), qk, qbar);
-      qf = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sQf), p * r + k), qk, qf);
-    }
-    const float sA_i = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sA), p * 16 + i);
-    const float lgA_i = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgA), p * 16 + i);
-    const float lgB_j = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgB), p * 16 + j);
-    const float lgQ_i = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgQ), p * 16 + i);
-    const float lgQ_j = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgQ), p * 16 + j);
-    const float rdiag = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(a.c.rinv), p * 16 + i);
-    if (e < 16) a.x0f[q * 16 + e] = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.s.x0), p * 16 + e);
-    for (int t = 1; t <= T; ++t) {
-      const long long at = (q * T + (t - 1)) * 256 + e;
-      a.dA[at] = i == j ? 1.f + expf(-(float)t * lgA_i) * sA_i : 0.f;
-      a.dB[at] = bbar * expf(-(float)t * lgB_j);
-      a.dQ[at] = t == T ? qf : expf(-(float)t * lgQ_i) * qbar * expf(-(float)t * lgQ_j);
-      a.dR[at] = i == j ? rdiag : 0.f;
-    }
-  }
-}
-
-template <typename TIn>
-__global__ void __launch_bounds__(256) cxt_contract_kernel(const CxtBackwardArgs a) {
-  __shared__ float M[3][256];     // reductions over rows or columns; then dl/dBbar, dl/dQbar, dl/dQ_T
-  const int e = threadIdx.x, i = e >> 4, j = e & 15;
-  const int r = a.c.r, T = a.c.s.T;
-  const TIn* const Bb = reinterpret_cast<const TIn*>(a.c.Bbasis);
-  const TIn* const Qb = reinterpret_cast<const TIn*>(a.c.Qbasis);
-  for (long long q = blockIdx.x; q < a.count; q += gridDim.x) {
-    const long long p = a.first + q;
-    float bbar = 0.f, qbar = 0.f;
-    for (int k = 0; k < r; ++k) {
-      bbar = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sB), p * r + k), ld1<TIn>(Bb, (long)k * 256 + e), bbar);
-      qbar = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sQ), p * r + k), ld1<TIn>(Qb, (long)k * 256 + e), qbar);
-    }
-    const float sA_i = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sA), p * 16 + i);
-    const float lgA_i = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgA), p * 16 + i);
-    const float lgB_j = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgB), p * 16 + j);
-    const float lgQ_i = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgQ), p * 16 + i);
-    const float lgQ_j = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgQ), p * 16 + j);
-    const float rinv_i = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.rinv), p * 16 + i);
-    float dsA = 0.f, dlgA = 0.f, dR = 0.f;      // used by the diagonal threads
-    float dBbar = 0.f, dQbar = 0.f, dQf = 0.f;  // entry (i, j)
-    float colB = 0.f, hadQ = 0.f;               // entry (i, j) of the sums that are reduced below
-    for (int t = 1; t <= T; ++t) {
-      const long long at = (q * T + (t - 1)) * 256 + e;
-      const float ga = a.gA[at], gb = a.gB[at], gq = a.gQ[at], gr = a.gR[at];
-      const float tf = (float)t;
-      const float gamA = expf(-tf * lgA_i), gamB = expf(-tf * lgB_j), gamQ = expf(-tf * lgQ_i) * expf(-tf * lgQ_j);
-      dsA = __builtin_fmaf(gamA, ga, dsA);
-      dlgA = __builtin_fmaf(-tf * gamA * sA_i, ga, dlgA);
-      dR += gr;
-      dBbar = __builtin_fmaf(gamB, gb, dBbar);
-      colB = __builtin_fmaf(-tf * gamB * bbar, gb, colB);
-      if (t < T) {
-        dQbar = __builtin_fmaf(gamQ, gq, dQbar);
-        hadQ = __builtin_fmaf(-tf * gamQ * qbar, gq, hadQ);
-      } else {
-        dQf = gq;
+  // sum_j M[i][j] v[j] for two vectors at once, M row-major in global memory
+  auto row_dot2 = [&](const float* M, const float* va, const float* vc, float& ya, float& yc) {
+    float sa = 0.f, sc = 0.f;
+#pragma unroll
+    for (int j4 = 0; j4 < D; j4 += 4) {
+      const floatx4 m = *reinterpret_cast<const floatx4*>(M + i * D + j4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sa = __builtin_fmaf(m[e], va[j4 + e], sa);
+        sc = __builtin_fmaf(m[e], vc[j4 + e], sc);
       }
     }
-    if (i == j) {
-      a.gsA[p * 16 + i] = dsA;
-      a.glgA[p * 16 + i] = dlgA;
-      a.grinv[p * 16 + i] = -dR / (rinv_i * rinv_i);
+    ya = sa;
+    yc = sc;
+  };
+  for (long long grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+    const bool valid = grp * 4 + g < a.count;
+    const long long q = valid ? grp * 4 + g : a.count - 1;  // within the chunk
+    const long long prob = a.first + q;                      // within the batch
+    const float* const e = a.roll + q * slots * D * D;
+    float* const tX = a.traj + q * 4 * (long long)(T + 1) * D;
+    float* const tXt = tX + (long long)(T + 1) * D;
+    float* const tU = tXt + (long long)(T + 1) * D;
+    float* const tUt = tU + (long long)(T + 1) * D;
+    const float sA_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sA), prob * D + i);
+    const float lgA_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgA), prob * D + i);
+    const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgB), prob * D + i);
+    const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgQ), prob * D + i);
+    const float rinv_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.rinv), prob * D + i);
+    const bool bad = a.info && a.info[prob] != 0;
+    float bb[D], qq[D];  // row i of Bbar and of Qbar
+#pragma unroll
+    for (int j4 = 0; j4 < D; j4 += 4) {
+      const floatx4 b4 = *reinterpret_cast<const floatx4*>(e + i * D + j4);
+      const floatx4 q4 = *reinterpret_cast<const floatx4*>(e + D * D + i * D + j4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        bb[j4 + k] = b4[k];
+        qq[j4 + k] = q4[k];
+      }
     }
-    __syncthreads();  // M is free (the previous problem's readers are done)
-    M[0][e] = colB;
-    M[1][e] = hadQ;
+    float* const v0 = vb[g][0];
+    float* const v1 = vb[g][1];
+    float* const v2 = vb[g][2];
+    float* const v3 = vb[g][3];
+    float* const vgB = vb[g][4];
+    float* const vgQ = vb[g][5];
+
+    // ---- forward: both closed loops
+    float x = ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), prob * D + i), xt = 0.f;
+    for (int s = 0; s < T; ++s) {
+      const float tf = -1.44269504f * (float)(s + 1);
+      __syncthreads();
+      v0[i] = x;
+      v1[i] = xt;
+      if (s == 0) v2[i] = a.g[prob * D + i];
+      __syncthreads();
+      float u, ut;
+      if (s == 0) {
+        float dummy, y, sy, corr;
+        row_dot2(e + 3 * D * D, v0, v1, u, dummy);                    // u_0 = K_0 x_0
+        row_dot2(e + (long long)(T + 4) * D * D, v2, v1, y, dummy);   // y = S_0^{-1} g
+        __syncthreads();
+        v3[i] = y;
+        __syncthreads();
+        row_dot2(e + (long long)(T + 3) * D * D, v3, v1, sy, dummy);  // S_0 y
+        __syncthreads();
+        v3[i] = v2[i] - sy;                                           // the residual g - S_0 y
+        __syncthreads();
+        row_dot2(e + (long long)(T + 4) * D * D, v3, v1, corr, dummy);
+        ut = -(y + corr);
+      } else {
+        row_dot2(e + (long long)(3 + s) * D * D, v0, v1, u, ut);      // u_s = K_s x_s, both loops
+      }
+      tX[(long long)s * D + i] = x;
+      tXt[(long long)s * D + i] = xt;
+      tU[(long long)s * D + i] = u;
+      tUt[(long long)s * D + i] = ut;
+      const float gb = __builtin_amdgcn_exp2f(tf * lgB_m);
+      __syncthreads();
+      v2[i] = gb * u;
+      v3[i] = gb * ut;
+      __syncthreads();
+      const float am = 1.f + __builtin_amdgcn_exp2f(tf * lgA_m) * sA_m;
+      float bu = 0.f, but = 0.f;
+#pragma unroll
+      for (int j = 0; j < D; ++j) {
+        bu = __builtin_fmaf(bb[j], v2[j], bu);
+        but = __builtin_fmaf(bb[j], v3[j], but);
+      }
+      x = am * x + bu;
+      xt = am * xt + but;
+    }
+    tX[(long long)T * D + i] = x;
+    tXt[(long long)T * D + i] = xt;
+
+    // ---- backward: co-states, and the gradients of every step as they become available
+    float lam, lamt;
     __syncthreads();
-    if (e < 16) {          // dlgB_j: column sums
-      float s = 0.f;
+    v0[i] = x;
+    v1[i] = xt;
+    __syncthreads();
+    row_dot2(e + 2 * D * D, v0, v1, lam, lamt);  // lam_T = Q_T x_T
+    float dsA = 0.f, dlgA = 0.f, dR = 0.f, dlgQ = 0.f;
+    float dB[D], dQ[D], dQf[D], cB[D];
 #pragma unroll
-      for (int ii = 0; ii < 16; ++ii) s += M[0][16 * ii + e];
-      a.glgB[p * 16 + e] = s;
-    } else if (e < 32) {   // dlgQ_i: row i plus column i
-      const int c = e - 16;
-      float s = 0.f;
+    for (int j = 0; j < D; ++j) dB[j] = dQ[j] = dQf[j] = cB[j] = 0.f;
+    // v0, v1 hold x_t, xt_t on entry to iteration t
+    for (int t = T; t >= 1; --t) {
+      const int s = t - 1;
+      const float tf = -1.44269504f * (float)t, tt = (float)t;
+      const float xs = tX[(long long)s * D + i], xts = tXt[(long long)s * D + i];
+      const float us = tU[(long long)s * D + i], uts = tUt[(long long)s * D + i];
+      const float gamA = __builtin_amdgcn_exp2f(tf * lgA_m), gamQ = __builtin_amdgcn_exp2f(tf * lgQ_m);
+      __syncthreads();
+      v2[i] = us;
+      v3[i] = uts;
+      vgB[i] = __builtin_amdgcn_exp2f(tf * lgB_m);
+      vgQ[i] = gamQ;
+      __syncthreads();
+      const float gAii = lam * xts + lamt * xs;
+      dsA = __builtin_fmaf(gamA, gAii, dsA);
+      dlgA = __builtin_fmaf(-tt * gamA * sA_m, gAii, dlgA);
+      dR = __builtin_fmaf(uts, us, dR);
+      const float xi = v0[i], xti = v1[i];  // x_t[i], xt_t[i]
+      float hq = 0.f;
 #pragma unroll
-      for (int k = 0; k < 16; ++k) s += M[1][16 * c + k] + M[1][16 * k + c];
-      a.glgQ[p * 16 + c] = s;
+      for (int j = 0; j < D; ++j) {
+        const float gbij = lam * v3[j] + lamt * v2[j];                  // dl/dB_t [i][j]
+        dB[j] = __builtin_fmaf(vgB[j], gbij, dB[j]);
+        cB[j] = __builtin_fmaf(-tt * vgB[j] * bb[j], gbij, cB[j]);
+        const float gqij = 0.5f * (xti * v0[j] + xi * v1[j]);           // dl/dQ_t [i][j], symmetric
+        if (t < T) {
+          const float gm = gamQ * vgQ[j];
+          dQ[j] = __builtin_fmaf(gm, gqij, dQ[j]);
+          hq = __builtin_fmaf(gm * qq[j], gqij, hq);
+        } else {
+          dQf[j] = gqij;
+        }
+      }
+      dlgQ = __builtin_fmaf(-2.f * tt, hq, dlgQ);
+      // the co-state one step earlier: lam_{t-1} = Q_{t-1} x_{t-1} + a_t lam_t (t >= 2); lamt_0 = a_1 lamt_1
+      const float am = 1.f + gamA * sA_m;
+      if (t >= 2) {
+        const float gq1 = __builtin_amdgcn_exp2f(-1.44269504f * (float)(t - 1) * lgQ_m);
+        __syncthreads();
+        v0[i] = xs;   // x_{t-1}, xt_{t-1}: what the next iteration needs
+        v1[i] = xts;
+        v2[i] = gq1 * xs;
+        v3[i] = gq1 * xts;
+        __syncthreads();
+        float qa = 0.f, qc = 0.f;
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+          qa = __builtin_fmaf(qq[j], v2[j], qa);
+          qc = __builtin_fmaf(qq[j], v3[j], qc);
+        }
+        lam = gq1 * qa + am * lam;
+        lamt = gq1 * qc + am * lamt;
+      } else {
+        lamt = am * lamt;
+      }
+    }
+    // ---- outputs
+    if (valid) {
+      a.gx0[prob * D + i] = bad ? nanv : lamt;
+      a.gsA[prob * D + i] = bad ? nanv : dsA;
+      a.glgA[prob * D + i] = bad ? nanv : dlgA;
+      a.glgQ[prob * D + i] = bad ? nanv : dlgQ;
+      a.grinv[prob * D + i] = bad ? nanv : -dR / (rinv_m * rinv_m);
+    }
+    {  // dl/dlgB_j: the column sums of cB over the problem's lanes
+      float mine = 0.f;
+#pragma unroll
+      for (int j = 0; j < D; ++j) {
+        const float sj = sum16(cB[j]);
+        mine = (i == j) ? sj : mine;
+      }
+      if (valid) a.glgB[prob * D + i] = bad ? nanv : mine;
+    }
+    for (int k = 0; k < r; ++k) {  // the inner products with the basis matrices
+      float sb = 0.f, sq = 0.f, sf = 0.f;
+#pragma unroll
+      for (int j = 0; j < D; ++j) {
+        const float bk = ld1<TIn>(Bb, (long)k * 256 + i * D + j), qk = ld1<TIn>(Qb, (long)k * 256 + i * D + j);
+        sb = __builtin_fmaf(bk, dB[j], sb);
+        sq = __builtin_fmaf(qk, dQ[j], sq);
+        sf = __builtin_fmaf(qk, dQf[j], sf);
+      }
+      sb = sum16(sb);
+      sq = sum16(sq);
+      sf = sum16(sf);
+      if (valid && i == 0) {
+        a.gsB[prob * r + k] = bad ? nanv : sb;
+        a.gsQ[prob * r + k] = bad ? nanv : sq;
+        a.gsQf[prob * r + k] = bad ? nanv : sf;
+      }
+    }
+    if (valid) {  // rows of dl/dBbar, dl/dQbar, dl/dQ_T for the bases' sums
+      float* const keep = a.keep + q * 768;
+#pragma unroll
+      for (int j4 = 0; j4 < D; j4 += 4) {
+        const float f = bad ? nanv : 1.f;
+        *reinterpret_cast<floatx4*>(keep + i * D + j4) = floatx4{dB[j4] * f, dB[j4 + 1] * f, dB[j4 + 2] * f, dB[j4 + 3] * f};
+        *reinterpret_cast<floatx4*>(keep + 256 + i * D + j4) = floatx4{dQ[j4] * f, dQ[j4 + 1] * f, dQ[j4 + 2] * f, dQ[j4 + 3] * f};
+        *reinterpret_cast<floatx4*>(keep + 512 + i * D + j4) = floatx4{dQf[j4] * f, dQf[j4 + 1] * f, dQf[j4 + 2] * f, dQf[j4 + 3] * f};
+      }
     }
     __syncthreads();
-    M[0][e] = dBbar;
-    M[1][e] = dQbar;
-    M[2][e] = dQf;
-    float* const keep = a.keep + q * 768;
-    keep[e] = dBbar;
-    keep[256 + e] = dQbar;
-    keep[512 + e] = dQf;
-    __syncthreads();
-    // the 3 r inner products with the basis matrices: a wavefront per product, four entries per lane
-    for (int o = e >> 6; o < 3 * r; o += 4) {
-      const int which = o / r, k = o % r, lane = e & 63;
-      const TIn* basis = which == 0 ? Bb : Qb;
-      float s = 0.f;
-#pragma unroll
-      for (int x = 0; x < 4; ++x) s = __builtin_fmaf(ld1<TIn>(basis, (long)k * 256 + lane + 64 * x), M[which][lane + 64 * x], s);
-#pragma unroll
-      for (int sh = 1; sh < 64; sh <<= 1) s += __shfl_xor(s, sh, 64);
-      float* dst = which == 0 ? a.gsB : which == 1 ? a.gsQ : a.gsQf;
-      if (lane == 0) dst[p * r + k] = s;
-    }
   }
 }
 

@@ -39,10 +39,9 @@ hipError_t launch_cxt(const CxtArgs& a, bool bf16, int ppw, dim3 grid, hipStream
 int occupancy_cxt(bool bf16);
 hipError_t launch_rollout_cxt_forward(const CxtRolloutArgs& a, bool bf16, dim3 grid, hipStream_t st);
 
-// backward pass of the structured problems (ttc_cxt_backward.hpp): one workgroup per problem of the chunk (expand,
-// contract), one per slab of problems (basis), a plain fill
-hipError_t launch_cxt_expand(const CxtBackwardArgs& a, bool bf16, dim3 grid, hipStream_t st);
-hipError_t launch_cxt_contract(const CxtBackwardArgs& a, bool bf16, dim3 grid, hipStream_t st);
+// backward pass of the structured problems (ttc_cxt_backward.hpp): one wavefront per four problems of the chunk (vec),
+// one workgroup per slab of problems (basis), a plain fill
+hipError_t launch_cxt_backward_vec(const CxtBackwardArgs& a, bool bf16, dim3 grid, hipStream_t st);
 hipError_t launch_cxt_basis(const CxtBackwardArgs& a, bool bf16, hipStream_t st);
 hipError_t launch_zero_floats(float* dst, long long n, hipStream_t st);
 // the block around the structured solver (ttc_block.hpp)
