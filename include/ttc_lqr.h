@@ -310,9 +310,11 @@ typedef struct {
   int32_t *info;
 } ttc_lqr_cxt_grads_t;
 
-/* The problems are taken a chunk at a time: their T steps are written out densely into the workspace, the kernel of
- * ttc_lqr_backward_tv produces the per-step gradients there, and two small kernels carry them on to the outputs
- * (four launches per chunk, after one that clears the basis gradients).  workspace: DEVICE, 16-byte aligned,
+/* The problems are taken a chunk at a time, three launches per chunk after two that clear the basis gradients: the
+ * backward recursion of the forward pass once more, keeping every gain, S_0 and its inverse in the workspace; one sweep
+ * of sixteen lanes per problem over both closed loops, both co-state recursions and the gradients, contracted straight
+ * onto the parameterisation (no dense per-step matrices are formed); the sums for the bases.  Bbasis and Qbasis have to
+ * be 16-byte aligned here (TTC_ERR_INVALID_ARG otherwise).  workspace: DEVICE, 16-byte aligned,
  * ttc_lqr_backward_cxt_workspace_bytes(problem) bytes (about 1 GiB for large batches; TTC_ERR_WORKSPACE otherwise).
  * Allocates nothing; asynchronous on hip_stream. */
 size_t ttc_lqr_backward_cxt_workspace_bytes(const ttc_lqr_cxt_problem_t *problem);

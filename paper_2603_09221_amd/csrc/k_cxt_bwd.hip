@@ -9,7 +9,7 @@ hipError_t launch_cxt_backward_vec(const CxtBackwardArgs& a, bool bf16, dim3 gri
   return hipGetLastError();
 }
 hipError_t launch_cxt_basis(const CxtBackwardArgs& a, bool bf16, hipStream_t st) {
-  const dim3 grid((unsigned)((a.count + CXT_BASIS_SLAB - 1) / CXT_BASIS_SLAB));
+  const dim3 grid((unsigned)((a.count + a.basis_slab - 1) / a.basis_slab));
   if (bf16) hipLaunchKernelGGL((cxt_basis_kernel<uint16_t>), grid, dim3(256), 0, st, a);
   else hipLaunchKernelGGL((cxt_basis_kernel<float>), grid, dim3(256), 0, st, a);
   return hipGetLastError();

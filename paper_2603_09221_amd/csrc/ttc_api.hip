@@ -880,6 +880,8 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
   for (const float* ptr : outs)
     if ((q->n > 0 && !ptr) || !ttc::aligned_ptr(ptr, 4)) return TTC_ERR_INVALID_ARG;  // an empty batch has no per-problem arrays
   if (q->n > 0 && !grad_u0) return TTC_ERR_INVALID_ARG;
+  // the kernels read the bases' rows with 16-byte (float32) or 8-byte (bfloat16) loads
+  if (q->n > 0 && (!ttc::aligned_ptr(q->Bbasis, 16) || !ttc::aligned_ptr(q->Qbasis, 16))) return TTC_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   // the sums over the problems start from zero (a fill kernel: also safe under stream capture)
   if (ttc::launch_zero_floats(gr->gBbasis, (long long)q->r * 256, st) != hipSuccess) return TTC_ERR_DEVICE;
@@ -922,6 +924,9 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
     a.info = gr->info ? gr->info : info_ws - first;  // indexed by the problem's number in the batch
     if (run_cxt(sc, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;
     const long long groups = (a.count + 3) / 4;
+    // slabs of the basis sums: four workgroups per compute unit when the chunk is large, never under the smallest slab
+    const long long slab = (a.count + 4LL * ttc::cu_count() - 1) / (4LL * ttc::cu_count());
+    a.basis_slab = (int)(slab < ttc::CXT_BASIS_SLAB ? ttc::CXT_BASIS_SLAB : slab > 4096 ? 4096 : slab);
     if (ttc::launch_cxt_backward_vec(a, bf16, dim3((unsigned)(groups < vgrid ? groups : vgrid)), st) != hipSuccess)
       return TTC_ERR_DEVICE;
     if (ttc::launch_cxt_basis(a, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;

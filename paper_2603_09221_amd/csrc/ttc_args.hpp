@@ -86,10 +86,12 @@ struct CxtRolloutArgs {
 };
 
 // ---- backward pass of the structured problems (ttc_cxt_backward.hpp)
+constexpr int CXT_BASIS_SLAB = 32;  // the smallest slab of the basis sums
 struct CxtBackwardArgs {
   CxtArgs c;             // the problems (inputs only, the whole batch; c.s.n = all problems)
   long long first;       // the chunk: problems first .. first + count - 1
   long long count;
+  int basis_slab;        // problems per workgroup of the basis sums (>= CXT_BASIS_SLAB: atomic additions stay rare)
   float* roll;           // (count, T + 5, 256): what solve_cxt_kernel leaves for the backward pass (c.roll_ws layout)
   float* traj;           // (count, 4, T + 1, 16): the primal and dual states and controls
   float* keep;           // (count, 3, 256): dl/dBbar, dl/dQbar, dl/dQ_T

@@ -22,16 +22,64 @@
 
 namespace ttc {
 
-// The backward pass proper, on vectors: sixteen lanes per problem (four problems per wavefront), lane i owning entry
-// i of every vector and row i of every 16 x 16 matrix it accumulates.  solve_cxt_kernel has left, per problem,
-// Bbar, Qbar, Q_T, the gains K_0 .. K_{T-1}, S_0 and S_0^{-1}.  Forward: both closed loops (Alg. 1; the dual one starts
-// from ut_0 = -S_0^{-1} g, refined once with S_0, from the state 0), states and controls to the workspace.  Backward:
-// the co-states of both (Alg. 2) with A_t diagonal and Q_t = Gamma^t Qbar Gamma^t, and in the same sweep the
-// gradients of Thm 3.2 contracted straight onto the parameterisation: no per-step gradient matrix is ever formed.
+// Orders the wavefront's own LDS traffic without waiting for its global loads: a workgroup here is one wavefront,
+// whose LDS instructions execute in issue order, so what one lane wrote is what another lane reads after this point
+// once the compiler keeps the order.  A workgroup barrier would also drain every load in flight, which the kernel
+// below relies on not happening (it fetches the next step's operands while the current step is computed).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Row i (sixteen numbers) of a row-major 16 x 16 matrix in global memory.
+struct Row16 {
+  floatx4 v[4];
+};
+template <typename T>
+__device__ __forceinline__ Row16 load_row16(const T* M, int i) {
+  Row16 r;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) r.v[c] = ld4<T>(M, (long)i * 16 + 4 * c);
+  return r;
+}
+// <row, v> and <row, w> for two vectors in LDS
+__device__ __forceinline__ void row_dot2(const Row16& m, const float* va, const float* vc, float& ya, float& yc) {
+  float sa = 0.f, sc = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      sa = __builtin_fmaf(m.v[c][e], va[4 * c + e], sa);
+      sc = __builtin_fmaf(m.v[c][e], vc[4 * c + e], sc);
+    }
+  }
+  ya = sa;
+  yc = sc;
+}
+__device__ __forceinline__ float row_dot(const Row16& m, const float* va) {
+  float sa = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sa = __builtin_fmaf(m.v[c][e], va[4 * c + e], sa);
+  }
+  return sa;
+}
+
+// The backward pass proper, on vectors: sixteen lanes per problem (four problems per wavefront, one wavefront per
+// workgroup), lane i owning entry i of every vector and row i of every 16 x 16 matrix it accumulates.
+// solve_cxt_kernel has left, per problem, Bbar, Qbar, Q_T, the gains K_0 .. K_{T-1}, S_0 and S_0^{-1}.  Forward: both
+// closed loops (Alg. 1; the dual one starts from ut_0 = -S_0^{-1} g, refined once with S_0, from the state 0), states
+// and controls to the workspace.  Backward: the co-states of both (Alg. 2) with A_t diagonal and
+// Q_t = Gamma^t Qbar Gamma^t, and in the same sweep the gradients of Thm 3.2 contracted straight onto the
+// parameterisation: no per-step gradient matrix is ever formed.  Every step is a short chain of dependent
+// operations, so the rows of the coming step (a gain, the stored states and controls, a basis matrix) are requested
+// one step ahead and the lanes exchange vectors through LDS without a barrier that would wait for them.
 template <typename TIn>
 __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardArgs a) {
   constexpr int D = 16;
-  __shared__ float vb[4][6][D];  // per problem: vectors every lane of the problem reads
+  __shared__ __attribute__((aligned(16))) float vb[4][6][D];  // per problem: vectors every lane of the problem reads
   const SolveArgs& p = a.c.s;
   const int T = p.T, r = a.c.r;
   const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
@@ -40,21 +88,12 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
   const float nanv = __builtin_nanf("");
   const TIn* const Bb = reinterpret_cast<const TIn*>(a.c.Bbasis);
   const TIn* const Qb = reinterpret_cast<const TIn*>(a.c.Qbasis);
-  // sum_j M[i][j] v[j] for two vectors at once, M row-major in global memory
-  auto row_dot2 = [&](const float* M, const float* va, const float* vc, float& ya, float& yc) {
-    float sa = 0.f, sc = 0.f;
-#pragma unroll
-    for (int j4 = 0; j4 < D; j4 += 4) {
-      const floatx4 m = *reinterpret_cast<const floatx4*>(M + i * D + j4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        sa = __builtin_fmaf(m[e], va[j4 + e], sa);
-        sc = __builtin_fmaf(m[e], vc[j4 + e], sc);
-      }
-    }
-    ya = sa;
-    yc = sc;
-  };
+  float* const v0 = vb[g][0];
+  float* const v1 = vb[g][1];
+  float* const v2 = vb[g][2];
+  float* const v3 = vb[g][3];
+  float* const vgB = vb[g][4];
+  float* const vgQ = vb[g][5];
   for (long long grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
     const bool valid = grp * 4 + g < a.count;
     const long long q = valid ? grp * 4 + g : a.count - 1;  // within the chunk
@@ -64,65 +103,61 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
     float* const tXt = tX + (long long)(T + 1) * D;
     float* const tU = tXt + (long long)(T + 1) * D;
     float* const tUt = tU + (long long)(T + 1) * D;
+    // everything the first step needs is requested at once
+    Row16 kc = load_row16(e + 3 * D * D, i);                              // K_0
+    const Row16 sinv = load_row16(e + (long long)(T + 4) * D * D, i);     // S_0^{-1}
+    const Row16 s0 = load_row16(e + (long long)(T + 3) * D * D, i);       // S_0
+    const Row16 bbr = load_row16(e, i);                                   // Bbar
     const float sA_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sA), prob * D + i);
     const float lgA_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgA), prob * D + i);
     const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgB), prob * D + i);
     const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgQ), prob * D + i);
     const float rinv_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.rinv), prob * D + i);
+    const float g_m = a.g[prob * D + i];
+    float x = ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), prob * D + i), xt = 0.f;
     const bool bad = a.info && a.info[prob] != 0;
-    float bb[D], qq[D];  // row i of Bbar and of Qbar
+    float bb[D];  // row i of Bbar
 #pragma unroll
-    for (int j4 = 0; j4 < D; j4 += 4) {
-      const floatx4 b4 = *reinterpret_cast<const floatx4*>(e + i * D + j4);
-      const floatx4 q4 = *reinterpret_cast<const floatx4*>(e + D * D + i * D + j4);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        bb[j4 + k] = b4[k];
-        qq[j4 + k] = q4[k];
-      }
-    }
-    float* const v0 = vb[g][0];
-    float* const v1 = vb[g][1];
-    float* const v2 = vb[g][2];
-    float* const v3 = vb[g][3];
-    float* const vgB = vb[g][4];
-    float* const vgQ = vb[g][5];
+    for (int j = 0; j < D; ++j) bb[j] = bbr.v[j >> 2][j & 3];
 
     // ---- forward: both closed loops
-    float x = ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), prob * D + i), xt = 0.f;
+    float u, ut;
+    {  // step 0: u_0 = K_0 x_0; ut_0 = -(y + S_0^{-1} (g - S_0 y)), y = S_0^{-1} g
+      wave_lds_sync();
+      v0[i] = x;
+      v2[i] = g_m;
+      wave_lds_sync();
+      u = row_dot(kc, v0);
+      const float y = row_dot(sinv, v2);
+      v3[i] = y;
+      wave_lds_sync();
+      const float sy = row_dot(s0, v3);
+      wave_lds_sync();
+      v3[i] = g_m - sy;
+      wave_lds_sync();
+      ut = -(y + row_dot(sinv, v3));
+    }
     for (int s = 0; s < T; ++s) {
       const float tf = -1.44269504f * (float)(s + 1);
-      __syncthreads();
-      v0[i] = x;
-      v1[i] = xt;
-      if (s == 0) v2[i] = a.g[prob * D + i];
-      __syncthreads();
-      float u, ut;
-      if (s == 0) {
-        float dummy, y, sy, corr;
-        row_dot2(e + 3 * D * D, v0, v1, u, dummy);                    // u_0 = K_0 x_0
-        row_dot2(e + (long long)(T + 4) * D * D, v2, v1, y, dummy);   // y = S_0^{-1} g
-        __syncthreads();
-        v3[i] = y;
-        __syncthreads();
-        row_dot2(e + (long long)(T + 3) * D * D, v3, v1, sy, dummy);  // S_0 y
-        __syncthreads();
-        v3[i] = v2[i] - sy;                                           // the residual g - S_0 y
-        __syncthreads();
-        row_dot2(e + (long long)(T + 4) * D * D, v3, v1, corr, dummy);
-        ut = -(y + corr);
-      } else {
-        row_dot2(e + (long long)(3 + s) * D * D, v0, v1, u, ut);      // u_s = K_s x_s, both loops
+      Row16 kn = kc;
+      if (s + 1 < T) kn = load_row16(e + (long long)(4 + s) * D * D, i);  // the next step's gain, or Q_T after the last
+      else kn = load_row16(e + 2 * D * D, i);
+      if (s > 0) {
+        wave_lds_sync();
+        v0[i] = x;
+        v1[i] = xt;
+        wave_lds_sync();
+        row_dot2(kc, v0, v1, u, ut);  // u_s = K_s x_s, both loops
       }
       tX[(long long)s * D + i] = x;
       tXt[(long long)s * D + i] = xt;
       tU[(long long)s * D + i] = u;
       tUt[(long long)s * D + i] = ut;
       const float gb = __builtin_amdgcn_exp2f(tf * lgB_m);
-      __syncthreads();
+      wave_lds_sync();
       v2[i] = gb * u;
       v3[i] = gb * ut;
-      __syncthreads();
+      wave_lds_sync();
       const float am = 1.f + __builtin_amdgcn_exp2f(tf * lgA_m) * sA_m;
       float bu = 0.f, but = 0.f;
 #pragma unroll
@@ -132,17 +167,24 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
       }
       x = am * x + bu;
       xt = am * xt + but;
+      kc = kn;
     }
     tX[(long long)T * D + i] = x;
     tXt[(long long)T * D + i] = xt;
 
     // ---- backward: co-states, and the gradients of every step as they become available
+    const Row16 qqr = load_row16(e + D * D, i);  // Qbar
+    float nxs = tX[(long long)(T - 1) * D + i], nxts = tXt[(long long)(T - 1) * D + i];
+    float nus = tU[(long long)(T - 1) * D + i], nuts = tUt[(long long)(T - 1) * D + i];
     float lam, lamt;
-    __syncthreads();
+    wave_lds_sync();
     v0[i] = x;
     v1[i] = xt;
-    __syncthreads();
-    row_dot2(e + 2 * D * D, v0, v1, lam, lamt);  // lam_T = Q_T x_T
+    wave_lds_sync();
+    row_dot2(kc, v0, v1, lam, lamt);  // lam_T = Q_T x_T
+    float qq[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) qq[j] = qqr.v[j >> 2][j & 3];
     float dsA = 0.f, dlgA = 0.f, dR = 0.f, dlgQ = 0.f;
     float dB[D], dQ[D], dQf[D], cB[D];
 #pragma unroll
@@ -151,15 +193,20 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
     for (int t = T; t >= 1; --t) {
       const int s = t - 1;
       const float tf = -1.44269504f * (float)t, tt = (float)t;
-      const float xs = tX[(long long)s * D + i], xts = tXt[(long long)s * D + i];
-      const float us = tU[(long long)s * D + i], uts = tUt[(long long)s * D + i];
+      const float xs = nxs, xts = nxts, us = nus, uts = nuts;
+      if (s >= 1) {  // the stored step before, for the next iteration
+        nxs = tX[(long long)(s - 1) * D + i];
+        nxts = tXt[(long long)(s - 1) * D + i];
+        nus = tU[(long long)(s - 1) * D + i];
+        nuts = tUt[(long long)(s - 1) * D + i];
+      }
       const float gamA = __builtin_amdgcn_exp2f(tf * lgA_m), gamQ = __builtin_amdgcn_exp2f(tf * lgQ_m);
-      __syncthreads();
+      wave_lds_sync();
       v2[i] = us;
       v3[i] = uts;
       vgB[i] = __builtin_amdgcn_exp2f(tf * lgB_m);
       vgQ[i] = gamQ;
-      __syncthreads();
+      wave_lds_sync();
       const float gAii = lam * xts + lamt * xs;
       dsA = __builtin_fmaf(gamA, gAii, dsA);
       dlgA = __builtin_fmaf(-tt * gamA * sA_m, gAii, dlgA);
@@ -185,12 +232,12 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
       const float am = 1.f + gamA * sA_m;
       if (t >= 2) {
         const float gq1 = __builtin_amdgcn_exp2f(-1.44269504f * (float)(t - 1) * lgQ_m);
-        __syncthreads();
+        wave_lds_sync();
         v0[i] = xs;   // x_{t-1}, xt_{t-1}: what the next iteration needs
         v1[i] = xts;
         v2[i] = gq1 * xs;
         v3[i] = gq1 * xts;
-        __syncthreads();
+        wave_lds_sync();
         float qa = 0.f, qc = 0.f;
 #pragma unroll
         for (int j = 0; j < D; ++j) {
@@ -204,6 +251,7 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
       }
     }
     // ---- outputs
+    Row16 bk = load_row16(Bb, i), qk = load_row16(Qb, i);  // rows i of the first basis matrices (r >= 1)
     if (valid) {
       a.gx0[prob * D + i] = bad ? nanv : lamt;
       a.gsA[prob * D + i] = bad ? nanv : dsA;
@@ -220,24 +268,6 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
       }
       if (valid) a.glgB[prob * D + i] = bad ? nanv : mine;
     }
-    for (int k = 0; k < r; ++k) {  // the inner products with the basis matrices
-      float sb = 0.f, sq = 0.f, sf = 0.f;
-#pragma unroll
-      for (int j = 0; j < D; ++j) {
-        const float bk = ld1<TIn>(Bb, (long)k * 256 + i * D + j), qk = ld1<TIn>(Qb, (long)k * 256 + i * D + j);
-        sb = __builtin_fmaf(bk, dB[j], sb);
-        sq = __builtin_fmaf(qk, dQ[j], sq);
-        sf = __builtin_fmaf(qk, dQf[j], sf);
-      }
-      sb = sum16(sb);
-      sq = sum16(sq);
-      sf = sum16(sf);
-      if (valid && i == 0) {
-        a.gsB[prob * r + k] = bad ? nanv : sb;
-        a.gsQ[prob * r + k] = bad ? nanv : sq;
-        a.gsQf[prob * r + k] = bad ? nanv : sf;
-      }
-    }
     if (valid) {  // rows of dl/dBbar, dl/dQbar, dl/dQ_T for the bases' sums
       float* const keep = a.keep + q * 768;
 #pragma unroll
@@ -248,36 +278,70 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
         *reinterpret_cast<floatx4*>(keep + 512 + i * D + j4) = floatx4{dQf[j4] * f, dQf[j4 + 1] * f, dQf[j4 + 2] * f, dQf[j4 + 3] * f};
       }
     }
-    __syncthreads();
+    for (int k = 0; k < r; ++k) {  // the inner products with the basis matrices, the next one's rows on their way
+      const Row16 bc = bk, qc = qk;
+      if (k + 1 < r) {
+        bk = load_row16(Bb + (long)(k + 1) * 256, i);
+        qk = load_row16(Qb + (long)(k + 1) * 256, i);
+      }
+      float sb = 0.f, sq = 0.f, sf = 0.f;
+#pragma unroll
+      for (int j = 0; j < D; ++j) {
+        sb = __builtin_fmaf(bc.v[j >> 2][j & 3], dB[j], sb);
+        sq = __builtin_fmaf(qc.v[j >> 2][j & 3], dQ[j], sq);
+        sf = __builtin_fmaf(qc.v[j >> 2][j & 3], dQf[j], sf);
+      }
+      sb = sum16(sb);
+      sq = sum16(sq);
+      sf = sum16(sf);
+      if (valid && i == 0) {
+        a.gsB[prob * r + k] = bad ? nanv : sb;
+        a.gsQ[prob * r + k] = bad ? nanv : sq;
+        a.gsQf[prob * r + k] = bad ? nanv : sf;
+      }
+    }
+    wave_lds_sync();
   }
 }
 
 // gBbasis[k] += sum_p sB[p][k] dBbar[p], gQbasis[k] += sum_p (sQ[p][k] dQbar[p] + sQf[p][k] dQ_T[p]) over a slab of
-// the chunk's problems per workgroup; thread e owns entry e of every basis matrix, the sums of a slab are added to the
+// a.basis_slab of the chunk's problems per workgroup; thread e owns entry e of every basis matrix, the sums of a slab are added to the
 // caller's arrays with one atomic addition per entry (the order of the slabs, and with it the last bits, may vary).
-constexpr int CXT_BASIS_SLAB = 32;
 template <typename TIn>
 __global__ void __launch_bounds__(256) cxt_basis_kernel(const CxtBackwardArgs a) {
   const int e = threadIdx.x;
   const int r = a.c.r;
-  const long long q0 = (long long)blockIdx.x * CXT_BASIS_SLAB;
-  long long q1 = q0 + CXT_BASIS_SLAB;
+  const long long q0 = (long long)blockIdx.x * a.basis_slab;
+  long long q1 = q0 + a.basis_slab;
   q1 = q1 < a.count ? q1 : a.count;
   for (int k0 = 0; k0 < r; k0 += 16) {  // sixteen basis matrices of each group at a time (registers)
     float sb[16], sq[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) sb[k] = sq[k] = 0.f;
+    // Lane 16 g + k of every wavefront reads coefficient k0 + k of group g (sB, sQ, sQf) with one load per problem
+    // and the others take it from that lane; the next problem's values are fetched while this one's products are
+    // formed.
+    const int lane = threadIdx.x & 63, grp = lane >> 4, kk = k0 + (lane & 15);
+    const TIn* const cbase = reinterpret_cast<const TIn*>(grp == 0 ? a.c.sB : grp == 1 ? a.c.sQ : a.c.sQf);
+    const bool cread = grp < 3 && kk < r;
+    float nB = 0.f, nQ = 0.f, nF = 0.f, nC = 0.f;
+    if (q0 < q1) {
+      const float* keep = a.keep + q0 * 768;
+      nB = keep[e]; nQ = keep[256 + e]; nF = keep[512 + e];
+      if (cread) nC = ld1<TIn>(cbase, (a.first + q0) * r + kk);
+    }
     for (long long q = q0; q < q1; ++q) {
-      const long long p = a.first + q;
-      const float* keep = a.keep + q * 768;
-      const float dBbar = keep[e], dQbar = keep[256 + e], dQf = keep[512 + e];
+      const float dBbar = nB, dQbar = nQ, dQf = nF, cv = nC;
+      if (q + 1 < q1) {
+        const float* keep = a.keep + (q + 1) * 768;
+        nB = keep[e]; nQ = keep[256 + e]; nF = keep[512 + e];
+        if (cread) nC = ld1<TIn>(cbase, (a.first + q + 1) * r + kk);
+      }
 #pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        if (k0 + k < r) {
-          sb[k] = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sB), p * r + k0 + k), dBbar, sb[k]);
-          sq[k] = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sQ), p * r + k0 + k), dQbar, sq[k]);
-          sq[k] = __builtin_fmaf(ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sQf), p * r + k0 + k), dQf, sq[k]);
-        }
+      for (int k = 0; k < 16; ++k) {  // coefficients past r were read as zero
+        sb[k] = __builtin_fmaf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cv), k)), dBbar, sb[k]);
+        sq[k] = __builtin_fmaf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cv), 16 + k)), dQbar, sq[k]);
+        sq[k] = __builtin_fmaf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cv), 32 + k)), dQf, sq[k]);
       }
     }
 #pragma unroll
