@@ -8,7 +8,7 @@
 // scalings:  with V = P B_t (P = P_{t}, symmetric) and a = diag(A_t),
 //     S = R + B_t^T V,   F = B_t^T P A_t = V^T diag(a),   A_t^T P A_t = diag(a) P diag(a),
 //     K = -S^{-1} F,   P_{t-1} = Q_{t-1} + diag(a) P diag(a) + F^T K,
-// four products and one inverse of a positive definite matrix per step (S^{-1} is formed in place, half
+// four products and one inverse of a positive definite matrix per step (S^{-1} is formed in place, negated, half
 // the eliminations of a solve with sixteen right-hand sides; the product S^{-1} F goes to the matrix cores).  Four problems share a wavefront, as in the
 // other d = 16 kernels.  At d = 16 the accumulator layout of a matrix (lane (i, g): column i, rows
 // 4g..4g+3) is the A-operand layout of its transpose, which is what lets Bbar, V and P be used in both
@@ -39,7 +39,6 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
   float (*const coef)[3][CXT_RMAX] = reinterpret_cast<float (*)[3][CXT_RMAX]>(&Vt[0][0]);
   __shared__ __attribute__((aligned(16))) float vecs[2][PPW][4][D];      // a_t, gamma_B^t, gamma_Q^(t-1), 1/rinv;
                                                                          // steps alternate between the two copies
-  __shared__ float s_red[C::NW];
   const SolveArgs& p = ca.s;
   const int r = ca.r;
   const long long slots = ca.roll_slots ? ca.roll_slots : p.T + 3;  // matrices per problem in roll_ws
@@ -77,10 +76,12 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
     const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgB), pg * D + i);
     const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgQ), pg * D + i);
     vecs[0][gq][3][i] = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(ca.rinv), pg * D + i);
-    for (int k = i; k < r; k += 16) {
-      coef[gq][0][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sB), pg * r + k);
-      coef[gq][1][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQ), pg * r + k);
-      coef[gq][2][k] = ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQf), pg * r + k);
+    const float x0_m = ca.roll_ws ? 0.f : ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), pg * p.sx0 + i);  // for the outputs
+    const int r4 = (r + 3) & ~3;  // the coefficients are read four at a time: zeros past r
+    for (int k = i; k < r4; k += 16) {
+      coef[gq][0][k] = k < r ? ld1<TIn>(reinterpret_cast<const TIn*>(ca.sB), pg * r + k) : 0.f;
+      coef[gq][1][k] = k < r ? ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQ), pg * r + k) : 0.f;
+      coef[gq][2][k] = k < r ? ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQf), pg * r + k) : 0.f;
     }
     __syncthreads();
 
@@ -94,22 +95,31 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
       pn[q][0][0] = Bbar[q];
       rI[q] = vecs[0][q][3][i];
     }
-#pragma unroll 2
-    for (int k = 0; k < r; ++k) {
-      floatx4 bb, qb;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        bb[v] = ld1<TIn>(Bbasis, (long)k * D * D + (4 * g + v) * D + i);
-        qb[v] = ld1<TIn>(Qbasis, (long)k * D * D + (4 * g + v) * D + i);
-      }
+    for (int k0 = 0; k0 < r4; k0 += 4) {
+      floatx4 cb[PPW], cq[PPW], cf[PPW];
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
-        const float cb = coef[q][0][k], cq = coef[q][1][k], cf = coef[q][2][k];
+        cb[q] = *reinterpret_cast<const floatx4*>(&coef[q][0][k0]);
+        cq[q] = *reinterpret_cast<const floatx4*>(&coef[q][1][k0]);
+        cf[q] = *reinterpret_cast<const floatx4*>(&coef[q][2][k0]);
+      }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int k = k0 + kk < r ? k0 + kk : r - 1;  // past r: any matrix, its coefficients are zero
+        floatx4 bb, qb;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          Bbar[q][v] += cb * bb[v];
-          Qbar[q][v] += cq * qb[v];
-          pn[q][0][0][v] += cf * qb[v];  // P_T = Q_T
+          bb[v] = ld1<TIn>(Bbasis, (long)k * D * D + (4 * g + v) * D + i);
+          qb[v] = ld1<TIn>(Qbasis, (long)k * D * D + (4 * g + v) * D + i);
+        }
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            Bbar[q][v] += cb[q][kk] * bb[v];
+            Qbar[q][v] += cq[q][kk] * qb[v];
+            pn[q][0][0][v] += cf[q][kk] * qb[v];  // P_T = Q_T
+          }
         }
       }
     }
@@ -175,7 +185,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
         const float aI = vec[q][0][i];
         put_acc(Vt[q], PT, accVT[q][0][0]);  // V^T[4g+v][i] = V[i][4g+v]
 #pragma unroll
-        for (int v = 0; v < 4; ++v) cFT[q][0][v] = -aI * accVT[q][0][0][v];  // rows of -F^T = -diag(a) V
+        for (int v = 0; v < 4; ++v) cFT[q][0][v] = aI * accVT[q][0][0][v];  // rows of F^T = diag(a) V
       }
       __syncthreads();
       floatx4 accW[PPW][C::RB][C::NT];
@@ -202,33 +212,35 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
       }
       __syncthreads();
       tm.toc(2);
-      note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
+      note(invert_rows16<true>(Wmine, lane));  // left halves: -S^{-1}, so that the next product is the gain itself
       tm.toc(1);
       if (s == 0 && slots == p.T + 5) {  // and S_0^{-1}: one 16-byte piece per lane, row-major
 #pragma unroll
         for (int q = 0; q < PPW; ++q)
-          if (valid[q])
+          if (valid[q]) {
+            const floatx4 ms = *reinterpret_cast<const floatx4*>(Wm[q] + (lane >> 2) * C::PITCH + 4 * (lane & 3));
             *reinterpret_cast<floatx4*>(ca.roll_ws + (prob[q] * slots + p.T + 4) * D * D + 4 * lane) =
-                *reinterpret_cast<const floatx4*>(Wm[q] + (lane >> 2) * C::PITCH + 4 * (lane & 3));
+                floatx4{-ms[0], -ms[1], -ms[2], -ms[3]};
+          }
       }
       {
         float cSi[PPW][C::RB][C::KS];
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
-          load_aop_lds<D>(Wm[q], cSi[q], w, i, g);  // rows of S^{-1}
+          load_aop_lds<D>(Wm[q], cSi[q], w, i, g);  // rows of -S^{-1}
           zero_acc<D>(accW[q]);
         }
-        // cFT holds -F^T in the A-operand layout, which is the accumulator layout of -F: B operand of W
+        // cFT holds F^T in the A-operand layout, which is the accumulator layout of F: B operand of the gain
 #pragma unroll
-        for (int t = 0; t < 4; ++t)  // K = -W = S^{-1} (-F)
+        for (int t = 0; t < 4; ++t)  // K = (-S^{-1}) F
 #pragma unroll
           for (int q = 0; q < PPW; ++q)
             accW[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cSi[q][0][t], cFT[q][0][t], accW[q][0][0], 0, 0, 0);
 #pragma unroll
-        for (int t = 0; t < 4; ++t)  // P += (-F^T) W: the accumulator layout of W = -K is its B operand
+        for (int t = 0; t < 4; ++t)  // P += F^T K: the accumulator layout of K is its B operand
 #pragma unroll
           for (int q = 0; q < PPW; ++q)
-            pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cFT[q][0][t], -accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
+            pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(cFT[q][0][t], accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
       }
       if (ca.roll_ws) {  // the gain K_s of this step, for the forward sweep
 #pragma unroll
@@ -250,7 +262,11 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
         tm.toc(2);
       } else {
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) put_acc(Wm[q] + D, C::PITCH, pn[q][0][0]);  // P_0 (no cost on x_0)
+        for (int q = 0; q < PPW; ++q) {
+          put_acc(Wm[q] + D, C::PITCH, pn[q][0][0]);  // P_0 (no cost on x_0)
+          put_acc(Vt[q], PT, accW[q][0][0]);          // K_0, row-major
+        }
+        vecs[1][gq][0][i] = x0_m;
         __syncthreads();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
@@ -260,19 +276,49 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
           store_rows<D>(Wm[q], pn[q], w, i, g);  // symmetric P_0
         }
         __syncthreads();
+        if (ca.roll_ws) {  // the roll-out wants the gains (written above) and info only
 #pragma unroll
-        for (int q = 0; q < PPW; ++q) {
-          if (!valid[q]) continue;  // uniform over the wavefront
-          if (ca.roll_ws) {         // the roll-out wants the gains (written above) and info only
-            if (tid == 0 && p.info) p.info[prob[q]] = info[q];
-            continue;
+          for (int q = 0; q < PPW; ++q)
+            if (valid[q] && tid == 0 && p.info) p.info[prob[q]] = info[q];
+        } else {
+          // All the wavefront's problems at once: lane (i, g) takes row i of its problem's K_0 and P_0 for
+          // u_0 = K_0 x_0 and value = x_0^T P_0 x_0; the matrices leave as one 16-byte piece per lane and problem.
+          const float nanv = __builtin_nanf("");
+          const float* const xv = vecs[1][gq][0];
+          float u = 0.f, pw = 0.f;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const floatx4 kr = *reinterpret_cast<const floatx4*>(Vt[gq] + i * PT + 4 * c);
+            const floatx4 pr = *reinterpret_cast<const floatx4*>(Wm[gq] + i * C::PITCH + 4 * c);
+            const floatx4 xr = *reinterpret_cast<const floatx4*>(xv + 4 * c);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              u = __builtin_fmaf(kr[v], xr[v], u);
+              pw = __builtin_fmaf(pr[v], xr[v], pw);
+            }
           }
-          const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
-          floatx4 acc[C::RB][C::NT];
+          const float val = sum16(x0_m * pw);
+          int myinfo = info[0];
 #pragma unroll
-          for (int v = 0; v < 4; ++v) acc[0][0][v] = -accW[q][0][0][v];  // rows of -K_0
-          emit_gain<D, TIn>(p, prob[q], acc, x0p, info[q], tid);
-          emit_value<D, TIn>(p, prob[q], Wm[q], static_cast<const TIn*>(nullptr), x0p, info[q], s_red, tid);
+          for (int q = 1; q < PPW; ++q) myinfo = (gq == q) ? info[q] : myinfo;
+          if (quad * PPW + gq < p.n && (PPW == 4 || g == 0)) {
+            p.u0[pg * D + i] = myinfo ? nanv : u;
+            if (i == 0) {
+              if (p.value) p.value[pg] = myinfo ? nanv : val;
+              if (p.info) p.info[pg] = myinfo;
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) {
+            if (!valid[q]) continue;  // uniform over the wavefront
+            const floatx4 nan4 = floatx4{nanv, nanv, nanv, nanv};
+            if (p.K0)
+              *reinterpret_cast<floatx4*>(p.K0 + prob[q] * (long)D * D + 4 * lane) =
+                  info[q] ? nan4 : *reinterpret_cast<const floatx4*>(Vt[q] + (lane >> 2) * PT + 4 * (lane & 3));
+            if (p.P0)
+              *reinterpret_cast<floatx4*>(p.P0 + prob[q] * (long)D * D + 4 * lane) =
+                  info[q] ? nan4 : *reinterpret_cast<const floatx4*>(Wm[q] + (lane >> 2) * C::PITCH + 4 * (lane & 3));
+          }
         }
         __syncthreads();
         tm.toc(3);

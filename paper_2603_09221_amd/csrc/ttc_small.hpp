@@ -103,7 +103,8 @@ __device__ __forceinline__ int solve_rows16(float* Wq, int lane) {
 // column j of M, which has just become a unit vector.  Rows are scaled by their pivots at the end.
 // The pivot row is broadcast within each row of 16 lanes by DPP.  The caller synchronises before (M
 // complete in LDS); the function ends with a barrier.  Returns, per lane, whether its problem broke
-// down (a pivot that is not positive and finite).
+// down (a pivot that is not positive and finite).  NEGATE leaves -M^{-1} instead (the sign rides on the final scaling).
+template <bool NEGATE = false>
 __device__ __forceinline__ int invert_rows16(float* Wq, int lane) {
   using C = Cfg<16>;
   const int r = lane & 15;
@@ -153,7 +154,7 @@ __device__ __forceinline__ int invert_rows16(float* Wq, int lane) {
 #undef TTC_AK
     a[j] = mine ? 1.f : nl;  // column j of the right part
   });
-  const float s = __builtin_amdgcn_rcpf(mypiv);
+  const float s = NEGATE ? -__builtin_amdgcn_rcpf(mypiv) : __builtin_amdgcn_rcpf(mypiv);
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     floatx4 t;
