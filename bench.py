@@ -477,6 +477,12 @@ def bench_scan(args):
     b = synth.make_tv_batch(n, d, d, T, seed=0, device=dev)
     ws = torch.empty((n * T * 3 * d * d * 4,), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+    if args.calib_copy_mib:
+        src = torch.ones((args.calib_copy_mib << 18,), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
     out = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, b.R, b.x0, workspace=ws, stream=stream)
     seq = binding.ttc_lqr_solve_tv(b.A, b.B, b.Q, b.R, b.x0, stream=stream)
 
