@@ -129,3 +129,21 @@ def test_many_items_at_d16_four_per_wavefront():
     assert info[17] == 1 and (np.delete(info, 17) == 0).all()
     keep = torch.tensor([k for k in range(41) if k != 17], device=DEV)
     assert torch.equal(bad["u0"][keep], good["u0"][keep]) and torch.isnan(bad["u0"][17]).all()
+
+
+def test_many_items_even_horizon():
+    """As test_many_items_at_d16_four_per_wavefront with an even horizon (no odd element left over in the first
+    round) and a ragged last group of pairs."""
+    b = synth.make_tv_batch(41, 16, 16, 334, seed=14, device=DEV)      # 6847 pairs, not a multiple of four
+    check(b, TOL_F32)
+    check_values(b, TOL_F32)
+    check(synth.make_tv_batch(41, 16, 16, 334, seed=15, device=DEV, dtype="bf16"), TOL_BF16)
+    good = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, b.R, b.x0)
+    R = b.R.clone()
+    R[23, 201] = -100.0 * torch.eye(16, device=DEV)
+    bad = binding.ttc_lqr_solve_tv_scan(b.A, b.B, b.Q, R, b.x0)
+    torch.cuda.synchronize()
+    info = bad["info"].cpu().numpy()
+    assert info[23] == 1 and (np.delete(info, 23) == 0).all()
+    keep = torch.tensor([k for k in range(41) if k != 23], device=DEV)
+    assert torch.equal(bad["u0"][keep], good["u0"][keep]) and torch.isnan(bad["u0"][23]).all()
