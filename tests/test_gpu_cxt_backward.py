@@ -84,3 +84,39 @@ def test_workspace_and_arguments_are_checked():
     out = binding.ttc_lqr_backward_cxt(*(getattr(e0, k) for k in KEYS), e0.T, torch.zeros((0, 16), device=DEV))
     torch.cuda.synchronize()
     assert out["gsA"].shape == (0, 16) and float(out["gBbasis"].abs().max()) == 0.0
+
+
+def test_full_size_sample_and_halves():
+    """1M problems (batch 8 x 16 heads x 8192 tokens), r = 16, T = 8, as the benchmark runs them: some twenty chunks per
+    call.  The oracle checks the per-problem gradients of a random sample spread over the chunks (they do not depend
+    on the other problems); every problem's gradients are finite; and the basis gradients, sums over all the
+    problems, equal the sum of what two calls on the two halves of the batch give (a property of the sums at any
+    size; the order of the atomic additions differs between the calls, hence a tolerance)."""
+    n = 8 * 16 * 8192
+    b = synth.make_contextual_batch(n, 16, 16, 8, seed=0, device=DEV)
+    g, out = run(b, seed=2)
+    assert int(out["info"].abs().max()) == 0
+    for k in PER_PROBLEM + ("gBbasis", "gQbasis"):
+        assert bool(torch.isfinite(out[k]).all()), k
+    idx = torch.randperm(n, generator=torch.Generator().manual_seed(321))[:254].sort().values
+    idx = torch.cat([torch.tensor([0]), idx, torch.tensor([n - 1])]).unique().to(DEV)
+    sub = b.take(idx)
+    ref = go.contextual_gradients(*sub.numpy64(), sub.T, g[idx].cpu().double().numpy())
+    for k in PER_PROBLEM:
+        got = out[k][idx].cpu().numpy()
+        if k in ("gsB", "gsQ", "gsQf"):
+            err = float(np.abs(got - ref[k]).max() / np.abs(ref[k]).max())
+        else:
+            err = float(rel_err(got, ref[k]).max())
+        assert err <= 2e-5, (k, err)
+    h = n // 2
+    parts = []
+    for sl in (slice(0, h), slice(h, n)):
+        part = b.take(sl)
+        parts.append(binding.ttc_lqr_backward_cxt(*(getattr(part, k) for k in KEYS), part.T, g[sl].contiguous()))
+        torch.cuda.synchronize()
+    for k in ("gBbasis", "gQbasis"):
+        both = parts[0][k].double() + parts[1][k].double()
+        assert float((out[k].double() - both).abs().max() / both.abs().max()) <= 1e-4, k
+    for k in PER_PROBLEM:   # and the per-problem gradients do not depend on where the chunks fall
+        assert torch.equal(out[k][:h], parts[0][k]) and torch.equal(out[k][h:], parts[1][k]), k
