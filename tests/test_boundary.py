@@ -209,3 +209,29 @@ def test_structured_rollout_argument_validation_without_device(lib):
     assert call(_cxt_problem(), U=None) == binding.TTC_ERR_INVALID_ARG
     assert call(_cxt_problem(), ws=None) == binding.TTC_ERR_WORKSPACE
     assert call(_cxt_problem(), nbytes=need - 1) == binding.TTC_ERR_WORKSPACE
+
+
+def test_structured_backward_argument_validation_without_device(lib):
+    def grads(**kw):
+        g = binding.CxtGrads()
+        for k in binding.CXT_GRADS:
+            setattr(g, k, 0x8000)
+        for k, v in kw.items():
+            setattr(g, k, v)
+        return g
+    call = lambda p, g=None, gu=0x7000, ws=0x1000, nbytes=1 << 40: lib.ttc_lqr_backward_cxt(
+        ctypes.byref(p), gu, ctypes.byref(g if g is not None else grads()), ws, nbytes, None)
+    need = lib.ttc_lqr_backward_cxt_workspace_bytes(ctypes.byref(_cxt_problem()))
+    per_problem = (4 + 5) * 256 + 4 * (4 + 1) * 16 + 768 + 1   # kept matrices, trajectories, rows for the bases, info
+    assert need == (8 * per_problem + 63) // 64 * 64 * 4   # floats, rounded up to a multiple of 64
+    assert lib.ttc_lqr_backward_cxt_workspace_bytes(ctypes.byref(_cxt_problem(d=32))) == 0
+    assert call(_cxt_problem(T=0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(r=0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(d=32)) == binding.TTC_ERR_UNSUPPORTED
+    assert call(_cxt_problem(sQ=None)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(), gu=None) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(), grads(gBbasis=None)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(), grads(glgB=None)) == binding.TTC_ERR_INVALID_ARG
+    assert call(_cxt_problem(), grads(gsA=0x8002)) == binding.TTC_ERR_INVALID_ARG            # misaligned output
+    assert call(_cxt_problem(Bbasis=0x1004)) == binding.TTC_ERR_INVALID_ARG                  # the bases' rows are read 16 bytes at a time
+    assert call(_cxt_problem(Qbasis=0x1008)) == binding.TTC_ERR_INVALID_ARG
