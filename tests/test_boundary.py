@@ -235,3 +235,32 @@ def test_structured_backward_argument_validation_without_device(lib):
     assert call(_cxt_problem(), grads(gsA=0x8002)) == binding.TTC_ERR_INVALID_ARG            # misaligned output
     assert call(_cxt_problem(Bbasis=0x1004)) == binding.TTC_ERR_INVALID_ARG                  # the bases' rows are read 16 bytes at a time
     assert call(_cxt_problem(Qbasis=0x1008)) == binding.TTC_ERR_INVALID_ARG
+
+
+def test_block_argument_validation_without_device(lib):
+    def block(**kw):
+        b = binding.Block()
+        b.n_tokens, b.C, b.H, b.d, b.r, b.T, b.flags, b.eps = 12, 64, 4, 16, 8, 3, 0, 1e-5
+        for k in binding.BLOCK_WEIGHTS:
+            setattr(b, k, 0x1000)
+        for k, v in kw.items():
+            setattr(b, k, v)
+        return b
+    call = lambda b, x=0x2000, y=0x3000, ws=0x4000, nbytes=1 << 40: lib.ttc_block_forward(ctypes.byref(b), x, y, None, None,
+                                                                                         None, ws, nbytes, None)
+    need = lib.ttc_block_workspace_bytes(ctypes.byref(block()))
+    assert need > 0 and need % 16 == 0
+    assert lib.ttc_block_workspace_bytes(ctypes.byref(block(d=32))) == 0
+    assert call(block(T=0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(block(eps=0.0)) == binding.TTC_ERR_INVALID_ARG
+    assert call(block(flags=2)) == binding.TTC_ERR_INVALID_ARG
+    assert call(block(d=32)) == binding.TTC_ERR_UNSUPPORTED
+    assert call(block(r=6)) == binding.TTC_ERR_UNSUPPORTED                               # r is a multiple of four
+    assert call(block(C=62)) == binding.TTC_ERR_UNSUPPORTED                              # so is C
+    assert call(block(C=68, flags=binding.TTC_BLOCK_FLAG_BF16)) == binding.TTC_ERR_UNSUPPORTED   # of eight for bfloat16
+    assert call(block(n_tokens=0)) == binding.TTC_OK
+    assert call(block(W_out=None)) == binding.TTC_ERR_INVALID_ARG
+    assert call(block(W_head=0x1004)) == binding.TTC_ERR_INVALID_ARG                     # misaligned
+    assert call(block(), x=None) == binding.TTC_ERR_INVALID_ARG
+    assert call(block(), ws=None) == binding.TTC_ERR_WORKSPACE
+    assert call(block(), nbytes=need - 1) == binding.TTC_ERR_WORKSPACE
