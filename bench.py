@@ -373,9 +373,11 @@ def bench_cxt_bwd(args):
     kernel_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
     kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
     assert int(out["info"].abs().max()) == 0, "a problem reported numerical breakdown"
-    # bytes the path moves by construction: per problem the T + 5 matrices the solve kernel leaves and the sweep reads,
-    # the four trajectories written and read, the three kept matrices written and read, inputs and outputs
-    path_bytes = n * (2 * (T + 5) * d * d * 4 + 2 * 4 * (T + 1) * d * 4 + 2 * 3 * d * d * 4 + 2 * (6 * d + 3 * r) * 4 + 2 * (6 * d + 3 * r) * 4)
+    # bytes the path moves by construction: per problem the T + 3 matrices and the dual problem's first control that the
+    # solve kernel leaves and the sweep reads, the four trajectories written and read (horizons past 15 only: shorter
+    # ones stay in LDS), the three kept matrices written and read, inputs and outputs
+    traj = 0 if T <= 15 else 2 * 4 * (T + 1) * d * 4
+    path_bytes = n * (2 * (T + 3) * d * d * 4 + 2 * d * 4 + traj + 2 * 3 * d * d * 4 + 2 * (6 * d + 3 * r) * 4 + 2 * (6 * d + 3 * r) * 4)
     achieved = path_bytes / kernel_s / 1e9
     res = {
         "metric": "LQR backward passes/sec at d=%d, T=%d, structured parameters" % (d, T),

@@ -311,7 +311,7 @@ typedef struct {
 } ttc_lqr_cxt_grads_t;
 
 /* The problems are taken a chunk at a time, three launches per chunk after two that clear the basis gradients: the
- * backward recursion of the forward pass once more, keeping every gain, S_0 and its inverse in the workspace; one sweep
+ * backward recursion of the forward pass once more, keeping every gain and the dual problem's first control in the workspace; one sweep
  * of sixteen lanes per problem over both closed loops, both co-state recursions and the gradients, contracted straight
  * onto the parameterisation (no dense per-step matrices are formed); the sums for the bases.  Bbasis and Qbasis have to
  * be 16-byte aligned here (TTC_ERR_INVALID_ARG otherwise).  workspace: DEVICE, 16-byte aligned,

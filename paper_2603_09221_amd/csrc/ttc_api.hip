@@ -853,9 +853,9 @@ ttc_status_t ttc_lqr_backward_tv(const ttc_lqr_tv_problem_t* q, const float* gra
 
 // ---- backward pass of the structured problems ------------------------------------------------------------------
 namespace {
-// floats of workspace per problem of a chunk: T + 5 matrices left by the solve kernel, four trajectories of T + 1
+// floats of workspace per problem of a chunk: T + 4 matrices left by the solve kernel, four trajectories of T + 1
 // vectors, three matrices kept for the bases' sums, one int
-size_t cxt_bwd_floats_per_problem(int T) { return (size_t)(T + 5) * 256 + 4 * (size_t)(T + 1) * 16 + 768 + 1; }
+size_t cxt_bwd_floats_per_problem(int T) { return (size_t)(T + 4) * 256 + 4 * (size_t)(T + 1) * 16 + 768 + 1; }
 // problems per chunk: about 1 GiB of workspace
 long long cxt_bwd_chunk(long long n, int T) {
   long long ch = (long long)((1ull << 28) / cxt_bwd_floats_per_problem(T));
@@ -897,7 +897,7 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
   ttc::CxtBackwardArgs a;
   fill_cxt_args(a.c, q);
   a.roll = ws;
-  a.traj = a.roll + (size_t)chunk * (T + 5) * 256;
+  a.traj = a.roll + (size_t)chunk * (T + 4) * 256;
   a.keep = a.traj + (size_t)chunk * 4 * (T + 1) * 16;
   int* const info_ws = reinterpret_cast<int*>(a.keep + (size_t)chunk * 768);  // the chunk's info when the caller wants none
   a.g = grad_u0;
@@ -905,6 +905,7 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
   a.glgA = gr->glgA; a.glgB = gr->glgB; a.glgQ = gr->glgQ; a.gx0 = gr->gx0;
   a.gBbasis = gr->gBbasis; a.gQbasis = gr->gQbasis;
   const long long vgrid = 16LL * ttc::cu_count();  // wavefronts of the vector kernel, four problems at a time each
+  a.traj_in_lds = T <= 15;  // 1 KB of LDS per step and wavefront: eight wavefronts per compute unit keep their place
   auto shifted = [&](const void* base, long long elems) {
     return static_cast<const void*>(static_cast<const char*>(base) + (size_t)elems * esz);
   };
@@ -919,7 +920,8 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
     sc.lgA = shifted(q->lgA, first * 16); sc.lgB = shifted(q->lgB, first * 16); sc.lgQ = shifted(q->lgQ, first * 16);
     sc.sB = shifted(q->sB, first * q->r); sc.sQ = shifted(q->sQ, first * q->r); sc.sQf = shifted(q->sQf, first * q->r);
     sc.roll_ws = a.roll;
-    sc.roll_slots = T + 5;
+    sc.roll_slots = T + 4;
+    sc.dual_g = grad_u0 + first * 16;
     sc.s.info = gr->info ? gr->info + first : info_ws;
     a.info = gr->info ? gr->info : info_ws - first;  // indexed by the problem's number in the batch
     if (run_cxt(sc, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;

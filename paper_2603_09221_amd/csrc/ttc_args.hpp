@@ -75,9 +75,11 @@ struct CxtArgs {
   const void *sA, *sB, *sQ, *sQf, *rinv, *lgA, *lgB, *lgQ;  // (n,16) vectors, (n,r) coefficients
   const void *Bbasis, *Qbasis;                              // (r,16,16), shared by all problems
   // roll-out and backward pass: per problem roll_slots matrices of 256 floats: Bbar, Qbar, Q_T, K_0 .. K_{T-1} and, for
-  // the backward pass (roll_slots = T + 5), S_0 and S_0^{-1}; NULL for a plain solve
+  // the backward pass (dual_g set, roll_slots = T + 4), in the first 16 floats of the last one the first control of the
+  // dual problem, ut_0 = -S_0^{-1} g refined once with S_0; NULL for a plain solve
   float* roll_ws = nullptr;
-  int roll_slots = 0;  // 0 stands for T + 3
+  int roll_slots = 0;             // 0 stands for T + 3
+  const float* dual_g = nullptr;  // (n,16) dl/du_0, or NULL
 };
 
 struct CxtRolloutArgs {
@@ -92,7 +94,8 @@ struct CxtBackwardArgs {
   long long first;       // the chunk: problems first .. first + count - 1
   long long count;
   int basis_slab;        // problems per workgroup of the basis sums (>= CXT_BASIS_SLAB: atomic additions stay rare)
-  float* roll;           // (count, T + 5, 256): what solve_cxt_kernel leaves for the backward pass (c.roll_ws layout)
+  int traj_in_lds;       // the trajectories of a wavefront's four problems stay in (dynamic) LDS: short horizons
+  float* roll;           // (count, T + 4, 256): what solve_cxt_kernel leaves for the backward pass (c.roll_ws layout)
   float* traj;           // (count, 4, T + 1, 16): the primal and dual states and controls
   float* keep;           // (count, 3, 256): dl/dBbar, dl/dQbar, dl/dQ_T
   const float* g;        // (n, 16) dl/du_0

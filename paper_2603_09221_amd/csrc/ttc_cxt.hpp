@@ -23,6 +23,8 @@ namespace ttc {
 #ifndef TTC_CXT_WAVES
 #define TTC_CXT_WAVES 2  // wavefronts per SIMD the register allocation aims at
 #endif
+// The workgroup is one wavefront: its lanes exchange data through LDS with wave_lds_sync(), which leaves the stores
+// of the roll-out's gains in flight (a workgroup barrier would wait for each of them).
 // PPW = problems per wavefront: 4 for batches that fill the chip; 1 for small batches, where a wavefront's
 // latency is what counts: the four rows of 16 lanes then all hold the same problem (they compute, and
 // write, the same values), and every per-problem loop below runs once instead of four times.
@@ -77,13 +79,14 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
     const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(ca.lgQ), pg * D + i);
     vecs[0][gq][3][i] = 1.f / ld1<TIn>(reinterpret_cast<const TIn*>(ca.rinv), pg * D + i);
     const float x0_m = ca.roll_ws ? 0.f : ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), pg * p.sx0 + i);  // for the outputs
+    const float g_m = ca.dual_g ? ca.dual_g[pg * D + i] : 0.f;
     const int r4 = (r + 3) & ~3;  // the coefficients are read four at a time: zeros past r
     for (int k = i; k < r4; k += 16) {
       coef[gq][0][k] = k < r ? ld1<TIn>(reinterpret_cast<const TIn*>(ca.sB), pg * r + k) : 0.f;
       coef[gq][1][k] = k < r ? ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQ), pg * r + k) : 0.f;
       coef[gq][2][k] = k < r ? ld1<TIn>(reinterpret_cast<const TIn*>(ca.sQf), pg * r + k) : 0.f;
     }
-    __syncthreads();
+    wave_lds_sync();
 
     // ---- Bbar, Qbar, Q_T in the accumulator layout: element (4g+v, i) of each of the four problems
     floatx4 Bbar[PPW], Qbar[PPW], pn[PPW][C::RB][C::NT];
@@ -153,7 +156,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 #pragma unroll
     for (int q = 0; q < PPW; ++q) put_acc(Wm[q] + D, C::PITCH, pn[q][0][0]);
     write_vec(p.T - 1);
-    __syncthreads();
+    wave_lds_sync();
     tm.toc(0);
 
     for (int s = p.T - 1; s >= 0; --s) {  // step s turns P_t (pn, also in LDS) into P_{t-1}
@@ -187,7 +190,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 #pragma unroll
         for (int v = 0; v < 4; ++v) cFT[q][0][v] = aI * accVT[q][0][0][v];  // rows of F^T = diag(a) V
       }
-      __syncthreads();
+      wave_lds_sync();
       floatx4 accW[PPW][C::RB][C::NT];
       {
         floatx4 accS[PPW][C::RB][C::NT];
@@ -206,22 +209,37 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
           store_rows<D>(Wm[q], accS[q], w, i, g);
-          if (s == 0 && slots == p.T + 5 && valid[q])  // the backward pass solves with S_0 once more
-            write_rows_global<D>(ca.roll_ws + (prob[q] * slots + p.T + 3) * D * D, accS[q][0], 0, i, g);
+          if (s == 0 && ca.dual_g) put_acc(Vt[q], PT, accS[q][0][0]);  // S_0 once more below (V^T has been read)
         }
       }
-      __syncthreads();
+      wave_lds_sync();
       tm.toc(2);
-      note(invert_rows16<true>(Wmine, lane));  // left halves: -S^{-1}, so that the next product is the gain itself
+      note(invert_rows16<true, true>(Wmine, lane));  // left halves: -S^{-1}, so that the next product is the gain itself
       tm.toc(1);
-      if (s == 0 && slots == p.T + 5) {  // and S_0^{-1}: one 16-byte piece per lane, row-major
+      if (s == 0 && ca.dual_g) {
+        // The dual problem of the backward pass starts from ut_0 = -S_0^{-1} g: y = S_0^{-1} g, refined once with the
+        // residual g - S_0 y.  Lane (i, g) takes row i of its problem's -S_0^{-1} (Wm) and S_0 (Vt).
+        float (*dv)[D] = vecs[1][gq];  // the other step's copy is free at s = 0: g, y, residual
+        dv[0][i] = g_m;
+        wave_lds_sync();
+        auto row_dot = [&](const float* M, int pitch, const float* v) {
+          float acc = 0.f;
 #pragma unroll
-        for (int q = 0; q < PPW; ++q)
-          if (valid[q]) {
-            const floatx4 ms = *reinterpret_cast<const floatx4*>(Wm[q] + (lane >> 2) * C::PITCH + 4 * (lane & 3));
-            *reinterpret_cast<floatx4*>(ca.roll_ws + (prob[q] * slots + p.T + 4) * D * D + 4 * lane) =
-                floatx4{-ms[0], -ms[1], -ms[2], -ms[3]};
+          for (int c = 0; c < 4; ++c) {
+            const floatx4 m = *reinterpret_cast<const floatx4*>(M + i * pitch + 4 * c);
+            const floatx4 x = *reinterpret_cast<const floatx4*>(v + 4 * c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc = __builtin_fmaf(m[e], x[e], acc);
           }
+          return acc;
+        };
+        const float y = -row_dot(Wm[gq], C::PITCH, dv[0]);
+        dv[1][i] = y;
+        wave_lds_sync();
+        dv[2][i] = g_m - row_dot(Vt[gq], PT, dv[1]);
+        wave_lds_sync();
+        const float ut0 = -(y - row_dot(Wm[gq], C::PITCH, dv[2]));
+        if (quad * PPW + gq < p.n && (PPW == 4 || g == 0)) ca.roll_ws[(pg * slots + p.T + 3) * D * D + i] = ut0;
       }
       {
         float cSi[PPW][C::RB][C::KS];
@@ -258,7 +276,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
           put_acc(Wm[q] + D, C::PITCH, pn[q][0][0]);
         }
         write_vec(s - 1);
-        __syncthreads();
+        wave_lds_sync();
         tm.toc(2);
       } else {
 #pragma unroll
@@ -267,7 +285,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
           put_acc(Vt[q], PT, accW[q][0][0]);          // K_0, row-major
         }
         vecs[1][gq][0][i] = x0_m;
-        __syncthreads();
+        wave_lds_sync();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
           const floatx4 pt = get_row(Wm[q] + D, C::PITCH);
@@ -275,7 +293,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
           for (int v = 0; v < 4; ++v) pn[q][0][0][v] = 0.5f * (pn[q][0][0][v] + pt[v]);
           store_rows<D>(Wm[q], pn[q], w, i, g);  // symmetric P_0
         }
-        __syncthreads();
+        wave_lds_sync();
         if (ca.roll_ws) {  // the roll-out wants the gains (written above) and info only
 #pragma unroll
           for (int q = 0; q < PPW; ++q)
@@ -320,7 +338,7 @@ __global__ void __launch_bounds__(64, TTC_CXT_WAVES) solve_cxt_kernel(const CxtA
                   info[q] ? nan4 : *reinterpret_cast<const floatx4*>(Wm[q] + (lane >> 2) * C::PITCH + 4 * (lane & 3));
           }
         }
-        __syncthreads();
+        wave_lds_sync();
         tm.toc(3);
       }
     }

@@ -4,7 +4,7 @@
 //
 // Three launches per chunk of problems:
 //   solve_cxt_kernel         the backward recursion of the forward pass again (ttc_cxt.hpp), leaving per problem
-//                            Bbar, Qbar, Q_T, every gain K_s, S_0 and S_0^{-1} in the workspace
+//                            Bbar, Qbar, Q_T, every gain K_s and the dual problem's first control in the workspace
 //   backward_cxt_vec_kernel  both closed loops, both co-state recursions and the gradients, on vectors (below)
 //   cxt_basis_kernel         the bases' gradients: sums over the problems of the chunk, added to the caller's arrays
 // With t = 1..T, gam_X^t = exp(-t lg_X), Bbar = sum_k sB_k B^(k), Qbar = sum_k sQ_k Q^(k), and the per-step gradients
@@ -21,16 +21,6 @@
 #include "ttc_common.hpp"
 
 namespace ttc {
-
-// Orders the wavefront's own LDS traffic without waiting for its global loads: a workgroup here is one wavefront,
-// whose LDS instructions execute in issue order, so what one lane wrote is what another lane reads after this point
-// once the compiler keeps the order.  A workgroup barrier would also drain every load in flight, which the kernel
-// below relies on not happening (it fetches the next step's operands while the current step is computed).
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 // Row i (sixteen numbers) of a row-major 16 x 16 matrix in global memory.
 struct Row16 {
@@ -69,9 +59,9 @@ __device__ __forceinline__ float row_dot(const Row16& m, const float* va) {
 
 // The backward pass proper, on vectors: sixteen lanes per problem (four problems per wavefront, one wavefront per
 // workgroup), lane i owning entry i of every vector and row i of every 16 x 16 matrix it accumulates.
-// solve_cxt_kernel has left, per problem, Bbar, Qbar, Q_T, the gains K_0 .. K_{T-1}, S_0 and S_0^{-1}.  Forward: both
-// closed loops (Alg. 1; the dual one starts from ut_0 = -S_0^{-1} g, refined once with S_0, from the state 0), states
-// and controls to the workspace.  Backward: the co-states of both (Alg. 2) with A_t diagonal and
+// solve_cxt_kernel has left, per problem, Bbar, Qbar, Q_T, the gains K_0 .. K_{T-1} and ut_0.  Forward: both closed
+// loops (Alg. 1; the dual one starts from the state 0 with ut_0 = -S_0^{-1} g), states and controls to the workspace,
+// or to LDS when the horizon is short enough for the wavefront's four problems to fit there (a.traj_in_lds).  Backward: the co-states of both (Alg. 2) with A_t diagonal and
 // Q_t = Gamma^t Qbar Gamma^t, and in the same sweep the gradients of Thm 3.2 contracted straight onto the
 // parameterisation: no per-step gradient matrix is ever formed.  Every step is a short chain of dependent
 // operations, so the rows of the coming step (a gain, the stored states and controls, a basis matrix) are requested
@@ -80,10 +70,11 @@ template <typename TIn>
 __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardArgs a) {
   constexpr int D = 16;
   __shared__ __attribute__((aligned(16))) float vb[4][6][D];  // per problem: vectors every lane of the problem reads
+  extern __shared__ __attribute__((aligned(16))) float traj_lds[];  // 4 problems x 4 trajectories x (T + 1) x 16, or nothing
   const SolveArgs& p = a.c.s;
   const int T = p.T, r = a.c.r;
   const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
-  const long long slots = T + 5;
+  const long long slots = T + 4;
   const long long ngroups = (a.count + 3) / 4;
   const float nanv = __builtin_nanf("");
   const TIn* const Bb = reinterpret_cast<const TIn*>(a.c.Bbasis);
@@ -94,26 +85,24 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
   float* const v3 = vb[g][3];
   float* const vgB = vb[g][4];
   float* const vgQ = vb[g][5];
+  PhaseTimers tm;  // phases: 4 first loads and step 0, 5 forward, 6 backward, 7 outputs (0..3 belong to the solve kernel)
   for (long long grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
     const bool valid = grp * 4 + g < a.count;
     const long long q = valid ? grp * 4 + g : a.count - 1;  // within the chunk
     const long long prob = a.first + q;                      // within the batch
     const float* const e = a.roll + q * slots * D * D;
-    float* const tX = a.traj + q * 4 * (long long)(T + 1) * D;
+    float* const tX = a.traj_in_lds ? traj_lds + g * 4 * (T + 1) * D : a.traj + q * 4 * (long long)(T + 1) * D;
     float* const tXt = tX + (long long)(T + 1) * D;
     float* const tU = tXt + (long long)(T + 1) * D;
     float* const tUt = tU + (long long)(T + 1) * D;
-    // everything the first step needs is requested at once
-    Row16 kc = load_row16(e + 3 * D * D, i);                              // K_0
-    const Row16 sinv = load_row16(e + (long long)(T + 4) * D * D, i);     // S_0^{-1}
-    const Row16 s0 = load_row16(e + (long long)(T + 3) * D * D, i);       // S_0
+    // everything the first steps need is requested at once
     const Row16 bbr = load_row16(e, i);                                   // Bbar
+    float ut = e[(long long)(T + 3) * D * D + i];                         // ut_0
     const float sA_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.sA), prob * D + i);
     const float lgA_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgA), prob * D + i);
     const float lgB_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgB), prob * D + i);
     const float lgQ_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.lgQ), prob * D + i);
     const float rinv_m = ld1<TIn>(reinterpret_cast<const TIn*>(a.c.rinv), prob * D + i);
-    const float g_m = a.g[prob * D + i];
     float x = ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), prob * D + i), xt = 0.f;
     const bool bad = a.info && a.info[prob] != 0;
     float bb[D];  // row i of Bbar
@@ -121,59 +110,58 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
     for (int j = 0; j < D; ++j) bb[j] = bbr.v[j >> 2][j & 3];
 
     // ---- forward: both closed loops
-    float u, ut;
-    {  // step 0: u_0 = K_0 x_0; ut_0 = -(y + S_0^{-1} (g - S_0 y)), y = S_0^{-1} g
-      wave_lds_sync();
-      v0[i] = x;
-      v2[i] = g_m;
-      wave_lds_sync();
-      u = row_dot(kc, v0);
-      const float y = row_dot(sinv, v2);
-      v3[i] = y;
-      wave_lds_sync();
-      const float sy = row_dot(s0, v3);
-      wave_lds_sync();
-      v3[i] = g_m - sy;
-      wave_lds_sync();
-      ut = -(y + row_dot(sinv, v3));
-    }
-    for (int s = 0; s < T; ++s) {
-      const float tf = -1.44269504f * (float)(s + 1);
-      Row16 kn = kc;
-      if (s + 1 < T) kn = load_row16(e + (long long)(4 + s) * D * D, i);  // the next step's gain, or Q_T after the last
-      else kn = load_row16(e + 2 * D * D, i);
-      if (s > 0) {
+    // Four steps' gains are requested together (one wait per four steps instead of one per step); with the last
+    // ones come the rows of Q_T and Qbar for the co-states.
+    float u = 0.f;
+    Row16 qtr = bbr, qqr = bbr;
+    for (int s0 = 0; s0 < T; s0 += 4) {
+      Row16 kb[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int sk = s0 + k < T ? s0 + k : T - 1;
+        kb[k] = load_row16(e + (long long)(3 + sk) * D * D, i);
+      }
+      if (s0 + 4 >= T) {
+        qtr = load_row16(e + 2 * D * D, i);
+        qqr = load_row16(e + D * D, i);
+      }
+      if (s0 == 0) tm.toc(4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int s = s0 + k;
+        if (s >= T) break;
+        const float tf = -1.44269504f * (float)(s + 1);
         wave_lds_sync();
         v0[i] = x;
         v1[i] = xt;
         wave_lds_sync();
-        row_dot2(kc, v0, v1, u, ut);  // u_s = K_s x_s, both loops
-      }
-      tX[(long long)s * D + i] = x;
-      tXt[(long long)s * D + i] = xt;
-      tU[(long long)s * D + i] = u;
-      tUt[(long long)s * D + i] = ut;
-      const float gb = __builtin_amdgcn_exp2f(tf * lgB_m);
-      wave_lds_sync();
-      v2[i] = gb * u;
-      v3[i] = gb * ut;
-      wave_lds_sync();
-      const float am = 1.f + __builtin_amdgcn_exp2f(tf * lgA_m) * sA_m;
-      float bu = 0.f, but = 0.f;
+        if (s > 0) row_dot2(kb[k], v0, v1, u, ut);  // u_s = K_s x_s, both loops
+        else u = row_dot(kb[k], v0);               // u_0 = K_0 x_0 (ut_0 came with the matrices)
+        tX[(long long)s * D + i] = x;
+        tXt[(long long)s * D + i] = xt;
+        tU[(long long)s * D + i] = u;
+        tUt[(long long)s * D + i] = ut;
+        const float gb = __builtin_amdgcn_exp2f(tf * lgB_m);
+        wave_lds_sync();
+        v2[i] = gb * u;
+        v3[i] = gb * ut;
+        wave_lds_sync();
+        const float am = 1.f + __builtin_amdgcn_exp2f(tf * lgA_m) * sA_m;
+        float bu = 0.f, but = 0.f;
 #pragma unroll
-      for (int j = 0; j < D; ++j) {
-        bu = __builtin_fmaf(bb[j], v2[j], bu);
-        but = __builtin_fmaf(bb[j], v3[j], but);
+        for (int j = 0; j < D; ++j) {
+          bu = __builtin_fmaf(bb[j], v2[j], bu);
+          but = __builtin_fmaf(bb[j], v3[j], but);
+        }
+        x = am * x + bu;
+        xt = am * xt + but;
       }
-      x = am * x + bu;
-      xt = am * xt + but;
-      kc = kn;
     }
     tX[(long long)T * D + i] = x;
     tXt[(long long)T * D + i] = xt;
+    tm.toc(5);
 
     // ---- backward: co-states, and the gradients of every step as they become available
-    const Row16 qqr = load_row16(e + D * D, i);  // Qbar
     float nxs = tX[(long long)(T - 1) * D + i], nxts = tXt[(long long)(T - 1) * D + i];
     float nus = tU[(long long)(T - 1) * D + i], nuts = tUt[(long long)(T - 1) * D + i];
     float lam, lamt;
@@ -181,7 +169,7 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
     v0[i] = x;
     v1[i] = xt;
     wave_lds_sync();
-    row_dot2(kc, v0, v1, lam, lamt);  // lam_T = Q_T x_T
+    row_dot2(qtr, v0, v1, lam, lamt);  // lam_T = Q_T x_T
     float qq[D];
 #pragma unroll
     for (int j = 0; j < D; ++j) qq[j] = qqr.v[j >> 2][j & 3];
@@ -250,8 +238,8 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
         lamt = am * lamt;
       }
     }
+    tm.toc(6);
     // ---- outputs
-    Row16 bk = load_row16(Bb, i), qk = load_row16(Qb, i);  // rows i of the first basis matrices (r >= 1)
     if (valid) {
       a.gx0[prob * D + i] = bad ? nanv : lamt;
       a.gsA[prob * D + i] = bad ? nanv : dsA;
@@ -278,30 +266,39 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
         *reinterpret_cast<floatx4*>(keep + 512 + i * D + j4) = floatx4{dQf[j4] * f, dQf[j4 + 1] * f, dQf[j4 + 2] * f, dQf[j4 + 3] * f};
       }
     }
-    for (int k = 0; k < r; ++k) {  // the inner products with the basis matrices, the next one's rows on their way
-      const Row16 bc = bk, qc = qk;
-      if (k + 1 < r) {
-        bk = load_row16(Bb + (long)(k + 1) * 256, i);
-        qk = load_row16(Qb + (long)(k + 1) * 256, i);
-      }
-      float sb = 0.f, sq = 0.f, sf = 0.f;
+    for (int k0 = 0; k0 < r; k0 += 4) {  // the inner products with the basis matrices, four matrices' rows per wait
+      Row16 bk[4], qk[4];
 #pragma unroll
-      for (int j = 0; j < D; ++j) {
-        sb = __builtin_fmaf(bc.v[j >> 2][j & 3], dB[j], sb);
-        sq = __builtin_fmaf(qc.v[j >> 2][j & 3], dQ[j], sq);
-        sf = __builtin_fmaf(qc.v[j >> 2][j & 3], dQf[j], sf);
+      for (int kk = 0; kk < 4; ++kk) {
+        const int k = k0 + kk < r ? k0 + kk : r - 1;
+        bk[kk] = load_row16(Bb + (long)k * 256, i);
+        qk[kk] = load_row16(Qb + (long)k * 256, i);
       }
-      sb = sum16(sb);
-      sq = sum16(sq);
-      sf = sum16(sf);
-      if (valid && i == 0) {
-        a.gsB[prob * r + k] = bad ? nanv : sb;
-        a.gsQ[prob * r + k] = bad ? nanv : sq;
-        a.gsQf[prob * r + k] = bad ? nanv : sf;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int k = k0 + kk;
+        if (k >= r) break;
+        float sb = 0.f, sq = 0.f, sf = 0.f;
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+          sb = __builtin_fmaf(bk[kk].v[j >> 2][j & 3], dB[j], sb);
+          sq = __builtin_fmaf(qk[kk].v[j >> 2][j & 3], dQ[j], sq);
+          sf = __builtin_fmaf(qk[kk].v[j >> 2][j & 3], dQf[j], sf);
+        }
+        sb = sum16(sb);
+        sq = sum16(sq);
+        sf = sum16(sf);
+        if (valid && i == 0) {
+          a.gsB[prob * r + k] = bad ? nanv : sb;
+          a.gsQ[prob * r + k] = bad ? nanv : sq;
+          a.gsQf[prob * r + k] = bad ? nanv : sf;
+        }
       }
     }
     wave_lds_sync();
+    tm.toc(7);
   }
+  tm.dump(p);
 }
 
 // gBbasis[k] += sum_p sB[p][k] dBbar[p], gQbasis[k] += sum_p (sQ[p][k] dQbar[p] + sQf[p][k] dQ_T[p]) over a slab of

@@ -81,6 +81,16 @@ template <>
 __device__ __forceinline__ float ld1<uint16_t>(const uint16_t* p, long i) {
   return __uint_as_float(((uint32_t)p[i]) << 16);
 }
+// Orders the wavefront's own LDS traffic without waiting for its global loads: a workgroup here is one wavefront,
+// whose LDS instructions execute in issue order, so what one lane wrote is what another lane reads after this point
+// once the compiler keeps the order.  A workgroup barrier would also drain every load in flight, which kernels that
+// keep loads or stores in flight across their LDS exchanges rely on not happening.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <typename TIn>
 __device__ __forceinline__ floatx4 ld4(const TIn* p, long i);  // i % 4 == 0, p + i vector-aligned
 template <>

@@ -103,8 +103,10 @@ __device__ __forceinline__ int solve_rows16(float* Wq, int lane) {
 // column j of M, which has just become a unit vector.  Rows are scaled by their pivots at the end.
 // The pivot row is broadcast within each row of 16 lanes by DPP.  The caller synchronises before (M
 // complete in LDS); the function ends with a barrier.  Returns, per lane, whether its problem broke
-// down (a pivot that is not positive and finite).  NEGATE leaves -M^{-1} instead (the sign rides on the final scaling).
-template <bool NEGATE = false>
+// down (a pivot that is not positive and finite).  NEGATE leaves -M^{-1} instead (the sign rides on the final scaling);
+// ONE_WAVE: the workgroup is this wavefront alone, and the final barrier is replaced by an ordering of its LDS
+// traffic that does not wait for its global stores.
+template <bool NEGATE = false, bool ONE_WAVE = false>
 __device__ __forceinline__ int invert_rows16(float* Wq, int lane) {
   using C = Cfg<16>;
   const int r = lane & 15;
@@ -161,7 +163,8 @@ __device__ __forceinline__ int invert_rows16(float* Wq, int lane) {
     t[0] = a[4 * k + 0] * s; t[1] = a[4 * k + 1] * s; t[2] = a[4 * k + 2] * s; t[3] = a[4 * k + 3] * s;
     *reinterpret_cast<floatx4*>(Wq + r * C::PITCH + 4 * k) = t;
   }
-  __syncthreads();
+  if (ONE_WAVE) wave_lds_sync();
+  else __syncthreads();
   return bad;
 }
 

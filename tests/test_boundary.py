@@ -222,7 +222,7 @@ def test_structured_backward_argument_validation_without_device(lib):
     call = lambda p, g=None, gu=0x7000, ws=0x1000, nbytes=1 << 40: lib.ttc_lqr_backward_cxt(
         ctypes.byref(p), gu, ctypes.byref(g if g is not None else grads()), ws, nbytes, None)
     need = lib.ttc_lqr_backward_cxt_workspace_bytes(ctypes.byref(_cxt_problem()))
-    per_problem = (4 + 5) * 256 + 4 * (4 + 1) * 16 + 768 + 1   # kept matrices, trajectories, rows for the bases, info
+    per_problem = (4 + 4) * 256 + 4 * (4 + 1) * 16 + 768 + 1   # kept matrices, trajectories, rows for the bases, info
     assert need == (8 * per_problem + 63) // 64 * 64 * 4   # floats, rounded up to a multiple of 64
     assert lib.ttc_lqr_backward_cxt_workspace_bytes(ctypes.byref(_cxt_problem(d=32))) == 0
     assert call(_cxt_problem(T=0)) == binding.TTC_ERR_INVALID_ARG
