@@ -4,9 +4,8 @@
 
 namespace ttc {
 hipError_t launch_cxt_backward_vec(const CxtBackwardArgs& a, bool bf16, dim3 grid, hipStream_t st) {
-  const size_t lds = a.traj_in_lds ? (size_t)4 * 4 * (a.c.s.T + 1) * 16 * sizeof(float) : 0;
-  if (bf16) hipLaunchKernelGGL((backward_cxt_vec_kernel<uint16_t>), grid, dim3(64), lds, st, a);
-  else hipLaunchKernelGGL((backward_cxt_vec_kernel<float>), grid, dim3(64), lds, st, a);
+  if (bf16) hipLaunchKernelGGL((backward_cxt_vec_kernel<uint16_t>), grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((backward_cxt_vec_kernel<float>), grid, dim3(256), 0, st, a);
   return hipGetLastError();
 }
 hipError_t launch_cxt_basis(const CxtBackwardArgs& a, bool bf16, hipStream_t st) {

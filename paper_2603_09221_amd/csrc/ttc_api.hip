@@ -904,8 +904,9 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
   a.gsA = gr->gsA; a.gsB = gr->gsB; a.gsQ = gr->gsQ; a.gsQf = gr->gsQf; a.grinv = gr->grinv;
   a.glgA = gr->glgA; a.glgB = gr->glgB; a.glgQ = gr->glgQ; a.gx0 = gr->gx0;
   a.gBbasis = gr->gBbasis; a.gQbasis = gr->gQbasis;
-  const long long vgrid = 16LL * ttc::cu_count();  // wavefronts of the vector kernel, four problems at a time each
-  a.traj_in_lds = T <= 15;  // 1 KB of LDS per step and wavefront: eight wavefronts per compute unit keep their place
+  const long long vgrid = 4LL * ttc::cu_count();  // workgroups of the vector kernel: four wavefronts, four problems at a time each
+  a.traj_in_lds = T <= 8;         // the kernel's LDS holds T + 1 <= 9 points of four trajectories per problem
+  a.basis_in_lds = q->r <= 16;    // and two groups of up to sixteen basis matrices
   auto shifted = [&](const void* base, long long elems) {
     return static_cast<const void*>(static_cast<const char*>(base) + (size_t)elems * esz);
   };
@@ -925,7 +926,7 @@ ttc_status_t ttc_lqr_backward_cxt(const ttc_lqr_cxt_problem_t* q, const float* g
     sc.s.info = gr->info ? gr->info + first : info_ws;
     a.info = gr->info ? gr->info : info_ws - first;  // indexed by the problem's number in the batch
     if (run_cxt(sc, bf16, st) != hipSuccess) return TTC_ERR_DEVICE;
-    const long long groups = (a.count + 3) / 4;
+    const long long groups = (a.count + 15) / 16;  // workgroups' worth of problems
     // slabs of the basis sums: four workgroups per compute unit when the chunk is large, never under the smallest slab
     const long long slab = (a.count + 4LL * ttc::cu_count() - 1) / (4LL * ttc::cu_count());
     a.basis_slab = (int)(slab < ttc::CXT_BASIS_SLAB ? ttc::CXT_BASIS_SLAB : slab > 4096 ? 4096 : slab);

@@ -94,7 +94,8 @@ struct CxtBackwardArgs {
   long long first;       // the chunk: problems first .. first + count - 1
   long long count;
   int basis_slab;        // problems per workgroup of the basis sums (>= CXT_BASIS_SLAB: atomic additions stay rare)
-  int traj_in_lds;       // the trajectories of a wavefront's four problems stay in (dynamic) LDS: short horizons
+  int traj_in_lds;       // the trajectories of a wavefront's four problems stay in LDS: short horizons
+  int basis_in_lds;      // the workgroup keeps a copy of the basis matrices in LDS: r <= 16
   float* roll;           // (count, T + 4, 256): what solve_cxt_kernel leaves for the backward pass (c.roll_ws layout)
   float* traj;           // (count, 4, T + 1, 16): the primal and dual states and controls
   float* keep;           // (count, 3, 256): dl/dBbar, dl/dQbar, dl/dQ_T

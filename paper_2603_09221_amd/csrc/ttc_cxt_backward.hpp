@@ -57,36 +57,48 @@ __device__ __forceinline__ float row_dot(const Row16& m, const float* va) {
   return sa;
 }
 
-// The backward pass proper, on vectors: sixteen lanes per problem (four problems per wavefront, one wavefront per
-// workgroup), lane i owning entry i of every vector and row i of every 16 x 16 matrix it accumulates.
-// solve_cxt_kernel has left, per problem, Bbar, Qbar, Q_T, the gains K_0 .. K_{T-1} and ut_0.  Forward: both closed
-// loops (Alg. 1; the dual one starts from the state 0 with ut_0 = -S_0^{-1} g), states and controls to the workspace,
-// or to LDS when the horizon is short enough for the wavefront's four problems to fit there (a.traj_in_lds).  Backward: the co-states of both (Alg. 2) with A_t diagonal and
-// Q_t = Gamma^t Qbar Gamma^t, and in the same sweep the gradients of Thm 3.2 contracted straight onto the
-// parameterisation: no per-step gradient matrix is ever formed.  Every step is a short chain of dependent
-// operations, so the rows of the coming step (a gain, the stored states and controls, a basis matrix) are requested
-// one step ahead and the lanes exchange vectors through LDS without a barrier that would wait for them.
+// The backward pass proper, on vectors: sixteen lanes per problem (four problems per wavefront), lane i owning entry
+// i of every vector and row i of every 16 x 16 matrix it accumulates.  solve_cxt_kernel has left, per problem,
+// Bbar, Qbar, Q_T, the gains K_0 .. K_{T-1} and ut_0.  Forward: both closed loops (Alg. 1; the dual one starts from
+// the state 0 with ut_0 = -S_0^{-1} g), states and scaled controls to the workspace, or to LDS when the horizon is
+// short (a.traj_in_lds).  Backward: the co-states of both (Alg. 2) with A_t diagonal and Q_t = Gamma^t Qbar Gamma^t,
+// and in the same sweep the gradients of Thm 3.2 contracted straight onto the parameterisation: no per-step gradient
+// matrix is ever formed.  Every step is a short chain of dependent operations: gains are requested four steps at a
+// time, and the lanes of a problem exchange vectors through LDS with an ordering point that does not wait for loads
+// in flight.  The four wavefronts of a workgroup work independently (each on its own groups of four problems, with
+// its own LDS areas); what they share is a copy of the basis matrices in LDS (a.basis_in_lds: r <= 16), which the
+// inner products at the end read instead of going to memory once per problem.
+constexpr int CXT_BWD_LDS_R = 16;  // most basis matrices per group kept in LDS
+constexpr int CXT_BWD_LDS_T = 8;   // longest horizon whose trajectories stay in LDS
 template <typename TIn>
-__global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardArgs a) {
+__global__ void __launch_bounds__(256, 2) backward_cxt_vec_kernel(const CxtBackwardArgs a) {
   constexpr int D = 16;
-  __shared__ __attribute__((aligned(16))) float vb[4][6][D];  // per problem: vectors every lane of the problem reads
-  extern __shared__ __attribute__((aligned(16))) float traj_lds[];  // 4 problems x 4 trajectories x (T + 1) x 16, or nothing
+  __shared__ __attribute__((aligned(16))) float vb_all[4][4][4][D];  // per wavefront and problem: vectors every lane of the problem reads
+  __shared__ __attribute__((aligned(16))) float traj_all[4][4 * 4 * (CXT_BWD_LDS_T + 1) * D];
+  __shared__ __attribute__((aligned(16))) float basis_lds[2 * CXT_BWD_LDS_R * D * D];  // Bbasis, then Qbasis
   const SolveArgs& p = a.c.s;
   const int T = p.T, r = a.c.r;
-  const int lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
   const long long slots = T + 4;
   const long long ngroups = (a.count + 3) / 4;
   const float nanv = __builtin_nanf("");
   const TIn* const Bb = reinterpret_cast<const TIn*>(a.c.Bbasis);
   const TIn* const Qb = reinterpret_cast<const TIn*>(a.c.Qbasis);
+  if (a.basis_in_lds) {
+    for (int k = threadIdx.x; k < r * D * D; k += 256) {
+      basis_lds[k] = ld1<TIn>(Bb, k);
+      basis_lds[r * D * D + k] = ld1<TIn>(Qb, k);
+    }
+  }
+  __syncthreads();  // the only barrier: from here on a wavefront touches its own LDS areas and reads the bases
+  float (*const vb)[4][D] = vb_all[w];
+  float* const traj_lds = traj_all[w];
   float* const v0 = vb[g][0];
   float* const v1 = vb[g][1];
   float* const v2 = vb[g][2];
   float* const v3 = vb[g][3];
-  float* const vgB = vb[g][4];
-  float* const vgQ = vb[g][5];
   PhaseTimers tm;  // phases: 4 first loads and step 0, 5 forward, 6 backward, 7 outputs (0..3 belong to the solve kernel)
-  for (long long grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+  for (long long grp = blockIdx.x * 4LL + w; grp < ngroups; grp += gridDim.x * 4LL) {
     const bool valid = grp * 4 + g < a.count;
     const long long q = valid ? grp * 4 + g : a.count - 1;  // within the chunk
     const long long prob = a.first + q;                      // within the batch
@@ -112,7 +124,7 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
     // ---- forward: both closed loops
     // Four steps' gains are requested together (one wait per four steps instead of one per step); with the last
     // ones come the rows of Q_T and Qbar for the co-states.
-    float u = 0.f;
+    float u = 0.f, dR = 0.f;
     Row16 qtr = bbr, qqr = bbr;
     for (int s0 = 0; s0 < T; s0 += 4) {
       Row16 kb[4];
@@ -137,14 +149,16 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
         wave_lds_sync();
         if (s > 0) row_dot2(kb[k], v0, v1, u, ut);  // u_s = K_s x_s, both loops
         else u = row_dot(kb[k], v0);               // u_0 = K_0 x_0 (ut_0 came with the matrices)
+        const float gb = __builtin_amdgcn_exp2f(tf * lgB_m);
+        const float us = gb * u, uts = gb * ut;  // the controls as B_t sees them, gamma_B^t u: also what dl/dBbar needs
+        dR = __builtin_fmaf(ut, u, dR);          // dl/dR_t [i][i]
         tX[(long long)s * D + i] = x;
         tXt[(long long)s * D + i] = xt;
-        tU[(long long)s * D + i] = u;
-        tUt[(long long)s * D + i] = ut;
-        const float gb = __builtin_amdgcn_exp2f(tf * lgB_m);
+        tU[(long long)s * D + i] = us;
+        tUt[(long long)s * D + i] = uts;
         wave_lds_sync();
-        v2[i] = gb * u;
-        v3[i] = gb * ut;
+        v2[i] = us;
+        v3[i] = uts;
         wave_lds_sync();
         const float am = 1.f + __builtin_amdgcn_exp2f(tf * lgA_m) * sA_m;
         float bu = 0.f, but = 0.f;
@@ -161,7 +175,12 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
     tXt[(long long)T * D + i] = xt;
     tm.toc(5);
 
-    // ---- backward: co-states, and the gradients of every step as they become available
+    // ---- backward: co-states, and the gradients of every step as they become available.  Iteration t (the paper's
+    // step t, s = t - 1) takes lam_t and, in one exchange of four vectors, the scaled controls gamma_B^t u_s (for
+    // dl/dB_t) and the scaled states gamma_Q^s x_s (for dl/dQ_s and for lam_s = Q_s x_s + a_t lam_t); with
+    // B_t = Bbar Gamma_B^t and Q_s = Gamma_Q^s Qbar Gamma_Q^s the modulation factors are then already in place:
+    //   dBbar[i][j] += lam_i ut'_j + lamt_i u'_j =: incB,   dlgB_j += -t Bbar[i][j] incB   (summed over i at the end)
+    //   2 dQbar[i][j] += xt'_i x'_j + x'_i xt'_j =: incQ,   dlgQ_i += -s sum_j Qbar[i][j] incQ
     float nxs = tX[(long long)(T - 1) * D + i], nxts = tXt[(long long)(T - 1) * D + i];
     float nus = tU[(long long)(T - 1) * D + i], nuts = tUt[(long long)(T - 1) * D + i];
     float lam, lamt;
@@ -173,11 +192,13 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
     float qq[D];
 #pragma unroll
     for (int j = 0; j < D; ++j) qq[j] = qqr.v[j >> 2][j & 3];
-    float dsA = 0.f, dlgA = 0.f, dR = 0.f, dlgQ = 0.f;
-    float dB[D], dQ[D], dQf[D], cB[D];
+    float dsA = 0.f, dlgA = 0.f, dlgQ = 0.f;
+    float dB[D], dQ[D], dQf[D], cB[D];  // dQ holds twice dl/dQbar, cB holds dl/dlgB's terms without their Bbar[i][j]
 #pragma unroll
-    for (int j = 0; j < D; ++j) dB[j] = dQ[j] = dQf[j] = cB[j] = 0.f;
-    // v0, v1 hold x_t, xt_t on entry to iteration t
+    for (int j = 0; j < D; ++j) {
+      dB[j] = dQ[j] = cB[j] = 0.f;
+      dQf[j] = 0.5f * (xt * v0[j] + x * v1[j]);  // dl/dQ_T [i][j], symmetric
+    }
     for (int t = T; t >= 1; --t) {
       const int s = t - 1;
       const float tf = -1.44269504f * (float)t, tt = (float)t;
@@ -188,55 +209,49 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
         nus = tU[(long long)(s - 1) * D + i];
         nuts = tUt[(long long)(s - 1) * D + i];
       }
-      const float gamA = __builtin_amdgcn_exp2f(tf * lgA_m), gamQ = __builtin_amdgcn_exp2f(tf * lgQ_m);
+      const float gamA = __builtin_amdgcn_exp2f(tf * lgA_m);
+      const float gq1 = __builtin_amdgcn_exp2f(-1.44269504f * (float)s * lgQ_m);
+      const float xq = gq1 * xs, xtq = gq1 * xts;  // gamma_Q^s x_s
       wave_lds_sync();
-      v2[i] = us;
-      v3[i] = uts;
-      vgB[i] = __builtin_amdgcn_exp2f(tf * lgB_m);
-      vgQ[i] = gamQ;
+      v0[i] = us;
+      v1[i] = uts;
+      v2[i] = xq;
+      v3[i] = xtq;
       wave_lds_sync();
       const float gAii = lam * xts + lamt * xs;
       dsA = __builtin_fmaf(gamA, gAii, dsA);
       dlgA = __builtin_fmaf(-tt * gamA * sA_m, gAii, dlgA);
-      dR = __builtin_fmaf(uts, us, dR);
-      const float xi = v0[i], xti = v1[i];  // x_t[i], xt_t[i]
-      float hq = 0.f;
-#pragma unroll
-      for (int j = 0; j < D; ++j) {
-        const float gbij = lam * v3[j] + lamt * v2[j];                  // dl/dB_t [i][j]
-        dB[j] = __builtin_fmaf(vgB[j], gbij, dB[j]);
-        cB[j] = __builtin_fmaf(-tt * vgB[j] * bb[j], gbij, cB[j]);
-        const float gqij = 0.5f * (xti * v0[j] + xi * v1[j]);           // dl/dQ_t [i][j], symmetric
-        if (t < T) {
-          const float gm = gamQ * vgQ[j];
-          dQ[j] = __builtin_fmaf(gm, gqij, dQ[j]);
-          hq = __builtin_fmaf(gm * qq[j], gqij, hq);
-        } else {
-          dQf[j] = gqij;
-        }
-      }
-      dlgQ = __builtin_fmaf(-2.f * tt, hq, dlgQ);
-      // the co-state one step earlier: lam_{t-1} = Q_{t-1} x_{t-1} + a_t lam_t (t >= 2); lamt_0 = a_1 lamt_1
       const float am = 1.f + gamA * sA_m;
-      if (t >= 2) {
-        const float gq1 = __builtin_amdgcn_exp2f(-1.44269504f * (float)(t - 1) * lgQ_m);
-        wave_lds_sync();
-        v0[i] = xs;   // x_{t-1}, xt_{t-1}: what the next iteration needs
-        v1[i] = xts;
-        v2[i] = gq1 * xs;
-        v3[i] = gq1 * xts;
-        wave_lds_sync();
-        float qa = 0.f, qc = 0.f;
+      if (s >= 1) {
+        float hq = 0.f, qa = 0.f, qc = 0.f;
 #pragma unroll
         for (int j = 0; j < D; ++j) {
+          const float incB = __builtin_fmaf(lam, v1[j], lamt * v0[j]);
+          dB[j] += incB;
+          cB[j] = __builtin_fmaf(-tt, incB, cB[j]);
+          const float incQ = __builtin_fmaf(xtq, v2[j], xq * v3[j]);
+          dQ[j] += incQ;
+          hq = __builtin_fmaf(qq[j], incQ, hq);
           qa = __builtin_fmaf(qq[j], v2[j], qa);
           qc = __builtin_fmaf(qq[j], v3[j], qc);
         }
-        lam = gq1 * qa + am * lam;
+        dlgQ = __builtin_fmaf(-(float)s, hq, dlgQ);
+        lam = gq1 * qa + am * lam;  // lam_s = Q_s x_s + a_t lam_t
         lamt = gq1 * qc + am * lamt;
-      } else {
+      } else {  // s = 0: no cost on x_0; lamt_0 = a_1 lamt_1 is dl/dx_0
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+          const float incB = __builtin_fmaf(lam, v1[j], lamt * v0[j]);
+          dB[j] += incB;
+          cB[j] = __builtin_fmaf(-tt, incB, cB[j]);
+        }
         lamt = am * lamt;
       }
+    }
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      dQ[j] *= 0.5f;
+      cB[j] *= bb[j];
     }
     tm.toc(6);
     // ---- outputs
@@ -266,13 +281,19 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
         *reinterpret_cast<floatx4*>(keep + 512 + i * D + j4) = floatx4{dQf[j4] * f, dQf[j4 + 1] * f, dQf[j4 + 2] * f, dQf[j4 + 3] * f};
       }
     }
+    float msb = 0.f, msq = 0.f, msf = 0.f;
     for (int k0 = 0; k0 < r; k0 += 4) {  // the inner products with the basis matrices, four matrices' rows per wait
       Row16 bk[4], qk[4];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         const int k = k0 + kk < r ? k0 + kk : r - 1;
-        bk[kk] = load_row16(Bb + (long)k * 256, i);
-        qk[kk] = load_row16(Qb + (long)k * 256, i);
+        if (a.basis_in_lds) {
+          bk[kk] = load_row16(basis_lds + k * 256, i);
+          qk[kk] = load_row16(basis_lds + (r + k) * 256, i);
+        } else {
+          bk[kk] = load_row16(Bb + (long)k * 256, i);
+          qk[kk] = load_row16(Qb + (long)k * 256, i);
+        }
       }
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
@@ -288,10 +309,18 @@ __global__ void __launch_bounds__(64) backward_cxt_vec_kernel(const CxtBackwardA
         sb = sum16(sb);
         sq = sum16(sq);
         sf = sum16(sf);
-        if (valid && i == 0) {
-          a.gsB[prob * r + k] = bad ? nanv : sb;
-          a.gsQ[prob * r + k] = bad ? nanv : sq;
-          a.gsQf[prob * r + k] = bad ? nanv : sf;
+        // lane k mod 16 keeps the three numbers of matrix k; sixteen matrices leave with one store per array
+        const bool mine = (k & 15) == i;
+        msb = mine ? sb : msb;
+        msq = mine ? sq : msq;
+        msf = mine ? sf : msf;
+        if ((k & 15) == 15 || k == r - 1) {
+          if (valid && i <= (k & 15)) {
+            const long long o = prob * r + (k & ~15) + i;
+            a.gsB[o] = bad ? nanv : msb;
+            a.gsQ[o] = bad ? nanv : msq;
+            a.gsQf[o] = bad ? nanv : msf;
+          }
         }
       }
     }
