@@ -306,12 +306,33 @@ __device__ __forceinline__ void riccati_quad(float (*Wm)[16 * Cfg<16>::PITCH], f
     for (int q = 0; q < PPW; ++q)
       if (!info[q] && ((m >> (16 * q)) & 0xFFFFull)) info[q] = nsolve;
   };
+  // One problem per wavefront is the shape of small batches, where nothing else hides a step's reads of its matrices:
+  // there they are requested one step ahead (PF), into registers, and handed to LDS when their turn comes.
+  constexpr bool PF = PPW == 1;
+  HalfRegs<D> hA[PPW], hB[PPW], hQ[PPW];
+  floatx4 rR[PPW][C::RB][C::NT];
+  auto fetch_abr = [&](int s) {
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) {
+      issue_half<D, TIn>(hA[q], Ap[q] + (long long)s * tA, tid);
+      issue_half<D, TIn>(hB[q], Bp[q] + (long long)s * tB, tid);
+      load_rows_input<D, TIn>(Rp[q] + (long long)s * tR, rR[q], w, i, g);
+    }
+  };
+  auto fetch_q = [&](int s) {  // the stage cost on the state step s starts from
+#pragma unroll
+    for (int q = 0; q < PPW; ++q) issue_half<D, TIn>(hQ[q], Qp[q] + (long long)(s - 1) * tQ, tid);
+  };
+  if (PF) {
+    fetch_abr(T - 1);
+    if (T >= 2) fetch_q(T - 1);
+  }
 #pragma unroll
   for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q] + D, PTp[q], tid);  // P_T = Q_T
-  __syncthreads();
+  wave_lds_sync();
 #pragma unroll
   for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-  __syncthreads();
+  wave_lds_sync();
   for (int s = T - 1; s >= 0; --s) {
     // the step of riccati_step, for four problems at once
     floatx4 pn[PPW][C::RB][C::NT], accF[PPW][C::RB][C::NT], accW[PPW][C::RB][C::NT];
@@ -324,17 +345,19 @@ __device__ __forceinline__ void riccati_quad(float (*Wm)[16 * Cfg<16>::PITCH], f
 #pragma unroll
           for (int q = 0; q < PPW; ++q) {
             load_aop_lds<D>(Wm[q] + D, cP[q], w, i, g);  // rows of P
-            load_half<D, TIn, false>(Wm[q], Ap[q] + (long long)s * tA, tid);
+            if (PF) commit_half<D, false>(Wm[q], hA[q], tid);
+            else load_half<D, TIn, false>(Wm[q], Ap[q] + (long long)s * tA, tid);
           }
-          __syncthreads();
+          wave_lds_sync();
 #pragma unroll
           for (int q = 0; q < PPW; ++q) {
-            load_half<D, TIn, false>(Wm[q] + D, Bp[q] + (long long)s * tB, tid);  // P is in registers now
+            if (PF) commit_half<D, false>(Wm[q] + D, hB[q], tid);  // P is in registers now
+            else load_half<D, TIn, false>(Wm[q] + D, Bp[q] + (long long)s * tB, tid);
             zero_acc<D>(accPA[q]);
             zero_acc<D>(accPB[q]);
           }
           gemm_acc_quad<PPW>(accPA, cP, Wm, 0, i, g);  // P A
-          __syncthreads();
+          wave_lds_sync();
           gemm_acc_quad<PPW>(accPB, cP, Wm, D, i, g);  // P B
         }
 #pragma unroll
@@ -342,36 +365,38 @@ __device__ __forceinline__ void riccati_quad(float (*Wm)[16 * Cfg<16>::PITCH], f
           load_aopT_lds<D>(Wm[q], cAT[q], w, i, g);      // rows of A^T
           load_aopT_lds<D>(Wm[q] + D, cBT[q], w, i, g);  // rows of B^T
         }
-        __syncthreads();
+        wave_lds_sync();
 #pragma unroll
         for (int q = 0; q < PPW; ++q) {
           store_rows<D>(Wm[q], accPA[q], w, i, g);
           store_rows<D>(Wm[q] + D, accPB[q], w, i, g);
         }
-        __syncthreads();
+        wave_lds_sync();
       }
       floatx4 accS[PPW][C::RB][C::NT];
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
-        load_rows_input<D, TIn>(Rp[q] + (long long)s * tR, accS[q], w, i, g);
+        if (PF) accS[q][0][0] = rR[q][0][0];
+        else load_rows_input<D, TIn>(Rp[q] + (long long)s * tR, accS[q], w, i, g);
         zero_acc<D>(accF[q]);
         zero_acc<D>(pn[q]);
       }
+      if (PF && s >= 1) fetch_abr(s - 1);  // the next step's matrices, while this step computes
       gemm_acc_quad<PPW>(accS, cBT, Wm, D, i, g);  // S = R + B^T P B
       gemm_acc_quad<PPW>(accF, cBT, Wm, 0, i, g);  // F = B^T P A
       gemm_acc_quad<PPW>(pn, cAT, Wm, 0, i, g);    // A^T P A
-      __syncthreads();
+      wave_lds_sync();
 #pragma unroll
       for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], accS[q], w, i, g);
-      __syncthreads();
+      wave_lds_sync();
     }
 #pragma unroll
     for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);  // R is read as its symmetric part
-    __syncthreads();
+    wave_lds_sync();
     float cS[PPW][C::RB][C::KS];
 #pragma unroll
     for (int q = 0; q < PPW; ++q) load_aop_lds<D>(Wm[q], cS[q], w, i, g);  // rows of S, for the refinement below
-    note(invert_rows16(Wmine, lane));  // left halves: S^{-1}
+    note(invert_rows16<false, true>(Wmine, lane));  // left halves: S^{-1}
     {
       // At d = 16 the accumulator layout of F is both the B operand of F and the A operand of F^T.
       float cSi[PPW][C::RB][C::KS];
@@ -406,14 +431,18 @@ __device__ __forceinline__ void riccati_quad(float (*Wm)[16 * Cfg<16>::PITCH], f
         for (int q = 0; q < PPW; ++q)
           pn[q][0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(-accF[q][0][0][t], accW[q][0][0][t], pn[q][0][0], 0, 0, 0);
     }
-    __syncthreads();
+    wave_lds_sync();
     if (s >= 1) {
 #pragma unroll
-      for (int q = 0; q < PPW; ++q) load_half<D, TIn, false>(Wm[q], Qp[q] + (long long)(s - 1) * tQ, tid);
-      __syncthreads();
+      for (int q = 0; q < PPW; ++q) {
+        if (PF) commit_half<D, false>(Wm[q], hQ[q], tid);
+        else load_half<D, TIn, false>(Wm[q], Qp[q] + (long long)(s - 1) * tQ, tid);
+      }
+      if (PF && s >= 2) fetch_q(s - 1);
+      wave_lds_sync();
 #pragma unroll
       for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
-      __syncthreads();
+      wave_lds_sync();
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
         floatx4 qs[C::RB][C::NT];
@@ -421,17 +450,17 @@ __device__ __forceinline__ void riccati_quad(float (*Wm)[16 * Cfg<16>::PITCH], f
         pn[q][0][0] += qs[0][0];
         store_rows<D>(Wm[q] + D, pn[q], w, i, g);  // P_s
       }
-      __syncthreads();
+      wave_lds_sync();
 #pragma unroll
       for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q] + D, tid);
-      __syncthreads();
+      wave_lds_sync();
     } else {
 #pragma unroll
       for (int q = 0; q < PPW; ++q) store_rows<D>(Wm[q], pn[q], w, i, g);  // P_0 (no cost on x_0)
-      __syncthreads();
+      wave_lds_sync();
 #pragma unroll
       for (int q = 0; q < PPW; ++q) symmetrise_half<D>(Wm[q], tid);
-      __syncthreads();
+      wave_lds_sync();
 #pragma unroll
       for (int q = 0; q < PPW; ++q) {
         if (!valid[q]) continue;  // uniform over the wavefront
