@@ -23,13 +23,19 @@ __device__ __forceinline__ uint32_t row16_max_u32(uint32_t x) {
   return x;
 }
 
+#ifndef TTC_PIVOT_THRESHOLD
+#define TTC_PIVOT_THRESHOLD 0.25f  // a diagonal entry this close to the column's largest is taken as the pivot
+#endif
 // Dense solves M X = RHS of the four 16 x 32 augmented arrays Wm[q] = [M | RHS] (row r at
 // Wm[q] + r*PITCH), all at once: Gauss-Jordan with partial pivoting, a lane holding one row.  The pivot
 // of a column is found by a 16-lane DPP max of a packed key (|value| with the row index in the low
 // mantissa bits), the pivot row is broadcast with ds_bpermute, every other row of that problem is
 // eliminated.  Rows never move; the row that was the pivot of column c ends up as row c of X, written
-// to the right half.  PIVOT = false takes the diagonal (symmetric positive definite M); the pivot row is
-// then known at compile time and is broadcast by DPP (row_newbcast) instead.
+// to the right half.  The search is threshold pivoting: row c itself is preferred when it is still free and its
+// entry is at least TTC_PIVOT_THRESHOLD times the column's largest (element growth stays bounded by 1 + 1/threshold
+// per step instead of 2); when that holds for all four problems of the wavefront, the pivot row is known at compile
+// time and is broadcast by DPP (row_newbcast) instead of going through the LDS crossbar, which is what bounds this
+// function otherwise.  PIVOT = false always takes the diagonal (symmetric positive definite M).
 // Returns, per lane, whether its problem broke down (zero / non-finite / non-positive pivot).
 template <bool PIVOT>
 __device__ __forceinline__ int solve_rows16(float* Wq, int lane) {
@@ -49,17 +55,26 @@ __device__ __forceinline__ int solve_rows16(float* Wq, int lane) {
   static_for<0, 16>([&](auto J) {
     constexpr int j = decltype(J)::value;
     int pr;
+    bool diagonal = !PIVOT;  // the pivot row is lane j of every row of 16 lanes
     if constexpr (PIVOT) {
       uint32_t key = (__float_as_uint(a[j]) & 0x7FFFFF80u) | (uint32_t)(127 - r);
       key = act ? key : 0u;
+      // Threshold pivoting: row j itself is taken when it is still free and its entry is within a factor of
+      // TTC_PIVOT_THRESHOLD of the column's largest; when that holds for all of the wavefront's problems the
+      // pivot row is known at compile time and travels by DPP instead of the LDS crossbar.
+      const uint32_t own = (uint32_t)__builtin_amdgcn_mov_dpp((int)key, 0x150 + j, 0xF, 0xF, true);  // row j's key, 0 if used
       key = row16_max_u32(key);
+      const float big = __uint_as_float(key & 0x7FFFFF80u), mine_abs = __uint_as_float(own & 0x7FFFFF80u);
+      const bool fine = own != 0u && mine_abs >= TTC_PIVOT_THRESHOLD * big;
+      diagonal = __ballot(!fine) == 0ull;
       pr = 127 - (int)(key & 0x7Fu);
       pr = pr < 16 ? pr : 15;  // never leave the problem's lanes, whatever the data
+      pr = diagonal ? j : pr;
     } else {
       pr = j;
     }
     float prow[32];
-    if constexpr (PIVOT) {
+    if (PIVOT && !diagonal) {
       const int src = ((lane & 48) | pr) << 2;  // byte address of the pivot row's lane
       static_for<j, 32>([&](auto K) {
         constexpr int k = decltype(K)::value;
