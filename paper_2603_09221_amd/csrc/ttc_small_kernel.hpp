@@ -16,6 +16,7 @@ __global__ void __launch_bounds__(64, PPW == 4 ? 2 : 1) solve_small_kernel(const
   static_assert(PPW == 1 || PPW == 4, "one problem or four per wavefront");
   __shared__ __attribute__((aligned(16))) float Wm[PPW][D * C::PITCH];
   __shared__ float s_red[C::NW];
+  __shared__ __attribute__((aligned(16))) float s_x0[PPW][D];  // the problems' initial states, for the outputs
   const bool pure = (p.flags & TTC_FLAG_PURE_SYMPLECTIC) != 0;
   const long long nquads = (p.n + PPW - 1) / PPW;
 
@@ -256,17 +257,73 @@ __global__ void __launch_bounds__(64, PPW == 4 ? 2 : 1) solve_small_kernel(const
 
     tm.toc(2);
     // ---- outputs: the right halves hold P_0 (paper convention, Q_0 = 0)
+    if (p.flags & TTC_FLAG_STAGE_COST_AT_X0) {  // P_0 + Q is assembled problem by problem
 #pragma unroll
-    for (int q = 0; q < PPW; ++q) {
-      if (!valid[q]) continue;  // uniform over the wavefront
-      const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob[q] * p.sQ;
-      const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
-      zero_acc<D>(acc[q]);
-      gemm_acc<D>(acc[q], cCK[q], Wm[q] + D, i, g);  // -K_0 = C_K P_0
-      emit_gain<D, TIn>(p, prob[q], acc[q], x0p, info[q], tid);
-      emit_value<D, TIn>(p, prob[q], Wm[q] + D, Qp, x0p, info[q], s_red, tid);
+      for (int q = 0; q < PPW; ++q) {
+        if (!valid[q]) continue;  // uniform over the wavefront
+        const TIn* Qp = reinterpret_cast<const TIn*>(p.Q) + prob[q] * p.sQ;
+        const TIn* x0p = reinterpret_cast<const TIn*>(p.x0) + prob[q] * p.sx0;
+        zero_acc<D>(acc[q]);
+        gemm_acc<D>(acc[q], cCK[q], Wm[q] + D, i, g);  // -K_0 = C_K P_0
+        emit_gain<D, TIn>(p, prob[q], acc[q], x0p, info[q], tid);
+        emit_value<D, TIn>(p, prob[q], Wm[q] + D, Qp, x0p, info[q], s_red, tid);
+      }
+      __syncthreads();
+    } else {
+      // All the wavefront's problems at once: -K_0 = C_K P_0 on the matrix cores, K_0 to the left halves, then lane
+      // (i, g) takes row i of its problem's K_0 and P_0 for u_0 = K_0 x_0 and value = x_0^T P_0 x_0; the matrices
+      // leave as one 16-byte piece per lane and problem.
+      const int gq = g & (PPW - 1);
+      const long long pg = (quad * PPW + gq < p.n) ? quad * PPW + gq : p.n - 1;
+      const float x0_m = ld1<TIn>(reinterpret_cast<const TIn*>(p.x0), pg * p.sx0 + i);
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) zero_acc<D>(acc[q]);
+      gemm_acc_quad<PPW>(acc, cCK, Wm, D, i, g);
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[q][0][0][v] = -acc[q][0][0][v];
+        store_rows<D>(Wm[q], acc[q], w, i, g);  // left halves: K_0, row-major
+      }
+      s_x0[gq][i] = x0_m;
+      __syncthreads();
+      const float nanv = __builtin_nanf("");
+      float u = 0.f, pw = 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const floatx4 kr = *reinterpret_cast<const floatx4*>(Wm[gq] + i * C::PITCH + 4 * c);
+        const floatx4 pr = *reinterpret_cast<const floatx4*>(Wm[gq] + D + i * C::PITCH + 4 * c);
+        const floatx4 xr = *reinterpret_cast<const floatx4*>(&s_x0[gq][4 * c]);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          u = __builtin_fmaf(kr[v], xr[v], u);
+          pw = __builtin_fmaf(pr[v], xr[v], pw);
+        }
+      }
+      const float val = sum16(x0_m * pw);
+      int myinfo = info[0];
+#pragma unroll
+      for (int q = 1; q < PPW; ++q) myinfo = (gq == q) ? info[q] : myinfo;
+      if (quad * PPW + gq < p.n && (PPW == 4 || g == 0)) {
+        p.u0[pg * D + i] = myinfo ? nanv : u;
+        if (i == 0) {
+          if (p.value) p.value[pg] = myinfo ? nanv : val;
+          if (p.info) p.info[pg] = myinfo;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < PPW; ++q) {
+        if (!valid[q]) continue;  // uniform over the wavefront
+        const floatx4 nan4 = floatx4{nanv, nanv, nanv, nanv};
+        if (p.K0)
+          *reinterpret_cast<floatx4*>(p.K0 + prob[q] * (long)D * D + 4 * lane) =
+              info[q] ? nan4 : *reinterpret_cast<const floatx4*>(Wm[q] + (lane >> 2) * C::PITCH + 4 * (lane & 3));
+        if (p.P0)
+          *reinterpret_cast<floatx4*>(p.P0 + prob[q] * (long)D * D + 4 * lane) =
+              info[q] ? nan4 : *reinterpret_cast<const floatx4*>(Wm[q] + D + (lane >> 2) * C::PITCH + 4 * (lane & 3));
+      }
+      __syncthreads();
     }
-    __syncthreads();
     tm.toc(3);
     tm.dump(p);
   }
