@@ -171,6 +171,29 @@ def test_needs_pivoting():
     check(synth.LqrBatch(A, b.B, b.Q, b.R, b.x0, b.T), TOL_F32)
 
 
+@pytest.mark.parametrize("n", [10, 4100])
+def test_needs_pivoting_d16(n):
+    """The same at d = 16, where the pivot search prefers the diagonal row when it is large enough (a pivot row in a
+    known lane is broadcast without the LDS crossbar) and the choice is made per wavefront: one problem per
+    wavefront (small batch), and four per wavefront with every third problem close to a cyclic shift among ordinary
+    ones, so that steps of both kinds occur within a wavefront."""
+    d = 16
+    b = synth.make_batch(n, d, d, 5, seed=19, device=DEV)
+    shift = torch.roll(torch.eye(d, device=DEV), 1, dims=1)
+    A = b.A.clone()
+    A[::3] = 0.9 * shift + 0.05 * (b.A[::3] - torch.eye(d, device=DEV))
+    check(synth.LqrBatch(A.contiguous(), b.B, b.Q, b.R, b.x0, b.T), TOL_F32)
+    tv = synth.make_tv_batch(n if n < 100 else 4100, d, d, 3, seed=20, device=DEV)
+    Atv = tv.A.clone()
+    Atv[::3] = 0.9 * shift + 0.05 * (tv.A[::3] - torch.eye(d, device=DEV))
+    out = binding.ttc_lqr_solve_tv_scan(Atv.contiguous(), tv.B, tv.Q, tv.R, tv.x0)   # the compositions solve with I + G H
+    seq = binding.ttc_lqr_solve_tv(Atv.contiguous(), tv.B, tv.Q, tv.R, tv.x0)
+    torch.cuda.synchronize()
+    assert int(out["info"].abs().max()) == 0 and int(seq["info"].abs().max()) == 0
+    for k in ("P0", "K0", "u0", "value"):
+        assert float(rel_err(out[k].cpu().numpy(), seq[k].cpu().numpy()).max()) <= 2e-5, k
+
+
 def test_info_reports_breakdown():
     b = synth.make_batch(6, 16, 16, 4, seed=10, device=DEV)
     A = b.A.clone()
